@@ -1,0 +1,192 @@
+"""Shapes, distributions and seeds of the five benchmark subgraphs, plus small
+variants of each that a slow CPU oracle finishes in seconds.
+
+Every tensor is returned as float64 holding *exactly* the value that is stored
+for the GPU (fp32 or bfloat16 storage), so both sides start from the same numbers.
+Seeds: ``22120100 + 16 * config_index + tensor_index``.
+"""
+
+from dataclasses import dataclass, field
+import numpy as np
+
+from . import rng
+
+_SEED0 = 22120100
+
+
+def _store(x: np.ndarray, dtype: str) -> np.ndarray:
+    if dtype == "bf16":
+        return rng.round_to_bf16(x)
+    return np.asarray(x, dtype=np.float32).astype(np.float64)
+
+
+def _f32(x):
+    return np.asarray(x, dtype=np.float32).astype(np.float64)
+
+
+@dataclass
+class InvresCase:
+    """1x1 expand (+b1, ReLU6) -> depthwise 3x3 pad 1 (+bd, ReLU6) -> 1x1 project (+b2) [+x]."""
+    N: int; H: int; W: int; Cin: int; Cexp: int; Cout: int
+    stride: int = 1
+    residual: bool = False
+    bias: bool = True
+    dtype: str = "f32"
+    seed: int = _SEED0
+    x_scale: float = 1.0
+    name: str = "invres"
+
+    @property
+    def OH(self): return (self.H + 2 - 3) // self.stride + 1
+    @property
+    def OW(self): return (self.W + 2 - 3) // self.stride + 1
+
+    def flops(self):
+        pe = self.N * self.H * self.W
+        po = self.N * self.OH * self.OW
+        return 2 * pe * self.Cin * self.Cexp + 2 * 9 * po * self.Cexp + 2 * po * self.Cexp * self.Cout
+
+    def alg_bytes(self):
+        e = 2 if self.dtype == "bf16" else 4
+        nb = 4 * (2 * self.Cexp + self.Cout) if self.bias else 0
+        return e * (self.N * self.H * self.W * self.Cin + self.Cin * self.Cexp + 9 * self.Cexp
+                    + self.Cexp * self.Cout + self.N * self.OH * self.OW * self.Cout) + nb
+
+    def tensors(self):
+        s, d = self.seed, self.dtype
+        t = {
+            "x": _store(self.x_scale * rng.uniform(s + 0, (self.N, self.H, self.W, self.Cin), -1.0, 1.0), d),
+            "w1": _store(rng.normal(s + 1, (self.Cin, self.Cexp), (1.0 / self.Cin) ** 0.5), d),
+            "wd": _store(rng.normal(s + 2, (3, 3, self.Cexp), (1.0 / 9.0) ** 0.5), d),
+            "w2": _store(rng.normal(s + 3, (self.Cexp, self.Cout), (1.0 / self.Cexp) ** 0.5), d),
+        }
+        if self.bias:
+            t["b1"] = _f32(rng.uniform(s + 4, (self.Cexp,), -0.1, 0.1))
+            t["bd"] = _f32(rng.uniform(s + 5, (self.Cexp,), -0.1, 0.1))
+            t["b2"] = _f32(rng.uniform(s + 6, (self.Cout,), -0.1, 0.1))
+        else:
+            t["b1"] = t["bd"] = t["b2"] = None
+        return t
+
+
+@dataclass
+class ChainCase:
+    """conv3x3 pad 1 (+ba, ReLU) -> conv3x3 pad 1 (+bb) [+x] -> ReLU, C -> C channels."""
+    N: int; H: int; W: int; C: int
+    residual: bool = True
+    dtype: str = "bf16"
+    seed: int = _SEED0 + 32
+    name: str = "conv_chain"
+
+    def flops(self):
+        return 2 * 2 * 9 * self.N * self.H * self.W * self.C * self.C
+
+    def alg_bytes(self):
+        e = 2 if self.dtype == "bf16" else 4
+        return e * (2 * self.N * self.H * self.W * self.C + 2 * 9 * self.C * self.C) + 4 * 2 * self.C
+
+    def tensors(self):
+        s, d = self.seed, self.dtype
+        std = (2.0 / (9 * self.C)) ** 0.5
+        return {
+            "x": _store(rng.normal(s + 0, (self.N, self.H, self.W, self.C), 1.0), d),
+            "wa": _store(rng.normal(s + 1, (3, 3, self.C, self.C), std), d),
+            "wb": _store(rng.normal(s + 2, (3, 3, self.C, self.C), std), d),
+            "ba": _f32(rng.uniform(s + 3, (self.C,), -0.1, 0.1)),
+            "bb": _f32(rng.uniform(s + 4, (self.C,), -0.1, 0.1)),
+        }
+
+
+@dataclass
+class FfnCase:
+    """y = gelu_tanh(x w1 + b1) w2 + b2, x:[M,K] w1:[K,F] w2:[F,K2]."""
+    M: int; K: int; F: int; K2: int
+    dtype: str = "bf16"
+    seed: int = _SEED0 + 48
+    name: str = "ffn"
+
+    def flops(self):
+        return 2 * self.M * self.K * self.F + 2 * self.M * self.F * self.K2
+
+    def alg_bytes(self):
+        e = 2 if self.dtype == "bf16" else 4
+        return e * (self.M * self.K + self.K * self.F + self.F * self.K2 + self.M * self.K2) \
+            + 4 * (self.F + self.K2)
+
+    def tensors(self):
+        s, d = self.seed, self.dtype
+        return {
+            "x": _store(rng.normal(s + 0, (self.M, self.K), 1.0), d),
+            "w1": _store(rng.normal(s + 1, (self.K, self.F), 0.02), d),
+            "w2": _store(rng.normal(s + 2, (self.F, self.K2), 0.02), d),
+            "b1": _f32(rng.uniform(s + 3, (self.F,), -0.1, 0.1)),
+            "b2": _f32(rng.uniform(s + 4, (self.K2,), -0.1, 0.1)),
+        }
+
+
+@dataclass
+class AttnCase:
+    """o = softmax_rows(scale * q k^T) v per (batch, head); q,k,v,o:[B,Hh,S,D]."""
+    B: int; Hh: int; S: int; D: int
+    scale: float = 0.125
+    dtype: str = "bf16"
+    seed: int = _SEED0 + 64
+    name: str = "attn"
+
+    def flops(self):
+        return 2 * 2 * self.B * self.Hh * self.S * self.S * self.D
+
+    def alg_bytes(self):
+        e = 2 if self.dtype == "bf16" else 4
+        return e * 4 * self.B * self.Hh * self.S * self.D
+
+    def tensors(self):
+        s, d = self.seed, self.dtype
+        shp = (self.B, self.Hh, self.S, self.D)
+        return {
+            "q": _store(rng.normal(s + 0, shp, 1.0), d),
+            "k": _store(rng.normal(s + 1, shp, 1.0), d),
+            "v": _store(rng.normal(s + 2, shp, 1.0), d),
+        }
+
+
+BASELINE_NAMES = ["invres_14x14x32_f32", "invres_56x56x24_s2_bf16", "chain_8x56x56x64_bf16",
+                  "ffn_2048x768x3072_bf16", "attn_8x12x384x64_bf16"]
+
+
+def baseline_case(i: int):
+    """The i-th benchmark configuration at its full size."""
+    if i == 0:
+        return InvresCase(1, 14, 14, 32, 192, 32, stride=1, residual=True, bias=True,
+                          dtype="f32", seed=_SEED0, name=BASELINE_NAMES[0])
+    if i == 1:
+        return InvresCase(1, 56, 56, 24, 144, 32, stride=2, residual=False, bias=False,
+                          dtype="bf16", seed=_SEED0 + 16, name=BASELINE_NAMES[1])
+    if i == 2:
+        return ChainCase(8, 56, 56, 64, residual=True, dtype="bf16", seed=_SEED0 + 32,
+                         name=BASELINE_NAMES[2])
+    if i == 3:
+        return FfnCase(2048, 768, 3072, 768, dtype="bf16", seed=_SEED0 + 48, name=BASELINE_NAMES[3])
+    if i == 4:
+        return AttnCase(8, 12, 384, 64, scale=0.125, dtype="bf16", seed=_SEED0 + 64,
+                        name=BASELINE_NAMES[4])
+    raise IndexError(i)
+
+
+def small_cases():
+    """Reduced-size variants: several tiles plus a ragged tail, seconds for the oracle."""
+    s = _SEED0 + 1000
+    return [
+        InvresCase(1, 14, 14, 32, 192, 32, 1, True, True, "f32", s + 0, name="invres_f32_s1"),
+        InvresCase(2, 9, 11, 16, 96, 24, 2, False, True, "f32", s + 16, name="invres_f32_s2_ragged"),
+        InvresCase(1, 14, 14, 32, 192, 32, 1, True, True, "f32", s + 32, x_scale=16.0,
+                   name="invres_f32_clamp"),
+        InvresCase(1, 20, 20, 24, 144, 32, 2, False, False, "bf16", s + 48, name="invres_bf16_s2"),
+        InvresCase(2, 13, 10, 32, 192, 32, 1, True, True, "bf16", s + 64, name="invres_bf16_s1_res"),
+        ChainCase(1, 20, 17, 64, True, "bf16", s + 80, name="chain_ragged"),
+        ChainCase(2, 14, 14, 64, False, "bf16", s + 96, name="chain_nores"),
+        FfnCase(200, 768, 3072, 768, "bf16", s + 112, name="ffn_ragged_rows"),
+        FfnCase(96, 256, 512, 128, "bf16", s + 128, name="ffn_small"),
+        AttnCase(1, 2, 384, 64, 0.125, "bf16", s + 144, name="attn_s384"),
+        AttnCase(2, 3, 100, 64, 0.125, "bf16", s + 160, name="attn_ragged_s100"),
+    ]
