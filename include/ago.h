@@ -1,0 +1,209 @@
+/*
+ * ago.h - C ABI of the MI355X (gfx950) fused-subgraph library.
+ *
+ * The library runs a *subgraph holding several complex operators* (convolutions,
+ * matrix products; AGO, arXiv 2212.01005, Sec. II problem statement and Sec. III-B
+ * "intensive operator fusion") as one fused GPU kernel that keeps the tensors on
+ * the edges between the complex operators on-chip, and also exposes the same
+ * subgraphs operator by operator (Sec. III-A, Figs. 3 and 4) as the un-fused
+ * baselines.
+ *
+ * Conventions for every entry point
+ *   pointers   DEVICE pointers unless the comment says "host".  The caller owns
+ *              every buffer; the library never allocates or frees device memory.
+ *              All tensor pointers must be 16-byte aligned.  Outputs must not
+ *              alias inputs unless stated.
+ *   layouts    activations NHWC ([N][H][W][C], C fastest); 1x1 weights [Cin][Cout];
+ *              depthwise weights [3][3][C]; dense 3x3 weights [3][3][Cin][Cout];
+ *              GEMM operands row-major; attention tensors [B][Hh][S][D].
+ *   dtypes     `dt` is the storage type of activations and weights (AGO_F32 or
+ *              AGO_BF16).  Biases are always fp32 and may be NULL (= no bias).
+ *              bf16 paths accumulate, add biases, apply activations, residuals
+ *              and softmax in fp32; on-chip intermediates that feed a bf16 matrix
+ *              instruction are rounded to bf16 (nearest even).
+ *   padding    spatial convolutions use zero padding 1; for the second operator
+ *              of a chain the *intermediate* tensor is what is padded with zeros.
+ *   execution  asynchronous on `hip_stream` (a hipStream_t passed as void*;
+ *              NULL = the default stream); the call returns after enqueue.
+ *   errors     return codes only.  Argument validation happens on the host
+ *              before any HIP call; AGO_ERR_LAUNCH reports a failed launch.
+ *              A shape the kernels cannot run returns AGO_ERR_UNSUPPORTED,
+ *              never a wrong answer.
+ *   workspace  scratch for cross-workgroup partial results; size from
+ *              ago_workspace_bytes().  May be NULL when that size is 0.
+ */
+#ifndef AGO_H
+#define AGO_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    AGO_OK = 0,
+    AGO_ERR_NULL = 1,         /* a required pointer is NULL */
+    AGO_ERR_SHAPE = 2,        /* non-positive or inconsistent dimension */
+    AGO_ERR_DTYPE = 3,        /* unknown dtype / activation code */
+    AGO_ERR_ALIGN = 4,        /* pointer not 16-byte aligned */
+    AGO_ERR_UNSUPPORTED = 5,  /* valid request the kernels do not cover */
+    AGO_ERR_WORKSPACE = 6,    /* workspace missing or too small */
+    AGO_ERR_LAUNCH = 7        /* HIP reported an error at launch */
+} ago_status;
+
+typedef enum { AGO_F32 = 0, AGO_BF16 = 1 } ago_dtype;
+typedef enum { AGO_ACT_NONE = 0, AGO_ACT_RELU = 1, AGO_ACT_RELU6 = 2, AGO_ACT_GELU_TANH = 3 } ago_act;
+typedef enum {
+    AGO_OP_FUSED_INVRES = 0, AGO_OP_FUSED_CONV_CHAIN = 1, AGO_OP_FUSED_FFN = 2, AGO_OP_FUSED_ATTN = 3,
+    AGO_OP_UNFUSED_INVRES = 4, AGO_OP_UNFUSED_CONV_CHAIN = 5, AGO_OP_UNFUSED_FFN = 6, AGO_OP_UNFUSED_ATTN = 7
+} ago_op;
+
+/* ------------------------------------------------------------------------- */
+/* Fused subgraphs (Sec. III-B): several complex operators, one kernel.        */
+/* ------------------------------------------------------------------------- */
+
+/* pointwise -> depthwise -> pointwise (the pw->dw and dw->pw pairs of Sec. III-B,
+ * Fig. 7a/7b; MobileNetV2 / MNasNet blocks of Sec. VI):
+ *   E = relu6(x * w1 + b1)              1x1 conv, Cin -> Cexp, E := 0 outside the image
+ *   D = relu6(dw3x3(E, wd, stride) + bd)
+ *   y = D * w2 + b2 (+ x if residual)   1x1 conv, Cexp -> Cout
+ * x:[N,H,W,Cin] w1:[Cin,Cexp] wd:[3,3,Cexp] w2:[Cexp,Cout] y:[N,OH,OW,Cout],
+ * OH = (H-1)/stride + 1.  stride is 1 or 2.  residual != 0 requires stride == 1 and
+ * Cin == Cout.  Requires Cin % 8 == 0, Cexp % 16 == 0, Cout % 8 == 0 (else UNSUPPORTED). */
+ago_status ago_fused_invres(const void* x, const void* w1, const float* b1,
+                            const void* wd, const float* bd,
+                            const void* w2, const float* b2, void* y,
+                            int N, int H, int W, int Cin, int Cexp, int Cout,
+                            int stride, int residual, ago_dtype dt,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* conv3x3 -> conv3x3 (general convolution downstream, Sec. III-B Fig. 5 and the
+ * recompute analysis that follows it), fused with halo recompute:
+ *   T = relu(conv3x3(x, wa) + ba), T := 0 outside the image
+ *   y = relu(conv3x3(T, wb) + bb (+ x if residual))
+ * x,y:[N,H,W,C]  wa,wb:[3,3,C,C].  bf16 only; C must be 64 (else UNSUPPORTED). */
+ago_status ago_fused_conv_chain(const void* x, const void* wa, const float* ba,
+                                const void* wb, const float* bb, void* y,
+                                int N, int H, int W, int C, int residual, ago_dtype dt,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* matmul -> matmul (pw->pw; a matrix product is a pointwise convolution, Sec. III-B):
+ *   y = act(x w1 + b1) w2 + b2
+ * x:[M,K] w1:[K,F] w2:[F,K2] y:[M,K2].  bf16 only.  The hidden activation never
+ * leaves the chip; partial sums over slices of F go through `workspace`.
+ * Requires K % 32 == 0, F % 64 == 0, K2 % 64 == 0 (else UNSUPPORTED). */
+ago_status ago_fused_ffn(const void* x, const void* w1, const float* b1,
+                         const void* w2, const float* b2, void* y,
+                         int M, int K, int F, int K2, ago_act act, ago_dtype dt,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* matmul -> simple operators -> matmul (the attention chain of Sec. VI-C):
+ *   o = softmax_rows(scale * q k^T) v      per (batch, head), fp32 softmax
+ * q,k,v,o:[B,Hh,S,D].  bf16 only; D must be 64 (else UNSUPPORTED); any S >= 1. */
+ago_status ago_fused_attn(const void* q, const void* k, const void* v, void* o,
+                          int B, int Hh, int S, int D, float scale, ago_dtype dt,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------- */
+/* Un-fused per-operator kernels (Sec. III-A).  With bias == NULL and           */
+/* act == AGO_ACT_NONE each is exactly one operator (Fig. 3); with a bias /     */
+/* activation it is the conventional epilogue fusion of Fig. 4.                 */
+/* ------------------------------------------------------------------------- */
+
+/* c = act(a b + bias + res).  a:[M,K] b:[K,N] c,res:[M,N] bias:[N]; bias and res may be NULL.
+ * K % 8 == 0, N % 8 == 0. */
+ago_status ago_gemm(const void* a, const void* b, const float* bias, const void* res, void* c,
+                    int M, int K, int N, ago_act act, ago_dtype dt, void* hip_stream);
+/* Pointwise convolution = ago_gemm with M = N*H*W (Sec. III-B). x:[N,H,W,Cin] w:[Cin,Cout]. */
+ago_status ago_conv1x1(const void* x, const void* w, const float* bias, const void* res, void* y,
+                       int N, int H, int W, int Cin, int Cout, ago_act act, ago_dtype dt,
+                       void* hip_stream);
+/* y = act(dw3x3(x, w, stride, pad 1) + bias).  C % 8 == 0. */
+ago_status ago_dwconv3x3(const void* x, const void* w, const float* bias, void* y,
+                         int N, int H, int W, int C, int stride, ago_act act, ago_dtype dt,
+                         void* hip_stream);
+/* y = act(conv3x3(x, w, pad 1) + bias + res).  res may be NULL.  bf16, Cin == Cout == 64. */
+ago_status ago_conv3x3(const void* x, const void* w, const float* bias, const void* res, void* y,
+                       int N, int H, int W, int Cin, int Cout, ago_act act, ago_dtype dt,
+                       void* hip_stream);
+/* y[p][c] = act(x[p][c] + bias[c]); bias may be NULL; y may alias x.  C % 8 == 0. */
+ago_status ago_bias_act(const void* x, const float* bias, void* y, long P, int C,
+                        ago_act act, ago_dtype dt, void* hip_stream);
+/* y = act(a + b) elementwise; y may alias a.  n % 8 == 0. */
+ago_status ago_add_act(const void* a, const void* b, void* y, long n,
+                       ago_act act, ago_dtype dt, void* hip_stream);
+/* y = alpha * x elementwise; y may alias x.  n % 8 == 0. */
+ago_status ago_scale(const void* x, void* y, long n, float alpha, ago_dtype dt, void* hip_stream);
+/* Row softmax (max-subtracted, fp32 inside).  x has type in_dt, y type out_dt; supported pairs:
+ * (bf16,bf16), (f32,f32), (f32,bf16).  y may alias x when the types are equal.
+ * cols % 8 == 0, cols <= 4096. */
+ago_status ago_softmax_rows(const void* x, void* y, long rows, int cols, ago_dtype in_dt,
+                            ago_dtype out_dt, void* hip_stream);
+/* c[i] = alpha * a[i] b[i]^T.  a:[batch,M,K] b:[batch,N,K] bf16; c:[batch,M,N] of type out_dt
+ * (fp32 keeps attention scores unrounded for the fp32 softmax). */
+ago_status ago_bmm_nt(const void* a, const void* b, void* c, long batch, int M, int N, int K,
+                      float alpha, ago_dtype dt, ago_dtype out_dt, void* hip_stream);
+/* c[i] = a[i] b[i].  a:[batch,M,K] b:[batch,K,N] c:[batch,M,N].  bf16. */
+ago_status ago_bmm_nn(const void* a, const void* b, void* c, long batch, int M, int N, int K,
+                      ago_dtype dt, void* hip_stream);
+
+/* The same four subgraphs run operator by operator on the kernels above, with every
+ * intermediate tensor written to `workspace` (device) and read back by the next kernel.
+ * epilogue_fused == 0: one kernel per operator, simple operators included (Fig. 3);
+ * epilogue_fused != 0: each complex operator with its bias/activation/residual fused
+ * (Fig. 4, the paper's "conventional fusion").  Arguments as in the fused calls. */
+ago_status ago_unfused_invres(const void* x, const void* w1, const float* b1,
+                              const void* wd, const float* bd,
+                              const void* w2, const float* b2, void* y,
+                              int N, int H, int W, int Cin, int Cexp, int Cout,
+                              int stride, int residual, ago_dtype dt, int epilogue_fused,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+ago_status ago_unfused_conv_chain(const void* x, const void* wa, const float* ba,
+                                  const void* wb, const float* bb, void* y,
+                                  int N, int H, int W, int C, int residual, ago_dtype dt,
+                                  int epilogue_fused,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+ago_status ago_unfused_ffn(const void* x, const void* w1, const float* b1,
+                           const void* w2, const float* b2, void* y,
+                           int M, int K, int F, int K2, ago_act act, ago_dtype dt,
+                           int epilogue_fused,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+ago_status ago_unfused_attn(const void* q, const void* k, const void* v, void* o,
+                            int B, int Hh, int S, int D, float scale, ago_dtype dt,
+                            int epilogue_fused,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------- */
+/* Host-side helpers (no GPU work).                                            */
+/* ------------------------------------------------------------------------- */
+
+/* Bytes of workspace the given entry point needs for the given dimensions
+ * (`dims` is a host array holding the call's integer shape arguments in order,
+ * e.g. {M,K,F,K2} for the FFN or {N,H,W,Cin,Cexp,Cout,stride} for the inverted
+ * residual).  Returns 0 when none is needed or the arguments are invalid. */
+size_t ago_workspace_bytes(ago_op op, const int* dims, int ndims, ago_dtype dt);
+
+/* Static string naming a status code. */
+const char* ago_status_string(ago_status s);
+
+/* Select a tile configuration for a fused entry point (hook for the offline tile-size
+ * sweep that stands in for the paper's schedule search).  config_id = -1 restores the
+ * built-in choice.  Returns 0, or -1 for an unknown op / id. */
+int ago_set_tile_config(ago_op op, int config_id);
+/* Number of selectable tile configurations for `op` (0 for an unknown op). */
+int ago_num_tile_configs(ago_op op);
+
+/* Redundancy model of Sec. III-B: number of times the upstream reduction body runs
+ * when a conv R1xC1 (I -> O1) is fused under a downstream conv R2xC2 (O1 -> O2) whose
+ * output is tiled (to2, th2, tw2) on (O2, H2, W2), no padding, stride 1 (the setting of
+ * Fig. 5).  `unfused` (host pointer, may be NULL) receives the count without fusion,
+ * N*O1*(H2+R2-1)*(W2+C2-1).  Both counts exclude the I*R1*C1 factor of the reduction
+ * itself.  Tile sizes must divide the dimensions; returns -1 otherwise. */
+long long ago_fused_upstream_iterations(int N, int O1, int O2, int H2, int W2, int R2, int C2,
+                                        int to2, int th2, int tw2, long long* unfused);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AGO_H */

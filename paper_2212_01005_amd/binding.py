@@ -1,0 +1,235 @@
+"""Thin ctypes binding over libago.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point (include/ago.h),
+takes torch tensors that already live on the GPU, passes their device pointers plus the
+current torch stream, and raises AgoError on a non-zero status.  No arithmetic happens
+here; there is no fallback path: if the library is missing, importing this module fails.
+"""
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libago.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libago.so is not built; run `python -m paper_2212_01005_amd.build` "
+        "(there is no CPU or PyTorch fallback)")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+F32, BF16 = 0, 1
+ACT_NONE, ACT_RELU, ACT_RELU6, ACT_GELU_TANH = 0, 1, 2, 3
+OP_FUSED_INVRES, OP_FUSED_CONV_CHAIN, OP_FUSED_FFN, OP_FUSED_ATTN = 0, 1, 2, 3
+OP_UNFUSED_INVRES, OP_UNFUSED_CONV_CHAIN, OP_UNFUSED_FFN, OP_UNFUSED_ATTN = 4, 5, 6, 7
+
+_vp, _i, _l, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float, ctypes.c_size_t
+
+_SIGS = {
+    "ago_fused_invres": [_vp] * 8 + [_i] * 9 + [_vp, _sz, _vp],
+    "ago_fused_conv_chain": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
+    "ago_fused_ffn": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
+    "ago_fused_attn": [_vp] * 4 + [_i] * 4 + [_f, _i, _vp, _sz, _vp],
+    "ago_gemm": [_vp] * 5 + [_i] * 5 + [_vp],
+    "ago_conv1x1": [_vp] * 5 + [_i] * 7 + [_vp],
+    "ago_dwconv3x3": [_vp] * 4 + [_i] * 7 + [_vp],
+    "ago_conv3x3": [_vp] * 5 + [_i] * 7 + [_vp],
+    "ago_bias_act": [_vp] * 3 + [_l, _i, _i, _i, _vp],
+    "ago_add_act": [_vp] * 3 + [_l, _i, _i, _vp],
+    "ago_scale": [_vp] * 2 + [_l, _f, _i, _vp],
+    "ago_softmax_rows": [_vp] * 2 + [_l, _i, _i, _i, _vp],
+    "ago_bmm_nt": [_vp] * 3 + [_l, _i, _i, _i, _f, _i, _i, _vp],
+    "ago_bmm_nn": [_vp] * 3 + [_l, _i, _i, _i, _i, _vp],
+    "ago_unfused_invres": [_vp] * 8 + [_i] * 10 + [_vp, _sz, _vp],
+    "ago_unfused_conv_chain": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
+    "ago_unfused_ffn": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
+    "ago_unfused_attn": [_vp] * 4 + [_i] * 4 + [_f, _i, _i, _vp, _sz, _vp],
+}
+for _name, _args in _SIGS.items():
+    _fn = getattr(lib, _name)
+    _fn.argtypes = _args
+    _fn.restype = _i
+
+lib.ago_workspace_bytes.argtypes = [_i, ctypes.POINTER(_i), _i, _i]
+lib.ago_workspace_bytes.restype = _sz
+lib.ago_status_string.argtypes = [_i]
+lib.ago_status_string.restype = ctypes.c_char_p
+lib.ago_set_tile_config.argtypes = [_i, _i]
+lib.ago_set_tile_config.restype = _i
+lib.ago_num_tile_configs.argtypes = [_i]
+lib.ago_num_tile_configs.restype = _i
+lib.ago_fused_upstream_iterations.argtypes = [_i] * 10 + [ctypes.POINTER(ctypes.c_longlong)]
+lib.ago_fused_upstream_iterations.restype = ctypes.c_longlong
+
+EXPORTED = sorted(list(_SIGS) + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
+                                 "ago_num_tile_configs", "ago_fused_upstream_iterations"])
+
+
+class AgoError(RuntimeError):
+    def __init__(self, status):
+        self.status = int(status)
+        super().__init__(lib.ago_status_string(self.status).decode())
+
+
+def _chk(status):
+    if status != 0:
+        raise AgoError(status)
+
+
+def _p(t):
+    return None if t is None else t.data_ptr()
+
+
+def _dt(t):
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ws(ws):
+    return (None, 0) if ws is None else (ws.data_ptr(), ws.numel() * ws.element_size())
+
+
+def workspace_bytes(op, dims, dt):
+    arr = (_i * len(dims))(*dims)
+    return int(lib.ago_workspace_bytes(op, arr, len(dims), dt))
+
+
+def set_tile_config(op, config_id):
+    return int(lib.ago_set_tile_config(op, config_id))
+
+
+def num_tile_configs(op):
+    return int(lib.ago_num_tile_configs(op))
+
+
+def fused_upstream_iterations(N, O1, O2, H2, W2, R2, C2, to2, th2, tw2):
+    unf = ctypes.c_longlong(0)
+    v = lib.ago_fused_upstream_iterations(N, O1, O2, H2, W2, R2, C2, to2, th2, tw2, ctypes.byref(unf))
+    return int(v), int(unf.value)
+
+
+# ---- fused subgraphs ---------------------------------------------------------------
+
+def ago_fused_invres(x, w1, b1, wd, bd, w2, b2, y, stride, residual, workspace=None):
+    N, H, W, Cin = x.shape
+    Cexp, Cout = w2.shape
+    wp, wb = _ws(workspace)
+    _chk(lib.ago_fused_invres(_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
+                              N, H, W, Cin, Cexp, Cout, stride, int(residual), _dt(x), wp, wb, _stream()))
+
+
+def ago_fused_conv_chain(x, wa, ba, wb_, bb, y, residual, workspace=None):
+    N, H, W, C = x.shape
+    wp, wb = _ws(workspace)
+    _chk(lib.ago_fused_conv_chain(_p(x), _p(wa), _p(ba), _p(wb_), _p(bb), _p(y),
+                                  N, H, W, C, int(residual), _dt(x), wp, wb, _stream()))
+
+
+def ago_fused_ffn(x, w1, b1, w2, b2, y, act=ACT_GELU_TANH, workspace=None):
+    M, K = x.shape
+    F, K2 = w2.shape
+    wp, wb = _ws(workspace)
+    _chk(lib.ago_fused_ffn(_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
+                           wp, wb, _stream()))
+
+
+def ago_fused_attn(q, k, v, o, scale, workspace=None):
+    B, Hh, S, D = q.shape
+    wp, wb = _ws(workspace)
+    _chk(lib.ago_fused_attn(_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q), wp, wb, _stream()))
+
+
+# ---- un-fused operators ---------------------------------------------------------------
+
+def ago_gemm(a, b, bias, res, c, act=ACT_NONE):
+    M, K = a.shape
+    N = b.shape[1]
+    _chk(lib.ago_gemm(_p(a), _p(b), _p(bias), _p(res), _p(c), M, K, N, act, _dt(a), _stream()))
+
+
+def ago_conv1x1(x, w, bias, res, y, act=ACT_NONE):
+    N, H, W, Cin = x.shape
+    _chk(lib.ago_conv1x1(_p(x), _p(w), _p(bias), _p(res), _p(y), N, H, W, Cin, w.shape[1], act, _dt(x), _stream()))
+
+
+def ago_dwconv3x3(x, w, bias, y, stride, act=ACT_NONE):
+    N, H, W, C = x.shape
+    _chk(lib.ago_dwconv3x3(_p(x), _p(w), _p(bias), _p(y), N, H, W, C, stride, act, _dt(x), _stream()))
+
+
+def ago_conv3x3(x, w, bias, res, y, act=ACT_NONE):
+    N, H, W, Cin = x.shape
+    _chk(lib.ago_conv3x3(_p(x), _p(w), _p(bias), _p(res), _p(y), N, H, W, Cin, w.shape[3], act, _dt(x), _stream()))
+
+
+def ago_bias_act(x, bias, y, act=ACT_NONE):
+    C = x.shape[-1]
+    _chk(lib.ago_bias_act(_p(x), _p(bias), _p(y), x.numel() // C, C, act, _dt(x), _stream()))
+
+
+def ago_add_act(a, b, y, act=ACT_NONE):
+    _chk(lib.ago_add_act(_p(a), _p(b), _p(y), a.numel(), act, _dt(a), _stream()))
+
+
+def ago_scale(x, y, alpha):
+    _chk(lib.ago_scale(_p(x), _p(y), x.numel(), float(alpha), _dt(x), _stream()))
+
+
+def ago_softmax_rows(x, y):
+    cols = x.shape[-1]
+    _chk(lib.ago_softmax_rows(_p(x), _p(y), x.numel() // cols, cols, _dt(x), _dt(y), _stream()))
+
+
+def ago_bmm_nt(a, b, c, alpha=1.0):
+    M, K = a.shape[-2:]
+    N = b.shape[-2]
+    _chk(lib.ago_bmm_nt(_p(a), _p(b), _p(c), a.numel() // (M * K), M, N, K, float(alpha), _dt(a), _dt(c), _stream()))
+
+
+def ago_bmm_nn(a, b, c):
+    M, K = a.shape[-2:]
+    N = b.shape[-1]
+    _chk(lib.ago_bmm_nn(_p(a), _p(b), _p(c), a.numel() // (M * K), M, N, K, _dt(a), _stream()))
+
+
+# ---- un-fused subgraphs ---------------------------------------------------------------
+
+def ago_unfused_invres(x, w1, b1, wd, bd, w2, b2, y, stride, residual, epilogue_fused, workspace):
+    N, H, W, Cin = x.shape
+    Cexp, Cout = w2.shape
+    wp, wb = _ws(workspace)
+    _chk(lib.ago_unfused_invres(_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
+                                N, H, W, Cin, Cexp, Cout, stride, int(residual), _dt(x),
+                                int(epilogue_fused), wp, wb, _stream()))
+
+
+def ago_unfused_conv_chain(x, wa, ba, wb_, bb, y, residual, epilogue_fused, workspace):
+    N, H, W, C = x.shape
+    wp, wb = _ws(workspace)
+    _chk(lib.ago_unfused_conv_chain(_p(x), _p(wa), _p(ba), _p(wb_), _p(bb), _p(y), N, H, W, C,
+                                    int(residual), _dt(x), int(epilogue_fused), wp, wb, _stream()))
+
+
+def ago_unfused_ffn(x, w1, b1, w2, b2, y, act, epilogue_fused, workspace):
+    M, K = x.shape
+    F, K2 = w2.shape
+    wp, wb = _ws(workspace)
+    _chk(lib.ago_unfused_ffn(_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
+                             int(epilogue_fused), wp, wb, _stream()))
+
+
+def ago_unfused_attn(q, k, v, o, scale, epilogue_fused, workspace):
+    B, Hh, S, D = q.shape
+    wp, wb = _ws(workspace)
+    _chk(lib.ago_unfused_attn(_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q),
+                              int(epilogue_fused), wp, wb, _stream()))

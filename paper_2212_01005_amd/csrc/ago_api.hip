@@ -1,0 +1,271 @@
+// C ABI entry points: validate on the host (no HIP call before validation passes), then launch.
+#include <hip/hip_runtime.h>
+#include "ago_host.hpp"
+#include "ago_launch.hpp"
+
+using namespace ago;
+
+static inline ago_status from_hip(hipError_t e) {
+    if (e == hipSuccess) return AGO_OK;
+    return e == hipErrorInvalidValue ? AGO_ERR_UNSUPPORTED : AGO_ERR_LAUNCH;
+}
+static inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+static inline size_t esize(ago_dtype dt) { return dt == AGO_BF16 ? 2 : 4; }
+
+extern "C" {
+
+// ---------------------------------------------------------------- fused subgraphs
+ago_status ago_fused_invres(const void* x, const void* w1, const float* b1, const void* wd,
+                            const float* bd, const void* w2, const float* b2, void* y, int N, int H,
+                            int W, int Cin, int Cexp, int Cout, int stride, int residual, ago_dtype dt,
+                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    ago_status st = check_invres(x, w1, wd, w2, y, b1, bd, b2, N, H, W, Cin, Cexp, Cout, stride, residual, dt);
+    if (st != AGO_OK) return st;
+    return from_hip(fused_invres(x, w1, b1, wd, bd, w2, b2, y, N, H, W, Cin, Cexp, Cout, stride,
+                                 residual, dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES),
+                                 as_stream(hip_stream)));
+}
+
+ago_status ago_fused_conv_chain(const void* x, const void* wa, const float* ba, const void* wb,
+                                const float* bb, void* y, int N, int H, int W, int C, int residual,
+                                ago_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    ago_status st = check_conv_chain(x, wa, wb, y, ba, bb, N, H, W, C, dt);
+    if (st != AGO_OK) return st;
+    return from_hip(fused_conv_chain(x, wa, ba, wb, bb, y, N, H, W, residual,
+                                     tile_config(AGO_OP_FUSED_CONV_CHAIN), as_stream(hip_stream)));
+}
+
+ago_status ago_fused_ffn(const void* x, const void* w1, const float* b1, const void* w2,
+                         const float* b2, void* y, int M, int K, int F, int K2, ago_act act,
+                         ago_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    ago_status st = check_ffn(x, w1, w2, y, b1, b2, M, K, F, K2, act, dt);
+    if (st != AGO_OK) return st;
+    const int cfg = tile_config(AGO_OP_FUSED_FFN);
+    if (fused_ffn_pick_cfg(M, K, F, K2, cfg) < 0) return AGO_ERR_UNSUPPORTED;
+    const int dims[4] = {M, K, F, K2};
+    st = check_workspace(workspace, workspace_bytes, ago::workspace_bytes(AGO_OP_FUSED_FFN, dims, 4, dt));
+    if (st != AGO_OK) return st;
+    return from_hip(fused_ffn(x, w1, b1, w2, b2, y, M, K, F, K2, act, cfg, workspace, as_stream(hip_stream)));
+}
+
+ago_status ago_fused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
+                          int D, float scale, ago_dtype dt, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    ago_status st = check_attn(q, k, v, o, B, Hh, S, D, scale, dt);
+    if (st != AGO_OK) return st;
+    return from_hip(fused_attn(q, k, v, o, B, Hh, S, scale, tile_config(AGO_OP_FUSED_ATTN), as_stream(hip_stream)));
+}
+
+// ---------------------------------------------------------------- un-fused operators
+ago_status ago_gemm(const void* a, const void* b, const float* bias, const void* res, void* c, int M,
+                    int K, int N, ago_act act, ago_dtype dt, void* hip_stream) {
+    const void* ps[5] = {a, b, c, bias, res};
+    ago_status st = check_ptrs(ps, 3, 5);
+    if (st != AGO_OK) return st;
+    if (!valid_dtype(dt) || !valid_act(act)) return AGO_ERR_DTYPE;
+    if (M <= 0 || K <= 0 || N <= 0) return AGO_ERR_SHAPE;
+    if (K % 8 || N % 8) return AGO_ERR_UNSUPPORTED;
+    return from_hip(dt == AGO_BF16 ? gemm_bf16(a, b, bias, res, c, M, K, N, act, as_stream(hip_stream))
+                                   : gemm_f32(a, b, bias, res, c, M, K, N, act, as_stream(hip_stream)));
+}
+
+ago_status ago_conv1x1(const void* x, const void* w, const float* bias, const void* res, void* y, int N,
+                       int H, int W, int Cin, int Cout, ago_act act, ago_dtype dt, void* hip_stream) {
+    if (N <= 0 || H <= 0 || W <= 0) return (x && w && y) ? AGO_ERR_SHAPE : AGO_ERR_NULL;
+    const long P = (long)N * H * W;
+    if (P > 0x7fffffffL) return AGO_ERR_UNSUPPORTED;
+    return ago_gemm(x, w, bias, res, y, (int)P, Cin, Cout, act, dt, hip_stream);
+}
+
+ago_status ago_dwconv3x3(const void* x, const void* w, const float* bias, void* y, int N, int H, int W,
+                         int C, int stride, ago_act act, ago_dtype dt, void* hip_stream) {
+    const void* ps[4] = {x, w, y, bias};
+    ago_status st = check_ptrs(ps, 3, 4);
+    if (st != AGO_OK) return st;
+    if (!valid_dtype(dt) || !valid_act(act)) return AGO_ERR_DTYPE;
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || (stride != 1 && stride != 2)) return AGO_ERR_SHAPE;
+    if (C % 8) return AGO_ERR_UNSUPPORTED;
+    return from_hip(dwconv3x3(x, w, bias, y, N, H, W, C, stride, act, dt == AGO_BF16, as_stream(hip_stream)));
+}
+
+ago_status ago_conv3x3(const void* x, const void* w, const float* bias, const void* res, void* y, int N,
+                       int H, int W, int Cin, int Cout, ago_act act, ago_dtype dt, void* hip_stream) {
+    const void* ps[5] = {x, w, y, bias, res};
+    ago_status st = check_ptrs(ps, 3, 5);
+    if (st != AGO_OK) return st;
+    if (!valid_dtype(dt) || !valid_act(act)) return AGO_ERR_DTYPE;
+    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0) return AGO_ERR_SHAPE;
+    if (dt != AGO_BF16 || Cin != 64 || Cout != 64) return AGO_ERR_UNSUPPORTED;
+    return from_hip(conv3x3_bf16(x, w, bias, res, y, N, H, W, act, as_stream(hip_stream)));
+}
+
+ago_status ago_bias_act(const void* x, const float* bias, void* y, long P, int C, ago_act act,
+                        ago_dtype dt, void* hip_stream) {
+    const void* ps[3] = {x, y, bias};
+    ago_status st = check_ptrs(ps, 2, 3);
+    if (st != AGO_OK) return st;
+    if (!valid_dtype(dt) || !valid_act(act)) return AGO_ERR_DTYPE;
+    if (P <= 0 || C <= 0) return AGO_ERR_SHAPE;
+    if (C % 8) return AGO_ERR_UNSUPPORTED;
+    return from_hip(bias_act(x, bias, y, P, C, act, dt == AGO_BF16, as_stream(hip_stream)));
+}
+
+ago_status ago_add_act(const void* a, const void* b, void* y, long n, ago_act act, ago_dtype dt,
+                       void* hip_stream) {
+    const void* ps[3] = {a, b, y};
+    ago_status st = check_ptrs(ps, 3, 3);
+    if (st != AGO_OK) return st;
+    if (!valid_dtype(dt) || !valid_act(act)) return AGO_ERR_DTYPE;
+    if (n <= 0) return AGO_ERR_SHAPE;
+    if (n % 8) return AGO_ERR_UNSUPPORTED;
+    return from_hip(add_act(a, b, y, n, act, dt == AGO_BF16, as_stream(hip_stream)));
+}
+
+ago_status ago_scale(const void* x, void* y, long n, float alpha, ago_dtype dt, void* hip_stream) {
+    const void* ps[2] = {x, y};
+    ago_status st = check_ptrs(ps, 2, 2);
+    if (st != AGO_OK) return st;
+    if (!valid_dtype(dt)) return AGO_ERR_DTYPE;
+    if (n <= 0) return AGO_ERR_SHAPE;
+    if (n % 8) return AGO_ERR_UNSUPPORTED;
+    return from_hip(scale(x, y, n, alpha, dt == AGO_BF16, as_stream(hip_stream)));
+}
+
+ago_status ago_softmax_rows(const void* x, void* y, long rows, int cols, ago_dtype in_dt,
+                            ago_dtype out_dt, void* hip_stream) {
+    const void* ps[2] = {x, y};
+    ago_status st = check_ptrs(ps, 2, 2);
+    if (st != AGO_OK) return st;
+    if (!valid_dtype(in_dt) || !valid_dtype(out_dt)) return AGO_ERR_DTYPE;
+    if (rows <= 0 || cols <= 0) return AGO_ERR_SHAPE;
+    if (cols % 8 || cols > 4096 || (in_dt == AGO_BF16 && out_dt == AGO_F32)) return AGO_ERR_UNSUPPORTED;
+    return from_hip(softmax_rows(x, y, rows, cols, in_dt == AGO_BF16, out_dt == AGO_BF16, as_stream(hip_stream)));
+}
+
+ago_status ago_bmm_nt(const void* a, const void* b, void* c, long batch, int M, int N, int K, float alpha,
+                      ago_dtype dt, ago_dtype out_dt, void* hip_stream) {
+    const void* ps[3] = {a, b, c};
+    ago_status st = check_ptrs(ps, 3, 3);
+    if (st != AGO_OK) return st;
+    if (!valid_dtype(dt) || !valid_dtype(out_dt)) return AGO_ERR_DTYPE;
+    if (batch <= 0 || M <= 0 || N <= 0 || K <= 0) return AGO_ERR_SHAPE;
+    if (dt != AGO_BF16 || K % 8 || N % 8 || batch > 65535) return AGO_ERR_UNSUPPORTED;
+    return from_hip(bmm_nt_bf16(a, b, c, batch, M, N, K, alpha, out_dt == AGO_F32, as_stream(hip_stream)));
+}
+
+ago_status ago_bmm_nn(const void* a, const void* b, void* c, long batch, int M, int N, int K,
+                      ago_dtype dt, void* hip_stream) {
+    const void* ps[3] = {a, b, c};
+    ago_status st = check_ptrs(ps, 3, 3);
+    if (st != AGO_OK) return st;
+    if (!valid_dtype(dt)) return AGO_ERR_DTYPE;
+    if (batch <= 0 || M <= 0 || N <= 0 || K <= 0) return AGO_ERR_SHAPE;
+    if (dt != AGO_BF16 || K % 8 || N % 8 || batch > 65535) return AGO_ERR_UNSUPPORTED;
+    return from_hip(bmm_nn_bf16(a, b, c, batch, M, N, K, as_stream(hip_stream)));
+}
+
+// ---------------------------------------------------------------- un-fused subgraphs
+#define AGO_TRY(expr) do { ago_status _s = (expr); if (_s != AGO_OK) return _s; } while (0)
+
+ago_status ago_unfused_invres(const void* x, const void* w1, const float* b1, const void* wd,
+                              const float* bd, const void* w2, const float* b2, void* y, int N, int H,
+                              int W, int Cin, int Cexp, int Cout, int stride, int residual,
+                              ago_dtype dt, int epilogue_fused, void* workspace, size_t workspace_bytes,
+                              void* s) {
+    AGO_TRY(check_invres(x, w1, wd, w2, y, b1, bd, b2, N, H, W, Cin, Cexp, Cout, stride, residual, dt));
+    const int dims[7] = {N, H, W, Cin, Cexp, Cout, stride};
+    AGO_TRY(check_workspace(workspace, workspace_bytes, ago::workspace_bytes(AGO_OP_UNFUSED_INVRES, dims, 7, dt)));
+    const int OH = (H - 1) / stride + 1, OW = (W - 1) / stride + 1;
+    const long PE = (long)N * H * W, PO = (long)N * OH * OW;
+    char* e = static_cast<char*>(workspace);
+    char* d = e + (size_t)PE * Cexp * esize(dt);
+    if (epilogue_fused) {
+        AGO_TRY(ago_conv1x1(x, w1, b1, nullptr, e, N, H, W, Cin, Cexp, AGO_ACT_RELU6, dt, s));
+        AGO_TRY(ago_dwconv3x3(e, wd, bd, d, N, H, W, Cexp, stride, AGO_ACT_RELU6, dt, s));
+        AGO_TRY(ago_conv1x1(d, w2, b2, residual ? x : nullptr, y, N, OH, OW, Cexp, Cout, AGO_ACT_NONE, dt, s));
+    } else {
+        AGO_TRY(ago_conv1x1(x, w1, nullptr, nullptr, e, N, H, W, Cin, Cexp, AGO_ACT_NONE, dt, s));
+        if (b1) AGO_TRY(ago_bias_act(e, b1, e, PE, Cexp, AGO_ACT_NONE, dt, s));
+        AGO_TRY(ago_bias_act(e, nullptr, e, PE, Cexp, AGO_ACT_RELU6, dt, s));
+        AGO_TRY(ago_dwconv3x3(e, wd, nullptr, d, N, H, W, Cexp, stride, AGO_ACT_NONE, dt, s));
+        if (bd) AGO_TRY(ago_bias_act(d, bd, d, PO, Cexp, AGO_ACT_NONE, dt, s));
+        AGO_TRY(ago_bias_act(d, nullptr, d, PO, Cexp, AGO_ACT_RELU6, dt, s));
+        AGO_TRY(ago_conv1x1(d, w2, nullptr, nullptr, y, N, OH, OW, Cexp, Cout, AGO_ACT_NONE, dt, s));
+        if (b2) AGO_TRY(ago_bias_act(y, b2, y, PO, Cout, AGO_ACT_NONE, dt, s));
+        if (residual) AGO_TRY(ago_add_act(y, x, y, PO * Cout, AGO_ACT_NONE, dt, s));
+    }
+    return AGO_OK;
+}
+
+ago_status ago_unfused_conv_chain(const void* x, const void* wa, const float* ba, const void* wb,
+                                  const float* bb, void* y, int N, int H, int W, int C, int residual,
+                                  ago_dtype dt, int epilogue_fused, void* workspace,
+                                  size_t workspace_bytes, void* s) {
+    AGO_TRY(check_conv_chain(x, wa, wb, y, ba, bb, N, H, W, C, dt));
+    const int dims[4] = {N, H, W, C};
+    AGO_TRY(check_workspace(workspace, workspace_bytes, ago::workspace_bytes(AGO_OP_UNFUSED_CONV_CHAIN, dims, 4, dt)));
+    const long P = (long)N * H * W;
+    void* t = workspace;
+    if (epilogue_fused) {
+        AGO_TRY(ago_conv3x3(x, wa, ba, nullptr, t, N, H, W, C, C, AGO_ACT_RELU, dt, s));
+        AGO_TRY(ago_conv3x3(t, wb, bb, residual ? x : nullptr, y, N, H, W, C, C, AGO_ACT_RELU, dt, s));
+    } else {
+        AGO_TRY(ago_conv3x3(x, wa, nullptr, nullptr, t, N, H, W, C, C, AGO_ACT_NONE, dt, s));
+        if (ba) AGO_TRY(ago_bias_act(t, ba, t, P, C, AGO_ACT_NONE, dt, s));
+        AGO_TRY(ago_bias_act(t, nullptr, t, P, C, AGO_ACT_RELU, dt, s));
+        AGO_TRY(ago_conv3x3(t, wb, nullptr, nullptr, y, N, H, W, C, C, AGO_ACT_NONE, dt, s));
+        if (bb) AGO_TRY(ago_bias_act(y, bb, y, P, C, AGO_ACT_NONE, dt, s));
+        if (residual) AGO_TRY(ago_add_act(y, x, y, P * C, AGO_ACT_NONE, dt, s));
+        AGO_TRY(ago_bias_act(y, nullptr, y, P, C, AGO_ACT_RELU, dt, s));
+    }
+    return AGO_OK;
+}
+
+ago_status ago_unfused_ffn(const void* x, const void* w1, const float* b1, const void* w2,
+                           const float* b2, void* y, int M, int K, int F, int K2, ago_act act,
+                           ago_dtype dt, int epilogue_fused, void* workspace, size_t workspace_bytes,
+                           void* s) {
+    AGO_TRY(check_ffn(x, w1, w2, y, b1, b2, M, K, F, K2, act, dt));
+    const int dims[4] = {M, K, F, K2};
+    AGO_TRY(check_workspace(workspace, workspace_bytes, ago::workspace_bytes(AGO_OP_UNFUSED_FFN, dims, 4, dt)));
+    void* h = workspace;
+    if (epilogue_fused) {
+        AGO_TRY(ago_gemm(x, w1, b1, nullptr, h, M, K, F, act, dt, s));
+        AGO_TRY(ago_gemm(h, w2, b2, nullptr, y, M, F, K2, AGO_ACT_NONE, dt, s));
+    } else {
+        AGO_TRY(ago_gemm(x, w1, nullptr, nullptr, h, M, K, F, AGO_ACT_NONE, dt, s));
+        if (b1) AGO_TRY(ago_bias_act(h, b1, h, M, F, AGO_ACT_NONE, dt, s));
+        if (act != AGO_ACT_NONE) AGO_TRY(ago_bias_act(h, nullptr, h, M, F, act, dt, s));
+        AGO_TRY(ago_gemm(h, w2, nullptr, nullptr, y, M, F, K2, AGO_ACT_NONE, dt, s));
+        if (b2) AGO_TRY(ago_bias_act(y, b2, y, M, K2, AGO_ACT_NONE, dt, s));
+    }
+    return AGO_OK;
+}
+
+ago_status ago_unfused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
+                            int D, float scale, ago_dtype dt, int epilogue_fused, void* workspace,
+                            size_t workspace_bytes, void* s) {
+    AGO_TRY(check_attn(q, k, v, o, B, Hh, S, D, scale, dt));
+    if (S % 8) return AGO_ERR_UNSUPPORTED;
+    const int dims[4] = {B, Hh, S, D};
+    AGO_TRY(check_workspace(workspace, workspace_bytes, ago::workspace_bytes(AGO_OP_UNFUSED_ATTN, dims, 4, dt)));
+    // scores stay fp32 (the softmax is an fp32 operator); the probabilities are rounded to bf16
+    // because they feed a bf16 matrix product
+    const long batch = (long)B * Hh;
+    void* sc = workspace;
+    void* pr = static_cast<char*>(workspace) + (size_t)batch * S * S * 4;
+    if (epilogue_fused) {
+        AGO_TRY(ago_bmm_nt(q, k, sc, batch, S, S, D, scale, dt, AGO_F32, s));
+    } else {
+        AGO_TRY(ago_bmm_nt(q, k, sc, batch, S, S, D, 1.0f, dt, AGO_F32, s));
+        AGO_TRY(ago_scale(sc, sc, batch * S * S, scale, AGO_F32, s));
+    }
+    AGO_TRY(ago_softmax_rows(sc, pr, batch * S, S, AGO_F32, dt, s));
+    AGO_TRY(ago_bmm_nn(pr, v, o, batch, S, D, S, dt, s));
+    return AGO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,180 @@
+// Un-fused spatial convolutions: depthwise 3x3 (VALU) and dense 3x3, 64 -> 64 channels,
+// as an implicit GEMM on the matrix cores.  Zero padding 1.
+#include "ago_dev.hpp"
+#include "ago_launch.hpp"
+
+namespace ago {
+
+// ---------------------------------------------------------------------------------------
+// depthwise 3x3: one thread per (output pixel, 8 channels); 9 taps, fp32 accumulate.
+// ---------------------------------------------------------------------------------------
+template <bool BF16>
+__device__ __forceinline__ void load8(const void* base, long elem, float (&v)[8]) {
+    if constexpr (BF16) {
+        const uint4 u = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(base) + elem);
+        v[0] = lo_bf16(u.x); v[1] = hi_bf16(u.x); v[2] = lo_bf16(u.y); v[3] = hi_bf16(u.y);
+        v[4] = lo_bf16(u.z); v[5] = hi_bf16(u.z); v[6] = lo_bf16(u.w); v[7] = hi_bf16(u.w);
+    } else {
+        const float4 a = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + elem);
+        const float4 b = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + elem + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void dwconv3x3_kernel(const void* x, const void* w,
+                                                        const float* __restrict__ bias, void* y,
+                                                        int N, int H, int W, int C, int OH, int OW,
+                                                        int stride, int act) {
+    const int C8 = C / 8;
+    const long total = (long)N * OH * OW * C8;
+    for (long it = blockIdx.x * 256L + threadIdx.x; it < total; it += (long)gridDim.x * 256) {
+        const int c = (int)(it % C8) * 8;
+        long p = it / C8;
+        const int ow = (int)(p % OW); p /= OW;
+        const int oh = (int)(p % OH);
+        const int n = (int)(p / OH);
+        float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int ih = oh * stride + r - 1;
+            if (ih < 0 || ih >= H) continue;
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const int iw = ow * stride + s - 1;
+                if (iw < 0 || iw >= W) continue;
+                float xv[8], wv[8];
+                load8<BF16>(x, (((long)n * H + ih) * W + iw) * C + c, xv);
+                load8<BF16>(w, (long)(r * 3 + s) * C + c, wv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] = fmaf(xv[e], wv[e], acc[e]);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = apply_act_rt(acc[e] + (bias ? bias[c + e] : 0.0f), act);
+        const long o = (((long)n * OH + oh) * OW + ow) * C + c;
+        if constexpr (BF16) {
+            *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(y) + o) =
+                make_uint4(pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3]),
+                           pack_bf16(acc[4], acc[5]), pack_bf16(acc[6], acc[7]));
+        } else {
+            float* yp = reinterpret_cast<float*>(y) + o;
+            *reinterpret_cast<float4*>(yp) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            *reinterpret_cast<float4*>(yp + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        }
+    }
+}
+
+hipError_t dwconv3x3(const void* x, const void* w, const float* bias, void* y, int N, int H, int W,
+                     int C, int stride, int act, bool bf16, hipStream_t s) {
+    const int OH = (H - 1) / stride + 1, OW = (W - 1) / stride + 1;
+    const long total = (long)N * OH * OW * (C / 8);
+    long g = (total + 255) / 256;
+    if (g > 4096) g = 4096;
+    if (g < 1) g = 1;
+    if (bf16) hipLaunchKernelGGL(dwconv3x3_kernel<true>, dim3((unsigned)g), dim3(256), 0, s, x, w, bias, y, N, H, W, C, OH, OW, stride, act);
+    else hipLaunchKernelGGL(dwconv3x3_kernel<false>, dim3((unsigned)g), dim3(256), 0, s, x, w, bias, y, N, H, W, C, OH, OW, stride, act);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// dense 3x3, C = 64 in and out, bf16: implicit GEMM  [pixels] x [9 taps * 64] x [64].
+// Workgroup: 128 consecutive output pixels x 64 channels, one k-tile (64 channels) per tap,
+// double-buffered LDS, 2 x 2 waves each 64 pixels x 32 channels.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void conv3x3_c64_kernel(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wt, const float* __restrict__ bias,
+    const bf16_t* __restrict__ R, bf16_t* __restrict__ Y, int N, int H, int W, int act) {
+    constexpr int C = 64, BM = 128, BN = 64, LD = C + 8;
+    __shared__ __align__(16) bf16_t As[2][BM][LD];
+    __shared__ __align__(16) bf16_t Bs[2][BN][LD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const long P = (long)N * H * W;
+    const long p0 = (long)blockIdx.x * BM;
+
+    // the 4 (pixel, 8-channel chunk) items of the A tile this thread stages
+    int ph[4], pw[4];
+    long pbase[4];
+    bool pv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int c = tid + 256 * u, row = c >> 3;
+        const long p = p0 + row;
+        pv[u] = p < P;
+        const long pp = pv[u] ? p : 0;
+        pw[u] = (int)(pp % W);
+        ph[u] = (int)((pp / W) % H);
+        pbase[u] = pp * C + (c & 7) * 8;
+    }
+    uint4 ra[4];
+    uint2 rb[8];
+    auto load_tile = [&](int tap) {
+        const int dr = tap / 3 - 1, ds = tap % 3 - 1;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int ih = ph[u] + dr, iw = pw[u] + ds;
+            const bool ok = pv[u] && ih >= 0 && ih < H && iw >= 0 && iw < W;
+            ra[u] = ok ? ld_u4(X + pbase[u] + ((long)dr * W + ds) * C) : make_uint4(0, 0, 0, 0);
+        }
+        if (tid < 128) {
+            const int nq = tid & 15, ko = tid >> 4;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                rb[kk] = *reinterpret_cast<const uint2*>(Wt + ((long)tap * C + ko * 8 + kk) * C + nq * 4);
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = tid + 256 * u;
+            st_u4(&As[buf][c >> 3][(c & 7) * 8], ra[u]);
+        }
+        if (tid < 128) {
+            const int nq = tid & 15, ko = tid >> 4;
+            uint4 t[4];
+            transpose_8x4(rb, t);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) st_u4(&Bs[buf][nq * 4 + q][ko * 8], t[q]);
+        }
+    };
+
+    f32x16 acc[2][1];
+    zero_acc(acc);
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+    for (int tap = 0; tap < 9; ++tap) {
+        const int buf = tap & 1;
+        if (tap + 1 < 9) load_tile(tap + 1);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            wave_mma_k16<2, 1>(acc, &As[buf][wm * 64][ks * 16], LD, &Bs[buf][wn * 32][ks * 16], LD, lane);
+        if (tap + 1 < 9) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+    const int j = lane & 31, h = lane >> 5;
+    const int col = wn * 32 + j;
+    const float bv = bias ? bias[col] : 0.0f;
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const long p = p0 + wm * 64 + m * 32 + acc_row(r, h);
+            if (p < P) {
+                float v = acc[m][0][r] + bv;
+                if (R) v += (float)R[p * C + col];
+                Y[p * C + col] = (bf16_t)apply_act_rt(v, act);
+            }
+        }
+}
+
+hipError_t conv3x3_bf16(const void* x, const void* w, const float* bias, const void* res, void* y,
+                        int N, int H, int W, int act, hipStream_t s) {
+    const long P = (long)N * H * W;
+    hipLaunchKernelGGL(conv3x3_c64_kernel, dim3((unsigned)((P + 127) / 128)), dim3(256), 0, s,
+                       (const bf16_t*)x, (const bf16_t*)w, bias, (const bf16_t*)res, (bf16_t*)y, N, H, W, act);
+    return hipGetLastError();
+}
+
+}  // namespace ago

@@ -1,0 +1,313 @@
+// Fused pointwise -> depthwise -> pointwise block (AGO Sec. III-B: pw->dw follows the
+// "downstream depthwise" rule of Fig. 7a, dw->pw the "downstream pointwise" rule of Fig. 7b).
+//
+// One workgroup owns a TOH x TOW tile of output pixels of one image and *all* expanded
+// channels, so the depthwise stage needs no data from other workgroups and the projection
+// reduces over channels that are all on-chip.  The expanded tensor E for the tile plus its
+// 1-pixel halo (recomputed by neighbouring tiles) lives in LDS as fp32; the depthwise output D
+// lives in LDS in the matrix-instruction input type.  Stages, separated by workgroup barriers:
+//   0  global -> LDS: X halo tile, W1, Wd, W2 (weights transposed for the bf16 path)
+//   1  E = relu6(X W1 + b1) on the matrix cores; E := 0 for pixels outside the image
+//   2  D = relu6(dw3x3(E) + bd) on the vector ALUs
+//   3  Y = D W2 + b2 (+ X) on the matrix cores, stored straight to global memory
+// Matrix instructions: 16x16x32 bf16 / 16x16x4 fp32 (small tiles: few pixels per workgroup).
+#include "ago_dev.hpp"
+#include "ago_launch.hpp"
+
+namespace ago {
+
+struct InvresParams {
+    const void* x; const void* w1; const float* b1; const void* wd; const float* bd;
+    const void* w2; const float* b2; void* y;
+    int N, H, W, Cin, Cexp, Cout, OH, OW, residual;
+    int TOH, TOW, tiles_h, tiles_w;
+    int EH, EW, PE, PEpad, POpad;   // E-region geometry of one tile
+    int KP1;                        // Cin padded to the k granularity of the matrix instruction
+    int KP2;                        // Cexp padded likewise
+    int CoutP;                      // Cout padded to 16
+    int ldx, ldw1, lde, ldd, ldw2;  // LDS leading dimensions (elements)
+    int off_w1, off_e, off_d, off_w2, off_wd;  // LDS byte offsets (Xs at 0)
+};
+
+template <bool BF16> struct InT { typedef float type; };
+template <> struct InT<true> { typedef bf16_t type; };
+
+template <bool BF16, int STRIDE>
+__global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p) {
+    typedef typename InT<BF16>::type T;
+    extern __shared__ __align__(16) unsigned char smem[];
+    T* Xs = reinterpret_cast<T*>(smem);
+    T* W1s = reinterpret_cast<T*>(smem + p.off_w1);
+    float* Es = reinterpret_cast<float*>(smem + p.off_e);
+    T* Ds = reinterpret_cast<T*>(smem + p.off_d);
+    T* W2s = reinterpret_cast<T*>(smem + p.off_w2);
+    float* Wds = reinterpret_cast<float*>(smem + p.off_wd);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int b = blockIdx.x;
+    const int tw = b % p.tiles_w; b /= p.tiles_w;
+    const int th = b % p.tiles_h;
+    const int n = b / p.tiles_h;
+    const int oh0 = th * p.TOH, ow0 = tw * p.TOW;
+    const int ih0 = oh0 * STRIDE - 1, iw0 = ow0 * STRIDE - 1;
+    const T* X = reinterpret_cast<const T*>(p.x) + (long)n * p.H * p.W * p.Cin;
+
+    // ---- stage 0: stage inputs and weights ------------------------------------------
+    constexpr int VE = BF16 ? 8 : 4;   // elements per 16-byte chunk
+    {
+        const int kch = p.KP1 / VE;
+        for (int it = tid; it < p.PEpad * kch; it += 256) {
+            const int pix = it / kch, kc = it % kch;
+            const int ey = pix / p.EW, ex = pix % p.EW;
+            const int ih = ih0 + ey, iw = iw0 + ex;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (pix < p.PE && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W && kc * VE < p.Cin)
+                v = ld_u4(X + ((long)ih * p.W + iw) * p.Cin + kc * VE);
+            st_u4(Xs + pix * p.ldx + kc * VE, v);
+        }
+    }
+    if constexpr (BF16) {
+        // W1 [Cin][Cexp] -> W1s[e][k], W2 [Cexp][Cout] -> W2s[co][k]; k beyond the real extent = 0
+        const bf16_t* W1 = reinterpret_cast<const bf16_t*>(p.w1);
+        const int nq1 = p.Cexp / 4;
+        for (int it = tid; it < (p.KP1 / 8) * nq1; it += 256) {
+            const int nq = it % nq1, ko = it / nq1;
+            uint2 r[8];
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                const int k = ko * 8 + kk;
+                r[kk] = k < p.Cin ? *reinterpret_cast<const uint2*>(W1 + (long)k * p.Cexp + nq * 4) : make_uint2(0, 0);
+            }
+            uint4 t[4];
+            transpose_8x4(r, t);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) st_u4(W1s + (nq * 4 + q) * p.ldw1 + ko * 8, t[q]);
+        }
+        const bf16_t* W2 = reinterpret_cast<const bf16_t*>(p.w2);
+        const int nq2 = p.CoutP / 4;
+        for (int it = tid; it < (p.KP2 / 8) * nq2; it += 256) {
+            const int nq = it % nq2, ko = it / nq2;
+            uint2 r[8];
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                const int k = ko * 8 + kk;
+                r[kk] = (k < p.Cexp && nq * 4 < p.Cout)
+                            ? *reinterpret_cast<const uint2*>(W2 + (long)k * p.Cout + nq * 4) : make_uint2(0, 0);
+            }
+            uint4 t[4];
+            transpose_8x4(r, t);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) st_u4(W2s + (nq * 4 + q) * p.ldw2 + ko * 8, t[q]);
+        }
+        // depthwise weights as fp32 [9][Cexp]
+        const uint16_t* WD = reinterpret_cast<const uint16_t*>(p.wd);
+        for (int it = tid; it < 9 * p.Cexp; it += 256) Wds[it] = bf16_to_f32(WD[it]);
+    } else {
+        // fp32: weights keep their [k][n] layout (the fp32 matrix instruction reads one k per lane)
+        const float* W1 = reinterpret_cast<const float*>(p.w1);
+        const int c4 = p.Cexp / 4;
+        for (int it = tid; it < p.KP1 * c4; it += 256) {
+            const int k = it / c4, q = it % c4;
+            const uint4 v = k < p.Cin ? ld_u4(W1 + (long)k * p.Cexp + q * 4) : make_uint4(0, 0, 0, 0);
+            st_u4(W1s + k * p.ldw1 + q * 4, v);
+        }
+        const float* W2 = reinterpret_cast<const float*>(p.w2);
+        const int o4 = p.CoutP / 4;
+        for (int it = tid; it < p.KP2 * o4; it += 256) {
+            const int k = it / o4, q = it % o4;
+            const uint4 v = (k < p.Cexp && q * 4 < p.Cout) ? ld_u4(W2 + (long)k * p.Cout + q * 4)
+                                                          : make_uint4(0, 0, 0, 0);
+            st_u4(W2s + k * p.ldw2 + q * 4, v);
+        }
+        const float* WD = reinterpret_cast<const float*>(p.wd);
+        for (int it = tid; it < 9 * p.Cexp; it += 256) Wds[it] = WD[it];
+    }
+    __syncthreads();
+
+    // ---- stage 1: expand.  acc rows = channels, cols = pixels (weights are operand A) ---
+    {
+        const int i = lane & 15, g = lane >> 4;
+        const int ptiles = p.PEpad / 16, ctiles = p.Cexp / 16;
+        for (int job = wave; job < ptiles * ctiles; job += 4) {
+            const int pt = job % ptiles, ct = job / ptiles;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (BF16) {
+                const bf16_t* ap = W1s + (ct * 16 + i) * p.ldw1 + 8 * g;
+                const bf16_t* bp = Xs + (pt * 16 + i) * p.ldx + 8 * g;
+                for (int k0 = 0; k0 < p.KP1; k0 += 32)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ld_bf16x8(ap + k0), ld_bf16x8(bp + k0), acc, 0, 0, 0);
+            } else {
+                const float* ap = W1s + g * p.ldw1 + ct * 16 + i;
+                const float* bp = Xs + (pt * 16 + i) * p.ldx + g;
+                for (int k0 = 0; k0 < p.KP1; k0 += 4)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[k0 * p.ldw1], bp[k0], acc, 0, 0, 0);
+            }
+            const int pix = pt * 16 + i;       // this lane's pixel; registers = channels 4g..4g+3
+            if (pix < p.PE) {
+                const int ey = pix / p.EW, ex = pix % p.EW;
+                const int ih = ih0 + ey, iw = iw0 + ex;
+                const bool inside = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+                const int e0 = ct * 16 + 4 * g;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (inside) {
+                    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (p.b1) bv = *reinterpret_cast<const float4*>(p.b1 + e0);
+                    v.x = apply_act<kRelu6>(acc[0] + bv.x);
+                    v.y = apply_act<kRelu6>(acc[1] + bv.y);
+                    v.z = apply_act<kRelu6>(acc[2] + bv.z);
+                    v.w = apply_act<kRelu6>(acc[3] + bv.w);
+                }
+                *reinterpret_cast<float4*>(Es + pix * p.lde + e0) = v;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- stage 2: depthwise 3x3 on the vector ALUs -------------------------------------
+    {
+        const int Q = p.KP2 / 4;           // channel quads including the zero k-padding of D
+        const int Qr = p.Cexp / 4;
+        for (int it = tid; it < p.TOH * p.TOW * Q; it += 256) {
+            const int q = it % Q, po = it / Q;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (q < Qr) {
+                const int oy = po / p.TOW, ox = po % p.TOW;
+                const float* ep = Es + ((oy * STRIDE) * p.EW + ox * STRIDE) * p.lde + 4 * q;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int s = 0; s < 3; ++s) {
+                        const float4 e = *reinterpret_cast<const float4*>(ep + (r * p.EW + s) * p.lde);
+                        const float4 w = *reinterpret_cast<const float4*>(Wds + (r * 3 + s) * p.Cexp + 4 * q);
+                        a.x = fmaf(e.x, w.x, a.x); a.y = fmaf(e.y, w.y, a.y);
+                        a.z = fmaf(e.z, w.z, a.z); a.w = fmaf(e.w, w.w, a.w);
+                    }
+                float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (p.bd) bv = *reinterpret_cast<const float4*>(p.bd + 4 * q);
+                a.x = apply_act<kRelu6>(a.x + bv.x); a.y = apply_act<kRelu6>(a.y + bv.y);
+                a.z = apply_act<kRelu6>(a.z + bv.z); a.w = apply_act<kRelu6>(a.w + bv.w);
+            }
+            if constexpr (BF16) {
+                *reinterpret_cast<uint2*>(Ds + po * p.ldd + 4 * q) = make_uint2(pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));
+            } else {
+                *reinterpret_cast<float4*>(Ds + po * p.ldd + 4 * q) = a;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- stage 3: project.  acc rows = pixels, cols = output channels -------------------
+    {
+        const int i = lane & 15, g = lane >> 4;
+        const int ptiles = p.POpad / 16, otiles = p.CoutP / 16;
+        T* Y = reinterpret_cast<T*>(p.y) + (long)n * p.OH * p.OW * p.Cout;
+        for (int job = wave; job < ptiles * otiles; job += 4) {
+            const int pt = job % ptiles, ot = job / ptiles;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (BF16) {
+                const bf16_t* ap = Ds + (pt * 16 + i) * p.ldd + 8 * g;
+                const bf16_t* bp = W2s + (ot * 16 + i) * p.ldw2 + 8 * g;
+                for (int k0 = 0; k0 < p.KP2; k0 += 32)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ld_bf16x8(ap + k0), ld_bf16x8(bp + k0), acc, 0, 0, 0);
+            } else {
+                const float* ap = Ds + (pt * 16 + i) * p.ldd + g;
+                const float* bp = W2s + g * p.ldw2 + ot * 16 + i;
+                for (int k0 = 0; k0 < p.KP2; k0 += 4)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[k0], bp[k0 * p.ldw2], acc, 0, 0, 0);
+            }
+            const int co = ot * 16 + i;        // this lane's output channel; registers = pixels 4g..4g+3
+            if (co < p.Cout) {
+                const float bv = p.b2 ? p.b2[co] : 0.0f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int po = pt * 16 + 4 * g + r;
+                    const int oy = po / p.TOW, ox = po % p.TOW;
+                    const int oh = oh0 + oy, ow = ow0 + ox;
+                    if (po < p.TOH * p.TOW && oh < p.OH && ow < p.OW) {
+                        float v = acc[r] + bv;
+                        if (p.residual) v += (float)Xs[((oy + 1) * p.EW + ox + 1) * p.ldx + co];
+                        Y[((long)oh * p.OW + ow) * p.Cout + co] = (T)v;
+                    }
+                }
+            }
+        }
+    }
+}
+
+static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// Lay out LDS for a tile; returns the byte count.
+static size_t plan_tile(InvresParams& p, bool bf16, int stride, int toh, int tow) {
+    p.TOH = toh; p.TOW = tow;
+    p.tiles_h = (p.OH + toh - 1) / toh; p.tiles_w = (p.OW + tow - 1) / tow;
+    p.EH = (toh - 1) * stride + 3; p.EW = (tow - 1) * stride + 3;
+    p.PE = p.EH * p.EW; p.PEpad = round_up(p.PE, 16); p.POpad = round_up(toh * tow, 16);
+    const int kg = bf16 ? 32 : 4, es = bf16 ? 2 : 4;
+    p.KP1 = round_up(p.Cin, kg); p.KP2 = round_up(p.Cexp, kg); p.CoutP = round_up(p.Cout, 16);
+    auto pad16 = [](int c) { int q = c; while (q % 32 != 16) q += 4; return q; };  // fp32 [k][n] rows
+    p.ldx = bf16 ? p.KP1 + 8 : p.KP1 + 4;
+    p.ldw1 = bf16 ? p.KP1 + 8 : pad16(p.Cexp);
+    p.lde = p.Cexp + 4;
+    p.ldd = bf16 ? p.KP2 + 8 : p.KP2 + 4;
+    p.ldw2 = bf16 ? p.KP2 + 8 : pad16(p.CoutP);
+    size_t off = (size_t)p.PEpad * p.ldx * es;
+    auto al = [](size_t v) { return (v + 15) / 16 * 16; };
+    p.off_w1 = (int)(off = al(off));
+    off += (size_t)(bf16 ? p.Cexp : p.KP1) * p.ldw1 * es;
+    p.off_e = (int)(off = al(off));
+    off += (size_t)p.PE * p.lde * 4;
+    p.off_d = (int)(off = al(off));
+    off += (size_t)p.POpad * p.ldd * es;
+    p.off_w2 = (int)(off = al(off));
+    off += (size_t)(bf16 ? p.CoutP : p.KP2) * p.ldw2 * es;
+    p.off_wd = (int)(off = al(off));
+    off += (size_t)9 * p.Cexp * 4;
+    return al(off);
+}
+
+// tile_cfg: -1 = built-in choice; otherwise index into the candidate list below.
+static const int kTileCand[][2] = {{2, 14}, {4, 4}, {1, 14}, {2, 2}, {4, 8}, {7, 7}, {2, 8}, {1, 8}};
+int fused_invres_num_cfgs() { return (int)(sizeof(kTileCand) / sizeof(kTileCand[0])); }
+
+hipError_t fused_invres(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
+                        const void* w2, const float* b2, void* y, int N, int H, int W, int Cin,
+                        int Cexp, int Cout, int stride, int residual, bool bf16, int tile_cfg,
+                        hipStream_t s) {
+    InvresParams p;
+    p.x = x; p.w1 = w1; p.b1 = b1; p.wd = wd; p.bd = bd; p.w2 = w2; p.b2 = b2; p.y = y;
+    p.N = N; p.H = H; p.W = W; p.Cin = Cin; p.Cexp = Cexp; p.Cout = Cout;
+    p.OH = (H - 1) / stride + 1; p.OW = (W - 1) / stride + 1; p.residual = residual;
+    constexpr size_t kLdsMax = 160 * 1024;
+    size_t smem = 0;
+    if (tile_cfg >= 0 && tile_cfg < fused_invres_num_cfgs()) {
+        smem = plan_tile(p, bf16, stride, kTileCand[tile_cfg][0], kTileCand[tile_cfg][1]);
+        if (smem > kLdsMax) return hipErrorInvalidValue;
+    } else {
+        // built-in choice: full-width strips of 2 rows when the image is narrow (stride 1),
+        // 4x4 tiles otherwise; shrink until the tile fits in LDS.
+        int toh = (stride == 1 && p.OW <= 16) ? 2 : 4;
+        int tow = (stride == 1 && p.OW <= 16) ? p.OW : 4;
+        for (;;) {
+            smem = plan_tile(p, bf16, stride, toh, tow);
+            if (smem <= kLdsMax) break;
+            if (tow > 1 && tow >= toh) tow = (tow + 1) / 2;
+            else if (toh > 1) toh = (toh + 1) / 2;
+            else return hipErrorInvalidValue;
+        }
+    }
+    const unsigned grid = (unsigned)(N * p.tiles_h * p.tiles_w);
+#define AGO_LAUNCH_INVRES(BF, ST)                                                                       \
+    do {                                                                                                \
+        auto kern = fused_invres_kernel<BF, ST>;                                                        \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                         \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax);   \
+        if (e != hipSuccess) return e;                                                                  \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, p);                                    \
+    } while (0)
+    if (bf16) { if (stride == 1) AGO_LAUNCH_INVRES(true, 1); else AGO_LAUNCH_INVRES(true, 2); }
+    else { if (stride == 1) AGO_LAUNCH_INVRES(false, 1); else AGO_LAUNCH_INVRES(false, 2); }
+#undef AGO_LAUNCH_INVRES
+    return hipGetLastError();
+}
+
+}  // namespace ago

@@ -1,0 +1,30 @@
+// Host-only logic behind the C ABI: argument validation, workspace sizes, tile-configuration
+// state and the recompute model.  No HIP header is included here, so this translation unit also
+// builds with a plain C++ compiler.
+#pragma once
+#include <stddef.h>
+#include "../../include/ago.h"
+
+namespace ago {
+
+// Validators return AGO_OK or the first problem found, in the order: NULL pointers, dtype /
+// activation codes, shapes, alignment, unsupported sizes, workspace.
+ago_status check_invres(const void* x, const void* w1, const void* wd, const void* w2, const void* y,
+                        const void* b1, const void* bd, const void* b2,
+                        int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int residual,
+                        int dt);
+ago_status check_conv_chain(const void* x, const void* wa, const void* wb, const void* y,
+                            const void* ba, const void* bb, int N, int H, int W, int C, int dt);
+ago_status check_ffn(const void* x, const void* w1, const void* w2, const void* y, const void* b1,
+                     const void* b2, int M, int K, int F, int K2, int act, int dt);
+ago_status check_attn(const void* q, const void* k, const void* v, const void* o, int B, int Hh, int S,
+                      int D, float scale, int dt);
+ago_status check_workspace(const void* workspace, size_t have, size_t need);
+ago_status check_ptrs(const void* const* ptrs, int n_required, int n_total);
+bool valid_dtype(int dt);
+bool valid_act(int act);
+
+size_t workspace_bytes(int op, const int* dims, int ndims, int dt);
+int tile_config(int op);          // current selection for a fused op (-1 = built-in)
+
+}  // namespace ago

@@ -1,0 +1,51 @@
+// Host-side launchers implemented next to their kernels; the C ABI in ago_api.hip validates
+// arguments and then calls these.  Every launcher enqueues on `s` and returns hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace ago {
+
+// un-fused operators
+hipError_t gemm_bf16(const void* a, const void* b, const float* bias, const void* res, void* c, int M,
+                     int K, int N, int act, hipStream_t s);
+hipError_t gemm_f32(const void* a, const void* b, const float* bias, const void* res, void* c, int M,
+                    int K, int N, int act, hipStream_t s);
+hipError_t bmm_nt_bf16(const void* a, const void* b, void* c, long batch, int M, int N, int K,
+                       float alpha, bool out_f32, hipStream_t s);
+hipError_t bmm_nn_bf16(const void* a, const void* b, void* c, long batch, int M, int N, int K,
+                       hipStream_t s);
+hipError_t dwconv3x3(const void* x, const void* w, const float* bias, void* y, int N, int H, int W,
+                     int C, int stride, int act, bool bf16, hipStream_t s);
+hipError_t conv3x3_bf16(const void* x, const void* w, const float* bias, const void* res, void* y,
+                        int N, int H, int W, int act, hipStream_t s);
+hipError_t bias_act(const void* x, const float* bias, void* y, long P, int C, int act, bool bf16,
+                    hipStream_t s);
+hipError_t add_act(const void* a, const void* b, void* y, long n, int act, bool bf16, hipStream_t s);
+hipError_t scale(const void* x, void* y, long n, float alpha, bool bf16, hipStream_t s);
+hipError_t softmax_rows(const void* x, void* y, long rows, int cols, bool in_bf16, bool out_bf16,
+                        hipStream_t s);
+
+// fused subgraphs
+hipError_t fused_invres(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
+                        const void* w2, const float* b2, void* y, int N, int H, int W, int Cin,
+                        int Cexp, int Cout, int stride, int residual, bool bf16, int tile_cfg,
+                        hipStream_t s);
+hipError_t fused_conv_chain(const void* x, const void* wa, const float* ba, const void* wb,
+                            const float* bb, void* y, int N, int H, int W, int residual, int tile_cfg,
+                            hipStream_t s);
+hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
+                     void* y, int M, int K, int F, int K2, int act, int tile_cfg, void* workspace,
+                     hipStream_t s);
+hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
+                      float scale, int tile_cfg, hipStream_t s);
+
+// tile-configuration tables (host only)
+int fused_invres_num_cfgs();
+int fused_conv_chain_num_cfgs();
+int fused_ffn_num_cfgs();
+int fused_attn_num_cfgs();
+int fused_ffn_pick_cfg(int M, int K, int F, int K2, int tile_cfg);   // -1 = no configuration fits
+int fused_ffn_nsplit(int cfg, int F);
+
+}  // namespace ago

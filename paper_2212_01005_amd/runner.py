@@ -1,0 +1,97 @@
+"""Plumbing shared by the tests and the benchmark: put a workload's tensors on the GPU,
+allocate outputs / workspaces with torch, and call the library through the binding.
+Nothing here computes any part of a subgraph.
+"""
+
+import numpy as np
+import torch
+
+from . import binding as ago
+
+
+def _torch_dtype(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def to_device(case, device="cuda:0"):
+    """numpy fp64 tensors of a workloads.*Case -> dict of device tensors in storage dtype."""
+    td = _torch_dtype(case.dtype)
+    out = {}
+    for name, arr in case.tensors().items():
+        if arr is None:
+            out[name] = None
+        elif name.startswith("b") and arr.ndim == 1:      # biases are always fp32
+            out[name] = torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(device)
+        else:
+            # values are already exactly representable in the storage dtype
+            out[name] = torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(device).to(td).contiguous()
+    return out
+
+
+def _dims(case):
+    k = type(case).__name__
+    if k == "InvresCase":
+        return [case.N, case.H, case.W, case.Cin, case.Cexp, case.Cout, case.stride]
+    if k == "ChainCase":
+        return [case.N, case.H, case.W, case.C]
+    if k == "FfnCase":
+        return [case.M, case.K, case.F, case.K2]
+    return [case.B, case.Hh, case.S, case.D]
+
+
+_FUSED_OP = {"InvresCase": ago.OP_FUSED_INVRES, "ChainCase": ago.OP_FUSED_CONV_CHAIN,
+             "FfnCase": ago.OP_FUSED_FFN, "AttnCase": ago.OP_FUSED_ATTN}
+
+
+def alloc_output(case, device="cuda:0"):
+    td = _torch_dtype(case.dtype)
+    k = type(case).__name__
+    if k == "InvresCase":
+        shape = (case.N, case.OH, case.OW, case.Cout)
+    elif k == "ChainCase":
+        shape = (case.N, case.H, case.W, case.C)
+    elif k == "FfnCase":
+        shape = (case.M, case.K2)
+    else:
+        shape = (case.B, case.Hh, case.S, case.D)
+    return torch.empty(shape, dtype=td, device=device)
+
+
+def alloc_workspace(case, fused=True, device="cuda:0"):
+    op = _FUSED_OP[type(case).__name__] + (0 if fused else 4)
+    n = ago.workspace_bytes(op, _dims(case), ago.BF16 if case.dtype == "bf16" else ago.F32)
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device) if n > 0 else None
+
+
+def run_fused(case, t, y, ws=None):
+    k = type(case).__name__
+    if k == "InvresCase":
+        ago.ago_fused_invres(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
+                             case.stride, case.residual, ws)
+    elif k == "ChainCase":
+        ago.ago_fused_conv_chain(t["x"], t["wa"], t["ba"], t["wb"], t["bb"], y, case.residual, ws)
+    elif k == "FfnCase":
+        ago.ago_fused_ffn(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, ago.ACT_GELU_TANH, ws)
+    else:
+        ago.ago_fused_attn(t["q"], t["k"], t["v"], y, case.scale, ws)
+    return y
+
+
+def run_unfused(case, t, y, ws, epilogue_fused):
+    k = type(case).__name__
+    if k == "InvresCase":
+        ago.ago_unfused_invres(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
+                               case.stride, case.residual, epilogue_fused, ws)
+    elif k == "ChainCase":
+        ago.ago_unfused_conv_chain(t["x"], t["wa"], t["ba"], t["wb"], t["bb"], y, case.residual,
+                                   epilogue_fused, ws)
+    elif k == "FfnCase":
+        ago.ago_unfused_ffn(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, ago.ACT_GELU_TANH,
+                            epilogue_fused, ws)
+    else:
+        ago.ago_unfused_attn(t["q"], t["k"], t["v"], y, case.scale, epilogue_fused, ws)
+    return y
+
+
+def to_numpy64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)

@@ -1,0 +1,172 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every symbol the header
+declares, rejects bad arguments before touching HIP, sizes workspaces, and its recompute model
+reproduces the closed forms of the paper's redundancy analysis (Sec. III-B)."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ago.h")
+LIB = os.path.join(ROOT, "paper_2212_01005_amd", "libago.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2212_01005_amd import build
+        build.build()
+    return ctypes.CDLL(LIB)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ago_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for must in ("ago_fused_invres", "ago_fused_ffn", "ago_fused_conv_chain", "ago_fused_attn",
+                 "ago_gemm", "ago_conv1x1", "ago_dwconv3x3", "ago_conv3x3", "ago_bias_act",
+                 "ago_add_act", "ago_softmax_rows", "ago_bmm_nt", "ago_bmm_nn",
+                 "ago_unfused_invres", "ago_unfused_ffn", "ago_workspace_bytes", "ago_status_string"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), "libago.so does not export " + name
+
+
+def test_binding_covers_every_declared_symbol(lib):
+    from paper_2212_01005_amd import binding
+    assert set(declared_functions()) == set(binding.EXPORTED)
+
+
+def _fake(addr=0x1000):
+    return ctypes.c_void_p(addr)
+
+
+def test_validation_runs_before_any_gpu_call(lib):
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.ago_fused_ffn.argtypes = [vp] * 6 + [ci] * 6 + [vp, sz, vp]
+    p = _fake()
+    ffn = lambda x, w1, w2, y, M, K, F, K2, act=3, dt=1, ws=None, wsz=0: lib.ago_fused_ffn(
+        x, w1, None, w2, None, y, M, K, F, K2, act, dt, ws, wsz, None)
+    assert ffn(None, p, p, p, 128, 64, 64, 64) == 1                       # NULL
+    assert ffn(p, p, p, p, 128, 64, 64, 64, dt=7) == 3                    # dtype
+    assert ffn(p, p, p, p, 128, 64, 64, 64, act=9) == 3                   # activation
+    assert ffn(p, p, p, p, 0, 64, 64, 64) == 2                            # shape
+    assert ffn(_fake(0x1004), p, p, p, 128, 64, 64, 64) == 4              # alignment
+    assert ffn(p, p, p, p, 128, 64, 64, 64, dt=0) == 5                    # fp32 FFN unsupported
+    assert ffn(p, p, p, p, 128, 64, 72, 64) == 5                          # F not tileable
+    assert ffn(p, p, p, p, 128, 64, 3072, 768) == 6                       # workspace missing
+    assert ffn(p, p, p, p, 128, 64, 3072, 768, ws=_fake(), wsz=16) == 6   # workspace too small
+
+    lib.ago_fused_invres.argtypes = [vp] * 8 + [ci] * 9 + [vp, sz, vp]
+    inv = lambda N, H, W, Cin, Cexp, Cout, st, res, dt=0, x=p: lib.ago_fused_invres(
+        x, p, None, p, None, p, None, p, N, H, W, Cin, Cexp, Cout, st, res, dt, None, 0, None)
+    assert inv(1, 14, 14, 32, 192, 32, 1, 1, x=None) == 1
+    assert inv(1, 14, 14, 32, 192, 32, 3, 0) == 2                         # stride
+    assert inv(1, 14, 14, 32, 192, 24, 1, 1) == 2                         # residual needs Cin == Cout
+    assert inv(1, 14, 14, 32, 192, 32, 2, 1) == 2                         # residual needs stride 1
+    assert inv(1, 14, 14, 30, 192, 32, 1, 0) == 5                         # Cin % 8
+
+    lib.ago_fused_conv_chain.argtypes = [vp] * 6 + [ci] * 6 + [vp, sz, vp]
+    assert lib.ago_fused_conv_chain(p, p, None, p, None, p, 1, 8, 8, 32, 0, 1, None, 0, None) == 5
+    assert lib.ago_fused_conv_chain(p, p, None, p, None, p, 1, 8, 8, 64, 0, 0, None, 0, None) == 5
+    assert lib.ago_fused_conv_chain(p, p, None, p, None, p, 1, -8, 8, 64, 0, 1, None, 0, None) == 2
+
+    lib.ago_fused_attn.argtypes = [vp] * 4 + [ci] * 4 + [ctypes.c_float, ci, vp, sz, vp]
+    assert lib.ago_fused_attn(p, p, p, None, 1, 1, 8, 64, 0.125, 1, None, 0, None) == 1
+    assert lib.ago_fused_attn(p, p, p, p, 1, 1, 8, 32, 0.125, 1, None, 0, None) == 5
+    assert lib.ago_fused_attn(p, p, p, p, 1, 1, 8, 64, -1.0, 1, None, 0, None) == 5
+
+    lib.ago_gemm.argtypes = [vp] * 5 + [ci] * 5 + [vp]
+    assert lib.ago_gemm(p, p, None, None, None, 8, 8, 8, 0, 1, None) == 1
+    assert lib.ago_gemm(p, p, None, None, p, 8, 12, 8, 0, 1, None) == 5
+
+
+def test_status_strings(lib):
+    lib.ago_status_string.restype = ctypes.c_char_p
+    lib.ago_status_string.argtypes = [ctypes.c_int]
+    seen = set()
+    for code in range(8):
+        s = lib.ago_status_string(code).decode()
+        assert s.startswith("AGO_") and s not in seen
+        seen.add(s)
+    assert lib.ago_status_string(99).decode().startswith("unknown")
+
+
+def test_workspace_sizes(lib):
+    from paper_2212_01005_amd import binding as ago
+    # FFN 2048x768x3072x768 with the built-in 192-wide hidden slices: 16 fp32 partial matrices
+    assert ago.workspace_bytes(ago.OP_FUSED_FFN, [2048, 768, 3072, 768], ago.BF16) == 16 * 2048 * 768 * 4
+    assert ago.workspace_bytes(ago.OP_FUSED_FFN, [64, 64, 64, 64], ago.BF16) == 0       # single slice
+    assert ago.workspace_bytes(ago.OP_FUSED_ATTN, [8, 12, 384, 64], ago.BF16) == 0
+    assert ago.workspace_bytes(ago.OP_UNFUSED_FFN, [2048, 768, 3072, 768], ago.BF16) == 2048 * 3072 * 2
+    assert ago.workspace_bytes(ago.OP_UNFUSED_ATTN, [8, 12, 384, 64], ago.BF16) == 96 * 384 * 384 * (4 + 2)
+    assert ago.workspace_bytes(ago.OP_UNFUSED_INVRES, [1, 56, 56, 24, 144, 32, 2], ago.BF16) == \
+        (56 * 56 + 28 * 28) * 144 * 2
+    assert ago.workspace_bytes(ago.OP_UNFUSED_CONV_CHAIN, [8, 56, 56, 64], ago.BF16) == 8 * 56 * 56 * 64 * 2
+    assert ago.workspace_bytes(ago.OP_FUSED_FFN, [0, 768, 3072, 768], ago.BF16) == 0
+
+
+def test_tile_config_hook(lib):
+    from paper_2212_01005_amd import binding as ago
+    for op in (ago.OP_FUSED_INVRES, ago.OP_FUSED_CONV_CHAIN, ago.OP_FUSED_FFN, ago.OP_FUSED_ATTN):
+        n = ago.num_tile_configs(op)
+        assert n >= 1
+        assert ago.set_tile_config(op, n) == -1
+        assert ago.set_tile_config(op, n - 1) == 0
+        assert ago.set_tile_config(op, -1) == 0
+    assert ago.num_tile_configs(42) == 0 and ago.set_tile_config(42, 0) == -1
+    # the FFN workspace follows the selected slice width
+    ago.set_tile_config(ago.OP_FUSED_FFN, 1)      # 384-wide slices -> 8 partials
+    try:
+        assert ago.workspace_bytes(ago.OP_FUSED_FFN, [2048, 768, 3072, 768], ago.BF16) == 8 * 2048 * 768 * 4
+    finally:
+        ago.set_tile_config(ago.OP_FUSED_FFN, -1)
+
+
+# ---- the redundancy model of Sec. III-B -------------------------------------------------
+
+def _golden():
+    rows = []
+    with open(os.path.join(ROOT, "tests", "golden", "recompute_counts.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                rows.append([int(v) for v in line.split()])
+    return rows
+
+
+def test_recompute_model_matches_the_papers_closed_forms(lib):
+    from paper_2212_01005_amd import binding as ago
+    for (N, O1, O2, H2, W2, R2, C2, to2, th2, tw2, fused, unfused) in _golden():
+        got = ago.fused_upstream_iterations(N, O1, O2, H2, W2, R2, C2, to2, th2, tw2)
+        assert got == (fused, unfused)
+
+
+def test_recompute_model_symbolic_forms(lib):
+    from paper_2212_01005_amd import binding as ago
+    import itertools
+    for N, O1, O2, H2, W2, R2, C2 in itertools.product((1, 2), (3, 8), (4, 16), (6, 32), (16, 48), (1, 3), (1, 3)):
+        # the 1 x 1 x 16 downstream tile of Fig. 5
+        fused, unf = ago.fused_upstream_iterations(N, O1, O2, H2, W2, R2, C2, 1, 1, 16)
+        assert fused == N * O2 * H2 * (W2 // 16) * O1 * R2 * (15 + C2)
+        assert unf == N * O1 * (H2 + R2 - 1) * (W2 + C2 - 1)
+        # Fig. 7b: pointwise downstream (R2 = C2 = 1) with all output channels in the tile -> no redundancy
+        f2, u2 = ago.fused_upstream_iterations(N, O1, O2, H2, W2, 1, 1, O2, 1, 16)
+        assert f2 == u2
+        # untiled downstream -> no redundancy for any window
+        f3, u3 = ago.fused_upstream_iterations(N, O1, O2, H2, W2, R2, C2, O2, H2, W2)
+        assert f3 == u3
+        # spatial tiling of a 3x3 downstream costs ((th+2)(tw+2))/(th tw) on the tile grid
+        if R2 == 3 and C2 == 3 and H2 % 2 == 0:
+            f4, _ = ago.fused_upstream_iterations(N, O1, O2, H2, W2, 3, 3, O2, 2, 16)
+            assert f4 == N * O1 * (H2 // 2) * (W2 // 16) * 4 * 18
+    assert ago.fused_upstream_iterations(1, 8, 8, 7, 16, 3, 3, 1, 2, 16)[0] == -1   # tile must divide

@@ -1,0 +1,255 @@
+"""GPU parity: every HIP entry point against the fp64 CPU oracle, element by element, on the
+same seeded inputs, through the C ABI (ctypes binding).
+
+Tolerance (spec bar): max relative error 1e-4 for fp32 storage, 2e-2 for bf16 storage with
+fp32 accumulation.  "Relative" is taken per element against max(|oracle_i|, rms(oracle)) so that
+exact zeros after a ReLU and sign changes do not make the ratio meaningless.
+"""
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from workloads import rng
+
+pytestmark = pytest.mark.gpu
+
+RTOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def assert_close(got, ref, dtype, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), "non-finite values in " + what
+    rms = float(np.sqrt(np.mean(ref ** 2)))
+    denom = np.maximum(np.abs(ref), rms if rms > 0 else 1.0)
+    err = np.abs(got - ref) / denom
+    worst = float(err.max())
+    assert worst <= RTOL[dtype], "%s: max rel err %.3e > %.1e at %s" % (
+        what, worst, RTOL[dtype], np.unravel_index(int(err.argmax()), err.shape))
+    return worst
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2212_01005_amd import binding, runner
+    return torch, binding, runner
+
+
+def _cases():
+    return wl.small_cases()
+
+
+@pytest.mark.parametrize("case", _cases(), ids=lambda c: c.name)
+def test_fused_matches_oracle(gpu, oracle, case):
+    torch, ago, runner = gpu
+    t = runner.to_device(case)
+    y = runner.alloc_output(case)
+    ws = runner.alloc_workspace(case, fused=True)
+    runner.run_fused(case, t, y, ws)
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(y), oracle.run_case(case), case.dtype, case.name)
+
+
+@pytest.mark.parametrize("epilogue_fused", [0, 1])
+@pytest.mark.parametrize("case", _cases(), ids=lambda c: c.name)
+def test_unfused_matches_oracle(gpu, oracle, case, epilogue_fused):
+    torch, ago, runner = gpu
+    if type(case).__name__ == "AttnCase" and case.S % 8:
+        pytest.skip("un-fused attention needs S % 8 == 0 (16-byte rows of the score matrix)")
+    t = runner.to_device(case)
+    y = runner.alloc_output(case)
+    ws = runner.alloc_workspace(case, fused=False)
+    runner.run_unfused(case, t, y, ws, epilogue_fused)
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(y), oracle.run_case(case), case.dtype, case.name)
+
+
+@pytest.mark.parametrize("idx", range(5))
+def test_fused_full_size_baseline(gpu, oracle, idx):
+    """The five benchmark configurations at full size, in the launch configuration bench.py times."""
+    torch, ago, runner = gpu
+    case = wl.baseline_case(idx)
+    t = runner.to_device(case)
+    y = runner.alloc_output(case)
+    ws = runner.alloc_workspace(case, fused=True)
+    runner.run_fused(case, t, y, ws)
+    torch.cuda.synchronize()
+    ref = oracle.run_case(case)
+    assert_close(runner.to_numpy64(y), ref, case.dtype, case.name)
+    # determinism: a second run gives identical bits (no atomics in any reduction)
+    y2 = runner.alloc_output(case)
+    runner.run_fused(case, t, y2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("idx", range(5))
+@pytest.mark.parametrize("epilogue_fused", [0, 1])
+def test_unfused_full_size_baseline(gpu, oracle, idx, epilogue_fused):
+    torch, ago, runner = gpu
+    case = wl.baseline_case(idx)
+    t = runner.to_device(case)
+    y = runner.alloc_output(case)
+    ws = runner.alloc_workspace(case, fused=False)
+    runner.run_unfused(case, t, y, ws, epilogue_fused)
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(y), oracle.run_case(case), case.dtype, case.name)
+
+
+def test_every_tile_config_gives_the_same_answer(gpu, oracle):
+    """All selectable tile configurations of each fused kernel agree with the oracle
+    (different tilings = different LDS hand-offs; a missing barrier would show here)."""
+    torch, ago, runner = gpu
+    picks = {"InvresCase": [c for c in _cases() if c.name in ("invres_f32_s1", "invres_bf16_s2")],
+             "ChainCase": [c for c in _cases() if c.name == "chain_ragged"],
+             "FfnCase": [c for c in _cases() if c.name == "ffn_ragged_rows"]}
+    ops = {"InvresCase": ago.OP_FUSED_INVRES, "ChainCase": ago.OP_FUSED_CONV_CHAIN, "FfnCase": ago.OP_FUSED_FFN}
+    try:
+        for kind, cases in picks.items():
+            for case in cases:
+                ref = oracle.run_case(case)
+                t = runner.to_device(case)
+                for cfg in range(ago.num_tile_configs(ops[kind])):
+                    assert ago.set_tile_config(ops[kind], cfg) == 0
+                    y = runner.alloc_output(case)
+                    y.zero_()
+                    try:
+                        ws = runner.alloc_workspace(case, fused=True)
+                        runner.run_fused(case, t, y, ws)
+                    except ago.AgoError as e:
+                        assert e.status == 5, e      # UNSUPPORTED for this shape is fine
+                        continue
+                    torch.cuda.synchronize()
+                    assert_close(runner.to_numpy64(y), ref, case.dtype, "%s cfg %d" % (case.name, cfg))
+    finally:
+        for op in ops.values():
+            ago.set_tile_config(op, -1)
+
+
+# ---- single operators -----------------------------------------------------------------
+
+def _dev(torch, arr, dtype):
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).cuda().to(td).contiguous()
+
+
+def _store(arr, dtype):
+    return rng.round_to_bf16(arr) if dtype == "bf16" else np.asarray(arr, np.float32).astype(np.float64)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(200, 72, 136), (64, 768, 64), (333, 256, 320)])
+def test_gemm_op(gpu, oracle, dtype, shape):
+    torch, ago, runner = gpu
+    M, K, N = shape
+    a, b = _store(rng.normal(1, (M, K)), dtype), _store(rng.normal(2, (K, N), 0.1), dtype)
+    bias = _store(rng.uniform(3, (N,), -1, 1), "f32")
+    res = _store(rng.normal(4, (M, N)), dtype)
+    c = torch.empty((M, N), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda")
+    ago.ago_gemm(_dev(torch, a, dtype), _dev(torch, b, dtype), None, None, c, ago.ACT_NONE)
+    assert_close(runner.to_numpy64(c), oracle.gemm(a, b), dtype, "gemm")
+    ago.ago_gemm(_dev(torch, a, dtype), _dev(torch, b, dtype), _dev(torch, bias, "f32"),
+                 _dev(torch, res, dtype), c, ago.ACT_RELU)
+    ref = oracle.relu(oracle.add(oracle.bias(oracle.gemm(a, b), bias), res))
+    assert_close(runner.to_numpy64(c), ref, dtype, "gemm+bias+res+relu")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("stride", [1, 2])
+def test_dwconv_op(gpu, oracle, dtype, stride):
+    torch, ago, runner = gpu
+    x, w = _store(rng.normal(5, (2, 13, 9, 24)), dtype), _store(rng.normal(6, (3, 3, 24), 0.3), dtype)
+    bias = _store(rng.uniform(7, (24,), -1, 1), "f32")
+    ref = oracle.relu6(oracle.bias(oracle.dwconv3x3(x, w, stride), bias))
+    y = torch.empty(ref.shape, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda")
+    ago.ago_dwconv3x3(_dev(torch, x, dtype), _dev(torch, w, dtype), _dev(torch, bias, "f32"), y, stride, ago.ACT_RELU6)
+    assert_close(runner.to_numpy64(y), ref, dtype, "dwconv")
+
+
+def test_conv3x3_op(gpu, oracle):
+    torch, ago, runner = gpu
+    x, w = _store(rng.normal(8, (2, 11, 13, 64)), "bf16"), _store(rng.normal(9, (3, 3, 64, 64), 0.06), "bf16")
+    ref = oracle.conv3x3(x, w)
+    y = torch.empty(ref.shape, dtype=torch.bfloat16, device="cuda")
+    ago.ago_conv3x3(_dev(torch, x, "bf16"), _dev(torch, w, "bf16"), None, None, y, ago.ACT_NONE)
+    assert_close(runner.to_numpy64(y), ref, "bf16", "conv3x3")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_simple_ops(gpu, oracle, dtype):
+    torch, ago, runner = gpu
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    x = _store(rng.normal(10, (37, 5, 48), 3.0), dtype)
+    b = _store(rng.uniform(11, (48,), -1, 1), "f32")
+    xd = _dev(torch, x, dtype)
+    y = torch.empty_like(xd)
+    for act, f in ((ago.ACT_NONE, lambda v: v), (ago.ACT_RELU, oracle.relu), (ago.ACT_RELU6, oracle.relu6),
+                   (ago.ACT_GELU_TANH, oracle.gelu_tanh)):
+        ago.ago_bias_act(xd, _dev(torch, b, "f32"), y, act)
+        assert_close(runner.to_numpy64(y), f(oracle.bias(x, b)), dtype, "bias_act %d" % act)
+    x2 = _store(rng.normal(12, x.shape), dtype)
+    ago.ago_add_act(xd, _dev(torch, x2, dtype), y, ago.ACT_RELU)
+    assert_close(runner.to_numpy64(y), oracle.relu(oracle.add(x, x2)), dtype, "add_act")
+    ago.ago_scale(xd, y, 0.125)
+    assert_close(runner.to_numpy64(y), oracle.scale(x, 0.125), dtype, "scale")
+    s = _store(rng.normal(13, (50, 384), 2.0), dtype)
+    sd = _dev(torch, s, dtype)
+    p = torch.empty_like(sd)
+    ago.ago_softmax_rows(sd, p)
+    assert_close(runner.to_numpy64(p), oracle.softmax_rows(s), dtype, "softmax")
+    assert p.dtype == td
+
+
+def test_bmm_ops(gpu, oracle):
+    torch, ago, runner = gpu
+    q, k = _store(rng.normal(14, (3, 100, 64)), "bf16"), _store(rng.normal(15, (3, 72, 64)), "bf16")
+    s = torch.empty((3, 100, 72), dtype=torch.bfloat16, device="cuda")
+    ago.ago_bmm_nt(_dev(torch, q, "bf16"), _dev(torch, k, "bf16"), s, 0.125)
+    assert_close(runner.to_numpy64(s), oracle.scale(oracle.bmm_nt(q, k), 0.125), "bf16", "bmm_nt")
+    p, v = _store(rng.uniform(16, (3, 100, 72)), "bf16"), _store(rng.normal(17, (3, 72, 64)), "bf16")
+    o = torch.empty((3, 100, 64), dtype=torch.bfloat16, device="cuda")
+    ago.ago_bmm_nn(_dev(torch, p, "bf16"), _dev(torch, v, "bf16"), o)
+    assert_close(runner.to_numpy64(o), oracle.bmm_nn(p, v), "bf16", "bmm_nn")
+
+
+# ---- edge cases -------------------------------------------------------------------------
+
+def test_attention_single_key_and_tiny_sequences(gpu, oracle):
+    torch, ago, runner = gpu
+    for S in (1, 2, 31, 129):
+        case = wl.AttnCase(1, 2, S, 64, 0.125, "bf16", 777 + S, name="attn_S%d" % S)
+        t = runner.to_device(case)
+        y = runner.alloc_output(case)
+        runner.run_fused(case, t, y, None)
+        torch.cuda.synchronize()
+        assert_close(runner.to_numpy64(y), oracle.run_case(case), "bf16", case.name)
+
+
+def test_invres_single_pixel_and_odd_sizes(gpu, oracle):
+    torch, ago, runner = gpu
+    for (h, w, s) in ((1, 1, 1), (1, 7, 2), (5, 3, 2), (17, 17, 1)):
+        case = wl.InvresCase(1, h, w, 8, 16, 8, s, s == 1, True, "f32", 900 + h, name="invres_%dx%d" % (h, w))
+        t = runner.to_device(case)
+        y = runner.alloc_output(case)
+        runner.run_fused(case, t, y, None)
+        torch.cuda.synchronize()
+        assert_close(runner.to_numpy64(y), oracle.run_case(case), "f32", case.name)
+
+
+def test_fused_padding_pads_the_intermediate(gpu, oracle):
+    """Large positive bias on the first operator: a kernel that padded the *input* instead of the
+    intermediate would leak act(bias) into the border."""
+    torch, ago, runner = gpu
+    case = wl.ChainCase(1, 9, 9, 64, False, "bf16", 4242, name="chain_border")
+    tens = case.tensors()
+    tens["ba"] = np.full(64, 3.0)
+    case.tensors = lambda: tens
+    t = runner.to_device(case)
+    y = runner.alloc_output(case)
+    runner.run_fused(case, t, y, None)
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(y), oracle.run_case(case), "bf16", case.name)
