@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-subgraph hot path on one MI355X.
+
+A "step" is one pass of the whole hot path: the five benchmark subgraphs (two inverted
+residuals, the 3x3 -> 3x3 chain, the FFN chain, the attention chain) each run once as its fused
+kernel, inputs already resident in HBM.  The timed region is exactly --steps steps between two
+torch.cuda.synchronize() calls.  One JSON line is printed:
+
+  value        algorithmic TFLOP/s of a step (multiply-adds of the complex operators only)
+  per_config   fused / un-fused (one kernel per operator, and epilogue-fused) microseconds,
+               TFLOP/s, roofline fraction and speed-ups for each of the five configurations
+  roofline     dominant kernel (the fused FFN kernel): algorithmic FLOPs per launch divided by its
+               average duration, measured with HIP events recorded around that kernel on its
+               launch stream during the timed region, against the dense bf16 MFMA peak
+  cpu_baseline the fp64 CPU oracle timed on the host cores on the same step
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3       # fp32 MFMA / vector
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--detail-iters", type=int, default=100, help="launches per variant in the per-config table")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-detail", action="store_true")
+    ap.add_argument("--only", type=int, default=-1, help="run only this configuration in the timed step (profiling aid)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    from paper_2212_01005_amd import binding as ago, runner
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+
+    idxs = list(range(5)) if args.only < 0 else [args.only]
+    cases = [wl.baseline_case(i) for i in idxs]
+    state = []
+    for c in cases:
+        t = runner.to_device(c)
+        state.append((c, t, runner.alloc_output(c), runner.alloc_workspace(c, fused=True)))
+
+    def step():
+        for c, t, y, ws in state:
+            runner.run_fused(c, t, y, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    ago.profile_enable(min(args.steps, 4096))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kernel_ms = {}
+    for op in range(4):
+        tot, n = ago.profile_read(op)
+        if n:
+            kernel_ms[op] = tot / n
+    ago.profile_enable(0)
+
+    flops_step = sum(c.flops() for c in cases)
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    # ---- roofline of the dominant kernel (fused FFN) -----------------------------------
+    roofline = None
+    ffn = [c for c in cases if type(c).__name__ == "FfnCase"]
+    if ffn and ago.OP_FUSED_FFN in kernel_ms:
+        dur_s = kernel_ms[ago.OP_FUSED_FFN] * 1e-3
+        ach = ffn[0].flops() / dur_s / 1e12
+        roofline = {"bound": "mfma", "kernel": "fused_ffn_kernel", "achieved": round(ach, 2),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                    "avg_kernel_us": round(dur_s * 1e6, 2), "traffic": None}
+
+    # ---- per-configuration table: fused vs un-fused, device time by events ----------------
+    per_config = []
+    if not args.no_detail:
+        def time_us(fn, iters):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / iters
+
+        for (c, t, y, ws) in state:
+            wsu = runner.alloc_workspace(c, fused=False)
+            yu = runner.alloc_output(c)
+            fused_us = time_us(lambda: runner.run_fused(c, t, y, ws), args.detail_iters)
+            u1_us = time_us(lambda: runner.run_unfused(c, t, yu, wsu, 0), args.detail_iters)
+            u2_us = time_us(lambda: runner.run_unfused(c, t, yu, wsu, 1), args.detail_iters)
+            tf = c.flops() / (fused_us * 1e-6) / 1e12
+            peak = PEAK_F32_TFLOPS if c.dtype == "f32" else PEAK_BF16_TFLOPS
+            t_mfma = c.flops() / (peak * 1e12)
+            t_hbm = c.alg_bytes() / (PEAK_HBM_GBS * 1e9)
+            bound = "mfma" if t_mfma >= t_hbm else "hbm"
+            per_config.append({
+                "name": c.name, "dtype": c.dtype, "fused_us": round(fused_us, 2),
+                "unfused_per_op_us": round(u1_us, 2), "unfused_epilogue_us": round(u2_us, 2),
+                "tflops": round(tf, 3), "gbs": round(c.alg_bytes() / (fused_us * 1e-6) / 1e9, 1),
+                "bound": bound, "roofline_frac": round(max(t_mfma, t_hbm) / (fused_us * 1e-6), 4),
+                "speedup_vs_per_op": round(u1_us / fused_us, 2),
+                "speedup_vs_epilogue": round(u2_us / fused_us, 2),
+            })
+
+    # ---- CPU baseline: the oracle as it stands, on the host cores ---------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ago_oracle
+        ago_oracle.lib()
+        inputs = [c.tensors() for c in cases]      # generation is not timed
+        tc0 = time.perf_counter()
+        for c in cases:
+            ago_oracle.run_case(c)
+        tc1 = time.perf_counter()
+        gen0 = time.perf_counter()
+        for c in cases:
+            c.tensors()
+        gen = time.perf_counter() - gen0           # run_case regenerates inputs: subtract that
+        secs = max((tc1 - tc0) - gen, 1e-9)
+        cpu = {"value": round(flops_step / secs / 1e12, 5), "unit": "TFLOP/s",
+               "cores": ago_oracle.num_threads(), "kind": "oracle",
+               "sample": "one full step (all %d configurations once, fp64, %.2f s)" % (len(cases), secs)}
+        del inputs
+
+    out = {
+        "metric": "fused-block TFLOP/s (algorithmic, one pass over the 5 fused subgraphs)",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "all 5 BASELINE configs, one fused launch each per step"
+                   if args.only < 0 else cases[0].name,
+                   "configs": [c.name for c in cases],
+                   "note": "config 0 is fp32 storage, configs 1-4 bf16 storage with fp32 accumulation"},
+        "roofline": roofline, "cpu_baseline": cpu, "per_config": per_config,
+        "fused_kernel_us": {str(k): round(v * 1e3, 2) for k, v in kernel_ms.items()},
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -194,6 +194,15 @@ int ago_set_tile_config(ago_op op, int config_id);
 /* Number of selectable tile configurations for `op` (0 for an unknown op). */
 int ago_num_tile_configs(ago_op op);
 
+/* Instrumentation for benchmarks.  ago_profile_enable(capacity > 0) makes every fused entry point
+ * record a HIP event pair on its launch stream around its dominant kernel (the last `capacity`
+ * calls per entry point are kept; capacity <= 0 switches it off and frees the events; at most
+ * 4096).  ago_profile_read waits for the recorded calls of `op` (one of the four AGO_OP_FUSED_*),
+ * writes their summed kernel time in milliseconds and their number to the host pointers, and
+ * clears the record.  Both return 0, or -1 on misuse / a HIP error.  Not thread-safe. */
+int ago_profile_enable(int capacity);
+int ago_profile_read(ago_op op, float* total_ms, int* count);
+
 /* Redundancy model of Sec. III-B: number of times the upstream reduction body runs
  * when a conv R1xC1 (I -> O1) is fused under a downstream conv R2xC2 (O1 -> O2) whose
  * output is tiled (to2, th2, tw2) on (O2, H2, W2), no padding, stride 1 (the setting of

@@ -64,8 +64,14 @@ lib.ago_num_tile_configs.restype = _i
 lib.ago_fused_upstream_iterations.argtypes = [_i] * 10 + [ctypes.POINTER(ctypes.c_longlong)]
 lib.ago_fused_upstream_iterations.restype = ctypes.c_longlong
 
+lib.ago_profile_enable.argtypes = [_i]
+lib.ago_profile_enable.restype = _i
+lib.ago_profile_read.argtypes = [_i, ctypes.POINTER(_f), ctypes.POINTER(_i)]
+lib.ago_profile_read.restype = _i
+
 EXPORTED = sorted(list(_SIGS) + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
-                                 "ago_num_tile_configs", "ago_fused_upstream_iterations"])
+                                 "ago_num_tile_configs", "ago_fused_upstream_iterations",
+                                 "ago_profile_enable", "ago_profile_read"])
 
 
 class AgoError(RuntimeError):
@@ -110,6 +116,19 @@ def set_tile_config(op, config_id):
 
 def num_tile_configs(op):
     return int(lib.ago_num_tile_configs(op))
+
+
+def profile_enable(capacity):
+    if lib.ago_profile_enable(int(capacity)) != 0:
+        raise RuntimeError("ago_profile_enable failed")
+
+
+def profile_read(op):
+    """(total kernel milliseconds, number of calls) recorded for a fused entry point."""
+    ms, n = _f(0.0), _i(0)
+    if lib.ago_profile_read(op, ctypes.byref(ms), ctypes.byref(n)) != 0:
+        raise RuntimeError("ago_profile_read failed")
+    return float(ms.value), int(n.value)
 
 
 def fused_upstream_iterations(N, O1, O2, H2, W2, R2, C2, to2, th2, tw2):

@@ -1,5 +1,6 @@
 // C ABI entry points: validate on the host (no HIP call before validation passes), then launch.
 #include <hip/hip_runtime.h>
+#include <vector>
 #include "ago_host.hpp"
 #include "ago_launch.hpp"
 
@@ -12,7 +13,63 @@ static inline ago_status from_hip(hipError_t e) {
 static inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 static inline size_t esize(ago_dtype dt) { return dt == AGO_BF16 ? 2 : 4; }
 
+// ---------------------------------------------------------------- instrumentation
+namespace {
+struct ProfRing {
+    std::vector<hipEvent_t> start, stop;
+    long calls = 0;
+};
+ProfRing g_prof[4];
+int g_prof_cap = 0;
+}  // namespace
+
+namespace ago {
+void prof_start(int op, hipStream_t s) {
+    if (g_prof_cap > 0) hipEventRecord(g_prof[op].start[g_prof[op].calls % g_prof_cap], s);
+}
+void prof_stop(int op, hipStream_t s) {
+    if (g_prof_cap > 0) {
+        hipEventRecord(g_prof[op].stop[g_prof[op].calls % g_prof_cap], s);
+        ++g_prof[op].calls;
+    }
+}
+}  // namespace ago
+
 extern "C" {
+
+int ago_profile_enable(int capacity) {
+    for (auto& r : g_prof) {
+        for (hipEvent_t e : r.start) hipEventDestroy(e);
+        for (hipEvent_t e : r.stop) hipEventDestroy(e);
+        r.start.clear(); r.stop.clear(); r.calls = 0;
+    }
+    g_prof_cap = 0;
+    if (capacity <= 0) return 0;
+    if (capacity > 4096) return -1;
+    for (auto& r : g_prof) {
+        r.start.resize(capacity); r.stop.resize(capacity);
+        for (int i = 0; i < capacity; ++i)
+            if (hipEventCreate(&r.start[i]) != hipSuccess || hipEventCreate(&r.stop[i]) != hipSuccess) return -1;
+    }
+    g_prof_cap = capacity;
+    return 0;
+}
+
+int ago_profile_read(ago_op op, float* total_ms, int* count) {
+    if ((int)op < 0 || (int)op > 3 || !total_ms || !count || g_prof_cap <= 0) return -1;
+    ProfRing& r = g_prof[(int)op];
+    const int n = (int)(r.calls < g_prof_cap ? r.calls : g_prof_cap);
+    float tot = 0.f;
+    for (int i = 0; i < n; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop[i]) != hipSuccess) return -1;
+        if (hipEventElapsedTime(&ms, r.start[i], r.stop[i]) != hipSuccess) return -1;
+        tot += ms;
+    }
+    *total_ms = tot; *count = n;
+    r.calls = 0;
+    return 0;
+}
 
 // ---------------------------------------------------------------- fused subgraphs
 ago_status ago_fused_invres(const void* x, const void* w1, const float* b1, const void* wd,

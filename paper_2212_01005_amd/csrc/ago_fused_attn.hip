@@ -171,8 +171,10 @@ hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int 
         attr_set = true;
     }
     dim3 grid((S + 127) / 128, (unsigned)(B * Hh));
+    prof_start(3, s);
     hipLaunchKernelGGL(fused_attn_kernel, grid, dim3(256), smem, s, (const bf16_t*)q, (const bf16_t*)k,
                        (const bf16_t*)v, (bf16_t*)o, S, scale * 1.4426950408889634f);
+    prof_stop(3, s);
     return hipGetLastError();
 }
 

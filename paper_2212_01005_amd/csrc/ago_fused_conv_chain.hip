@@ -210,9 +210,11 @@ static hipError_t launch_chain(const void* x, const void* wa, const float* ba, c
         attr_set = true;
     }
     const int tiles_h = (H + TH - 1) / TH, tiles_w = (W + TW - 1) / TW;
+    prof_start(1, s);
     hipLaunchKernelGGL(kern, dim3((unsigned)(N * tiles_h * tiles_w)), dim3(256), smem, s,
                        (const bf16_t*)x, (const bf16_t*)wa, ba, (const bf16_t*)wb, bb, (bf16_t*)y,
                        H, W, tiles_h, tiles_w, residual);
+    prof_stop(1, s);
     return hipGetLastError();
 }
 

@@ -299,10 +299,16 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
 #define AGO_LAUNCH_INVRES(BF, ST)                                                                       \
     do {                                                                                                \
         auto kern = fused_invres_kernel<BF, ST>;                                                        \
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                         \
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax);   \
-        if (e != hipSuccess) return e;                                                                  \
+        static bool attr_set = false;                                                                   \
+        if (!attr_set) {                                                                                \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                     \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax); \
+            if (e != hipSuccess) return e;                                                              \
+            attr_set = true;                                                                            \
+        }                                                                                               \
+        prof_start(0, s);                                                                               \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, p);                                    \
+        prof_stop(0, s);                                                                                \
     } while (0)
     if (bf16) { if (stride == 1) AGO_LAUNCH_INVRES(true, 1); else AGO_LAUNCH_INVRES(true, 2); }
     else { if (stride == 1) AGO_LAUNCH_INVRES(false, 1); else AGO_LAUNCH_INVRES(false, 2); }

@@ -40,6 +40,11 @@ hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void*
 hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
                       float scale, int tile_cfg, hipStream_t s);
 
+// Instrumentation hook (see ago_profile_enable): record an event pair around the dominant kernel
+// of a fused entry point.  No-ops unless profiling is enabled.
+void prof_start(int op, hipStream_t s);
+void prof_stop(int op, hipStream_t s);
+
 // tile-configuration tables (host only)
 int fused_invres_num_cfgs();
 int fused_conv_chain_num_cfgs();
