@@ -5,33 +5,146 @@
 //
 // One workgroup owns a TH x TW tile of output pixels of one image:
 //   load   X tile with a 2-pixel halo, (TH+4) x (TW+4) x 64, zero outside the image -> LDS
+//          all nine taps of Wa, transposed to [tap][out][in] -> LDS (83 KB)
 //   conv1  T = relu(conv3x3(X) + ba) on the (TH+2) x (TW+2) region -> LDS (bf16), T := 0 outside
-//          the image (the intermediate is what the second convolution pads)
+//          the image (the intermediate is what the second convolution pads).  No barrier inside:
+//          everything conv1 reads is resident.  Meanwhile Wb is prefetched into registers.
+//   swap   barrier, Wb registers -> the weight area of LDS, barrier
 //   conv2  Y = relu(conv3x3(T) + bb (+ X)) on TH x TW -> global memory
 // Both convolutions are implicit GEMMs [pixels] x [9 taps x 64] x [64] on 32x32x16 bf16 matrix
-// instructions.  Weights are streamed one tap (64 x 64) at a time through a double-buffered,
-// transposed LDS tile shared by the four waves; waves split the 32-pixel row tiles.
+// instructions, on 16 waves (four per SIMD: a single wave cannot issue LDS fragment reads fast
+// enough to keep its SIMD's matrix pipe busy).  The work of each convolution is dealt out as
+// (32-pixel row tile, 32-output-channel half) jobs to 8 wave pairs; the two waves of a pair each
+// reduce over one half of the input channels and their partial sums are added through LDS.
+//
+// LDS layout of the weights: row = output channel, 8 chunks of 8 input channels, chunk index
+// XOR-ed with (row >> 4) & 3 so that both the transposing stores (rows 4 apart) and the
+// fragment reads (consecutive rows) are bank-conflict free.
 #include "ago_dev.hpp"
 #include "ago_launch.hpp"
 
 namespace ago {
 
 template <int TH, int TW>
-__global__ __launch_bounds__(256) void fused_conv_chain_kernel(
+struct ChainGeom {
+    static constexpr int C = 64, LD = C + 8;
+    static constexpr int XH = TH + 4, XW = TW + 4, R1H = TH + 2, R1W = TW + 2;
+    static constexpr int P1 = R1H * R1W, P2 = TH * TW;
+    static constexpr int NMT1 = (P1 + 31) / 32, NMT2 = (P2 + 31) / 32;
+    static constexpr size_t kSmem = ((size_t)XH * XW + P1 + 9 * 64) * LD * 2 + 128 * 4;
+};
+
+// One convolution over an LDS-resident source tile, on 8 waves.  The work is cut into
+// (32-pixel row tile, 32-channel half) jobs, 2 * NMT of them; wave w takes job w, and jobs beyond
+// the first eight go to owners 1, 3, 5, 7, 0, 2, 4, 6 in that order so that owners that share a
+// SIMD (w and w + 4) do not both get an extra job.
+// SRC_W = width (pixels) of the source tile, DST_W = width of the destination region,
+// NP = destination pixels, NMT = row tiles.  WEIGHTS_A: weights are MFMA operand A
+// (accumulator rows = channels, cols = pixels), else operand B.
+template <int SRC_W, int DST_W, int NP, int NMT, bool WEIGHTS_A>
+struct ConvStage {
+    static constexpr int LD = 72;
+    static constexpr int NJ = 2 * NMT;                  // jobs
+    static constexpr int J = (NJ + 7) / 8;              // job slots per wave
+    f32x16 acc[J];
+    int off[J];                                         // LDS offset of this lane's pixel, tap (0,0)
+    int wrow[J];                                        // LDS offset of this lane's weight row
+    int wsw[J];                                         // chunk swizzle of that row
+
+    __device__ __forceinline__ static int job(int i, int wave) {
+        const int extra = ((wave & 1) ? 0 : 4) + (wave >> 1);
+        return i == 0 ? wave : 8 * i + extra;
+    }
+    __device__ __forceinline__ static bool live(int i, int wave) { return job(i, wave) < NJ; }
+    __device__ __forceinline__ static int tile(int i, int wave) { return job(i, wave) >> 1; }
+    __device__ __forceinline__ static int nt(int i, int wave) { return job(i, wave) & 1; }
+
+    __device__ __forceinline__ void init(int wave, int j, int h) {
+#pragma unroll
+        for (int i = 0; i < J; ++i) {
+            int m = tile(i, wave) * 32 + j;
+            if (m >= NP) m = 0;
+            off[i] = ((m / DST_W) * SRC_W + (m % DST_W)) * LD + 8 * h;
+            const int row = nt(i, wave) * 32 + j;
+            wrow[i] = row * LD;
+            wsw[i] = (row >> 4) & 3;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        }
+    }
+
+    struct Frag { bf16x8 w, x; };
+    // step = tap * 2 + (k-step within this wave's half of the input channels)
+    __device__ __forceinline__ Frag fetch(const bf16_t* src, const bf16_t* ws, int step, int i, int h, int kh) const {
+        const int tap = step >> 1, ks = 2 * kh + (step & 1);
+        const int shift = ((tap / 3) * SRC_W + tap % 3) * LD;
+        Frag f;
+        f.w = ld_bf16x8(ws + tap * 64 * LD + wrow[i] + (((ks * 2 + h) ^ wsw[i]) << 3));
+        f.x = ld_bf16x8(src + off[i] + shift + ks * 16);
+        return f;
+    }
+
+    // 9 taps x 2 k-steps (this wave's half of the input channels), fully unrolled, with the LDS
+    // fragment reads issued DEPTH steps ahead of the matrix instruction that consumes them.
+    // src = activation tile, ws = [9][64][LD] swizzled weights.
+    __device__ __forceinline__ void run(const bf16_t* src, const bf16_t* ws, int wj, int h, int kh) {
+        constexpr int DEPTH = 3, STEPS = 18;
+#pragma unroll
+        for (int i = 0; i < J; ++i) {
+            if (!live(i, wj)) continue;
+            Frag q[DEPTH];
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) q[d] = fetch(src, ws, d, i, h, kh);
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const Frag cur = q[s % DEPTH];
+                if (s + DEPTH < STEPS) q[s % DEPTH] = fetch(src, ws, s + DEPTH, i, h, kh);
+                acc[i] = WEIGHTS_A ? mfma32(cur.w, cur.x, acc[i]) : mfma32(cur.x, cur.w, acc[i]);
+            }
+        }
+    }
+
+    // Sum the two channel-half partial accumulators of every job: the kh = 1 waves park theirs in
+    // `scratch` (4 KB per job, [job][4][64 lanes] float4), the kh = 0 waves add them.  The caller
+    // places barriers before (scratch no longer read as weights) and between the two halves.
+    __device__ __forceinline__ void park(float* scratch, int wj, int lane) const {
+#pragma unroll
+        for (int i = 0; i < J; ++i) {
+            if (!live(i, wj)) continue;
+            float4* p = reinterpret_cast<float4*>(scratch) + (job(i, wj) * 4) * 64 + lane;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) p[g * 64] = make_float4(acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]);
+        }
+    }
+    __device__ __forceinline__ void gather(const float* scratch, int wj, int lane) {
+#pragma unroll
+        for (int i = 0; i < J; ++i) {
+            if (!live(i, wj)) continue;
+            const float4* p = reinterpret_cast<const float4*>(scratch) + (job(i, wj) * 4) * 64 + lane;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 v = p[g * 64];
+                acc[i][4 * g] += v.x; acc[i][4 * g + 1] += v.y; acc[i][4 * g + 2] += v.z; acc[i][4 * g + 3] += v.w;
+            }
+        }
+    }
+};
+
+template <int TH, int TW>
+__global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wa, const float* __restrict__ ba,
     const bf16_t* __restrict__ Wb, const float* __restrict__ bb, bf16_t* __restrict__ Y,
     int H, int W, int tiles_h, int tiles_w, int residual) {
-    constexpr int C = 64, LD = C + 8;
-    constexpr int XH = TH + 4, XW = TW + 4, R1H = TH + 2, R1W = TW + 2;
-    constexpr int P1 = R1H * R1W, P2 = TH * TW;
-    constexpr int NMT1 = (P1 + 31) / 32, NMT2 = (P2 + 31) / 32;
-    constexpr int MT1 = (NMT1 + 3) / 4, MT2 = (NMT2 + 3) / 4;   // row tiles per wave
+    typedef ChainGeom<TH, TW> G;
+    constexpr int C = G::C, LD = G::LD, XW = G::XW, R1W = G::R1W, P1 = G::P1, P2 = G::P2;
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* Xs = reinterpret_cast<bf16_t*>(smem);      // [XH*XW][LD]
-    bf16_t* Ts = Xs + XH * XW * LD;                    // [P1][LD]
-    bf16_t* Ws = Ts + P1 * LD;                         // [2][64][LD]  (out channel, in channel)
+    bf16_t* Ts = Xs + G::XH * XW * LD;                 // [P1][LD]
+    bf16_t* Ws = Ts + P1 * LD;                         // [9][64][LD]  (tap, out channel, in channel)
+    float* Bias = reinterpret_cast<float*>(Ws + 9 * 64 * LD);   // ba[64], bb[64] (0 when absent)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wj = wave & 7, kh = wave >> 3;     // job owner index, input-channel half
     const int j = lane & 31, h = lane >> 5;
     int b = blockIdx.x;
     const int tw = b % tiles_w; b /= tiles_w;
@@ -41,155 +154,113 @@ __global__ __launch_bounds__(256) void fused_conv_chain_kernel(
     X += (long)n * H * W * C;
     Y += (long)n * H * W * C;
 
-    // weights of one tap: global [c][o] -> registers -> LDS [o][c]
-    uint2 rw[8];
-    auto load_w = [&](int step) {        // step 0..8: Wa taps, 9..17: Wb taps
-        if (tid < 128) {
-            const bf16_t* Wt = (step < 9 ? Wa : Wb) + (long)(step % 9) * C * C;
-            const int nq = tid & 15, ko = tid >> 4;
+    // All nine taps of one weight tensor: 9 * 128 transposition units of [8 in][4 out];
+    // unit u -> tap u / 128, out-channel quad (u & 15), in-channel octet (u >> 4) & 7.
+    constexpr int WU = 2;        // ceil(1152 / 1024)
+    uint2 rw[WU][8];
+    auto load_w = [&](const bf16_t* Wsrc) {
+#pragma unroll
+        for (int i = 0; i < WU; ++i) {
+            const int u = tid + 1024 * i;
+            if (u >= 9 * 128) continue;
+            const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk)
-                rw[kk] = *reinterpret_cast<const uint2*>(Wt + (ko * 8 + kk) * C + nq * 4);
+                rw[i][kk] = *reinterpret_cast<const uint2*>(Wsrc + ((long)tap * C + ko * 8 + kk) * C + nq * 4);
         }
     };
-    auto store_w = [&](int buf) {
-        if (tid < 128) {
-            const int nq = tid & 15, ko = tid >> 4;
-            uint4 t[4];
-            transpose_8x4(rw, t);
+    auto store_w = [&]() {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) st_u4(Ws + (buf * 64 + nq * 4 + q) * LD + ko * 8, t[q]);
+        for (int i = 0; i < WU; ++i) {
+            const int u = tid + 1024 * i;
+            if (u >= 9 * 128) continue;
+            const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
+            uint4 t[4];
+            transpose_8x4(rw[i], t);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int o = nq * 4 + q;
+                st_u4(Ws + (tap * 64 + o) * LD + ((ko ^ ((o >> 4) & 3)) << 3), t[q]);
+            }
         }
     };
 
-    load_w(0);
-    for (int it = tid; it < XH * XW * 8; it += 256) {
+    load_w(Wa);
+    if (tid < 128) Bias[tid] = tid < 64 ? (ba ? ba[tid] : 0.0f) : (bb ? bb[tid - 64] : 0.0f);
+    for (int it = tid; it < G::XH * XW * 8; it += 1024) {
         const int pix = it >> 3, kc = it & 7;
         const int ih = oh0 - 2 + pix / XW, iw = ow0 - 2 + pix % XW;
         uint4 v = make_uint4(0, 0, 0, 0);
         if (ih >= 0 && ih < H && iw >= 0 && iw < W) v = ld_u4(X + ((long)ih * W + iw) * C + kc * 8);
         st_u4(Xs + pix * LD + kc * 8, v);
     }
-    store_w(0);
+    store_w();
     __syncthreads();
+    load_w(Wb);            // in flight during conv1
 
-    // ---- conv1: rows = output channels (weights are operand A), cols = region pixels ----
+    // ---- conv1: rows = output channels (weights are operand A), cols = region pixels --------
     {
-        int off[MT1];           // LDS element offset of this lane's pixel (tap 0,0) per row tile
-        bool live[MT1];         // wave-uniform: the row tile exists
+        ConvStage<XW, R1W, P1, G::NMT1, true> st;
+        st.init(wj, j, h);
+        st.run(Xs, Ws, wj, h, kh);
+        __syncthreads();                       // Wa is dead: its LDS area becomes reduction scratch
+        if (kh == 1) st.park(reinterpret_cast<float*>(Ws), wj, lane);
+        __syncthreads();
+        if (kh == 0) st.gather(reinterpret_cast<const float*>(Ws), wj, lane);
+        // epilogue: bias + ReLU, zero outside the image, bf16 -> Ts[pixel][channel]
 #pragma unroll
-        for (int t = 0; t < MT1; ++t) {
-            const int mt = wave + 4 * t;
-            live[t] = mt < NMT1;
-            int m = mt * 32 + j;
-            if (m >= P1) m = 0;
-            off[t] = ((m / R1W) * XW + (m % R1W)) * LD + 8 * h;
-        }
-        f32x16 acc[2][MT1];
-        zero_acc(acc);
-        for (int tap = 0; tap < 9; ++tap) {
-            const int buf = tap & 1;
-            load_w(tap + 1);                      // tap 8 prefetches the first tap of conv2
-            const int shift = ((tap / 3) * XW + tap % 3) * LD;
-            const bf16_t* wsb = Ws + (buf * 64 + j) * LD + 8 * h;
+        for (int i = 0; i < st.J; ++i) {
+            if (kh != 0 || !st.live(i, wj)) continue;
+            const int m = st.tile(i, wj) * 32 + j, ot = st.nt(i, wj);
+            if (m >= P1) continue;
+            const int y = oh0 - 1 + m / R1W, x = ow0 - 1 + m % R1W;
+            const bool inside = y >= 0 && y < H && x >= 0 && x < W;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const bf16x8 w0 = ld_bf16x8(wsb + ks * 16), w1 = ld_bf16x8(wsb + 32 * LD + ks * 16);
-#pragma unroll
-                for (int t = 0; t < MT1; ++t) {
-                    if (!live[t]) continue;
-                    const bf16x8 xf = ld_bf16x8(Xs + off[t] + shift + ks * 16);
-                    acc[0][t] = mfma32(w0, xf, acc[0][t]);
-                    acc[1][t] = mfma32(w1, xf, acc[1][t]);
+            for (int g = 0; g < 4; ++g) {
+                const int o = ot * 32 + 8 * g + 4 * h;
+                uint2 v = make_uint2(0, 0);
+                if (inside) {
+                    const float4 bv = *reinterpret_cast<const float4*>(Bias + o);
+                    v = make_uint2(pack_bf16(fmaxf(st.acc[i][4 * g] + bv.x, 0.f), fmaxf(st.acc[i][4 * g + 1] + bv.y, 0.f)),
+                                   pack_bf16(fmaxf(st.acc[i][4 * g + 2] + bv.z, 0.f), fmaxf(st.acc[i][4 * g + 3] + bv.w, 0.f)));
                 }
+                *reinterpret_cast<uint2*>(Ts + m * LD + o) = v;
             }
-            if (tap == 8) {
-                // epilogue: bias + ReLU, zero outside the image, bf16 -> Ts[pixel][channel]
-#pragma unroll
-                for (int t = 0; t < MT1; ++t) {
-                    if (!live[t]) continue;
-                    const int m = (wave + 4 * t) * 32 + j;
-                    if (m < P1) {
-                        const int y = oh0 - 1 + m / R1W, x = ow0 - 1 + m % R1W;
-                        const bool inside = y >= 0 && y < H && x >= 0 && x < W;
-#pragma unroll
-                        for (int ot = 0; ot < 2; ++ot)
-#pragma unroll
-                            for (int g = 0; g < 4; ++g) {
-                                const int o = ot * 32 + 8 * g + 4 * h;
-                                uint2 v = make_uint2(0, 0);
-                                if (inside) {
-                                    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-                                    if (ba) bv = *reinterpret_cast<const float4*>(ba + o);
-                                    v = make_uint2(pack_bf16(fmaxf(acc[ot][t][4 * g] + bv.x, 0.f),
-                                                             fmaxf(acc[ot][t][4 * g + 1] + bv.y, 0.f)),
-                                                   pack_bf16(fmaxf(acc[ot][t][4 * g + 2] + bv.z, 0.f),
-                                                             fmaxf(acc[ot][t][4 * g + 3] + bv.w, 0.f)));
-                                }
-                                *reinterpret_cast<uint2*>(Ts + m * LD + o) = v;
-                            }
-                    }
-                }
-            }
-            store_w(buf ^ 1);
-            __syncthreads();
         }
     }
+    __syncthreads();       // Ts complete, reduction scratch no longer read
+    store_w();             // Wb -> LDS
+    __syncthreads();
 
-    // ---- conv2: rows = output pixels, cols = output channels -------------------------------
+    // ---- conv2: rows = output channels, cols = output pixels --------------------------------
     {
-        int off[MT2];
-        bool live[MT2];
+        ConvStage<R1W, TW, P2, G::NMT2, true> st;
+        st.init(wj, j, h);
+        st.run(Ts, Ws, wj, h, kh);
+        __syncthreads();
+        if (kh == 1) st.park(reinterpret_cast<float*>(Ws), wj, lane);
+        __syncthreads();
+        if (kh == 0) st.gather(reinterpret_cast<const float*>(Ws), wj, lane);
+        // epilogue: lane = pixel, registers = 4 consecutive channels: bias, residual, ReLU, 8-byte stores
 #pragma unroll
-        for (int t = 0; t < MT2; ++t) {
-            const int mt = wave + 4 * t;
-            live[t] = mt < NMT2;
-            int m = mt * 32 + j;
-            if (m >= P2) m = 0;
-            off[t] = ((m / TW) * R1W + (m % TW)) * LD + 8 * h;
-        }
-        f32x16 acc[MT2][2];
-        zero_acc(acc);
-        for (int tap = 0; tap < 9; ++tap) {
-            const int buf = (tap + 9) & 1;
-            if (tap + 1 < 9) load_w(tap + 10);
-            const int shift = ((tap / 3) * R1W + tap % 3) * LD;
-            const bf16_t* wsb = Ws + (buf * 64 + j) * LD + 8 * h;
+        for (int i = 0; i < st.J; ++i) {
+            if (kh != 0 || !st.live(i, wj)) continue;
+            const int m = st.tile(i, wj) * 32 + j, ot = st.nt(i, wj);
+            const int py = m / TW, px = m % TW;
+            const int y = oh0 + py, x = ow0 + px;
+            if (m >= P2 || y >= H || x >= W) continue;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const bf16x8 w0 = ld_bf16x8(wsb + ks * 16), w1 = ld_bf16x8(wsb + 32 * LD + ks * 16);
-#pragma unroll
-                for (int t = 0; t < MT2; ++t) {
-                    if (!live[t]) continue;
-                    const bf16x8 tf = ld_bf16x8(Ts + off[t] + shift + ks * 16);
-                    acc[t][0] = mfma32(tf, w0, acc[t][0]);
-                    acc[t][1] = mfma32(tf, w1, acc[t][1]);
+            for (int g = 0; g < 4; ++g) {
+                const int o = ot * 32 + 8 * g + 4 * h;
+                float4 v = make_float4(st.acc[i][4 * g], st.acc[i][4 * g + 1], st.acc[i][4 * g + 2], st.acc[i][4 * g + 3]);
+                const float4 bv = *reinterpret_cast<const float4*>(Bias + 64 + o);
+                v.x += bv.x; v.y += bv.y; v.z += bv.z; v.w += bv.w;
+                if (residual) {
+                    const uint2 xr = *reinterpret_cast<const uint2*>(Xs + ((py + 2) * XW + px + 2) * LD + o);
+                    v.x += lo_bf16(xr.x); v.y += hi_bf16(xr.x); v.z += lo_bf16(xr.y); v.w += hi_bf16(xr.y);
                 }
-            }
-            if (tap + 1 < 9) {
-                store_w(buf ^ 1);
-                __syncthreads();
-            }
-        }
-        // epilogue: lane = output channel, registers = pixels
-#pragma unroll
-        for (int t = 0; t < MT2; ++t) {
-            if (!live[t]) continue;
-#pragma unroll
-            for (int ot = 0; ot < 2; ++ot) {
-                const int o = ot * 32 + j;
-                const float bv = bb ? bb[o] : 0.0f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = (wave + 4 * t) * 32 + acc_row(r, h);
-                    const int py = m / TW, px = m % TW;
-                    const int y = oh0 + py, x = ow0 + px;
-                    if (m < P2 && y < H && x < W) {
-                        float v = acc[t][ot][r] + bv;
-                        if (residual) v += (float)Xs[((py + 2) * XW + px + 2) * LD + o];
-                        Y[((long)y * W + x) * C + o] = (bf16_t)fmaxf(v, 0.0f);
-                    }
-                }
+                *reinterpret_cast<uint2*>(Y + ((long)y * W + x) * C + o) =
+                    make_uint2(pack_bf16(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f)), pack_bf16(fmaxf(v.z, 0.f), fmaxf(v.w, 0.f)));
             }
         }
     }
@@ -199,7 +270,7 @@ template <int TH, int TW>
 static hipError_t launch_chain(const void* x, const void* wa, const float* ba, const void* wb,
                                const float* bb, void* y, int N, int H, int W, int residual,
                                hipStream_t s) {
-    constexpr size_t smem = ((size_t)(TH + 4) * (TW + 4) + (size_t)(TH + 2) * (TW + 2) + 128) * 72 * 2;
+    constexpr size_t smem = ChainGeom<TH, TW>::kSmem;
     static_assert(smem <= 160 * 1024, "LDS");
     auto kern = fused_conv_chain_kernel<TH, TW>;
     static bool attr_set = false;
@@ -211,14 +282,14 @@ static hipError_t launch_chain(const void* x, const void* wa, const float* ba, c
     }
     const int tiles_h = (H + TH - 1) / TH, tiles_w = (W + TW - 1) / TW;
     prof_start(1, s);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(N * tiles_h * tiles_w)), dim3(256), smem, s,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(N * tiles_h * tiles_w)), dim3(1024), smem, s,
                        (const bf16_t*)x, (const bf16_t*)wa, ba, (const bf16_t*)wb, bb, (bf16_t*)y,
                        H, W, tiles_h, tiles_w, residual);
     prof_stop(1, s);
     return hipGetLastError();
 }
 
-// Tile configurations (TH x TW output pixels per workgroup): 0: 7x14  1: 14x14  2: 8x8  3: 6x14
+// Tile configurations (TH x TW output pixels per workgroup): 0: 7x14  1: 7x7  2: 8x8  3: 6x14
 int fused_conv_chain_num_cfgs() { return 4; }
 
 hipError_t fused_conv_chain(const void* x, const void* wa, const float* ba, const void* wb,
@@ -226,7 +297,7 @@ hipError_t fused_conv_chain(const void* x, const void* wa, const float* ba, cons
                             hipStream_t s) {
     switch (tile_cfg < 0 ? 0 : tile_cfg) {
         case 0: return launch_chain<7, 14>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
-        case 1: return launch_chain<14, 14>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
+        case 1: return launch_chain<7, 7>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
         case 2: return launch_chain<8, 8>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
         case 3: return launch_chain<6, 14>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
         default: return hipErrorInvalidValue;

@@ -2,40 +2,128 @@
 // Sec. III-B / Fig. 7b: the downstream tile keeps all of its output channels, the upstream
 // tile is a slice o1 of the hidden dimension, which is the downstream reduction dimension).
 //
-// Workgroup (s, rb) owns BM rows of X and the slice [s*FS, (s+1)*FS) of the hidden dimension:
+// Workgroup (s, rb), 8 waves, owns BM rows of X and the slice [s*FS, (s+1)*FS) of the hidden
+// dimension:
 //   phase 1  Hs[BM][FS] = act(X[rb] * W1[:, slice] + b1[slice])   -> bf16, stays in LDS
 //   phase 2  P[s][rb]   = Hs * W2[slice, :]                        -> fp32 partial, all K2 columns
 // The hidden activation never leaves the chip.  Because the slice is only part of the
 // downstream reduction, the F/FS partial products are summed (deterministically, in slice
 // order) by a second small kernel that also adds b2 and rounds to bf16.  With a single slice
 // (F == FS) phase 2 writes y directly.
+//
+// Both phases run the same software pipeline over 64-deep k-tiles:
+//   global -> registers two tiles ahead, registers -> LDS one tile ahead (weights transposed to
+//   [n][k] and chunk-swizzled on the way), LDS -> MFMA fragments one k16 step ahead, one
+//   barrier per tile.  Two register sets and two LDS buffers alternate (loop unrolled by two).
 #include "ago_dev.hpp"
 #include "ago_launch.hpp"
 
 namespace ago {
 
-// WF x WM1 = 4 waves in phase 1 (hidden x rows); WM2 x WN2 = 4 waves in phase 2 (rows x cols).
-template <int BM, int FS, int WF, int WM1, int BN2, int WM2, int WN2>
+constexpr int kFfnThreads = 512;
+
+// Stage a [64 k][BN n] tile of a row-major [K][N] matrix into LDS as [n][k] (k contiguous, 72
+// elements per row, 16-byte chunk index XOR-ed with (n >> 4) & 3): 8x4 transposition units,
+// unit u -> n-quad u % (BN/4), k-octet u / (BN/4).
+template <int BN>
+struct WeightStager {
+    static constexpr int UNITS = 8 * (BN / 4);
+    static constexpr int U = (UNITS + kFfnThreads - 1) / kFfnThreads;
+    uint2 r[U][8];
+    // No bounds checks and no predication: the caller guarantees that the whole [64][BN] tile lies
+    // inside W, and every thread issues the same number of loads.  (A conditional load inside the
+    // pipelined loop would make the compiler wait for *all* outstanding loads at the next use.)
+    __device__ __forceinline__ void load(const bf16_t* W, long ldw, int k0, int n0, int tid) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = (tid + kFfnThreads * u) % UNITS;   // surplus threads repeat a unit (never stored)
+            const int nq = c % (BN / 4), ko = c / (BN / 4);
+            const bf16_t* src = W + (long)(k0 + ko * 8) * ldw + n0 + nq * 4;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) r[u][kk] = *reinterpret_cast<const uint2*>(src + kk * ldw);
+        }
+    }
+    __device__ __forceinline__ void store(bf16_t* dst, int tid) const {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = tid + kFfnThreads * u;
+            if (UNITS % kFfnThreads != 0 && c >= UNITS) continue;
+            const int nq = c % (BN / 4), ko = c / (BN / 4);
+            uint4 t[4];
+            transpose_8x4(r[u], t);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = nq * 4 + q;
+                st_u4(dst + n * 72 + ((ko ^ ((n >> 4) & 3)) << 3), t[q]);
+            }
+        }
+    }
+};
+
+// Stage a [BM m][64 k] tile of a row-major [M][K] matrix into LDS as [m][k], 72 elements per row.
+template <int BM>
+struct ActStager {
+    static constexpr int CH = BM * 8 / kFfnThreads;
+    static_assert(CH >= 1, "tile too small");
+    uint4 r[CH];
+    // Rows beyond M are clamped to the last row (their results are never stored); k0 + 64 <= K.
+    __device__ __forceinline__ void load(const bf16_t* X, int K, int m0, int k0, int M, int tid) {
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int c = tid + kFfnThreads * u, row = c >> 3, kc = c & 7;
+            const int gm = min(m0 + row, M - 1);
+            r[u] = ld_u4(X + (long)gm * K + k0 + kc * 8);
+        }
+    }
+    __device__ __forceinline__ void store(bf16_t* dst, int tid) const {
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int c = tid + kFfnThreads * u, row = c >> 3, kc = c & 7;
+            st_u4(dst + row * 72 + kc * 8, r[u]);
+        }
+    }
+};
+
+// Fragments of one k16 step of a wave tile: NW row tiles of a swizzled weight tile and NA row
+// tiles of a plain activation tile (row stride lda elements).
+template <int NW, int NA>
+struct Frags {
+    bf16x8 w[NW], a[NA];
+    // ws points at the weight tile's row 0; w0 = first row of this wave (a multiple of 32)
+    __device__ __forceinline__ void fetch(const bf16_t* ws, int w0, const bf16_t* as, int lda, int ks, int i, int h) {
+#pragma unroll
+        for (int t = 0; t < NW; ++t) {
+            const int row = w0 + t * 32 + i;
+            w[t] = ld_bf16x8(ws + row * 72 + (((ks * 2 + h) ^ ((row >> 4) & 3)) << 3));
+        }
+#pragma unroll
+        for (int t = 0; t < NA; ++t) a[t] = ld_bf16x8(as + (t * 32 + i) * lda + ks * 16 + 8 * h);
+    }
+};
+
+template <int BM, int FS, int BN2>
 struct FfnCfg {
-    static constexpr int BK = 64, LD = BK + 8, LDH = FS + 8;
-    static constexpr int FT = FS / WF / 32, MT1 = BM / WM1 / 32;   // phase-1 wave tile (f x m)
-    static constexpr int MT2 = BM / WM2 / 32, NT2 = BN2 / WN2 / 32; // phase-2 wave tile (m x n)
+    static constexpr int BK = 64, LD = 72, LDH = FS + 8;
+    // phase 1: 2 (hidden) x 4 (rows) waves; phase 2: 2 (rows) x 4 (cols) waves
+    static constexpr int FT = FS / 2 / 32, MT1 = BM / 4 / 32;
+    static constexpr int MT2 = BM / 2 / 32, NT2 = BN2 / 4 / 32;
     static constexpr int KT2 = FS / BK;
     static constexpr size_t kStage1 = (size_t)2 * (BM + FS) * LD * 2;
     static constexpr size_t kHs = (size_t)BM * LDH * 2;
     static constexpr size_t kStage2 = (size_t)2 * BN2 * LD * 2;
-    static constexpr size_t kSmem = kStage1 > kHs + kStage2 ? kStage1 : kHs + kStage2;
-    static_assert(WF * WM1 == 4 && WM2 * WN2 == 4, "4 waves");
-    static_assert(FS % BK == 0 && FS % (WF * 32) == 0 && BM % (WM1 * 32) == 0, "phase-1 tiling");
-    static_assert(BM % (WM2 * 32) == 0 && BN2 % (WN2 * 32) == 0, "phase-2 tiling");
+    static constexpr size_t kMain = kStage1 > kHs + kStage2 ? kStage1 : kHs + kStage2;
+    static constexpr size_t kSmem = kMain + FS * 4;      // + b1 slice
+    static_assert(FS % 64 == 0 && BM % 128 == 0 && BN2 % 128 == 0, "tiling");
+    static_assert((FS / 2) % 32 == 0, "each phase-1 wave row must start on a multiple of 32 hidden units");
     static_assert(kSmem <= 160 * 1024, "LDS");
 };
 
-template <class Cfg, int BM, int FS, int WF, int WM1, int BN2, int WM2, int WN2>
-__global__ __launch_bounds__(256) void fused_ffn_kernel(
+template <int BM, int FS, int BN2>
+__global__ __launch_bounds__(kFfnThreads) void fused_ffn_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W1, const float* __restrict__ b1,
     const bf16_t* __restrict__ W2, const float* __restrict__ b2, bf16_t* __restrict__ Y,
     float* __restrict__ part, int M, int K, int F, int K2, int act) {
+    typedef FfnCfg<BM, FS, BN2> Cfg;
     constexpr int BK = Cfg::BK, LD = Cfg::LD, LDH = Cfg::LDH;
     constexpr int FT = Cfg::FT, MT1 = Cfg::MT1, MT2 = Cfg::MT2, NT2 = Cfg::NT2, KT2 = Cfg::KT2;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -43,82 +131,75 @@ __global__ __launch_bounds__(256) void fused_ffn_kernel(
     bf16_t* W1s = Xs + 2 * BM * LD;                        // [2][FS][LD]   phase 1
     bf16_t* Hs = reinterpret_cast<bf16_t*>(smem);          // [BM][LDH]     phase 2 (aliases phase-1 staging)
     bf16_t* W2s = Hs + BM * LDH;                           // [2][BN2][LD]  phase 2
+    float* B1s = reinterpret_cast<float*>(smem + Cfg::kMain);   // [FS]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 31, h = lane >> 5;
     const int split = blockIdx.x, nsplit = gridDim.x;
     const int m0 = blockIdx.y * BM, f0 = split * FS;
 
+    for (int t = tid; t < FS; t += kFfnThreads) B1s[t] = b1 ? b1[f0 + t] : 0.0f;
+
     // ------------------------------ phase 1 -------------------------------------------
     {
-        constexpr int X_CH = BM * BK / 8 / 256;
-        constexpr int W_UNITS = (BK / 8) * (FS / 4), W_U = (W_UNITS + 255) / 256;
-        uint4 rx[X_CH];
-        uint2 rw[W_U][8];
-        auto load_tile = [&](int k0) {
-#pragma unroll
-            for (int u = 0; u < X_CH; ++u) {
-                const int c = tid + 256 * u, row = c / (BK / 8), kc = c % (BK / 8);
-                const int gm = m0 + row, gk = k0 + kc * 8;
-                rx[u] = (gm < M && gk < K) ? ld_u4(X + (long)gm * K + gk) : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int u = 0; u < W_U; ++u) {
-                const int c = tid + 256 * u, nq = c % (FS / 4), ko = c / (FS / 4);
-                if (c >= W_UNITS) continue;
-#pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    const int gk = k0 + ko * 8 + kk;
-                    rw[u][kk] = gk < K ? *reinterpret_cast<const uint2*>(W1 + (long)gk * F + f0 + nq * 4)
-                                       : make_uint2(0, 0);
-                }
-            }
-        };
-        auto store_tile = [&](int buf) {
-#pragma unroll
-            for (int u = 0; u < X_CH; ++u) {
-                const int c = tid + 256 * u, row = c / (BK / 8), kc = c % (BK / 8);
-                st_u4(Xs + (buf * BM + row) * LD + kc * 8, rx[u]);
-            }
-#pragma unroll
-            for (int u = 0; u < W_U; ++u) {
-                const int c = tid + 256 * u, nq = c % (FS / 4), ko = c / (FS / 4);
-                if (c >= W_UNITS) continue;
-                uint4 t[4];
-                transpose_8x4(rw[u], t);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) st_u4(W1s + (buf * FS + nq * 4 + q) * LD + ko * 8, t[q]);
-            }
-        };
-        const int wf = wave / WM1, wm = wave % WM1;
-        f32x16 acc[FT][MT1];   // rows = hidden units, cols = rows of X
+        const int wf = wave >> 2, wm = wave & 3;
+        f32x16 acc[FT][MT1];           // rows = hidden units, cols = rows of X
         zero_acc(acc);
-        const int nk = (K + BK - 1) / BK;
-        load_tile(0);
-        store_tile(0);
-        __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            const int buf = kt & 1;
-            if (kt + 1 < nk) load_tile((kt + 1) * BK);
-            const bf16_t* as = W1s + (buf * FS + wf * FT * 32) * LD;
-            const bf16_t* bs = Xs + (buf * BM + wm * MT1 * 32) * LD;
+        ActStager<BM> xa, xb;
+        WeightStager<FS> wa, wb;
+        const int nk = K / BK;                      // K % 64 == 0 (checked by the host)
+        auto load = [&](ActStager<BM>& xs, WeightStager<FS>& ws, int kt) {
+            xs.load(X, K, m0, kt * BK, M, tid);
+            ws.load(W1, F, kt * BK, f0, tid);
+        };
+        auto tile = [&](int buf, bool store_next, const ActStager<BM>& xs, const WeightStager<FS>& ws) {
+            const bf16_t* wsrc = W1s + buf * FS * LD;
+            const bf16_t* asrc = Xs + (buf * BM + wm * MT1 * 32) * LD;
+            Frags<FT, MT1> fr[2];
+            fr[0].fetch(wsrc, wf * FT * 32, asrc, LD, 0, i, h);
 #pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks)
-                wave_mma_k16<FT, MT1>(acc, as + ks * 16, LD, bs + ks * 16, LD, lane);
-            if (kt + 1 < nk) store_tile(buf ^ 1);
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks < 3) fr[(ks + 1) & 1].fetch(wsrc, wf * FT * 32, asrc, LD, ks + 1, i, h);
+                if (store_next && ks == 0) xs.store(Xs + (buf ^ 1) * BM * LD, tid);
+                if (store_next && ks == 1) ws.store(W1s + (buf ^ 1) * FS * LD, tid);
+#pragma unroll
+                for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                    for (int mt = 0; mt < MT1; ++mt)
+                        acc[ft][mt] = mfma32(fr[ks & 1].w[ft], fr[ks & 1].a[mt], acc[ft][mt]);
+            }
+        };
+        // Tiles are processed in pairs so that the two register sets and the two LDS buffers have
+        // fixed roles; prefetches past the end re-load the last tile (harmless) so that the loop
+        // body is branch-free.
+        load(xa, wa, 0);
+        load(xb, wb, min(1, nk - 1));
+        xa.store(Xs, tid);
+        wa.store(W1s, tid);
+        __syncthreads();
+        int kt = 0;
+        for (; kt + 1 < nk; kt += 2) {
+            load(xa, wa, min(kt + 2, nk - 1));
+            tile(0, true, xb, wb);
+            __syncthreads();
+            load(xb, wb, min(kt + 3, nk - 1));
+            tile(1, true, xa, wa);
+            __syncthreads();
+        }
+        if (kt < nk) {                      // odd tile count: the last tile sits in buffer 0
+            tile(0, false, xb, wb);
             __syncthreads();
         }
         // epilogue: bias + activation, round to bf16, Hs[m][f] (f contiguous = phase-2 k)
-        const int j = lane & 31, h = lane >> 5;
 #pragma unroll
         for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int fl = (wf * FT + ft) * 32 + 8 * g + 4 * h;   // local hidden index of 4 regs
-                float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (b1) bv = *reinterpret_cast<const float4*>(b1 + f0 + fl);
+                const float4 bv = *reinterpret_cast<const float4*>(B1s + fl);
 #pragma unroll
                 for (int mt = 0; mt < MT1; ++mt) {
-                    const int ml = (wm * MT1 + mt) * 32 + j;
+                    const int ml = (wm * MT1 + mt) * 32 + i;
                     const float v0 = apply_act_rt(acc[ft][mt][4 * g + 0] + bv.x, act);
                     const float v1 = apply_act_rt(acc[ft][mt][4 * g + 1] + bv.y, act);
                     const float v2 = apply_act_rt(acc[ft][mt][4 * g + 2] + bv.z, act);
@@ -130,67 +211,66 @@ __global__ __launch_bounds__(256) void fused_ffn_kernel(
 
     // ------------------------------ phase 2 -------------------------------------------
     {
-        constexpr int W_UNITS = (BK / 8) * (BN2 / 4), W_U = (W_UNITS + 255) / 256;
-        uint2 rw[W_U][8];
-        const int NB = K2 / BN2, T = NB * KT2;
-        auto load_tile = [&](int t) {
-            const int nb = t / KT2, kt = t % KT2;
-#pragma unroll
-            for (int u = 0; u < W_U; ++u) {
-                const int c = tid + 256 * u, nq = c % (BN2 / 4), ko = c / (BN2 / 4);
-                if (c >= W_UNITS) continue;
-#pragma unroll
-                for (int kk = 0; kk < 8; ++kk)
-                    rw[u][kk] = *reinterpret_cast<const uint2*>(
-                        W2 + (long)(f0 + kt * BK + ko * 8 + kk) * K2 + nb * BN2 + nq * 4);
-            }
-        };
-        auto store_tile = [&](int buf) {
-#pragma unroll
-            for (int u = 0; u < W_U; ++u) {
-                const int c = tid + 256 * u, nq = c % (BN2 / 4), ko = c / (BN2 / 4);
-                if (c >= W_UNITS) continue;
-                uint4 t4[4];
-                transpose_8x4(rw[u], t4);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) st_u4(W2s + (buf * BN2 + nq * 4 + q) * LD + ko * 8, t4[q]);
-            }
-        };
-        const int wm = wave / WN2, wn = wave % WN2;
-        const int j = lane & 31, h = lane >> 5;
-        f32x16 acc[MT2][NT2];  // rows = rows of X, cols = output columns
+        const int wm = wave >> 2, wn = wave & 3;
+        f32x16 acc[MT2][NT2];          // rows = rows of X, cols = output columns
         zero_acc(acc);
-        load_tile(0);
-        store_tile(0);
-        __syncthreads();       // also publishes Hs
-        for (int t = 0; t < T; ++t) {
-            const int buf = t & 1, nb = t / KT2, kt = t % KT2;
-            if (t + 1 < T) load_tile(t + 1);
-            const bf16_t* as = Hs + (wm * MT2 * 32) * LDH + kt * BK;
-            const bf16_t* bs = W2s + (buf * BN2 + wn * NT2 * 32) * LD;
+        WeightStager<BN2> wa, wb;
+        const int NB = K2 / BN2, T = NB * KT2;
+        auto load = [&](WeightStager<BN2>& ws, int t) {
+            const int nb = t / KT2, kt = t % KT2;
+            ws.load(W2 + (long)f0 * K2, K2, kt * BK, nb * BN2, tid);
+        };
+        auto tile = [&](int t, int buf, bool store_next, const WeightStager<BN2>& ws) {
+            const int nb = t / KT2, kt = t % KT2;
+            const bf16_t* wsrc = W2s + buf * BN2 * LD;
+            const bf16_t* asrc = Hs + (wm * MT2 * 32) * LDH + kt * BK;
+            Frags<NT2, MT2> fr[2];
+            fr[0].fetch(wsrc, wn * NT2 * 32, asrc, LDH, 0, i, h);
 #pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks)
-                wave_mma_k16<MT2, NT2>(acc, as + ks * 16, LDH, bs + ks * 16, LD, lane);
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks < 3) fr[(ks + 1) & 1].fetch(wsrc, wn * NT2 * 32, asrc, LDH, ks + 1, i, h);
+                if (store_next && ks == 1) ws.store(W2s + (buf ^ 1) * BN2 * LD, tid);
+#pragma unroll
+                for (int nt = 0; nt < NT2; ++nt)
+#pragma unroll
+                    for (int mt = 0; mt < MT2; ++mt)
+                        acc[mt][nt] = mfma32(fr[ks & 1].a[mt], fr[ks & 1].w[nt], acc[mt][nt]);
+            }
             if (kt == KT2 - 1) {
+                // this column block is complete: lane = output column, registers = rows of X
+                // (32 lanes write 128 contiguous bytes of one row of the partial matrix)
 #pragma unroll
                 for (int nt = 0; nt < NT2; ++nt) {
-                    const int col = nb * BN2 + (wn * NT2 + nt) * 32 + j;
+                    const int col = nb * BN2 + (wn * NT2 + nt) * 32 + i;
+                    const float bv = (nsplit == 1 && b2) ? b2[col] : 0.0f;
 #pragma unroll
                     for (int mt = 0; mt < MT2; ++mt)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int row = m0 + (wm * MT2 + mt) * 32 + acc_row(r, h);
                             if (row < M) {
-                                if (nsplit == 1) Y[(long)row * K2 + col] = (bf16_t)(acc[mt][nt][r] + (b2 ? b2[col] : 0.0f));
+                                if (nsplit == 1) Y[(long)row * K2 + col] = (bf16_t)(acc[mt][nt][r] + bv);
                                 else part[((long)split * M + row) * K2 + col] = acc[mt][nt][r];
                             }
                             acc[mt][nt][r] = 0.0f;
                         }
                 }
             }
-            if (t + 1 < T) store_tile(buf ^ 1);
+        };
+        load(wa, 0);
+        load(wb, min(1, T - 1));
+        wa.store(W2s, tid);
+        __syncthreads();       // also publishes Hs
+        int t = 0;
+        for (; t + 1 < T; t += 2) {
+            load(wa, min(t + 2, T - 1));
+            tile(t, 0, true, wb);
+            __syncthreads();
+            load(wb, min(t + 3, T - 1));
+            tile(t + 1, 1, true, wa);
             __syncthreads();
         }
+        if (t < T) tile(t, 0, false, wb);
     }
 }
 
@@ -213,12 +293,12 @@ __global__ __launch_bounds__(256) void ffn_reduce_kernel(const float* __restrict
     }
 }
 
-template <int BM, int FS, int WF, int WM1, int BN2, int WM2, int WN2>
+template <int BM, int FS, int BN2>
 static hipError_t launch_ffn(const void* x, const void* w1, const float* b1, const void* w2,
                              const float* b2, void* y, int M, int K, int F, int K2, int act,
                              void* workspace, hipStream_t s) {
-    typedef FfnCfg<BM, FS, WF, WM1, BN2, WM2, WN2> Cfg;
-    auto kern = fused_ffn_kernel<Cfg, BM, FS, WF, WM1, BN2, WM2, WN2>;
+    typedef FfnCfg<BM, FS, BN2> Cfg;
+    auto kern = fused_ffn_kernel<BM, FS, BN2>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -229,7 +309,7 @@ static hipError_t launch_ffn(const void* x, const void* w1, const float* b1, con
     const int nsplit = F / FS;
     dim3 grid(nsplit, (M + BM - 1) / BM);
     prof_start(2, s);
-    hipLaunchKernelGGL(kern, grid, dim3(256), Cfg::kSmem, s, (const bf16_t*)x, (const bf16_t*)w1, b1,
+    hipLaunchKernelGGL(kern, grid, dim3(kFfnThreads), Cfg::kSmem, s, (const bf16_t*)x, (const bf16_t*)w1, b1,
                        (const bf16_t*)w2, b2, (bf16_t*)y, (float*)workspace, M, K, F, K2, act);
     prof_stop(2, s);
     hipError_t e = hipGetLastError();
@@ -242,16 +322,16 @@ static hipError_t launch_ffn(const void* x, const void* w1, const float* b1, con
     return hipGetLastError();
 }
 
-// Tile configurations (BM rows, FS hidden slice, phase-2 column block):
-//   0: 128 x 192, 128   1: 64 x 384, 256   2: 128 x 128, 128   3: 128 x 64, 64 (small shapes)
+// Tile configurations (BM rows, FS hidden slice, phase-2 column block BN2):
+//   0: 128 x 192, 128   1: 128 x 192, 256   2: 128 x 128, 128   3: 128 x 64, 128
 int fused_ffn_num_cfgs() { return 4; }
 
 static bool ffn_cfg_ok(int cfg, int F, int K2) {
     switch (cfg) {
         case 0: return F % 192 == 0 && K2 % 128 == 0;
-        case 1: return F % 384 == 0 && K2 % 256 == 0;
+        case 1: return F % 192 == 0 && K2 % 256 == 0;
         case 2: return F % 128 == 0 && K2 % 128 == 0;
-        case 3: return F % 64 == 0 && K2 % 64 == 0;
+        case 3: return F % 64 == 0 && K2 % 128 == 0;
         default: return false;
     }
 }
@@ -265,7 +345,7 @@ int fused_ffn_pick_cfg(int M, int K, int F, int K2, int tile_cfg) {
 }
 
 int fused_ffn_nsplit(int cfg, int F) {
-    static const int fs[4] = {192, 384, 128, 64};
+    static const int fs[4] = {192, 192, 128, 64};
     return (cfg >= 0 && cfg < 4) ? F / fs[cfg] : 0;
 }
 
@@ -273,10 +353,10 @@ hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void*
                      void* y, int M, int K, int F, int K2, int act, int tile_cfg, void* workspace,
                      hipStream_t s) {
     switch (fused_ffn_pick_cfg(M, K, F, K2, tile_cfg)) {
-        case 0: return launch_ffn<128, 192, 2, 2, 128, 2, 2>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
-        case 1: return launch_ffn<64, 384, 4, 1, 256, 1, 4>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
-        case 2: return launch_ffn<128, 128, 2, 2, 128, 2, 2>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
-        case 3: return launch_ffn<128, 64, 1, 4, 64, 4, 1>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+        case 0: return launch_ffn<128, 192, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+        case 1: return launch_ffn<128, 192, 256>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+        case 2: return launch_ffn<128, 128, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+        case 3: return launch_ffn<128, 64, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
         default: return hipErrorInvalidValue;
     }
 }
