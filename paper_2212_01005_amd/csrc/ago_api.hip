@@ -25,11 +25,11 @@ int g_prof_cap = 0;
 
 namespace ago {
 void prof_start(int op, hipStream_t s) {
-    if (g_prof_cap > 0) hipEventRecord(g_prof[op].start[g_prof[op].calls % g_prof_cap], s);
+    if (g_prof_cap > 0) (void)hipEventRecord(g_prof[op].start[g_prof[op].calls % g_prof_cap], s);
 }
 void prof_stop(int op, hipStream_t s) {
     if (g_prof_cap > 0) {
-        hipEventRecord(g_prof[op].stop[g_prof[op].calls % g_prof_cap], s);
+        (void)hipEventRecord(g_prof[op].stop[g_prof[op].calls % g_prof_cap], s);
         ++g_prof[op].calls;
     }
 }
@@ -39,8 +39,8 @@ extern "C" {
 
 int ago_profile_enable(int capacity) {
     for (auto& r : g_prof) {
-        for (hipEvent_t e : r.start) hipEventDestroy(e);
-        for (hipEvent_t e : r.stop) hipEventDestroy(e);
+        for (hipEvent_t e : r.start) (void)hipEventDestroy(e);
+        for (hipEvent_t e : r.stop) (void)hipEventDestroy(e);
         r.start.clear(); r.stop.clear(); r.calls = 0;
     }
     g_prof_cap = 0;

@@ -19,7 +19,7 @@ namespace ago {
 constexpr int kD = 64;      // head dimension
 constexpr int kKB = 128;    // keys per block
 
-__global__ __launch_bounds__(256) void fused_attn_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_attn_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, int S, float c /* scale * log2(e) */) {
     constexpr int LDK = kD + 8, LDV = kKB + 8;
@@ -37,24 +37,25 @@ __global__ __launch_bounds__(256) void fused_attn_kernel(
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (q_row < S) v = ld_u4(Q + (long)q_row * kD + ks * 16 + 8 * h);
+        v = ld_u4(Q + (long)min(q_row, S - 1) * kD + ks * 16 + 8 * h);
         qf[ks] = __builtin_bit_cast(bf16x8, v);
     }
 
     uint4 rk[4];
     uint2 rv[8];
+    // Keys beyond S are clamped to the last key: their scores are masked to -inf below, so their
+    // probabilities are exactly 0 and the (finite) duplicate K / V rows contribute nothing.
+    // Unpredicated loads keep the block loop free of branches.
     auto load_block = [&](int key0) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int cidx = tid + 256 * u, row = cidx >> 3, kc = cidx & 7;
-            rk[u] = (key0 + row < S) ? ld_u4(K + (long)(key0 + row) * kD + kc * 8) : make_uint4(0, 0, 0, 0);
+            rk[u] = ld_u4(K + (long)min(key0 + row, S - 1) * kD + kc * 8);
         }
         const int nq = tid & 15, ko = tid >> 4;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const int key = key0 + ko * 8 + kk;
-            rv[kk] = key < S ? *reinterpret_cast<const uint2*>(V + (long)key * kD + nq * 4) : make_uint2(0, 0);
-        }
+        for (int kk = 0; kk < 8; ++kk)
+            rv[kk] = *reinterpret_cast<const uint2*>(V + (long)min(key0 + ko * 8 + kk, S - 1) * kD + nq * 4);
     };
     auto store_block = [&](int buf) {
 #pragma unroll
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(256) void fused_attn_kernel(
     __syncthreads();
     for (int blk = 0; blk < nblk; ++blk) {
         const int buf = blk & 1;
-        if (blk + 1 < nblk) load_block((blk + 1) * kKB);
+        load_block(min(blk + 1, nblk - 1) * kKB);     // past the end: re-load the last block
 
         f32x16 s[4];
 #pragma unroll
@@ -99,18 +100,23 @@ __global__ __launch_bounds__(256) void fused_attn_kernel(
             for (int kt = 0; kt < 4; ++kt)
                 s[kt] = mfma32(ld_bf16x8(&Ks[buf][kt * 32 + j][ks * 16 + 8 * h]), qf[ks], s[kt]);
 
-        // mask keys beyond S, block max of the raw scores (c >= 0 keeps the order)
+        // mask keys beyond S (only a block that straddles S needs it; the test is wave-uniform)
+        if ((blk + 1) * kKB > S) {
+            const int key_base = blk * kKB + 4 * h;
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key_base + kt * 32 + 8 * (r >> 2) + (r & 3);
+                    s[kt][r] = key < S ? s[kt][r] : -INFINITY;
+                }
+        }
+        // block max of the raw scores (c > 0 keeps the order); pairs fold into 3-input max
         float mx = -INFINITY;
-        const int key_base = blk * kKB + 4 * h;
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = key_base + kt * 32 + 8 * (r >> 2) + (r & 3);
-                const float v = key < S ? s[kt][r] : -INFINITY;
-                s[kt][r] = v;
-                mx = fmaxf(mx, v);
-            }
+            for (int r = 0; r < 16; r += 2) mx = fmaxf(fmaxf(s[kt][r], s[kt][r + 1]), mx);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m, mx * c);
         const float alpha = __builtin_amdgcn_exp2f(m - m_new);
@@ -138,7 +144,7 @@ __global__ __launch_bounds__(256) void fused_attn_kernel(
                 for (int dt = 0; dt < 2; ++dt)
                     o[dt] = mfma32(ld_bf16x8(&Vt[buf][dt * 32 + j][kt * 32 + 16 * u + 8 * h]), pf[kt][u], o[dt]);
 
-        if (blk + 1 < nblk) store_block(buf ^ 1);
+        store_block(buf ^ 1);
         __syncthreads();
     }
 
