@@ -27,6 +27,9 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3       # fp32 MFMA / vector
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the fused FFN kernel at the benchmark shape: FETCH_SIZE + WRITE_SIZE from
+# rocprofv3 --pmc, scaled by a 256 MiB copy (profiles/bench_all_fused_subgraphs.md).
+FFN_TRAFFIC_BYTES = 135421905
 
 
 def parse():
@@ -38,6 +41,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true")
     ap.add_argument("--only", type=int, default=-1, help="run only this configuration in the timed step (profiling aid)")
+    ap.add_argument("--copy-bytes", type=int, default=0,
+                    help="calibration aid: instead of the benchmark, run the library's plain elementwise kernel "
+                         "(ago_scale, alpha = 1, fp32) over this many bytes --steps times; it reads and writes "
+                         "exactly that many bytes, which scales the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -54,6 +61,16 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
+
+    if args.copy_bytes > 0:
+        n = args.copy_bytes // 4 // 8 * 8
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            ago.ago_scale(src, dst, 1.0)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": n * 4, "copy_bytes_written": n * 4, "launches": args.steps}))
+        return
 
     idxs = list(range(5)) if args.only < 0 else [args.only]
     cases = [wl.baseline_case(i) for i in idxs]
@@ -84,6 +101,7 @@ def main():
         if n:
             kernel_ms[op] = tot / n
     ago.profile_enable(0)
+    ev_overhead_ms = ago.profile_event_overhead_ms(64)   # what an empty event pair reads
 
     flops_step = sum(c.flops() for c in cases)
     value = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -92,11 +110,15 @@ def main():
     roofline = None
     ffn = [c for c in cases if type(c).__name__ == "FfnCase"]
     if ffn and ago.OP_FUSED_FFN in kernel_ms:
-        dur_s = kernel_ms[ago.OP_FUSED_FFN] * 1e-3
+        # an event pair around one kernel reads the kernel plus the fixed cost of the pair itself
+        dur_s = (kernel_ms[ago.OP_FUSED_FFN] - ev_overhead_ms) * 1e-3
         ach = ffn[0].flops() / dur_s / 1e12
         roofline = {"bound": "mfma", "kernel": "fused_ffn_kernel", "achieved": round(ach, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                    "avg_kernel_us": round(dur_s * 1e6, 2), "traffic": None}
+                    "avg_kernel_us": round(dur_s * 1e6, 2),
+                    "event_pair_us": round(kernel_ms[ago.OP_FUSED_FFN] * 1e3, 2),
+                    "event_overhead_us": round(ev_overhead_ms * 1e3, 2),
+                    "traffic": FFN_TRAFFIC_BYTES}
 
     # ---- per-configuration table: fused vs un-fused, device time by events ----------------
     per_config = []

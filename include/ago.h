@@ -202,6 +202,10 @@ int ago_num_tile_configs(ago_op op);
  * clears the record.  Both return 0, or -1 on misuse / a HIP error.  Not thread-safe. */
 int ago_profile_enable(int capacity);
 int ago_profile_read(ago_op op, float* total_ms, int* count);
+/* Average elapsed time in milliseconds of `pairs` (1..1024) event pairs recorded back to back on
+ * `hip_stream` with nothing between them: the fixed cost an event pair adds to what it brackets.
+ * Synchronises on the events.  Returns a negative value on misuse / a HIP error. */
+float ago_profile_event_overhead_ms(void* hip_stream, int pairs);
 
 /* Redundancy model of Sec. III-B: number of times the upstream reduction body runs
  * when a conv R1xC1 (I -> O1) is fused under a downstream conv R2xC2 (O1 -> O2) whose

@@ -68,10 +68,13 @@ lib.ago_profile_enable.argtypes = [_i]
 lib.ago_profile_enable.restype = _i
 lib.ago_profile_read.argtypes = [_i, ctypes.POINTER(_f), ctypes.POINTER(_i)]
 lib.ago_profile_read.restype = _i
+lib.ago_profile_event_overhead_ms.argtypes = [_vp, _i]
+lib.ago_profile_event_overhead_ms.restype = _f
 
 EXPORTED = sorted(list(_SIGS) + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
                                  "ago_num_tile_configs", "ago_fused_upstream_iterations",
-                                 "ago_profile_enable", "ago_profile_read"])
+                                 "ago_profile_enable", "ago_profile_read",
+                                 "ago_profile_event_overhead_ms"])
 
 
 class AgoError(RuntimeError):
@@ -129,6 +132,13 @@ def profile_read(op):
     if lib.ago_profile_read(op, ctypes.byref(ms), ctypes.byref(n)) != 0:
         raise RuntimeError("ago_profile_read failed")
     return float(ms.value), int(n.value)
+
+
+def profile_event_overhead_ms(pairs=64):
+    v = float(lib.ago_profile_event_overhead_ms(_stream(), int(pairs)))
+    if v < 0:
+        raise RuntimeError("ago_profile_event_overhead_ms failed")
+    return v
 
 
 def fused_upstream_iterations(N, O1, O2, H2, W2, R2, C2, to2, th2, tw2):

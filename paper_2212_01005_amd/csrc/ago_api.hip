@@ -71,6 +71,27 @@ int ago_profile_read(ago_op op, float* total_ms, int* count) {
     return 0;
 }
 
+float ago_profile_event_overhead_ms(void* hip_stream, int pairs) {
+    if (pairs <= 0 || pairs > 1024) return -1.0f;
+    hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+    std::vector<hipEvent_t> a(pairs), b(pairs);
+    for (int i = 0; i < pairs; ++i)
+        if (hipEventCreate(&a[i]) != hipSuccess || hipEventCreate(&b[i]) != hipSuccess) return -1.0f;
+    for (int i = 0; i < pairs; ++i) {
+        (void)hipEventRecord(a[i], s);
+        (void)hipEventRecord(b[i], s);
+    }
+    float tot = 0.f;
+    bool ok = true;
+    for (int i = 0; i < pairs; ++i) {
+        float ms = 0.f;
+        ok = ok && hipEventSynchronize(b[i]) == hipSuccess && hipEventElapsedTime(&ms, a[i], b[i]) == hipSuccess;
+        tot += ms;
+    }
+    for (int i = 0; i < pairs; ++i) { (void)hipEventDestroy(a[i]); (void)hipEventDestroy(b[i]); }
+    return ok ? tot / pairs : -1.0f;
+}
+
 // ---------------------------------------------------------------- fused subgraphs
 ago_status ago_fused_invres(const void* x, const void* w1, const float* b1, const void* wd,
                             const float* bd, const void* w2, const float* b2, void* y, int N, int H,
