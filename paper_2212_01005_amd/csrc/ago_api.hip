@@ -121,7 +121,9 @@ ago_status ago_fused_ffn(const void* x, const void* w1, const float* b1, const v
     ago_status st = check_ffn(x, w1, w2, y, b1, b2, M, K, F, K2, act, dt);
     if (st != AGO_OK) return st;
     const int cfg = tile_config(AGO_OP_FUSED_FFN);
-    if (fused_ffn_pick_cfg(M, K, F, K2, cfg) < 0) return AGO_ERR_UNSUPPORTED;
+    const int picked = fused_ffn_pick_cfg(M, K, F, K2, cfg);
+    if (picked < 0) return AGO_ERR_UNSUPPORTED;
+    if ((long long)fused_ffn_nsplit(picked, F) * M * K2 >= (1LL << 31)) return AGO_ERR_UNSUPPORTED;  // 32-bit offsets
     const int dims[4] = {M, K, F, K2};
     st = check_workspace(workspace, workspace_bytes, ago::workspace_bytes(AGO_OP_FUSED_FFN, dims, 4, dt));
     if (st != AGO_OK) return st;

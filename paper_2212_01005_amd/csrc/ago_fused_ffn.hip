@@ -22,12 +22,12 @@ namespace ago {
 
 constexpr int kFfnThreads = 512;
 
-// Stage a [64 k][BN n] tile of a row-major [K][N] matrix into LDS as [n][k] (k contiguous, 72
+// Stage a [KD k][BN n] tile of a row-major [K][N] matrix into LDS as [n][k] (k contiguous, KD + 8
 // elements per row, 16-byte chunk index XOR-ed with (n >> 4) & 3): 8x4 transposition units,
 // unit u -> n-quad u % (BN/4), k-octet u / (BN/4).
-template <int BN>
+template <int BN, int KD = 64>
 struct WeightStager {
-    static constexpr int UNITS = 8 * (BN / 4);
+    static constexpr int UNITS = (KD / 8) * (BN / 4), LDW = KD + 8;
     static constexpr int U = (UNITS + kFfnThreads - 1) / kFfnThreads;
     uint2 r[U][8];
     // No bounds checks and no predication: the caller guarantees that the whole [64][BN] tile lies
@@ -43,20 +43,21 @@ struct WeightStager {
             for (int kk = 0; kk < 8; ++kk) r[u][kk] = *reinterpret_cast<const uint2*>(src + kk * ldw);
         }
     }
+    __device__ __forceinline__ void store_unit(bf16_t* dst, int tid, int u) const {
+        const int c = tid + kFfnThreads * u;
+        if (UNITS % kFfnThreads != 0 && c >= UNITS) return;
+        const int nq = c % (BN / 4), ko = c / (BN / 4);
+        uint4 t[4];
+        transpose_8x4(r[u], t);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int n = nq * 4 + q;
+            st_u4(dst + n * LDW + ((ko ^ ((n >> 4) & 3)) << 3), t[q]);
+        }
+    }
     __device__ __forceinline__ void store(bf16_t* dst, int tid) const {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int c = tid + kFfnThreads * u;
-            if (UNITS % kFfnThreads != 0 && c >= UNITS) continue;
-            const int nq = c % (BN / 4), ko = c / (BN / 4);
-            uint4 t[4];
-            transpose_8x4(r[u], t);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = nq * 4 + q;
-                st_u4(dst + n * 72 + ((ko ^ ((n >> 4) & 3)) << 3), t[q]);
-            }
-        }
+        for (int u = 0; u < U; ++u) store_unit(dst, tid, u);
     }
 };
 
@@ -84,17 +85,17 @@ struct ActStager {
     }
 };
 
-// Fragments of one k16 step of a wave tile: NW row tiles of a swizzled weight tile and NA row
-// tiles of a plain activation tile (row stride lda elements).
+// Fragments of one k16 step of a wave tile: NW row tiles of a swizzled weight tile (row stride ldw
+// elements) and NA row tiles of a plain activation tile (row stride lda elements).
 template <int NW, int NA>
 struct Frags {
     bf16x8 w[NW], a[NA];
     // ws points at the weight tile's row 0; w0 = first row of this wave (a multiple of 32)
-    __device__ __forceinline__ void fetch(const bf16_t* ws, int w0, const bf16_t* as, int lda, int ks, int i, int h) {
+    __device__ __forceinline__ void fetch(const bf16_t* ws, int ldw, int w0, const bf16_t* as, int lda, int ks, int i, int h) {
 #pragma unroll
         for (int t = 0; t < NW; ++t) {
             const int row = w0 + t * 32 + i;
-            w[t] = ld_bf16x8(ws + row * 72 + (((ks * 2 + h) ^ ((row >> 4) & 3)) << 3));
+            w[t] = ld_bf16x8(ws + row * ldw + (((ks * 2 + h) ^ ((row >> 4) & 3)) << 3));
         }
 #pragma unroll
         for (int t = 0; t < NA; ++t) a[t] = ld_bf16x8(as + (t * 32 + i) * lda + ks * 16 + 8 * h);
@@ -107,10 +108,9 @@ struct FfnCfg {
     // phase 1: 2 (hidden) x 4 (rows) waves; phase 2: 2 (rows) x 4 (cols) waves
     static constexpr int FT = FS / 2 / 32, MT1 = BM / 4 / 32;
     static constexpr int MT2 = BM / 2 / 32, NT2 = BN2 / 4 / 32;
-    static constexpr int KT2 = FS / BK;
     static constexpr size_t kStage1 = (size_t)2 * (BM + FS) * LD * 2;
     static constexpr size_t kHs = (size_t)BM * LDH * 2;
-    static constexpr size_t kStage2 = (size_t)2 * BN2 * LD * 2;
+    static constexpr size_t kStage2 = (size_t)2 * BN2 * LDH * 2;   // phase-2 tiles span the whole slice
     static constexpr size_t kMain = kStage1 > kHs + kStage2 ? kStage1 : kHs + kStage2;
     static constexpr size_t kSmem = kMain + FS * 4;      // + b1 slice
     static_assert(FS % 64 == 0 && BM % 128 == 0 && BN2 % 128 == 0, "tiling");
@@ -125,12 +125,12 @@ __global__ __launch_bounds__(kFfnThreads) void fused_ffn_kernel(
     float* __restrict__ part, int M, int K, int F, int K2, int act) {
     typedef FfnCfg<BM, FS, BN2> Cfg;
     constexpr int BK = Cfg::BK, LD = Cfg::LD, LDH = Cfg::LDH;
-    constexpr int FT = Cfg::FT, MT1 = Cfg::MT1, MT2 = Cfg::MT2, NT2 = Cfg::NT2, KT2 = Cfg::KT2;
+    constexpr int FT = Cfg::FT, MT1 = Cfg::MT1, MT2 = Cfg::MT2, NT2 = Cfg::NT2;
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* Xs = reinterpret_cast<bf16_t*>(smem);          // [2][BM][LD]   phase 1
     bf16_t* W1s = Xs + 2 * BM * LD;                        // [2][FS][LD]   phase 1
     bf16_t* Hs = reinterpret_cast<bf16_t*>(smem);          // [BM][LDH]     phase 2 (aliases phase-1 staging)
-    bf16_t* W2s = Hs + BM * LDH;                           // [2][BN2][LD]  phase 2
+    bf16_t* W2s = Hs + BM * LDH;                           // [2][BN2][LDH] phase 2
     float* B1s = reinterpret_cast<float*>(smem + Cfg::kMain);   // [FS]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -155,18 +155,23 @@ __global__ __launch_bounds__(kFfnThreads) void fused_ffn_kernel(
         auto tile = [&](int buf, bool store_next, const ActStager<BM>& xs, const WeightStager<FS>& ws) {
             const bf16_t* wsrc = W1s + buf * FS * LD;
             const bf16_t* asrc = Xs + (buf * BM + wm * MT1 * 32) * LD;
-            Frags<FT, MT1> fr[2];
-            fr[0].fetch(wsrc, wf * FT * 32, asrc, LD, 0, i, h);
+            // LDS latency under load is ~250 clocks, several MFMA groups long: fragments are fetched
+            // D1 k-steps ahead of the matrix instructions that consume them.
+            constexpr int D1 = 3;
+            Frags<FT, MT1> fr[D1];
+#pragma unroll
+            for (int d = 0; d < D1; ++d) fr[d].fetch(wsrc, LD, wf * FT * 32, asrc, LD, d, i, h);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                if (ks < 3) fr[(ks + 1) & 1].fetch(wsrc, wf * FT * 32, asrc, LD, ks + 1, i, h);
+                const Frags<FT, MT1> cur = fr[ks % D1];
+                if (ks + D1 < 4) fr[ks % D1].fetch(wsrc, LD, wf * FT * 32, asrc, LD, ks + D1, i, h);
                 if (store_next && ks == 0) xs.store(Xs + (buf ^ 1) * BM * LD, tid);
                 if (store_next && ks == 1) ws.store(W1s + (buf ^ 1) * FS * LD, tid);
 #pragma unroll
                 for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
                     for (int mt = 0; mt < MT1; ++mt)
-                        acc[ft][mt] = mfma32(fr[ks & 1].w[ft], fr[ks & 1].a[mt], acc[ft][mt]);
+                        acc[ft][mt] = mfma32(cur.w[ft], cur.a[mt], acc[ft][mt]);
             }
         };
         // Tiles are processed in pairs so that the two register sets and the two LDS buffers have
@@ -212,65 +217,70 @@ __global__ __launch_bounds__(kFfnThreads) void fused_ffn_kernel(
     // ------------------------------ phase 2 -------------------------------------------
     {
         const int wm = wave >> 2, wn = wave & 3;
+        const bool full_block = m0 + BM <= M;       // uniform: no per-lane predication of the stores
         f32x16 acc[MT2][NT2];          // rows = rows of X, cols = output columns
         zero_acc(acc);
-        WeightStager<BN2> wa, wb;
-        const int NB = K2 / BN2, T = NB * KT2;
-        auto load = [&](WeightStager<BN2>& ws, int t) {
-            const int nb = t / KT2, kt = t % KT2;
-            ws.load(W2 + (long)f0 * K2, K2, kt * BK, nb * BN2, tid);
-        };
-        auto tile = [&](int t, int buf, bool store_next, const WeightStager<BN2>& ws) {
-            const int nb = t / KT2, kt = t % KT2;
-            const bf16_t* wsrc = W2s + buf * BN2 * LD;
-            const bf16_t* asrc = Hs + (wm * MT2 * 32) * LDH + kt * BK;
-            Frags<NT2, MT2> fr[2];
-            fr[0].fetch(wsrc, wn * NT2 * 32, asrc, LDH, 0, i, h);
+        typedef WeightStager<BN2, FS> W2Stager;     // one tile = the whole hidden slice x BN2 columns
+        W2Stager wreg;                              // one register set: a tile is long enough to hide the loads
+        const int T = K2 / BN2;                     // one tile per column block
+        constexpr int KS = FS / 16;
+        auto load = [&](W2Stager& ws, int nb) { ws.load(W2 + (long)f0 * K2, K2, 0, nb * BN2, tid); };
+        auto tile = [&](int nb, int buf, bool store_next, const W2Stager& ws) {
+            const bf16_t* wsrc = W2s + buf * BN2 * LDH;
+            const bf16_t* asrc = Hs + (wm * MT2 * 32) * LDH;
+            constexpr int D2 = KS < 4 ? KS : 4;
+            Frags<NT2, MT2> fr[D2];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                if (ks < 3) fr[(ks + 1) & 1].fetch(wsrc, wn * NT2 * 32, asrc, LDH, ks + 1, i, h);
-                if (store_next && ks == 1) ws.store(W2s + (buf ^ 1) * BN2 * LD, tid);
+            for (int d = 0; d < D2; ++d) fr[d].fetch(wsrc, LDH, wn * NT2 * 32, asrc, LDH, d, i, h);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const Frags<NT2, MT2> cur = fr[ks % D2];
+                if (ks + D2 < KS) fr[ks % D2].fetch(wsrc, LDH, wn * NT2 * 32, asrc, LDH, ks + D2, i, h);
+                // the LDS stores of the next tile go late in this tile (its loads were issued at the
+                // top of the tile), one unit per k step
+#pragma unroll
+                for (int u = 0; u < W2Stager::U; ++u)
+                    if (store_next && ks == KS - 1 - (W2Stager::U - 1 - u)) ws.store_unit(W2s + (buf ^ 1) * BN2 * LDH, tid, u);
 #pragma unroll
                 for (int nt = 0; nt < NT2; ++nt)
 #pragma unroll
                     for (int mt = 0; mt < MT2; ++mt)
-                        acc[mt][nt] = mfma32(fr[ks & 1].a[mt], fr[ks & 1].w[nt], acc[mt][nt]);
+                        acc[mt][nt] = mfma32(cur.a[mt], cur.w[nt], acc[mt][nt]);
             }
-            if (kt == KT2 - 1) {
+            {
                 // this column block is complete: lane = output column, registers = rows of X
-                // (32 lanes write 128 contiguous bytes of one row of the partial matrix)
+                // (32 lanes write 128 contiguous bytes of one row of the partial matrix).
+                // 32-bit element offsets (the host checks nsplit * M * K2 < 2^31): one scalar multiply
+                // and one vector add per store instead of 64-bit address arithmetic.
 #pragma unroll
                 for (int nt = 0; nt < NT2; ++nt) {
-                    const int col = nb * BN2 + (wn * NT2 + nt) * 32 + i;
+                    const unsigned col = nb * BN2 + (wn * NT2 + nt) * 32 + i;
                     const float bv = (nsplit == 1 && b2) ? b2[col] : 0.0f;
+                    const unsigned row0 = m0 + wm * MT2 * 32 + 4 * h;
+                    const unsigned base = ((nsplit == 1 ? 0u : (unsigned)split * (unsigned)M) + row0) * (unsigned)K2 + col;
 #pragma unroll
                     for (int mt = 0; mt < MT2; ++mt)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
-                            const int row = m0 + (wm * MT2 + mt) * 32 + acc_row(r, h);
-                            if (row < M) {
-                                if (nsplit == 1) Y[(long)row * K2 + col] = (bf16_t)(acc[mt][nt][r] + bv);
-                                else part[((long)split * M + row) * K2 + col] = acc[mt][nt][r];
+                            const int dr = mt * 32 + 8 * (r >> 2) + (r & 3);      // compile-time row step
+                            if (full_block || (int)row0 + dr < M) {
+                                const unsigned idx = base + (unsigned)dr * (unsigned)K2;
+                                if (nsplit == 1) Y[idx] = (bf16_t)(acc[mt][nt][r] + bv);
+                                else part[idx] = acc[mt][nt][r];
                             }
                             acc[mt][nt][r] = 0.0f;
                         }
                 }
             }
         };
-        load(wa, 0);
-        load(wb, min(1, T - 1));
-        wa.store(W2s, tid);
+        load(wreg, 0);
+        wreg.store(W2s, tid);
         __syncthreads();       // also publishes Hs
-        int t = 0;
-        for (; t + 1 < T; t += 2) {
-            load(wa, min(t + 2, T - 1));
-            tile(t, 0, true, wb);
-            __syncthreads();
-            load(wb, min(t + 3, T - 1));
-            tile(t + 1, 1, true, wa);
+        for (int nb = 0; nb < T; ++nb) {
+            load(wreg, min(nb + 1, T - 1));          // past the end: re-load the last tile (never used)
+            tile(nb, nb & 1, true, wreg);
             __syncthreads();
         }
-        if (t < T) tile(t, 0, false, wb);
     }
 }
 
@@ -323,15 +333,14 @@ static hipError_t launch_ffn(const void* x, const void* w1, const float* b1, con
 }
 
 // Tile configurations (BM rows, FS hidden slice, phase-2 column block BN2):
-//   0: 128 x 192, 128   1: 128 x 192, 256   2: 128 x 128, 128   3: 128 x 64, 128
-int fused_ffn_num_cfgs() { return 4; }
+//   0: 128 x 192, 128   1: 128 x 128, 128   2: 128 x 64, 128
+int fused_ffn_num_cfgs() { return 3; }
 
 static bool ffn_cfg_ok(int cfg, int F, int K2) {
     switch (cfg) {
         case 0: return F % 192 == 0 && K2 % 128 == 0;
-        case 1: return F % 192 == 0 && K2 % 256 == 0;
-        case 2: return F % 128 == 0 && K2 % 128 == 0;
-        case 3: return F % 64 == 0 && K2 % 128 == 0;
+        case 1: return F % 128 == 0 && K2 % 128 == 0;
+        case 2: return F % 64 == 0 && K2 % 128 == 0;
         default: return false;
     }
 }
@@ -339,14 +348,14 @@ static bool ffn_cfg_ok(int cfg, int F, int K2) {
 int fused_ffn_pick_cfg(int M, int K, int F, int K2, int tile_cfg) {
     (void)M; (void)K;
     if (tile_cfg >= 0) return ffn_cfg_ok(tile_cfg, F, K2) ? tile_cfg : -1;
-    for (int c = 0; c < 4; ++c)
+    for (int c = 0; c < 3; ++c)
         if (ffn_cfg_ok(c, F, K2)) return c;
     return -1;
 }
 
 int fused_ffn_nsplit(int cfg, int F) {
-    static const int fs[4] = {192, 192, 128, 64};
-    return (cfg >= 0 && cfg < 4) ? F / fs[cfg] : 0;
+    static const int fs[3] = {192, 128, 64};
+    return (cfg >= 0 && cfg < 3) ? F / fs[cfg] : 0;
 }
 
 hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
@@ -354,9 +363,8 @@ hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void*
                      hipStream_t s) {
     switch (fused_ffn_pick_cfg(M, K, F, K2, tile_cfg)) {
         case 0: return launch_ffn<128, 192, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
-        case 1: return launch_ffn<128, 192, 256>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
-        case 2: return launch_ffn<128, 128, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
-        case 3: return launch_ffn<128, 64, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+        case 1: return launch_ffn<128, 128, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+        case 2: return launch_ffn<128, 64, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -125,7 +125,7 @@ def test_tile_config_hook(lib):
         assert ago.set_tile_config(op, -1) == 0
     assert ago.num_tile_configs(42) == 0 and ago.set_tile_config(42, 0) == -1
     # the FFN workspace follows the selected slice width
-    ago.set_tile_config(ago.OP_FUSED_FFN, 2)      # 128-wide slices -> 24 partials
+    ago.set_tile_config(ago.OP_FUSED_FFN, 1)      # 128-wide slices -> 24 partials
     try:
         assert ago.workspace_bytes(ago.OP_FUSED_FFN, [2048, 768, 3072, 768], ago.BF16) == 24 * 2048 * 768 * 4
     finally:
