@@ -26,14 +26,17 @@ struct InvresParams {
     int KP2;                        // Cexp padded likewise
     int CoutP;                      // Cout padded to 16
     int ldx, ldw1, lde, ldd, ldw2;  // LDS leading dimensions (elements)
-    int off_w1, off_e, off_d, off_w2, off_wd;  // LDS byte offsets (Xs at 0)
+    int off_w1, off_e, off_d, off_w2, off_wd, off_b;  // LDS byte offsets (Xs at 0)
+    int ksplit;                     // stage 3: waves per (pixel tile, channel tile) job, splitting k
 };
 
 template <bool BF16> struct InT { typedef float type; };
 template <> struct InT<true> { typedef bf16_t type; };
 
+constexpr int kInvresThreads = 1024;   // 16 waves: LDS / global latency is hidden by wave-level parallelism
+
 template <bool BF16, int STRIDE>
-__global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p) {
+__global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const InvresParams p) {
     typedef typename InT<BF16>::type T;
     extern __shared__ __align__(16) unsigned char smem[];
     T* Xs = reinterpret_cast<T*>(smem);
@@ -42,6 +45,9 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
     T* Ds = reinterpret_cast<T*>(smem + p.off_d);
     T* W2s = reinterpret_cast<T*>(smem + p.off_w2);
     float* Wds = reinterpret_cast<float*>(smem + p.off_wd);
+    float* B1s = reinterpret_cast<float*>(smem + p.off_b);     // b1[Cexp], bd[Cexp], b2[CoutP]; 0 when absent
+    float* Bds = B1s + p.Cexp;
+    float* B2s = Bds + p.Cexp;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int b = blockIdx.x;
@@ -56,7 +62,7 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
     constexpr int VE = BF16 ? 8 : 4;   // elements per 16-byte chunk
     {
         const int kch = p.KP1 / VE;
-        for (int it = tid; it < p.PEpad * kch; it += 256) {
+        for (int it = tid; it < p.PEpad * kch; it += kInvresThreads) {
             const int pix = it / kch, kc = it % kch;
             const int ey = pix / p.EW, ex = pix % p.EW;
             const int ih = ih0 + ey, iw = iw0 + ex;
@@ -66,11 +72,18 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
             st_u4(Xs + pix * p.ldx + kc * VE, v);
         }
     }
+    for (int it = tid; it < 2 * p.Cexp + p.CoutP; it += kInvresThreads) {
+        float v = 0.0f;
+        if (it < p.Cexp) { if (p.b1) v = p.b1[it]; }
+        else if (it < 2 * p.Cexp) { if (p.bd) v = p.bd[it - p.Cexp]; }
+        else if (it - 2 * p.Cexp < p.Cout) { if (p.b2) v = p.b2[it - 2 * p.Cexp]; }
+        B1s[it] = v;
+    }
     if constexpr (BF16) {
         // W1 [Cin][Cexp] -> W1s[e][k], W2 [Cexp][Cout] -> W2s[co][k]; k beyond the real extent = 0
         const bf16_t* W1 = reinterpret_cast<const bf16_t*>(p.w1);
         const int nq1 = p.Cexp / 4;
-        for (int it = tid; it < (p.KP1 / 8) * nq1; it += 256) {
+        for (int it = tid; it < (p.KP1 / 8) * nq1; it += kInvresThreads) {
             const int nq = it % nq1, ko = it / nq1;
             uint2 r[8];
 #pragma unroll
@@ -85,7 +98,7 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
         }
         const bf16_t* W2 = reinterpret_cast<const bf16_t*>(p.w2);
         const int nq2 = p.CoutP / 4;
-        for (int it = tid; it < (p.KP2 / 8) * nq2; it += 256) {
+        for (int it = tid; it < (p.KP2 / 8) * nq2; it += kInvresThreads) {
             const int nq = it % nq2, ko = it / nq2;
             uint2 r[8];
 #pragma unroll
@@ -101,26 +114,26 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
         }
         // depthwise weights as fp32 [9][Cexp]
         const uint16_t* WD = reinterpret_cast<const uint16_t*>(p.wd);
-        for (int it = tid; it < 9 * p.Cexp; it += 256) Wds[it] = bf16_to_f32(WD[it]);
+        for (int it = tid; it < 9 * p.Cexp; it += kInvresThreads) Wds[it] = bf16_to_f32(WD[it]);
     } else {
         // fp32: weights keep their [k][n] layout (the fp32 matrix instruction reads one k per lane)
         const float* W1 = reinterpret_cast<const float*>(p.w1);
         const int c4 = p.Cexp / 4;
-        for (int it = tid; it < p.KP1 * c4; it += 256) {
+        for (int it = tid; it < p.KP1 * c4; it += kInvresThreads) {
             const int k = it / c4, q = it % c4;
             const uint4 v = k < p.Cin ? ld_u4(W1 + (long)k * p.Cexp + q * 4) : make_uint4(0, 0, 0, 0);
             st_u4(W1s + k * p.ldw1 + q * 4, v);
         }
         const float* W2 = reinterpret_cast<const float*>(p.w2);
         const int o4 = p.CoutP / 4;
-        for (int it = tid; it < p.KP2 * o4; it += 256) {
+        for (int it = tid; it < p.KP2 * o4; it += kInvresThreads) {
             const int k = it / o4, q = it % o4;
             const uint4 v = (k < p.Cexp && q * 4 < p.Cout) ? ld_u4(W2 + (long)k * p.Cout + q * 4)
                                                           : make_uint4(0, 0, 0, 0);
             st_u4(W2s + k * p.ldw2 + q * 4, v);
         }
         const float* WD = reinterpret_cast<const float*>(p.wd);
-        for (int it = tid; it < 9 * p.Cexp; it += 256) Wds[it] = WD[it];
+        for (int it = tid; it < 9 * p.Cexp; it += kInvresThreads) Wds[it] = WD[it];
     }
     __syncthreads();
 
@@ -128,7 +141,7 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
     {
         const int i = lane & 15, g = lane >> 4;
         const int ptiles = p.PEpad / 16, ctiles = p.Cexp / 16;
-        for (int job = wave; job < ptiles * ctiles; job += 4) {
+        for (int job = wave; job < ptiles * ctiles; job += kInvresThreads / 64) {
             const int pt = job % ptiles, ct = job / ptiles;
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
             if constexpr (BF16) {
@@ -139,6 +152,7 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
             } else {
                 const float* ap = W1s + g * p.ldw1 + ct * 16 + i;
                 const float* bp = Xs + (pt * 16 + i) * p.ldx + g;
+#pragma unroll 8
                 for (int k0 = 0; k0 < p.KP1; k0 += 4)
                     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[k0 * p.ldw1], bp[k0], acc, 0, 0, 0);
             }
@@ -150,8 +164,7 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
                 const int e0 = ct * 16 + 4 * g;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (inside) {
-                    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (p.b1) bv = *reinterpret_cast<const float4*>(p.b1 + e0);
+                    const float4 bv = *reinterpret_cast<const float4*>(B1s + e0);
                     v.x = apply_act<kRelu6>(acc[0] + bv.x);
                     v.y = apply_act<kRelu6>(acc[1] + bv.y);
                     v.z = apply_act<kRelu6>(acc[2] + bv.z);
@@ -167,7 +180,7 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
     {
         const int Q = p.KP2 / 4;           // channel quads including the zero k-padding of D
         const int Qr = p.Cexp / 4;
-        for (int it = tid; it < p.TOH * p.TOW * Q; it += 256) {
+        for (int it = tid; it < p.TOH * p.TOW * Q; it += kInvresThreads) {
             const int q = it % Q, po = it / Q;
             float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
             if (q < Qr) {
@@ -182,8 +195,7 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
                         a.x = fmaf(e.x, w.x, a.x); a.y = fmaf(e.y, w.y, a.y);
                         a.z = fmaf(e.z, w.z, a.z); a.w = fmaf(e.w, w.w, a.w);
                     }
-                float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (p.bd) bv = *reinterpret_cast<const float4*>(p.bd + 4 * q);
+                const float4 bv = *reinterpret_cast<const float4*>(Bds + 4 * q);
                 a.x = apply_act<kRelu6>(a.x + bv.x); a.y = apply_act<kRelu6>(a.y + bv.y);
                 a.z = apply_act<kRelu6>(a.z + bv.z); a.w = apply_act<kRelu6>(a.w + bv.w);
             }
@@ -197,38 +209,66 @@ __global__ __launch_bounds__(256) void fused_invres_kernel(const InvresParams p)
     __syncthreads();
 
     // ---- stage 3: project.  acc rows = pixels, cols = output channels -------------------
+    // Few (pixel tile, channel tile) jobs and a long k: when there are fewer jobs than waves,
+    // ksplit waves share a job, each reducing over a slice of k; the partial accumulators are
+    // summed through LDS (the E region is free by now) by the wave that owns the job.
     {
         const int i = lane & 15, g = lane >> 4;
-        const int ptiles = p.POpad / 16, otiles = p.CoutP / 16;
+        const int ptiles = p.POpad / 16, otiles = p.CoutP / 16, njobs = ptiles * otiles;
+        constexpr int KG = BF16 ? 32 : 4;
+        const int ksteps = p.KP2 / KG, klen = (ksteps + p.ksplit - 1) / p.ksplit;
         T* Y = reinterpret_cast<T*>(p.y) + (long)n * p.OH * p.OW * p.Cout;
-        for (int job = wave; job < ptiles * otiles; job += 4) {
-            const int pt = job % ptiles, ot = job / ptiles;
+        float4* scratch = reinterpret_cast<float4*>(Es);
+        auto partial = [&](int pt, int ot, int ks0, int ks1) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
             if constexpr (BF16) {
                 const bf16_t* ap = Ds + (pt * 16 + i) * p.ldd + 8 * g;
                 const bf16_t* bp = W2s + (ot * 16 + i) * p.ldw2 + 8 * g;
-                for (int k0 = 0; k0 < p.KP2; k0 += 32)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ld_bf16x8(ap + k0), ld_bf16x8(bp + k0), acc, 0, 0, 0);
+#pragma unroll 4
+                for (int ks = ks0; ks < ks1; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ld_bf16x8(ap + ks * 32), ld_bf16x8(bp + ks * 32), acc, 0, 0, 0);
             } else {
                 const float* ap = Ds + (pt * 16 + i) * p.ldd + g;
                 const float* bp = W2s + g * p.ldw2 + ot * 16 + i;
-                for (int k0 = 0; k0 < p.KP2; k0 += 4)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[k0], bp[k0 * p.ldw2], acc, 0, 0, 0);
+#pragma unroll 8
+                for (int ks = ks0; ks < ks1; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[ks * 4], bp[ks * 4 * p.ldw2], acc, 0, 0, 0);
             }
+            return acc;
+        };
+        auto emit = [&](int pt, int ot, const f32x4& acc) {
             const int co = ot * 16 + i;        // this lane's output channel; registers = pixels 4g..4g+3
-            if (co < p.Cout) {
-                const float bv = p.b2 ? p.b2[co] : 0.0f;
+            if (co >= p.Cout) return;
+            const float bv = B2s[co];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int po = pt * 16 + 4 * g + r;
-                    const int oy = po / p.TOW, ox = po % p.TOW;
-                    const int oh = oh0 + oy, ow = ow0 + ox;
-                    if (po < p.TOH * p.TOW && oh < p.OH && ow < p.OW) {
-                        float v = acc[r] + bv;
-                        if (p.residual) v += (float)Xs[((oy + 1) * p.EW + ox + 1) * p.ldx + co];
-                        Y[((long)oh * p.OW + ow) * p.Cout + co] = (T)v;
-                    }
+            for (int r = 0; r < 4; ++r) {
+                const int po = pt * 16 + 4 * g + r;
+                const int oy = po / p.TOW, ox = po % p.TOW;
+                const int oh = oh0 + oy, ow = ow0 + ox;
+                if (po < p.TOH * p.TOW && oh < p.OH && ow < p.OW) {
+                    float v = acc[r] + bv;
+                    if (p.residual) v += (float)Xs[((oy + 1) * p.EW + ox + 1) * p.ldx + co];
+                    Y[((long)oh * p.OW + ow) * p.Cout + co] = (T)v;
                 }
+            }
+        };
+        if (p.ksplit == 1) {
+            for (int job = wave; job < njobs; job += kInvresThreads / 64)
+                emit(job % ptiles, job / ptiles, partial(job % ptiles, job / ptiles, 0, ksteps));
+        } else {                                   // njobs * ksplit <= number of waves
+            const int job = wave / p.ksplit, kq = wave % p.ksplit;
+            if (job < njobs) {
+                const f32x4 acc = partial(job % ptiles, job / ptiles, kq * klen, min((kq + 1) * klen, ksteps));
+                scratch[wave * 64 + lane] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            }
+            __syncthreads();
+            if (wave < njobs) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                for (int q = 0; q < p.ksplit; ++q) {
+                    const float4 v = scratch[(wave * p.ksplit + q) * 64 + lane];
+                    acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+                }
+                emit(wave % ptiles, wave / ptiles, acc);
             }
         }
     }
@@ -262,6 +302,17 @@ static size_t plan_tile(InvresParams& p, bool bf16, int stride, int toh, int tow
     off += (size_t)(bf16 ? p.CoutP : p.KP2) * p.ldw2 * es;
     p.off_wd = (int)(off = al(off));
     off += (size_t)9 * p.Cexp * 4;
+    p.off_b = (int)(off = al(off));
+    off += (size_t)(2 * p.Cexp + p.CoutP) * 4;
+    // stage-3 k split: as many waves per job as there are, limited by the k steps and by the
+    // scratch (1 KB per wave) that fits in the E region
+    const int nwaves = kInvresThreads / 64, njobs = (p.POpad / 16) * (p.CoutP / 16);
+    const int ksteps = p.KP2 / kg;
+    int ks = njobs < nwaves ? nwaves / njobs : 1;
+    if (ks > ksteps) ks = ksteps;
+    const size_t e_bytes = (size_t)p.PE * p.lde * 4;
+    while (ks > 1 && (size_t)njobs * ks * 1024 > e_bytes) --ks;
+    p.ksplit = ks < 1 ? 1 : ks;
     return al(off);
 }
 
@@ -307,7 +358,7 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
             attr_set = true;                                                                            \
         }                                                                                               \
         prof_start(0, s);                                                                               \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, p);                                    \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kInvresThreads), smem, s, p);                                    \
         prof_stop(0, s);                                                                                \
     } while (0)
     if (bf16) { if (stride == 1) AGO_LAUNCH_INVRES(true, 1); else AGO_LAUNCH_INVRES(true, 2); }
