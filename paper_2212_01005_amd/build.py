@@ -25,6 +25,7 @@ SOURCES = [
     "ago_fused_invres.hip",
     "ago_fused_conv_chain.hip",
     "ago_fused_ffn.hip",
+    "ago_fused_ffn_stream.hip",
     "ago_fused_attn.hip",
 ]
 

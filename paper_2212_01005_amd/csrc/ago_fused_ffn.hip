@@ -303,6 +303,13 @@ __global__ __launch_bounds__(256) void ffn_reduce_kernel(const float* __restrict
     }
 }
 
+hipError_t ffn_reduce(const float* part, const float* b2, void* y, long MK2, int K2, int nsplit, hipStream_t s) {
+    long g = (MK2 / 4 + 255) / 256;
+    if (g > 2048) g = 2048;
+    hipLaunchKernelGGL(ffn_reduce_kernel, dim3((unsigned)g), dim3(256), 0, s, part, b2, (bf16_t*)y, MK2, K2, nsplit);
+    return hipGetLastError();
+}
+
 template <int BM, int FS, int BN2>
 static hipError_t launch_ffn(const void* x, const void* w1, const float* b1, const void* w2,
                              const float* b2, void* y, int M, int K, int F, int K2, int act,
@@ -324,38 +331,37 @@ static hipError_t launch_ffn(const void* x, const void* w1, const float* b1, con
     prof_stop(2, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nsplit == 1) return e;
-    const long MK2 = (long)M * K2;
-    long g = (MK2 / 4 + 255) / 256;
-    if (g > 2048) g = 2048;
-    hipLaunchKernelGGL(ffn_reduce_kernel, dim3((unsigned)g), dim3(256), 0, s, (const float*)workspace, b2,
-                       (bf16_t*)y, MK2, K2, nsplit);
-    return hipGetLastError();
+    return ffn_reduce((const float*)workspace, b2, y, (long)M * K2, K2, nsplit, s);
 }
 
 // Tile configurations (BM rows, FS hidden slice, phase-2 column block BN2):
 //   0: 128 x 192, 128   1: 128 x 128, 128   2: 128 x 64, 128
-int fused_ffn_num_cfgs() { return 3; }
+//   3: the wave-specialised streaming kernel (64 x 384, 384); the built-in choice whenever the
+//      shape allows it (K % 64 == 0, F % 384 == 0, K2 % 384 == 0)
+int fused_ffn_num_cfgs() { return 4; }
 
-static bool ffn_cfg_ok(int cfg, int F, int K2) {
+static bool ffn_cfg_ok(int cfg, int K, int F, int K2) {
     switch (cfg) {
         case 0: return F % 192 == 0 && K2 % 128 == 0;
         case 1: return F % 128 == 0 && K2 % 128 == 0;
         case 2: return F % 64 == 0 && K2 % 128 == 0;
+        case 3: return fused_ffn_stream_ok(0, K, F, K2);
         default: return false;
     }
 }
 
 int fused_ffn_pick_cfg(int M, int K, int F, int K2, int tile_cfg) {
-    (void)M; (void)K;
-    if (tile_cfg >= 0) return ffn_cfg_ok(tile_cfg, F, K2) ? tile_cfg : -1;
+    (void)M;
+    if (tile_cfg >= 0) return ffn_cfg_ok(tile_cfg, K, F, K2) ? tile_cfg : -1;
+    if (ffn_cfg_ok(3, K, F, K2)) return 3;
     for (int c = 0; c < 3; ++c)
-        if (ffn_cfg_ok(c, F, K2)) return c;
+        if (ffn_cfg_ok(c, K, F, K2)) return c;
     return -1;
 }
 
 int fused_ffn_nsplit(int cfg, int F) {
-    static const int fs[3] = {192, 128, 64};
-    return (cfg >= 0 && cfg < 3) ? F / fs[cfg] : 0;
+    static const int fs[4] = {192, 128, 64, 384};
+    return (cfg >= 0 && cfg < 4) ? F / fs[cfg] : 0;
 }
 
 hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
@@ -365,6 +371,7 @@ hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void*
         case 0: return launch_ffn<128, 192, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
         case 1: return launch_ffn<128, 128, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
         case 2: return launch_ffn<128, 64, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+        case 3: return fused_ffn_stream(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
         default: return hipErrorInvalidValue;
     }
 }

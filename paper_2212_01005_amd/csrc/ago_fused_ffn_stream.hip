@@ -1,0 +1,399 @@
+// Fused matmul -> activation -> matmul, wave-specialised streaming variant (pw->pw, the
+// "downstream pointwise" rule of AGO Sec. III-B / Fig. 7b: the downstream tile keeps all of its
+// output channels, the upstream tile is a slice of the hidden dimension).
+//
+// Workgroup (split s, row block rb) owns 64 rows of X and 384 hidden units.  Twelve waves:
+//   waves 0..7   consumers: LDS -> MFMA only (plus the two epilogues)
+//   waves 8..11  producers: global -> LDS only, with the direct-to-LDS load (no registers, no LDS
+//                store instructions); weights land in their natural [k][n] layout and the consumers
+//                read them with the transposing LDS read, so nothing is transposed by hand.
+//                Three of them stream weight tiles, the fourth streams X far ahead (see below)
+// The two kinds of wave meet at one workgroup barrier per 32-deep k-tile.  Tiles travel through a
+// ring of four LDS stages: during iteration t the producers issue tile t+3 and wait until tile
+// t+2 has landed, the consumers multiply tile t and already fetch the fragments of tile t+1, so
+// neither the global latency nor the LDS latency is exposed at a barrier.
+//   phase 1  Hs[64][384] = act(X[rb] W1[:, slice] + b1[slice])      K/32 tiles of X and W1
+//   phase 2  P[s][rb]    = Hs W2[slice, :]                          12 tiles of W2 per 384 columns
+// The F/384 partial products are summed by ffn_reduce (which adds b2 and rounds); with a single
+// slice phase 2 writes y directly.
+//
+// LDS layouts (16-byte chunks; the producers realise the permutation by choosing which global
+// chunk each lane fetches, because the direct load writes lane i's 16 bytes at base + 16 i):
+//   X block  [64 m][64 k] (two tiles): 128-byte rows, chunk ^= (m >> 1) & 7
+//   W tile   [32 k][384 n]: 768-byte rows, 32-byte chunk pair ^= ((k & 3) << 1) | ((k >> 3) & 1)
+//   Hs       [64 m][384 f] bf16, 392 elements per row
+// All three give conflict-free fragment reads.
+#include "ago_dev.hpp"
+#include "ago_launch.hpp"
+#include <type_traits>
+
+namespace ago {
+namespace {
+
+constexpr int kConsumerWaves = 8, kProducerWaves = 4;
+constexpr int kStreamThreads = (kConsumerWaves + kProducerWaves) * 64;
+constexpr int BM = 64, FS = 384, BK = 32, CB = 384, NST = 4;
+constexpr int kRowB = 384 * 2;                 // bytes per k-row of a weight tile
+constexpr int kXBlockB = BM * 64 * 2;          // X travels in 64-deep blocks (whole 128-byte lines): 8192
+constexpr int kXSlots = 7;
+constexpr int kWTileB = BK * kRowB;            // 24576
+constexpr int kHsLd = FS + 8;
+constexpr int kHsB = BM * kHsLd * 2;           // 50176
+// Hs is only written after the last phase-1 tile has been consumed, so the phase-1 buffers may
+// overlap it; the phase-2 ring starts right behind Hs.
+constexpr int kXRing = 4096;
+constexpr int kRing1 = kXRing + kXSlots * kXBlockB;   // 61440
+constexpr int kRing2 = kHsB;
+constexpr int kB1 = kRing1 + NST * kWTileB;    // 159744
+constexpr int kStreamSmem = kB1 + FS * 4;      // 161280
+static_assert(kRing2 + NST * kWTileB <= kB1, "phase-2 ring must not reach the bias slice");
+static_assert(kStreamSmem <= 160 * 1024, "LDS");
+constexpr int kWWaves = kProducerWaves - 1;                   // three waves load weights, one loads X
+constexpr int kWLoadsPerWave = kWTileB / 1024 / kWWaves;      // 8 direct loads of 1 KB per wave and tile
+constexpr int kXLead = 4;                                     // X blocks in flight ahead of the weight tiles
+
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+typedef __attribute__((address_space(1))) const void gptr_t;
+typedef __attribute__((address_space(3))) void lptr_t;
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+
+// wait until at most n of this wave's vector-memory operations are outstanding (n < 64)
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// 16 bytes per lane from global memory straight into LDS at base + 16 * lane (base wave-uniform)
+__device__ __forceinline__ void load_to_lds(const bf16_t* src, lds_byte* base) {
+    __builtin_amdgcn_global_load_lds((gptr_t*)src, (lptr_t*)base, 16, 0, 0);
+}
+
+// fragment of a weight tile for the 32 columns starting at the column pair the lane offset encodes:
+// two transposing reads (k rows 0..3 and 4..7 of the lane's k-group)
+__device__ __forceinline__ bf16x8 read_w_frag(const lds_byte* p) {
+    typedef __attribute__((address_space(3))) bf16x4_t lds_bf16x4;
+    const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p));
+    const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 4 * kRowB));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+__device__ __forceinline__ bf16x8 read_a_frag(const lds_byte* p) {
+    typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+    return *(const lds_bf16x8*)p;
+}
+
+struct Frag {
+    bf16x8 a, w[3];
+};
+
+__global__ __launch_bounds__(kStreamThreads) void fused_ffn_stream_kernel(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W1, const float* __restrict__ b1,
+    const bf16_t* __restrict__ W2, const float* __restrict__ b2, bf16_t* __restrict__ Y,
+    float* __restrict__ part, int M, int K, int F, int K2, int act) {
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    lds_byte* smem = (lds_byte*)smem_generic;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int split = blockIdx.x, nsplit = gridDim.x;
+    const int m0 = blockIdx.y * BM, f0 = split * FS;
+    const int NT1 = K / BK;                 // phase-1 tiles
+    const int NCB = K2 / CB;                // phase-2 column blocks
+    const int NT2 = NCB * (FS / BK);        // phase-2 tiles
+    // The workgroups of one hidden slice run in lockstep on one XCD and would all ask its L2 for the
+    // same lines at the same moment (and W1's row stride maps a tile onto few L2 channels): each row
+    // block walks the reduction dimension from a different starting tile instead.
+    const int rot1 = 2 * (blockIdx.y % (NT1 / 2)), rot2 = blockIdx.y % (FS / BK);
+
+    if (wave >= kConsumerWaves) {
+        // ================================ producers ======================================
+        const int pw = wave - kConsumerWaves;
+        if (pw == kWWaves) {
+            // ---- the X wave.  Every row block reads its own rows of X, so these loads miss the L2
+            // that serves the (shared) weight tiles and take much longer; loads complete in order
+            // within a wave, hence a wave of their own, running kXLead blocks (2 kXLead tiles) ahead.
+            unsigned xoff[8];                 // load q: rows 8 q .. 8 q + 7 x 128 bytes; lane = (row, physical chunk)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int xrow = 8 * q + (lane >> 3);
+                const int xchunk = (lane & 7) ^ ((xrow >> 1) & 7);
+                xoff[q] = (unsigned)min(m0 + xrow, M - 1) * (unsigned)K + 8 * xchunk;
+            }
+            const int NB = NT1 / 2;
+            auto issue_x = [&](int blk) {
+                lds_byte* xs = smem + kXRing + (blk % kXSlots) * kXBlockB;
+                const int kt = 2 * blk + rot1 < NT1 ? 2 * blk + rot1 : 2 * blk + rot1 - NT1;   // rot1 is even
+#pragma unroll
+                for (int q = 0; q < 8; ++q) load_to_lds(X + xoff[q] + kt * BK, xs + q * 1024);
+            };
+            auto wait_blocks = [&](int n) {      // at most n blocks (8 loads each) outstanding
+                if (n >= 5) wait_vm<40>();
+                else if (n == 4) wait_vm<32>();
+                else if (n == 3) wait_vm<24>();
+                else if (n == 2) wait_vm<16>();
+                else if (n == 1) wait_vm<8>();
+                else wait_vm<0>();
+            };
+            for (int blk = 0; blk < min(kXLead, NB); ++blk) issue_x(blk);
+            wait_blocks(min(kXLead, NB) - 1);            // block 0 has landed
+            __builtin_amdgcn_s_barrier();
+            for (int t = 0; t < NT1; ++t) {
+                const int blk = (t >> 1) + kXLead;
+                if ((t & 1) == 0 && blk < NB) issue_x(blk);
+                // the consumers fetch from tile t + 2 during the next iteration
+                wait_blocks(min(blk, NB - 1) - min((t + 2) >> 1, NB - 1));
+                __builtin_amdgcn_s_barrier();
+            }
+            for (int t = 0; t < NT2 + 1; ++t) __builtin_amdgcn_s_barrier();    // phase 2: nothing to load
+            return;
+        }
+        // W tile: load j of this wave covers LDS chunks 64 (8 pw + j) .. + 63
+        int wk[kWLoadsPerWave], wc[kWLoadsPerWave];
+#pragma unroll
+        for (int j = 0; j < kWLoadsPerWave; ++j) {
+            const int ci = 64 * (kWLoadsPerWave * pw + j) + lane;
+            const int k = ci / 48, pc = ci % 48;
+            const int sw = ((k & 3) << 1) | ((k >> 3) & 1);
+            wk[j] = k;
+            wc[j] = ((((pc >> 1) ^ sw) << 1) | (pc & 1)) * 8;     // first element of the global chunk
+        }
+        // ---- phase 1 ----
+        {
+            unsigned woff[kWLoadsPerWave];
+#pragma unroll
+            for (int j = 0; j < kWLoadsPerWave; ++j) woff[j] = (unsigned)wk[j] * (unsigned)F + wc[j];
+            const bf16_t* wsrc = W1 + f0;
+            auto issue = [&](int t) {
+                lds_byte* st = smem + kRing1 + (t & (NST - 1)) * kWTileB;
+                const int kt = t + rot1 < NT1 ? t + rot1 : t + rot1 - NT1;
+                const bf16_t* w = wsrc + (long)kt * BK * F;
+#pragma unroll
+                for (int j = 0; j < kWLoadsPerWave; ++j)
+                    load_to_lds(w + woff[j], st + (kWLoadsPerWave * pw + j) * 1024);
+            };
+            constexpr int PER = kWLoadsPerWave;
+            issue(0);                        // NT1 is even and at least 2
+            issue(1);
+            issue(min(2, NT1 - 1));          // a surplus issue repeats the last tile into its own stage
+            wait_vm<PER>();                  // tiles 0 and 1 have landed
+            __builtin_amdgcn_s_barrier();
+            for (int t = 0; t < NT1; ++t) {
+                if (t + 3 < NT1) {
+                    issue(t + 3);
+                    wait_vm<PER>();          // everything up to tile t+2 has landed
+                } else {
+                    wait_vm<0>();
+                }
+                __builtin_amdgcn_s_barrier();
+            }
+        }
+        // ---- phase 2 (the ring restarts behind Hs; all phase-1 stages are dead by now) ----
+        {
+            unsigned woff[kWLoadsPerWave];
+#pragma unroll
+            for (int j = 0; j < kWLoadsPerWave; ++j) woff[j] = (unsigned)wk[j] * (unsigned)K2 + wc[j];
+            const bf16_t* wsrc = W2 + (long)f0 * K2;
+            auto issue = [&](int t) {
+                const int cb = t / (FS / BK), kt = (t + rot2) % (FS / BK);
+                lds_byte* st = smem + kRing2 + (t & (NST - 1)) * kWTileB;
+                const bf16_t* w = wsrc + (long)kt * BK * K2 + cb * CB;
+#pragma unroll
+                for (int j = 0; j < kWLoadsPerWave; ++j)
+                    load_to_lds(w + woff[j], st + (kWLoadsPerWave * pw + j) * 1024);
+            };
+            constexpr int PER = kWLoadsPerWave;
+            issue(0);
+            issue(1);
+            issue(2);                        // NT2 >= 12
+            wait_vm<PER>();
+            __builtin_amdgcn_s_barrier();    // matches the consumers' barrier after the Hs epilogue
+            for (int t = 0; t < NT2; ++t) {
+                if (t + 3 < NT2) {
+                    issue(t + 3);
+                    wait_vm<PER>();
+                } else {
+                    wait_vm<0>();
+                }
+                __builtin_amdgcn_s_barrier();
+            }
+        }
+        return;
+    }
+
+    // ================================== consumers ========================================
+    const int i = lane & 31, h = lane >> 5;
+    const int g = lane >> 4, s = lane & 15;
+    const int wm = wave & 1, wq = wave >> 1;       // row tile; group of three 32-wide hidden / column tiles
+    float* B1s = reinterpret_cast<float*>(smem_generic + kB1);
+    for (int t = tid; t < FS; t += kConsumerWaves * 64) B1s[t] = b1 ? b1[f0 + t] : 0.0f;
+
+    // lane offsets inside a weight tile for the three column tiles of this wave (k step 0, rows 0..3)
+    const int sw = ((s >> 2) << 1) | (g >> 1);
+    int woff[3];
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+        woff[t] = (8 * (g >> 1) + (s >> 2)) * kRowB + (((6 * wq + 2 * t + (g & 1)) ^ sw) << 5) + 8 * (s & 3);
+
+    // ------------------------------ phase 1 -------------------------------------------
+    {
+        const int xrow = 32 * wm + i;
+        // byte offset of this lane's chunk in an X block for k step 0 / 1 of the block's first tile;
+        // the second tile's chunks are 4 further on, which after the XOR swizzle is bit 6 flipped
+        const int xoff0 = xrow * 128 + ((h ^ ((xrow >> 1) & 7)) << 4);
+        const int xoff1 = xrow * 128 + (((2 + h) ^ ((xrow >> 1) & 7)) << 4);
+        f32x16 acc[3];
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+        auto fetch = [&](Frag& fr, int tile, int ks) {      // past the last tile: stale data, never used
+            const lds_byte* st = smem + kRing1 + (tile & (NST - 1)) * kWTileB;
+            const lds_byte* xs = smem + kXRing + ((tile >> 1) % kXSlots) * kXBlockB;
+            fr.a = read_a_frag(xs + ((ks ? xoff1 : xoff0) ^ ((tile & 1) << 6)));
+#pragma unroll
+            for (int t = 0; t < 3; ++t) fr.w[t] = read_w_frag(st + woff[t] + ks * 16 * kRowB);
+        };
+        Frag f0r, f1r;
+        __builtin_amdgcn_s_barrier();              // tiles 0 and 1 are in LDS
+        fetch(f0r, 0, 0);
+        fetch(f1r, 0, 1);
+        for (int t = 0; t < NT1; ++t) {
+            const int nx = t + 1;
+            // each fragment set is re-filled (for the next tile) right after the matrix instructions
+            // that read it have been issued: no copies, and the reads have most of a tile to land
+#pragma unroll
+            for (int u = 0; u < 3; ++u) acc[u] = mfma32(f0r.w[u], f0r.a, acc[u]);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(f0r, nx, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < 3; ++u) acc[u] = mfma32(f1r.w[u], f1r.a, acc[u]);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(f1r, nx, 1);
+            __builtin_amdgcn_s_barrier();
+        }
+        // epilogue: bias + activation, round to bf16, Hs[m][f] (f contiguous = phase-2 k).
+        // acc rows = hidden units, columns = rows of X.
+        bf16_t* Hs = reinterpret_cast<bf16_t*>(smem_generic);
+        const int ml = 32 * wm + i;
+        auto epilogue = [&](auto act_tag) {
+            constexpr int ACT = decltype(act_tag)::value;
+#pragma unroll
+            for (int t = 0; t < 3; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int fl = 96 * wq + 32 * t + 8 * q + 4 * h;
+                    const float4 bv = *reinterpret_cast<const float4*>(B1s + fl);
+                    const float v0 = apply_act<ACT>(acc[t][4 * q + 0] + bv.x);
+                    const float v1 = apply_act<ACT>(acc[t][4 * q + 1] + bv.y);
+                    const float v2 = apply_act<ACT>(acc[t][4 * q + 2] + bv.z);
+                    const float v3 = apply_act<ACT>(acc[t][4 * q + 3] + bv.w);
+                    *reinterpret_cast<uint2*>(Hs + ml * kHsLd + fl) = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
+                }
+        };
+        switch (act) {          // uniform
+            case kGeluTanh: epilogue(std::integral_constant<int, kGeluTanh>()); break;
+            case kRelu: epilogue(std::integral_constant<int, kRelu>()); break;
+            case kRelu6: epilogue(std::integral_constant<int, kRelu6>()); break;
+            default: epilogue(std::integral_constant<int, kNone>()); break;
+        }
+    }
+    __syncthreads();       // Hs complete (workgroup barrier: the producers arrive with W2 tiles 0 and 1 landed)
+
+    // ------------------------------ phase 2 -------------------------------------------
+    {
+        const bool full_block = m0 + BM <= M;
+        const lds_byte* hs = smem + (32 * wm + i) * (kHsLd * 2) + 16 * h;
+        f32x16 acc[3];             // rows = rows of X, columns = output columns
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+        constexpr int KT = FS / BK;      // 12 tiles per column block
+        auto fetch = [&](Frag& fr, int tile, int ks) {
+            const lds_byte* st = smem + kRing2 + (tile & (NST - 1)) * kWTileB;
+            fr.a = read_a_frag(hs + (((tile + rot2) % KT) * BK + ks * 16) * 2);
+#pragma unroll
+            for (int t = 0; t < 3; ++t) fr.w[t] = read_w_frag(st + woff[t] + ks * 16 * kRowB);
+        };
+        Frag f0r, f1r;
+        fetch(f0r, 0, 0);
+        fetch(f1r, 0, 1);
+        for (int cb = 0; cb < NCB; ++cb) {
+            for (int kt = 0; kt < KT; ++kt) {
+                const int tile = cb * KT + kt;
+#pragma unroll
+                for (int u = 0; u < 3; ++u) acc[u] = mfma32(f0r.a, f0r.w[u], acc[u]);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(f0r, tile + 1, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < 3; ++u) acc[u] = mfma32(f1r.a, f1r.w[u], acc[u]);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(f1r, tile + 1, 1);
+                __builtin_amdgcn_s_barrier();
+            }
+            // this column block is complete: lane = output column, registers = rows of X
+            // (32 lanes write 128 contiguous bytes of one row); 32-bit element offsets
+            const unsigned row0 = m0 + 32 * wm + 4 * h;
+            if (nsplit != 1 && full_block) {          // uniform: the common case, plain stores
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    const unsigned col = cb * CB + 96 * wq + 32 * t + i;
+                    const unsigned base = ((unsigned)split * (unsigned)M + row0) * (unsigned)K2 + col;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        part[base + (unsigned)(8 * (r >> 2) + (r & 3)) * (unsigned)K2] = acc[t][r];
+                        acc[t][r] = 0.0f;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    const unsigned col = cb * CB + 96 * wq + 32 * t + i;
+                    const float bv = (nsplit == 1 && b2) ? b2[col] : 0.0f;
+                    const unsigned base = ((nsplit == 1 ? 0u : (unsigned)split * (unsigned)M) + row0) * (unsigned)K2 + col;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int dr = 8 * (r >> 2) + (r & 3);
+                        if ((int)row0 + dr < M) {
+                            const unsigned idx = base + (unsigned)dr * (unsigned)K2;
+                            if (nsplit == 1) Y[idx] = (bf16_t)(acc[t][r] + bv);
+                            else part[idx] = acc[t][r];
+                        }
+                        acc[t][r] = 0.0f;
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+bool fused_ffn_stream_ok(int M, int K, int F, int K2) {
+    (void)M;
+    return K % 64 == 0 && F % FS == 0 && K2 % CB == 0 && K >= 64;
+}
+
+hipError_t fused_ffn_stream(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
+                            void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s) {
+    if (!fused_ffn_stream_ok(M, K, F, K2)) return hipErrorInvalidValue;
+    auto kern = fused_ffn_stream_kernel;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kStreamSmem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int nsplit = F / FS;
+    dim3 grid(nsplit, (M + BM - 1) / BM);
+    prof_start(2, s);
+    hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), kStreamSmem, s, (const bf16_t*)x, (const bf16_t*)w1, b1,
+                       (const bf16_t*)w2, b2, (bf16_t*)y, (float*)workspace, M, K, F, K2, act);
+    prof_stop(2, s);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || nsplit == 1) return e;
+    return ffn_reduce((const float*)workspace, b2, y, (long)M * K2, K2, nsplit, s);
+}
+
+}  // namespace ago

@@ -103,8 +103,8 @@ def test_status_strings(lib):
 
 def test_workspace_sizes(lib):
     from paper_2212_01005_amd import binding as ago
-    # FFN 2048x768x3072x768 with the built-in 192-wide hidden slices: 16 fp32 partial matrices
-    assert ago.workspace_bytes(ago.OP_FUSED_FFN, [2048, 768, 3072, 768], ago.BF16) == 16 * 2048 * 768 * 4
+    # FFN 2048x768x3072x768 with the built-in 384-wide hidden slices: 8 fp32 partial matrices
+    assert ago.workspace_bytes(ago.OP_FUSED_FFN, [2048, 768, 3072, 768], ago.BF16) == 8 * 2048 * 768 * 4
     assert ago.workspace_bytes(ago.OP_FUSED_FFN, [64, 64, 64, 64], ago.BF16) == 0       # single slice
     assert ago.workspace_bytes(ago.OP_FUSED_ATTN, [8, 12, 384, 64], ago.BF16) == 0
     assert ago.workspace_bytes(ago.OP_UNFUSED_FFN, [2048, 768, 3072, 768], ago.BF16) == 2048 * 3072 * 2

@@ -187,6 +187,8 @@ def small_cases():
         ChainCase(2, 14, 14, 64, False, "bf16", s + 96, name="chain_nores"),
         FfnCase(200, 768, 3072, 768, "bf16", s + 112, name="ffn_ragged_rows"),
         FfnCase(96, 256, 512, 128, "bf16", s + 128, name="ffn_small"),
+        FfnCase(70, 192, 384, 384, "bf16", s + 176, name="ffn_single_slice_ragged"),
+        FfnCase(130, 64, 768, 768, "bf16", s + 192, name="ffn_two_k_tiles"),
         AttnCase(1, 2, 384, 64, 0.125, "bf16", s + 144, name="attn_s384"),
         AttnCase(2, 3, 100, 64, 0.125, "bf16", s + 160, name="attn_ragged_s100"),
     ]
