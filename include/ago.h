@@ -199,8 +199,12 @@ int ago_num_tile_configs(ago_op op);
  * calls per entry point are kept; capacity <= 0 switches it off and frees the events; at most
  * 4096).  ago_profile_read waits for the recorded calls of `op` (one of the four AGO_OP_FUSED_*),
  * writes their summed kernel time in milliseconds and their number to the host pointers, and
- * clears the record.  Both return 0, or -1 on misuse / a HIP error.  Not thread-safe. */
+ * clears the record.  ago_profile_select restricts the recording to the entry points whose bit
+ * (1u << AGO_OP_FUSED_*) is set in op_mask (default: all four); an event pair costs a few
+ * microseconds on the stream, so a benchmark brackets only the kernel it reports.  All three
+ * return 0, or -1 on misuse / a HIP error.  Not thread-safe. */
 int ago_profile_enable(int capacity);
+int ago_profile_select(unsigned op_mask);
 int ago_profile_read(ago_op op, float* total_ms, int* count);
 /* Average elapsed time in milliseconds of `pairs` (1..1024) event pairs recorded back to back on
  * `hip_stream` with nothing between them: the fixed cost an event pair adds to what it brackets.

@@ -66,6 +66,8 @@ lib.ago_fused_upstream_iterations.restype = ctypes.c_longlong
 
 lib.ago_profile_enable.argtypes = [_i]
 lib.ago_profile_enable.restype = _i
+lib.ago_profile_select.argtypes = [ctypes.c_uint]
+lib.ago_profile_select.restype = _i
 lib.ago_profile_read.argtypes = [_i, ctypes.POINTER(_f), ctypes.POINTER(_i)]
 lib.ago_profile_read.restype = _i
 lib.ago_profile_event_overhead_ms.argtypes = [_vp, _i]
@@ -73,7 +75,7 @@ lib.ago_profile_event_overhead_ms.restype = _f
 
 EXPORTED = sorted(list(_SIGS) + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
                                  "ago_num_tile_configs", "ago_fused_upstream_iterations",
-                                 "ago_profile_enable", "ago_profile_read",
+                                 "ago_profile_enable", "ago_profile_select", "ago_profile_read",
                                  "ago_profile_event_overhead_ms"])
 
 
@@ -126,6 +128,11 @@ def profile_enable(capacity):
         raise RuntimeError("ago_profile_enable failed")
 
 
+def profile_select(op_mask):
+    if lib.ago_profile_select(int(op_mask)) != 0:
+        raise RuntimeError("ago_profile_select failed")
+
+
 def profile_read(op):
     """(total kernel milliseconds, number of calls) recorded for a fused entry point."""
     ms, n = _f(0.0), _i(0)
@@ -147,118 +154,161 @@ def fused_upstream_iterations(N, O1, O2, H2, W2, R2, C2, to2, th2, tw2):
     return int(v), int(unf.value)
 
 
+def _entry(marshal):
+    """Turn a marshalling function (tensors -> C function + argument tuple) into the entry point
+    wrapper; the marshalling step stays reachable for prepare()."""
+    def call(*a, **kw):
+        fn, args = marshal(*a, **kw)
+        _chk(fn(*args))
+    call.marshal = marshal
+    call.__name__ = marshal.__name__
+    call.__doc__ = marshal.__doc__
+    return call
+
+
+def prepare(entry, *a, **kw):
+    """Marshal the arguments of an entry point once and return a zero-argument callable that
+    launches it again with the same device pointers, sizes and stream (a serving loop calls the
+    same subgraph on the same buffers many times; only the C call remains per launch)."""
+    fn, args = entry.marshal(*a, **kw)
+
+    def run():
+        st = fn(*args)
+        if st:
+            raise AgoError(st)
+    return run
+
+
 # ---- fused subgraphs ---------------------------------------------------------------
 
+@_entry
 def ago_fused_invres(x, w1, b1, wd, bd, w2, b2, y, stride, residual, workspace=None):
     N, H, W, Cin = x.shape
     Cexp, Cout = w2.shape
     wp, wb = _ws(workspace)
-    _chk(lib.ago_fused_invres(_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
-                              N, H, W, Cin, Cexp, Cout, stride, int(residual), _dt(x), wp, wb, _stream()))
+    return lib.ago_fused_invres, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
+                              N, H, W, Cin, Cexp, Cout, stride, int(residual), _dt(x), wp, wb, _stream())
 
 
+@_entry
 def ago_fused_conv_chain(x, wa, ba, wb_, bb, y, residual, workspace=None):
     N, H, W, C = x.shape
     wp, wb = _ws(workspace)
-    _chk(lib.ago_fused_conv_chain(_p(x), _p(wa), _p(ba), _p(wb_), _p(bb), _p(y),
-                                  N, H, W, C, int(residual), _dt(x), wp, wb, _stream()))
+    return lib.ago_fused_conv_chain, (_p(x), _p(wa), _p(ba), _p(wb_), _p(bb), _p(y),
+                                  N, H, W, C, int(residual), _dt(x), wp, wb, _stream())
 
 
+@_entry
 def ago_fused_ffn(x, w1, b1, w2, b2, y, act=ACT_GELU_TANH, workspace=None):
     M, K = x.shape
     F, K2 = w2.shape
     wp, wb = _ws(workspace)
-    _chk(lib.ago_fused_ffn(_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
-                           wp, wb, _stream()))
+    return lib.ago_fused_ffn, (_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
+                           wp, wb, _stream())
 
 
+@_entry
 def ago_fused_attn(q, k, v, o, scale, workspace=None):
     B, Hh, S, D = q.shape
     wp, wb = _ws(workspace)
-    _chk(lib.ago_fused_attn(_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q), wp, wb, _stream()))
+    return lib.ago_fused_attn, (_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q), wp, wb, _stream())
 
 
 # ---- un-fused operators ---------------------------------------------------------------
 
+@_entry
 def ago_gemm(a, b, bias, res, c, act=ACT_NONE):
     M, K = a.shape
     N = b.shape[1]
-    _chk(lib.ago_gemm(_p(a), _p(b), _p(bias), _p(res), _p(c), M, K, N, act, _dt(a), _stream()))
+    return lib.ago_gemm, (_p(a), _p(b), _p(bias), _p(res), _p(c), M, K, N, act, _dt(a), _stream())
 
 
+@_entry
 def ago_conv1x1(x, w, bias, res, y, act=ACT_NONE):
     N, H, W, Cin = x.shape
-    _chk(lib.ago_conv1x1(_p(x), _p(w), _p(bias), _p(res), _p(y), N, H, W, Cin, w.shape[1], act, _dt(x), _stream()))
+    return lib.ago_conv1x1, (_p(x), _p(w), _p(bias), _p(res), _p(y), N, H, W, Cin, w.shape[1], act, _dt(x), _stream())
 
 
+@_entry
 def ago_dwconv3x3(x, w, bias, y, stride, act=ACT_NONE):
     N, H, W, C = x.shape
-    _chk(lib.ago_dwconv3x3(_p(x), _p(w), _p(bias), _p(y), N, H, W, C, stride, act, _dt(x), _stream()))
+    return lib.ago_dwconv3x3, (_p(x), _p(w), _p(bias), _p(y), N, H, W, C, stride, act, _dt(x), _stream())
 
 
+@_entry
 def ago_conv3x3(x, w, bias, res, y, act=ACT_NONE):
     N, H, W, Cin = x.shape
-    _chk(lib.ago_conv3x3(_p(x), _p(w), _p(bias), _p(res), _p(y), N, H, W, Cin, w.shape[3], act, _dt(x), _stream()))
+    return lib.ago_conv3x3, (_p(x), _p(w), _p(bias), _p(res), _p(y), N, H, W, Cin, w.shape[3], act, _dt(x), _stream())
 
 
+@_entry
 def ago_bias_act(x, bias, y, act=ACT_NONE):
     C = x.shape[-1]
-    _chk(lib.ago_bias_act(_p(x), _p(bias), _p(y), x.numel() // C, C, act, _dt(x), _stream()))
+    return lib.ago_bias_act, (_p(x), _p(bias), _p(y), x.numel() // C, C, act, _dt(x), _stream())
 
 
+@_entry
 def ago_add_act(a, b, y, act=ACT_NONE):
-    _chk(lib.ago_add_act(_p(a), _p(b), _p(y), a.numel(), act, _dt(a), _stream()))
+    return lib.ago_add_act, (_p(a), _p(b), _p(y), a.numel(), act, _dt(a), _stream())
 
 
+@_entry
 def ago_scale(x, y, alpha):
-    _chk(lib.ago_scale(_p(x), _p(y), x.numel(), float(alpha), _dt(x), _stream()))
+    return lib.ago_scale, (_p(x), _p(y), x.numel(), float(alpha), _dt(x), _stream())
 
 
+@_entry
 def ago_softmax_rows(x, y):
     cols = x.shape[-1]
-    _chk(lib.ago_softmax_rows(_p(x), _p(y), x.numel() // cols, cols, _dt(x), _dt(y), _stream()))
+    return lib.ago_softmax_rows, (_p(x), _p(y), x.numel() // cols, cols, _dt(x), _dt(y), _stream())
 
 
+@_entry
 def ago_bmm_nt(a, b, c, alpha=1.0):
     M, K = a.shape[-2:]
     N = b.shape[-2]
-    _chk(lib.ago_bmm_nt(_p(a), _p(b), _p(c), a.numel() // (M * K), M, N, K, float(alpha), _dt(a), _dt(c), _stream()))
+    return lib.ago_bmm_nt, (_p(a), _p(b), _p(c), a.numel() // (M * K), M, N, K, float(alpha), _dt(a), _dt(c), _stream())
 
 
+@_entry
 def ago_bmm_nn(a, b, c):
     M, K = a.shape[-2:]
     N = b.shape[-1]
-    _chk(lib.ago_bmm_nn(_p(a), _p(b), _p(c), a.numel() // (M * K), M, N, K, _dt(a), _stream()))
+    return lib.ago_bmm_nn, (_p(a), _p(b), _p(c), a.numel() // (M * K), M, N, K, _dt(a), _stream())
 
 
 # ---- un-fused subgraphs ---------------------------------------------------------------
 
+@_entry
 def ago_unfused_invres(x, w1, b1, wd, bd, w2, b2, y, stride, residual, epilogue_fused, workspace):
     N, H, W, Cin = x.shape
     Cexp, Cout = w2.shape
     wp, wb = _ws(workspace)
-    _chk(lib.ago_unfused_invres(_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
+    return lib.ago_unfused_invres, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
                                 N, H, W, Cin, Cexp, Cout, stride, int(residual), _dt(x),
-                                int(epilogue_fused), wp, wb, _stream()))
+                                int(epilogue_fused), wp, wb, _stream())
 
 
+@_entry
 def ago_unfused_conv_chain(x, wa, ba, wb_, bb, y, residual, epilogue_fused, workspace):
     N, H, W, C = x.shape
     wp, wb = _ws(workspace)
-    _chk(lib.ago_unfused_conv_chain(_p(x), _p(wa), _p(ba), _p(wb_), _p(bb), _p(y), N, H, W, C,
-                                    int(residual), _dt(x), int(epilogue_fused), wp, wb, _stream()))
+    return lib.ago_unfused_conv_chain, (_p(x), _p(wa), _p(ba), _p(wb_), _p(bb), _p(y), N, H, W, C,
+                                    int(residual), _dt(x), int(epilogue_fused), wp, wb, _stream())
 
 
+@_entry
 def ago_unfused_ffn(x, w1, b1, w2, b2, y, act, epilogue_fused, workspace):
     M, K = x.shape
     F, K2 = w2.shape
     wp, wb = _ws(workspace)
-    _chk(lib.ago_unfused_ffn(_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
-                             int(epilogue_fused), wp, wb, _stream()))
+    return lib.ago_unfused_ffn, (_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
+                             int(epilogue_fused), wp, wb, _stream())
 
 
+@_entry
 def ago_unfused_attn(q, k, v, o, scale, epilogue_fused, workspace):
     B, Hh, S, D = q.shape
     wp, wb = _ws(workspace)
-    _chk(lib.ago_unfused_attn(_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q),
-                              int(epilogue_fused), wp, wb, _stream()))
+    return lib.ago_unfused_attn, (_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q),
+                              int(epilogue_fused), wp, wb, _stream())

@@ -21,14 +21,15 @@ struct ProfRing {
 };
 ProfRing g_prof[4];
 int g_prof_cap = 0;
+unsigned g_prof_mask = 0xFu;      // bit op: that fused entry point records events
 }  // namespace
 
 namespace ago {
 void prof_start(int op, hipStream_t s) {
-    if (g_prof_cap > 0) (void)hipEventRecord(g_prof[op].start[g_prof[op].calls % g_prof_cap], s);
+    if (g_prof_cap > 0 && ((g_prof_mask >> op) & 1u)) (void)hipEventRecord(g_prof[op].start[g_prof[op].calls % g_prof_cap], s);
 }
 void prof_stop(int op, hipStream_t s) {
-    if (g_prof_cap > 0) {
+    if (g_prof_cap > 0 && ((g_prof_mask >> op) & 1u)) {
         (void)hipEventRecord(g_prof[op].stop[g_prof[op].calls % g_prof_cap], s);
         ++g_prof[op].calls;
     }
@@ -52,6 +53,12 @@ int ago_profile_enable(int capacity) {
             if (hipEventCreate(&r.start[i]) != hipSuccess || hipEventCreate(&r.stop[i]) != hipSuccess) return -1;
     }
     g_prof_cap = capacity;
+    return 0;
+}
+
+int ago_profile_select(unsigned op_mask) {
+    if (op_mask & ~0xFu) return -1;
+    g_prof_mask = op_mask;
     return 0;
 }
 

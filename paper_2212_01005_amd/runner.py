@@ -63,34 +63,53 @@ def alloc_workspace(case, fused=True, device="cuda:0"):
     return torch.empty(max(n, 16), dtype=torch.uint8, device=device) if n > 0 else None
 
 
-def run_fused(case, t, y, ws=None):
+def _fused_call(case, t, y, ws):
     k = type(case).__name__
     if k == "InvresCase":
-        ago.ago_fused_invres(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
-                             case.stride, case.residual, ws)
-    elif k == "ChainCase":
-        ago.ago_fused_conv_chain(t["x"], t["wa"], t["ba"], t["wb"], t["bb"], y, case.residual, ws)
-    elif k == "FfnCase":
-        ago.ago_fused_ffn(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, ago.ACT_GELU_TANH, ws)
-    else:
-        ago.ago_fused_attn(t["q"], t["k"], t["v"], y, case.scale, ws)
+        return ago.ago_fused_invres, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
+                                      case.stride, case.residual, ws)
+    if k == "ChainCase":
+        return ago.ago_fused_conv_chain, (t["x"], t["wa"], t["ba"], t["wb"], t["bb"], y, case.residual, ws)
+    if k == "FfnCase":
+        return ago.ago_fused_ffn, (t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, ago.ACT_GELU_TANH, ws)
+    return ago.ago_fused_attn, (t["q"], t["k"], t["v"], y, case.scale, ws)
+
+
+def run_fused(case, t, y, ws=None):
+    fn, args = _fused_call(case, t, y, ws)
+    fn(*args)
     return y
+
+
+def prepare_fused(case, t, y, ws=None):
+    """Zero-argument launcher of the fused subgraph on these buffers (arguments marshalled once)."""
+    fn, args = _fused_call(case, t, y, ws)
+    return ago.prepare(fn, *args)
+
+
+def _unfused_call(case, t, y, ws, epilogue_fused):
+    k = type(case).__name__
+    if k == "InvresCase":
+        return ago.ago_unfused_invres, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
+                                        case.stride, case.residual, epilogue_fused, ws)
+    if k == "ChainCase":
+        return ago.ago_unfused_conv_chain, (t["x"], t["wa"], t["ba"], t["wb"], t["bb"], y, case.residual,
+                                            epilogue_fused, ws)
+    if k == "FfnCase":
+        return ago.ago_unfused_ffn, (t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, ago.ACT_GELU_TANH,
+                                     epilogue_fused, ws)
+    return ago.ago_unfused_attn, (t["q"], t["k"], t["v"], y, case.scale, epilogue_fused, ws)
 
 
 def run_unfused(case, t, y, ws, epilogue_fused):
-    k = type(case).__name__
-    if k == "InvresCase":
-        ago.ago_unfused_invres(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
-                               case.stride, case.residual, epilogue_fused, ws)
-    elif k == "ChainCase":
-        ago.ago_unfused_conv_chain(t["x"], t["wa"], t["ba"], t["wb"], t["bb"], y, case.residual,
-                                   epilogue_fused, ws)
-    elif k == "FfnCase":
-        ago.ago_unfused_ffn(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, ago.ACT_GELU_TANH,
-                            epilogue_fused, ws)
-    else:
-        ago.ago_unfused_attn(t["q"], t["k"], t["v"], y, case.scale, epilogue_fused, ws)
+    fn, args = _unfused_call(case, t, y, ws, epilogue_fused)
+    fn(*args)
     return y
+
+
+def prepare_unfused(case, t, y, ws, epilogue_fused):
+    fn, args = _unfused_call(case, t, y, ws, epilogue_fused)
+    return ago.prepare(fn, *args)
 
 
 def to_numpy64(t):
