@@ -45,6 +45,9 @@ def parse():
                     help="calibration aid: instead of the benchmark, run the library's plain elementwise kernel "
                          "(ago_scale, alpha = 1, fp32) over this many bytes --steps times; it reads and writes "
                          "exactly that many bytes, which scales the FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--tile-config", default="",
+                    help="tile-size sweep aid: comma-separated op=id pairs (op: invres, chain, ffn, attn) passed to "
+                         "ago_set_tile_config before anything runs; the default is the library's built-in choice")
     return ap.parse_args()
 
 
@@ -71,6 +74,15 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": n * 4, "copy_bytes_written": n * 4, "launches": args.steps}))
         return
+
+    tile_cfg = {}
+    for item in filter(None, args.tile_config.split(",")):
+        name, cid = item.split("=")
+        op = {"invres": ago.OP_FUSED_INVRES, "chain": ago.OP_FUSED_CONV_CHAIN, "ffn": ago.OP_FUSED_FFN,
+              "attn": ago.OP_FUSED_ATTN}[name]
+        if ago.set_tile_config(op, int(cid)) != 0:
+            sys.exit("bench.py: unknown tile configuration %s" % item)
+        tile_cfg[name] = int(cid)
 
     idxs = list(range(5)) if args.only < 0 else [args.only]
     cases = [wl.baseline_case(i) for i in idxs]
@@ -188,6 +200,7 @@ def main():
         "config": {"workload": "all 5 BASELINE configs, one fused launch each per step"
                    if args.only < 0 else cases[0].name,
                    "configs": [c.name for c in cases],
+                   "tile_config": tile_cfg or "built-in",
                    "note": "config 0 is fp32 storage, configs 1-4 bf16 storage with fp32 accumulation"},
         "roofline": roofline, "cpu_baseline": cpu, "per_config": per_config,
         "fused_kernel_us": {str(k): round(v * 1e3, 2) for k, v in kernel_ms.items()},

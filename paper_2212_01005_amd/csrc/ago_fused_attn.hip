@@ -2,15 +2,26 @@
 // "downstream pointwise" rule of Sec. III-B: the downstream product keeps all of its output
 // columns and consumes the upstream result in slices of its reduction dimension, the keys).
 //
-// One workgroup = 4 waves = 128 query rows of one (batch, head); each wave owns 32 query rows.
-// Keys / values are streamed through LDS in blocks of 128 with register prefetch.  Per block:
+// One workgroup = 32 NQT query rows of one (batch, head), 2 NQT consumer waves and two producer waves.
+//   consumer (qt, kh) owns the 32 query rows of tile qt and, of every 128-key block, the 64 keys
+//       of half kh: the two waves of a query tile share a SIMD, so one's softmax arithmetic
+//       overlaps the other's matrix instructions.  Each keeps its own running (max, sum, O^T); the
+//       pair is merged once at the end through LDS.
+//   producers (one for K, one for V): stream the blocks global -> LDS with the direct-to-LDS load
+//       (no registers, no LDS stores, nothing transposed by hand), one block ahead, two LDS
+//       buffers; they meet the consumers at one workgroup barrier per block.
+// Per block and consumer:
 //   S^T = K_blk Q^T         (rows = keys, cols = queries: a lane owns one query column, so the
 //                            softmax statistics of a row are lane-local plus one cross-half step)
 //   online softmax in fp32  (running max m and sum l per query, exp2 with scale*log2(e) folded in)
 //   O^T += V_blk^T P^T      (P rounded to bf16; the accumulator layout of S^T *is* the B-operand
-//                            layout of this product, so P never leaves registers)
-// The scores and probabilities never leave the chip.  V is transposed while it is staged into
-// LDS, with the keys of every group of 16 permuted to match the accumulator row order.
+//                            layout of this product, so P never leaves registers; V^T fragments come
+//                            from V's natural [key][d] layout through the transposing LDS read, whose
+//                            row addresses also absorb the accumulator's key order)
+// The scores and probabilities never leave the chip.
+// LDS layouts (128-byte rows = one key; the producer realises the permutation by choosing which
+// global 16-byte chunk each lane fetches): K chunk ^= (key >> 1) & 7; V chunk ^= bit 2 from key
+// bit 1 and bit 1 from key bit 2.  Both make the fragment reads bank-conflict free.
 #include "ago_dev.hpp"
 #include "ago_launch.hpp"
 
@@ -18,170 +29,261 @@ namespace ago {
 
 constexpr int kD = 64;      // head dimension
 constexpr int kKB = 128;    // keys per block
+constexpr int kBlockB = kKB * kD * 2;          // bytes of one K (or V) block: 16384
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_attn_kernel(
+namespace {
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+__device__ __forceinline__ bf16x8 lds_read16(const lds_byte* p) {
+    typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+    return *(const lds_bf16x8*)p;
+}
+// V^T fragment: rows = head-dimension columns (the lane offset encodes them), k = the 8 keys whose
+// rows start at p (first four) and at p + 8 rows (last four)
+__device__ __forceinline__ bf16x8 lds_read_vt(const lds_byte* p) {
+    typedef __attribute__((address_space(3))) bf16x4_t lds_bf16x4;
+    const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p);
+    const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 8 * 128));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+}  // namespace
+
+template <int NQT, int NSTG>
+__global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per_eu(3, 4))) void fused_attn_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    bf16_t* __restrict__ O, int S, float c /* scale * log2(e) */) {
-    constexpr int LDK = kD + 8, LDV = kKB + 8;
-    extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t (*Ks)[kKB][LDK] = reinterpret_cast<bf16_t (*)[kKB][LDK]>(smem);                       // [2]
-    bf16_t (*Vt)[kD][LDV] = reinterpret_cast<bf16_t (*)[kD][LDV]>(smem + 2 * kKB * LDK * 2);     // [2]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int j = lane & 31, h = lane >> 5;
-    const long head_off = (long)blockIdx.y * S * kD;
+    bf16_t* __restrict__ O, int S, int heads, int qblocks, float c /* scale * log2(e) */) {
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    lds_byte* smem = (lds_byte*)smem_generic;          // [2 buffers][K block | V block]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Workgroups are dealt round-robin to the 8 XCDs (one L2 each) in launch order: the query blocks
+    // of one head get launch indices that are congruent modulo 8, so they land on the same XCD and
+    // the head's K and V come from HBM once instead of once per query block.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int head = (slot / qblocks) * 8 + xcd, qblk = slot % qblocks;
+    if (head >= heads) return;                         // padding workgroups of the last group of 8 heads
+    const long head_off = (long)head * S * kD;
     Q += head_off; K += head_off; V += head_off; O += head_off;
-    const int q_row = blockIdx.x * 128 + wave * 32 + j;
+    const int nblk = (S + kKB - 1) / kKB;
+
+    if (wave >= 2 * NQT) {
+        // ================================ producers ========================================
+        // Wave 2 NQT streams the K blocks, wave 2 NQT + 1 the V blocks.  Load q of a block covers its
+        // rows 8 q .. 8 q + 7: lane = (row, physical chunk).  Keys beyond S are clamped to the last
+        // key (their scores are masked by the consumers).
+        const bool is_v = wave == 2 * NQT + 1;
+        const bf16_t* src = is_v ? V : K;
+        const int r8 = lane >> 3, pc = lane & 7;
+        auto issue = [&](int blk) {
+            lds_byte* dst = smem + (blk % NSTG) * 2 * kBlockB + (is_v ? kBlockB : 0);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int row = 8 * q + r8;
+                const int sw = is_v ? ((((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1)) : ((row >> 1) & 7);
+                const bf16_t* g = src + (long)min(blk * kKB + row, S - 1) * kD + 8 * (pc ^ sw);
+                __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) const void*)g,
+                                                 (__attribute__((address_space(3))) void*)(dst + q * 1024), 16, 0, 0);
+            }
+        };
+        auto wait_blocks = [&](int n) {      // at most n blocks (16 loads each) outstanding
+            if (n >= 2) wait_vm<32>();
+            else if (n == 1) wait_vm<16>();
+            else wait_vm<0>();
+        };
+        static_assert(NSTG == 2 || NSTG == 3, "ring depth");
+        const int npro = min(NSTG, nblk);
+        for (int blk = 0; blk < npro; ++blk) issue(blk);
+        wait_blocks(npro - 1);
+        __builtin_amdgcn_s_barrier();                  // block 0 is in LDS
+        for (int blk = 0; blk < nblk; ++blk) {
+            // block blk + 1 must have landed before the consumers leave this iteration; blocks up to
+            // blk + NSTG - 1 have been issued.  Block blk + NSTG can only be issued once the buffer of
+            // block blk is free, i.e. after this iteration's barrier.
+            wait_blocks(max(0, min(blk + NSTG - 1, nblk - 1) - (blk + 1)));
+            __builtin_amdgcn_s_barrier();
+            if (blk + NSTG < nblk) issue(blk + NSTG);
+        }
+        __builtin_amdgcn_s_barrier();                  // the consumers' merge barrier
+        return;
+    }
+
+    // ================================== consumers ==========================================
+    const int qt = wave % NQT, kh = wave / NQT;
+    const int j = lane & 31, h = lane >> 5;
+    const int q_row = qblk * (32 * NQT) + qt * 32 + j;
 
     bf16x8 qf[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        v = ld_u4(Q + (long)min(q_row, S - 1) * kD + ks * 16 + 8 * h);
-        qf[ks] = __builtin_bit_cast(bf16x8, v);
-    }
+    for (int ks = 0; ks < 4; ++ks)
+        qf[ks] = __builtin_bit_cast(bf16x8, ld_u4(Q + (long)min(q_row, S - 1) * kD + ks * 16 + 8 * h));
 
-    uint4 rk[4];
-    uint2 rv[8];
-    // Keys beyond S are clamped to the last key: their scores are masked to -inf below, so their
-    // probabilities are exactly 0 and the (finite) duplicate K / V rows contribute nothing.
-    // Unpredicated loads keep the block loop free of branches.
-    auto load_block = [&](int key0) {
+    // K fragment of key tile kt (32 keys), k step ks: row = 64 kh + 32 kt + j, logical chunk 2 ks + h
+    const int krow = 64 * kh + j;                      // + 32 kt: bit 5, does not reach the swizzle bits 1..3
+    const int koff = krow * 128;
+    const int ksw = (krow >> 1) & 7;
+    // V^T fragment of (kt, u, dt): the lane addresses row (64 kh + 32 kt + 16 u + 4 h + (s >> 2)) [+ 8 for the
+    // second read], head-dimension columns dt * 32 + 16 (g & 1) + 4 (s & 3) .. + 3
+    const int g = lane >> 4, s15 = lane & 15;
+    const int vrow0 = 64 * kh + 4 * h + (s15 >> 2);    // + 32 kt + 16 u (+ 8): bits 3..5; swizzle uses bits 1, 2
+    const int vsw = (((vrow0 >> 1) & 1) << 2) | (((vrow0 >> 2) & 1) << 1);
+    int voff[2];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int cidx = tid + 256 * u, row = cidx >> 3, kc = cidx & 7;
-            rk[u] = ld_u4(K + (long)min(key0 + row, S - 1) * kD + kc * 8);
-        }
-        const int nq = tid & 15, ko = tid >> 4;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-            rv[kk] = *reinterpret_cast<const uint2*>(V + (long)min(key0 + ko * 8 + kk, S - 1) * kD + nq * 4);
-    };
-    auto store_block = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int cidx = tid + 256 * u, row = cidx >> 3, kc = cidx & 7;
-            st_u4(&Ks[buf][row][kc * 8], rk[u]);
-        }
-        const int nq = tid & 15, ko = tid >> 4;
-        uint4 t[4];
-        transpose_8x4(rv, t);
-        // keys ko*8 .. ko*8+7 of a group of 16: first four -> positions 4*(ko&1).., last four ->
-        // positions 8 + 4*(ko&1)..  (lane half h of the matrix instruction reads positions 8h..8h+7)
-        const int gb = (ko >> 1) * 16 + 4 * (ko & 1);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            *reinterpret_cast<uint2*>(&Vt[buf][nq * 4 + q][gb]) = make_uint2(t[q].x, t[q].y);
-            *reinterpret_cast<uint2*>(&Vt[buf][nq * 4 + q][gb + 8]) = make_uint2(t[q].z, t[q].w);
-        }
-    };
+    for (int dt = 0; dt < 2; ++dt) {
+        const int chunk = 4 * dt + 2 * (g & 1) + ((s15 & 3) >> 1);        // 16-byte chunk of the lane's 4 columns
+        voff[dt] = vrow0 * 128 + ((chunk ^ vsw) << 4) + 8 * (s15 & 1);
+    }
 
     f32x16 o[2];
 #pragma unroll
     for (int r = 0; r < 16; ++r) { o[0][r] = 0.f; o[1][r] = 0.f; }
     float m = -INFINITY, l = 0.f;     // running max of scaled scores, running (per-half) sum
 
-    const int nblk = (S + kKB - 1) / kKB;
-    load_block(0);
-    store_block(0);
-    __syncthreads();
+    __builtin_amdgcn_s_barrier();     // block 0 is in LDS
     for (int blk = 0; blk < nblk; ++blk) {
-        const int buf = blk & 1;
-        load_block(min(blk + 1, nblk - 1) * kKB);     // past the end: re-load the last block
+        const lds_byte* kb = smem + (blk % NSTG) * 2 * kBlockB;
+        const lds_byte* vb = kb + kBlockB;
 
-        f32x16 s[4];
+        f32x16 sc[2];
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+            for (int r = 0; r < 16; ++r) sc[kt][r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
-                s[kt] = mfma32(ld_bf16x8(&Ks[buf][kt * 32 + j][ks * 16 + 8 * h]), qf[ks], s[kt]);
+            for (int kt = 0; kt < 2; ++kt)
+                sc[kt] = mfma32(lds_read16(kb + koff + kt * 32 * 128 + (((2 * ks + h) ^ ksw) << 4)), qf[ks], sc[kt]);
 
         // mask keys beyond S (only a block that straddles S needs it; the test is wave-uniform)
         if ((blk + 1) * kKB > S) {
-            const int key_base = blk * kKB + 4 * h;
+            const int key_base = blk * kKB + 64 * kh + 4 * h;
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
+            for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int key = key_base + kt * 32 + 8 * (r >> 2) + (r & 3);
-                    s[kt][r] = key < S ? s[kt][r] : -INFINITY;
+                    sc[kt][r] = key < S ? sc[kt][r] : -INFINITY;
                 }
         }
         // block max of the raw scores (c > 0 keeps the order); pairs fold into 3-input max
         float mx = -INFINITY;
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) mx = fmaxf(fmaxf(s[kt][r], s[kt][r + 1]), mx);
+            for (int r = 0; r < 16; r += 2) mx = fmaxf(fmaxf(sc[kt][r], sc[kt][r + 1]), mx);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m, mx * c);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        // a half whose keys are all beyond S so far keeps m = -inf: subtract 0 instead (exp2(-inf) = 0)
+        const float mref = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m - mref);
         m = m_new;
         l *= alpha;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { o[0][r] *= alpha; o[1][r] *= alpha; }
 
-        bf16x8 pf[4][2];
+        bf16x8 pf[2][2];
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float pv = __builtin_amdgcn_exp2f(fmaf(s[kt][8 * u + e], c, -m_new));
+                    const float pv = __builtin_amdgcn_exp2f(fmaf(sc[kt][8 * u + e], c, -mref));
                     l += pv;
                     pf[kt][u][e] = (bf16_t)pv;
                 }
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int dt = 0; dt < 2; ++dt)
-                    o[dt] = mfma32(ld_bf16x8(&Vt[buf][dt * 32 + j][kt * 32 + 16 * u + 8 * h]), pf[kt][u], o[dt]);
+                    o[dt] = mfma32(lds_read_vt(vb + voff[dt] + (kt * 32 + 16 * u) * 128), pf[kt][u], o[dt]);
 
-        store_block(buf ^ 1);
-        __syncthreads();
+        __builtin_amdgcn_s_barrier();
     }
 
+    // merge the two key halves of each query tile: the kh = 1 wave parks (m, l, O^T) in LDS (the
+    // K / V buffers are free after the last barrier), the kh = 0 wave combines and writes O.
     l += __shfl_xor(l, 32, 64);
-    const float inv = 1.0f / l;
-    if (q_row < S) {
+    float* park = reinterpret_cast<float*>(smem_generic) + qt * 34 * 64;     // [34][64] floats per query tile
+    if (kh == 1) {
+        park[lane] = m;
+        park[64 + lane] = l;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int d = dt * 32 + 8 * g + 4 * h;
-                *reinterpret_cast<uint2*>(O + (long)q_row * kD + d) =
-                    make_uint2(pack_bf16(o[dt][4 * g] * inv, o[dt][4 * g + 1] * inv),
-                               pack_bf16(o[dt][4 * g + 2] * inv, o[dt][4 * g + 3] * inv));
-            }
+            for (int r = 0; r < 16; ++r) park[(2 + dt * 16 + r) * 64 + lane] = o[dt][r];
+    }
+    __syncthreads();
+    if (kh == 0) {
+        const float m1 = park[lane], l1 = park[64 + lane];
+        const float mt = fmaxf(m, m1);                 // finite: key 0 belongs to half 0
+        const float a0 = __builtin_amdgcn_exp2f(m - mt), a1 = __builtin_amdgcn_exp2f(m1 - mt);
+        const float inv = 1.0f / (l * a0 + l1 * a1);
+        const float w0 = a0 * inv, w1 = a1 * inv;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[dt][r] = o[dt][r] * w0 + park[(2 + dt * 16 + r) * 64 + lane] * w1;
+        if (q_row < S) {
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int d = dt * 32 + 8 * gq + 4 * h;
+                    *reinterpret_cast<uint2*>(O + (long)q_row * kD + d) =
+                        make_uint2(pack_bf16(o[dt][4 * gq], o[dt][4 * gq + 1]), pack_bf16(o[dt][4 * gq + 2], o[dt][4 * gq + 3]));
+                }
+        }
     }
 }
 
-int fused_attn_num_cfgs() { return 1; }
-
-hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
-                      float scale, int tile_cfg, hipStream_t s) {
-    (void)tile_cfg;
-    constexpr size_t smem = (size_t)2 * kKB * (kD + 8) * 2 + (size_t)2 * kD * (kKB + 8) * 2;
+template <int NQT, int NSTG>
+static hipError_t launch_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
+                              float scale, hipStream_t s) {
+    constexpr size_t smem = (size_t)NSTG * 2 * kBlockB;    // ring of (K block, V block) buffers; the merge reuses them
+    static_assert((size_t)NQT * 34 * 64 * 4 <= smem, "merge scratch");
+    auto kern = fused_attn_kernel<NQT, NSTG>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_attn_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((S + 127) / 128, (unsigned)(B * Hh));
+    const int heads = B * Hh, qblocks = (S + 32 * NQT - 1) / (32 * NQT);
+    dim3 grid((unsigned)(8 * qblocks * ((heads + 7) / 8)));
     prof_start(3, s);
-    hipLaunchKernelGGL(fused_attn_kernel, grid, dim3(256), smem, s, (const bf16_t*)q, (const bf16_t*)k,
-                       (const bf16_t*)v, (bf16_t*)o, S, scale * 1.4426950408889634f);
+    hipLaunchKernelGGL(kern, grid, dim3((2 * NQT + 2) * 64), smem, s, (const bf16_t*)q, (const bf16_t*)k,
+                       (const bf16_t*)v, (bf16_t*)o, S, heads, qblocks, scale * 1.4426950408889634f);
     prof_stop(3, s);
     return hipGetLastError();
+}
+
+// Tile configurations: query rows per workgroup (two workgroups share a compute unit except for 3).
+//   0: 96   1: 128   2: 64   3: 192, one workgroup per compute unit, three LDS buffers
+int fused_attn_num_cfgs() { return 4; }
+
+hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
+                      float scale, int tile_cfg, hipStream_t s) {
+    if (tile_cfg < 0) {
+        // built-in choice: 192-query workgroups (a compute unit to themselves, K and V of the first
+        // three blocks requested at once) when that still gives the chip enough workgroups
+        const long wgs = (long)((S + 191) / 192) * B * Hh;
+        tile_cfg = (S > 96 && wgs >= 128) ? 3 : 0;
+    }
+    switch (tile_cfg) {
+        case 1: return launch_attn<4, 2>(q, k, v, o, B, Hh, S, scale, s);
+        case 2: return launch_attn<2, 2>(q, k, v, o, B, Hh, S, scale, s);
+        case 3: return launch_attn<6, 3>(q, k, v, o, B, Hh, S, scale, s);
+        default: return launch_attn<3, 2>(q, k, v, o, B, Hh, S, scale, s);
+    }
 }
 
 }  // namespace ago
