@@ -317,7 +317,8 @@ static size_t plan_tile(InvresParams& p, bool bf16, int stride, int toh, int tow
 }
 
 // tile_cfg: -1 = built-in choice; otherwise index into the candidate list below.
-static const int kTileCand[][2] = {{2, 14}, {4, 4}, {1, 14}, {2, 2}, {4, 8}, {7, 7}, {2, 8}, {1, 8}};
+static const int kTileCand[][2] = {{2, 14}, {4, 4}, {1, 14}, {2, 2}, {4, 8}, {7, 7}, {2, 8}, {1, 8},
+                                   {1, 2}, {2, 4}, {3, 3}, {1, 4}, {2, 3}, {1, 1}, {3, 4}, {2, 7}};
 int fused_invres_num_cfgs() { return (int)(sizeof(kTileCand) / sizeof(kTileCand[0])); }
 
 hipError_t fused_invres(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
@@ -334,10 +335,14 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
         smem = plan_tile(p, bf16, stride, kTileCand[tile_cfg][0], kTileCand[tile_cfg][1]);
         if (smem > kLdsMax) return hipErrorInvalidValue;
     } else {
-        // built-in choice: full-width strips of 2 rows when the image is narrow (stride 1),
-        // 4x4 tiles otherwise; shrink until the tile fits in LDS.
-        int toh = (stride == 1 && p.OW <= 16) ? 2 : 4;
-        int tow = (stride == 1 && p.OW <= 16) ? p.OW : 4;
+        // built-in choice: 4x4 output tiles, halved (down to 2x2) while the launch has fewer than 128
+        // workgroups: these blocks are latency-bound, so more, smaller workgroups (each recomputing a
+        // larger share of halo) finish sooner than few large ones; then shrink until the tile fits LDS.
+        int toh = 4, tow = 4;
+        auto wgs = [&](int th, int tw) { return (long)N * ((p.OH + th - 1) / th) * ((p.OW + tw - 1) / tw); };
+        while (wgs(toh, tow) < 128 && (toh > 2 || tow > 2)) {
+            if (tow >= toh) tow /= 2; else toh /= 2;
+        }
         for (;;) {
             smem = plan_tile(p, bf16, stride, toh, tow);
             if (smem <= kLdsMax) break;
