@@ -45,6 +45,8 @@ def parse():
                     help="calibration aid: instead of the benchmark, run the library's plain elementwise kernel "
                          "(ago_scale, alpha = 1, fp32) over this many bytes --steps times; it reads and writes "
                          "exactly that many bytes, which scales the FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--variants", default="fused,u1,u2",
+                    help="which variants the per-config table runs (profiling aid: counters of one variant alone)")
     ap.add_argument("--tile-config", default="",
                     help="tile-size sweep aid: comma-separated op=id pairs (op: invres, chain, ffn, attn) passed to "
                          "ago_set_tile_config before anything runs; the default is the library's built-in choice")
@@ -155,9 +157,10 @@ def main():
         for (c, t, y, ws) in state:
             wsu = runner.alloc_workspace(c, fused=False)
             yu = runner.alloc_output(c)
-            fused_us = time_us(runner.prepare_fused(c, t, y, ws), args.detail_iters)
-            u1_us = time_us(runner.prepare_unfused(c, t, yu, wsu, 0), args.detail_iters)
-            u2_us = time_us(runner.prepare_unfused(c, t, yu, wsu, 1), args.detail_iters)
+            variants = args.variants.split(",")
+            fused_us = time_us(runner.prepare_fused(c, t, y, ws), args.detail_iters) if "fused" in variants else float("nan")
+            u1_us = time_us(runner.prepare_unfused(c, t, yu, wsu, 0), args.detail_iters) if "u1" in variants else float("nan")
+            u2_us = time_us(runner.prepare_unfused(c, t, yu, wsu, 1), args.detail_iters) if "u2" in variants else float("nan")
             tf = c.flops() / (fused_us * 1e-6) / 1e12
             peak = PEAK_F32_TFLOPS if c.dtype == "f32" else PEAK_BF16_TFLOPS
             t_mfma = c.flops() / (peak * 1e12)

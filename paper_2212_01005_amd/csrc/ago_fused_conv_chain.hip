@@ -17,9 +17,13 @@
 // (32-pixel row tile, 32-output-channel half) jobs to 8 wave pairs; the two waves of a pair each
 // reduce over one half of the input channels and their partial sums are added through LDS.
 //
-// LDS layout of the weights: row = output channel, 8 chunks of 8 input channels, chunk index
-// XOR-ed with (row >> 4) & 3 so that both the transposing stores (rows 4 apart) and the
-// fragment reads (consecutive rows) are bank-conflict free.
+// LDS layouts.  A 16-byte-per-lane fragment read is served one half-wave (32 lanes) at a time and is
+// bank-conflict free when the 32 rows it touches are 144 bytes apart (72-element rows) or fall into
+// two runs of 16 such rows whose starts differ by a multiple of 256 bytes (measured with the LDS
+// bank-conflict counter).  Weights: row = output channel, 8 chunks of 8 input channels, 72-element
+// rows, chunk index XOR-ed with (row >> 5) & 1 (constant within a fragment read; it only spreads the
+// transposing stores).  Activation tiles: 72 elements per pixel, pixel rows padded to a multiple of
+// 256 bytes, and every half-wave of a fragment read covers 16 consecutive pixels of two tile rows.
 #include "ago_dev.hpp"
 #include "ago_launch.hpp"
 
@@ -29,19 +33,27 @@ template <int TH, int TW>
 struct ChainGeom {
     static constexpr int C = 64, LD = C + 8;
     static constexpr int XH = TH + 4, XW = TW + 4, R1H = TH + 2, R1W = TW + 2;
-    static constexpr int P1 = R1H * R1W, P2 = TH * TW;
+    // A 16-byte fragment read is conflict-free when the two pixel rows that the 32 lanes of a
+    // half-wave cover start a multiple of 256 bytes apart: rows of the X and T tiles are padded
+    // to that pitch (elements).
+    static constexpr int XROW = (XW * LD * 2 + 255) / 256 * 128, TROW = (R1W * LD * 2 + 255) / 256 * 128;
+    // conv2 lays its output pixels out 16 to a lane row when the tile is 9..16 wide (so that a
+    // half-wave covers exactly two rows of T); narrower tiles keep the dense numbering
+    static constexpr int P2W = (TW > 8 && TW <= 16) ? 16 : TW;
+    static constexpr int P1 = R1H * R1W, P2 = TH * P2W;
     static constexpr int NMT1 = (P1 + 31) / 32, NMT2 = (P2 + 31) / 32;
-    static constexpr size_t kSmem = ((size_t)XH * XW + P1 + 9 * 64) * LD * 2 + 128 * 4;
+    static constexpr size_t kSmem = ((size_t)XH * XROW + R1H * TROW + 9 * 64 * LD) * 2 + 128 * 4;
 };
 
 // One convolution over an LDS-resident source tile, on 8 waves.  The work is cut into
 // (32-pixel row tile, 32-channel half) jobs, 2 * NMT of them; wave w takes job w, and jobs beyond
 // the first eight go to owners 1, 3, 5, 7, 0, 2, 4, 6 in that order so that owners that share a
 // SIMD (w and w + 4) do not both get an extra job.
-// SRC_W = width (pixels) of the source tile, DST_W = width of the destination region,
-// NP = destination pixels, NMT = row tiles.  WEIGHTS_A: weights are MFMA operand A
-// (accumulator rows = channels, cols = pixels), else operand B.
-template <int SRC_W, int DST_W, int NP, int NMT, bool WEIGHTS_A>
+// SRC_ROW = elements per pixel row of the source tile, DST_P = lanes per destination row (pixel
+// m sits at row m / DST_P, column m % DST_P; columns >= DST_W are padding), NP = destination
+// lane slots, NMT = row tiles.  WEIGHTS_A: weights are MFMA operand A (accumulator rows =
+// channels, cols = pixels), else operand B.
+template <int SRC_ROW, int DST_P, int DST_W, int NP, int NMT, bool WEIGHTS_A>
 struct ConvStage {
     static constexpr int LD = 72;
     static constexpr int NJ = 2 * NMT;                  // jobs
@@ -64,10 +76,11 @@ struct ConvStage {
         for (int i = 0; i < J; ++i) {
             int m = tile(i, wave) * 32 + j;
             if (m >= NP) m = 0;
-            off[i] = ((m / DST_W) * SRC_W + (m % DST_W)) * LD + 8 * h;
+            const int px = (m % DST_P) < DST_W ? m % DST_P : 0;      // padding lanes read a valid pixel
+            off[i] = (m / DST_P) * SRC_ROW + px * LD + 8 * h;
             const int row = nt(i, wave) * 32 + j;
             wrow[i] = row * LD;
-            wsw[i] = (row >> 4) & 3;
+            wsw[i] = (row >> 5) & 1;     // constant over the 32 rows of a fragment read (those must stay 144 bytes apart)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
         }
@@ -77,7 +90,7 @@ struct ConvStage {
     // step = tap * 2 + (k-step within this wave's half of the input channels)
     __device__ __forceinline__ Frag fetch(const bf16_t* src, const bf16_t* ws, int step, int i, int h, int kh) const {
         const int tap = step >> 1, ks = 2 * kh + (step & 1);
-        const int shift = ((tap / 3) * SRC_W + tap % 3) * LD;
+        const int shift = (tap / 3) * SRC_ROW + (tap % 3) * LD;
         Frag f;
         f.w = ld_bf16x8(ws + tap * 64 * LD + wrow[i] + (((ks * 2 + h) ^ wsw[i]) << 3));
         f.x = ld_bf16x8(src + off[i] + shift + ks * 16);
@@ -137,10 +150,11 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
     int H, int W, int tiles_h, int tiles_w, int residual) {
     typedef ChainGeom<TH, TW> G;
     constexpr int C = G::C, LD = G::LD, XW = G::XW, R1W = G::R1W, P1 = G::P1, P2 = G::P2;
+    constexpr int XROW = G::XROW, TROW = G::TROW, P2W = G::P2W;
     extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t* Xs = reinterpret_cast<bf16_t*>(smem);      // [XH*XW][LD]
-    bf16_t* Ts = Xs + G::XH * XW * LD;                 // [P1][LD]
-    bf16_t* Ws = Ts + P1 * LD;                         // [9][64][LD]  (tap, out channel, in channel)
+    bf16_t* Xs = reinterpret_cast<bf16_t*>(smem);      // [XH][XROW]: pixel (r, x) at r * XROW + x * LD
+    bf16_t* Ts = Xs + G::XH * XROW;                    // [R1H][TROW]
+    bf16_t* Ws = Ts + G::R1H * TROW;                   // [9][64][LD]  (tap, out channel, in channel)
     float* Bias = reinterpret_cast<float*>(Ws + 9 * 64 * LD);   // ba[64], bb[64] (0 when absent)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -175,12 +189,24 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
             const int u = tid + 1024 * i;
             if (u >= 9 * 128) continue;
             const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
-            uint4 t[4];
-            transpose_8x4(rw[i], t);
+            // Transpose the [8 in][4 out] block one output channel at a time.  In store t lane nq writes
+            // output channel 4 nq + ((t + nq + nq / 4) & 3): with that rotation (and the row >> 5 swizzle)
+            // the 16-byte stores of a wave, whose rows are 4 apart, are bank-conflict free.
+            const int rot = nq + (nq >> 2);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int t = 0; t < 4; ++t) {
+                const int q = (t + rot) & 3;
+                const bool hi_word = q & 2;
+                const int sh = (q & 1) << 4;
+                uint32_t v[4];
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const uint32_t e = hi_word ? rw[i][2 * m].y : rw[i][2 * m].x;
+                    const uint32_t d = hi_word ? rw[i][2 * m + 1].y : rw[i][2 * m + 1].x;
+                    v[m] = ((e >> sh) & 0xffffu) | ((d >> sh) << 16);
+                }
                 const int o = nq * 4 + q;
-                st_u4(Ws + (tap * 64 + o) * LD + ((ko ^ ((o >> 4) & 3)) << 3), t[q]);
+                st_u4(Ws + (tap * 64 + o) * LD + ((ko ^ ((o >> 5) & 1)) << 3), make_uint4(v[0], v[1], v[2], v[3]));
             }
         }
     };
@@ -192,7 +218,7 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
         const int ih = oh0 - 2 + pix / XW, iw = ow0 - 2 + pix % XW;
         uint4 v = make_uint4(0, 0, 0, 0);
         if (ih >= 0 && ih < H && iw >= 0 && iw < W) v = ld_u4(X + ((long)ih * W + iw) * C + kc * 8);
-        st_u4(Xs + pix * LD + kc * 8, v);
+        st_u4(Xs + (pix / XW) * XROW + (pix % XW) * LD + kc * 8, v);
     }
     store_w();
     __syncthreads();
@@ -200,7 +226,7 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
 
     // ---- conv1: rows = output channels (weights are operand A), cols = region pixels --------
     {
-        ConvStage<XW, R1W, P1, G::NMT1, true> st;
+        ConvStage<XROW, R1W, R1W, P1, G::NMT1, true> st;
         st.init(wj, j, h);
         st.run(Xs, Ws, wj, h, kh);
         __syncthreads();                       // Wa is dead: its LDS area becomes reduction scratch
@@ -224,7 +250,7 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
                     v = make_uint2(pack_bf16(fmaxf(st.acc[i][4 * g] + bv.x, 0.f), fmaxf(st.acc[i][4 * g + 1] + bv.y, 0.f)),
                                    pack_bf16(fmaxf(st.acc[i][4 * g + 2] + bv.z, 0.f), fmaxf(st.acc[i][4 * g + 3] + bv.w, 0.f)));
                 }
-                *reinterpret_cast<uint2*>(Ts + m * LD + o) = v;
+                *reinterpret_cast<uint2*>(Ts + (m / R1W) * TROW + (m % R1W) * LD + o) = v;
             }
         }
     }
@@ -234,7 +260,7 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
 
     // ---- conv2: rows = output channels, cols = output pixels --------------------------------
     {
-        ConvStage<R1W, TW, P2, G::NMT2, true> st;
+        ConvStage<TROW, P2W, TW, P2, G::NMT2, true> st;
         st.init(wj, j, h);
         st.run(Ts, Ws, wj, h, kh);
         __syncthreads();
@@ -246,9 +272,9 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
         for (int i = 0; i < st.J; ++i) {
             if (kh != 0 || !st.live(i, wj)) continue;
             const int m = st.tile(i, wj) * 32 + j, ot = st.nt(i, wj);
-            const int py = m / TW, px = m % TW;
+            const int py = m / P2W, px = m % P2W;
             const int y = oh0 + py, x = ow0 + px;
-            if (m >= P2 || y >= H || x >= W) continue;
+            if (m >= P2 || px >= TW || y >= H || x >= W) continue;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int o = ot * 32 + 8 * g + 4 * h;
@@ -256,7 +282,7 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
                 const float4 bv = *reinterpret_cast<const float4*>(Bias + 64 + o);
                 v.x += bv.x; v.y += bv.y; v.z += bv.z; v.w += bv.w;
                 if (residual) {
-                    const uint2 xr = *reinterpret_cast<const uint2*>(Xs + ((py + 2) * XW + px + 2) * LD + o);
+                    const uint2 xr = *reinterpret_cast<const uint2*>(Xs + (py + 2) * XROW + (px + 2) * LD + o);
                     v.x += lo_bf16(xr.x); v.y += hi_bf16(xr.x); v.z += lo_bf16(xr.y); v.w += hi_bf16(xr.y);
                 }
                 *reinterpret_cast<uint2*>(Y + ((long)y * W + x) * C + o) =
