@@ -154,6 +154,31 @@ def main():
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) * 1e3 / iters
 
+        # cold timing: evict the L2s and the 256 MB Infinity Cache with a 2 x 768 MiB copy before every
+        # launch, then time that one launch with an event pair (minus what an empty pair reads)
+        flush_n = 768 * 1024 * 1024 // 4
+        flush_src = torch.ones(flush_n, dtype=torch.float32, device="cuda")
+        flush_dst = torch.empty_like(flush_src)
+
+        def cold_us(fn, iters=12, flush=True):
+            tot, best = 0.0, 1e30
+            for _ in range(iters):
+                if flush:
+                    ago.ago_scale(flush_src, flush_dst, 1.0)
+                else:
+                    torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn()
+                e1.record()
+                torch.cuda.synchronize()
+                us = (e0.elapsed_time(e1) - ev_overhead_ms) * 1e3
+                tot += us
+                best = min(best, us)
+            return tot / iters, best
+
+        fused_ops = {"InvresCase": ago.OP_FUSED_INVRES, "ChainCase": ago.OP_FUSED_CONV_CHAIN,
+                     "FfnCase": ago.OP_FUSED_FFN, "AttnCase": ago.OP_FUSED_ATTN}
         for (c, t, y, ws) in state:
             wsu = runner.alloc_workspace(c, fused=False)
             yu = runner.alloc_output(c)
@@ -161,6 +186,18 @@ def main():
             fused_us = time_us(runner.prepare_fused(c, t, y, ws), args.detail_iters) if "fused" in variants else float("nan")
             u1_us = time_us(runner.prepare_unfused(c, t, yu, wsu, 0), args.detail_iters) if "u1" in variants else float("nan")
             u2_us = time_us(runner.prepare_unfused(c, t, yu, wsu, 1), args.detail_iters) if "u2" in variants else float("nan")
+            launch = runner.prepare_fused(c, t, y, ws)
+            cold_avg, cold_min = cold_us(launch)
+            warm_avg, _ = cold_us(launch, flush=False)       # same single-launch method, caches warm
+            # launch floors: an empty kernel with the fused kernel's grid and workgroup size, and a plain
+            # copy kernel moving the configuration's algorithmic bytes (half read, half written)
+            grid, block = ago.profile_last_launch(fused_ops[type(c).__name__])
+            stream = torch.cuda.current_stream().cuda_stream
+            empty_us = time_us(lambda: ago.lib.ago_bench_empty_kernel(grid, block, stream), args.detail_iters)
+            n_copy = max(8, c.alg_bytes() // 8 // 8 * 8)
+            cp_src = torch.ones(n_copy, dtype=torch.float32, device="cuda")
+            cp_dst = torch.empty_like(cp_src)
+            copy_us = time_us(ago.prepare(ago.ago_scale, cp_src, cp_dst, 1.0), args.detail_iters)
             tf = c.flops() / (fused_us * 1e-6) / 1e12
             peak = PEAK_F32_TFLOPS if c.dtype == "f32" else PEAK_BF16_TFLOPS
             t_mfma = c.flops() / (peak * 1e12)
@@ -171,6 +208,11 @@ def main():
                 "unfused_per_op_us": round(u1_us, 2), "unfused_epilogue_us": round(u2_us, 2),
                 "tflops": round(tf, 3), "gbs": round(c.alg_bytes() / (fused_us * 1e-6) / 1e9, 1),
                 "bound": bound, "roofline_frac": round(max(t_mfma, t_hbm) / (fused_us * 1e-6), 4),
+                "fused_single_launch_warm_us": round(warm_avg, 2),
+                "fused_cold_us": round(cold_avg, 2), "fused_cold_min_us": round(cold_min, 2),
+                "roofline_frac_cold": round(max(t_mfma, t_hbm) / (cold_avg * 1e-6), 4),
+                "launch": {"grid": grid, "block": block},
+                "floor_empty_kernel_us": round(empty_us, 2), "floor_copy_kernel_us": round(copy_us, 2),
                 "speedup_vs_per_op": round(u1_us / fused_us, 2),
                 "speedup_vs_epilogue": round(u2_us / fused_us, 2),
             })

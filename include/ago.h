@@ -210,6 +210,13 @@ int ago_profile_read(ago_op op, float* total_ms, int* count);
  * `hip_stream` with nothing between them: the fixed cost an event pair adds to what it brackets.
  * Synchronises on the events.  Returns a negative value on misuse / a HIP error. */
 float ago_profile_event_overhead_ms(void* hip_stream, int pairs);
+/* Launch floors for the latency-bound configurations.  ago_profile_last_launch writes the grid and
+ * workgroup size (in workgroups / threads) that the dominant kernel of fused entry point `op` was
+ * last launched with (-1 if it has not run yet); ago_bench_empty_kernel enqueues a kernel that does
+ * nothing with that shape on `hip_stream`, so a benchmark can report what launching alone costs.
+ * Both return 0, or -1 on misuse / a HIP error. */
+int ago_profile_last_launch(ago_op op, int* grid, int* block);
+int ago_bench_empty_kernel(int grid, int block, void* hip_stream);
 
 /* Redundancy model of Sec. III-B: number of times the upstream reduction body runs
  * when a conv R1xC1 (I -> O1) is fused under a downstream conv R2xC2 (O1 -> O2) whose

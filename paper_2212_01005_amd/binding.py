@@ -70,13 +70,18 @@ lib.ago_profile_select.argtypes = [ctypes.c_uint]
 lib.ago_profile_select.restype = _i
 lib.ago_profile_read.argtypes = [_i, ctypes.POINTER(_f), ctypes.POINTER(_i)]
 lib.ago_profile_read.restype = _i
+lib.ago_profile_last_launch.argtypes = [_i, ctypes.POINTER(_i), ctypes.POINTER(_i)]
+lib.ago_profile_last_launch.restype = _i
+lib.ago_bench_empty_kernel.argtypes = [_i, _i, _vp]
+lib.ago_bench_empty_kernel.restype = _i
 lib.ago_profile_event_overhead_ms.argtypes = [_vp, _i]
 lib.ago_profile_event_overhead_ms.restype = _f
 
 EXPORTED = sorted(list(_SIGS) + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
                                  "ago_num_tile_configs", "ago_fused_upstream_iterations",
                                  "ago_profile_enable", "ago_profile_select", "ago_profile_read",
-                                 "ago_profile_event_overhead_ms"])
+                                 "ago_profile_event_overhead_ms", "ago_profile_last_launch",
+                                 "ago_bench_empty_kernel"])
 
 
 class AgoError(RuntimeError):
@@ -139,6 +144,19 @@ def profile_read(op):
     if lib.ago_profile_read(op, ctypes.byref(ms), ctypes.byref(n)) != 0:
         raise RuntimeError("ago_profile_read failed")
     return float(ms.value), int(n.value)
+
+
+def profile_last_launch(op):
+    """(grid, block) of the last launch of a fused entry point's dominant kernel."""
+    g, b = _i(0), _i(0)
+    if lib.ago_profile_last_launch(op, ctypes.byref(g), ctypes.byref(b)) != 0:
+        raise RuntimeError("ago_profile_last_launch: the entry point has not run yet")
+    return int(g.value), int(b.value)
+
+
+def bench_empty_kernel(grid, block):
+    if lib.ago_bench_empty_kernel(int(grid), int(block), _stream()) != 0:
+        raise RuntimeError("ago_bench_empty_kernel failed")
 
 
 def profile_event_overhead_ms(pairs=64):

@@ -22,6 +22,8 @@ struct ProfRing {
 ProfRing g_prof[4];
 int g_prof_cap = 0;
 unsigned g_prof_mask = 0xFu;      // bit op: that fused entry point records events
+unsigned g_last_grid[4] = {0, 0, 0, 0}, g_last_block[4] = {0, 0, 0, 0};
+__global__ void empty_kernel() {}
 }  // namespace
 
 namespace ago {
@@ -34,9 +36,22 @@ void prof_stop(int op, hipStream_t s) {
         ++g_prof[op].calls;
     }
 }
+void prof_shape(int op, unsigned grid, unsigned block) { g_last_grid[op] = grid; g_last_block[op] = block; }
 }  // namespace ago
 
 extern "C" {
+
+int ago_profile_last_launch(ago_op op, int* grid, int* block) {
+    if ((int)op < 0 || (int)op > 3 || !grid || !block || g_last_block[(int)op] == 0) return -1;
+    *grid = (int)g_last_grid[(int)op]; *block = (int)g_last_block[(int)op];
+    return 0;
+}
+
+int ago_bench_empty_kernel(int grid, int block, void* hip_stream) {
+    if (grid <= 0 || block <= 0 || block > 1024) return -1;
+    hipLaunchKernelGGL(empty_kernel, dim3((unsigned)grid), dim3((unsigned)block), 0, reinterpret_cast<hipStream_t>(hip_stream));
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
 
 int ago_profile_enable(int capacity) {
     for (auto& r : g_prof) {

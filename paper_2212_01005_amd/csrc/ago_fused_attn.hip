@@ -260,6 +260,7 @@ static hipError_t launch_attn(const void* q, const void* k, const void* v, void*
     const int heads = B * Hh, qblocks = (S + 32 * NQT - 1) / (32 * NQT);
     dim3 grid((unsigned)(8 * qblocks * ((heads + 7) / 8)));
     prof_start(3, s);
+    prof_shape(3, grid.x, (2 * NQT + 2) * 64);
     hipLaunchKernelGGL(kern, grid, dim3((2 * NQT + 2) * 64), smem, s, (const bf16_t*)q, (const bf16_t*)k,
                        (const bf16_t*)v, (bf16_t*)o, S, heads, qblocks, scale * 1.4426950408889634f);
     prof_stop(3, s);

@@ -308,6 +308,7 @@ static hipError_t launch_chain(const void* x, const void* wa, const float* ba, c
     }
     const int tiles_h = (H + TH - 1) / TH, tiles_w = (W + TW - 1) / TW;
     prof_start(1, s);
+    prof_shape(1, (unsigned)(N * tiles_h * tiles_w), 1024);
     hipLaunchKernelGGL(kern, dim3((unsigned)(N * tiles_h * tiles_w)), dim3(1024), smem, s,
                        (const bf16_t*)x, (const bf16_t*)wa, ba, (const bf16_t*)wb, bb, (bf16_t*)y,
                        H, W, tiles_h, tiles_w, residual);

@@ -388,6 +388,7 @@ hipError_t fused_ffn_stream(const void* x, const void* w1, const float* b1, cons
     const int nsplit = F / FS;
     dim3 grid(nsplit, (M + BM - 1) / BM);
     prof_start(2, s);
+    prof_shape(2, grid.x * grid.y, kStreamThreads);
     hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), kStreamSmem, s, (const bf16_t*)x, (const bf16_t*)w1, b1,
                        (const bf16_t*)w2, b2, (bf16_t*)y, (float*)workspace, M, K, F, K2, act);
     prof_stop(2, s);

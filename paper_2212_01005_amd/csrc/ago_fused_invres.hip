@@ -363,6 +363,7 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
             attr_set = true;                                                                            \
         }                                                                                               \
         prof_start(0, s);                                                                               \
+        prof_shape(0, grid, kInvresThreads);                                                            \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(kInvresThreads), smem, s, p);                                    \
         prof_stop(0, s);                                                                                \
     } while (0)

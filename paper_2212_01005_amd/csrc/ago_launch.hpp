@@ -44,6 +44,7 @@ hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int 
 // of a fused entry point.  No-ops unless profiling is enabled.
 void prof_start(int op, hipStream_t s);
 void prof_stop(int op, hipStream_t s);
+void prof_shape(int op, unsigned grid, unsigned block);   // remembers the launch shape of the dominant kernel
 
 // tile-configuration tables (host only)
 int fused_invres_num_cfgs();

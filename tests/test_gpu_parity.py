@@ -107,7 +107,7 @@ def test_every_tile_config_gives_the_same_answer(gpu, oracle):
     picks = {"InvresCase": [c for c in _cases() if c.name in ("invres_f32_s1", "invres_bf16_s2")],
              "ChainCase": [c for c in _cases() if c.name == "chain_ragged"],
              "FfnCase": [c for c in _cases() if c.name == "ffn_ragged_rows"],
-             "AttnCase": [c for c in _cases() if c.name in ("attn_s384", "attn_ragged_s100")]}
+             "AttnCase": [c for c in _cases() if c.name in ("attn_s384", "attn_ragged_s100", "attn_long_s600")]}
     ops = {"InvresCase": ago.OP_FUSED_INVRES, "ChainCase": ago.OP_FUSED_CONV_CHAIN, "FfnCase": ago.OP_FUSED_FFN,
            "AttnCase": ago.OP_FUSED_ATTN}
     try:

@@ -191,4 +191,5 @@ def small_cases():
         FfnCase(130, 64, 768, 768, "bf16", s + 192, name="ffn_two_k_tiles"),
         AttnCase(1, 2, 384, 64, 0.125, "bf16", s + 144, name="attn_s384"),
         AttnCase(2, 3, 100, 64, 0.125, "bf16", s + 160, name="attn_ragged_s100"),
+        AttnCase(1, 3, 600, 64, 0.125, "bf16", s + 208, name="attn_long_s600"),
     ]
