@@ -228,6 +228,21 @@ def main():
                 "speedup_vs_epilogue": round(u2_us / fused_us, 2),
             })
 
+    # ---- the two-operator pairs (not part of the step): fused vs operator by operator --------------
+    pairs = []
+    if not args.no_detail and args.only < 0:
+        for c in wl.pair_cases():
+            if "ragged" in c.name:
+                continue
+            t = runner.to_device(c)
+            y, ws = runner.alloc_output(c), runner.alloc_workspace(c, fused=True)
+            scratch = runner.alloc_pair_scratch(c)
+            f_us = time_us(runner.prepare_fused(c, t, y, ws), args.detail_iters)
+            u_us = time_us(runner.prepare_pair_unfused(c, t, y, scratch), args.detail_iters)
+            pairs.append({"name": c.name, "fused_us": round(f_us, 2), "unfused_epilogue_us": round(u_us, 2),
+                          "speedup": round(u_us / f_us, 2),
+                          "tflops": round(c.flops() / (f_us * 1e-6) / 1e12, 3)})
+
     # ---- CPU baseline: the oracle as it stands, on the host cores ---------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -258,7 +273,7 @@ def main():
                    "configs": [c.name for c in cases],
                    "tile_config": tile_cfg or "built-in",
                    "note": "config 0 is fp32 storage, configs 1-4 bf16 storage with fp32 accumulation"},
-        "roofline": roofline, "cpu_baseline": cpu, "per_config": per_config,
+        "roofline": roofline, "cpu_baseline": cpu, "per_config": per_config, "pairs": pairs,
         "fused_kernel_us": {str(k): round(v * 1e3, 2) for k, v in kernel_ms.items()},
     }
     print(json.dumps(out))

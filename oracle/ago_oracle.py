@@ -195,10 +195,53 @@ def attn(q, k, v, scale_=0.125):
     return o
 
 
+# ---- two-operator pairs (Sec. VI, Fig. 13): the operators above called one after another --------
+
+def pw_dw(x, w1, b1, wd, bd, stride=1):
+    """relu6(dw3x3(relu6(x * w1 + b1)) + bd); the padding of the depthwise pads the activated tensor."""
+    e = conv1x1(x, w1)
+    if b1 is not None:
+        e = bias(e, b1)
+    e = relu6(e)
+    d = dwconv3x3(e, wd, stride)
+    if bd is not None:
+        d = bias(d, bd)
+    return relu6(d)
+
+
+def dw_pw(x, wd, bd, w2, b2, stride=1):
+    """relu6(dw3x3(x) + bd) * w2 + b2."""
+    d = dwconv3x3(x, wd, stride)
+    if bd is not None:
+        d = bias(d, bd)
+    y = conv1x1(relu6(d), w2)
+    if b2 is not None:
+        y = bias(y, b2)
+    return y
+
+
+def pw_pw(x, w1, b1, w2, b2, act="relu"):
+    """act(x * w1 + b1) * w2 + b2 on an NHWC tensor."""
+    h = conv1x1(x, w1)
+    if b1 is not None:
+        h = bias(h, b1)
+    h = {"none": lambda v: v, "relu": relu, "relu6": relu6, "gelu_tanh": gelu_tanh}[act](h)
+    y = conv1x1(h, w2)
+    if b2 is not None:
+        y = bias(y, b2)
+    return y
+
+
 def run_case(case):
     """Evaluate a workloads.*Case on the oracle; returns the fp64 output."""
     t = case.tensors()
     kind = type(case).__name__
+    if kind == "PairCase":
+        if case.kind == "pw_dw":
+            return pw_dw(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], case.stride)
+        if case.kind == "dw_pw":
+            return dw_pw(t["x"], t["wd"], t["bd"], t["w2"], t["b2"], case.stride)
+        return pw_pw(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], case.act)
     if kind == "InvresCase":
         return invres(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"],
                       case.stride, case.residual)

@@ -25,6 +25,7 @@ F32, BF16 = 0, 1
 ACT_NONE, ACT_RELU, ACT_RELU6, ACT_GELU_TANH = 0, 1, 2, 3
 OP_FUSED_INVRES, OP_FUSED_CONV_CHAIN, OP_FUSED_FFN, OP_FUSED_ATTN = 0, 1, 2, 3
 OP_UNFUSED_INVRES, OP_UNFUSED_CONV_CHAIN, OP_UNFUSED_FFN, OP_UNFUSED_ATTN = 4, 5, 6, 7
+OP_FUSED_PW_DW, OP_FUSED_DW_PW, OP_FUSED_PW_PW = 8, 9, 10
 
 _vp, _i, _l, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float, ctypes.c_size_t
 
@@ -33,6 +34,9 @@ _SIGS = {
     "ago_fused_conv_chain": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_ffn": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_attn": [_vp] * 4 + [_i] * 4 + [_f, _i, _vp, _sz, _vp],
+    "ago_fused_pw_dw": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
+    "ago_fused_dw_pw": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
+    "ago_fused_pw_pw": [_vp] * 6 + [_i] * 8 + [_vp, _sz, _vp],
     "ago_gemm": [_vp] * 5 + [_i] * 5 + [_vp],
     "ago_conv1x1": [_vp] * 5 + [_i] * 7 + [_vp],
     "ago_dwconv3x3": [_vp] * 4 + [_i] * 7 + [_vp],
@@ -230,6 +234,33 @@ def ago_fused_attn(q, k, v, o, scale, workspace=None):
     B, Hh, S, D = q.shape
     wp, wb = _ws(workspace)
     return lib.ago_fused_attn, (_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q), wp, wb, _stream())
+
+
+@_entry
+def ago_fused_pw_dw(x, w1, b1, wd, bd, y, stride, workspace=None):
+    N, H, W, Cin = x.shape
+    Cexp = w1.shape[1]
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_pw_dw, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(y), N, H, W, Cin, Cexp, stride,
+                                 _dt(x), wp, wb, _stream())
+
+
+@_entry
+def ago_fused_dw_pw(x, wd, bd, w2, b2, y, stride, workspace=None):
+    N, H, W, C = x.shape
+    Cout = w2.shape[1]
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_dw_pw, (_p(x), _p(wd), _p(bd), _p(w2), _p(b2), _p(y), N, H, W, C, Cout, stride,
+                                 _dt(x), wp, wb, _stream())
+
+
+@_entry
+def ago_fused_pw_pw(x, w1, b1, w2, b2, y, act=ACT_RELU, workspace=None):
+    N, H, W, Cin = x.shape
+    Cmid, Cout = w2.shape
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_pw_pw, (_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), N, H, W, Cin, Cmid, Cout, act,
+                                 _dt(x), wp, wb, _stream())
 
 
 # ---- un-fused operators ---------------------------------------------------------------

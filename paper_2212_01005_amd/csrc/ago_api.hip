@@ -127,6 +127,36 @@ ago_status ago_fused_invres(const void* x, const void* w1, const float* b1, cons
                                  as_stream(hip_stream)));
 }
 
+ago_status ago_fused_pw_dw(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
+                           void* y, int N, int H, int W, int Cin, int Cexp, int stride, ago_dtype dt,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    ago_status st = check_pw_dw(x, w1, wd, y, b1, bd, N, H, W, Cin, Cexp, stride, dt);
+    if (st != AGO_OK) return st;
+    return from_hip(fused_invres(x, w1, b1, wd, bd, nullptr, nullptr, y, N, H, W, Cin, Cexp, 16, stride, 0,
+                                 dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES), as_stream(hip_stream), 1));
+}
+
+ago_status ago_fused_dw_pw(const void* x, const void* wd, const float* bd, const void* w2, const float* b2,
+                           void* y, int N, int H, int W, int C, int Cout, int stride, ago_dtype dt,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    ago_status st = check_dw_pw(x, wd, w2, y, bd, b2, N, H, W, C, Cout, stride, dt);
+    if (st != AGO_OK) return st;
+    return from_hip(fused_invres(x, nullptr, nullptr, wd, bd, w2, b2, y, N, H, W, 8, C, Cout, stride, 0,
+                                 dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES), as_stream(hip_stream), 2));
+}
+
+ago_status ago_fused_pw_pw(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
+                           void* y, int N, int H, int W, int Cin, int Cmid, int Cout, ago_act act,
+                           ago_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (N <= 0 || H <= 0 || W <= 0) return x && w1 && w2 && y ? AGO_ERR_SHAPE : AGO_ERR_NULL;
+    const long long m = (long long)N * H * W;
+    if (m >= (1LL << 31)) return AGO_ERR_UNSUPPORTED;
+    return ago_fused_ffn(x, w1, b1, w2, b2, y, (int)m, Cin, Cmid, Cout, act, dt, workspace, workspace_bytes,
+                         hip_stream);
+}
+
 ago_status ago_fused_conv_chain(const void* x, const void* wa, const float* ba, const void* wb,
                                 const float* bb, void* y, int N, int H, int W, int C, int residual,
                                 ago_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream) {

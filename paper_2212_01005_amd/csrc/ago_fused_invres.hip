@@ -11,6 +11,11 @@
 //   2  D = relu6(dw3x3(E) + bd) on the vector ALUs
 //   3  Y = D W2 + b2 (+ X) on the matrix cores, stored straight to global memory
 // Matrix instructions: 16x16x32 bf16 / 16x16x4 fp32 (small tiles: few pixels per workgroup).
+//
+// The same kernel runs the two-operator pairs of the block (the paper's Fig. 13 micro-benchmarks):
+//   mode 1  pw -> dw: stages 0-2, D is stored to global memory instead of LDS
+//   mode 2  dw -> pw: the input *is* E (stage 0 loads its halo tile into the E region, zero outside
+//           the image), stages 2-3 follow
 #include "ago_dev.hpp"
 #include "ago_launch.hpp"
 
@@ -28,6 +33,7 @@ struct InvresParams {
     int ldx, ldw1, lde, ldd, ldw2;  // LDS leading dimensions (elements)
     int off_w1, off_e, off_d, off_w2, off_wd, off_b;  // LDS byte offsets (Xs at 0)
     int ksplit;                     // stage 3: waves per (pixel tile, channel tile) job, splitting k
+    int mode;                       // 0: pw -> dw -> pw   1: pw -> dw   2: dw -> pw
 };
 
 template <bool BF16> struct InT { typedef float type; };
@@ -60,7 +66,26 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
 
     // ---- stage 0: stage inputs and weights ------------------------------------------
     constexpr int VE = BF16 ? 8 : 4;   // elements per 16-byte chunk
-    {
+    if (p.mode == 2) {
+        // the input has Cexp channels and is the depthwise operand itself: fp32 into the E region
+        const T* Xe = reinterpret_cast<const T*>(p.x) + (long)n * p.H * p.W * p.Cexp;
+        const int q4 = p.Cexp / 4;
+        for (int it = tid; it < p.PE * q4; it += kInvresThreads) {
+            const int pix = it / q4, q = it % q4;
+            const int ih = ih0 + pix / p.EW, iw = iw0 + pix % p.EW;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W) {
+                const T* src = Xe + ((long)ih * p.W + iw) * p.Cexp + 4 * q;
+                if constexpr (BF16) {
+                    const uint2 u = *reinterpret_cast<const uint2*>(src);
+                    v = make_float4(lo_bf16(u.x), hi_bf16(u.x), lo_bf16(u.y), hi_bf16(u.y));
+                } else {
+                    v = *reinterpret_cast<const float4*>(src);
+                }
+            }
+            *reinterpret_cast<float4*>(Es + pix * p.lde + 4 * q) = v;
+        }
+    } else {
         const int kch = p.KP1 / VE;
         for (int it = tid; it < p.PEpad * kch; it += kInvresThreads) {
             const int pix = it / kch, kc = it % kch;
@@ -82,7 +107,7 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
     if constexpr (BF16) {
         // W1 [Cin][Cexp] -> W1s[e][k], W2 [Cexp][Cout] -> W2s[co][k]; k beyond the real extent = 0
         const bf16_t* W1 = reinterpret_cast<const bf16_t*>(p.w1);
-        const int nq1 = p.Cexp / 4;
+        const int nq1 = p.mode == 2 ? 0 : p.Cexp / 4;
         for (int it = tid; it < (p.KP1 / 8) * nq1; it += kInvresThreads) {
             const int nq = it % nq1, ko = it / nq1;
             uint2 r[8];
@@ -97,7 +122,7 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
             for (int q = 0; q < 4; ++q) st_u4(W1s + (nq * 4 + q) * p.ldw1 + ko * 8, t[q]);
         }
         const bf16_t* W2 = reinterpret_cast<const bf16_t*>(p.w2);
-        const int nq2 = p.CoutP / 4;
+        const int nq2 = p.mode == 1 ? 0 : p.CoutP / 4;
         for (int it = tid; it < (p.KP2 / 8) * nq2; it += kInvresThreads) {
             const int nq = it % nq2, ko = it / nq2;
             uint2 r[8];
@@ -118,14 +143,14 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
     } else {
         // fp32: weights keep their [k][n] layout (the fp32 matrix instruction reads one k per lane)
         const float* W1 = reinterpret_cast<const float*>(p.w1);
-        const int c4 = p.Cexp / 4;
+        const int c4 = p.mode == 2 ? 0 : p.Cexp / 4;
         for (int it = tid; it < p.KP1 * c4; it += kInvresThreads) {
             const int k = it / c4, q = it % c4;
             const uint4 v = k < p.Cin ? ld_u4(W1 + (long)k * p.Cexp + q * 4) : make_uint4(0, 0, 0, 0);
             st_u4(W1s + k * p.ldw1 + q * 4, v);
         }
         const float* W2 = reinterpret_cast<const float*>(p.w2);
-        const int o4 = p.CoutP / 4;
+        const int o4 = p.mode == 1 ? 0 : p.CoutP / 4;
         for (int it = tid; it < p.KP2 * o4; it += kInvresThreads) {
             const int k = it / o4, q = it % o4;
             const uint4 v = (k < p.Cexp && q * 4 < p.Cout) ? ld_u4(W2 + (long)k * p.Cout + q * 4)
@@ -138,7 +163,7 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
     __syncthreads();
 
     // ---- stage 1: expand.  acc rows = channels, cols = pixels (weights are operand A) ---
-    {
+    if (p.mode != 2) {
         const int i = lane & 15, g = lane >> 4;
         const int ptiles = p.PEpad / 16, ctiles = p.Cexp / 16;
         for (int job = wave; job < ptiles * ctiles; job += kInvresThreads / 64) {
@@ -199,13 +224,20 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
                 a.x = apply_act<kRelu6>(a.x + bv.x); a.y = apply_act<kRelu6>(a.y + bv.y);
                 a.z = apply_act<kRelu6>(a.z + bv.z); a.w = apply_act<kRelu6>(a.w + bv.w);
             }
+            T* dst = Ds + po * p.ldd + 4 * q;
+            if (p.mode == 1) {                 // pw -> dw: D is the result
+                const int oh = oh0 + po / p.TOW, ow = ow0 + po % p.TOW;
+                if (q >= Qr || oh >= p.OH || ow >= p.OW) continue;
+                dst = reinterpret_cast<T*>(p.y) + (((long)n * p.OH + oh) * p.OW + ow) * p.Cexp + 4 * q;
+            }
             if constexpr (BF16) {
-                *reinterpret_cast<uint2*>(Ds + po * p.ldd + 4 * q) = make_uint2(pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));
+                *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));
             } else {
-                *reinterpret_cast<float4*>(Ds + po * p.ldd + 4 * q) = a;
+                *reinterpret_cast<float4*>(dst) = a;
             }
         }
     }
+    if (p.mode == 1) return;
     __syncthreads();
 
     // ---- stage 3: project.  acc rows = pixels, cols = output channels -------------------
@@ -324,8 +356,9 @@ int fused_invres_num_cfgs() { return (int)(sizeof(kTileCand) / sizeof(kTileCand[
 hipError_t fused_invres(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
                         const void* w2, const float* b2, void* y, int N, int H, int W, int Cin,
                         int Cexp, int Cout, int stride, int residual, bool bf16, int tile_cfg,
-                        hipStream_t s) {
+                        hipStream_t s, int mode) {
     InvresParams p;
+    p.mode = mode;
     p.x = x; p.w1 = w1; p.b1 = b1; p.wd = wd; p.bd = bd; p.w2 = w2; p.b2 = b2; p.y = y;
     p.N = N; p.H = H; p.W = W; p.Cin = Cin; p.Cexp = Cexp; p.Cout = Cout;
     p.OH = (H - 1) / stride + 1; p.OW = (W - 1) / stride + 1; p.residual = residual;

@@ -50,6 +50,32 @@ ago_status check_invres(const void* x, const void* w1, const void* wd, const voi
     return AGO_OK;
 }
 
+ago_status check_pw_dw(const void* x, const void* w1, const void* wd, const void* y, const void* b1,
+                       const void* bd, int N, int H, int W, int Cin, int Cexp, int stride, int dt) {
+    if (!x || !w1 || !wd || !y) return AGO_ERR_NULL;
+    if (!valid_dtype(dt)) return AGO_ERR_DTYPE;
+    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cexp <= 0) return AGO_ERR_SHAPE;
+    if (stride != 1 && stride != 2) return AGO_ERR_SHAPE;
+    const void* ps[6] = {x, w1, wd, y, b1, bd};
+    for (const void* p : ps)
+        if (p && !aligned16(p)) return AGO_ERR_ALIGN;
+    if (Cin % 8 || Cexp % 16) return AGO_ERR_UNSUPPORTED;
+    return AGO_OK;
+}
+
+ago_status check_dw_pw(const void* x, const void* wd, const void* w2, const void* y, const void* bd,
+                       const void* b2, int N, int H, int W, int C, int Cout, int stride, int dt) {
+    if (!x || !wd || !w2 || !y) return AGO_ERR_NULL;
+    if (!valid_dtype(dt)) return AGO_ERR_DTYPE;
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || Cout <= 0) return AGO_ERR_SHAPE;
+    if (stride != 1 && stride != 2) return AGO_ERR_SHAPE;
+    const void* ps[6] = {x, wd, w2, y, bd, b2};
+    for (const void* p : ps)
+        if (p && !aligned16(p)) return AGO_ERR_ALIGN;
+    if (C % 16 || Cout % 8) return AGO_ERR_UNSUPPORTED;
+    return AGO_OK;
+}
+
 ago_status check_conv_chain(const void* x, const void* wa, const void* wb, const void* y,
                             const void* ba, const void* bb, int N, int H, int W, int C, int dt) {
     if (!x || !wa || !wb || !y) return AGO_ERR_NULL;
@@ -94,6 +120,14 @@ size_t workspace_bytes(int op, const int* d, int nd, int dt) {
         if (d[i] <= 0) return 0;
     const size_t es = dt == AGO_BF16 ? 2 : 4;
     switch (op) {
+        case AGO_OP_FUSED_PW_PW: {        // dims N, H, W, Cin, Cmid, Cout: the FFN kernel on M = N H W rows
+            if (nd < 6) return 0;
+            const long long m = (long long)d[0] * d[1] * d[2];
+            if (m >= (1LL << 31)) return 0;
+            const int cfg = fused_ffn_pick_cfg((int)m, d[3], d[4], d[5], g_tile_cfg[AGO_OP_FUSED_FFN]);
+            const int ns = fused_ffn_nsplit(cfg, d[4]);
+            return ns > 1 ? (size_t)ns * (size_t)m * d[5] * 4 : 0;
+        }
         case AGO_OP_FUSED_FFN: {
             if (nd < 4) return 0;
             const int cfg = fused_ffn_pick_cfg(d[0], d[1], d[2], d[3], g_tile_cfg[AGO_OP_FUSED_FFN]);

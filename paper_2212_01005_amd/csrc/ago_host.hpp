@@ -13,6 +13,10 @@ ago_status check_invres(const void* x, const void* w1, const void* wd, const voi
                         const void* b1, const void* bd, const void* b2,
                         int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int residual,
                         int dt);
+ago_status check_pw_dw(const void* x, const void* w1, const void* wd, const void* y, const void* b1,
+                       const void* bd, int N, int H, int W, int Cin, int Cexp, int stride, int dt);
+ago_status check_dw_pw(const void* x, const void* wd, const void* w2, const void* y, const void* bd,
+                       const void* b2, int N, int H, int W, int C, int Cout, int stride, int dt);
 ago_status check_conv_chain(const void* x, const void* wa, const void* wb, const void* y,
                             const void* ba, const void* bb, int N, int H, int W, int C, int dt);
 ago_status check_ffn(const void* x, const void* w1, const void* w2, const void* y, const void* b1,

@@ -46,6 +46,8 @@ _FUSED_OP = {"InvresCase": ago.OP_FUSED_INVRES, "ChainCase": ago.OP_FUSED_CONV_C
 def alloc_output(case, device="cuda:0"):
     td = _torch_dtype(case.dtype)
     k = type(case).__name__
+    if k == "PairCase":
+        return torch.empty(case.out_shape(), dtype=td, device=device)
     if k == "InvresCase":
         shape = (case.N, case.OH, case.OW, case.Cout)
     elif k == "ChainCase":
@@ -58,13 +60,27 @@ def alloc_output(case, device="cuda:0"):
 
 
 def alloc_workspace(case, fused=True, device="cuda:0"):
+    if type(case).__name__ == "PairCase":
+        if case.kind != "pw_pw" or not fused:
+            return None
+        n = ago.workspace_bytes(ago.OP_FUSED_PW_PW, [case.N, case.H, case.W, case.C1, case.C2, case.C3], ago.BF16)
+        return torch.empty(max(n, 16), dtype=torch.uint8, device=device) if n > 0 else None
     op = _FUSED_OP[type(case).__name__] + (0 if fused else 4)
     n = ago.workspace_bytes(op, _dims(case), ago.BF16 if case.dtype == "bf16" else ago.F32)
     return torch.empty(max(n, 16), dtype=torch.uint8, device=device) if n > 0 else None
 
 
+_ACT = {"none": ago.ACT_NONE, "relu": ago.ACT_RELU, "relu6": ago.ACT_RELU6, "gelu_tanh": ago.ACT_GELU_TANH}
+
+
 def _fused_call(case, t, y, ws):
     k = type(case).__name__
+    if k == "PairCase":
+        if case.kind == "pw_dw":
+            return ago.ago_fused_pw_dw, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], y, case.stride, ws)
+        if case.kind == "dw_pw":
+            return ago.ago_fused_dw_pw, (t["x"], t["wd"], t["bd"], t["w2"], t["b2"], y, case.stride, ws)
+        return ago.ago_fused_pw_pw, (t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, _ACT[case.act], ws)
     if k == "InvresCase":
         return ago.ago_fused_invres, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
                                       case.stride, case.residual, ws)
@@ -110,6 +126,45 @@ def run_unfused(case, t, y, ws, epilogue_fused):
 def prepare_unfused(case, t, y, ws, epilogue_fused):
     fn, args = _unfused_call(case, t, y, ws, epilogue_fused)
     return ago.prepare(fn, *args)
+
+
+def _pair_unfused_calls(case, t, y, scratch):
+    if case.kind == "pw_dw":
+        return [(ago.ago_conv1x1, (t["x"], t["w1"], t["b1"], None, scratch, ago.ACT_RELU6)),
+                (ago.ago_dwconv3x3, (scratch, t["wd"], t["bd"], y, case.stride, ago.ACT_RELU6))]
+    if case.kind == "dw_pw":
+        return [(ago.ago_dwconv3x3, (t["x"], t["wd"], t["bd"], scratch, case.stride, ago.ACT_RELU6)),
+                (ago.ago_conv1x1, (scratch, t["w2"], t["b2"], None, y, ago.ACT_NONE))]
+    return [(ago.ago_conv1x1, (t["x"], t["w1"], t["b1"], None, scratch, _ACT[case.act])),
+            (ago.ago_conv1x1, (scratch, t["w2"], t["b2"], None, y, ago.ACT_NONE))]
+
+
+def run_pair_unfused(case, t, y, scratch):
+    """The pair operator by operator with epilogue-fused kernels (the conventional-fusion baseline);
+    `scratch` holds the intermediate tensor."""
+    for fn, args in _pair_unfused_calls(case, t, y, scratch):
+        fn(*args)
+    return y
+
+
+def prepare_pair_unfused(case, t, y, scratch):
+    launches = [ago.prepare(fn, *args) for fn, args in _pair_unfused_calls(case, t, y, scratch)]
+
+    def run():
+        for launch in launches:
+            launch()
+    return run
+
+
+def alloc_pair_scratch(case, device="cuda:0"):
+    td = _torch_dtype(case.dtype)
+    if case.kind == "pw_dw":
+        shape = (case.N, case.H, case.W, case.C2)
+    elif case.kind == "dw_pw":
+        shape = (case.N, case.OH, case.OW, case.C1)
+    else:
+        shape = (case.N, case.H, case.W, case.C2)
+    return torch.empty(shape, dtype=td, device=device)
 
 
 def to_numpy64(t):

@@ -50,6 +50,39 @@ def _fake(addr=0x1000):
     return ctypes.c_void_p(addr)
 
 
+def test_pair_entry_points_validate_before_any_gpu_call(lib):
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    p = _fake()
+    lib.ago_fused_pw_dw.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
+    pwdw = lambda N, H, W, Cin, Cexp, st, dt=1, x=p: lib.ago_fused_pw_dw(
+        x, p, None, p, None, p, N, H, W, Cin, Cexp, st, dt, None, 0, None)
+    assert pwdw(1, 8, 8, 16, 96, 1, x=None) == 1
+    assert pwdw(1, 8, 8, 16, 96, 3) == 2                                  # stride
+    assert pwdw(1, 0, 8, 16, 96, 1) == 2
+    assert pwdw(1, 8, 8, 16, 96, 1, dt=5) == 3
+    assert pwdw(1, 8, 8, 16, 96, 1, x=_fake(0x1008)) == 4
+    assert pwdw(1, 8, 8, 12, 96, 1) == 5                                  # Cin % 8
+    assert pwdw(1, 8, 8, 16, 100, 1) == 5                                 # Cexp % 16
+    lib.ago_fused_dw_pw.argtypes = [vp] * 6 + [ci] * 7 + [vp, sz, vp]
+    dwpw = lambda N, H, W, C, Cout, st, dt=1, y=p: lib.ago_fused_dw_pw(
+        p, p, None, p, None, y, N, H, W, C, Cout, st, dt, None, 0, None)
+    assert dwpw(1, 8, 8, 96, 24, 1, y=None) == 1
+    assert dwpw(1, 8, 8, 96, 24, 0) == 2
+    assert dwpw(1, 8, 8, 90, 24, 1) == 5                                  # C % 16
+    assert dwpw(1, 8, 8, 96, 20, 1) == 5                                  # Cout % 8
+    lib.ago_fused_pw_pw.argtypes = [vp] * 6 + [ci] * 8 + [vp, sz, vp]
+    pwpw = lambda N, H, W, C1, C2, C3, act=1, dt=1, ws=None, wsz=0: lib.ago_fused_pw_pw(
+        p, p, None, p, None, p, N, H, W, C1, C2, C3, act, dt, ws, wsz, None)
+    assert pwpw(0, 8, 8, 64, 128, 128) == 2
+    assert pwpw(1, 8, 8, 64, 128, 128, act=11) == 3
+    assert pwpw(1, 8, 8, 60, 128, 128) == 5                               # same divisibility rules as the FFN chain
+    assert pwpw(1, 8, 8, 64, 768, 128) == 6                               # several hidden slices need a workspace
+    from paper_2212_01005_amd import binding as ago
+    # the pair's workspace is the FFN chain's on N*H*W rows
+    assert ago.workspace_bytes(ago.OP_FUSED_PW_PW, [1, 8, 8, 64, 768, 128], ago.BF16) == \
+        ago.workspace_bytes(ago.OP_FUSED_FFN, [64, 64, 768, 128], ago.BF16) > 0
+
+
 def test_validation_runs_before_any_gpu_call(lib):
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.ago_fused_ffn.argtypes = [vp] * 6 + [ci] * 6 + [vp, sz, vp]

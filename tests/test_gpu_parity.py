@@ -132,6 +132,27 @@ def test_every_tile_config_gives_the_same_answer(gpu, oracle):
             ago.set_tile_config(op, -1)
 
 
+# ---- two-operator pairs ------------------------------------------------------------------
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", wl.pair_cases(), ids=lambda c: c.name)
+def test_pair_fused_matches_oracle(gpu, oracle, case):
+    """pw->dw, dw->pw and pw->pw as entry points of their own, element by element against the oracle;
+    the same pair run operator by operator must agree too."""
+    torch, ago, runner = gpu
+    ref = oracle.run_case(case)
+    t = runner.to_device(case)
+    y = runner.alloc_output(case)
+    y.zero_()
+    runner.run_fused(case, t, y, runner.alloc_workspace(case, fused=True))
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(y), ref, case.dtype, case.name)
+    yu = runner.alloc_output(case)
+    runner.run_pair_unfused(case, t, yu, runner.alloc_pair_scratch(case))
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(yu), ref, case.dtype, case.name + " un-fused")
+
+
 # ---- single operators -----------------------------------------------------------------
 
 def _dev(torch, arr, dtype):

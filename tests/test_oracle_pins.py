@@ -422,6 +422,41 @@ def test_subgraphs_equal_op_by_op(oracle):
 # input generator sanity (not part of the method, but both sides rely on it)
 # --------------------------------------------------------------------------
 
+@pytest.mark.parametrize("stride", [1, 2])
+def test_pair_pw_dw_brute(oracle, stride):
+    """pw -> dw pair against the paper's loop nest: pointwise, bias, ReLU6, then a depthwise pass
+    over the zero-padded activated tensor."""
+    x = _tiny(901, (1, 5, 6, 3)); w1 = _tiny(902, (3, 4)); wd = _tiny(903, (3, 3, 4))
+    b1 = _tiny(904, (4,), -0.3, 0.3); bd = _tiny(905, (4,), -0.3, 0.3)
+    e = brute_bias_act(brute_conv_nchw(nhwc_to_lists(x), w1x1_to_oihw(w1), 0, 1), b1.tolist(), "relu6")
+    d = brute_bias_act(brute_conv_nchw(e, wdw_to_oihw(wd), 1, stride, groups_depthwise=True), bd.tolist(), "relu6")
+    np.testing.assert_allclose(oracle.pw_dw(x, w1, b1, wd, bd, stride), lists_to_nhwc(d), rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_pair_dw_pw_brute(oracle, stride):
+    x = _tiny(911, (2, 4, 5, 3)); wd = _tiny(912, (3, 3, 3)); w2 = _tiny(913, (3, 5))
+    bd = _tiny(914, (3,), -0.3, 0.3); b2 = _tiny(915, (5,), -0.3, 0.3)
+    d = brute_bias_act(brute_conv_nchw(nhwc_to_lists(x), wdw_to_oihw(wd), 1, stride, groups_depthwise=True), bd.tolist(), "relu6")
+    y = brute_bias_act(brute_conv_nchw(d, w1x1_to_oihw(w2), 0, 1), b2.tolist(), "none")
+    np.testing.assert_allclose(oracle.dw_pw(x, wd, bd, w2, b2, stride), lists_to_nhwc(y), rtol=1e-12, atol=1e-12)
+
+
+def test_pairs_compose_to_the_block_and_to_the_ffn(oracle):
+    """pw_dw followed by the projection, and the expansion followed by dw_pw, both give the
+    inverted residual; pw_pw on an NHWC tensor is the FFN chain on its rows."""
+    x = _tiny(921, (1, 6, 7, 4)); w1 = _tiny(922, (4, 8)); wd = _tiny(923, (3, 3, 8)); w2 = _tiny(924, (8, 4))
+    b1 = _tiny(925, (8,), -0.2, 0.2); bd = _tiny(926, (8,), -0.2, 0.2); b2 = _tiny(927, (4,), -0.2, 0.2)
+    full = oracle.invres(x, w1, b1, wd, bd, w2, b2, 2, False)
+    via_pw_dw = oracle.bias(oracle.conv1x1(oracle.pw_dw(x, w1, b1, wd, bd, 2), w2), b2)
+    via_dw_pw = oracle.dw_pw(oracle.relu6(oracle.bias(oracle.conv1x1(x, w1), b1)), wd, bd, w2, b2, 2)
+    np.testing.assert_allclose(via_pw_dw, full, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(via_dw_pw, full, rtol=1e-13, atol=1e-13)
+    h = oracle.pw_pw(x, w1, b1, w2, b2, "gelu_tanh")
+    f = oracle.ffn(x.reshape(-1, 4), w1, b1, w2, b2)
+    np.testing.assert_allclose(h.reshape(-1, 4), f, rtol=1e-13, atol=1e-13)
+
+
 def test_generator_is_counter_based_and_calibrated():
     a = rng.uniform(123, (1000,), -1, 1)
     b = rng.uniform(123, (4000,), -1, 1)

@@ -173,6 +173,82 @@ def baseline_case(i: int):
     raise IndexError(i)
 
 
+@dataclass
+class PairCase:
+    """Two-operator pairs of the inverted residual block (the paper's Fig. 13 micro-benchmarks).
+    kind "pw_dw": 1x1 C1 -> C2 (+b1, ReLU6) -> depthwise 3x3 (+bd, ReLU6)
+    kind "dw_pw": depthwise 3x3 on C1 channels (+bd, ReLU6) -> 1x1 C1 -> C2 (+b2)
+    kind "pw_pw": 1x1 C1 -> C2 (+b1, act) -> 1x1 C2 -> C3 (+b2)"""
+    kind: str
+    N: int; H: int; W: int; C1: int; C2: int
+    C3: int = 0
+    stride: int = 1
+    bias: bool = True
+    act: str = "relu"
+    dtype: str = "bf16"
+    seed: int = _SEED0 + 2000
+    name: str = "pair"
+
+    @property
+    def OH(self): return (self.H - 1) // self.stride + 1 if self.kind != "pw_pw" else self.H
+    @property
+    def OW(self): return (self.W - 1) // self.stride + 1 if self.kind != "pw_pw" else self.W
+
+    def out_shape(self):
+        c = {"pw_dw": self.C2, "dw_pw": self.C2, "pw_pw": self.C3}[self.kind]
+        return (self.N, self.OH, self.OW, c)
+
+    def flops(self):
+        pe, po = self.N * self.H * self.W, self.N * self.OH * self.OW
+        if self.kind == "pw_dw":
+            return 2 * pe * self.C1 * self.C2 + 2 * 9 * po * self.C2
+        if self.kind == "dw_pw":
+            return 2 * 9 * po * self.C1 + 2 * po * self.C1 * self.C2
+        return 2 * pe * self.C2 * (self.C1 + self.C3)
+
+    def alg_bytes(self):
+        e = 2 if self.dtype == "bf16" else 4
+        t = self.tensors()
+        n_in = sum(v.size * (4 if k.startswith("b") else e) for k, v in t.items() if v is not None)
+        n_out = 1
+        for d in self.out_shape():
+            n_out *= d
+        return n_in + n_out * e
+
+    def tensors(self):
+        s, d = self.seed, self.dtype
+        b = (lambda k, n: _f32(rng.uniform(s + k, (n,), -0.1, 0.1))) if self.bias else (lambda k, n: None)
+        if self.kind == "pw_dw":
+            return {"x": _store(rng.uniform(s, (self.N, self.H, self.W, self.C1), -1.0, 1.0), d),
+                    "w1": _store(rng.normal(s + 1, (self.C1, self.C2), (1.0 / self.C1) ** 0.5), d),
+                    "wd": _store(rng.normal(s + 2, (3, 3, self.C2), (1.0 / 9.0) ** 0.5), d),
+                    "b1": b(4, self.C2), "bd": b(5, self.C2)}
+        if self.kind == "dw_pw":
+            return {"x": _store(rng.uniform(s, (self.N, self.H, self.W, self.C1), -1.0, 1.0), d),
+                    "wd": _store(rng.normal(s + 2, (3, 3, self.C1), (1.0 / 9.0) ** 0.5), d),
+                    "w2": _store(rng.normal(s + 3, (self.C1, self.C2), (1.0 / self.C1) ** 0.5), d),
+                    "bd": b(5, self.C1), "b2": b(6, self.C2)}
+        return {"x": _store(rng.uniform(s, (self.N, self.H, self.W, self.C1), -1.0, 1.0), d),
+                "w1": _store(rng.normal(s + 1, (self.C1, self.C2), (1.0 / self.C1) ** 0.5), d),
+                "w2": _store(rng.normal(s + 3, (self.C2, self.C3), (1.0 / self.C2) ** 0.5), d),
+                "b1": b(4, self.C2), "b2": b(6, self.C3)}
+
+
+def pair_cases():
+    """The two-operator pairs at the block shapes of configurations 0 and 1 plus ragged variants."""
+    s = _SEED0 + 2000
+    return [
+        PairCase("pw_dw", 1, 14, 14, 32, 192, stride=1, dtype="f32", seed=s, name="pw_dw_14x14x32_f32"),
+        PairCase("pw_dw", 1, 56, 56, 24, 144, stride=2, bias=False, dtype="bf16", seed=s + 16, name="pw_dw_56x56x24_s2_bf16"),
+        PairCase("pw_dw", 2, 9, 11, 16, 96, stride=2, dtype="bf16", seed=s + 32, name="pw_dw_ragged_bf16"),
+        PairCase("dw_pw", 1, 14, 14, 192, 32, stride=1, dtype="f32", seed=s + 48, name="dw_pw_14x14x192_f32"),
+        PairCase("dw_pw", 1, 56, 56, 144, 32, stride=2, bias=False, dtype="bf16", seed=s + 64, name="dw_pw_56x56x144_s2_bf16"),
+        PairCase("dw_pw", 2, 13, 10, 96, 24, stride=1, dtype="bf16", seed=s + 80, name="dw_pw_ragged_bf16"),
+        PairCase("pw_pw", 2, 14, 14, 64, 384, 384, act="relu", dtype="bf16", seed=s + 96, name="pw_pw_2x14x14x64_bf16"),
+        PairCase("pw_pw", 1, 10, 13, 64, 128, 128, act="relu6", dtype="bf16", seed=s + 112, name="pw_pw_ragged_bf16"),
+    ]
+
+
 def small_cases():
     """Reduced-size variants: several tiles plus a ragged tail, seconds for the oracle."""
     s = _SEED0 + 1000
