@@ -45,6 +45,8 @@ def parse():
                     help="calibration aid: instead of the benchmark, run the library's plain elementwise kernel "
                          "(ago_scale, alpha = 1, fp32) over this many bytes --steps times; it reads and writes "
                          "exactly that many bytes, which scales the FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--no-cold", action="store_true",
+                    help="skip the cold-cache timings and launch floors of the per-config table (profiling aid)")
     ap.add_argument("--variants", default="fused,u1,u2",
                     help="which variants the per-config table runs (profiling aid: counters of one variant alone)")
     ap.add_argument("--tile-config", default="",
@@ -198,17 +200,20 @@ def main():
             u1_us = time_us(runner.prepare_unfused(c, t, yu, wsu, 0), args.detail_iters) if "u1" in variants else float("nan")
             u2_us = time_us(runner.prepare_unfused(c, t, yu, wsu, 1), args.detail_iters) if "u2" in variants else float("nan")
             launch = runner.prepare_fused(c, t, y, ws)
-            cold_avg, cold_min = cold_us(launch)
-            warm_avg, _ = cold_us(launch, flush=False)       # same single-launch method, caches warm
+            nan = float("nan")
+            cold_avg, cold_min = (nan, nan) if args.no_cold else cold_us(launch)
+            warm_avg, _ = (nan, nan) if args.no_cold else cold_us(launch, flush=False)   # same method, caches warm
             # launch floors: an empty kernel with the fused kernel's grid and workgroup size, and a plain
             # copy kernel moving the configuration's algorithmic bytes (half read, half written)
             grid, block = ago.profile_last_launch(fused_ops[type(c).__name__])
             stream = torch.cuda.current_stream().cuda_stream
-            empty_us = time_us(lambda: ago.lib.ago_bench_empty_kernel(grid, block, stream), args.detail_iters)
-            n_copy = max(8, c.alg_bytes() // 8 // 8 * 8)
-            cp_src = torch.ones(n_copy, dtype=torch.float32, device="cuda")
-            cp_dst = torch.empty_like(cp_src)
-            copy_us = time_us(ago.prepare(ago.ago_scale, cp_src, cp_dst, 1.0), args.detail_iters)
+            empty_us = copy_us = nan
+            if not args.no_cold:
+                empty_us = time_us(lambda: ago.lib.ago_bench_empty_kernel(grid, block, stream), args.detail_iters)
+                n_copy = max(8, c.alg_bytes() // 8 // 8 * 8)
+                cp_src = torch.ones(n_copy, dtype=torch.float32, device="cuda")
+                cp_dst = torch.empty_like(cp_src)
+                copy_us = time_us(ago.prepare(ago.ago_scale, cp_src, cp_dst, 1.0), args.detail_iters)
             tf = c.flops() / (fused_us * 1e-6) / 1e12
             peak = PEAK_F32_TFLOPS if c.dtype == "f32" else PEAK_BF16_TFLOPS
             t_mfma = c.flops() / (peak * 1e12)
@@ -230,7 +235,7 @@ def main():
 
     # ---- the two-operator pairs (not part of the step): fused vs operator by operator --------------
     pairs = []
-    if not args.no_detail and args.only < 0:
+    if not args.no_detail and not args.no_cold and args.only < 0:
         for c in wl.pair_cases():
             if "ragged" in c.name:
                 continue
