@@ -132,6 +132,48 @@ def test_every_tile_config_gives_the_same_answer(gpu, oracle):
             ago.set_tile_config(op, -1)
 
 
+# ---- seeded random shapes --------------------------------------------------------------------
+
+def _random_cases():
+    """Small shapes drawn from a fixed seed: odd image sizes, batches, channel counts at the supported
+    granularity, both strides, sequence lengths around the block boundaries, row counts that are not
+    multiples of any tile."""
+    r = np.random.RandomState(20221201)
+    cases = []
+    for i in range(8):
+        stride = int(r.choice([1, 2]))
+        cin = int(r.choice([8, 16, 24, 32, 40]))
+        cout = cin if (stride == 1 and r.rand() < 0.5) else int(r.choice([8, 16, 24, 48]))
+        cases.append(wl.InvresCase(int(r.randint(1, 4)), int(r.randint(1, 19)), int(r.randint(1, 19)), cin,
+                                   int(r.choice([16, 48, 96, 144, 208])), cout, stride,
+                                   stride == 1 and cin == cout, bool(r.rand() < 0.7),
+                                   str(r.choice(["f32", "bf16"])), 5000 + i, name="rand_invres_%d" % i))
+    for i in range(4):
+        cases.append(wl.ChainCase(int(r.randint(1, 3)), int(r.randint(1, 23)), int(r.randint(1, 23)), 64,
+                                  bool(r.rand() < 0.5), "bf16", 5100 + i, name="rand_chain_%d" % i))
+    for i in range(6):
+        k = 64 * int(r.randint(1, 5))
+        f, k2 = [(384, 384), (768, 384), (192, 128), (320, 256), (384, 768), (64, 128)][i]
+        cases.append(wl.FfnCase(int(r.randint(1, 300)), k, f, k2, "bf16", 5200 + i, name="rand_ffn_%d" % i))
+    for i in range(6):
+        s_len = int(r.choice([1, 31, 33, 64, 127, 129, 191, 193, 255, 257, 400, 513]))
+        cases.append(wl.AttnCase(int(r.randint(1, 3)), int(r.randint(1, 6)), s_len, 64, float(r.choice([0.125, 0.3])),
+                                 "bf16", 5300 + i, name="rand_attn_%d" % i))
+    return cases
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", _random_cases(), ids=lambda c: c.name)
+def test_fused_random_shapes(gpu, oracle, case):
+    torch, ago, runner = gpu
+    t = runner.to_device(case)
+    y = runner.alloc_output(case)
+    y.zero_()
+    runner.run_fused(case, t, y, runner.alloc_workspace(case, fused=True))
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(y), oracle.run_case(case), case.dtype, "%s %r" % (case.name, case))
+
+
 # ---- two-operator pairs ------------------------------------------------------------------
 
 @pytest.mark.gpu
