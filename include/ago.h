@@ -57,7 +57,7 @@ typedef enum { AGO_ACT_NONE = 0, AGO_ACT_RELU = 1, AGO_ACT_RELU6 = 2, AGO_ACT_GE
 typedef enum {
     AGO_OP_FUSED_INVRES = 0, AGO_OP_FUSED_CONV_CHAIN = 1, AGO_OP_FUSED_FFN = 2, AGO_OP_FUSED_ATTN = 3,
     AGO_OP_UNFUSED_INVRES = 4, AGO_OP_UNFUSED_CONV_CHAIN = 5, AGO_OP_UNFUSED_FFN = 6, AGO_OP_UNFUSED_ATTN = 7,
-    AGO_OP_FUSED_PW_DW = 8, AGO_OP_FUSED_DW_PW = 9, AGO_OP_FUSED_PW_PW = 10
+    AGO_OP_FUSED_PW_DW = 8, AGO_OP_FUSED_DW_PW = 9, AGO_OP_FUSED_PW_PW = 10, AGO_OP_FUSED_DW_DW = 11
 } ago_op;
 
 /* ------------------------------------------------------------------------- */
@@ -80,13 +80,16 @@ ago_status ago_fused_invres(const void* x, const void* w1, const float* b1,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* The two-operator pairs of the block as calls of their own (the micro-benchmark pairs of
- * Sec. VI, Fig. 13: pw->dw, dw->pw, pw->pw).  Same kernels, conventions and restrictions as the
+ * Sec. VI, Fig. 13: pw->dw, dw->pw, dw->dw, pw->pw).  Same kernels, conventions and restrictions as the
  * entry points they are cut from; tile configurations follow AGO_OP_FUSED_INVRES / _FFN.
  *   ago_fused_pw_dw   y = relu6(dw3x3(relu6(x * w1 + b1), wd, stride) + bd)       (Fig. 7a)
  *                     x:[N,H,W,Cin] w1:[Cin,Cexp] wd:[3,3,Cexp] y:[N,OH,OW,Cexp]; the expanded
  *                     tensor is 0 outside the image.  Cin % 8 == 0, Cexp % 16 == 0.
  *   ago_fused_dw_pw   y = relu6(dw3x3(x, wd, stride) + bd) * w2 + b2                (Fig. 7b)
  *                     x:[N,H,W,C] wd:[3,3,C] w2:[C,Cout] y:[N,OH,OW,Cout].  C % 16 == 0, Cout % 8 == 0.
+ *   ago_fused_dw_dw   y = relu6(dw3x3(relu6(dw3x3(x, wa, stride) + ba), wb, 1) + bb)  (Fig. 7a twice)
+ *                     x:[N,H,W,C] wa,wb:[3,3,C] y:[N,OH,OW,C]; the intermediate is 0 outside its
+ *                     image.  C % 4 == 0.  Vector ALUs only.
  *   ago_fused_pw_pw   y = act(x * w1 + b1) * w2 + b2 on NHWC tensors: ago_fused_ffn with
  *                     M = N H W, K = Cin, F = Cmid, K2 = Cout (bf16; same divisibility rules);
  *                     workspace size from ago_workspace_bytes(AGO_OP_FUSED_PW_PW,
@@ -99,6 +102,10 @@ ago_status ago_fused_pw_dw(const void* x, const void* w1, const float* b1,
 ago_status ago_fused_dw_pw(const void* x, const void* wd, const float* bd,
                            const void* w2, const float* b2, void* y,
                            int N, int H, int W, int C, int Cout, int stride, ago_dtype dt,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+ago_status ago_fused_dw_dw(const void* x, const void* wa, const float* ba,
+                           const void* wb, const float* bb, void* y,
+                           int N, int H, int W, int C, int stride, ago_dtype dt,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 ago_status ago_fused_pw_pw(const void* x, const void* w1, const float* b1,
                            const void* w2, const float* b2, void* y,

@@ -220,6 +220,17 @@ def dw_pw(x, wd, bd, w2, b2, stride=1):
     return y
 
 
+def dw_dw(x, wa, ba, wb, bb, stride=1):
+    """relu6(dw3x3(relu6(dw3x3(x, wa, stride) + ba), wb, 1) + bb)."""
+    t = dwconv3x3(x, wa, stride)
+    if ba is not None:
+        t = bias(t, ba)
+    y = dwconv3x3(relu6(t), wb, 1)
+    if bb is not None:
+        y = bias(y, bb)
+    return relu6(y)
+
+
 def pw_pw(x, w1, b1, w2, b2, act="relu"):
     """act(x * w1 + b1) * w2 + b2 on an NHWC tensor."""
     h = conv1x1(x, w1)
@@ -241,6 +252,8 @@ def run_case(case):
             return pw_dw(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], case.stride)
         if case.kind == "dw_pw":
             return dw_pw(t["x"], t["wd"], t["bd"], t["w2"], t["b2"], case.stride)
+        if case.kind == "dw_dw":
+            return dw_dw(t["x"], t["wd"], t["bd"], t["wd2"], t["bd2"], case.stride)
         return pw_pw(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], case.act)
     if kind == "InvresCase":
         return invres(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"],

@@ -25,7 +25,7 @@ F32, BF16 = 0, 1
 ACT_NONE, ACT_RELU, ACT_RELU6, ACT_GELU_TANH = 0, 1, 2, 3
 OP_FUSED_INVRES, OP_FUSED_CONV_CHAIN, OP_FUSED_FFN, OP_FUSED_ATTN = 0, 1, 2, 3
 OP_UNFUSED_INVRES, OP_UNFUSED_CONV_CHAIN, OP_UNFUSED_FFN, OP_UNFUSED_ATTN = 4, 5, 6, 7
-OP_FUSED_PW_DW, OP_FUSED_DW_PW, OP_FUSED_PW_PW = 8, 9, 10
+OP_FUSED_PW_DW, OP_FUSED_DW_PW, OP_FUSED_PW_PW, OP_FUSED_DW_DW = 8, 9, 10, 11
 
 _vp, _i, _l, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float, ctypes.c_size_t
 
@@ -37,6 +37,7 @@ _SIGS = {
     "ago_fused_pw_dw": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
     "ago_fused_dw_pw": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
     "ago_fused_pw_pw": [_vp] * 6 + [_i] * 8 + [_vp, _sz, _vp],
+    "ago_fused_dw_dw": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_gemm": [_vp] * 5 + [_i] * 5 + [_vp],
     "ago_conv1x1": [_vp] * 5 + [_i] * 7 + [_vp],
     "ago_dwconv3x3": [_vp] * 4 + [_i] * 7 + [_vp],
@@ -251,6 +252,14 @@ def ago_fused_dw_pw(x, wd, bd, w2, b2, y, stride, workspace=None):
     Cout = w2.shape[1]
     wp, wb = _ws(workspace)
     return lib.ago_fused_dw_pw, (_p(x), _p(wd), _p(bd), _p(w2), _p(b2), _p(y), N, H, W, C, Cout, stride,
+                                 _dt(x), wp, wb, _stream())
+
+
+@_entry
+def ago_fused_dw_dw(x, wa, ba, wb_, bb, y, stride, workspace=None):
+    N, H, W, C = x.shape
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_dw_dw, (_p(x), _p(wa), _p(ba), _p(wb_), _p(bb), _p(y), N, H, W, C, stride,
                                  _dt(x), wp, wb, _stream())
 
 

@@ -26,6 +26,7 @@ SOURCES = [
     "ago_fused_conv_chain.hip",
     "ago_fused_ffn.hip",
     "ago_fused_ffn_stream.hip",
+    "ago_fused_dw_dw.hip",
     "ago_fused_attn.hip",
 ]
 

@@ -147,6 +147,19 @@ ago_status ago_fused_dw_pw(const void* x, const void* wd, const float* bd, const
                                  dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES), as_stream(hip_stream), 2));
 }
 
+ago_status ago_fused_dw_dw(const void* x, const void* wa, const float* ba, const void* wb, const float* bb,
+                           void* y, int N, int H, int W, int C, int stride, ago_dtype dt,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    const void* ps[6] = {x, wa, wb, y, ba, bb};
+    ago_status st = check_ptrs(ps, 4, 6);
+    if (st != AGO_OK) return st;
+    if (!valid_dtype(dt)) return AGO_ERR_DTYPE;
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || (stride != 1 && stride != 2)) return AGO_ERR_SHAPE;
+    if (C % 4) return AGO_ERR_UNSUPPORTED;
+    return from_hip(fused_dw_dw(x, wa, ba, wb, bb, y, N, H, W, C, stride, dt == AGO_BF16, as_stream(hip_stream)));
+}
+
 ago_status ago_fused_pw_pw(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
                            void* y, int N, int H, int W, int Cin, int Cmid, int Cout, ago_act act,
                            ago_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream) {

@@ -47,6 +47,8 @@ void prof_stop(int op, hipStream_t s);
 void prof_shape(int op, unsigned grid, unsigned block);   // remembers the launch shape of the dominant kernel
 
 // tile-configuration tables (host only)
+hipError_t fused_dw_dw(const void* x, const void* wa, const float* ba, const void* wb, const float* bb,
+                       void* y, int N, int H, int W, int C, int stride, bool bf16, hipStream_t s);
 int fused_invres_num_cfgs();
 int fused_conv_chain_num_cfgs();
 // streaming (wave-specialised) FFN variant and the partial-product reduction shared by both variants

@@ -80,6 +80,8 @@ def _fused_call(case, t, y, ws):
             return ago.ago_fused_pw_dw, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], y, case.stride, ws)
         if case.kind == "dw_pw":
             return ago.ago_fused_dw_pw, (t["x"], t["wd"], t["bd"], t["w2"], t["b2"], y, case.stride, ws)
+        if case.kind == "dw_dw":
+            return ago.ago_fused_dw_dw, (t["x"], t["wd"], t["bd"], t["wd2"], t["bd2"], y, case.stride, ws)
         return ago.ago_fused_pw_pw, (t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, _ACT[case.act], ws)
     if k == "InvresCase":
         return ago.ago_fused_invres, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
@@ -135,6 +137,9 @@ def _pair_unfused_calls(case, t, y, scratch):
     if case.kind == "dw_pw":
         return [(ago.ago_dwconv3x3, (t["x"], t["wd"], t["bd"], scratch, case.stride, ago.ACT_RELU6)),
                 (ago.ago_conv1x1, (scratch, t["w2"], t["b2"], None, y, ago.ACT_NONE))]
+    if case.kind == "dw_dw":
+        return [(ago.ago_dwconv3x3, (t["x"], t["wd"], t["bd"], scratch, case.stride, ago.ACT_RELU6)),
+                (ago.ago_dwconv3x3, (scratch, t["wd2"], t["bd2"], y, 1, ago.ACT_RELU6))]
     return [(ago.ago_conv1x1, (t["x"], t["w1"], t["b1"], None, scratch, _ACT[case.act])),
             (ago.ago_conv1x1, (scratch, t["w2"], t["b2"], None, y, ago.ACT_NONE))]
 
@@ -160,7 +165,7 @@ def alloc_pair_scratch(case, device="cuda:0"):
     td = _torch_dtype(case.dtype)
     if case.kind == "pw_dw":
         shape = (case.N, case.H, case.W, case.C2)
-    elif case.kind == "dw_pw":
+    elif case.kind in ("dw_pw", "dw_dw"):
         shape = (case.N, case.OH, case.OW, case.C1)
     else:
         shape = (case.N, case.H, case.W, case.C2)

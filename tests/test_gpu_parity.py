@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 RTOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
-def assert_close(got, ref, dtype, what=""):
+def assert_close(got, ref, dtype, what="", scale=1.0):
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (got.shape, ref.shape)
@@ -26,8 +26,8 @@ def assert_close(got, ref, dtype, what=""):
     denom = np.maximum(np.abs(ref), rms if rms > 0 else 1.0)
     err = np.abs(got - ref) / denom
     worst = float(err.max())
-    assert worst <= RTOL[dtype], "%s: max rel err %.3e > %.1e at %s" % (
-        what, worst, RTOL[dtype], np.unravel_index(int(err.argmax()), err.shape))
+    assert worst <= scale * RTOL[dtype], "%s: max rel err %.3e > %.1e at %s" % (
+        what, worst, scale * RTOL[dtype], np.unravel_index(int(err.argmax()), err.shape))
     return worst
 
 
@@ -192,7 +192,10 @@ def test_pair_fused_matches_oracle(gpu, oracle, case):
     yu = runner.alloc_output(case)
     runner.run_pair_unfused(case, t, yu, runner.alloc_pair_scratch(case))
     torch.cuda.synchronize()
-    assert_close(runner.to_numpy64(yu), ref, case.dtype, case.name + " un-fused")
+    # operator by operator the intermediate tensor goes through memory in the storage type: one more
+    # bf16 rounding than the fused path, so this sanity check of the baseline gets 1.5x the bar
+    worst = assert_close(runner.to_numpy64(yu), ref, case.dtype, case.name + " un-fused", scale=1.5)
+    assert worst <= 1.5 * RTOL[case.dtype]
 
 
 # ---- single operators -----------------------------------------------------------------

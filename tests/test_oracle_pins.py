@@ -442,6 +442,15 @@ def test_pair_dw_pw_brute(oracle, stride):
     np.testing.assert_allclose(oracle.dw_pw(x, wd, bd, w2, b2, stride), lists_to_nhwc(y), rtol=1e-12, atol=1e-12)
 
 
+@pytest.mark.parametrize("stride", [1, 2])
+def test_pair_dw_dw_brute(oracle, stride):
+    x = _tiny(931, (1, 6, 5, 3)); wa = _tiny(932, (3, 3, 3)); wb = _tiny(933, (3, 3, 3))
+    ba = _tiny(934, (3,), -0.3, 0.3); bb = _tiny(935, (3,), -0.3, 0.3)
+    t = brute_bias_act(brute_conv_nchw(nhwc_to_lists(x), wdw_to_oihw(wa), 1, stride, groups_depthwise=True), ba.tolist(), "relu6")
+    y = brute_bias_act(brute_conv_nchw(t, wdw_to_oihw(wb), 1, 1, groups_depthwise=True), bb.tolist(), "relu6")
+    np.testing.assert_allclose(oracle.dw_dw(x, wa, ba, wb, bb, stride), lists_to_nhwc(y), rtol=1e-12, atol=1e-12)
+
+
 def test_pairs_compose_to_the_block_and_to_the_ffn(oracle):
     """pw_dw followed by the projection, and the expansion followed by dw_pw, both give the
     inverted residual; pw_pw on an NHWC tensor is the FFN chain on its rows."""

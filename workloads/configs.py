@@ -178,6 +178,7 @@ class PairCase:
     """Two-operator pairs of the inverted residual block (the paper's Fig. 13 micro-benchmarks).
     kind "pw_dw": 1x1 C1 -> C2 (+b1, ReLU6) -> depthwise 3x3 (+bd, ReLU6)
     kind "dw_pw": depthwise 3x3 on C1 channels (+bd, ReLU6) -> 1x1 C1 -> C2 (+b2)
+    kind "dw_dw": depthwise 3x3 (stride) on C1 channels (+bd, ReLU6) -> depthwise 3x3 (+bd2, ReLU6); C2 = C1
     kind "pw_pw": 1x1 C1 -> C2 (+b1, act) -> 1x1 C2 -> C3 (+b2)"""
     kind: str
     N: int; H: int; W: int; C1: int; C2: int
@@ -195,7 +196,7 @@ class PairCase:
     def OW(self): return (self.W - 1) // self.stride + 1 if self.kind != "pw_pw" else self.W
 
     def out_shape(self):
-        c = {"pw_dw": self.C2, "dw_pw": self.C2, "pw_pw": self.C3}[self.kind]
+        c = {"pw_dw": self.C2, "dw_pw": self.C2, "dw_dw": self.C1, "pw_pw": self.C3}[self.kind]
         return (self.N, self.OH, self.OW, c)
 
     def flops(self):
@@ -204,6 +205,8 @@ class PairCase:
             return 2 * pe * self.C1 * self.C2 + 2 * 9 * po * self.C2
         if self.kind == "dw_pw":
             return 2 * 9 * po * self.C1 + 2 * po * self.C1 * self.C2
+        if self.kind == "dw_dw":
+            return 2 * 2 * 9 * po * self.C1
         return 2 * pe * self.C2 * (self.C1 + self.C3)
 
     def alg_bytes(self):
@@ -228,6 +231,11 @@ class PairCase:
                     "wd": _store(rng.normal(s + 2, (3, 3, self.C1), (1.0 / 9.0) ** 0.5), d),
                     "w2": _store(rng.normal(s + 3, (self.C1, self.C2), (1.0 / self.C1) ** 0.5), d),
                     "bd": b(5, self.C1), "b2": b(6, self.C2)}
+        if self.kind == "dw_dw":
+            return {"x": _store(rng.uniform(s, (self.N, self.H, self.W, self.C1), -1.0, 1.0), d),
+                    "wd": _store(rng.normal(s + 2, (3, 3, self.C1), (1.0 / 9.0) ** 0.5), d),
+                    "wd2": _store(rng.normal(s + 7, (3, 3, self.C1), (1.0 / 9.0) ** 0.5), d),
+                    "bd": b(5, self.C1), "bd2": b(8, self.C1)}
         return {"x": _store(rng.uniform(s, (self.N, self.H, self.W, self.C1), -1.0, 1.0), d),
                 "w1": _store(rng.normal(s + 1, (self.C1, self.C2), (1.0 / self.C1) ** 0.5), d),
                 "w2": _store(rng.normal(s + 3, (self.C2, self.C3), (1.0 / self.C2) ** 0.5), d),
@@ -244,6 +252,10 @@ def pair_cases():
         PairCase("dw_pw", 1, 14, 14, 192, 32, stride=1, dtype="f32", seed=s + 48, name="dw_pw_14x14x192_f32"),
         PairCase("dw_pw", 1, 56, 56, 144, 32, stride=2, bias=False, dtype="bf16", seed=s + 64, name="dw_pw_56x56x144_s2_bf16"),
         PairCase("dw_pw", 2, 13, 10, 96, 24, stride=1, dtype="bf16", seed=s + 80, name="dw_pw_ragged_bf16"),
+        PairCase("dw_dw", 1, 14, 14, 192, 192, stride=1, dtype="f32", seed=s + 128, name="dw_dw_14x14x192_f32"),
+        PairCase("dw_dw", 1, 56, 56, 144, 144, stride=2, bias=False, dtype="bf16", seed=s + 144, name="dw_dw_56x56x144_s2_bf16"),
+        PairCase("dw_dw", 2, 11, 9, 40, 40, stride=2, dtype="bf16", seed=s + 160, name="dw_dw_ragged_bf16"),
+        PairCase("dw_dw", 3, 7, 19, 72, 72, stride=1, dtype="f32", seed=s + 176, name="dw_dw_ragged_f32"),
         PairCase("pw_pw", 2, 14, 14, 64, 384, 384, act="relu", dtype="bf16", seed=s + 96, name="pw_pw_2x14x14x64_bf16"),
         PairCase("pw_pw", 1, 10, 13, 64, 128, 128, act="relu6", dtype="bf16", seed=s + 112, name="pw_pw_ragged_bf16"),
     ]
