@@ -139,6 +139,19 @@ ago_status ago_fused_attn(const void* q, const void* k, const void* v, void* o,
                           int B, int Hh, int S, int D, float scale, ago_dtype dt,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same attention chain on tensors whose rows are laid out by strides (in elements, the same
+ * for q, k, v and o): row s of (batch b, head h) starts at b * stride_b + h * stride_h +
+ * s * stride_s and holds D contiguous elements.  [B][Hh][S][D] is (Hh S D, S D, D); the
+ * projection output layout [B][S][Hh][D] is (S Hh D, D, Hh D), which folds the transposes that
+ * surround the chain into its addressing (Sec. VI-C counts those reshapes / transposes among the
+ * simple operators between the two products).  Strides must be positive multiples of 8,
+ * stride_s >= D (else SHAPE / ALIGN); rows must not overlap (not checked). */
+ago_status ago_fused_attn_strided(const void* q, const void* k, const void* v, void* o,
+                                  int B, int Hh, int S, int D,
+                                  long long stride_b, long long stride_h, long long stride_s,
+                                  float scale, ago_dtype dt,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------------- */
 /* Un-fused per-operator kernels (Sec. III-A).  With bias == NULL and           */
 /* act == AGO_ACT_NONE each is exactly one operator (Fig. 3); with a bias /     */

@@ -34,6 +34,7 @@ _SIGS = {
     "ago_fused_conv_chain": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_ffn": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_attn": [_vp] * 4 + [_i] * 4 + [_f, _i, _vp, _sz, _vp],
+    "ago_fused_attn_strided": [_vp] * 4 + [_i] * 4 + [ctypes.c_longlong] * 3 + [_f, _i, _vp, _sz, _vp],
     "ago_fused_pw_dw": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
     "ago_fused_dw_pw": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
     "ago_fused_pw_pw": [_vp] * 6 + [_i] * 8 + [_vp, _sz, _vp],
@@ -235,6 +236,15 @@ def ago_fused_attn(q, k, v, o, scale, workspace=None):
     B, Hh, S, D = q.shape
     wp, wb = _ws(workspace)
     return lib.ago_fused_attn, (_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q), wp, wb, _stream())
+
+
+@_entry
+def ago_fused_attn_bshd(q, k, v, o, scale, workspace=None):
+    """q, k, v, o: [B, S, Hh, D] tensors (the layout a QKV projection leaves behind)."""
+    B, S, Hh, D = q.shape
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_attn_strided, (_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, S * Hh * D, D, Hh * D,
+                                        float(scale), _dt(q), wp, wb, _stream())
 
 
 @_entry

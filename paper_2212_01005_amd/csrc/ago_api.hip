@@ -390,6 +390,20 @@ ago_status ago_unfused_ffn(const void* x, const void* w1, const float* b1, const
     return AGO_OK;
 }
 
+ago_status ago_fused_attn_strided(const void* q, const void* k, const void* v, void* o, int B, int Hh,
+                                  int S, int D, long long stride_b, long long stride_h, long long stride_s,
+                                  float scale, ago_dtype dt, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    ago_status st = check_attn(q, k, v, o, B, Hh, S, D, scale, dt);
+    if (st != AGO_OK) return st;
+    // rows of D contiguous elements, every row start 16-byte aligned, and no two rows overlapping
+    if (stride_b <= 0 || stride_h <= 0 || stride_s < D) return AGO_ERR_SHAPE;
+    if (stride_b % 8 || stride_h % 8 || stride_s % 8) return AGO_ERR_ALIGN;
+    return from_hip(fused_attn(q, k, v, o, B, Hh, S, scale, tile_config(AGO_OP_FUSED_ATTN), as_stream(hip_stream),
+                               (long)stride_b, (long)stride_h, (long)stride_s));
+}
+
 ago_status ago_unfused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
                             int D, float scale, ago_dtype dt, int epilogue_fused, void* workspace,
                             size_t workspace_bytes, void* s) {

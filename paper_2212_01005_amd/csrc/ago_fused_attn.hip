@@ -56,7 +56,8 @@ __device__ __forceinline__ bf16x8 lds_read_vt(const lds_byte* p) {
 template <int NQT, int NSTG>
 __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per_eu(3, 4))) void fused_attn_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    bf16_t* __restrict__ O, int S, int heads, int qblocks, float c /* scale * log2(e) */) {
+    bf16_t* __restrict__ O, int S, int heads, int qblocks, int Hh, long stride_b, long stride_h, long stride_s,
+    float c /* scale * log2(e) */) {
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_byte* smem = (lds_byte*)smem_generic;          // [2 buffers][K block | V block]
     const int tid = threadIdx.x, lane = tid & 63;
@@ -67,7 +68,9 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int head = (slot / qblocks) * 8 + xcd, qblk = slot % qblocks;
     if (head >= heads) return;                         // padding workgroups of the last group of 8 heads
-    const long head_off = (long)head * S * kD;
+    // row s of (batch b, head hh) starts at b * stride_b + hh * stride_h + s * stride_s elements: the
+    // [B][Hh][S][D] and [B][S][Hh][D] layouts (and any other with contiguous rows) without a transpose
+    const long head_off = (long)(head / Hh) * stride_b + (long)(head % Hh) * stride_h;
     Q += head_off; K += head_off; V += head_off; O += head_off;
     const int nblk = (S + kKB - 1) / kKB;
 
@@ -85,7 +88,7 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
             for (int q = 0; q < 16; ++q) {
                 const int row = 8 * q + r8;
                 const int sw = is_v ? ((((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1)) : ((row >> 1) & 7);
-                const bf16_t* g = src + (long)min(blk * kKB + row, S - 1) * kD + 8 * (pc ^ sw);
+                const bf16_t* g = src + (long)min(blk * kKB + row, S - 1) * stride_s + 8 * (pc ^ sw);
                 __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) const void*)g,
                                                  (__attribute__((address_space(3))) void*)(dst + q * 1024), 16, 0, 0);
             }
@@ -120,7 +123,7 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
     bf16x8 qf[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-        qf[ks] = __builtin_bit_cast(bf16x8, ld_u4(Q + (long)min(q_row, S - 1) * kD + ks * 16 + 8 * h));
+        qf[ks] = __builtin_bit_cast(bf16x8, ld_u4(Q + (long)min(q_row, S - 1) * stride_s + ks * 16 + 8 * h));
 
     // K fragment of key tile kt (32 keys), k step ks: row = 64 kh + 32 kt + j, logical chunk 2 ks + h
     const int krow = 64 * kh + j;                      // + 32 kt: bit 5, does not reach the swizzle bits 1..3
@@ -237,7 +240,7 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const int d = dt * 32 + 8 * gq + 4 * h;
-                    *reinterpret_cast<uint2*>(O + (long)q_row * kD + d) =
+                    *reinterpret_cast<uint2*>(O + (long)q_row * stride_s + d) =
                         make_uint2(pack_bf16(o[dt][4 * gq], o[dt][4 * gq + 1]), pack_bf16(o[dt][4 * gq + 2], o[dt][4 * gq + 3]));
                 }
         }
@@ -246,7 +249,7 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
 
 template <int NQT, int NSTG>
 static hipError_t launch_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
-                              float scale, hipStream_t s) {
+                              long stride_b, long stride_h, long stride_s, float scale, hipStream_t s) {
     constexpr size_t smem = (size_t)NSTG * 2 * kBlockB;    // ring of (K block, V block) buffers; the merge reuses them
     static_assert((size_t)NQT * 34 * 64 * 4 <= smem, "merge scratch");
     auto kern = fused_attn_kernel<NQT, NSTG>;
@@ -262,7 +265,8 @@ static hipError_t launch_attn(const void* q, const void* k, const void* v, void*
     prof_start(3, s);
     prof_shape(3, grid.x, (2 * NQT + 2) * 64);
     hipLaunchKernelGGL(kern, grid, dim3((2 * NQT + 2) * 64), smem, s, (const bf16_t*)q, (const bf16_t*)k,
-                       (const bf16_t*)v, (bf16_t*)o, S, heads, qblocks, scale * 1.4426950408889634f);
+                       (const bf16_t*)v, (bf16_t*)o, S, heads, qblocks, Hh, stride_b, stride_h, stride_s,
+                       scale * 1.4426950408889634f);
     prof_stop(3, s);
     return hipGetLastError();
 }
@@ -272,7 +276,8 @@ static hipError_t launch_attn(const void* q, const void* k, const void* v, void*
 int fused_attn_num_cfgs() { return 4; }
 
 hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
-                      float scale, int tile_cfg, hipStream_t s) {
+                      float scale, int tile_cfg, hipStream_t s, long stride_b, long stride_h, long stride_s) {
+    if (stride_s == 0) { stride_b = (long)Hh * S * kD; stride_h = (long)S * kD; stride_s = kD; }   // [B][Hh][S][D]
     if (tile_cfg < 0) {
         // built-in choice: 192-query workgroups (a compute unit to themselves, K and V of the first
         // three blocks requested at once) when that still gives the chip enough workgroups
@@ -280,10 +285,10 @@ hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int 
         tile_cfg = (S > 96 && wgs >= 128) ? 3 : 0;
     }
     switch (tile_cfg) {
-        case 1: return launch_attn<4, 2>(q, k, v, o, B, Hh, S, scale, s);
-        case 2: return launch_attn<2, 2>(q, k, v, o, B, Hh, S, scale, s);
-        case 3: return launch_attn<6, 3>(q, k, v, o, B, Hh, S, scale, s);
-        default: return launch_attn<3, 2>(q, k, v, o, B, Hh, S, scale, s);
+        case 1: return launch_attn<4, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
+        case 2: return launch_attn<2, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
+        case 3: return launch_attn<6, 3>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
+        default: return launch_attn<3, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
     }
 }
 

@@ -38,7 +38,8 @@ hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void*
                      void* y, int M, int K, int F, int K2, int act, int tile_cfg, void* workspace,
                      hipStream_t s);
 hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
-                      float scale, int tile_cfg, hipStream_t s);
+                      float scale, int tile_cfg, hipStream_t s,
+                      long stride_b = 0, long stride_h = 0, long stride_s = 0);   // element strides; 0 = [B][Hh][S][D]
 
 // Instrumentation hook (see ago_profile_enable): record an event pair around the dominant kernel
 // of a fused entry point.  No-ops unless profiling is enabled.

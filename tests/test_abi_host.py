@@ -77,6 +77,13 @@ def test_pair_entry_points_validate_before_any_gpu_call(lib):
     assert pwpw(1, 8, 8, 64, 128, 128, act=11) == 3
     assert pwpw(1, 8, 8, 60, 128, 128) == 5                               # same divisibility rules as the FFN chain
     assert pwpw(1, 8, 8, 64, 768, 128) == 6                               # several hidden slices need a workspace
+    ll = ctypes.c_longlong
+    lib.ago_fused_attn_strided.argtypes = [vp] * 4 + [ci] * 4 + [ll] * 3 + [ctypes.c_float, ci, vp, sz, vp]
+    att = lambda sb, sh, ss, D=64: lib.ago_fused_attn_strided(p, p, p, p, 2, 4, 100, D, sb, sh, ss, 0.125, 1, None, 0, None)
+    assert att(0, 64, 256) == 2                                           # strides must be positive
+    assert att(25600, 64, 32) == 2                                        # rows would overlap
+    assert att(25600, 60, 256) == 4                                       # row starts must stay 16-byte aligned
+    assert att(25600, 64, 256, D=32) == 5                                 # head dimension other than 64
     from paper_2212_01005_amd import binding as ago
     # the pair's workspace is the FFN chain's on N*H*W rows
     assert ago.workspace_bytes(ago.OP_FUSED_PW_PW, [1, 8, 8, 64, 768, 128], ago.BF16) == \

@@ -132,6 +132,20 @@ def test_every_tile_config_gives_the_same_answer(gpu, oracle):
             ago.set_tile_config(op, -1)
 
 
+def test_attention_strided_layout(gpu, oracle):
+    """[B][S][Hh][D] tensors through the strided entry point give the [B][Hh][S][D] answer."""
+    torch, ago, runner = gpu
+    for case in (wl.AttnCase(2, 3, 200, 64, 0.125, "bf16", 6100, name="attn_bshd_s200"),
+                 wl.AttnCase(1, 12, 384, 64, 0.125, "bf16", 6101, name="attn_bshd_s384")):
+        ref = oracle.run_case(case)                                    # [B, Hh, S, D]
+        t = runner.to_device(case)
+        q, k, v = (t[n].permute(0, 2, 1, 3).contiguous() for n in ("q", "k", "v"))   # [B, S, Hh, D]
+        o = torch.zeros_like(q)
+        ago.ago_fused_attn_bshd(q, k, v, o, case.scale)
+        torch.cuda.synchronize()
+        assert_close(runner.to_numpy64(o.permute(0, 2, 1, 3)), ref, "bf16", case.name)
+
+
 # ---- seeded random shapes --------------------------------------------------------------------
 
 def _random_cases():
