@@ -12,10 +12,10 @@
 //   swap   barrier, Wb registers -> the weight area of LDS, barrier
 //   conv2  Y = relu(conv3x3(T) + bb (+ X)) on TH x TW -> global memory
 // Both convolutions are implicit GEMMs [pixels] x [9 taps x 64] x [64] on 32x32x16 bf16 matrix
-// instructions, on 16 waves (four per SIMD: a single wave cannot issue LDS fragment reads fast
-// enough to keep its SIMD's matrix pipe busy).  The work of each convolution is dealt out as
-// (32-pixel row tile, 32-output-channel half) jobs to 8 wave pairs; the two waves of a pair each
-// reduce over one half of the input channels and their partial sums are added through LDS.
+// instructions, on up to 15 of 16 waves (four per SIMD: a single wave cannot issue LDS fragment
+// reads fast enough to keep its SIMD's matrix pipe busy).  The work of each convolution is dealt
+// out as (32-pixel row tile, kernel row) units, one per wave; the three partial sums of a row tile
+// are added through LDS.
 //
 // LDS layouts.  A 16-byte-per-lane fragment read is served one half-wave (32 lanes) at a time and is
 // bank-conflict free when the 32 rows it touches are 144 bytes apart (72-element rows) or fall into
@@ -45,100 +45,101 @@ struct ChainGeom {
     static constexpr size_t kSmem = ((size_t)XH * XROW + R1H * TROW + 9 * 64 * LD) * 2 + 128 * 4;
 };
 
-// One convolution over an LDS-resident source tile, on 8 waves.  The work is cut into
-// (32-pixel row tile, 32-channel half) jobs, 2 * NMT of them; wave w takes job w, and jobs beyond
-// the first eight go to owners 1, 3, 5, 7, 0, 2, 4, 6 in that order so that owners that share a
-// SIMD (w and w + 4) do not both get an extra job.
+// One convolution over an LDS-resident source tile.  The work is cut into units of (32-pixel row
+// tile, kernel row): 3 NMT of them, one per wave (the remaining waves idle).  A unit runs the three
+// taps of its kernel row over all 64 input channels for both 32-channel halves of the output, so
+// every activation fragment feeds two matrix instructions (two independent accumulators); the three
+// partial sums of a row tile are added through LDS, each unit reducing and finishing a third of
+// the tile's channels.
 // SRC_ROW = elements per pixel row of the source tile, DST_P = lanes per destination row (pixel
 // m sits at row m / DST_P, column m % DST_P; columns >= DST_W are padding), NP = destination
-// lane slots, NMT = row tiles.  WEIGHTS_A: weights are MFMA operand A (accumulator rows =
-// channels, cols = pixels), else operand B.
-template <int SRC_ROW, int DST_P, int DST_W, int NP, int NMT, bool WEIGHTS_A>
+// lane slots, NMT = row tiles.  Weights are MFMA operand A: accumulator rows = output channels,
+// columns = pixels.
+template <int SRC_ROW, int DST_P, int DST_W, int NP, int NMT>
 struct ConvStage {
     static constexpr int LD = 72;
-    static constexpr int NJ = 2 * NMT;                  // jobs
-    static constexpr int J = (NJ + 7) / 8;              // job slots per wave
-    f32x16 acc[J];
-    int off[J];                                         // LDS offset of this lane's pixel, tap (0,0)
-    int wrow[J];                                        // LDS offset of this lane's weight row
-    int wsw[J];                                         // chunk swizzle of that row
+    static constexpr int NU = 3 * NMT;                  // units
+    static_assert(NU <= 16, "one unit per wave");
+    f32x16 acc[2];                                      // output channels 0..31, 32..63
+    int off;                                            // LDS offset of this lane's pixel, kernel row tg, column 0
+    int wbase;                                          // LDS offset of this lane's weight row, kernel row tg
 
-    __device__ __forceinline__ static int job(int i, int wave) {
-        const int extra = ((wave & 1) ? 0 : 4) + (wave >> 1);
-        return i == 0 ? wave : 8 * i + extra;
-    }
-    __device__ __forceinline__ static bool live(int i, int wave) { return job(i, wave) < NJ; }
-    __device__ __forceinline__ static int tile(int i, int wave) { return job(i, wave) >> 1; }
-    __device__ __forceinline__ static int nt(int i, int wave) { return job(i, wave) & 1; }
+    __device__ __forceinline__ static bool live(int wave) { return wave < NU; }
+    __device__ __forceinline__ static int tile(int wave) { return wave / 3; }
+    __device__ __forceinline__ static int tg(int wave) { return wave % 3; }
 
     __device__ __forceinline__ void init(int wave, int j, int h) {
+        int m = tile(wave) * 32 + j;
+        if (m >= NP) m = 0;
+        const int px = (m % DST_P) < DST_W ? m % DST_P : 0;      // padding lanes read a valid pixel
+        off = (m / DST_P + tg(wave)) * SRC_ROW + px * LD + 8 * h;
+        wbase = (tg(wave) * 3 * 64 + j) * LD;
 #pragma unroll
-        for (int i = 0; i < J; ++i) {
-            int m = tile(i, wave) * 32 + j;
-            if (m >= NP) m = 0;
-            const int px = (m % DST_P) < DST_W ? m % DST_P : 0;      // padding lanes read a valid pixel
-            off[i] = (m / DST_P) * SRC_ROW + px * LD + 8 * h;
-            const int row = nt(i, wave) * 32 + j;
-            wrow[i] = row * LD;
-            wsw[i] = (row >> 5) & 1;     // constant over the 32 rows of a fragment read (those must stay 144 bytes apart)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-        }
+        for (int r = 0; r < 16; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }
     }
 
-    struct Frag { bf16x8 w, x; };
-    // step = tap * 2 + (k-step within this wave's half of the input channels)
-    __device__ __forceinline__ Frag fetch(const bf16_t* src, const bf16_t* ws, int step, int i, int h, int kh) const {
-        const int tap = step >> 1, ks = 2 * kh + (step & 1);
-        const int shift = (tap / 3) * SRC_ROW + (tap % 3) * LD;
+    struct Frag { bf16x8 x, w0, w1; };
+    // step = (kernel column) * 4 + k step; the weight rows of output channels 32..63 carry the
+    // chunk swizzle bit (row >> 5)
+    __device__ __forceinline__ Frag fetch(const bf16_t* src, const bf16_t* ws, int step, int h) const {
+        const int col = step >> 2, ks = step & 3;
         Frag f;
-        f.w = ld_bf16x8(ws + tap * 64 * LD + wrow[i] + (((ks * 2 + h) ^ wsw[i]) << 3));
-        f.x = ld_bf16x8(src + off[i] + shift + ks * 16);
+        f.x = ld_bf16x8(src + off + col * LD + ks * 16);
+        f.w0 = ld_bf16x8(ws + wbase + col * 64 * LD + ((ks * 2 + h) << 3));
+        f.w1 = ld_bf16x8(ws + wbase + (col * 64 + 32) * LD + (((ks * 2 + h) ^ 1) << 3));
         return f;
     }
 
-    // 9 taps x 2 k-steps (this wave's half of the input channels), fully unrolled, with the LDS
-    // fragment reads issued DEPTH steps ahead of the matrix instruction that consumes them.
-    // src = activation tile, ws = [9][64][LD] swizzled weights.
-    __device__ __forceinline__ void run(const bf16_t* src, const bf16_t* ws, int wj, int h, int kh) {
-        constexpr int DEPTH = 3, STEPS = 18;
+    // 3 taps x 4 k-steps, fully unrolled, with the LDS fragment reads issued DEPTH steps ahead of
+    // the matrix instructions that consume them.  src = activation tile, ws = [9][64][LD] weights.
+    __device__ __forceinline__ void run(const bf16_t* src, const bf16_t* ws, int h) {
+        constexpr int DEPTH = 3, STEPS = 12;
+        Frag q[DEPTH];
 #pragma unroll
-        for (int i = 0; i < J; ++i) {
-            if (!live(i, wj)) continue;
-            Frag q[DEPTH];
+        for (int d = 0; d < DEPTH; ++d) q[d] = fetch(src, ws, d, h);
 #pragma unroll
-            for (int d = 0; d < DEPTH; ++d) q[d] = fetch(src, ws, d, i, h, kh);
-#pragma unroll
-            for (int s = 0; s < STEPS; ++s) {
-                const Frag cur = q[s % DEPTH];
-                if (s + DEPTH < STEPS) q[s % DEPTH] = fetch(src, ws, s + DEPTH, i, h, kh);
-                acc[i] = WEIGHTS_A ? mfma32(cur.w, cur.x, acc[i]) : mfma32(cur.x, cur.w, acc[i]);
-            }
+        for (int s = 0; s < STEPS; ++s) {
+            const Frag cur = q[s % DEPTH];
+            if (s + DEPTH < STEPS) q[s % DEPTH] = fetch(src, ws, s + DEPTH, h);
+            acc[0] = mfma32(cur.w0, cur.x, acc[0]);
+            acc[1] = mfma32(cur.w1, cur.x, acc[1]);
         }
     }
 
-    // Sum the two channel-half partial accumulators of every job: the kh = 1 waves park theirs in
-    // `scratch` (4 KB per job, [job][4][64 lanes] float4), the kh = 0 waves add them.  The caller
-    // places barriers before (scratch no longer read as weights) and between the two halves.
-    __device__ __forceinline__ void park(float* scratch, int wj, int lane) const {
+    // Sum the three kernel-row partial accumulators of every row tile.  The accumulators are cut
+    // into 8 groups of 4 registers (group = channel half * 4 + g: output channels 32 n + 8 g + 4 h
+    // .. + 3 of this lane's pixel); the unit of kernel row 0 owns groups 0..2, row 1 groups 3..5,
+    // row 2 groups 6, 7.  Every unit parks the groups it does not own in `scratch`
+    // ([tile][group][source slot 0 / 1][64 lanes] float4, 16 KB per tile) and, after a barrier,
+    // adds the two parked copies of the groups it owns, so that the reduction and the epilogue
+    // are spread over all units.  The caller places barriers before (scratch no longer read as
+    // weights) and between the two halves.
+    __device__ __forceinline__ static int owner_of(int grp) { return grp < 3 ? 0 : grp < 6 ? 1 : 2; }
+    __device__ __forceinline__ void park(float* scratch, int wave, int lane) const {
+        const int me = tg(wave);
+        float4* base = reinterpret_cast<float4*>(scratch) + tile(wave) * 16 * 64 + lane;
 #pragma unroll
-        for (int i = 0; i < J; ++i) {
-            if (!live(i, wj)) continue;
-            float4* p = reinterpret_cast<float4*>(scratch) + (job(i, wj) * 4) * 64 + lane;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) p[g * 64] = make_float4(acc[i][4 * g], acc[i][4 * g + 1], acc[i][4 * g + 2], acc[i][4 * g + 3]);
+        for (int grp = 0; grp < 8; ++grp) {
+            const int ow = grp < 3 ? 0 : grp < 6 ? 1 : 2;
+            if (me == ow) continue;
+            // the two sources of a group are the non-owners in increasing order
+            const int slot = me > ow ? me - 1 : me;
+            const int n = grp >> 2, g = grp & 3;
+            base[(grp * 2 + slot) * 64] = make_float4(acc[n][4 * g], acc[n][4 * g + 1], acc[n][4 * g + 2], acc[n][4 * g + 3]);
         }
     }
-    __device__ __forceinline__ void gather(const float* scratch, int wj, int lane) {
+    // adds the parked copies into the owned groups (the other groups of acc are left as they are)
+    __device__ __forceinline__ void gather(const float* scratch, int wave, int lane) {
+        const int me = tg(wave);
+        const float4* base = reinterpret_cast<const float4*>(scratch) + tile(wave) * 16 * 64 + lane;
 #pragma unroll
-        for (int i = 0; i < J; ++i) {
-            if (!live(i, wj)) continue;
-            const float4* p = reinterpret_cast<const float4*>(scratch) + (job(i, wj) * 4) * 64 + lane;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const float4 v = p[g * 64];
-                acc[i][4 * g] += v.x; acc[i][4 * g + 1] += v.y; acc[i][4 * g + 2] += v.z; acc[i][4 * g + 3] += v.w;
-            }
+        for (int grp = 0; grp < 8; ++grp) {
+            const int ow = grp < 3 ? 0 : grp < 6 ? 1 : 2;
+            if (me != ow) continue;
+            const int n = grp >> 2, g = grp & 3;
+            const float4 u = base[(grp * 2) * 64], v = base[(grp * 2 + 1) * 64];
+            acc[n][4 * g] += u.x + v.x; acc[n][4 * g + 1] += u.y + v.y;
+            acc[n][4 * g + 2] += u.z + v.z; acc[n][4 * g + 3] += u.w + v.w;
         }
     }
 };
@@ -158,7 +159,6 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
     float* Bias = reinterpret_cast<float*>(Ws + 9 * 64 * LD);   // ba[64], bb[64] (0 when absent)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wj = wave & 7, kh = wave >> 3;     // job owner index, input-channel half
     const int j = lane & 31, h = lane >> 5;
     int b = blockIdx.x;
     const int tw = b % tiles_w; b /= tiles_w;
@@ -170,45 +170,44 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
 
     // All nine taps of one weight tensor: 9 * 128 transposition units of [8 in][4 out];
     // unit u -> tap u / 128, out-channel quad (u & 15), in-channel octet (u >> 4) & 7.
-    constexpr int WU = 2;        // ceil(1152 / 1024)
-    uint2 rw[WU][8];
-    auto load_w = [&](const bf16_t* Wsrc) {
+    // Unit u < 1024 belongs to thread u and may stay in registers for a long time (the second weight
+    // tensor is prefetched during conv1); the remaining 128 units are loaded and stored in one go
+    // by the first 128 threads, so that only 16 registers are held across conv1.
+    uint2 rw[8];
+    auto load_unit = [&](const bf16_t* Wsrc, int u, uint2 (&r)[8]) {
+        const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
 #pragma unroll
-        for (int i = 0; i < WU; ++i) {
-            const int u = tid + 1024 * i;
-            if (u >= 9 * 128) continue;
-            const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
+        for (int kk = 0; kk < 8; ++kk)
+            r[kk] = *reinterpret_cast<const uint2*>(Wsrc + ((long)tap * C + ko * 8 + kk) * C + nq * 4);
+    };
+    auto store_unit = [&](int u, const uint2 (&r)[8]) {
+        const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
+        // Transpose the [8 in][4 out] block one output channel at a time.  In store t lane nq writes
+        // output channel 4 nq + ((t + nq + nq / 4) & 3): with that rotation (and the row >> 5 swizzle)
+        // the 16-byte stores of a wave, whose rows are 4 apart, are bank-conflict free.
+        const int rot = nq + (nq >> 2);
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                rw[i][kk] = *reinterpret_cast<const uint2*>(Wsrc + ((long)tap * C + ko * 8 + kk) * C + nq * 4);
+        for (int t = 0; t < 4; ++t) {
+            const int q = (t + rot) & 3;
+            const bool hi_word = q & 2;
+            const int sh = (q & 1) << 4;
+            uint32_t v[4];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t e = hi_word ? r[2 * m].y : r[2 * m].x;
+                const uint32_t d = hi_word ? r[2 * m + 1].y : r[2 * m + 1].x;
+                v[m] = ((e >> sh) & 0xffffu) | ((d >> sh) << 16);
+            }
+            const int o = nq * 4 + q;
+            st_u4(Ws + (tap * 64 + o) * LD + ((ko ^ ((o >> 5) & 1)) << 3), make_uint4(v[0], v[1], v[2], v[3]));
         }
     };
-    auto store_w = [&]() {
-#pragma unroll
-        for (int i = 0; i < WU; ++i) {
-            const int u = tid + 1024 * i;
-            if (u >= 9 * 128) continue;
-            const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
-            // Transpose the [8 in][4 out] block one output channel at a time.  In store t lane nq writes
-            // output channel 4 nq + ((t + nq + nq / 4) & 3): with that rotation (and the row >> 5 swizzle)
-            // the 16-byte stores of a wave, whose rows are 4 apart, are bank-conflict free.
-            const int rot = nq + (nq >> 2);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int q = (t + rot) & 3;
-                const bool hi_word = q & 2;
-                const int sh = (q & 1) << 4;
-                uint32_t v[4];
-#pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    const uint32_t e = hi_word ? rw[i][2 * m].y : rw[i][2 * m].x;
-                    const uint32_t d = hi_word ? rw[i][2 * m + 1].y : rw[i][2 * m + 1].x;
-                    v[m] = ((e >> sh) & 0xffffu) | ((d >> sh) << 16);
-                }
-                const int o = nq * 4 + q;
-                st_u4(Ws + (tap * 64 + o) * LD + ((ko ^ ((o >> 5) & 1)) << 3), make_uint4(v[0], v[1], v[2], v[3]));
-            }
-        }
+    auto load_w = [&](const bf16_t* Wsrc) { load_unit(Wsrc, tid, rw); };
+    auto store_w = [&](const bf16_t* Wsrc) {
+        uint2 extra[8];
+        if (tid < 9 * 128 - 1024) load_unit(Wsrc, 1024 + tid, extra);
+        store_unit(tid, rw);
+        if (tid < 9 * 128 - 1024) store_unit(1024 + tid, extra);
     };
 
     load_w(Wa);
@@ -220,73 +219,86 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
         if (ih >= 0 && ih < H && iw >= 0 && iw < W) v = ld_u4(X + ((long)ih * W + iw) * C + kc * 8);
         st_u4(Xs + (pix / XW) * XROW + (pix % XW) * LD + kc * 8, v);
     }
-    store_w();
+    store_w(Wa);
     __syncthreads();
     load_w(Wb);            // in flight during conv1
 
     // ---- conv1: rows = output channels (weights are operand A), cols = region pixels --------
     {
-        ConvStage<XROW, R1W, R1W, P1, G::NMT1, true> st;
-        st.init(wj, j, h);
-        st.run(Xs, Ws, wj, h, kh);
+        typedef ConvStage<XROW, R1W, R1W, P1, G::NMT1> Stage;
+        Stage st;
+        const bool live = Stage::live(wave);
+        const int me = Stage::tg(wave);
+        if (live) {
+            st.init(wave, j, h);
+            st.run(Xs, Ws, h);
+        }
         __syncthreads();                       // Wa is dead: its LDS area becomes reduction scratch
-        if (kh == 1) st.park(reinterpret_cast<float*>(Ws), wj, lane);
+        if (live) st.park(reinterpret_cast<float*>(Ws), wave, lane);
         __syncthreads();
-        if (kh == 0) st.gather(reinterpret_cast<const float*>(Ws), wj, lane);
-        // epilogue: bias + ReLU, zero outside the image, bf16 -> Ts[pixel][channel]
+        if (live) {
+            st.gather(reinterpret_cast<const float*>(Ws), wave, lane);
+            // epilogue of the owned groups: bias + ReLU, zero outside the image, bf16 -> Ts[pixel][channel]
+            const int m = Stage::tile(wave) * 32 + j;
+            if (m < P1) {
+                const int y = oh0 - 1 + m / R1W, x = ow0 - 1 + m % R1W;
+                const bool inside = y >= 0 && y < H && x >= 0 && x < W;
 #pragma unroll
-        for (int i = 0; i < st.J; ++i) {
-            if (kh != 0 || !st.live(i, wj)) continue;
-            const int m = st.tile(i, wj) * 32 + j, ot = st.nt(i, wj);
-            if (m >= P1) continue;
-            const int y = oh0 - 1 + m / R1W, x = ow0 - 1 + m % R1W;
-            const bool inside = y >= 0 && y < H && x >= 0 && x < W;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int o = ot * 32 + 8 * g + 4 * h;
-                uint2 v = make_uint2(0, 0);
-                if (inside) {
-                    const float4 bv = *reinterpret_cast<const float4*>(Bias + o);
-                    v = make_uint2(pack_bf16(fmaxf(st.acc[i][4 * g] + bv.x, 0.f), fmaxf(st.acc[i][4 * g + 1] + bv.y, 0.f)),
-                                   pack_bf16(fmaxf(st.acc[i][4 * g + 2] + bv.z, 0.f), fmaxf(st.acc[i][4 * g + 3] + bv.w, 0.f)));
+                for (int grp = 0; grp < 8; ++grp) {
+                    if (Stage::owner_of(grp) != me) continue;
+                    const int ot = grp >> 2, g = grp & 3;
+                    const int o = ot * 32 + 8 * g + 4 * h;
+                    uint2 v = make_uint2(0, 0);
+                    if (inside) {
+                        const float4 bv = *reinterpret_cast<const float4*>(Bias + o);
+                        v = make_uint2(pack_bf16(fmaxf(st.acc[ot][4 * g] + bv.x, 0.f), fmaxf(st.acc[ot][4 * g + 1] + bv.y, 0.f)),
+                                       pack_bf16(fmaxf(st.acc[ot][4 * g + 2] + bv.z, 0.f), fmaxf(st.acc[ot][4 * g + 3] + bv.w, 0.f)));
+                    }
+                    *reinterpret_cast<uint2*>(Ts + (m / R1W) * TROW + (m % R1W) * LD + o) = v;
                 }
-                *reinterpret_cast<uint2*>(Ts + (m / R1W) * TROW + (m % R1W) * LD + o) = v;
             }
         }
     }
     __syncthreads();       // Ts complete, reduction scratch no longer read
-    store_w();             // Wb -> LDS
+    store_w(Wb);           // Wb -> LDS
     __syncthreads();
 
     // ---- conv2: rows = output channels, cols = output pixels --------------------------------
     {
-        ConvStage<TROW, P2W, TW, P2, G::NMT2, true> st;
-        st.init(wj, j, h);
-        st.run(Ts, Ws, wj, h, kh);
+        typedef ConvStage<TROW, P2W, TW, P2, G::NMT2> Stage;
+        Stage st;
+        const bool live = Stage::live(wave);
+        const int me = Stage::tg(wave);
+        if (live) {
+            st.init(wave, j, h);
+            st.run(Ts, Ws, h);
+        }
         __syncthreads();
-        if (kh == 1) st.park(reinterpret_cast<float*>(Ws), wj, lane);
+        if (live) st.park(reinterpret_cast<float*>(Ws), wave, lane);
         __syncthreads();
-        if (kh == 0) st.gather(reinterpret_cast<const float*>(Ws), wj, lane);
-        // epilogue: lane = pixel, registers = 4 consecutive channels: bias, residual, ReLU, 8-byte stores
-#pragma unroll
-        for (int i = 0; i < st.J; ++i) {
-            if (kh != 0 || !st.live(i, wj)) continue;
-            const int m = st.tile(i, wj) * 32 + j, ot = st.nt(i, wj);
+        if (live) {
+            st.gather(reinterpret_cast<const float*>(Ws), wave, lane);
+            // epilogue of the owned groups: lane = pixel, 4 consecutive channels per group: bias, residual,
+            // ReLU, 8-byte stores
+            const int m = Stage::tile(wave) * 32 + j;
             const int py = m / P2W, px = m % P2W;
             const int y = oh0 + py, x = ow0 + px;
-            if (m >= P2 || px >= TW || y >= H || x >= W) continue;
+            if (m < P2 && px < TW && y < H && x < W) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int o = ot * 32 + 8 * g + 4 * h;
-                float4 v = make_float4(st.acc[i][4 * g], st.acc[i][4 * g + 1], st.acc[i][4 * g + 2], st.acc[i][4 * g + 3]);
-                const float4 bv = *reinterpret_cast<const float4*>(Bias + 64 + o);
-                v.x += bv.x; v.y += bv.y; v.z += bv.z; v.w += bv.w;
-                if (residual) {
-                    const uint2 xr = *reinterpret_cast<const uint2*>(Xs + (py + 2) * XROW + (px + 2) * LD + o);
-                    v.x += lo_bf16(xr.x); v.y += hi_bf16(xr.x); v.z += lo_bf16(xr.y); v.w += hi_bf16(xr.y);
+                for (int grp = 0; grp < 8; ++grp) {
+                    if (Stage::owner_of(grp) != me) continue;
+                    const int ot = grp >> 2, g = grp & 3;
+                    const int o = ot * 32 + 8 * g + 4 * h;
+                    float4 v = make_float4(st.acc[ot][4 * g], st.acc[ot][4 * g + 1], st.acc[ot][4 * g + 2], st.acc[ot][4 * g + 3]);
+                    const float4 bv = *reinterpret_cast<const float4*>(Bias + 64 + o);
+                    v.x += bv.x; v.y += bv.y; v.z += bv.z; v.w += bv.w;
+                    if (residual) {
+                        const uint2 xr = *reinterpret_cast<const uint2*>(Xs + (py + 2) * XROW + (px + 2) * LD + o);
+                        v.x += lo_bf16(xr.x); v.y += hi_bf16(xr.x); v.z += lo_bf16(xr.y); v.w += hi_bf16(xr.y);
+                    }
+                    *reinterpret_cast<uint2*>(Y + ((long)y * W + x) * C + o) =
+                        make_uint2(pack_bf16(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f)), pack_bf16(fmaxf(v.z, 0.f), fmaxf(v.w, 0.f)));
                 }
-                *reinterpret_cast<uint2*>(Y + ((long)y * W + x) * C + o) =
-                    make_uint2(pack_bf16(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f)), pack_bf16(fmaxf(v.z, 0.f), fmaxf(v.w, 0.f)));
             }
         }
     }
