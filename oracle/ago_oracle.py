@@ -195,6 +195,18 @@ def attn(q, k, v, scale_=0.125):
     return o
 
 
+def attn_bias(q, k, v, b, scale_=0.125):
+    """softmax_rows(scale * q k^T + b) v: the attention chain of Sec. VI-C with one more simple operator
+    (an elementwise add of a bias / mask) between the two products.  b broadcasts over the batch and
+    head dimensions: b:[Bb,Hb,S,S] with Bb in {1, B}, Hb in {1, Hh}."""
+    q, k, v, b = _c(q), _c(k), _c(v), _c(b)
+    bq, hh, s, _ = q.shape
+    assert b.shape[0] in (1, bq) and b.shape[1] in (1, hh) and b.shape[2:] == (s, s)
+    sc = scale(bmm_nt(q, k), scale_)
+    sc = add(sc, np.ascontiguousarray(np.broadcast_to(b, sc.shape)))
+    return bmm_nn(softmax_rows(sc), v)
+
+
 # ---- two-operator pairs (Sec. VI, Fig. 13): the operators above called one after another --------
 
 def pw_dw(x, w1, b1, wd, bd, stride=1):
@@ -262,6 +274,8 @@ def run_case(case):
         return conv_chain(t["x"], t["wa"], t["ba"], t["wb"], t["bb"], case.residual)
     if kind == "FfnCase":
         return ffn(t["x"], t["w1"], t["b1"], t["w2"], t["b2"])
+    if kind == "AttnCase" and case.bias != "none":
+        return attn_bias(t["q"], t["k"], t["v"], t["bias"], case.scale)
     if kind == "AttnCase":
         return attn(t["q"], t["k"], t["v"], case.scale)
     raise TypeError(kind)

@@ -196,6 +196,56 @@ def test_attn_brute(oracle):
     np.testing.assert_allclose(oracle.attn(q, k, v, 0.5), ref, rtol=0, atol=1e-13)
 
 
+def test_attn_bias_brute(oracle):
+    # bias [1, Hh, S, S] broadcast over the batch, added after the scale and before the softmax
+    b, hh, s, d = 2, 2, 5, 3
+    q, k, v = _tiny(43, (b, hh, s, d), -2, 2), _tiny(44, (b, hh, s, d), -2, 2), _tiny(45, (b, hh, s, d))
+    bs = _tiny(46, (1, hh, s, s), -3, 3)
+    ref = np.zeros((b, hh, s, d))
+    for bi in range(b):
+        for h in range(hh):
+            for i in range(s):
+                sc = [0.5 * sum(q[bi, h, i, t] * k[bi, h, j, t] for t in range(d)) + bs[0, h, i, j] for j in range(s)]
+                den = sum(math.exp(z) for z in sc)
+                for t in range(d):
+                    ref[bi, h, i, t] = sum(math.exp(sc[j]) / den * v[bi, h, j, t] for j in range(s))
+    np.testing.assert_allclose(oracle.attn_bias(q, k, v, bs, 0.5), ref, rtol=0, atol=1e-13)
+
+
+def test_attn_bias_properties(oracle):
+    def attn_kv(q_, k_, v_, c):       # the chain with a key count that differs from the query count
+        return oracle.bmm_nn(oracle.softmax_rows(oracle.scale(oracle.bmm_nt(q_, k_), c)), v_)
+
+    b, hh, s, d = 2, 2, 7, 4
+    q, k, v = _tiny(94, (b, hh, s, d), -2, 2), _tiny(95, (b, hh, s, d), -2, 2), _tiny(96, (b, hh, s, d))
+    o = oracle.attn(q, k, v, 0.5)
+    # a zero bias, and a bias that is constant along every row (softmax is shift invariant), change nothing
+    np.testing.assert_allclose(oracle.attn_bias(q, k, v, np.zeros((1, 1, s, s)), 0.5), o, rtol=0, atol=1e-14)
+    rows = np.broadcast_to(_tiny(97, (b, hh, s, 1), -4, 4), (b, hh, s, s))
+    np.testing.assert_allclose(oracle.attn_bias(q, k, v, rows, 0.5), o, rtol=0, atol=1e-13)
+    # a large negative bias on some keys removes them: the result is attention over the remaining keys
+    keep = np.array([0, 2, 3, 6])
+    mask = np.full((1, 1, s, s), -1e4)
+    mask[..., keep] = 0.0
+    np.testing.assert_allclose(oracle.attn_bias(q, k, v, mask, 0.5),
+                               attn_kv(q, k[:, :, keep], v[:, :, keep], 0.5), rtol=0, atol=1e-13)
+    # a bias of +log(2) on one key weighs it twice: the same as listing that key (and its value) twice
+    dup = np.zeros((1, 1, s, s))
+    dup[..., 4] = math.log(2.0)
+    k2, v2 = np.concatenate([k, k[:, :, 4:5]], 2), np.concatenate([v, v[:, :, 4:5]], 2)
+    np.testing.assert_allclose(oracle.attn_bias(q, k, v, dup, 0.5), attn_kv(q, k2, v2, 0.5), rtol=0, atol=1e-13)
+    # the bias is not scaled: doubling the scale and halving q leaves the result alone only because
+    # the bias stays outside the product
+    bs = _tiny(98, (b, 1, s, s), -2, 2)
+    np.testing.assert_allclose(oracle.attn_bias(0.5 * q, k, v, bs, 1.0), oracle.attn_bias(q, k, v, bs, 0.5),
+                               rtol=0, atol=1e-13)
+    # per-batch bias [B, 1, S, S]: batch 1's bias must not leak into batch 0
+    bs2 = bs.copy()
+    bs2[1] += _tiny(99, (1, s, s), -1, 1)
+    np.testing.assert_allclose(oracle.attn_bias(q, k, v, bs2, 0.5)[0], oracle.attn_bias(q, k, v, bs, 0.5)[0],
+                               rtol=0, atol=0)
+
+
 # --------------------------------------------------------------------------
 # delta / identity weights
 # --------------------------------------------------------------------------

@@ -126,12 +126,17 @@ class FfnCase:
 
 @dataclass
 class AttnCase:
-    """o = softmax_rows(scale * q k^T) v per (batch, head); q,k,v,o:[B,Hh,S,D]."""
+    """o = softmax_rows(scale * q k^T [+ bias]) v per (batch, head); q,k,v,o:[B,Hh,S,D].
+
+    bias: "none"; "full" = [B,Hh,S,S] random; "head" = [1,Hh,S,S] random (a relative-position table
+    shared by the batch); "batch" = [B,1,S,S] key-padding mask (0 for the first len_b keys of batch b,
+    -10000 for the rest, len_b seeded in [S/2, S])."""
     B: int; Hh: int; S: int; D: int
     scale: float = 0.125
     dtype: str = "bf16"
     seed: int = _SEED0 + 64
     name: str = "attn"
+    bias: str = "none"
 
     def flops(self):
         return 2 * 2 * self.B * self.Hh * self.S * self.S * self.D
@@ -143,11 +148,24 @@ class AttnCase:
     def tensors(self):
         s, d = self.seed, self.dtype
         shp = (self.B, self.Hh, self.S, self.D)
-        return {
+        t = {
             "q": _store(rng.normal(s + 0, shp, 1.0), d),
             "k": _store(rng.normal(s + 1, shp, 1.0), d),
             "v": _store(rng.normal(s + 2, shp, 1.0), d),
         }
+        if self.bias == "full":
+            t["bias"] = _store(rng.normal(s + 3, (self.B, self.Hh, self.S, self.S), 1.0), d)
+        elif self.bias == "head":
+            t["bias"] = _store(rng.normal(s + 3, (1, self.Hh, self.S, self.S), 1.0), d)
+        elif self.bias == "batch":
+            lens = self.S // 2 + (rng.uniform(s + 3, (self.B,), 0.0, 1.0) * (self.S - self.S // 2 + 1)).astype(np.int64)
+            lens = np.minimum(lens, self.S)
+            keys = np.arange(self.S)[None, None, None, :]
+            m = np.where(keys < lens[:, None, None, None], 0.0, -10000.0)
+            t["bias"] = _store(np.broadcast_to(m, (self.B, 1, self.S, self.S)).copy(), d)
+        elif self.bias != "none":
+            raise ValueError(self.bias)
+        return t
 
 
 BASELINE_NAMES = ["invres_14x14x32_f32", "invres_56x56x24_s2_bf16", "chain_8x56x56x64_bf16",
