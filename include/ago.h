@@ -152,6 +152,22 @@ ago_status ago_fused_attn_strided(const void* q, const void* k, const void* v, v
                                   float scale, ago_dtype dt,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The attention chain with one more simple operator between the products (Sec. VI-C: the chain is
+ * matmul -> simple operators -> matmul): an elementwise add of a bias or mask ahead of the softmax,
+ *   o = softmax_rows(scale * q k^T + bias) v
+ * q,k,v,o:[B,Hh,S,D] contiguous, bf16, D = 64.  bias (device, bf16): element (b, h, i, j) at
+ * bias[b * bias_stride_b + h * bias_stride_h + i * S + j]; a stride of 0 broadcasts over that
+ * dimension (a [1,Hh,S,S] relative-position table, a [B,1,S,S] padding mask), otherwise
+ * bias_stride_h >= S*S and bias_stride_b >= Hh * bias_stride_h (else SHAPE).  The bias is not scaled.
+ * Large negative finite values (or -inf) mask keys; a row whose keys are all -inf is undefined (NaN).
+ * Rows are fetched with 16-byte loads when S and both strides are multiples of 8 and the base is
+ * 16-byte aligned, element by element otherwise. */
+ago_status ago_fused_attn_bias(const void* q, const void* k, const void* v, const void* bias, void* o,
+                               int B, int Hh, int S, int D,
+                               long long bias_stride_b, long long bias_stride_h,
+                               float scale, ago_dtype dt,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------------- */
 /* Un-fused per-operator kernels (Sec. III-A).  With bias == NULL and           */
 /* act == AGO_ACT_NONE each is exactly one operator (Fig. 3); with a bias /     */

@@ -52,6 +52,7 @@ _SIGS = {
     "ago_unfused_invres": [_vp] * 8 + [_i] * 10 + [_vp, _sz, _vp],
     "ago_unfused_conv_chain": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
     "ago_unfused_ffn": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
+    "ago_fused_attn_bias": [_vp] * 5 + [_i] * 4 + [ctypes.c_longlong] * 2 + [_f, _i, _vp, _sz, _vp],
     "ago_unfused_attn": [_vp] * 4 + [_i] * 4 + [_f, _i, _i, _vp, _sz, _vp],
 }
 for _name, _args in _SIGS.items():
@@ -236,6 +237,20 @@ def ago_fused_attn(q, k, v, o, scale, workspace=None):
     B, Hh, S, D = q.shape
     wp, wb = _ws(workspace)
     return lib.ago_fused_attn, (_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q), wp, wb, _stream())
+
+
+@_entry
+def ago_fused_attn_bias(q, k, v, bias, o, scale, workspace=None):
+    """bias: [Bb, Hb, S, S] with Bb in (1, B) and Hb in (1, Hh); size-1 dimensions broadcast."""
+    B, Hh, S, D = q.shape
+    Bb, Hb = bias.shape[:2]
+    if Bb not in (1, B) or Hb not in (1, Hh) or tuple(bias.shape[2:]) != (S, S) or not bias.is_contiguous():
+        raise ValueError("bias must be a contiguous [1|B, 1|Hh, S, S] tensor")
+    sh = S * S if Hb > 1 else 0
+    sb = Hb * S * S if Bb > 1 else 0
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_attn_bias, (_p(q), _p(k), _p(v), _p(bias), _p(o), B, Hh, S, D, sb, sh, float(scale),
+                                     _dt(q), wp, wb, _stream())
 
 
 @_entry

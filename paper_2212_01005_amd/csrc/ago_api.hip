@@ -404,6 +404,23 @@ ago_status ago_fused_attn_strided(const void* q, const void* k, const void* v, v
                                (long)stride_b, (long)stride_h, (long)stride_s));
 }
 
+ago_status ago_fused_attn_bias(const void* q, const void* k, const void* v, const void* bias, void* o, int B,
+                               int Hh, int S, int D, long long bias_stride_b, long long bias_stride_h,
+                               float scale, ago_dtype dt, void* workspace, size_t workspace_bytes,
+                               void* hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    ago_status st = check_attn(q, k, v, o, B, Hh, S, D, scale, dt);
+    if (st != AGO_OK) return st;
+    if (!bias) return AGO_ERR_NULL;
+    // a stride is 0 (broadcast) or at least the extent below it
+    const long long plane = (long long)S * S;
+    if (bias_stride_h != 0 && bias_stride_h < plane) return AGO_ERR_SHAPE;
+    if (bias_stride_b != 0 && bias_stride_b < (bias_stride_h ? bias_stride_h * Hh : plane)) return AGO_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(bias) % 2) return AGO_ERR_ALIGN;
+    return from_hip(fused_attn_bias(q, k, v, bias, o, B, Hh, S, (long)bias_stride_b, (long)bias_stride_h, scale,
+                                    tile_config(AGO_OP_FUSED_ATTN), as_stream(hip_stream)));
+}
+
 ago_status ago_unfused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
                             int D, float scale, ago_dtype dt, int epilogue_fused, void* workspace,
                             size_t workspace_bytes, void* s) {

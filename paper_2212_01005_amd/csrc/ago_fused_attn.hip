@@ -53,11 +53,15 @@ __device__ __forceinline__ bf16x8 lds_read_vt(const lds_byte* p) {
 }
 }  // namespace
 
-template <int NQT, int NSTG>
-__global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per_eu(3, 4))) void fused_attn_kernel(
+// HAS_BIAS: an additive term between the scale and the softmax, Bias[b * bias_sb + hh * bias_sh + q * S + key]
+// (a stride of 0 broadcasts over that dimension).  Each lane fetches the 32 values of its query row and
+// its keys straight from global memory before the block's first product, so the loads overlap it.
+template <int NQT, int NSTG, int BIAS /* 0 none, 1 rows by 16-byte loads, 2 element by element */>
+__global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per_eu(BIAS == 2 ? 2 : (BIAS == 1 ? 4 : 3), 4))) void fused_attn_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, int S, int heads, int qblocks, int Hh, long stride_b, long stride_h, long stride_s,
-    float c /* scale * log2(e) */) {
+    float c /* scale * log2(e) */, const bf16_t* __restrict__ Bias, long bias_sb, long bias_sh) {
+    constexpr bool HAS_BIAS = BIAS != 0;
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_byte* smem = (lds_byte*)smem_generic;          // [2 buffers][K block | V block]
     const int tid = threadIdx.x, lane = tid & 63;
@@ -145,11 +149,52 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
 #pragma unroll
     for (int r = 0; r < 16; ++r) { o[0][r] = 0.f; o[1][r] = 0.f; }
     float m = -INFINITY, l = 0.f;     // running max of scaled scores, running (per-half) sum
+    // with a bias the scores are rescaled (and biased) once, ahead of the max; without, the scale rides
+    // in the exponent's multiply-add
+    const float ce = HAS_BIAS ? 1.f : c;
+    const bf16_t* brow = nullptr;
+    if constexpr (HAS_BIAS)
+        brow = Bias + (long)(head / Hh) * bias_sb + (long)(head % Hh) * bias_sh + (long)min(q_row, S - 1) * S;
 
+    // Bias values of the lane's query row: register group gq of key tile kt covers the 4 consecutive
+    // keys 4 h + 8 gq (+ 32 kt + 64 kh).  BIAS == 1 (S % 8 == 0, 16-byte aligned rows): lane (j, h) loads
+    // the 8 keys 16 p + 8 h .. + 7 in one 16-byte access; its low half belongs to the h = 0 lane and its
+    // high half to the h = 1 lane, so one swap of 32-lane halves per register pair (done when the values
+    // are used) hands every lane its groups 2 p and 2 p + 1.  A chunk beyond S is clamped to the row's
+    // last chunk (those keys are masked).  The loads are issued ahead of the block's first product; holding
+    // them a whole iteration ahead would cost the 16 registers that separate 4 waves per SIMD from 3.
+    uint4 bw[2][2];
+    auto load_bias = [&](int blk) {
+        const int key_wave = blk * kKB + 64 * kh;
+        if constexpr (BIAS == 1) {
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int pr = 0; pr < 2; ++pr)
+                    bw[kt][pr] = ld_u4(brow + min(key_wave + kt * 32 + 16 * pr + 8 * h, S - 8));
+        } else {
+            const unsigned short* be = reinterpret_cast<const unsigned short*>(brow);
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int pr = 0; pr < 2; ++pr) {
+                    unsigned e8[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int key = key_wave + 4 * h + kt * 32 + 16 * pr + 8 * (e >> 2) + (e & 3);
+                        e8[e] = be[min(key, S - 1)];
+                    }
+                    bw[kt][pr] = make_uint4(e8[0] | (e8[1] << 16), e8[2] | (e8[3] << 16), e8[4] | (e8[5] << 16),
+                                            e8[6] | (e8[7] << 16));
+                }
+        }
+    };
     __builtin_amdgcn_s_barrier();     // block 0 is in LDS
     for (int blk = 0; blk < nblk; ++blk) {
         const lds_byte* kb = smem + (blk % NSTG) * 2 * kBlockB;
         const lds_byte* vb = kb + kBlockB;
+
+        if constexpr (HAS_BIAS) load_bias(blk);     // in flight across the first product
 
         f32x16 sc[2];
 #pragma unroll
@@ -162,6 +207,27 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
             for (int kt = 0; kt < 2; ++kt)
                 sc[kt] = mfma32(lds_read16(kb + koff + kt * 32 * 128 + (((2 * ks + h) ^ ksw) << 4)), qf[ks], sc[kt]);
 
+        if constexpr (HAS_BIAS) {
+            constexpr float kLog2e = 1.4426950408889634f;
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int pr = 0; pr < 2; ++pr) {
+                    uint4 w = bw[kt][pr];
+                    if constexpr (BIAS == 1) {
+                        const auto s0 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
+                        const auto s1 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
+                        w = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+                    }
+                    const unsigned raw[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int r = 8 * pr + 2 * e;                  // registers r, r + 1 of key tile kt
+                        sc[kt][r] = fmaf(sc[kt][r], c, __uint_as_float(raw[e] << 16) * kLog2e);
+                        sc[kt][r + 1] = fmaf(sc[kt][r + 1], c, __uint_as_float(raw[e] & 0xffff0000u) * kLog2e);
+                    }
+                }
+        }
         // mask keys beyond S (only a block that straddles S needs it; the test is wave-uniform)
         if ((blk + 1) * kKB > S) {
             const int key_base = blk * kKB + 64 * kh + 4 * h;
@@ -180,7 +246,7 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
 #pragma unroll
             for (int r = 0; r < 16; r += 2) mx = fmaxf(fmaxf(sc[kt][r], sc[kt][r + 1]), mx);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m, mx * c);
+        const float m_new = fmaxf(m, mx * ce);
         // a half whose keys are all beyond S so far keeps m = -inf: subtract 0 instead (exp2(-inf) = 0)
         const float mref = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m - mref);
@@ -196,7 +262,7 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float pv = __builtin_amdgcn_exp2f(fmaf(sc[kt][8 * u + e], c, -mref));
+                    const float pv = __builtin_amdgcn_exp2f(fmaf(sc[kt][8 * u + e], ce, -mref));
                     l += pv;
                     pf[kt][u][e] = (bf16_t)pv;
                 }
@@ -226,7 +292,7 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
     __syncthreads();
     if (kh == 0) {
         const float m1 = park[lane], l1 = park[64 + lane];
-        const float mt = fmaxf(m, m1);                 // finite: key 0 belongs to half 0
+        const float mt = fmaxf(m, m1);                 // finite unless a bias of -inf covers the whole row
         const float a0 = __builtin_amdgcn_exp2f(m - mt), a1 = __builtin_amdgcn_exp2f(m1 - mt);
         const float inv = 1.0f / (l * a0 + l1 * a1);
         const float w0 = a0 * inv, w1 = a1 * inv;
@@ -247,12 +313,18 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
     }
 }
 
-template <int NQT, int NSTG>
+struct AttnBias {
+    const void* ptr;
+    long sb, sh;      // element strides over batch and head, 0 = broadcast
+};
+
+template <int NQT, int NSTG, int BIAS>
 static hipError_t launch_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
-                              long stride_b, long stride_h, long stride_s, float scale, hipStream_t s) {
+                              long stride_b, long stride_h, long stride_s, float scale, hipStream_t s,
+                              AttnBias bias = AttnBias{nullptr, 0, 0}) {
     constexpr size_t smem = (size_t)NSTG * 2 * kBlockB;    // ring of (K block, V block) buffers; the merge reuses them
     static_assert((size_t)NQT * 34 * 64 * 4 <= smem, "merge scratch");
-    auto kern = fused_attn_kernel<NQT, NSTG>;
+    auto kern = fused_attn_kernel<NQT, NSTG, BIAS>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -266,7 +338,7 @@ static hipError_t launch_attn(const void* q, const void* k, const void* v, void*
     prof_shape(3, grid.x, (2 * NQT + 2) * 64);
     hipLaunchKernelGGL(kern, grid, dim3((2 * NQT + 2) * 64), smem, s, (const bf16_t*)q, (const bf16_t*)k,
                        (const bf16_t*)v, (bf16_t*)o, S, heads, qblocks, Hh, stride_b, stride_h, stride_s,
-                       scale * 1.4426950408889634f);
+                       scale * 1.4426950408889634f, (const bf16_t*)bias.ptr, bias.sb, bias.sh);
     prof_stop(3, s);
     return hipGetLastError();
 }
@@ -285,11 +357,36 @@ hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int 
         tile_cfg = (S > 96 && wgs >= 128) ? 3 : 0;
     }
     switch (tile_cfg) {
-        case 1: return launch_attn<4, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
-        case 2: return launch_attn<2, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
-        case 3: return launch_attn<6, 3>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
-        default: return launch_attn<3, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
+        case 1: return launch_attn<4, 2, 0>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
+        case 2: return launch_attn<2, 2, 0>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
+        case 3: return launch_attn<6, 3, 0>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
+        default: return launch_attn<3, 2, 0>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
     }
+}
+
+// The chain with an additive bias / mask ahead of the softmax; q, k, v, o contiguous [B][Hh][S][D].
+hipError_t fused_attn_bias(const void* q, const void* k, const void* v, const void* bias, void* o, int B, int Hh,
+                           int S, long bias_sb, long bias_sh, float scale, int tile_cfg, hipStream_t s) {
+    const long stride_b = (long)Hh * S * kD, stride_h = (long)S * kD, stride_s = kD;
+    const AttnBias bs{bias, bias_sb, bias_sh};
+    // Two LDS buffers throughout (the third costs the registers that the bias values need); the
+    // element-by-element variant needs more registers still and runs configuration 3 as configuration 1.
+    if (tile_cfg < 0) {
+        const long wgs = (long)((S + 191) / 192) * B * Hh;
+        tile_cfg = (S > 96 && wgs >= 128) ? 3 : 0;
+    }
+    // 16-byte loads of 8 bias values need every row start 16-byte aligned
+    const bool vec = S % 8 == 0 && bias_sb % 8 == 0 && bias_sh % 8 == 0 && reinterpret_cast<uintptr_t>(bias) % 16 == 0;
+#define AGO_ATTN_BIAS_CASE(NQT, NQT_E)                                                                        \
+    return vec ? launch_attn<NQT, 2, 1>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s, bs)     \
+               : launch_attn<NQT_E, 2, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s, bs)
+    switch (tile_cfg) {
+        case 1: AGO_ATTN_BIAS_CASE(4, 4);
+        case 2: AGO_ATTN_BIAS_CASE(2, 2);
+        case 3: AGO_ATTN_BIAS_CASE(6, 4);
+        default: AGO_ATTN_BIAS_CASE(3, 3);
+    }
+#undef AGO_ATTN_BIAS_CASE
 }
 
 }  // namespace ago

@@ -90,6 +90,8 @@ def _fused_call(case, t, y, ws):
         return ago.ago_fused_conv_chain, (t["x"], t["wa"], t["ba"], t["wb"], t["bb"], y, case.residual, ws)
     if k == "FfnCase":
         return ago.ago_fused_ffn, (t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, ago.ACT_GELU_TANH, ws)
+    if case.bias != "none":
+        return ago.ago_fused_attn_bias, (t["q"], t["k"], t["v"], t["bias"], y, case.scale, ws)
     return ago.ago_fused_attn, (t["q"], t["k"], t["v"], y, case.scale, ws)
 
 

@@ -84,6 +84,14 @@ def test_pair_entry_points_validate_before_any_gpu_call(lib):
     assert att(25600, 64, 32) == 2                                        # rows would overlap
     assert att(25600, 60, 256) == 4                                       # row starts must stay 16-byte aligned
     assert att(25600, 64, 256, D=32) == 5                                 # head dimension other than 64
+    lib.ago_fused_attn_bias.argtypes = [vp] * 5 + [ci] * 4 + [ll] * 2 + [ctypes.c_float, ci, vp, sz, vp]
+    atb = lambda sb, sh, bias=p, S=100: lib.ago_fused_attn_bias(p, p, p, bias, p, 2, 4, S, 64, sb, sh, 0.125, 1, None, 0, None)
+    assert atb(0, 0, bias=None) == 1                                      # the bias is not optional here
+    assert atb(0, 9999) == 2                                              # head stride below one [S][S] plane
+    assert atb(30000, 10000) == 2                                         # batch stride below Hh planes
+    assert atb(9999, 0) == 2                                              # batch stride below one plane
+    assert atb(0, 0, bias=_fake(0x1001)) == 4                             # bf16 elements are 2-byte aligned
+    assert atb(0, 0, S=0) == 2
     from paper_2212_01005_amd import binding as ago
     # the pair's workspace is the FFN chain's on N*H*W rows
     assert ago.workspace_bytes(ago.OP_FUSED_PW_PW, [1, 8, 8, 64, 768, 128], ago.BF16) == \

@@ -146,6 +146,41 @@ def test_attention_strided_layout(gpu, oracle):
         assert_close(runner.to_numpy64(o.permute(0, 2, 1, 3)), ref, "bf16", case.name)
 
 
+def test_attention_bias(gpu, oracle):
+    """softmax(scale q k^T + bias) v: every bias broadcast kind, 16-byte and element-wise row loads (S % 8),
+    ragged key blocks, every tile configuration, and the benchmark's shape with a per-head table."""
+    torch, ago, runner = gpu
+    cases = [wl.AttnCase(2, 2, 200, 64, 0.125, "bf16", 6200, name="attn_bias_full_s200", bias="full"),
+             wl.AttnCase(2, 4, 384, 64, 0.125, "bf16", 6201, name="attn_bias_head_s384", bias="head"),
+             wl.AttnCase(3, 2, 130, 64, 0.3, "bf16", 6202, name="attn_bias_mask_s130", bias="batch"),
+             wl.AttnCase(1, 3, 77, 64, 0.125, "bf16", 6203, name="attn_bias_full_s77", bias="full"),
+             wl.AttnCase(1, 2, 600, 64, 0.125, "bf16", 6204, name="attn_bias_head_s600", bias="head"),
+             wl.AttnCase(1, 1, 1, 64, 0.125, "bf16", 6205, name="attn_bias_s1", bias="full"),
+             wl.AttnCase(8, 12, 384, 64, 0.125, "bf16", 6206, name="attn_bias_head_8x12x384", bias="head")]
+    for case in cases:
+        ref = oracle.run_case(case)
+        t = runner.to_device(case)
+        cfgs = [-1] if case.B * case.Hh > 16 else [-1, 0, 1, 2, 3]
+        try:
+            for cfg in cfgs:
+                ago.set_tile_config(ago.OP_FUSED_ATTN, cfg)
+                o = torch.zeros_like(t["q"])
+                ago.ago_fused_attn_bias(t["q"], t["k"], t["v"], t["bias"], o, case.scale)
+                torch.cuda.synchronize()
+                assert_close(runner.to_numpy64(o), ref, "bf16", "%s cfg %d" % (case.name, cfg))
+        finally:
+            ago.set_tile_config(ago.OP_FUSED_ATTN, -1)
+    # a zero bias reproduces the plain chain bit for bit apart from the order of the scale multiply
+    case = wl.AttnCase(2, 3, 200, 64, 0.125, "bf16", 6210, name="attn_bias_zero")
+    t = runner.to_device(case)
+    o0, o1 = torch.zeros_like(t["q"]), torch.zeros_like(t["q"])
+    ago.ago_fused_attn(t["q"], t["k"], t["v"], o0, case.scale)
+    ago.ago_fused_attn_bias(t["q"], t["k"], t["v"], torch.zeros(1, 1, 200, 200, dtype=torch.bfloat16, device="cuda:0"),
+                            o1, case.scale)
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(o1), runner.to_numpy64(o0), "bf16", "zero bias vs plain")
+
+
 # ---- seeded random shapes --------------------------------------------------------------------
 
 def _random_cases():
