@@ -74,6 +74,29 @@ void ago_oracle_dwconv3x3(const double* x, const double* w, double* y,
             }
 }
 
+/* Depthwise R x R for odd R (the 5x5 depthwise layers of the MNasNet-style blocks among the paper's
+ * mobile networks, Sec. VI), zero pad (R-1)/2, stride st:
+ * y[n][oh][ow][c] = sum_{r,s} xpad[n][oh*st + r - pad][ow*st + s - pad][c] w[r][s][c] */
+void ago_oracle_dwconv(const double* x, const double* w, double* y,
+                       int N, int H, int W, int C, int st, int R) {
+    const int pad = (R - 1) / 2;
+    const int OH = (H + 2 * pad - R) / st + 1, OW = (W + 2 * pad - R) / st + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int oh = 0; oh < OH; ++oh)
+            for (int ow = 0; ow < OW; ++ow)
+                for (int c = 0; c < C; ++c) {
+                    double acc = 0.0;
+                    for (int r = 0; r < R; ++r)
+                        for (int s = 0; s < R; ++s) {
+                            const int ih = oh * st + r - pad, iw = ow * st + s - pad;
+                            if (ih >= 0 && ih < H && iw >= 0 && iw < W)
+                                acc += x[(((long)n * H + ih) * W + iw) * C + c] * w[((long)r * R + s) * C + c];
+                        }
+                    y[(((long)n * OH + oh) * OW + ow) * C + c] = acc;
+                }
+}
+
 /* Dense 3x3 convolution, zero pad 1, stride 1 (Fig. 3 with R = C = 3).
  * y[n][h][w][o] = sum_{r,s,c} xpad[n][h+r-1][w+s-1][c] wt[r][s][c][o] */
 void ago_oracle_conv3x3(const double* x, const double* wt, double* y,

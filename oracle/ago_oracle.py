@@ -77,6 +77,18 @@ def dwconv3x3(x, w, stride=1):
     return y
 
 
+def dwconv(x, w, stride=1):
+    """Depthwise R x R, odd R = w.shape[0], zero pad (R - 1) / 2."""
+    x, w = _c(x), _c(w)
+    n, h, wd, c = x.shape
+    r = w.shape[0]
+    assert r % 2 == 1 and w.shape == (r, r, c)
+    oh, ow = (h - 1) // stride + 1, (wd - 1) // stride + 1
+    y = np.empty((n, oh, ow, c), dtype=np.float64)
+    lib().ago_oracle_dwconv(_p(x), _p(w), _p(y), n, h, wd, c, stride, r)
+    return y
+
+
 def conv3x3(x, w):
     x, w = _c(x), _c(w)
     n, h, wd, cin = x.shape
@@ -161,6 +173,20 @@ def invres(x, w1, b1, wd, bd, w2, b2, stride=1, residual=False):
                                  n, h, w, cin, cexp, cout, stride, int(bool(residual)))
     assert rc == 0
     return y
+
+
+def invres_k(x, w1, b1, wd, bd, w2, b2, stride=1, residual=False):
+    """The block with an R x R depthwise (R = wd.shape[0]): the operators called one after another."""
+    e = conv1x1(x, w1)
+    if b1 is not None:
+        e = bias(e, b1)
+    d = dwconv(relu6(e), wd, stride)
+    if bd is not None:
+        d = bias(d, bd)
+    y = conv1x1(relu6(d), w2)
+    if b2 is not None:
+        y = bias(y, b2)
+    return add(y, x) if residual else y
 
 
 def conv_chain(x, wa, ba, wb, bb, residual=True):
@@ -267,6 +293,9 @@ def run_case(case):
         if case.kind == "dw_dw":
             return dw_dw(t["x"], t["wd"], t["bd"], t["wd2"], t["bd2"], case.stride)
         return pw_pw(t["x"], t["w1"], t["b1"], t["w2"], t["b2"], case.act)
+    if kind == "InvresCase" and case.ksize != 3:
+        return invres_k(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"],
+                        case.stride, case.residual)
     if kind == "InvresCase":
         return invres(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"],
                       case.stride, case.residual)

@@ -124,6 +124,46 @@ def test_dwconv_brute(oracle, stride, hw):
     np.testing.assert_allclose(got, ref, rtol=0, atol=1e-13)
 
 
+@pytest.mark.parametrize("stride", [1, 2])
+@pytest.mark.parametrize("hw,r", [((6, 7), 5), ((3, 4), 5), ((5, 5), 3), ((9, 8), 7), ((4, 4), 1)])
+def test_dwconv_general_brute(oracle, stride, hw, r):
+    """Odd depthwise sizes against the padded brute force, and the embedding identities that tie the
+    general routine to the 3x3 one."""
+    h, w = hw
+    x, wt = _tiny(13, (2, h, w, 3)), _tiny(14, (r, r, 3))
+    ref = lists_to_nhwc(brute_conv_nchw(nhwc_to_lists(x), wdw_to_oihw(wt), (r - 1) // 2, stride, True))
+    got = oracle.dwconv(x, wt, stride)
+    assert got.shape == ref.shape == (2, (h - 1) // stride + 1, (w - 1) // stride + 1, 3)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-13)
+    if r == 3:
+        np.testing.assert_array_equal(got, oracle.dwconv3x3(x, wt, stride))
+    if r == 5:
+        # a 3x3 kernel embedded in the centre of a zero 5x5 kernel is the 3x3 depthwise
+        w3 = _tiny(15, (3, 3, 3))
+        w5 = np.zeros((5, 5, 3))
+        w5[1:4, 1:4] = w3
+        np.testing.assert_allclose(oracle.dwconv(x, w5, stride), oracle.dwconv3x3(x, w3, stride), rtol=0, atol=1e-14)
+        # a single off-centre tap shifts the image: tap (r0, s0) reads x[oh*st + r0 - 2, ow*st + s0 - 2]
+        tap = np.zeros((5, 5, 3))
+        tap[0, 3] = 1.0
+        xp = np.pad(x, ((0, 0), (2, 2), (2, 2), (0, 0)))
+        np.testing.assert_array_equal(oracle.dwconv(x, tap, stride), xp[:, 0:h:stride, 3:3 + w:stride][:, :got.shape[1], :got.shape[2]])
+
+
+def test_invres_k_composition(oracle):
+    """The block with a general depthwise equals the monolithic 3x3 block when the kernel is 3x3, and with a
+    5x5 kernel whose ring is zero."""
+    x, w1, w2 = _tiny(20, (2, 6, 5, 4)), _tiny(21, (4, 8)), _tiny(22, (8, 4))
+    b1, bd, b2 = _tiny(23, (8,)), _tiny(24, (8,)), _tiny(25, (4,))
+    wd3 = _tiny(26, (3, 3, 8))
+    wd5 = np.zeros((5, 5, 8))
+    wd5[1:4, 1:4] = wd3
+    for stride, res in ((1, True), (2, False)):
+        ref = oracle.invres(x, w1, b1, wd3, bd, w2, b2, stride, res)
+        np.testing.assert_allclose(oracle.invres_k(x, w1, b1, wd3, bd, w2, b2, stride, res), ref, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(oracle.invres_k(x, w1, b1, wd5, bd, w2, b2, stride, res), ref, rtol=0, atol=1e-13)
+
+
 @pytest.mark.parametrize("hw", [(5, 5), (3, 6)])
 def test_conv3x3_brute(oracle, hw):
     h, w = hw

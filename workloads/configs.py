@@ -26,7 +26,7 @@ def _f32(x):
 
 @dataclass
 class InvresCase:
-    """1x1 expand (+b1, ReLU6) -> depthwise 3x3 pad 1 (+bd, ReLU6) -> 1x1 project (+b2) [+x]."""
+    """1x1 expand (+b1, ReLU6) -> depthwise ksize x ksize, pad (ksize-1)/2 (+bd, ReLU6) -> 1x1 project (+b2) [+x]."""
     N: int; H: int; W: int; Cin: int; Cexp: int; Cout: int
     stride: int = 1
     residual: bool = False
@@ -35,6 +35,7 @@ class InvresCase:
     seed: int = _SEED0
     x_scale: float = 1.0
     name: str = "invres"
+    ksize: int = 3
 
     @property
     def OH(self): return (self.H + 2 - 3) // self.stride + 1
@@ -44,12 +45,13 @@ class InvresCase:
     def flops(self):
         pe = self.N * self.H * self.W
         po = self.N * self.OH * self.OW
-        return 2 * pe * self.Cin * self.Cexp + 2 * 9 * po * self.Cexp + 2 * po * self.Cexp * self.Cout
+        return (2 * pe * self.Cin * self.Cexp + 2 * self.ksize ** 2 * po * self.Cexp
+                + 2 * po * self.Cexp * self.Cout)
 
     def alg_bytes(self):
         e = 2 if self.dtype == "bf16" else 4
         nb = 4 * (2 * self.Cexp + self.Cout) if self.bias else 0
-        return e * (self.N * self.H * self.W * self.Cin + self.Cin * self.Cexp + 9 * self.Cexp
+        return e * (self.N * self.H * self.W * self.Cin + self.Cin * self.Cexp + self.ksize ** 2 * self.Cexp
                     + self.Cexp * self.Cout + self.N * self.OH * self.OW * self.Cout) + nb
 
     def tensors(self):
@@ -57,7 +59,7 @@ class InvresCase:
         t = {
             "x": _store(self.x_scale * rng.uniform(s + 0, (self.N, self.H, self.W, self.Cin), -1.0, 1.0), d),
             "w1": _store(rng.normal(s + 1, (self.Cin, self.Cexp), (1.0 / self.Cin) ** 0.5), d),
-            "wd": _store(rng.normal(s + 2, (3, 3, self.Cexp), (1.0 / 9.0) ** 0.5), d),
+            "wd": _store(rng.normal(s + 2, (self.ksize, self.ksize, self.Cexp), 1.0 / self.ksize), d),
             "w2": _store(rng.normal(s + 3, (self.Cexp, self.Cout), (1.0 / self.Cexp) ** 0.5), d),
         }
         if self.bias:
