@@ -79,6 +79,17 @@ ago_status ago_fused_invres(const void* x, const void* w1, const float* b1,
                             int stride, int residual, ago_dtype dt,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same block with a ksize x ksize depthwise, zero padding (ksize-1)/2 (the 5x5 depthwise layers
+ * of the MNasNet blocks among the networks of Sec. VI): wd:[ksize,ksize,Cexp], everything else as
+ * above.  ksize is 3 or 5 (else UNSUPPORTED).  The halo of E that a tile recomputes is (ksize-1)/2
+ * pixels wide (the re-computation factor of Fig. 7a grows accordingly). */
+ago_status ago_fused_invres_k(const void* x, const void* w1, const float* b1,
+                              const void* wd, const float* bd,
+                              const void* w2, const float* b2, void* y,
+                              int N, int H, int W, int Cin, int Cexp, int Cout,
+                              int stride, int ksize, int residual, ago_dtype dt,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* The two-operator pairs of the block as calls of their own (the micro-benchmark pairs of
  * Sec. VI, Fig. 13: pw->dw, dw->pw, dw->dw, pw->pw).  Same kernels, conventions and restrictions as the
  * entry points they are cut from; tile configurations follow AGO_OP_FUSED_INVRES / _FFN.

@@ -31,6 +31,7 @@ _vp, _i, _l, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_fl
 
 _SIGS = {
     "ago_fused_invres": [_vp] * 8 + [_i] * 9 + [_vp, _sz, _vp],
+    "ago_fused_invres_k": [_vp] * 8 + [_i] * 10 + [_vp, _sz, _vp],
     "ago_fused_conv_chain": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_ffn": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_attn": [_vp] * 4 + [_i] * 4 + [_f, _i, _vp, _sz, _vp],
@@ -213,6 +214,19 @@ def ago_fused_invres(x, w1, b1, wd, bd, w2, b2, y, stride, residual, workspace=N
     wp, wb = _ws(workspace)
     return lib.ago_fused_invres, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
                               N, H, W, Cin, Cexp, Cout, stride, int(residual), _dt(x), wp, wb, _stream())
+
+
+@_entry
+def ago_fused_invres_k(x, w1, b1, wd, bd, w2, b2, y, stride, residual, workspace=None):
+    """wd: [ksize, ksize, Cexp]; the depthwise size is read off its shape."""
+    N, H, W, Cin = x.shape
+    Cexp, Cout = w2.shape
+    if wd.shape[0] != wd.shape[1]:
+        raise ValueError("square depthwise kernels only")
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_invres_k, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
+                                    N, H, W, Cin, Cexp, Cout, stride, int(wd.shape[0]), int(residual), _dt(x),
+                                    wp, wb, _stream())
 
 
 @_entry

@@ -127,6 +127,19 @@ ago_status ago_fused_invres(const void* x, const void* w1, const float* b1, cons
                                  as_stream(hip_stream)));
 }
 
+ago_status ago_fused_invres_k(const void* x, const void* w1, const float* b1, const void* wd,
+                              const float* bd, const void* w2, const float* b2, void* y, int N, int H,
+                              int W, int Cin, int Cexp, int Cout, int stride, int ksize, int residual,
+                              ago_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    ago_status st = check_invres(x, w1, wd, w2, y, b1, bd, b2, N, H, W, Cin, Cexp, Cout, stride, residual, dt);
+    if (st != AGO_OK) return st;
+    if (ksize != 3 && ksize != 5) return AGO_ERR_UNSUPPORTED;
+    return from_hip(fused_invres(x, w1, b1, wd, bd, w2, b2, y, N, H, W, Cin, Cexp, Cout, stride,
+                                 residual, dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES),
+                                 as_stream(hip_stream), 0, ksize));
+}
+
 ago_status ago_fused_pw_dw(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
                            void* y, int N, int H, int W, int Cin, int Cexp, int stride, ago_dtype dt,
                            void* workspace, size_t workspace_bytes, void* hip_stream) {

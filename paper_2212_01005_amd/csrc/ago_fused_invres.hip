@@ -4,13 +4,19 @@
 // One workgroup owns a TOH x TOW tile of output pixels of one image and *all* expanded
 // channels, so the depthwise stage needs no data from other workgroups and the projection
 // reduces over channels that are all on-chip.  The expanded tensor E for the tile plus its
-// 1-pixel halo (recomputed by neighbouring tiles) lives in LDS as fp32; the depthwise output D
+// halo of (KS - 1) / 2 pixels (recomputed by neighbouring tiles) lives in LDS as fp32; the depthwise output D
 // lives in LDS in the matrix-instruction input type.  Stages, separated by workgroup barriers:
 //   0  global -> LDS: X halo tile, W1, Wd, W2 (weights transposed for the bf16 path)
 //   1  E = relu6(X W1 + b1) on the matrix cores; E := 0 for pixels outside the image
-//   2  D = relu6(dw3x3(E) + bd) on the vector ALUs
+//   2  D = relu6(dw KSxKS(E) + bd) on the vector ALUs (KS = 3, or 5 as in MNasNet-style blocks)
 //   3  Y = D W2 + b2 (+ X) on the matrix cores, stored straight to global memory
 // Matrix instructions: 16x16x32 bf16 / 16x16x4 fp32 (small tiles: few pixels per workgroup).
+//
+// When the weights and E of all expanded channels do not fit LDS (the 576- and 960-channel blocks
+// of the networks), stages 0-3 run once per chunk of CC expanded channels: the projection reduces over
+// the expanded channels, so each chunk adds its slice of that reduction to accumulators that stay
+// in registers (the "downstream pointwise" rule applied inside the block: D is consumed in slices
+// of the reduction dimension).  One chunk = the whole of Cexp is the common case.
 //
 // The same kernel runs the two-operator pairs of the block (the paper's Fig. 13 micro-benchmarks):
 //   mode 1  pw -> dw: stages 0-2, D is stored to global memory instead of LDS
@@ -28,7 +34,8 @@ struct InvresParams {
     int TOH, TOW, tiles_h, tiles_w;
     int EH, EW, PE, PEpad, POpad;   // E-region geometry of one tile
     int KP1;                        // Cin padded to the k granularity of the matrix instruction
-    int KP2;                        // Cexp padded likewise
+    int CC, nchunks;                // expanded channels per chunk (multiple of 16), number of chunks
+    int KPC;                        // CC padded to the k granularity
     int CoutP;                      // Cout padded to 16
     int ldx, ldw1, lde, ldd, ldw2;  // LDS leading dimensions (elements)
     int off_w1, off_e, off_d, off_w2, off_wd, off_b;  // LDS byte offsets (Xs at 0)
@@ -40,8 +47,13 @@ template <bool BF16> struct InT { typedef float type; };
 template <> struct InT<true> { typedef bf16_t type; };
 
 constexpr int kInvresThreads = 1024;   // 16 waves: LDS / global latency is hidden by wave-level parallelism
+constexpr int kInvresWaves = kInvresThreads / 64;
+constexpr int kInvresJobsPerWave = 4;  // stage-3 accumulators a wave can hold across the chunks
 
-template <bool BF16, int STRIDE>
+// KS: odd depthwise kernel size (3 or 5), zero padding (KS - 1) / 2.  CHUNKED: several chunks of expanded
+// channels with the projection's accumulators carried in registers; the single-chunk instantiation
+// keeps none (64 registers or fewer: two workgroups per compute unit).
+template <bool BF16, int STRIDE, int KS, bool CHUNKED>
 __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const InvresParams p) {
     typedef typename InT<BF16>::type T;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -50,42 +62,26 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
     float* Es = reinterpret_cast<float*>(smem + p.off_e);
     T* Ds = reinterpret_cast<T*>(smem + p.off_d);
     T* W2s = reinterpret_cast<T*>(smem + p.off_w2);
-    float* Wds = reinterpret_cast<float*>(smem + p.off_wd);
-    float* B1s = reinterpret_cast<float*>(smem + p.off_b);     // b1[Cexp], bd[Cexp], b2[CoutP]; 0 when absent
+    float* Wds = reinterpret_cast<float*>(smem + p.off_wd);     // [KS * KS][CC]
+    float* B1s = reinterpret_cast<float*>(smem + p.off_b);      // b1[Cexp], bd[Cexp], b2[CoutP]; 0 when absent
     float* Bds = B1s + p.Cexp;
     float* B2s = Bds + p.Cexp;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, g = lane >> 4;
     int b = blockIdx.x;
     const int tw = b % p.tiles_w; b /= p.tiles_w;
     const int th = b % p.tiles_h;
     const int n = b / p.tiles_h;
     const int oh0 = th * p.TOH, ow0 = tw * p.TOW;
-    const int ih0 = oh0 * STRIDE - 1, iw0 = ow0 * STRIDE - 1;
+    constexpr int PAD = (KS - 1) / 2;
+    const int ih0 = oh0 * STRIDE - PAD, iw0 = ow0 * STRIDE - PAD;
     const T* X = reinterpret_cast<const T*>(p.x) + (long)n * p.H * p.W * p.Cin;
-
-    // ---- stage 0: stage inputs and weights ------------------------------------------
     constexpr int VE = BF16 ? 8 : 4;   // elements per 16-byte chunk
-    if (p.mode == 2) {
-        // the input has Cexp channels and is the depthwise operand itself: fp32 into the E region
-        const T* Xe = reinterpret_cast<const T*>(p.x) + (long)n * p.H * p.W * p.Cexp;
-        const int q4 = p.Cexp / 4;
-        for (int it = tid; it < p.PE * q4; it += kInvresThreads) {
-            const int pix = it / q4, q = it % q4;
-            const int ih = ih0 + pix / p.EW, iw = iw0 + pix % p.EW;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W) {
-                const T* src = Xe + ((long)ih * p.W + iw) * p.Cexp + 4 * q;
-                if constexpr (BF16) {
-                    const uint2 u = *reinterpret_cast<const uint2*>(src);
-                    v = make_float4(lo_bf16(u.x), hi_bf16(u.x), lo_bf16(u.y), hi_bf16(u.y));
-                } else {
-                    v = *reinterpret_cast<const float4*>(src);
-                }
-            }
-            *reinterpret_cast<float4*>(Es + pix * p.lde + 4 * q) = v;
-        }
-    } else {
+    constexpr int KG = BF16 ? 32 : 4;  // k per matrix instruction
+
+    // ---- stage 0 (once): the X halo tile and the biases ---------------------------------
+    if (p.mode != 2) {
         const int kch = p.KP1 / VE;
         for (int it = tid; it < p.PEpad * kch; it += kInvresThreads) {
             const int pix = it / kch, kc = it % kch;
@@ -104,248 +100,325 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
         else if (it - 2 * p.Cexp < p.Cout) { if (p.b2) v = p.b2[it - 2 * p.Cexp]; }
         B1s[it] = v;
     }
-    if constexpr (BF16) {
-        // W1 [Cin][Cexp] -> W1s[e][k], W2 [Cexp][Cout] -> W2s[co][k]; k beyond the real extent = 0
-        const bf16_t* W1 = reinterpret_cast<const bf16_t*>(p.w1);
-        const int nq1 = p.mode == 2 ? 0 : p.Cexp / 4;
-        for (int it = tid; it < (p.KP1 / 8) * nq1; it += kInvresThreads) {
-            const int nq = it % nq1, ko = it / nq1;
-            uint2 r[8];
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const int k = ko * 8 + kk;
-                r[kk] = k < p.Cin ? *reinterpret_cast<const uint2*>(W1 + (long)k * p.Cexp + nq * 4) : make_uint2(0, 0);
-            }
-            uint4 t[4];
-            transpose_8x4(r, t);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) st_u4(W1s + (nq * 4 + q) * p.ldw1 + ko * 8, t[q]);
-        }
-        const bf16_t* W2 = reinterpret_cast<const bf16_t*>(p.w2);
-        const int nq2 = p.mode == 1 ? 0 : p.CoutP / 4;
-        for (int it = tid; it < (p.KP2 / 8) * nq2; it += kInvresThreads) {
-            const int nq = it % nq2, ko = it / nq2;
-            uint2 r[8];
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const int k = ko * 8 + kk;
-                r[kk] = (k < p.Cexp && nq * 4 < p.Cout)
-                            ? *reinterpret_cast<const uint2*>(W2 + (long)k * p.Cout + nq * 4) : make_uint2(0, 0);
-            }
-            uint4 t[4];
-            transpose_8x4(r, t);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) st_u4(W2s + (nq * 4 + q) * p.ldw2 + ko * 8, t[q]);
-        }
-        // depthwise weights as fp32 [9][Cexp]
-        const uint16_t* WD = reinterpret_cast<const uint16_t*>(p.wd);
-        for (int it = tid; it < 9 * p.Cexp; it += kInvresThreads) Wds[it] = bf16_to_f32(WD[it]);
-    } else {
-        // fp32: weights keep their [k][n] layout (the fp32 matrix instruction reads one k per lane)
-        const float* W1 = reinterpret_cast<const float*>(p.w1);
-        const int c4 = p.mode == 2 ? 0 : p.Cexp / 4;
-        for (int it = tid; it < p.KP1 * c4; it += kInvresThreads) {
-            const int k = it / c4, q = it % c4;
-            const uint4 v = k < p.Cin ? ld_u4(W1 + (long)k * p.Cexp + q * 4) : make_uint4(0, 0, 0, 0);
-            st_u4(W1s + k * p.ldw1 + q * 4, v);
-        }
-        const float* W2 = reinterpret_cast<const float*>(p.w2);
-        const int o4 = p.mode == 1 ? 0 : p.CoutP / 4;
-        for (int it = tid; it < p.KP2 * o4; it += kInvresThreads) {
-            const int k = it / o4, q = it % o4;
-            const uint4 v = (k < p.Cexp && q * 4 < p.Cout) ? ld_u4(W2 + (long)k * p.Cout + q * 4)
-                                                          : make_uint4(0, 0, 0, 0);
-            st_u4(W2s + k * p.ldw2 + q * 4, v);
-        }
-        const float* WD = reinterpret_cast<const float*>(p.wd);
-        for (int it = tid; it < 9 * p.Cexp; it += kInvresThreads) Wds[it] = WD[it];
-    }
-    __syncthreads();
 
-    // ---- stage 1: expand.  acc rows = channels, cols = pixels (weights are operand A) ---
-    if (p.mode != 2) {
-        const int i = lane & 15, g = lane >> 4;
-        const int ptiles = p.PEpad / 16, ctiles = p.Cexp / 16;
-        for (int job = wave; job < ptiles * ctiles; job += kInvresThreads / 64) {
-            const int pt = job % ptiles, ct = job / ptiles;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            if constexpr (BF16) {
-                const bf16_t* ap = W1s + (ct * 16 + i) * p.ldw1 + 8 * g;
-                const bf16_t* bp = Xs + (pt * 16 + i) * p.ldx + 8 * g;
-                for (int k0 = 0; k0 < p.KP1; k0 += 32)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ld_bf16x8(ap + k0), ld_bf16x8(bp + k0), acc, 0, 0, 0);
-            } else {
-                const float* ap = W1s + g * p.ldw1 + ct * 16 + i;
-                const float* bp = Xs + (pt * 16 + i) * p.ldx + g;
-#pragma unroll 8
-                for (int k0 = 0; k0 < p.KP1; k0 += 4)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[k0 * p.ldw1], bp[k0], acc, 0, 0, 0);
+    // stage-3 accumulators: job = wave + 16 jj without a k split, job = wave / ksplit with one
+    const int ptiles3 = p.POpad / 16, njobs = ptiles3 * (p.CoutP / 16);
+    f32x4 accj[CHUNKED ? kInvresJobsPerWave : 1];
+#pragma unroll
+    for (int jj = 0; jj < (CHUNKED ? kInvresJobsPerWave : 1); ++jj) accj[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+    T* Y = reinterpret_cast<T*>(p.y) + (long)n * p.OH * p.OW * p.Cout;
+    auto emit = [&](int pt, int ot, const f32x4& acc) {
+        const int co = ot * 16 + i;        // this lane's output channel; registers = pixels 4g..4g+3
+        if (co >= p.Cout) return;
+        const float bv = B2s[co];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int po = pt * 16 + 4 * g + r;
+            const int oy = po / p.TOW, ox = po % p.TOW;
+            const int oh = oh0 + oy, ow = ow0 + ox;
+            if (po < p.TOH * p.TOW && oh < p.OH && ow < p.OW) {
+                float v = acc[r] + bv;
+                if (p.residual) v += (float)Xs[((oy + PAD) * p.EW + ox + PAD) * p.ldx + co];
+                Y[((long)oh * p.OW + ow) * p.Cout + co] = (T)v;
             }
-            const int pix = pt * 16 + i;       // this lane's pixel; registers = channels 4g..4g+3
-            if (pix < p.PE) {
-                const int ey = pix / p.EW, ex = pix % p.EW;
-                const int ih = ih0 + ey, iw = iw0 + ex;
-                const bool inside = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-                const int e0 = ct * 16 + 4 * g;
+        }
+    };
+
+    const int nchunks = CHUNKED ? p.nchunks : 1;
+    for (int chunk = 0; chunk < nchunks; ++chunk) {
+        const int c0 = chunk * p.CC;                       // first expanded channel of the chunk
+        const int cw = min(p.CC, p.Cexp - c0);             // its width (a multiple of 16)
+        const int kpc = (cw + KG - 1) / KG * KG;           // padded to the k granularity (zeros beyond cw)
+
+        // ---- stage 0 (per chunk): weights of the chunk, and E itself for dw -> pw ---------
+        if (p.mode == 2) {
+            // the input has Cexp channels and is the depthwise operand itself: fp32 into the E region
+            const T* Xe = reinterpret_cast<const T*>(p.x) + (long)n * p.H * p.W * p.Cexp + c0;
+            const int q4 = cw / 4;
+            for (int it = tid; it < p.PE * q4; it += kInvresThreads) {
+                const int pix = it / q4, q = it % q4;
+                const int ih = ih0 + pix / p.EW, iw = iw0 + pix % p.EW;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (inside) {
-                    const float4 bv = *reinterpret_cast<const float4*>(B1s + e0);
-                    v.x = apply_act<kRelu6>(acc[0] + bv.x);
-                    v.y = apply_act<kRelu6>(acc[1] + bv.y);
-                    v.z = apply_act<kRelu6>(acc[2] + bv.z);
-                    v.w = apply_act<kRelu6>(acc[3] + bv.w);
-                }
-                *reinterpret_cast<float4*>(Es + pix * p.lde + e0) = v;
-            }
-        }
-    }
-    __syncthreads();
-
-    // ---- stage 2: depthwise 3x3 on the vector ALUs -------------------------------------
-    {
-        const int Q = p.KP2 / 4;           // channel quads including the zero k-padding of D
-        const int Qr = p.Cexp / 4;
-        for (int it = tid; it < p.TOH * p.TOW * Q; it += kInvresThreads) {
-            const int q = it % Q, po = it / Q;
-            float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (q < Qr) {
-                const int oy = po / p.TOW, ox = po % p.TOW;
-                const float* ep = Es + ((oy * STRIDE) * p.EW + ox * STRIDE) * p.lde + 4 * q;
-#pragma unroll
-                for (int r = 0; r < 3; ++r)
-#pragma unroll
-                    for (int s = 0; s < 3; ++s) {
-                        const float4 e = *reinterpret_cast<const float4*>(ep + (r * p.EW + s) * p.lde);
-                        const float4 w = *reinterpret_cast<const float4*>(Wds + (r * 3 + s) * p.Cexp + 4 * q);
-                        a.x = fmaf(e.x, w.x, a.x); a.y = fmaf(e.y, w.y, a.y);
-                        a.z = fmaf(e.z, w.z, a.z); a.w = fmaf(e.w, w.w, a.w);
+                if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W) {
+                    const T* src = Xe + ((long)ih * p.W + iw) * p.Cexp + 4 * q;
+                    if constexpr (BF16) {
+                        const uint2 u = *reinterpret_cast<const uint2*>(src);
+                        v = make_float4(lo_bf16(u.x), hi_bf16(u.x), lo_bf16(u.y), hi_bf16(u.y));
+                    } else {
+                        v = *reinterpret_cast<const float4*>(src);
                     }
-                const float4 bv = *reinterpret_cast<const float4*>(Bds + 4 * q);
-                a.x = apply_act<kRelu6>(a.x + bv.x); a.y = apply_act<kRelu6>(a.y + bv.y);
-                a.z = apply_act<kRelu6>(a.z + bv.z); a.w = apply_act<kRelu6>(a.w + bv.w);
-            }
-            T* dst = Ds + po * p.ldd + 4 * q;
-            if (p.mode == 1) {                 // pw -> dw: D is the result
-                const int oh = oh0 + po / p.TOW, ow = ow0 + po % p.TOW;
-                if (q >= Qr || oh >= p.OH || ow >= p.OW) continue;
-                dst = reinterpret_cast<T*>(p.y) + (((long)n * p.OH + oh) * p.OW + ow) * p.Cexp + 4 * q;
-            }
-            if constexpr (BF16) {
-                *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));
-            } else {
-                *reinterpret_cast<float4*>(dst) = a;
+                }
+                *reinterpret_cast<float4*>(Es + pix * p.lde + 4 * q) = v;
             }
         }
+        if constexpr (BF16) {
+            // W1 [Cin][Cexp] -> W1s[e][k], W2 [Cexp][Cout] -> W2s[co][k]; k beyond the real extent = 0
+            const bf16_t* W1 = reinterpret_cast<const bf16_t*>(p.w1) + c0;
+            const int nq1 = p.mode == 2 ? 0 : cw / 4;
+            for (int it = tid; it < (p.KP1 / 8) * nq1; it += kInvresThreads) {
+                const int nq = it % nq1, ko = it / nq1;
+                uint2 r[8];
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) {
+                    const int k = ko * 8 + kk;
+                    r[kk] = k < p.Cin ? *reinterpret_cast<const uint2*>(W1 + (long)k * p.Cexp + nq * 4) : make_uint2(0, 0);
+                }
+                uint4 t[4];
+                transpose_8x4(r, t);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) st_u4(W1s + (nq * 4 + q) * p.ldw1 + ko * 8, t[q]);
+            }
+            const bf16_t* W2 = reinterpret_cast<const bf16_t*>(p.w2) + (long)c0 * p.Cout;
+            const int nq2 = p.mode == 1 ? 0 : p.CoutP / 4;
+            for (int it = tid; it < (kpc / 8) * nq2; it += kInvresThreads) {
+                const int nq = it % nq2, ko = it / nq2;
+                uint2 r[8];
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) {
+                    const int k = ko * 8 + kk;
+                    r[kk] = (k < cw && nq * 4 < p.Cout)
+                                ? *reinterpret_cast<const uint2*>(W2 + (long)k * p.Cout + nq * 4) : make_uint2(0, 0);
+                }
+                uint4 t[4];
+                transpose_8x4(r, t);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) st_u4(W2s + (nq * 4 + q) * p.ldw2 + ko * 8, t[q]);
+            }
+            // depthwise weights as fp32 [KS * KS][CC]
+            const uint16_t* WD = reinterpret_cast<const uint16_t*>(p.wd) + c0;
+            for (int it = tid; it < KS * KS * cw; it += kInvresThreads) {
+                const int tap = it / cw, ch = it % cw;
+                Wds[tap * p.CC + ch] = bf16_to_f32(WD[tap * p.Cexp + ch]);
+            }
+        } else {
+            // fp32: weights keep their [k][n] layout (the fp32 matrix instruction reads one k per lane)
+            const float* W1 = reinterpret_cast<const float*>(p.w1) + c0;
+            const int c4 = p.mode == 2 ? 0 : cw / 4;
+            for (int it = tid; it < p.KP1 * c4; it += kInvresThreads) {
+                const int k = it / c4, q = it % c4;
+                const uint4 v = k < p.Cin ? ld_u4(W1 + (long)k * p.Cexp + q * 4) : make_uint4(0, 0, 0, 0);
+                st_u4(W1s + k * p.ldw1 + q * 4, v);
+            }
+            const float* W2 = reinterpret_cast<const float*>(p.w2) + (long)c0 * p.Cout;
+            const int o4 = p.mode == 1 ? 0 : p.CoutP / 4;
+            for (int it = tid; it < kpc * o4; it += kInvresThreads) {
+                const int k = it / o4, q = it % o4;
+                const uint4 v = (k < cw && q * 4 < p.Cout) ? ld_u4(W2 + (long)k * p.Cout + q * 4)
+                                                          : make_uint4(0, 0, 0, 0);
+                st_u4(W2s + k * p.ldw2 + q * 4, v);
+            }
+            const float* WD = reinterpret_cast<const float*>(p.wd) + c0;
+            for (int it = tid; it < KS * KS * cw; it += kInvresThreads) {
+                const int tap = it / cw, ch = it % cw;
+                Wds[tap * p.CC + ch] = WD[tap * p.Cexp + ch];
+            }
+        }
+        __syncthreads();
+
+        // ---- stage 1: expand.  acc rows = channels, cols = pixels (weights are operand A) ---
+        if (p.mode != 2) {
+            const int ptiles = p.PEpad / 16, ctiles = cw / 16;
+            for (int job = wave; job < ptiles * ctiles; job += kInvresWaves) {
+                const int pt = job % ptiles, ct = job / ptiles;
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                if constexpr (BF16) {
+                    const bf16_t* ap = W1s + (ct * 16 + i) * p.ldw1 + 8 * g;
+                    const bf16_t* bp = Xs + (pt * 16 + i) * p.ldx + 8 * g;
+                    for (int k0 = 0; k0 < p.KP1; k0 += 32)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ld_bf16x8(ap + k0), ld_bf16x8(bp + k0), acc, 0, 0, 0);
+                } else {
+                    const float* ap = W1s + g * p.ldw1 + ct * 16 + i;
+                    const float* bp = Xs + (pt * 16 + i) * p.ldx + g;
+#pragma unroll 8
+                    for (int k0 = 0; k0 < p.KP1; k0 += 4)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[k0 * p.ldw1], bp[k0], acc, 0, 0, 0);
+                }
+                const int pix = pt * 16 + i;       // this lane's pixel; registers = channels 4g..4g+3
+                if (pix < p.PE) {
+                    const int ey = pix / p.EW, ex = pix % p.EW;
+                    const int ih = ih0 + ey, iw = iw0 + ex;
+                    const bool inside = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+                    const int e0 = ct * 16 + 4 * g;
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (inside) {
+                        const float4 bv = *reinterpret_cast<const float4*>(B1s + c0 + e0);
+                        v.x = apply_act<kRelu6>(acc[0] + bv.x);
+                        v.y = apply_act<kRelu6>(acc[1] + bv.y);
+                        v.z = apply_act<kRelu6>(acc[2] + bv.z);
+                        v.w = apply_act<kRelu6>(acc[3] + bv.w);
+                    }
+                    *reinterpret_cast<float4*>(Es + pix * p.lde + e0) = v;
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- stage 2: depthwise KS x KS on the vector ALUs -----------------------------------
+        {
+            const int Q = kpc / 4;             // channel quads including the zero k-padding of D
+            const int Qr = cw / 4;
+            for (int it = tid; it < p.TOH * p.TOW * Q; it += kInvresThreads) {
+                const int q = it % Q, po = it / Q;
+                float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (q < Qr) {
+                    const int oy = po / p.TOW, ox = po % p.TOW;
+                    const float* ep = Es + ((oy * STRIDE) * p.EW + ox * STRIDE) * p.lde + 4 * q;
+#pragma unroll
+                    for (int r = 0; r < KS; ++r)
+#pragma unroll
+                        for (int s = 0; s < KS; ++s) {
+                            const float4 e = *reinterpret_cast<const float4*>(ep + (r * p.EW + s) * p.lde);
+                            const float4 w = *reinterpret_cast<const float4*>(Wds + (r * KS + s) * p.CC + 4 * q);
+                            a.x = fmaf(e.x, w.x, a.x); a.y = fmaf(e.y, w.y, a.y);
+                            a.z = fmaf(e.z, w.z, a.z); a.w = fmaf(e.w, w.w, a.w);
+                        }
+                    const float4 bv = *reinterpret_cast<const float4*>(Bds + c0 + 4 * q);
+                    a.x = apply_act<kRelu6>(a.x + bv.x); a.y = apply_act<kRelu6>(a.y + bv.y);
+                    a.z = apply_act<kRelu6>(a.z + bv.z); a.w = apply_act<kRelu6>(a.w + bv.w);
+                }
+                T* dst = Ds + po * p.ldd + 4 * q;
+                if (p.mode == 1) {                 // pw -> dw: D is the result
+                    const int oh = oh0 + po / p.TOW, ow = ow0 + po % p.TOW;
+                    if (q >= Qr || oh >= p.OH || ow >= p.OW) continue;
+                    dst = reinterpret_cast<T*>(p.y) + (((long)n * p.OH + oh) * p.OW + ow) * p.Cexp + c0 + 4 * q;
+                }
+                if constexpr (BF16) {
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));
+                } else {
+                    *reinterpret_cast<float4*>(dst) = a;
+                }
+            }
+        }
+        if (p.mode != 1) {
+            __syncthreads();
+
+            // ---- stage 3: project.  acc rows = pixels, cols = output channels; this chunk's k slice ----
+            // Few (pixel tile, channel tile) jobs and a long k: when there are fewer jobs than waves,
+            // ksplit waves share a job, each reducing over a slice of the chunk's k.
+            const int ksteps = kpc / KG, klen = (ksteps + p.ksplit - 1) / p.ksplit;
+            auto partial = [&](int pt, int ot, int ks0, int ks1, f32x4 acc) {
+                if constexpr (BF16) {
+                    const bf16_t* ap = Ds + (pt * 16 + i) * p.ldd + 8 * g;
+                    const bf16_t* bp = W2s + (ot * 16 + i) * p.ldw2 + 8 * g;
+#pragma unroll 4
+                    for (int ks = ks0; ks < ks1; ++ks)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ld_bf16x8(ap + ks * 32), ld_bf16x8(bp + ks * 32), acc, 0, 0, 0);
+                } else {
+                    const float* ap = Ds + (pt * 16 + i) * p.ldd + g;
+                    const float* bp = W2s + g * p.ldw2 + ot * 16 + i;
+#pragma unroll 8
+                    for (int ks = ks0; ks < ks1; ++ks)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[ks * 4], bp[ks * 4 * p.ldw2], acc, 0, 0, 0);
+                }
+                return acc;
+            };
+            if (p.ksplit == 1) {
+                if constexpr (CHUNKED) {
+#pragma unroll
+                    for (int jj = 0; jj < kInvresJobsPerWave; ++jj) {
+                        const int job = wave + jj * kInvresWaves;
+                        if (job < njobs) accj[jj] = partial(job % ptiles3, job / ptiles3, 0, ksteps, accj[jj]);
+                    }
+                } else {                               // one chunk: any number of jobs, stored as they finish
+                    for (int job = wave; job < njobs; job += kInvresWaves)
+                        emit(job % ptiles3, job / ptiles3,
+                             partial(job % ptiles3, job / ptiles3, 0, ksteps, f32x4{0.f, 0.f, 0.f, 0.f}));
+                }
+            } else {                                   // njobs * ksplit <= number of waves
+                const int job = wave / p.ksplit, kq = wave % p.ksplit;
+                if (job < njobs)
+                    accj[0] = partial(job % ptiles3, job / ptiles3, min(kq * klen, ksteps), min((kq + 1) * klen, ksteps), accj[0]);
+            }
+        }
+        if (chunk + 1 < nchunks) __syncthreads();    // the next chunk overwrites the weights, E and D
     }
     if (p.mode == 1) return;
-    __syncthreads();
 
-    // ---- stage 3: project.  acc rows = pixels, cols = output channels -------------------
-    // Few (pixel tile, channel tile) jobs and a long k: when there are fewer jobs than waves,
-    // ksplit waves share a job, each reducing over a slice of k; the partial accumulators are
-    // summed through LDS (the E region is free by now) by the wave that owns the job.
-    {
-        const int i = lane & 15, g = lane >> 4;
-        const int ptiles = p.POpad / 16, otiles = p.CoutP / 16, njobs = ptiles * otiles;
-        constexpr int KG = BF16 ? 32 : 4;
-        const int ksteps = p.KP2 / KG, klen = (ksteps + p.ksplit - 1) / p.ksplit;
-        T* Y = reinterpret_cast<T*>(p.y) + (long)n * p.OH * p.OW * p.Cout;
-        float4* scratch = reinterpret_cast<float4*>(Es);
-        auto partial = [&](int pt, int ot, int ks0, int ks1) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            if constexpr (BF16) {
-                const bf16_t* ap = Ds + (pt * 16 + i) * p.ldd + 8 * g;
-                const bf16_t* bp = W2s + (ot * 16 + i) * p.ldw2 + 8 * g;
-#pragma unroll 4
-                for (int ks = ks0; ks < ks1; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ld_bf16x8(ap + ks * 32), ld_bf16x8(bp + ks * 32), acc, 0, 0, 0);
-            } else {
-                const float* ap = Ds + (pt * 16 + i) * p.ldd + g;
-                const float* bp = W2s + g * p.ldw2 + ot * 16 + i;
-#pragma unroll 8
-                for (int ks = ks0; ks < ks1; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[ks * 4], bp[ks * 4 * p.ldw2], acc, 0, 0, 0);
-            }
-            return acc;
-        };
-        auto emit = [&](int pt, int ot, const f32x4& acc) {
-            const int co = ot * 16 + i;        // this lane's output channel; registers = pixels 4g..4g+3
-            if (co >= p.Cout) return;
-            const float bv = B2s[co];
+    // ---- epilogue: (sum the k split through LDS: the E region is free by now) + b2 (+ x), store ----
+    if (p.ksplit == 1) {
+        if constexpr (CHUNKED) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int po = pt * 16 + 4 * g + r;
-                const int oy = po / p.TOW, ox = po % p.TOW;
-                const int oh = oh0 + oy, ow = ow0 + ox;
-                if (po < p.TOH * p.TOW && oh < p.OH && ow < p.OW) {
-                    float v = acc[r] + bv;
-                    if (p.residual) v += (float)Xs[((oy + 1) * p.EW + ox + 1) * p.ldx + co];
-                    Y[((long)oh * p.OW + ow) * p.Cout + co] = (T)v;
-                }
+            for (int jj = 0; jj < kInvresJobsPerWave; ++jj) {
+                const int job = wave + jj * kInvresWaves;
+                if (job < njobs) emit(job % ptiles3, job / ptiles3, accj[jj]);
             }
-        };
-        if (p.ksplit == 1) {
-            for (int job = wave; job < njobs; job += kInvresThreads / 64)
-                emit(job % ptiles, job / ptiles, partial(job % ptiles, job / ptiles, 0, ksteps));
-        } else {                                   // njobs * ksplit <= number of waves
-            const int job = wave / p.ksplit, kq = wave % p.ksplit;
-            if (job < njobs) {
-                const f32x4 acc = partial(job % ptiles, job / ptiles, kq * klen, min((kq + 1) * klen, ksteps));
-                scratch[wave * 64 + lane] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        }
+    } else {
+        float4* scratch = reinterpret_cast<float4*>(Es);
+        if (wave / p.ksplit < njobs)
+            scratch[wave * 64 + lane] = make_float4(accj[0][0], accj[0][1], accj[0][2], accj[0][3]);
+        __syncthreads();
+        if (wave < njobs) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int q = 0; q < p.ksplit; ++q) {
+                const float4 v = scratch[(wave * p.ksplit + q) * 64 + lane];
+                acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
             }
-            __syncthreads();
-            if (wave < njobs) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-                for (int q = 0; q < p.ksplit; ++q) {
-                    const float4 v = scratch[(wave * p.ksplit + q) * 64 + lane];
-                    acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
-                }
-                emit(wave % ptiles, wave / ptiles, acc);
-            }
+            emit(wave % ptiles3, wave / ptiles3, acc);
         }
     }
 }
 
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-// Lay out LDS for a tile; returns the byte count.
-static size_t plan_tile(InvresParams& p, bool bf16, int stride, int toh, int tow) {
+// Lay out LDS for a tile and a chunk width cc of expanded channels; returns the byte count.
+static size_t plan_layout(InvresParams& p, bool bf16, int stride, int toh, int tow, int ksize, int cc) {
     p.TOH = toh; p.TOW = tow;
     p.tiles_h = (p.OH + toh - 1) / toh; p.tiles_w = (p.OW + tow - 1) / tow;
-    p.EH = (toh - 1) * stride + 3; p.EW = (tow - 1) * stride + 3;
+    p.EH = (toh - 1) * stride + ksize; p.EW = (tow - 1) * stride + ksize;
     p.PE = p.EH * p.EW; p.PEpad = round_up(p.PE, 16); p.POpad = round_up(toh * tow, 16);
     const int kg = bf16 ? 32 : 4, es = bf16 ? 2 : 4;
-    p.KP1 = round_up(p.Cin, kg); p.KP2 = round_up(p.Cexp, kg); p.CoutP = round_up(p.Cout, 16);
+    p.CC = cc; p.nchunks = (p.Cexp + cc - 1) / cc;
+    p.KP1 = round_up(p.Cin, kg); p.KPC = round_up(cc, kg); p.CoutP = round_up(p.Cout, 16);
     auto pad16 = [](int c) { int q = c; while (q % 32 != 16) q += 4; return q; };  // fp32 [k][n] rows
     p.ldx = bf16 ? p.KP1 + 8 : p.KP1 + 4;
-    p.ldw1 = bf16 ? p.KP1 + 8 : pad16(p.Cexp);
-    p.lde = p.Cexp + 4;
-    p.ldd = bf16 ? p.KP2 + 8 : p.KP2 + 4;
-    p.ldw2 = bf16 ? p.KP2 + 8 : pad16(p.CoutP);
+    p.ldw1 = bf16 ? p.KP1 + 8 : pad16(cc);
+    p.lde = cc + 4;
+    p.ldd = bf16 ? p.KPC + 8 : p.KPC + 4;
+    p.ldw2 = bf16 ? p.KPC + 8 : pad16(p.CoutP);
     size_t off = (size_t)p.PEpad * p.ldx * es;
     auto al = [](size_t v) { return (v + 15) / 16 * 16; };
     p.off_w1 = (int)(off = al(off));
-    off += (size_t)(bf16 ? p.Cexp : p.KP1) * p.ldw1 * es;
+    off += (size_t)(bf16 ? cc : p.KP1) * p.ldw1 * es;
     p.off_e = (int)(off = al(off));
     off += (size_t)p.PE * p.lde * 4;
     p.off_d = (int)(off = al(off));
     off += (size_t)p.POpad * p.ldd * es;
     p.off_w2 = (int)(off = al(off));
-    off += (size_t)(bf16 ? p.CoutP : p.KP2) * p.ldw2 * es;
+    off += (size_t)(bf16 ? p.CoutP : p.KPC) * p.ldw2 * es;
     p.off_wd = (int)(off = al(off));
-    off += (size_t)9 * p.Cexp * 4;
+    off += (size_t)ksize * ksize * cc * 4;
     p.off_b = (int)(off = al(off));
     off += (size_t)(2 * p.Cexp + p.CoutP) * 4;
-    // stage-3 k split: as many waves per job as there are, limited by the k steps and by the
-    // scratch (1 KB per wave) that fits in the E region
-    const int nwaves = kInvresThreads / 64, njobs = (p.POpad / 16) * (p.CoutP / 16);
-    const int ksteps = p.KP2 / kg;
-    int ks = njobs < nwaves ? nwaves / njobs : 1;
+    // stage-3 k split: as many waves per job as there are, limited by the k steps of a chunk and by
+    // the scratch (1 KB per wave) that fits in the E region
+    const int njobs = (p.POpad / 16) * (p.CoutP / 16);
+    const int ksteps = p.KPC / kg;
+    int ks = njobs < kInvresWaves ? kInvresWaves / njobs : 1;
     if (ks > ksteps) ks = ksteps;
     const size_t e_bytes = (size_t)p.PE * p.lde * 4;
     while (ks > 1 && (size_t)njobs * ks * 1024 > e_bytes) --ks;
     p.ksplit = ks < 1 ? 1 : ks;
     return al(off);
+}
+
+constexpr size_t kInvresLdsMax = 160 * 1024;
+
+// Lay out a tile with the fewest chunks of expanded channels that fit LDS (chunks balanced, widths
+// multiples of 32).  Returns the byte count, or 0 when the tile cannot run: no chunk width fits, or it
+// has more stage-3 jobs than the waves can hold accumulators for.
+static size_t plan_tile(InvresParams& p, bool bf16, int stride, int toh, int tow, int ksize) {
+    size_t smem = plan_layout(p, bf16, stride, toh, tow, ksize, p.Cexp);
+    if (smem <= kInvresLdsMax) return smem;
+    const int njobs = round_up(toh * tow, 16) / 16 * (round_up(p.Cout, 16) / 16);
+    if (njobs > kInvresWaves * kInvresJobsPerWave) return 0;
+    for (int cc = (p.Cexp - 1) / 32 * 32; cc >= 32; cc -= 32) {
+        if (plan_layout(p, bf16, stride, toh, tow, ksize, cc) > kInvresLdsMax) continue;
+        const int nch = (p.Cexp + cc - 1) / cc;
+        const int bal = round_up((p.Cexp + nch - 1) / nch, 32);      // <= cc: same chunk count, balanced
+        return plan_layout(p, bf16, stride, toh, tow, ksize, bal);
+    }
+    return 0;
 }
 
 // tile_cfg: -1 = built-in choice; otherwise index into the candidate list below.
@@ -356,17 +429,18 @@ int fused_invres_num_cfgs() { return (int)(sizeof(kTileCand) / sizeof(kTileCand[
 hipError_t fused_invres(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
                         const void* w2, const float* b2, void* y, int N, int H, int W, int Cin,
                         int Cexp, int Cout, int stride, int residual, bool bf16, int tile_cfg,
-                        hipStream_t s, int mode) {
+                        hipStream_t s, int mode, int ksize) {
+    if (ksize != 3 && ksize != 5) return hipErrorInvalidValue;
     InvresParams p;
     p.mode = mode;
     p.x = x; p.w1 = w1; p.b1 = b1; p.wd = wd; p.bd = bd; p.w2 = w2; p.b2 = b2; p.y = y;
     p.N = N; p.H = H; p.W = W; p.Cin = Cin; p.Cexp = Cexp; p.Cout = Cout;
     p.OH = (H - 1) / stride + 1; p.OW = (W - 1) / stride + 1; p.residual = residual;
-    constexpr size_t kLdsMax = 160 * 1024;
+    constexpr size_t kLdsMax = kInvresLdsMax;
     size_t smem = 0;
     if (tile_cfg >= 0 && tile_cfg < fused_invres_num_cfgs()) {
-        smem = plan_tile(p, bf16, stride, kTileCand[tile_cfg][0], kTileCand[tile_cfg][1]);
-        if (smem > kLdsMax) return hipErrorInvalidValue;
+        smem = plan_tile(p, bf16, stride, kTileCand[tile_cfg][0], kTileCand[tile_cfg][1], ksize);
+        if (smem == 0) return hipErrorInvalidValue;
     } else {
         // built-in choice: 4x4 output tiles, halved (down to 2x2) while the launch has fewer than 128
         // workgroups: these blocks are latency-bound, so more, smaller workgroups (each recomputing a
@@ -377,17 +451,17 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
             if (tow >= toh) tow /= 2; else toh /= 2;
         }
         for (;;) {
-            smem = plan_tile(p, bf16, stride, toh, tow);
-            if (smem <= kLdsMax) break;
+            smem = plan_tile(p, bf16, stride, toh, tow, ksize);
+            if (smem != 0) break;
             if (tow > 1 && tow >= toh) tow = (tow + 1) / 2;
             else if (toh > 1) toh = (toh + 1) / 2;
             else return hipErrorInvalidValue;
         }
     }
     const unsigned grid = (unsigned)(N * p.tiles_h * p.tiles_w);
-#define AGO_LAUNCH_INVRES(BF, ST)                                                                       \
+#define AGO_LAUNCH_INVRES_KC(BF, ST, KS, CH)                                                                      \
     do {                                                                                                \
-        auto kern = fused_invres_kernel<BF, ST>;                                                        \
+        auto kern = fused_invres_kernel<BF, ST, KS, CH>;                                                       \
         static bool attr_set = false;                                                                   \
         if (!attr_set) {                                                                                \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                     \
@@ -400,9 +474,19 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
         hipLaunchKernelGGL(kern, dim3(grid), dim3(kInvresThreads), smem, s, p);                                    \
         prof_stop(0, s);                                                                                \
     } while (0)
+#define AGO_LAUNCH_INVRES_K(BF, ST, KS)                                                                 \
+    do {                                                                                                \
+        if (p.nchunks == 1) AGO_LAUNCH_INVRES_KC(BF, ST, KS, false); else AGO_LAUNCH_INVRES_KC(BF, ST, KS, true); \
+    } while (0)
+#define AGO_LAUNCH_INVRES(BF, ST)                                                                       \
+    do {                                                                                                \
+        if (ksize == 3) AGO_LAUNCH_INVRES_K(BF, ST, 3); else AGO_LAUNCH_INVRES_K(BF, ST, 5);            \
+    } while (0)
     if (bf16) { if (stride == 1) AGO_LAUNCH_INVRES(true, 1); else AGO_LAUNCH_INVRES(true, 2); }
     else { if (stride == 1) AGO_LAUNCH_INVRES(false, 1); else AGO_LAUNCH_INVRES(false, 2); }
 #undef AGO_LAUNCH_INVRES
+#undef AGO_LAUNCH_INVRES_K
+#undef AGO_LAUNCH_INVRES_KC
     return hipGetLastError();
 }
 

@@ -30,7 +30,8 @@ hipError_t softmax_rows(const void* x, void* y, long rows, int cols, bool in_bf1
 hipError_t fused_invres(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
                         const void* w2, const float* b2, void* y, int N, int H, int W, int Cin,
                         int Cexp, int Cout, int stride, int residual, bool bf16, int tile_cfg,
-                        hipStream_t s, int mode = 0);   // mode 1: pw -> dw (y = D), mode 2: dw -> pw (x = E)
+                        hipStream_t s, int mode = 0,    // mode 1: pw -> dw (y = D), mode 2: dw -> pw (x = E)
+                        int ksize = 3);                 // depthwise kernel size, 3 or 5
 hipError_t fused_conv_chain(const void* x, const void* wa, const float* ba, const void* wb,
                             const float* bb, void* y, int N, int H, int W, int residual, int tile_cfg,
                             hipStream_t s);

@@ -83,6 +83,9 @@ def _fused_call(case, t, y, ws):
         if case.kind == "dw_dw":
             return ago.ago_fused_dw_dw, (t["x"], t["wd"], t["bd"], t["wd2"], t["bd2"], y, case.stride, ws)
         return ago.ago_fused_pw_pw, (t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, _ACT[case.act], ws)
+    if k == "InvresCase" and case.ksize != 3:
+        return ago.ago_fused_invres_k, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
+                                        case.stride, case.residual, ws)
     if k == "InvresCase":
         return ago.ago_fused_invres, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
                                       case.stride, case.residual, ws)

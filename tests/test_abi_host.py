@@ -84,6 +84,13 @@ def test_pair_entry_points_validate_before_any_gpu_call(lib):
     assert att(25600, 64, 32) == 2                                        # rows would overlap
     assert att(25600, 60, 256) == 4                                       # row starts must stay 16-byte aligned
     assert att(25600, 64, 256, D=32) == 5                                 # head dimension other than 64
+    lib.ago_fused_invres_k.argtypes = [vp] * 8 + [ci] * 10 + [vp, sz, vp]
+    irk = lambda ks, st=1, res=0, Cexp=96: lib.ago_fused_invres_k(p, p, None, p, None, p, None, p, 1, 8, 8, 16, Cexp, 16,
+                                                              st, ks, res, 1, None, 0, None)
+    assert irk(4) == 5 and irk(7) == 5 and irk(1) == 5                    # depthwise sizes 3 and 5 only
+    assert irk(5, st=3) == 2
+    assert irk(5, st=2, res=1) == 2                                       # a residual needs stride 1
+    assert irk(5, Cexp=100) == 5
     lib.ago_fused_attn_bias.argtypes = [vp] * 5 + [ci] * 4 + [ll] * 2 + [ctypes.c_float, ci, vp, sz, vp]
     atb = lambda sb, sh, bias=p, S=100: lib.ago_fused_attn_bias(p, p, p, bias, p, 2, 4, S, 64, sb, sh, 0.125, 1, None, 0, None)
     assert atb(0, 0, bias=None) == 1                                      # the bias is not optional here

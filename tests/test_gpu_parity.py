@@ -146,6 +146,72 @@ def test_attention_strided_layout(gpu, oracle):
         assert_close(runner.to_numpy64(o.permute(0, 2, 1, 3)), ref, "bf16", case.name)
 
 
+def test_invres_5x5_depthwise(gpu, oracle):
+    """The block with a 5x5 depthwise (2-pixel halo): both dtypes and strides, residual, ragged images,
+    images smaller than the kernel, the built-in tile choice and explicit tile configurations."""
+    torch, ago, runner = gpu
+    cases = [wl.InvresCase(1, 14, 14, 40, 240, 40, 1, True, True, "f32", 6300, name="invres5_f32_s1_res", ksize=5),
+             wl.InvresCase(1, 28, 28, 24, 144, 40, 2, False, False, "bf16", 6301, name="invres5_bf16_s2", ksize=5),
+             wl.InvresCase(2, 9, 11, 16, 96, 24, 2, False, True, "f32", 6302, name="invres5_f32_s2_ragged", ksize=5),
+             wl.InvresCase(2, 13, 10, 32, 192, 32, 1, True, True, "bf16", 6303, name="invres5_bf16_s1_res", ksize=5),
+             wl.InvresCase(3, 1, 2, 8, 16, 8, 1, True, True, "f32", 6304, name="invres5_tiny", ksize=5),
+             wl.InvresCase(1, 3, 3, 8, 48, 16, 2, False, True, "bf16", 6305, name="invres5_3x3_image", ksize=5)]
+    for case in cases:
+        ref = oracle.run_case(case)
+        t = runner.to_device(case)
+        try:
+            ran = 0
+            for cfg in (-1, 1, 3, 9, 13):
+                ago.set_tile_config(ago.OP_FUSED_INVRES, cfg)
+                y = runner.alloc_output(case)
+                try:
+                    runner.run_fused(case, t, y)
+                except ago.AgoError as e:
+                    assert cfg >= 0 and e.status == 5, e      # an explicit tile that does not fit LDS
+                    continue
+                ran += 1
+                torch.cuda.synchronize()
+                assert_close(runner.to_numpy64(y), ref, case.dtype, "%s cfg %d" % (case.name, cfg))
+            assert ran >= 2, case.name
+        finally:
+            ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
+
+
+def test_invres_expanded_channels_in_chunks(gpu, oracle):
+    """Blocks whose weights and expanded tensor exceed LDS (the 576-, 672- and 960-channel blocks of the
+    mobile networks): the kernel walks the expanded channels in chunks and carries the projection's
+    accumulators across them.  Full block in both dtypes, 5x5 depthwise, and both pairs."""
+    torch, ago, runner = gpu
+    cases = [wl.InvresCase(2, 7, 7, 160, 960, 160, 1, True, True, "bf16", 6400, name="invres_960_bf16"),
+             wl.InvresCase(1, 14, 14, 96, 576, 96, 1, True, True, "f32", 6401, name="invres_576_f32"),
+             wl.InvresCase(1, 14, 14, 112, 672, 160, 2, False, True, "bf16", 6402, name="invres5_672_s2_bf16", ksize=5),
+             wl.InvresCase(1, 9, 7, 160, 944, 320, 1, False, False, "bf16", 6403, name="invres_944_ragged_chunk"),
+             wl.PairCase("pw_dw", 1, 7, 7, 160, 960, stride=1, dtype="bf16", seed=6404, name="pw_dw_960"),
+             wl.PairCase("dw_pw", 1, 7, 7, 960, 160, stride=1, dtype="bf16", seed=6405, name="dw_pw_960"),
+             wl.PairCase("pw_dw", 1, 9, 9, 96, 576, stride=2, dtype="f32", seed=6406, name="pw_dw_576_f32_s2"),
+             wl.PairCase("dw_pw", 1, 9, 9, 576, 96, stride=2, dtype="f32", seed=6407, name="dw_pw_576_f32_s2")]
+    for case in cases:
+        ref = oracle.run_case(case)
+        t = runner.to_device(case)
+        try:
+            ran = 0
+            for cfg in (-1, 1, 3, 5, 10):
+                ago.set_tile_config(ago.OP_FUSED_INVRES, cfg)
+                y = runner.alloc_output(case)
+                y.zero_()
+                try:
+                    runner.run_fused(case, t, y)
+                except ago.AgoError as e:
+                    assert cfg >= 0 and e.status == 5, e      # an explicit tile that cannot run
+                    continue
+                ran += 1
+                torch.cuda.synchronize()
+                assert_close(runner.to_numpy64(y), ref, case.dtype, "%s cfg %d" % (case.name, cfg))
+            assert ran >= 2, case.name
+        finally:
+            ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
+
+
 def test_attention_bias(gpu, oracle):
     """softmax(scale q k^T + bias) v: every bias broadcast kind, 16-byte and element-wise row loads (S % 8),
     ragged key blocks, every tile configuration, and the benchmark's shape with a per-head table."""
