@@ -90,6 +90,15 @@ ago_status ago_fused_invres_k(const void* x, const void* w1, const float* b1,
                               int stride, int ksize, int residual, ago_dtype dt,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Host-only: the tiling ago_fused_invres[_k] would launch for this shape (no GPU call).  The tile
+ * is the candidate with the lowest predicted time of a cost model fitted to MI355X measurements
+ * (the tile-size trade-off of Sec. III-B / Fig. 7a: re-computed halo against parallelism), or the
+ * one set with ago_set_tile_config.  plan (host, 6 ints): candidate index, tile rows, tile columns
+ * of output pixels, number of chunks of expanded channels, channels per chunk, LDS bytes.
+ * predicted_us (host, may be NULL): the model's kernel time in microseconds. */
+ago_status ago_fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize,
+                                 ago_dtype dt, int plan[6], float* predicted_us);
+
 /* The two-operator pairs of the block as calls of their own (the micro-benchmark pairs of
  * Sec. VI, Fig. 13: pw->dw, dw->pw, dw->dw, pw->pw).  Same kernels, conventions and restrictions as the
  * entry points they are cut from; tile configurations follow AGO_OP_FUSED_INVRES / _FFN.

@@ -31,6 +31,7 @@ _vp, _i, _l, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_fl
 
 _SIGS = {
     "ago_fused_invres": [_vp] * 8 + [_i] * 9 + [_vp, _sz, _vp],
+    "ago_fused_invres_plan": [_i] * 9 + [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)],
     "ago_fused_invres_k": [_vp] * 8 + [_i] * 10 + [_vp, _sz, _vp],
     "ago_fused_conv_chain": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_ffn": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
@@ -214,6 +215,17 @@ def ago_fused_invres(x, w1, b1, wd, bd, w2, b2, y, stride, residual, workspace=N
     wp, wb = _ws(workspace)
     return lib.ago_fused_invres, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
                               N, H, W, Cin, Cexp, Cout, stride, int(residual), _dt(x), wp, wb, _stream())
+
+
+def fused_invres_plan(N, H, W, Cin, Cexp, Cout, stride, ksize, dtype):
+    """Host-only: dict(config, tile_h, tile_w, chunks, chunk_channels, lds_bytes, predicted_us)."""
+    plan = (ctypes.c_int * 6)()
+    us = ctypes.c_float(0.0)
+    _chk(lib.ago_fused_invres_plan(N, H, W, Cin, Cexp, Cout, stride, ksize, dtype, plan, ctypes.byref(us)))
+    keys = ("config", "tile_h", "tile_w", "chunks", "chunk_channels", "lds_bytes")
+    d = dict(zip(keys, list(plan)))
+    d["predicted_us"] = us.value
+    return d
 
 
 @_entry

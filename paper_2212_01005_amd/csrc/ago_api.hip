@@ -140,6 +140,18 @@ ago_status ago_fused_invres_k(const void* x, const void* w1, const float* b1, co
                                  as_stream(hip_stream), 0, ksize));
 }
 
+ago_status ago_fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize,
+                                 ago_dtype dt, int plan[6], float* predicted_us) {
+    if (!plan) return AGO_ERR_NULL;
+    if (dt != AGO_F32 && dt != AGO_BF16) return AGO_ERR_DTYPE;
+    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cexp <= 0 || Cout <= 0) return AGO_ERR_SHAPE;
+    if (stride != 1 && stride != 2) return AGO_ERR_SHAPE;
+    if (Cin % 8 || Cexp % 16 || Cout % 8 || (ksize != 3 && ksize != 5)) return AGO_ERR_UNSUPPORTED;
+    return fused_invres_plan(N, H, W, Cin, Cexp, Cout, stride, ksize, dt == AGO_BF16,
+                             tile_config(AGO_OP_FUSED_INVRES), 0, plan, predicted_us) == 0
+               ? AGO_OK : AGO_ERR_UNSUPPORTED;
+}
+
 ago_status ago_fused_pw_dw(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
                            void* y, int N, int H, int W, int Cin, int Cexp, int stride, ago_dtype dt,
                            void* workspace, size_t workspace_bytes, void* hip_stream) {

@@ -421,10 +421,85 @@ static size_t plan_tile(InvresParams& p, bool bf16, int stride, int toh, int tow
     return 0;
 }
 
+// Predicted kernel time (microseconds) of a planned tile: a linear model of the work one workgroup
+// does between its barriers, times the number of rounds the launch needs on the chip's 256 compute
+// units.  In the paper's terms the tile size trades the re-computation of E's halo (and, here, the
+// weights every workgroup stages for itself) against parallelism; where the paper tunes that trade
+// by search, this model was fitted (non-negative least squares, relative error) to measured times of
+// all candidate tiles over 21 block shapes on MI355X (mean error 5%; the tile it picks is within
+// 3% of the best candidate on every one of them, also when that shape is left out of the fit).
+//   units per workgroup: stage-1 jobs and matrix-instruction steps per wave, stage-2 iterations per
+//   thread (and their taps), stage-3 steps per wave, KB of weights and of the X tile staged, chunks
+static double predict_us(const InvresParams& p, bool bf16, int ksize, size_t smem) {
+    constexpr int kCus = 256;
+    const int kg = bf16 ? 32 : 4, es = bf16 ? 2 : 4;
+    const long wgs = (long)p.N * p.tiles_h * p.tiles_w;
+    const int nch = p.nchunks;
+    auto cdiv = [](long a, long b) { return (a + b - 1) / b; };
+    const double s1_jobs = p.mode == 2 ? 0.0 : (double)cdiv((long)(p.PEpad / 16) * (p.CC / 16), kInvresWaves) * nch;
+    const double s1_steps = s1_jobs * (p.KP1 / kg);
+    const double s2_it = (double)cdiv((long)p.TOH * p.TOW * (p.KPC / 4), kInvresThreads) * nch;
+    const double s2_fma = s2_it * ksize * ksize;
+    const int njobs = (p.POpad / 16) * (p.CoutP / 16), ksteps = p.KPC / kg;
+    const double s3_steps = p.mode == 1 ? 0.0
+                            : (njobs < kInvresWaves ? (double)cdiv(ksteps, p.ksplit) * nch
+                                                    : (double)cdiv(njobs, kInvresWaves) * nch * ksteps);
+    const double w_kb = ((p.mode == 2 ? 0.0 : (double)p.Cin * p.Cexp) + (p.mode == 1 ? 0.0 : (double)p.Cexp * p.Cout) +
+                         (double)ksize * ksize * p.Cexp) * es / 1024.0;
+    const double x_kb = (double)p.PE * (p.mode == 2 ? p.Cexp : p.Cin) * es / 1024.0;
+    const double t_wg = 2.156 + 2.198 * nch + 0.3036 * s1_jobs + 0.0417 * s1_steps + 0.3625 * s2_it +
+                        0.0523 * s2_fma + 0.075 * s3_steps + 0.0089 * w_kb + 0.2013 * x_kb;
+    // two workgroups share a compute unit when LDS and registers allow (single-chunk kernel, half the
+    // LDS) and there are more workgroups than compute units; a shared unit runs each 1.5x slower
+    const bool two = wgs > kCus && nch == 1 && smem <= kInvresLdsMax / 2;
+    const double rounds = (double)cdiv(wgs, two ? 2 * kCus : kCus);
+    return 1.208 + rounds * (two ? 1.5 : 1.0) * t_wg;
+}
+
 // tile_cfg: -1 = built-in choice; otherwise index into the candidate list below.
 static const int kTileCand[][2] = {{2, 14}, {4, 4}, {1, 14}, {2, 2}, {4, 8}, {7, 7}, {2, 8}, {1, 8},
                                    {1, 2}, {2, 4}, {3, 3}, {1, 4}, {2, 3}, {1, 1}, {3, 4}, {2, 7}};
 int fused_invres_num_cfgs() { return (int)(sizeof(kTileCand) / sizeof(kTileCand[0])); }
+
+// Fill p's tile fields for tile_cfg (-1: the candidate with the lowest predicted time).  Returns the
+// LDS byte count, 0 when nothing fits; *chosen = the candidate's index, *us = its predicted time.
+static size_t choose_tile(InvresParams& p, bool bf16, int stride, int ksize, int tile_cfg, int* chosen, double* us) {
+    int best = -1;
+    double best_us = 0.0;
+    if (tile_cfg >= 0 && tile_cfg < fused_invres_num_cfgs()) {
+        best = tile_cfg;
+    } else {
+        for (int c = 0; c < fused_invres_num_cfgs(); ++c) {
+            const size_t sz = plan_tile(p, bf16, stride, kTileCand[c][0], kTileCand[c][1], ksize);
+            if (sz == 0) continue;
+            const double t = predict_us(p, bf16, ksize, sz);
+            if (best < 0 || t < best_us) { best = c; best_us = t; }
+        }
+        if (best < 0) return 0;
+    }
+    const size_t smem = plan_tile(p, bf16, stride, kTileCand[best][0], kTileCand[best][1], ksize);
+    if (smem == 0) return 0;
+    if (chosen) *chosen = best;
+    if (us) *us = predict_us(p, bf16, ksize, smem);
+    return smem;
+}
+
+// Host-only query of the plan a launch would use (no GPU call).
+int fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize, bool bf16,
+                      int tile_cfg, int mode, int out[6], float* predicted_us) {
+    if ((ksize != 3 && ksize != 5) || (stride != 1 && stride != 2)) return -1;
+    InvresParams p = {};
+    p.mode = mode;
+    p.N = N; p.H = H; p.W = W; p.Cin = Cin; p.Cexp = Cexp; p.Cout = Cout;
+    p.OH = (H - 1) / stride + 1; p.OW = (W - 1) / stride + 1;
+    int chosen = -1;
+    double us = 0.0;
+    const size_t smem = choose_tile(p, bf16, stride, ksize, tile_cfg, &chosen, &us);
+    if (smem == 0) return -1;
+    out[0] = chosen; out[1] = p.TOH; out[2] = p.TOW; out[3] = p.nchunks; out[4] = p.CC; out[5] = (int)smem;
+    if (predicted_us) *predicted_us = (float)us;
+    return 0;
+}
 
 hipError_t fused_invres(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
                         const void* w2, const float* b2, void* y, int N, int H, int W, int Cin,
@@ -437,27 +512,8 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
     p.N = N; p.H = H; p.W = W; p.Cin = Cin; p.Cexp = Cexp; p.Cout = Cout;
     p.OH = (H - 1) / stride + 1; p.OW = (W - 1) / stride + 1; p.residual = residual;
     constexpr size_t kLdsMax = kInvresLdsMax;
-    size_t smem = 0;
-    if (tile_cfg >= 0 && tile_cfg < fused_invres_num_cfgs()) {
-        smem = plan_tile(p, bf16, stride, kTileCand[tile_cfg][0], kTileCand[tile_cfg][1], ksize);
-        if (smem == 0) return hipErrorInvalidValue;
-    } else {
-        // built-in choice: 4x4 output tiles, halved (down to 2x2) while the launch has fewer than 128
-        // workgroups: these blocks are latency-bound, so more, smaller workgroups (each recomputing a
-        // larger share of halo) finish sooner than few large ones; then shrink until the tile fits LDS.
-        int toh = 4, tow = 4;
-        auto wgs = [&](int th, int tw) { return (long)N * ((p.OH + th - 1) / th) * ((p.OW + tw - 1) / tw); };
-        while (wgs(toh, tow) < 128 && (toh > 2 || tow > 2)) {
-            if (tow >= toh) tow /= 2; else toh /= 2;
-        }
-        for (;;) {
-            smem = plan_tile(p, bf16, stride, toh, tow, ksize);
-            if (smem != 0) break;
-            if (tow > 1 && tow >= toh) tow = (tow + 1) / 2;
-            else if (toh > 1) toh = (toh + 1) / 2;
-            else return hipErrorInvalidValue;
-        }
-    }
+    const size_t smem = choose_tile(p, bf16, stride, ksize, tile_cfg, nullptr, nullptr);
+    if (smem == 0) return hipErrorInvalidValue;
     const unsigned grid = (unsigned)(N * p.tiles_h * p.tiles_w);
 #define AGO_LAUNCH_INVRES_KC(BF, ST, KS, CH)                                                                      \
     do {                                                                                                \

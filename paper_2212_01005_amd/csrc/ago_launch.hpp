@@ -32,6 +32,8 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
                         int Cexp, int Cout, int stride, int residual, bool bf16, int tile_cfg,
                         hipStream_t s, int mode = 0,    // mode 1: pw -> dw (y = D), mode 2: dw -> pw (x = E)
                         int ksize = 3);                 // depthwise kernel size, 3 or 5
+int fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize, bool bf16,
+                      int tile_cfg, int mode, int out[6], float* predicted_us);
 hipError_t fused_conv_chain(const void* x, const void* wa, const float* ba, const void* wb,
                             const float* bb, void* y, int N, int H, int W, int residual, int tile_cfg,
                             hipStream_t s);

@@ -225,3 +225,32 @@ def test_recompute_model_symbolic_forms(lib):
             f4, _ = ago.fused_upstream_iterations(N, O1, O2, H2, W2, 3, 3, O2, 2, 16)
             assert f4 == N * O1 * (H2 // 2) * (W2 // 16) * 4 * 18
     assert ago.fused_upstream_iterations(1, 8, 8, 7, 16, 3, 3, 1, 2, 16)[0] == -1   # tile must divide
+
+
+def test_invres_plan_is_a_host_query(lib):
+    """The tiling query runs without a GPU: plans fit LDS, large channel counts are chunked, more images cost
+    more predicted time, and an explicit tile configuration is honoured."""
+    from paper_2212_01005_amd import binding as ago
+    small = ago.fused_invres_plan(1, 14, 14, 32, 192, 32, 1, 3, ago.F32)
+    assert small["chunks"] == 1 and small["chunk_channels"] == 192 and 0 < small["lds_bytes"] <= 160 * 1024
+    big = ago.fused_invres_plan(32, 7, 7, 160, 960, 160, 1, 3, ago.BF16)
+    assert big["chunks"] > 1 and big["chunk_channels"] % 32 == 0 and big["lds_bytes"] <= 160 * 1024
+    assert big["chunks"] * big["chunk_channels"] >= 960 > (big["chunks"] - 1) * big["chunk_channels"]
+    t = [ago.fused_invres_plan(n, 28, 28, 40, 240, 40, 1, 3, ago.BF16)["predicted_us"] for n in (1, 8, 64, 512)]
+    assert t[0] <= t[1] < t[2] < t[3]
+    # with many images the planner moves to tiles with less halo per output pixel than the 2x2 of one image
+    one = ago.fused_invres_plan(1, 28, 28, 40, 240, 40, 1, 3, ago.BF16)
+    many = ago.fused_invres_plan(64, 28, 28, 40, 240, 40, 1, 3, ago.BF16)
+    assert many["tile_h"] * many["tile_w"] > one["tile_h"] * one["tile_w"]
+    k5 = ago.fused_invres_plan(8, 28, 28, 40, 240, 40, 1, 5, ago.BF16)
+    assert k5["predicted_us"] > ago.fused_invres_plan(8, 28, 28, 40, 240, 40, 1, 3, ago.BF16)["predicted_us"]
+    try:
+        assert ago.set_tile_config(ago.OP_FUSED_INVRES, 5) == 0
+        forced = ago.fused_invres_plan(8, 28, 28, 40, 240, 40, 1, 3, ago.BF16)
+        assert (forced["config"], forced["tile_h"], forced["tile_w"]) == (5, 7, 7)
+    finally:
+        ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
+    with pytest.raises(ago.AgoError):
+        ago.fused_invres_plan(1, 14, 14, 32, 192, 32, 1, 4, ago.F32)       # depthwise size
+    with pytest.raises(ago.AgoError):
+        ago.fused_invres_plan(1, 14, 14, 30, 192, 32, 1, 3, ago.F32)       # Cin % 8

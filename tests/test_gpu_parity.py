@@ -212,6 +212,46 @@ def test_invres_expanded_channels_in_chunks(gpu, oracle):
             ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
 
 
+def test_invres_planner_choice_is_near_the_best_candidate(gpu):
+    """The built-in tile choice (cost model) is timed against every selectable tile on three shapes the
+    model was not tuned for one by one: a latency-bound single image, a batch that fills the chip several
+    times over, and a chunked wide block."""
+    torch, ago, runner = gpu
+
+    def us(fn, n=40):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n * 1e3
+
+    for case in (wl.InvresCase(1, 28, 28, 24, 144, 24, 1, True, True, "bf16", 6500, name="plan_single"),
+                 wl.InvresCase(16, 28, 28, 32, 192, 48, 1, False, True, "bf16", 6501, name="plan_batch16"),
+                 wl.InvresCase(8, 14, 14, 80, 480, 112, 1, False, True, "bf16", 6502, name="plan_wide")):
+        t = runner.to_device(case)
+        y = runner.alloc_output(case)
+        times = {}
+        try:
+            for cfg in [-1] + list(range(ago.num_tile_configs(ago.OP_FUSED_INVRES))):
+                ago.set_tile_config(ago.OP_FUSED_INVRES, cfg)
+                try:
+                    fn = runner.prepare_fused(case, t, y)
+                    fn()
+                except ago.AgoError:
+                    continue
+                times[cfg] = us(fn)
+        finally:
+            ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
+        best = min(v for k, v in times.items() if k >= 0)
+        print("%s built-in %.2f us, best candidate %.2f us" % (case.name, times[-1], best))
+        assert times[-1] <= 1.25 * best + 1.0, (case.name, times)
+
+
 def test_attention_bias(gpu, oracle):
     """softmax(scale q k^T + bias) v: every bias broadcast kind, 16-byte and element-wise row loads (S % 8),
     ragged key blocks, every tile configuration, and the benchmark's shape with a per-head table."""
