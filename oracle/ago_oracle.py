@@ -233,6 +233,21 @@ def attn_bias(q, k, v, b, scale_=0.125):
     return bmm_nn(softmax_rows(sc), v)
 
 
+def qkv(x, wq, wk, wv, bq, bk, bv, batch, heads, head_major=True):
+    """Three sibling products that share their input (sibling fusion, Sec. III): x:[B*S, K] times
+    wq / wk / wv:[K, Hh*D], plus biases; each result viewed as [B, S, Hh, D] and, when head_major,
+    transposed to [B, Hh, S, D] (the transpose that follows the projections in an attention layer)."""
+    outs = []
+    for w, b in ((wq, bq), (wk, bk), (wv, bv)):
+        y = gemm(x, w)
+        if b is not None:
+            y = bias(y, b)
+        m, n = y.shape
+        y = y.reshape(batch, m // batch, heads, n // heads)
+        outs.append(np.ascontiguousarray(y.transpose(0, 2, 1, 3)) if head_major else y)
+    return tuple(outs)
+
+
 # ---- two-operator pairs (Sec. VI, Fig. 13): the operators above called one after another --------
 
 def pw_dw(x, w1, b1, wd, bd, stride=1):
@@ -303,6 +318,9 @@ def run_case(case):
         return conv_chain(t["x"], t["wa"], t["ba"], t["wb"], t["bb"], case.residual)
     if kind == "FfnCase":
         return ffn(t["x"], t["w1"], t["b1"], t["w2"], t["b2"])
+    if kind == "QkvCase":
+        return np.stack(qkv(t["x"], t["wq"], t["wk"], t["wv"], t["bq"], t["bk"], t["bv"], case.B, case.Hh,
+                            case.head_major))
     if kind == "AttnCase" and case.bias != "none":
         return attn_bias(t["q"], t["k"], t["v"], t["bias"], case.scale)
     if kind == "AttnCase":

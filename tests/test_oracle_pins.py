@@ -236,6 +236,33 @@ def test_attn_brute(oracle):
     np.testing.assert_allclose(oracle.attn(q, k, v, 0.5), ref, rtol=0, atol=1e-13)
 
 
+def test_qkv_brute_and_layouts(oracle):
+    """Sibling projections against plain loops; the two output layouts are transposes of each other; the
+    siblings do not see each other's weights."""
+    b, s_, k, hh, d = 2, 3, 4, 2, 3
+    x = _tiny(50, (b * s_, k))
+    w = [_tiny(51 + i, (k, hh * d)) for i in range(3)]
+    bs = [_tiny(54 + i, (hh * d,)) for i in range(3)]
+    got = oracle.qkv(x, w[0], w[1], w[2], bs[0], bs[1], bs[2], b, hh, head_major=True)
+    for i in range(3):
+        ref = np.zeros((b, hh, s_, d))
+        for bi in range(b):
+            for si in range(s_):
+                for h in range(hh):
+                    for di in range(d):
+                        ref[bi, h, si, di] = sum(x[bi * s_ + si, kk] * w[i][kk, h * d + di] for kk in range(k)) \
+                            + bs[i][h * d + di]
+        np.testing.assert_allclose(got[i], ref, rtol=0, atol=1e-13)
+    flat = oracle.qkv(x, w[0], w[1], w[2], bs[0], bs[1], bs[2], b, hh, head_major=False)
+    for i in range(3):
+        assert flat[i].shape == (b, s_, hh, d)
+        np.testing.assert_array_equal(flat[i].transpose(0, 2, 1, 3), got[i])
+    other = oracle.qkv(x, w[0], 2 * w[1], w[2], bs[0], bs[1], None, b, hh, head_major=True)
+    np.testing.assert_array_equal(other[0], got[0])
+    np.testing.assert_allclose(other[1], 2 * (got[1] - bs[1].reshape(hh, 1, d)) + bs[1].reshape(hh, 1, d), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(other[2], got[2] - bs[2].reshape(hh, 1, d), rtol=0, atol=1e-13)
+
+
 def test_attn_bias_brute(oracle):
     # bias [1, Hh, S, S] broadcast over the batch, added after the scale and before the softmax
     b, hh, s, d = 2, 2, 5, 3

@@ -194,6 +194,33 @@ def baseline_case(i: int):
 
 
 @dataclass
+class QkvCase:
+    """Sibling projections q, k, v = x wq + bq, x wk + bk, x wv + bv; x:[B*S, K], w:[K, Hh*D];
+    outputs [B, Hh, S, D] (head_major) or [B, S, Hh, D]."""
+    B: int; S: int; K: int; Hh: int; D: int
+    head_major: bool = True
+    bias: bool = True
+    dtype: str = "bf16"
+    seed: int = _SEED0 + 3000
+    name: str = "qkv"
+
+    def flops(self):
+        return 3 * 2 * self.B * self.S * self.K * self.Hh * self.D
+
+    def alg_bytes(self):
+        n = self.Hh * self.D
+        return 2 * (self.B * self.S * self.K + 3 * self.K * n + 3 * self.B * self.S * n) + (12 * n if self.bias else 0)
+
+    def tensors(self):
+        s, d, n = self.seed, self.dtype, self.Hh * self.D
+        t = {"x": _store(rng.normal(s + 0, (self.B * self.S, self.K), 1.0), d)}
+        for i, nm in enumerate("qkv"):
+            t["w" + nm] = _store(rng.normal(s + 1 + i, (self.K, n), (1.0 / self.K) ** 0.5), d)
+            t["b" + nm] = _f32(rng.uniform(s + 4 + i, (n,), -0.1, 0.1)) if self.bias else None
+        return t
+
+
+@dataclass
 class PairCase:
     """Two-operator pairs of the inverted residual block (the paper's Fig. 13 micro-benchmarks).
     kind "pw_dw": 1x1 C1 -> C2 (+b1, ReLU6) -> depthwise 3x3 (+bd, ReLU6)
