@@ -188,6 +188,19 @@ ago_status ago_fused_attn_bias(const void* q, const void* k, const void* v, cons
                                float scale, ago_dtype dt,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Sibling fusion (Sec. III: operators that share an input are fused into one subgraph): the three
+ * projections of an attention layer in one kernel,
+ *   q = x wq + bq,  k = x wk + bk,  v = x wv + bv
+ * x:[B*S,K]  wq,wk,wv:[K,Hh*D]  bq,bk,bv:[Hh*D] fp32 or NULL.  Outputs (device, written in full):
+ * head_major != 0: [B,Hh,S,D], the layout ago_fused_attn reads (the transpose after the projections
+ * is folded into the store); head_major == 0: [B,S,Hh,D] = [B*S, Hh*D], the layout
+ * ago_fused_attn_strided reads.  bf16 only; K % 8 == 0 and (Hh*D) % 8 == 0 (else UNSUPPORTED). */
+ago_status ago_fused_qkv(const void* x, const void* wq, const void* wk, const void* wv,
+                         const float* bq, const float* bk, const float* bv,
+                         void* q, void* k, void* v,
+                         int B, int S, int K, int Hh, int D, int head_major, ago_dtype dt,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------------- */
 /* Un-fused per-operator kernels (Sec. III-A).  With bias == NULL and           */
 /* act == AGO_ACT_NONE each is exactly one operator (Fig. 3); with a bias /     */

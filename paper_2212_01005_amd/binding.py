@@ -55,6 +55,7 @@ _SIGS = {
     "ago_unfused_conv_chain": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
     "ago_unfused_ffn": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
     "ago_fused_attn_bias": [_vp] * 5 + [_i] * 4 + [ctypes.c_longlong] * 2 + [_f, _i, _vp, _sz, _vp],
+    "ago_fused_qkv": [_vp] * 10 + [_i] * 7 + [_vp, _sz, _vp],
     "ago_unfused_attn": [_vp] * 4 + [_i] * 4 + [_f, _i, _i, _vp, _sz, _vp],
 }
 for _name, _args in _SIGS.items():
@@ -277,6 +278,21 @@ def ago_fused_attn_bias(q, k, v, bias, o, scale, workspace=None):
     wp, wb = _ws(workspace)
     return lib.ago_fused_attn_bias, (_p(q), _p(k), _p(v), _p(bias), _p(o), B, Hh, S, D, sb, sh, float(scale),
                                      _dt(q), wp, wb, _stream())
+
+
+@_entry
+def ago_fused_qkv(x, wq, wk, wv, bq, bk, bv, q, k, v, head_major=True, workspace=None):
+    """x: [B*S, K]; q, k, v: [B, Hh, S, D] when head_major, else [B, S, Hh, D]."""
+    rows, K = x.shape
+    if head_major:
+        B, Hh, S, D = q.shape
+    else:
+        B, S, Hh, D = q.shape
+    if B * S != rows or k.shape != q.shape or v.shape != q.shape:
+        raise ValueError("q, k, v must share one shape with B * S == x.shape[0]")
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_qkv, (_p(x), _p(wq), _p(wk), _p(wv), _p(bq), _p(bk), _p(bv), _p(q), _p(k), _p(v),
+                               B, S, K, Hh, D, int(head_major), _dt(x), wp, wb, _stream())
 
 
 @_entry

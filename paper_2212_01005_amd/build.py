@@ -28,6 +28,7 @@ SOURCES = [
     "ago_fused_ffn_stream.hip",
     "ago_fused_dw_dw.hip",
     "ago_fused_attn.hip",
+    "ago_fused_qkv.hip",
 ]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

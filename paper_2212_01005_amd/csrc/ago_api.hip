@@ -446,6 +446,23 @@ ago_status ago_fused_attn_bias(const void* q, const void* k, const void* v, cons
                                     tile_config(AGO_OP_FUSED_ATTN), as_stream(hip_stream)));
 }
 
+ago_status ago_fused_qkv(const void* x, const void* wq, const void* wk, const void* wv, const float* bq,
+                         const float* bk, const float* bv, void* q, void* k, void* v, int B, int S, int K,
+                         int Hh, int D, int head_major, ago_dtype dt, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    if (!x || !wq || !wk || !wv || !q || !k || !v) return AGO_ERR_NULL;
+    if (dt != AGO_F32 && dt != AGO_BF16) return AGO_ERR_DTYPE;
+    if (B <= 0 || S <= 0 || K <= 0 || Hh <= 0 || D <= 0) return AGO_ERR_SHAPE;
+    if ((long long)B * S > 0x7fffffffLL || (long long)Hh * D > 0x7fffffffLL) return AGO_ERR_SHAPE;
+    const void* ps[10] = {x, wq, wk, wv, q, k, v, bq, bk, bv};
+    for (const void* p : ps)
+        if (p && reinterpret_cast<uintptr_t>(p) % 16) return AGO_ERR_ALIGN;
+    if (dt != AGO_BF16 || K % 8 || (Hh * D) % 8) return AGO_ERR_UNSUPPORTED;
+    return from_hip(fused_qkv(x, wq, wk, wv, bq, bk, bv, q, k, v, B, S, K, Hh, D, head_major != 0,
+                              as_stream(hip_stream)));
+}
+
 ago_status ago_unfused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
                             int D, float scale, ago_dtype dt, int epilogue_fused, void* workspace,
                             size_t workspace_bytes, void* s) {

@@ -91,6 +91,15 @@ def test_pair_entry_points_validate_before_any_gpu_call(lib):
     assert irk(5, st=3) == 2
     assert irk(5, st=2, res=1) == 2                                       # a residual needs stride 1
     assert irk(5, Cexp=100) == 5
+    lib.ago_fused_qkv.argtypes = [vp] * 10 + [ci] * 7 + [vp, sz, vp]
+    qkv = lambda B=2, S=10, K=64, Hh=2, D=32, dt=1, x=p, v=p: lib.ago_fused_qkv(
+        x, p, p, p, None, None, None, p, p, v, B, S, K, Hh, D, 1, dt, None, 0, None)
+    assert qkv(x=None) == 1 and qkv(v=None) == 1
+    assert qkv(S=0) == 2
+    assert qkv(dt=9) == 3
+    assert qkv(x=_fake(0x1008)) == 4
+    assert qkv(dt=0) == 5                                                 # bf16 only
+    assert qkv(K=60) == 5 and qkv(Hh=3, D=4) == 5                         # K % 8, (Hh D) % 8
     lib.ago_fused_attn_bias.argtypes = [vp] * 5 + [ci] * 4 + [ll] * 2 + [ctypes.c_float, ci, vp, sz, vp]
     atb = lambda sb, sh, bias=p, S=100: lib.ago_fused_attn_bias(p, p, p, bias, p, 2, 4, S, 64, sb, sh, 0.125, 1, None, 0, None)
     assert atb(0, 0, bias=None) == 1                                      # the bias is not optional here

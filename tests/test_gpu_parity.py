@@ -252,6 +252,37 @@ def test_invres_planner_choice_is_near_the_best_candidate(gpu):
         assert times[-1] <= 1.25 * best + 1.0, (case.name, times)
 
 
+def test_sibling_qkv_projection(gpu, oracle):
+    """q, k, v = x W* + b* in one kernel, both output layouts, ragged row and column blocks; then the
+    projections feed the attention chain without a transpose in between."""
+    torch, ago, runner = gpu
+    cases = [wl.QkvCase(2, 100, 768, 12, 64, True, True, "bf16", 6600, name="qkv_ragged_rows"),
+             wl.QkvCase(1, 384, 256, 3, 64, False, True, "bf16", 6601, name="qkv_bshd"),
+             wl.QkvCase(3, 50, 72, 5, 24, True, False, "bf16", 6602, name="qkv_ragged_cols_nobias"),
+             wl.QkvCase(1, 1, 8, 1, 8, True, True, "bf16", 6603, name="qkv_tiny"),
+             wl.QkvCase(8, 384, 768, 12, 64, True, True, "bf16", 6604, name="qkv_8x384x768")]
+    for case in cases:
+        ref = oracle.run_case(case)                               # [3, ...]
+        t = runner.to_device(case)
+        shape = (case.B, case.Hh, case.S, case.D) if case.head_major else (case.B, case.S, case.Hh, case.D)
+        outs = [torch.zeros(shape, dtype=torch.bfloat16, device="cuda:0") for _ in range(3)]
+        ago.ago_fused_qkv(t["x"], t["wq"], t["wk"], t["wv"], t["bq"], t["bk"], t["bv"], *outs, head_major=case.head_major)
+        torch.cuda.synchronize()
+        for i in range(3):
+            assert_close(runner.to_numpy64(outs[i]), ref[i], "bf16", "%s %s" % (case.name, "qkv"[i]))
+    # projections (head-major) -> attention chain: against the oracle run on the oracle's projections,
+    # rounded to bf16 where the GPU path stores them
+    case = wl.QkvCase(2, 200, 256, 4, 64, True, True, "bf16", 6610, name="qkv_then_attn")
+    t = runner.to_device(case)
+    q, k, v = (torch.zeros((2, 4, 200, 64), dtype=torch.bfloat16, device="cuda:0") for _ in range(3))
+    o = torch.zeros_like(q)
+    ago.ago_fused_qkv(t["x"], t["wq"], t["wk"], t["wv"], t["bq"], t["bk"], t["bv"], q, k, v, head_major=True)
+    ago.ago_fused_attn(q, k, v, o, 0.125)
+    torch.cuda.synchronize()
+    rq, rk, rv = (wl.round_to_bf16(a) for a in oracle.run_case(case))
+    assert_close(runner.to_numpy64(o), oracle.attn(rq, rk, rv, 0.125), "bf16", case.name, scale=1.5)
+
+
 def test_attention_bias(gpu, oracle):
     """softmax(scale q k^T + bias) v: every bias broadcast kind, 16-byte and element-wise row loads (S % 8),
     ragged key blocks, every tile configuration, and the benchmark's shape with a per-head table."""
