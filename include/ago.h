@@ -323,6 +323,48 @@ int ago_bench_empty_kernel(int grid, int block, void* hip_stream);
 long long ago_fused_upstream_iterations(int N, int O1, int O2, int H2, int W2, int R2, int C2,
                                         int to2, int th2, int tw2, long long* unfused);
 
+/* ------------------------------------------------------------------------- */
+/* Graph frontend, host only (Sec. IV, V): which operators form one subgraph.  */
+/* No GPU call; every pointer is a host pointer owned by the caller.            */
+/* Nodes are 0..n_nodes-1; edge e goes from edge_src[e] to edge_dst[e] (a      */
+/* tensor produced by the source operator and consumed by the destination).     */
+/* Self-loops, out-of-range ids and cyclic edge sets give AGO_ERR_SHAPE.        */
+/* ------------------------------------------------------------------------- */
+
+/* Eq. 1: w = c * prod_l log(s_l) + b over the extents s_l of the operator's loop nest (natural
+ * logarithm; b when there are no loops; NaN when an extent is < 1). */
+double ago_graph_op_weight(const int* loop_extents, int n_loops, double c, double b);
+
+/* Topological stage (Sec. IV-B): stage[v] = number of nodes on the longest path from a root to v
+ * (roots have stage 1). */
+ago_status ago_graph_topological_stage(int n_nodes, int n_edges, const int* edge_src, const int* edge_dst,
+                                       int* stage);
+
+/* Function Cluster of the graph-partition algorithm (Sec. IV-B): repeatedly take the heaviest
+ * candidate (hyper) node v and merge it with the lightest node u of its affix set (a neighbour whose
+ * topological stage differs by one) for which w_v + w_u < td; a candidate without such a partner
+ * leaves the candidate set; edges and stages are updated after every merge.  The result is an
+ * acyclic partition whose merged subgraphs weigh less than td.
+ * weight:[n_nodes] >= 0.  is_complex:[n_nodes] (0/1) and max_complex > 0 additionally cap the number
+ * of complex operators per subgraph (max_complex <= 0: no cap, is_complex may be NULL).
+ * subgraph_of:[n_nodes] out, subgraphs numbered from 0 in order of their smallest node id;
+ * n_subgraphs out (may be NULL).  Ties: lowest id.  A node that left the candidate set can still be
+ * absorbed by a later candidate. */
+ago_status ago_graph_cluster(int n_nodes, const double* weight, const unsigned char* is_complex,
+                             int n_edges, const int* edge_src, const int* edge_dst, double td,
+                             int max_complex, int* subgraph_of, int* n_subgraphs);
+
+/* Split (Sec. V): Cluster applied inside every subgraph with threshold td_mini and at most one
+ * complex operator per mini-subgraph.  mini_of:[n_nodes] out; parent_of_mini:[>= n_nodes] out, the
+ * subgraph each mini-subgraph came from; n_minis out (may be NULL). */
+ago_status ago_graph_split(int n_nodes, const double* weight, const unsigned char* is_complex, int n_edges,
+                           const int* edge_src, const int* edge_dst, const int* subgraph_of, double td_mini,
+                           int* mini_of, int* parent_of_mini, int* n_minis);
+
+/* Join (Sec. V): the subgraph every node returns to when its mini-subgraphs are combined again. */
+ago_status ago_graph_join(int n_nodes, const int* mini_of, int n_minis, const int* parent_of_mini,
+                          int* subgraph_of);
+
 #ifdef __cplusplus
 }
 #endif

@@ -87,7 +87,20 @@ lib.ago_bench_empty_kernel.restype = _i
 lib.ago_profile_event_overhead_ms.argtypes = [_vp, _i]
 lib.ago_profile_event_overhead_ms.restype = _f
 
-EXPORTED = sorted(list(_SIGS) + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
+_ip, _dp, _bp = ctypes.POINTER(_i), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_ubyte)
+lib.ago_graph_op_weight.argtypes = [_ip, _i, ctypes.c_double, ctypes.c_double]
+lib.ago_graph_op_weight.restype = ctypes.c_double
+lib.ago_graph_topological_stage.argtypes = [_i, _i, _ip, _ip, _ip]
+lib.ago_graph_topological_stage.restype = _i
+lib.ago_graph_cluster.argtypes = [_i, _dp, _bp, _i, _ip, _ip, ctypes.c_double, _i, _ip, _ip]
+lib.ago_graph_cluster.restype = _i
+lib.ago_graph_split.argtypes = [_i, _dp, _bp, _i, _ip, _ip, _ip, ctypes.c_double, _ip, _ip, _ip]
+lib.ago_graph_split.restype = _i
+lib.ago_graph_join.argtypes = [_i, _ip, _i, _ip, _ip]
+lib.ago_graph_join.restype = _i
+
+EXPORTED = sorted(list(_SIGS) + ["ago_graph_op_weight", "ago_graph_topological_stage", "ago_graph_cluster",
+                                 "ago_graph_split", "ago_graph_join"] + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
                                  "ago_num_tile_configs", "ago_fused_upstream_iterations",
                                  "ago_profile_enable", "ago_profile_select", "ago_profile_read",
                                  "ago_profile_event_overhead_ms", "ago_profile_last_launch",
@@ -437,3 +450,55 @@ def ago_unfused_attn(q, k, v, o, scale, epilogue_fused, workspace):
     wp, wb = _ws(workspace)
     return lib.ago_unfused_attn, (_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q),
                               int(epilogue_fused), wp, wb, _stream())
+
+
+# ---- graph frontend (host only; plain Python sequences in, lists out) ---------------------------
+
+def _ints(seq):
+    seq = list(seq)
+    return (ctypes.c_int * max(len(seq), 1))(*seq)
+
+
+def _edges(edges):
+    edges = list(edges)
+    return len(edges), _ints(e[0] for e in edges), _ints(e[1] for e in edges)
+
+
+def graph_op_weight(loop_extents, c, b):
+    ext = list(loop_extents)
+    return lib.ago_graph_op_weight(_ints(ext), len(ext), float(c), float(b))
+
+
+def graph_topological_stage(n_nodes, edges):
+    ne, es, ed = _edges(edges)
+    out = (ctypes.c_int * n_nodes)()
+    _chk(lib.ago_graph_topological_stage(n_nodes, ne, es, ed, out))
+    return list(out)
+
+
+def graph_cluster(n_nodes, weight, edges, td, is_complex=None, max_complex=0):
+    ne, es, ed = _edges(edges)
+    w = (ctypes.c_double * n_nodes)(*[float(x) for x in weight])
+    cx = None if is_complex is None else (ctypes.c_ubyte * n_nodes)(*[1 if x else 0 for x in is_complex])
+    out = (ctypes.c_int * n_nodes)()
+    count = ctypes.c_int(0)
+    _chk(lib.ago_graph_cluster(n_nodes, w, cx, ne, es, ed, float(td), int(max_complex), out, ctypes.byref(count)))
+    return list(out)
+
+
+def graph_split(n_nodes, weight, edges, subgraph_of, is_complex, td_mini):
+    ne, es, ed = _edges(edges)
+    w = (ctypes.c_double * n_nodes)(*[float(x) for x in weight])
+    cx = (ctypes.c_ubyte * n_nodes)(*[1 if x else 0 for x in is_complex])
+    mini, parent = (ctypes.c_int * n_nodes)(), (ctypes.c_int * n_nodes)()
+    count = ctypes.c_int(0)
+    _chk(lib.ago_graph_split(n_nodes, w, cx, ne, es, ed, _ints(subgraph_of), float(td_mini), mini, parent,
+                             ctypes.byref(count)))
+    return list(mini), list(parent)[:count.value]
+
+
+def graph_join(mini_of, parent_of_mini):
+    n = len(mini_of)
+    out = (ctypes.c_int * n)()
+    _chk(lib.ago_graph_join(n, _ints(mini_of), len(parent_of_mini), _ints(parent_of_mini), out))
+    return list(out)
