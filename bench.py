@@ -3,8 +3,11 @@
 
 A "step" is one pass of the whole hot path: the five benchmark subgraphs (two inverted
 residuals, the 3x3 -> 3x3 chain, the FFN chain, the attention chain) each run once as its fused
-kernel, inputs already resident in HBM.  The timed region is exactly --steps steps between two
-torch.cuda.synchronize() calls.  One JSON line is printed:
+kernel, inputs already resident in HBM.  The subgraphs are independent of one another, so each is
+launched on a HIP stream of its own (--streams, default one per subgraph) and the GPU overlaps them:
+the small inverted-residual launches fill compute units the others leave idle.  --streams 1 runs
+the step back to back on one stream; that figure is reported too (one_stream).  The timed region is
+exactly --steps steps between two torch.cuda.synchronize() calls.  One JSON line is printed:
 
   value        algorithmic TFLOP/s of a step (multiply-adds of the complex operators only)
   per_config   fused / un-fused (one kernel per operator, and epilogue-fused) microseconds,
@@ -38,6 +41,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--detail-iters", type=int, default=100, help="launches per variant in the per-config table")
+    ap.add_argument("--streams", type=int, default=5,
+                    help="HIP streams (default priority) the subgraphs of a step are spread over; 1 = back to back")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true")
     ap.add_argument("--only", type=int, default=-1, help="run only this configuration in the timed step (profiling aid)")
@@ -95,41 +100,70 @@ def main():
         t = runner.to_device(c)
         state.append((c, t, runner.alloc_output(c), runner.alloc_workspace(c, fused=True)))
 
-    # arguments are marshalled once: a step is five C calls on resident buffers
-    launches = [runner.prepare_fused(c, t, y, ws) for c, t, y, ws in state]
+    # arguments (stream included) are marshalled once: a step is five C calls on resident buffers
+    def prepare_step(n_streams):
+        if n_streams <= 1:
+            return [runner.prepare_fused(c, t, y, ws) for c, t, y, ws in state]
+        streams = [torch.cuda.Stream() for _ in range(min(n_streams, len(state)))]     # default priority
+        out = []
+        for i, (c, t, y, ws) in enumerate(state):
+            with torch.cuda.stream(streams[i % len(streams)]):
+                out.append(runner.prepare_fused(c, t, y, ws))
+        return out
 
-    def step():
+    def timed(launches, steps, sample_mask):
+        """steps passes; the library brackets the kernels in sample_mask with an event pair on every
+        EVENT_EVERY-th step.  Returns milliseconds per step."""
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for i in range(steps):
+            if i % EVENT_EVERY == 0:
+                ago.profile_select(sample_mask)
+                for launch in launches:
+                    launch()
+                ago.profile_select(0)
+            else:
+                for launch in launches:
+                    launch()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t_start) * 1e3 / steps
+
+    launches = prepare_step(args.streams)
+    for _ in range(args.warmup):
         for launch in launches:
             launch()
-
-    for _ in range(args.warmup):
-        step()
     torch.cuda.synchronize()
 
     # The roofline needs the dominant kernel's duration from inside the timed region: the library
     # records a HIP event pair around that kernel on every EVENT_EVERY-th step (a pair costs about
     # 4.5 us of stream time, so bracketing every launch would inflate the step it measures).
-    EVENT_EVERY = 4
+    EVENT_EVERY = 10
     ago.profile_enable(min(args.steps // EVENT_EVERY + 1, 4096))
     ago.profile_select(0)
     ffn_mask = 1 << ago.OP_FUSED_FFN
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        if i % EVENT_EVERY == 0:
-            ago.profile_select(ffn_mask)
-            step()
-            ago.profile_select(0)
-        else:
-            step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kernel_ms = {}
-    for op in range(4):
-        tot, n = ago.profile_read(op)
-        if n:
-            kernel_ms[op] = tot / n
+    ms_per_step = timed(launches, args.steps, ffn_mask)
+
+    def read_kernel_ms():
+        out = {}
+        for op in range(4):
+            tot, n = ago.profile_read(op)
+            if n:
+                out[op] = tot / n
+        return out
+
+    kernel_ms = read_kernel_ms()
+    # the same steps back to back on one stream (not the headline: what the overlap is worth, and the
+    # dominant kernel's duration with the chip to itself)
+    one_stream = None
+    if args.streams > 1:
+        serial = prepare_step(1)
+        for _ in range(args.warmup):
+            for launch in serial:
+                launch()
+        ago.profile_enable(min(args.steps // EVENT_EVERY + 1, 4096))
+        ago.profile_select(0)
+        ms_serial = timed(serial, args.steps, ffn_mask)
+        one_stream = {"ms_per_step": round(ms_serial, 5), "kernel_ms": read_kernel_ms()}
     ago.profile_enable(0)
     ago.profile_select(0xF)
     ev_overhead_ms = ago.profile_event_overhead_ms(64)   # what an empty event pair reads
@@ -151,6 +185,15 @@ def main():
                     "event_overhead_us": round(ev_overhead_ms * 1e3, 2),
                     "event_sampling": "every %dth step of the timed region" % EVENT_EVERY,
                     "traffic": FFN_TRAFFIC_BYTES}
+        if one_stream and ago.OP_FUSED_FFN in one_stream["kernel_ms"]:
+            # the same kernel with the chip to itself (steps back to back on one stream)
+            d1 = (one_stream["kernel_ms"][ago.OP_FUSED_FFN] - ev_overhead_ms) * 1e-3
+            a1 = ffn[0].flops() / d1 / 1e12
+            roofline["one_stream"] = {"avg_kernel_us": round(d1 * 1e6, 2), "achieved": round(a1, 2),
+                                      "frac": round(a1 / PEAK_BF16_TFLOPS, 4)}
+    if one_stream:
+        one_stream = {"ms_per_step": one_stream["ms_per_step"],
+                      "value": round(flops_step / (one_stream["ms_per_step"] * 1e-3) / 1e12, 3)}
 
     # ---- per-configuration table: fused vs un-fused, device time by events ----------------
     per_config = []
@@ -276,9 +319,11 @@ def main():
         "config": {"workload": "all 5 BASELINE configs, one fused launch each per step"
                    if args.only < 0 else cases[0].name,
                    "configs": [c.name for c in cases],
+                   "streams": max(1, min(args.streams, len(cases))),
                    "tile_config": tile_cfg or "built-in",
                    "note": "config 0 is fp32 storage, configs 1-4 bf16 storage with fp32 accumulation"},
-        "roofline": roofline, "cpu_baseline": cpu, "per_config": per_config, "pairs": pairs,
+        "roofline": roofline, "cpu_baseline": cpu, "one_stream": one_stream,
+        "per_config": per_config, "pairs": pairs,
         "fused_kernel_us": {str(k): round(v * 1e3, 2) for k, v in kernel_ms.items()},
     }
     print(json.dumps(out))
