@@ -339,14 +339,15 @@ static hipError_t launch_ffn(const void* x, const void* w1, const float* b1, con
 //   0: 128 x 192, 128   1: 128 x 128, 128   2: 128 x 64, 128
 //   3: the wave-specialised streaming kernel (64 x 384, 384); the built-in choice whenever the
 //      shape allows it (K % 64 == 0, F % 384 == 0, K2 % 384 == 0)
-int fused_ffn_num_cfgs() { return 4; }
+//   4: the streaming kernel with four consumer waves of 64 x 96 wave tiles (64 x 384, 384), same shape rules
+int fused_ffn_num_cfgs() { return 5; }
 
 static bool ffn_cfg_ok(int cfg, int K, int F, int K2) {
     switch (cfg) {
         case 0: return F % 192 == 0 && K2 % 128 == 0;
         case 1: return F % 128 == 0 && K2 % 128 == 0;
         case 2: return F % 64 == 0 && K2 % 128 == 0;
-        case 3: return fused_ffn_stream_ok(0, K, F, K2);
+        case 3: case 4: return fused_ffn_stream_ok(0, K, F, K2);
         default: return false;
     }
 }
@@ -361,8 +362,8 @@ int fused_ffn_pick_cfg(int M, int K, int F, int K2, int tile_cfg) {
 }
 
 int fused_ffn_nsplit(int cfg, int F) {
-    static const int fs[4] = {192, 128, 64, 384};
-    return (cfg >= 0 && cfg < 4) ? F / fs[cfg] : 0;
+    static const int fs[5] = {192, 128, 64, 384, 384};
+    return (cfg >= 0 && cfg < 5) ? F / fs[cfg] : 0;
 }
 
 hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
@@ -373,6 +374,7 @@ hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void*
         case 1: return launch_ffn<128, 128, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
         case 2: return launch_ffn<128, 64, 128>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
         case 3: return fused_ffn_stream(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+        case 4: return fused_ffn_stream(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s, 1);
         default: return hipErrorInvalidValue;
     }
 }

@@ -23,6 +23,15 @@
 //   W tile   [32 k][384 n]: 768-byte rows, 32-byte chunk pair ^= ((k & 3) << 1) | ((k >> 3) & 1)
 //   Hs       [64 m][384 f] bf16, 392 elements per row
 // All three give conflict-free fragment reads.
+//
+// Template parameters: MW 32-row tiles per consumer wave, BK tile depth, CW consumer waves (4 column
+// groups x CW / 4 row groups; rows per workgroup = 32 MW CW / 4).  Two instantiations are launched, both
+// with 64 rows per workgroup: <1, 32, 8> (eight consumer waves, 32 x 96 wave tiles: 7 LDS reads per 3
+// matrix instructions and k step) and <2, 32, 4> (four consumer waves, 64 x 96 wave tiles: 8 reads per 6
+// matrix instructions, one consumer wave per SIMD, 239 registers).  They run within 2% of each other,
+// i.e. the consumers' LDS read issue is not what bounds the kernel; the first is the default.  A
+// 128-row workgroup (<2, 16, 8>, half the L2 -> LDS traffic per FLOP) needs about 200 registers per lane
+// with twelve waves per workgroup, 30 more than three waves per SIMD leave, and is not instantiated.
 #include "ago_dev.hpp"
 #include "ago_launch.hpp"
 #include <type_traits>
@@ -30,27 +39,40 @@
 namespace ago {
 namespace {
 
-constexpr int kConsumerWaves = 8, kProducerWaves = 4;
-constexpr int kStreamThreads = (kConsumerWaves + kProducerWaves) * 64;
-constexpr int BM = 64, FS = 384, BK = 32, CB = 384, NST = 4;
+constexpr int kProducerWaves = 4;
+constexpr int FS = 384, CB = 384, NST = 4;
 constexpr int kRowB = 384 * 2;                 // bytes per k-row of a weight tile
-constexpr int kXBlockB = BM * 64 * 2;          // X travels in 64-deep blocks (whole 128-byte lines): 8192
-constexpr int kXSlots = 7;
-constexpr int kWTileB = BK * kRowB;            // 24576
-constexpr int kHsLd = FS + 8;
-constexpr int kHsB = BM * kHsLd * 2;           // 50176
-// Hs is only written after the last phase-1 tile has been consumed, so the phase-1 buffers may
-// overlap it; the phase-2 ring starts right behind Hs.
+constexpr int kWWaves = kProducerWaves - 1;    // three waves load weights, one loads X
 constexpr int kXRing = 4096;
-constexpr int kRing1 = kXRing + kXSlots * kXBlockB;   // 61440
-constexpr int kRing2 = kHsB;
-constexpr int kB1 = kRing1 + NST * kWTileB;    // 159744
-constexpr int kStreamSmem = kB1 + FS * 4;      // 161280
-static_assert(kRing2 + NST * kWTileB <= kB1, "phase-2 ring must not reach the bias slice");
-static_assert(kStreamSmem <= 160 * 1024, "LDS");
-constexpr int kWWaves = kProducerWaves - 1;                   // three waves load weights, one loads X
-constexpr int kWLoadsPerWave = kWTileB / 1024 / kWWaves;      // 8 direct loads of 1 KB per wave and tile
-constexpr int kXLead = 4;                                     // X blocks in flight ahead of the weight tiles
+constexpr int kHsLd = FS + 8;
+
+// MW: 32-row tiles per consumer wave; BK_: tile depth; CW: consumer waves (4 column groups x CW / 4 row groups)
+template <int MW, int BK_, int CW>
+struct StreamCfg {
+    static constexpr int kThreads = (CW + kProducerWaves) * 64;
+    static constexpr int WMG = CW / 4;                      // row groups of consumer waves
+    static constexpr int BM = 32 * MW * WMG, BK = BK_;
+    static constexpr int KSTEPS = BK / 16;                  // 16-deep k steps per tile
+    static constexpr int TPB = 64 / BK;                     // tiles per 64-deep X block
+    static constexpr int kXBlockB = BM * 64 * 2;            // X travels in 64-deep blocks (whole 128-byte lines)
+    static constexpr int kXLoads = kXBlockB / 1024;         // direct loads of 1 KB per X block: 8 or 16
+    static constexpr int kXLead = BM == 64 ? 4 : 3;         // X blocks in flight ahead (at most 63 loads outstanding)
+    static constexpr int kXSlots = BM == 64 ? 7 : 5;
+    static constexpr int kWTileB = BK * kRowB;              // 24576 or 12288
+    static constexpr int kHsB = BM * kHsLd * 2;             // 50176 or 100352
+    // Hs is only written after the last phase-1 tile has been consumed, so the phase-1 buffers may
+    // overlap it; the phase-2 ring starts right behind Hs.
+    static constexpr int kRing1 = kXRing + kXSlots * kXBlockB;
+    static constexpr int kRing2 = kHsB;
+    static constexpr int kB1 = 159744;
+    static constexpr int kSmem = kB1 + FS * 4;              // 161280
+    static constexpr int kWLoadsPerWave = kWTileB / 1024 / kWWaves;      // 8 or 4 direct loads per wave and tile
+    static_assert(kRing1 + NST * kWTileB <= kB1, "phase-1 rings must not reach the bias slice");
+    static_assert(kRing2 + NST * kWTileB <= kB1, "phase-2 ring must not reach the bias slice");
+    static_assert(kSmem <= 160 * 1024, "LDS");
+    static_assert(kXSlots >= kXLead + 1 && kXLead * kXLoads < 64, "X ring");
+    static_assert(kWLoadsPerWave * 1024 * kWWaves == kWTileB, "weight tile split over the producer waves");
+};
 
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 typedef __attribute__((address_space(1))) const void gptr_t;
@@ -81,11 +103,13 @@ __device__ __forceinline__ bf16x8 read_a_frag(const lds_byte* p) {
     return *(const lds_bf16x8*)p;
 }
 
+template <int MW>
 struct Frag {
-    bf16x8 a, w[3];
+    bf16x8 a[MW], w[3];
 };
 
-__global__ __launch_bounds__(kStreamThreads) void fused_ffn_stream_kernel(
+template <int MW, int BK_, int CW>
+__global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W1, const float* __restrict__ b1,
     const bf16_t* __restrict__ W2, const float* __restrict__ b2, bf16_t* __restrict__ Y,
     float* __restrict__ part, int M, int K, int F, int K2, int act) {
@@ -93,6 +117,12 @@ __global__ __launch_bounds__(kStreamThreads) void fused_ffn_stream_kernel(
     lds_byte* smem = (lds_byte*)smem_generic;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    typedef StreamCfg<MW, BK_, CW> C;
+    constexpr int kConsumerWaves = CW, WMG = C::WMG;
+    constexpr int BM = C::BM, BK = C::BK, KSTEPS = C::KSTEPS, TPB = C::TPB;
+    constexpr int kXBlockB = C::kXBlockB, kXSlots = C::kXSlots, kXLead = C::kXLead, kXLoads = C::kXLoads;
+    constexpr int kWTileB = C::kWTileB, kRing1 = C::kRing1, kRing2 = C::kRing2, kB1 = C::kB1;
+    constexpr int kWLoadsPerWave = C::kWLoadsPerWave;
     const int split = blockIdx.x, nsplit = gridDim.x;
     const int m0 = blockIdx.y * BM, f0 = split * FS;
     const int NT1 = K / BK;                 // phase-1 tiles
@@ -101,7 +131,8 @@ __global__ __launch_bounds__(kStreamThreads) void fused_ffn_stream_kernel(
     // The workgroups of one hidden slice run in lockstep on one XCD and would all ask its L2 for the
     // same lines at the same moment (and W1's row stride maps a tile onto few L2 channels): each row
     // block walks the reduction dimension from a different starting tile instead.
-    const int rot1 = 2 * (blockIdx.y % (NT1 / 2)), rot2 = blockIdx.y % (FS / BK);
+    // (the phase-1 rotation is a whole number of X blocks)
+    const int rot1 = TPB * (blockIdx.y % (NT1 / TPB)), rot2 = blockIdx.y % (FS / BK);
 
     if (wave >= kConsumerWaves) {
         // ================================ producers ======================================
@@ -110,42 +141,41 @@ __global__ __launch_bounds__(kStreamThreads) void fused_ffn_stream_kernel(
             // ---- the X wave.  Every row block reads its own rows of X, so these loads miss the L2
             // that serves the (shared) weight tiles and take much longer; loads complete in order
             // within a wave, hence a wave of their own, running kXLead blocks (2 kXLead tiles) ahead.
-            unsigned xoff[8];                 // load q: rows 8 q .. 8 q + 7 x 128 bytes; lane = (row, physical chunk)
+            unsigned xoff[kXLoads];           // load q: rows 8 q .. 8 q + 7 x 128 bytes; lane = (row, physical chunk)
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
+            for (int q = 0; q < kXLoads; ++q) {
                 const int xrow = 8 * q + (lane >> 3);
                 const int xchunk = (lane & 7) ^ ((xrow >> 1) & 7);
                 xoff[q] = (unsigned)min(m0 + xrow, M - 1) * (unsigned)K + 8 * xchunk;
             }
-            const int NB = NT1 / 2;
+            const int NB = NT1 / TPB;
             auto issue_x = [&](int blk) {
                 lds_byte* xs = smem + kXRing + (blk % kXSlots) * kXBlockB;
-                const int kt = 2 * blk + rot1 < NT1 ? 2 * blk + rot1 : 2 * blk + rot1 - NT1;   // rot1 is even
+                const int kt = TPB * blk + rot1 < NT1 ? TPB * blk + rot1 : TPB * blk + rot1 - NT1;
 #pragma unroll
-                for (int q = 0; q < 8; ++q) load_to_lds(X + xoff[q] + kt * BK, xs + q * 1024);
+                for (int q = 0; q < kXLoads; ++q) load_to_lds(X + xoff[q] + kt * BK, xs + q * 1024);
             };
-            auto wait_blocks = [&](int n) {      // at most n blocks (8 loads each) outstanding
-                if (n >= 5) wait_vm<40>();
-                else if (n == 4) wait_vm<32>();
-                else if (n == 3) wait_vm<24>();
-                else if (n == 2) wait_vm<16>();
-                else if (n == 1) wait_vm<8>();
+            auto wait_blocks = [&](int n) {      // at most n blocks (kXLoads loads each) outstanding
+                if (n >= 4) wait_vm<(4 * kXLoads < 64 ? 4 * kXLoads : 63)>();
+                else if (n == 3) wait_vm<3 * kXLoads>();
+                else if (n == 2) wait_vm<2 * kXLoads>();
+                else if (n == 1) wait_vm<kXLoads>();
                 else wait_vm<0>();
             };
             for (int blk = 0; blk < min(kXLead, NB); ++blk) issue_x(blk);
             wait_blocks(min(kXLead, NB) - 1);            // block 0 has landed
             __builtin_amdgcn_s_barrier();
             for (int t = 0; t < NT1; ++t) {
-                const int blk = (t >> 1) + kXLead;
-                if ((t & 1) == 0 && blk < NB) issue_x(blk);
+                const int blk = t / TPB + kXLead;
+                if (t % TPB == 0 && blk < NB) issue_x(blk);
                 // the consumers fetch from tile t + 2 during the next iteration
-                wait_blocks(min(blk, NB - 1) - min((t + 2) >> 1, NB - 1));
+                wait_blocks(min(blk, NB - 1) - min((t + 2) / TPB, NB - 1));
                 __builtin_amdgcn_s_barrier();
             }
             for (int t = 0; t < NT2 + 1; ++t) __builtin_amdgcn_s_barrier();    // phase 2: nothing to load
             return;
         }
-        // W tile: load j of this wave covers LDS chunks 64 (8 pw + j) .. + 63
+        // W tile: load j of this wave covers LDS chunks 64 (kWLoadsPerWave pw + j) .. + 63
         int wk[kWLoadsPerWave], wc[kWLoadsPerWave];
 #pragma unroll
         for (int j = 0; j < kWLoadsPerWave; ++j) {
@@ -221,7 +251,7 @@ __global__ __launch_bounds__(kStreamThreads) void fused_ffn_stream_kernel(
     // ================================== consumers ========================================
     const int i = lane & 31, h = lane >> 5;
     const int g = lane >> 4, s = lane & 15;
-    const int wm = wave & 1, wq = wave >> 1;       // row tile; group of three 32-wide hidden / column tiles
+    const int wm = wave % WMG, wq = wave / WMG;    // row group; group of three 32-wide hidden / column tiles
     float* B1s = reinterpret_cast<float*>(smem_generic + kB1);
     for (int t = tid; t < FS; t += kConsumerWaves * 64) B1s[t] = b1 ? b1[f0 + t] : 0.0f;
 
@@ -233,61 +263,94 @@ __global__ __launch_bounds__(kStreamThreads) void fused_ffn_stream_kernel(
         woff[t] = (8 * (g >> 1) + (s >> 2)) * kRowB + (((6 * wq + 2 * t + (g & 1)) ^ sw) << 5) + 8 * (s & 3);
 
     // ------------------------------ phase 1 -------------------------------------------
+    // Fragment sets ping-pong: with two k steps per tile (BK = 32) set 0 / 1 hold k step 0 / 1 of the
+    // current tile and are re-filled for the next tile; with one k step per tile (BK = 16) set 0 / 1
+    // hold even / odd tiles.  "Step" u below = k step u of the stream (tile u / KSTEPS, k step u % KSTEPS).
     {
-        const int xrow = 32 * wm + i;
-        // byte offset of this lane's chunk in an X block for k step 0 / 1 of the block's first tile;
-        // the second tile's chunks are 4 further on, which after the XOR swizzle is bit 6 flipped
-        const int xoff0 = xrow * 128 + ((h ^ ((xrow >> 1) & 7)) << 4);
-        const int xoff1 = xrow * 128 + (((2 + h) ^ ((xrow >> 1) & 7)) << 4);
-        f32x16 acc[3];
+        // byte offset of this lane's chunk in an X block: row (32 (MW wm + mt) + i), logical chunk
+        // 2 (k step within the block) + h, chunk ^= (row >> 1) & 7
+        int xbase[MW], xsw[MW];
 #pragma unroll
-        for (int t = 0; t < 3; ++t)
+        for (int mt = 0; mt < MW; ++mt) {
+            const int xrow = 32 * (MW * wm + mt) + i;
+            xbase[mt] = xrow * 128;
+            xsw[mt] = (xrow >> 1) & 7;
+        }
+        f32x16 acc[MW][3];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-        auto fetch = [&](Frag& fr, int tile, int ks) {      // past the last tile: stale data, never used
+        for (int mt = 0; mt < MW; ++mt)
+#pragma unroll
+            for (int t = 0; t < 3; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mt][t][r] = 0.0f;
+        auto fetch = [&](Frag<MW>& fr, int step) {          // past the last tile: stale data, never used
+            const int tile = step / KSTEPS, ks = step % KSTEPS;
             const lds_byte* st = smem + kRing1 + (tile & (NST - 1)) * kWTileB;
-            const lds_byte* xs = smem + kXRing + ((tile >> 1) % kXSlots) * kXBlockB;
-            fr.a = read_a_frag(xs + ((ks ? xoff1 : xoff0) ^ ((tile & 1) << 6)));
+            const lds_byte* xs = smem + kXRing + ((tile / TPB) % kXSlots) * kXBlockB;
+            const int chunk = 2 * (step & 3) + h;            // four k steps per 64-deep block
+#pragma unroll
+            for (int mt = 0; mt < MW; ++mt) fr.a[mt] = read_a_frag(xs + xbase[mt] + ((chunk ^ xsw[mt]) << 4));
 #pragma unroll
             for (int t = 0; t < 3; ++t) fr.w[t] = read_w_frag(st + woff[t] + ks * 16 * kRowB);
         };
-        Frag f0r, f1r;
+        auto mma = [&](const Frag<MW>& fr) {
+#pragma unroll
+            for (int mt = 0; mt < MW; ++mt)
+#pragma unroll
+                for (int u = 0; u < 3; ++u) acc[mt][u] = mfma32(fr.w[u], fr.a[mt], acc[mt][u]);
+        };
+        Frag<MW> f0r, f1r;
         __builtin_amdgcn_s_barrier();              // tiles 0 and 1 are in LDS
-        fetch(f0r, 0, 0);
-        fetch(f1r, 0, 1);
-        for (int t = 0; t < NT1; ++t) {
-            const int nx = t + 1;
-            // each fragment set is re-filled (for the next tile) right after the matrix instructions
-            // that read it have been issued: no copies, and the reads have most of a tile to land
-#pragma unroll
-            for (int u = 0; u < 3; ++u) acc[u] = mfma32(f0r.w[u], f0r.a, acc[u]);
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(f0r, nx, 0);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < 3; ++u) acc[u] = mfma32(f1r.w[u], f1r.a, acc[u]);
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(f1r, nx, 1);
-            __builtin_amdgcn_s_barrier();
+        fetch(f0r, 0);
+        fetch(f1r, 1);
+        // each fragment set is re-filled right after the matrix instructions that read it have been
+        // issued: no copies, and the reads have most of a tile to land
+        if constexpr (KSTEPS == 2) {
+            for (int t = 0; t < NT1; ++t) {
+                mma(f0r);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(f0r, 2 * t + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(f1r);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(f1r, 2 * t + 3);
+                __builtin_amdgcn_s_barrier();
+            }
+        } else {
+            // one k step per tile: tile t + 2 is only guaranteed to have landed after barrier t, so the
+            // set freed in iteration t is re-filled at the start of iteration t + 1 (NT1 is even)
+            for (int t = 0; t < NT1; t += 2) {
+                mma(f0r);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t > 0) fetch(f1r, t + 1);
+                __builtin_amdgcn_s_barrier();
+                mma(f1r);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(f0r, t + 2);
+                __builtin_amdgcn_s_barrier();
+            }
         }
         // epilogue: bias + activation, round to bf16, Hs[m][f] (f contiguous = phase-2 k).
         // acc rows = hidden units, columns = rows of X.
         bf16_t* Hs = reinterpret_cast<bf16_t*>(smem_generic);
-        const int ml = 32 * wm + i;
         auto epilogue = [&](auto act_tag) {
             constexpr int ACT = decltype(act_tag)::value;
 #pragma unroll
-            for (int t = 0; t < 3; ++t)
+            for (int mt = 0; mt < MW; ++mt) {
+                const int ml = 32 * (MW * wm + mt) + i;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int fl = 96 * wq + 32 * t + 8 * q + 4 * h;
-                    const float4 bv = *reinterpret_cast<const float4*>(B1s + fl);
-                    const float v0 = apply_act<ACT>(acc[t][4 * q + 0] + bv.x);
-                    const float v1 = apply_act<ACT>(acc[t][4 * q + 1] + bv.y);
-                    const float v2 = apply_act<ACT>(acc[t][4 * q + 2] + bv.z);
-                    const float v3 = apply_act<ACT>(acc[t][4 * q + 3] + bv.w);
-                    *reinterpret_cast<uint2*>(Hs + ml * kHsLd + fl) = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
-                }
+                for (int t = 0; t < 3; ++t)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int fl = 96 * wq + 32 * t + 8 * q + 4 * h;
+                        const float4 bv = *reinterpret_cast<const float4*>(B1s + fl);
+                        const float v0 = apply_act<ACT>(acc[mt][t][4 * q + 0] + bv.x);
+                        const float v1 = apply_act<ACT>(acc[mt][t][4 * q + 1] + bv.y);
+                        const float v2 = apply_act<ACT>(acc[mt][t][4 * q + 2] + bv.z);
+                        const float v3 = apply_act<ACT>(acc[mt][t][4 * q + 3] + bv.w);
+                        *reinterpret_cast<uint2*>(Hs + ml * kHsLd + fl) = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
+                    }
+            }
         };
         switch (act) {          // uniform
             case kGeluTanh: epilogue(std::integral_constant<int, kGeluTanh>()); break;
@@ -301,65 +364,91 @@ __global__ __launch_bounds__(kStreamThreads) void fused_ffn_stream_kernel(
     // ------------------------------ phase 2 -------------------------------------------
     {
         const bool full_block = m0 + BM <= M;
-        const lds_byte* hs = smem + (32 * wm + i) * (kHsLd * 2) + 16 * h;
-        f32x16 acc[3];             // rows = rows of X, columns = output columns
+        const lds_byte* hs = smem + (32 * MW * wm + i) * (kHsLd * 2) + 16 * h;
+        f32x16 acc[MW][3];         // rows = rows of X, columns = output columns
 #pragma unroll
-        for (int t = 0; t < 3; ++t)
+        for (int mt = 0; mt < MW; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-        constexpr int KT = FS / BK;      // 12 tiles per column block
-        auto fetch = [&](Frag& fr, int tile, int ks) {
+            for (int t = 0; t < 3; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mt][t][r] = 0.0f;
+        constexpr int KT = FS / BK;      // tiles per column block
+        auto fetch = [&](Frag<MW>& fr, int step) {
+            const int tile = step / KSTEPS, ks = step % KSTEPS;
             const lds_byte* st = smem + kRing2 + (tile & (NST - 1)) * kWTileB;
-            fr.a = read_a_frag(hs + (((tile + rot2) % KT) * BK + ks * 16) * 2);
+            const int kbyte = (((tile + rot2) % KT) * BK + ks * 16) * 2;
+#pragma unroll
+            for (int mt = 0; mt < MW; ++mt) fr.a[mt] = read_a_frag(hs + mt * 32 * (kHsLd * 2) + kbyte);
 #pragma unroll
             for (int t = 0; t < 3; ++t) fr.w[t] = read_w_frag(st + woff[t] + ks * 16 * kRowB);
         };
-        Frag f0r, f1r;
-        fetch(f0r, 0, 0);
-        fetch(f1r, 0, 1);
+        auto mma = [&](const Frag<MW>& fr) {
+#pragma unroll
+            for (int mt = 0; mt < MW; ++mt)
+#pragma unroll
+                for (int u = 0; u < 3; ++u) acc[mt][u] = mfma32(fr.a[mt], fr.w[u], acc[mt][u]);
+        };
+        Frag<MW> f0r, f1r;
+        fetch(f0r, 0);
+        fetch(f1r, 1);
         for (int cb = 0; cb < NCB; ++cb) {
-            for (int kt = 0; kt < KT; ++kt) {
-                const int tile = cb * KT + kt;
-#pragma unroll
-                for (int u = 0; u < 3; ++u) acc[u] = mfma32(f0r.a, f0r.w[u], acc[u]);
-                __builtin_amdgcn_sched_barrier(0);
-                fetch(f0r, tile + 1, 0);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int u = 0; u < 3; ++u) acc[u] = mfma32(f1r.a, f1r.w[u], acc[u]);
-                __builtin_amdgcn_sched_barrier(0);
-                fetch(f1r, tile + 1, 1);
-                __builtin_amdgcn_s_barrier();
+            if constexpr (KSTEPS == 2) {
+                for (int kt = 0; kt < KT; ++kt) {
+                    const int tile = cb * KT + kt;
+                    mma(f0r);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fetch(f0r, 2 * tile + 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma(f1r);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fetch(f1r, 2 * tile + 3);
+                    __builtin_amdgcn_s_barrier();
+                }
+            } else {
+                for (int kt = 0; kt < KT; kt += 2) {          // KT is even
+                    const int tile = cb * KT + kt;
+                    mma(f0r);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (tile > 0) fetch(f1r, tile + 1);
+                    __builtin_amdgcn_s_barrier();
+                    mma(f1r);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fetch(f0r, tile + 2);
+                    __builtin_amdgcn_s_barrier();
+                }
             }
             // this column block is complete: lane = output column, registers = rows of X
             // (32 lanes write 128 contiguous bytes of one row); 32-bit element offsets
-            const unsigned row0 = m0 + 32 * wm + 4 * h;
-            if (nsplit != 1 && full_block) {          // uniform: the common case, plain stores
 #pragma unroll
-                for (int t = 0; t < 3; ++t) {
-                    const unsigned col = cb * CB + 96 * wq + 32 * t + i;
-                    const unsigned base = ((unsigned)split * (unsigned)M + row0) * (unsigned)K2 + col;
+            for (int mt = 0; mt < MW; ++mt) {
+                const unsigned row0 = m0 + 32 * (MW * wm + mt) + 4 * h;
+                if (nsplit != 1 && full_block) {          // uniform: the common case, plain stores
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        part[base + (unsigned)(8 * (r >> 2) + (r & 3)) * (unsigned)K2] = acc[t][r];
-                        acc[t][r] = 0.0f;
-                    }
-                }
-            } else {
+                    for (int t = 0; t < 3; ++t) {
+                        const unsigned col = cb * CB + 96 * wq + 32 * t + i;
+                        const unsigned base = ((unsigned)split * (unsigned)M + row0) * (unsigned)K2 + col;
 #pragma unroll
-                for (int t = 0; t < 3; ++t) {
-                    const unsigned col = cb * CB + 96 * wq + 32 * t + i;
-                    const float bv = (nsplit == 1 && b2) ? b2[col] : 0.0f;
-                    const unsigned base = ((nsplit == 1 ? 0u : (unsigned)split * (unsigned)M) + row0) * (unsigned)K2 + col;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int dr = 8 * (r >> 2) + (r & 3);
-                        if ((int)row0 + dr < M) {
-                            const unsigned idx = base + (unsigned)dr * (unsigned)K2;
-                            if (nsplit == 1) Y[idx] = (bf16_t)(acc[t][r] + bv);
-                            else part[idx] = acc[t][r];
+                        for (int r = 0; r < 16; ++r) {
+                            part[base + (unsigned)(8 * (r >> 2) + (r & 3)) * (unsigned)K2] = acc[mt][t][r];
+                            acc[mt][t][r] = 0.0f;
                         }
-                        acc[t][r] = 0.0f;
+                    }
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 3; ++t) {
+                        const unsigned col = cb * CB + 96 * wq + 32 * t + i;
+                        const float bv = (nsplit == 1 && b2) ? b2[col] : 0.0f;
+                        const unsigned base = ((nsplit == 1 ? 0u : (unsigned)split * (unsigned)M) + row0) * (unsigned)K2 + col;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int dr = 8 * (r >> 2) + (r & 3);
+                            if ((int)row0 + dr < M) {
+                                const unsigned idx = base + (unsigned)dr * (unsigned)K2;
+                                if (nsplit == 1) Y[idx] = (bf16_t)(acc[mt][t][r] + bv);
+                                else part[idx] = acc[mt][t][r];
+                            }
+                            acc[mt][t][r] = 0.0f;
+                        }
                     }
                 }
             }
@@ -374,27 +463,37 @@ bool fused_ffn_stream_ok(int M, int K, int F, int K2) {
     return K % 64 == 0 && F % FS == 0 && K2 % CB == 0 && K >= 64;
 }
 
-hipError_t fused_ffn_stream(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
-                            void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s) {
-    if (!fused_ffn_stream_ok(M, K, F, K2)) return hipErrorInvalidValue;
-    auto kern = fused_ffn_stream_kernel;
+template <int MW, int BK_, int CW>
+static hipError_t launch_stream(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
+                                void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s) {
+    typedef StreamCfg<MW, BK_, CW> C;
+    auto kern = fused_ffn_stream_kernel<MW, BK_, CW>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kStreamSmem);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kSmem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int nsplit = F / FS;
-    dim3 grid(nsplit, (M + BM - 1) / BM);
+    dim3 grid(nsplit, (M + C::BM - 1) / C::BM);
     prof_start(2, s);
-    prof_shape(2, grid.x * grid.y, kStreamThreads);
-    hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), kStreamSmem, s, (const bf16_t*)x, (const bf16_t*)w1, b1,
+    prof_shape(2, grid.x * grid.y, C::kThreads);
+    hipLaunchKernelGGL(kern, grid, dim3(C::kThreads), C::kSmem, s, (const bf16_t*)x, (const bf16_t*)w1, b1,
                        (const bf16_t*)w2, b2, (bf16_t*)y, (float*)workspace, M, K, F, K2, act);
     prof_stop(2, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nsplit == 1) return e;
     return ffn_reduce((const float*)workspace, b2, y, (long)M * K2, K2, nsplit, s);
+}
+
+// variant 0: eight consumer waves with 32 x 96 wave tiles; 1: four consumer waves with 64 x 96 wave tiles
+hipError_t fused_ffn_stream(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
+                            void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s,
+                            int variant) {
+    if (!fused_ffn_stream_ok(M, K, F, K2)) return hipErrorInvalidValue;
+    if (variant == 1) return launch_stream<2, 32, 4>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+    return launch_stream<1, 32, 8>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
 }
 
 }  // namespace ago

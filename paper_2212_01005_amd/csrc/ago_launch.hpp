@@ -63,7 +63,8 @@ int fused_conv_chain_num_cfgs();
 // streaming (wave-specialised) FFN variant and the partial-product reduction shared by both variants
 bool fused_ffn_stream_ok(int M, int K, int F, int K2);
 hipError_t fused_ffn_stream(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
-                            void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s);
+                            void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s,
+                            int variant = 0);
 hipError_t ffn_reduce(const float* part, const float* b2, void* y, long MK2, int K2, int nsplit, hipStream_t s);
 int fused_ffn_num_cfgs();
 int fused_attn_num_cfgs();
