@@ -48,6 +48,9 @@ def alloc_output(case, device="cuda:0"):
     k = type(case).__name__
     if k == "PairCase":
         return torch.empty(case.out_shape(), dtype=td, device=device)
+    if k == "QkvCase":          # q, k, v stacked
+        inner = (case.B, case.Hh, case.S, case.D) if case.head_major else (case.B, case.S, case.Hh, case.D)
+        return torch.empty((3,) + inner, dtype=td, device=device)
     if k == "InvresCase":
         shape = (case.N, case.OH, case.OW, case.Cout)
     elif k == "ChainCase":
@@ -60,6 +63,8 @@ def alloc_output(case, device="cuda:0"):
 
 
 def alloc_workspace(case, fused=True, device="cuda:0"):
+    if type(case).__name__ == "QkvCase":
+        return None
     if type(case).__name__ == "PairCase":
         if case.kind != "pw_pw" or not fused:
             return None
@@ -83,6 +88,9 @@ def _fused_call(case, t, y, ws):
         if case.kind == "dw_dw":
             return ago.ago_fused_dw_dw, (t["x"], t["wd"], t["bd"], t["wd2"], t["bd2"], y, case.stride, ws)
         return ago.ago_fused_pw_pw, (t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, _ACT[case.act], ws)
+    if k == "QkvCase":
+        return ago.ago_fused_qkv, (t["x"], t["wq"], t["wk"], t["wv"], t["bq"], t["bk"], t["bv"], y[0], y[1], y[2],
+                                   case.head_major, ws)
     if k == "InvresCase" and case.ksize != 3:
         return ago.ago_fused_invres_k, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], t["w2"], t["b2"], y,
                                         case.stride, case.residual, ws)

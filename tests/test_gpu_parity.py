@@ -345,6 +345,25 @@ def _random_cases():
         s_len = int(r.choice([1, 31, 33, 64, 127, 129, 191, 193, 255, 257, 400, 513]))
         cases.append(wl.AttnCase(int(r.randint(1, 3)), int(r.randint(1, 6)), s_len, 64, float(r.choice([0.125, 0.3])),
                                  "bf16", 5300 + i, name="rand_attn_%d" % i))
+    # the widened entry points: 5x5 depthwise, expanded channels in chunks, biased attention, sibling projections
+    for i in range(6):
+        stride = int(r.choice([1, 2]))
+        cin = int(r.choice([16, 40, 80, 112]))
+        cexp = int(r.choice([96, 240, 480, 672, 960]))
+        cout = cin if (stride == 1 and r.rand() < 0.5) else int(r.choice([24, 48, 160]))
+        cases.append(wl.InvresCase(int(r.randint(1, 3)), int(r.randint(1, 15)), int(r.randint(1, 15)), cin, cexp, cout,
+                                   stride, stride == 1 and cin == cout, bool(r.rand() < 0.7),
+                                   str(r.choice(["f32", "bf16"])), 5400 + i, name="rand_invres_wide_%d" % i,
+                                   ksize=int(r.choice([3, 5]))))
+    for i in range(5):
+        s_len = int(r.choice([7, 64, 100, 136, 200, 264, 391]))
+        cases.append(wl.AttnCase(int(r.randint(1, 3)), int(r.randint(1, 5)), s_len, 64, float(r.choice([0.125, 0.2])),
+                                 "bf16", 5500 + i, name="rand_attn_bias_%d" % i,
+                                 bias=str(r.choice(["full", "head", "batch"]))))
+    for i in range(5):
+        cases.append(wl.QkvCase(int(r.randint(1, 4)), int(r.randint(1, 150)), 8 * int(r.randint(1, 40)),
+                                int(r.randint(1, 7)), int(r.choice([8, 24, 64, 128])), bool(r.rand() < 0.5),
+                                bool(r.rand() < 0.7), "bf16", 5600 + i, name="rand_qkv_%d" % i))
     return cases
 
 
