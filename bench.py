@@ -32,7 +32,7 @@ PEAK_F32_TFLOPS = 157.3       # fp32 MFMA / vector
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the fused FFN kernel at the benchmark shape: FETCH_SIZE + WRITE_SIZE from
 # rocprofv3 --pmc, scaled by a 256 MiB copy (profiles/bench_all_fused_subgraphs.md).
-FFN_TRAFFIC_BYTES = 85094092
+FFN_TRAFFIC_BYTES = 85097536
 
 
 def parse():
@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--detail-iters", type=int, default=100, help="launches per variant in the per-config table")
     ap.add_argument("--streams", type=int, default=5,
                     help="HIP streams (default priority) the subgraphs of a step are spread over; 1 = back to back")
+    ap.add_argument("--no-one-stream", action="store_true",
+                    help="skip the second, back-to-back pass on one stream (profiling aid: a kernel trace then "
+                         "holds the timed region only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true")
     ap.add_argument("--only", type=int, default=-1, help="run only this configuration in the timed step (profiling aid)")
@@ -155,7 +158,7 @@ def main():
     # the same steps back to back on one stream (not the headline: what the overlap is worth, and the
     # dominant kernel's duration with the chip to itself)
     one_stream = None
-    if args.streams > 1:
+    if args.streams > 1 and not args.no_one_stream:
         serial = prepare_step(1)
         for _ in range(args.warmup):
             for launch in serial:
