@@ -146,7 +146,8 @@ ago_status ago_fused_conv_chain(const void* x, const void* wa, const float* ba,
  *   y = act(x w1 + b1) w2 + b2
  * x:[M,K] w1:[K,F] w2:[F,K2] y:[M,K2].  bf16 only.  The hidden activation never
  * leaves the chip; partial sums over slices of F go through `workspace`.
- * Requires K % 64 == 0, F % 64 == 0, K2 % 128 == 0 (else UNSUPPORTED). */
+ * Requires K % 64 == 0, F % 8 == 0, K2 % 8 == 0 (else UNSUPPORTED); F and K2 need not be multiples of
+ * the kernel's 384-wide hidden slices and column blocks. */
 ago_status ago_fused_ffn(const void* x, const void* w1, const float* b1,
                          const void* w2, const float* b2, void* y,
                          int M, int K, int F, int K2, ago_act act, ago_dtype dt,

@@ -338,7 +338,8 @@ static hipError_t launch_ffn(const void* x, const void* w1, const float* b1, con
 // Tile configurations (BM rows, FS hidden slice, phase-2 column block BN2):
 //   0: 128 x 192, 128   1: 128 x 128, 128   2: 128 x 64, 128
 //   3: the wave-specialised streaming kernel (64 x 384, 384); the built-in choice whenever the
-//      shape allows it (K % 64 == 0, F % 384 == 0, K2 % 384 == 0)
+//      shape allows it (K % 64 == 0, F % 8 == 0, K2 % 8 == 0; the last hidden slice and the last
+//      column block may be ragged)
 //   4: the streaming kernel with four consumer waves of 64 x 96 wave tiles (64 x 384, 384), same shape rules
 int fused_ffn_num_cfgs() { return 5; }
 
@@ -363,7 +364,7 @@ int fused_ffn_pick_cfg(int M, int K, int F, int K2, int tile_cfg) {
 
 int fused_ffn_nsplit(int cfg, int F) {
     static const int fs[5] = {192, 128, 64, 384, 384};
-    return (cfg >= 0 && cfg < 5) ? F / fs[cfg] : 0;
+    return (cfg >= 0 && cfg < 5) ? (F + fs[cfg] - 1) / fs[cfg] : 0;     // only the streaming kernels take ragged slices
 }
 
 hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,

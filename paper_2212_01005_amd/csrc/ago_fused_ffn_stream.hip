@@ -108,7 +108,8 @@ struct Frag {
     bf16x8 a[MW], w[3];
 };
 
-template <int MW, int BK_, int CW>
+// RAGGED: F or K2 is not a multiple of 384 (the exact instantiation carries none of the clamps and masks)
+template <int MW, int BK_, int CW, bool RAGGED>
 __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W1, const float* __restrict__ b1,
     const bf16_t* __restrict__ W2, const float* __restrict__ b2, bf16_t* __restrict__ Y,
@@ -126,7 +127,12 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
     const int split = blockIdx.x, nsplit = gridDim.x;
     const int m0 = blockIdx.y * BM, f0 = split * FS;
     const int NT1 = K / BK;                 // phase-1 tiles
-    const int NCB = K2 / CB;                // phase-2 column blocks
+    const int NCB = (K2 + CB - 1) / CB;     // phase-2 column blocks (the last one may be ragged)
+    // The last hidden slice may be ragged too (F and K2 are multiples of 8, one 16-byte chunk).  The
+    // producers clamp what they fetch beyond F / K2 to valid addresses; the hidden units beyond F are
+    // written as 0 into Hs, so whatever W2 rows stand in for them contribute nothing, and columns
+    // beyond K2 are never stored.
+    const int fvalid = RAGGED ? min(FS, F - f0) : FS;     // hidden units of this slice that exist
     const int NT2 = NCB * (FS / BK);        // phase-2 tiles
     // The workgroups of one hidden slice run in lockstep on one XCD and would all ask its L2 for the
     // same lines at the same moment (and W1's row stride maps a tile onto few L2 channels): each row
@@ -189,7 +195,8 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
         {
             unsigned woff[kWLoadsPerWave];
 #pragma unroll
-            for (int j = 0; j < kWLoadsPerWave; ++j) woff[j] = (unsigned)wk[j] * (unsigned)F + wc[j];
+            for (int j = 0; j < kWLoadsPerWave; ++j)
+                woff[j] = (unsigned)wk[j] * (unsigned)F + (RAGGED ? min(wc[j], fvalid - 8) : wc[j]);
             const bf16_t* wsrc = W1 + f0;
             auto issue = [&](int t) {
                 lds_byte* st = smem + kRing1 + (t & (NST - 1)) * kWTileB;
@@ -224,10 +231,20 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
             auto issue = [&](int t) {
                 const int cb = t / (FS / BK), kt = (t + rot2) % (FS / BK);
                 lds_byte* st = smem + kRing2 + (t & (NST - 1)) * kWTileB;
-                const bf16_t* w = wsrc + (long)kt * BK * K2 + cb * CB;
+                if constexpr (RAGGED) {
+                    const bf16_t* w = wsrc + cb * CB;
+                    const int cvalid = min(CB, K2 - cb * CB);       // columns of this block that exist
 #pragma unroll
-                for (int j = 0; j < kWLoadsPerWave; ++j)
-                    load_to_lds(w + woff[j], st + (kWLoadsPerWave * pw + j) * 1024);
+                    for (int j = 0; j < kWLoadsPerWave; ++j) {
+                        const unsigned row = (unsigned)min(kt * BK + wk[j], fvalid - 1);
+                        load_to_lds(w + row * (unsigned)K2 + min(wc[j], cvalid - 8), st + (kWLoadsPerWave * pw + j) * 1024);
+                    }
+                } else {
+                    const bf16_t* w = wsrc + (long)kt * BK * K2 + cb * CB;
+#pragma unroll
+                    for (int j = 0; j < kWLoadsPerWave; ++j)
+                        load_to_lds(w + woff[j], st + (kWLoadsPerWave * pw + j) * 1024);
+                }
             };
             constexpr int PER = kWLoadsPerWave;
             issue(0);
@@ -253,7 +270,7 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
     const int g = lane >> 4, s = lane & 15;
     const int wm = wave % WMG, wq = wave / WMG;    // row group; group of three 32-wide hidden / column tiles
     float* B1s = reinterpret_cast<float*>(smem_generic + kB1);
-    for (int t = tid; t < FS; t += kConsumerWaves * 64) B1s[t] = b1 ? b1[f0 + t] : 0.0f;
+    for (int t = tid; t < FS; t += kConsumerWaves * 64) B1s[t] = (b1 && (!RAGGED || t < fvalid)) ? b1[f0 + t] : 0.0f;
 
     // lane offsets inside a weight tile for the three column tiles of this wave (k step 0, rows 0..3)
     const int sw = ((s >> 2) << 1) | (g >> 1);
@@ -348,7 +365,8 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
                         const float v1 = apply_act<ACT>(acc[mt][t][4 * q + 1] + bv.y);
                         const float v2 = apply_act<ACT>(acc[mt][t][4 * q + 2] + bv.z);
                         const float v3 = apply_act<ACT>(acc[mt][t][4 * q + 3] + bv.w);
-                        *reinterpret_cast<uint2*>(Hs + ml * kHsLd + fl) = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
+                        *reinterpret_cast<uint2*>(Hs + ml * kHsLd + fl) =
+                            (!RAGGED || fl < fvalid) ? make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3)) : make_uint2(0u, 0u);
                     }
             }
         };
@@ -422,7 +440,7 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
 #pragma unroll
             for (int mt = 0; mt < MW; ++mt) {
                 const unsigned row0 = m0 + 32 * (MW * wm + mt) + 4 * h;
-                if (nsplit != 1 && full_block) {          // uniform: the common case, plain stores
+                if (nsplit != 1 && full_block && (!RAGGED || (cb + 1) * CB <= K2)) {   // uniform: the common case, plain stores
 #pragma unroll
                     for (int t = 0; t < 3; ++t) {
                         const unsigned col = cb * CB + 96 * wq + 32 * t + i;
@@ -437,12 +455,12 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
 #pragma unroll
                     for (int t = 0; t < 3; ++t) {
                         const unsigned col = cb * CB + 96 * wq + 32 * t + i;
-                        const float bv = (nsplit == 1 && b2) ? b2[col] : 0.0f;
+                        const float bv = (nsplit == 1 && b2 && (!RAGGED || (int)col < K2)) ? b2[col] : 0.0f;
                         const unsigned base = ((nsplit == 1 ? 0u : (unsigned)split * (unsigned)M) + row0) * (unsigned)K2 + col;
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int dr = 8 * (r >> 2) + (r & 3);
-                            if ((int)row0 + dr < M) {
+                            if ((int)row0 + dr < M && (!RAGGED || (int)col < K2)) {
                                 const unsigned idx = base + (unsigned)dr * (unsigned)K2;
                                 if (nsplit == 1) Y[idx] = (bf16_t)(acc[mt][t][r] + bv);
                                 else part[idx] = acc[mt][t][r];
@@ -460,14 +478,14 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
 
 bool fused_ffn_stream_ok(int M, int K, int F, int K2) {
     (void)M;
-    return K % 64 == 0 && F % FS == 0 && K2 % CB == 0 && K >= 64;
+    return K % 64 == 0 && K >= 64 && F % 8 == 0 && K2 % 8 == 0 && F >= 8 && K2 >= 8;
 }
 
-template <int MW, int BK_, int CW>
+template <int MW, int BK_, int CW, bool RAGGED>
 static hipError_t launch_stream(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
                                 void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s) {
     typedef StreamCfg<MW, BK_, CW> C;
-    auto kern = fused_ffn_stream_kernel<MW, BK_, CW>;
+    auto kern = fused_ffn_stream_kernel<MW, BK_, CW, RAGGED>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -475,7 +493,7 @@ static hipError_t launch_stream(const void* x, const void* w1, const float* b1, 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int nsplit = F / FS;
+    const int nsplit = (F + FS - 1) / FS;
     dim3 grid(nsplit, (M + C::BM - 1) / C::BM);
     prof_start(2, s);
     prof_shape(2, grid.x * grid.y, C::kThreads);
@@ -492,8 +510,15 @@ hipError_t fused_ffn_stream(const void* x, const void* w1, const float* b1, cons
                             void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s,
                             int variant) {
     if (!fused_ffn_stream_ok(M, K, F, K2)) return hipErrorInvalidValue;
-    if (variant == 1) return launch_stream<2, 32, 4>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
-    return launch_stream<1, 32, 8>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+    const bool ragged = F % FS != 0 || K2 % CB != 0;
+    if (variant == 1) {
+        if (ragged) return launch_stream<2, 32, 4, true>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+        return launch_stream<2, 32, 4, false>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+    }
+    // the eight-consumer-wave instantiation spills a few registers once the ragged clamps are in; the
+    // four-consumer-wave one (same speed) does not, so ragged shapes always take it
+    if (ragged) return launch_stream<2, 32, 4, true>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+    return launch_stream<1, 32, 8, false>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
 }
 
 }  // namespace ago

@@ -96,7 +96,7 @@ ago_status check_ffn(const void* x, const void* w1, const void* w2, const void* 
     const void* ps[6] = {x, w1, w2, y, b1, b2};
     for (const void* p : ps)
         if (p && !aligned16(p)) return AGO_ERR_ALIGN;
-    if (dt != AGO_BF16 || K % 64 || F % 64 || K2 % 128) return AGO_ERR_UNSUPPORTED;
+    if (dt != AGO_BF16 || K % 64 || F % 8 || K2 % 8) return AGO_ERR_UNSUPPORTED;
     return AGO_OK;
 }
 

@@ -126,7 +126,9 @@ def test_validation_runs_before_any_gpu_call(lib):
     assert ffn(p, p, p, p, 0, 64, 64, 64) == 2                            # shape
     assert ffn(_fake(0x1004), p, p, p, 128, 64, 64, 64) == 4              # alignment
     assert ffn(p, p, p, p, 128, 64, 64, 64, dt=0) == 5                    # fp32 FFN unsupported
-    assert ffn(p, p, p, p, 128, 64, 72, 64) == 5                          # F not tileable
+    assert ffn(p, p, p, p, 128, 64, 76, 64) == 5                          # F not a multiple of 8
+    assert ffn(p, p, p, p, 128, 64, 72, 60) == 5                          # K2 not a multiple of 8
+    assert ffn(p, p, p, p, 128, 96, 72, 64) == 5                          # K not a multiple of 64
     assert ffn(p, p, p, p, 128, 64, 3072, 768) == 6                       # workspace missing
     assert ffn(p, p, p, p, 128, 64, 3072, 768, ws=_fake(), wsz=16) == 6   # workspace too small
 

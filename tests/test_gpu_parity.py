@@ -252,6 +252,30 @@ def test_invres_planner_choice_is_near_the_best_candidate(gpu):
         assert times[-1] <= 1.25 * best + 1.0, (case.name, times)
 
 
+def test_ffn_ragged_hidden_slices_and_column_blocks(gpu, oracle):
+    """F and K2 that are not multiples of the streaming kernel's 384-wide hidden slices / column blocks
+    (BERT-large's 1024 -> 4096 -> 1024 among them): the last slice / block is clamped and masked."""
+    torch, ago, runner = gpu
+    cases = [wl.FfnCase(100, 128, 520, 264, "bf16", 6700, name="ffn_f520_k264"),
+             wl.FfnCase(70, 64, 8, 8, "bf16", 6701, name="ffn_f8_k8"),
+             wl.FfnCase(130, 192, 392, 768, "bf16", 6702, name="ffn_f392"),
+             wl.FfnCase(64, 256, 768, 1000, "bf16", 6703, name="ffn_k1000"),
+             wl.FfnCase(512, 1024, 4096, 1024, "bf16", 6704, name="ffn_bert_large_512")]
+    for case in cases:
+        ref = oracle.run_case(case)
+        t = runner.to_device(case)
+        try:
+            for cfg in (-1, 3, 4):
+                ago.set_tile_config(ago.OP_FUSED_FFN, cfg)
+                y = runner.alloc_output(case)
+                y.zero_()
+                runner.run_fused(case, t, y, runner.alloc_workspace(case, fused=True))
+                torch.cuda.synchronize()
+                assert_close(runner.to_numpy64(y), ref, "bf16", "%s cfg %d" % (case.name, cfg))
+        finally:
+            ago.set_tile_config(ago.OP_FUSED_FFN, -1)
+
+
 def test_sibling_qkv_projection(gpu, oracle):
     """q, k, v = x W* + b* in one kernel, both output layouts, ragged row and column blocks; then the
     projections feed the attention chain without a transpose in between."""
