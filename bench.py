@@ -111,8 +111,11 @@ def main():
         out = []
         for i, (c, t, y, ws) in enumerate(state):
             with torch.cuda.stream(streams[i % len(streams)]):
-                out.append(runner.prepare_fused(c, t, y, ws))
-        return out
+                out.append((c.flops(), runner.prepare_fused(c, t, y, ws)))
+        # largest subgraph first: the launch that needs every compute unit goes out before the small
+        # ones have spread over the chip (worth about 4% of the step against the listed order)
+        out.sort(key=lambda p: -p[0])
+        return [launch for _, launch in out]
 
     def timed(launches, steps, sample_mask):
         """steps passes; the library brackets the kernels in sample_mask with an event pair on every
