@@ -116,8 +116,8 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
     float* __restrict__ part, int M, int K, int F, int K2, int act) {
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_byte* smem = (lds_byte*)smem_generic;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tid0 = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
     typedef StreamCfg<MW, BK_, CW> C;
     constexpr int kConsumerWaves = CW, WMG = C::WMG;
     constexpr int BM = C::BM, BK = C::BK, KSTEPS = C::KSTEPS, TPB = C::TPB;
@@ -125,7 +125,8 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
     constexpr int kWTileB = C::kWTileB, kRing1 = C::kRing1, kRing2 = C::kRing2, kB1 = C::kB1;
     constexpr int kWLoadsPerWave = C::kWLoadsPerWave;
     const int split = blockIdx.x, nsplit = gridDim.x;
-    const int m0 = blockIdx.y * BM, f0 = split * FS;
+    const int f0 = split * FS;
+    const int nrb = (M + BM - 1) / BM;       // row blocks; a workgroup walks blockIdx.y, blockIdx.y + gridDim.y, ...
     const int NT1 = K / BK;                 // phase-1 tiles
     const int NCB = (K2 + CB - 1) / CB;     // phase-2 column blocks (the last one may be ragged)
     // The last hidden slice may be ragged too (F and K2 are multiples of 8, one 16-byte chunk).  The
@@ -138,7 +139,17 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
     // same lines at the same moment (and W1's row stride maps a tile onto few L2 channels): each row
     // block walks the reduction dimension from a different starting tile instead.
     // (the phase-1 rotation is a whole number of X blocks)
-    const int rot1 = TPB * (blockIdx.y % (NT1 / TPB)), rot2 = blockIdx.y % (FS / BK);
+    // Every pass of this loop is one row block, start to finish, with the same number of workgroup
+    // barriers for every wave; the next pass's first loads only overwrite LDS that the previous pass has
+    // finished reading before its last barrier.
+    for (int rb = blockIdx.y; rb < nrb; rb += gridDim.y) {
+    // opaque copy of the thread id: keeps the per-lane offsets of a pass from being hoisted out of this
+    // loop and held in registers across the whole kernel
+    int tid = tid0;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int m0 = rb * BM;
+    const int rot1 = TPB * (rb % (NT1 / TPB)), rot2 = rb % (FS / BK);
 
     if (wave >= kConsumerWaves) {
         // ================================ producers ======================================
@@ -179,7 +190,7 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
                 __builtin_amdgcn_s_barrier();
             }
             for (int t = 0; t < NT2 + 1; ++t) __builtin_amdgcn_s_barrier();    // phase 2: nothing to load
-            return;
+            continue;
         }
         // W tile: load j of this wave covers LDS chunks 64 (kWLoadsPerWave pw + j) .. + 63
         int wk[kWLoadsPerWave], wc[kWLoadsPerWave];
@@ -262,7 +273,7 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
                 __builtin_amdgcn_s_barrier();
             }
         }
-        return;
+        continue;
     }
 
     // ================================== consumers ========================================
@@ -472,6 +483,7 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
             }
         }
     }
+    }   // row blocks of this workgroup
 }
 
 }  // namespace
@@ -483,7 +495,8 @@ bool fused_ffn_stream_ok(int M, int K, int F, int K2) {
 
 template <int MW, int BK_, int CW, bool RAGGED>
 static hipError_t launch_stream(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
-                                void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s) {
+                                void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s,
+                                int blocks_per_wg) {
     typedef StreamCfg<MW, BK_, CW> C;
     auto kern = fused_ffn_stream_kernel<MW, BK_, CW, RAGGED>;
     static bool attr_set = false;
@@ -494,7 +507,8 @@ static hipError_t launch_stream(const void* x, const void* w1, const float* b1, 
         attr_set = true;
     }
     const int nsplit = (F + FS - 1) / FS;
-    dim3 grid(nsplit, (M + C::BM - 1) / C::BM);
+    const int nrb = (M + C::BM - 1) / C::BM;
+    dim3 grid(nsplit, (nrb + blocks_per_wg - 1) / blocks_per_wg);
     prof_start(2, s);
     prof_shape(2, grid.x * grid.y, C::kThreads);
     hipLaunchKernelGGL(kern, grid, dim3(C::kThreads), C::kSmem, s, (const bf16_t*)x, (const bf16_t*)w1, b1,
@@ -511,14 +525,18 @@ hipError_t fused_ffn_stream(const void* x, const void* w1, const float* b1, cons
                             int variant) {
     if (!fused_ffn_stream_ok(M, K, F, K2)) return hipErrorInvalidValue;
     const bool ragged = F % FS != 0 || K2 % CB != 0;
+    // Row blocks per workgroup.  Two (half as many workgroups, each twice as long, the other compute units
+    // left to other streams) was measured: 47 us instead of 30 us alone and a slower concurrent step, since
+    // what bounds a workgroup is its own compute unit's load path; one it stays.
+    const int bpw = 1;
     if (variant == 1) {
-        if (ragged) return launch_stream<2, 32, 4, true>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
-        return launch_stream<2, 32, 4, false>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+        if (ragged) return launch_stream<2, 32, 4, true>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s, 1);
+        return launch_stream<2, 32, 4, false>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s, 1);
     }
     // the eight-consumer-wave instantiation spills a few registers once the ragged clamps are in; the
     // four-consumer-wave one (same speed) does not, so ragged shapes always take it
-    if (ragged) return launch_stream<2, 32, 4, true>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
-    return launch_stream<1, 32, 8, false>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s);
+    if (ragged) return launch_stream<2, 32, 4, true>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s, bpw);
+    return launch_stream<1, 32, 8, false>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s, bpw);
 }
 
 }  // namespace ago
