@@ -155,7 +155,7 @@ ago_status ago_fused_ffn(const void* x, const void* w1, const float* b1,
 
 /* matmul -> simple operators -> matmul (the attention chain of Sec. VI-C):
  *   o = softmax_rows(scale * q k^T) v      per (batch, head), fp32 softmax
- * q,k,v,o:[B,Hh,S,D].  bf16 only; D must be 64 (else UNSUPPORTED); any S >= 1. */
+ * q,k,v,o:[B,Hh,S,D].  bf16 only; D must be 64 or 128 (else UNSUPPORTED); any S >= 1. */
 ago_status ago_fused_attn(const void* q, const void* k, const void* v, void* o,
                           int B, int Hh, int S, int D, float scale, ago_dtype dt,
                           void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -226,7 +226,8 @@ ago_status ago_fused_attn(const void* q, const void* k, const void* v, void* o, 
     (void)workspace; (void)workspace_bytes;
     ago_status st = check_attn(q, k, v, o, B, Hh, S, D, scale, dt);
     if (st != AGO_OK) return st;
-    return from_hip(fused_attn(q, k, v, o, B, Hh, S, scale, tile_config(AGO_OP_FUSED_ATTN), as_stream(hip_stream)));
+    return from_hip(fused_attn(q, k, v, o, B, Hh, S, scale, tile_config(AGO_OP_FUSED_ATTN), as_stream(hip_stream),
+                               0, 0, 0, D));
 }
 
 // ---------------------------------------------------------------- un-fused operators
@@ -426,7 +427,7 @@ ago_status ago_fused_attn_strided(const void* q, const void* k, const void* v, v
     if (stride_b <= 0 || stride_h <= 0 || stride_s < D) return AGO_ERR_SHAPE;
     if (stride_b % 8 || stride_h % 8 || stride_s % 8) return AGO_ERR_ALIGN;
     return from_hip(fused_attn(q, k, v, o, B, Hh, S, scale, tile_config(AGO_OP_FUSED_ATTN), as_stream(hip_stream),
-                               (long)stride_b, (long)stride_h, (long)stride_s));
+                               (long)stride_b, (long)stride_h, (long)stride_s, D));
 }
 
 ago_status ago_fused_attn_bias(const void* q, const void* k, const void* v, const void* bias, void* o, int B,
@@ -436,6 +437,7 @@ ago_status ago_fused_attn_bias(const void* q, const void* k, const void* v, cons
     (void)workspace; (void)workspace_bytes;
     ago_status st = check_attn(q, k, v, o, B, Hh, S, D, scale, dt);
     if (st != AGO_OK) return st;
+    if (D != 64) return AGO_ERR_UNSUPPORTED;
     if (!bias) return AGO_ERR_NULL;
     // a stride is 0 (broadcast) or at least the extent below it
     const long long plane = (long long)S * S;

@@ -27,9 +27,9 @@
 
 namespace ago {
 
-constexpr int kD = 64;      // head dimension
+constexpr int kD = 64;      // head-dimension columns per LDS plane (D = 64 NP)
 constexpr int kKB = 128;    // keys per block
-constexpr int kBlockB = kKB * kD * 2;          // bytes of one K (or V) block: 16384
+constexpr int kPlaneB = kKB * kD * 2;          // bytes of one 64-column plane of a K (or V) block: 16384
 
 namespace {
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
@@ -56,12 +56,18 @@ __device__ __forceinline__ bf16x8 lds_read_vt(const lds_byte* p) {
 // HAS_BIAS: an additive term between the scale and the softmax, Bias[b * bias_sb + hh * bias_sh + q * S + key]
 // (a stride of 0 broadcasts over that dimension).  Each lane fetches the 32 values of its query row and
 // its keys straight from global memory before the block's first product, so the loads overlap it.
-template <int NQT, int NSTG, int BIAS /* 0 none, 1 rows by 16-byte loads, 2 element by element */>
-__global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per_eu(BIAS == 2 ? 2 : (BIAS == 1 ? 4 : 3), 4))) void fused_attn_kernel(
+// NP: 64-column planes of the head dimension (D = 64 NP).  A K or V block is stored plane by plane,
+// [plane][128 keys][64], each plane with the layout described at the top, so every fragment address is
+// the D = 64 one plus a plane offset.
+template <int NQT, int NSTG, int BIAS /* 0 none, 1 rows by 16-byte loads, 2 element by element */, int NP = 1>
+__global__ __launch_bounds__((2 * NQT + 2) * 64)
+__attribute__((amdgpu_waves_per_eu(NP == 2 || BIAS == 2 ? 2 : (BIAS == 1 ? 4 : 3), 4))) void fused_attn_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, int S, int heads, int qblocks, int Hh, long stride_b, long stride_h, long stride_s,
     float c /* scale * log2(e) */, const bf16_t* __restrict__ Bias, long bias_sb, long bias_sh) {
     constexpr bool HAS_BIAS = BIAS != 0;
+    constexpr int kBlockB = NP * kPlaneB;
+    static_assert(NP == 1 || NSTG == 2, "two planes: two buffers");
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_byte* smem = (lds_byte*)smem_generic;          // [2 buffers][K block | V block]
     const int tid = threadIdx.x, lane = tid & 63;
@@ -89,17 +95,19 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
         auto issue = [&](int blk) {
             lds_byte* dst = smem + (blk % NSTG) * 2 * kBlockB + (is_v ? kBlockB : 0);
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int row = 8 * q + r8;
-                const int sw = is_v ? ((((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1)) : ((row >> 1) & 7);
-                const bf16_t* g = src + (long)min(blk * kKB + row, S - 1) * stride_s + 8 * (pc ^ sw);
-                __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) const void*)g,
-                                                 (__attribute__((address_space(3))) void*)(dst + q * 1024), 16, 0, 0);
-            }
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int row = 8 * q + r8;
+                    const int sw = is_v ? ((((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1)) : ((row >> 1) & 7);
+                    const bf16_t* g = src + (long)min(blk * kKB + row, S - 1) * stride_s + 64 * p + 8 * (pc ^ sw);
+                    __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) const void*)g,
+                                                     (__attribute__((address_space(3))) void*)(dst + p * kPlaneB + q * 1024), 16, 0, 0);
+                }
         };
-        auto wait_blocks = [&](int n) {      // at most n blocks (16 loads each) outstanding
-            if (n >= 2) wait_vm<32>();
-            else if (n == 1) wait_vm<16>();
+        auto wait_blocks = [&](int n) {      // at most n blocks (16 NP loads each) outstanding
+            if (n >= 2) wait_vm<(NP == 1 ? 32 : 63)>();          // n = 2 only with three buffers, i.e. NP = 1
+            else if (n == 1) wait_vm<16 * NP>();
             else wait_vm<0>();
         };
         static_assert(NSTG == 2 || NSTG == 3, "ring depth");
@@ -124,9 +132,9 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
     const int j = lane & 31, h = lane >> 5;
     const int q_row = qblk * (32 * NQT) + qt * 32 + j;
 
-    bf16x8 qf[4];
+    bf16x8 qf[4 * NP];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
+    for (int ks = 0; ks < 4 * NP; ++ks)
         qf[ks] = __builtin_bit_cast(bf16x8, ld_u4(Q + (long)min(q_row, S - 1) * stride_s + ks * 16 + 8 * h));
 
     // K fragment of key tile kt (32 keys), k step ks: row = 64 kh + 32 kt + j, logical chunk 2 ks + h
@@ -145,9 +153,11 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
         voff[dt] = vrow0 * 128 + ((chunk ^ vsw) << 4) + 8 * (s15 & 1);
     }
 
-    f32x16 o[2];
+    f32x16 o[2 * NP];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { o[0][r] = 0.f; o[1][r] = 0.f; }
+    for (int dt = 0; dt < 2 * NP; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
     float m = -INFINITY, l = 0.f;     // running max of scaled scores, running (per-half) sum
     // with a bias the scores are rescaled (and biased) once, ahead of the max; without, the scale rides
     // in the exponent's multiply-add
@@ -202,10 +212,11 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
 #pragma unroll
             for (int r = 0; r < 16; ++r) sc[kt][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
+        for (int ks = 0; ks < 4 * NP; ++ks)
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
-                sc[kt] = mfma32(lds_read16(kb + koff + kt * 32 * 128 + (((2 * ks + h) ^ ksw) << 4)), qf[ks], sc[kt]);
+                sc[kt] = mfma32(lds_read16(kb + (ks >> 2) * kPlaneB + koff + kt * 32 * 128 + (((2 * (ks & 3) + h) ^ ksw) << 4)),
+                                qf[ks], sc[kt]);
 
         if constexpr (HAS_BIAS) {
             constexpr float kLog2e = 1.4426950408889634f;
@@ -253,7 +264,9 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
         m = m_new;
         l *= alpha;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { o[0][r] *= alpha; o[1][r] *= alpha; }
+        for (int dt = 0; dt < 2 * NP; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
 
         bf16x8 pf[2][2];
 #pragma unroll
@@ -271,8 +284,8 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-                    o[dt] = mfma32(lds_read_vt(vb + voff[dt] + (kt * 32 + 16 * u) * 128), pf[kt][u], o[dt]);
+                for (int dt = 0; dt < 2 * NP; ++dt)
+                    o[dt] = mfma32(lds_read_vt(vb + (dt >> 1) * kPlaneB + voff[dt & 1] + (kt * 32 + 16 * u) * 128), pf[kt][u], o[dt]);
 
         __builtin_amdgcn_s_barrier();
     }
@@ -280,12 +293,13 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
     // merge the two key halves of each query tile: the kh = 1 wave parks (m, l, O^T) in LDS (the
     // K / V buffers are free after the last barrier), the kh = 0 wave combines and writes O.
     l += __shfl_xor(l, 32, 64);
-    float* park = reinterpret_cast<float*>(smem_generic) + qt * 34 * 64;     // [34][64] floats per query tile
+    constexpr int kParkRows = 2 + 32 * NP;
+    float* park = reinterpret_cast<float*>(smem_generic) + qt * kParkRows * 64;     // [2 + 32 NP][64] floats per query tile
     if (kh == 1) {
         park[lane] = m;
         park[64 + lane] = l;
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
+        for (int dt = 0; dt < 2 * NP; ++dt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) park[(2 + dt * 16 + r) * 64 + lane] = o[dt][r];
     }
@@ -297,12 +311,12 @@ __global__ __launch_bounds__((2 * NQT + 2) * 64) __attribute__((amdgpu_waves_per
         const float inv = 1.0f / (l * a0 + l1 * a1);
         const float w0 = a0 * inv, w1 = a1 * inv;
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
+        for (int dt = 0; dt < 2 * NP; ++dt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[dt][r] = o[dt][r] * w0 + park[(2 + dt * 16 + r) * 64 + lane] * w1;
         if (q_row < S) {
 #pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
+            for (int dt = 0; dt < 2 * NP; ++dt)
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const int d = dt * 32 + 8 * gq + 4 * h;
@@ -318,13 +332,13 @@ struct AttnBias {
     long sb, sh;      // element strides over batch and head, 0 = broadcast
 };
 
-template <int NQT, int NSTG, int BIAS>
+template <int NQT, int NSTG, int BIAS, int NP = 1>
 static hipError_t launch_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
                               long stride_b, long stride_h, long stride_s, float scale, hipStream_t s,
                               AttnBias bias = AttnBias{nullptr, 0, 0}) {
-    constexpr size_t smem = (size_t)NSTG * 2 * kBlockB;    // ring of (K block, V block) buffers; the merge reuses them
-    static_assert((size_t)NQT * 34 * 64 * 4 <= smem, "merge scratch");
-    auto kern = fused_attn_kernel<NQT, NSTG, BIAS>;
+    constexpr size_t smem = (size_t)NSTG * 2 * NP * kPlaneB;    // ring of (K block, V block) buffers; the merge reuses them
+    static_assert((size_t)NQT * (2 + 32 * NP) * 64 * 4 <= smem, "merge scratch");
+    auto kern = fused_attn_kernel<NQT, NSTG, BIAS, NP>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -348,8 +362,15 @@ static hipError_t launch_attn(const void* q, const void* k, const void* v, void*
 int fused_attn_num_cfgs() { return 4; }
 
 hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
-                      float scale, int tile_cfg, hipStream_t s, long stride_b, long stride_h, long stride_s) {
-    if (stride_s == 0) { stride_b = (long)Hh * S * kD; stride_h = (long)S * kD; stride_s = kD; }   // [B][Hh][S][D]
+                      float scale, int tile_cfg, hipStream_t s, long stride_b, long stride_h, long stride_s, int D) {
+    if (stride_s == 0) { stride_b = (long)Hh * S * D; stride_h = (long)S * D; stride_s = D; }   // [B][Hh][S][D]
+    if (D == 128) {
+        // two planes: 96 queries per workgroup (eight waves, two per SIMD: 32 query-fragment, 64 output and
+        // 32 score registers per lane need that budget), 64 for configuration 2
+        if (tile_cfg == 2) return launch_attn<2, 2, 0, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
+        return launch_attn<3, 2, 0, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
+    }
+    if (D != 64) return hipErrorInvalidValue;
     if (tile_cfg < 0) {
         // built-in choice: 192-query workgroups (a compute unit to themselves, K and V of the first
         // three blocks requested at once) when that still gives the chip enough workgroups

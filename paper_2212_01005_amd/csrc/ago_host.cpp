@@ -108,7 +108,7 @@ ago_status check_attn(const void* q, const void* k, const void* v, const void* o
     const void* ps[4] = {q, k, v, o};
     for (const void* p : ps)
         if (!aligned16(p)) return AGO_ERR_ALIGN;
-    if (dt != AGO_BF16 || D != 64 || !(scale > 0.0f)) return AGO_ERR_UNSUPPORTED;
+    if (dt != AGO_BF16 || (D != 64 && D != 128) || !(scale > 0.0f)) return AGO_ERR_UNSUPPORTED;
     return AGO_OK;
 }
 

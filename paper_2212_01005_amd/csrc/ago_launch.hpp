@@ -45,7 +45,7 @@ hipError_t fused_ffn(const void* x, const void* w1, const float* b1, const void*
                      hipStream_t s);
 hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
                       float scale, int tile_cfg, hipStream_t s,
-                      long stride_b = 0, long stride_h = 0, long stride_s = 0);
+                      long stride_b = 0, long stride_h = 0, long stride_s = 0, int D = 64);   // D: 64 or 128
 hipError_t fused_attn_bias(const void* q, const void* k, const void* v, const void* bias, void* o, int B, int Hh,
                            int S, long bias_sb, long bias_sh, float scale, int tile_cfg, hipStream_t s);   // element strides; 0 = [B][Hh][S][D]
 

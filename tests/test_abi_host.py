@@ -83,7 +83,7 @@ def test_pair_entry_points_validate_before_any_gpu_call(lib):
     assert att(0, 64, 256) == 2                                           # strides must be positive
     assert att(25600, 64, 32) == 2                                        # rows would overlap
     assert att(25600, 60, 256) == 4                                       # row starts must stay 16-byte aligned
-    assert att(25600, 64, 256, D=32) == 5                                 # head dimension other than 64
+    assert att(25600, 64, 256, D=32) == 5                                 # head dimension other than 64 / 128
     lib.ago_fused_invres_k.argtypes = [vp] * 8 + [ci] * 10 + [vp, sz, vp]
     irk = lambda ks, st=1, res=0, Cexp=96: lib.ago_fused_invres_k(p, p, None, p, None, p, None, p, 1, 8, 8, 16, Cexp, 16,
                                                               st, ks, res, 1, None, 0, None)

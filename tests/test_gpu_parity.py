@@ -307,6 +307,34 @@ def test_sibling_qkv_projection(gpu, oracle):
     assert_close(runner.to_numpy64(o), oracle.attn(rq, rk, rv, 0.125), "bf16", case.name, scale=1.5)
 
 
+def test_attention_head_dim_128(gpu, oracle):
+    """D = 128 (two 64-column planes per K / V block): contiguous and [B][S][Hh][D] layouts, ragged and
+    multi-block sequences, both workgroup sizes."""
+    torch, ago, runner = gpu
+    cases = [wl.AttnCase(1, 1, 1, 128, 0.09, "bf16", 6800, name="attn_d128_s1"),
+             wl.AttnCase(2, 3, 100, 128, 0.0884, "bf16", 6801, name="attn_d128_s100"),
+             wl.AttnCase(1, 4, 384, 128, 0.0884, "bf16", 6802, name="attn_d128_s384"),
+             wl.AttnCase(1, 2, 600, 128, 0.0884, "bf16", 6803, name="attn_d128_s600"),
+             wl.AttnCase(4, 8, 256, 128, 0.0884, "bf16", 6804, name="attn_d128_4x8x256")]
+    for case in cases:
+        ref = oracle.run_case(case)
+        t = runner.to_device(case)
+        try:
+            for cfg in (-1, 2):
+                ago.set_tile_config(ago.OP_FUSED_ATTN, cfg)
+                o = torch.zeros_like(t["q"])
+                ago.ago_fused_attn(t["q"], t["k"], t["v"], o, case.scale)
+                torch.cuda.synchronize()
+                assert_close(runner.to_numpy64(o), ref, "bf16", "%s cfg %d" % (case.name, cfg))
+        finally:
+            ago.set_tile_config(ago.OP_FUSED_ATTN, -1)
+        q, k, v = (t[n].permute(0, 2, 1, 3).contiguous() for n in ("q", "k", "v"))   # [B, S, Hh, D]
+        o = torch.zeros_like(q)
+        ago.ago_fused_attn_bshd(q, k, v, o, case.scale)
+        torch.cuda.synchronize()
+        assert_close(runner.to_numpy64(o.permute(0, 2, 1, 3)), ref, "bf16", case.name + " bshd")
+
+
 def test_attention_bias(gpu, oracle):
     """softmax(scale q k^T + bias) v: every bias broadcast kind, 16-byte and element-wise row loads (S % 8),
     ragged key blocks, every tile configuration, and the benchmark's shape with a per-head table."""
