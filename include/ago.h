@@ -176,7 +176,7 @@ ago_status ago_fused_attn_strided(const void* q, const void* k, const void* v, v
 /* The attention chain with one more simple operator between the products (Sec. VI-C: the chain is
  * matmul -> simple operators -> matmul): an elementwise add of a bias or mask ahead of the softmax,
  *   o = softmax_rows(scale * q k^T + bias) v
- * q,k,v,o:[B,Hh,S,D] contiguous, bf16, D = 64.  bias (device, bf16): element (b, h, i, j) at
+ * q,k,v,o:[B,Hh,S,D] contiguous, bf16, D = 64 or 128.  bias (device, bf16): element (b, h, i, j) at
  * bias[b * bias_stride_b + h * bias_stride_h + i * S + j]; a stride of 0 broadcasts over that
  * dimension (a [1,Hh,S,S] relative-position table, a [B,1,S,S] padding mask), otherwise
  * bias_stride_h >= S*S and bias_stride_b >= Hh * bias_stride_h (else SHAPE).  The bias is not scaled.

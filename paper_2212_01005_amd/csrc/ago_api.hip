@@ -437,7 +437,6 @@ ago_status ago_fused_attn_bias(const void* q, const void* k, const void* v, cons
     (void)workspace; (void)workspace_bytes;
     ago_status st = check_attn(q, k, v, o, B, Hh, S, D, scale, dt);
     if (st != AGO_OK) return st;
-    if (D != 64) return AGO_ERR_UNSUPPORTED;
     if (!bias) return AGO_ERR_NULL;
     // a stride is 0 (broadcast) or at least the extent below it
     const long long plane = (long long)S * S;
@@ -445,7 +444,7 @@ ago_status ago_fused_attn_bias(const void* q, const void* k, const void* v, cons
     if (bias_stride_b != 0 && bias_stride_b < (bias_stride_h ? bias_stride_h * Hh : plane)) return AGO_ERR_SHAPE;
     if (reinterpret_cast<uintptr_t>(bias) % 2) return AGO_ERR_ALIGN;
     return from_hip(fused_attn_bias(q, k, v, bias, o, B, Hh, S, (long)bias_stride_b, (long)bias_stride_h, scale,
-                                    tile_config(AGO_OP_FUSED_ATTN), as_stream(hip_stream)));
+                                    tile_config(AGO_OP_FUSED_ATTN), as_stream(hip_stream), D));
 }
 
 ago_status ago_fused_qkv(const void* x, const void* wq, const void* wk, const void* wv, const float* bq,

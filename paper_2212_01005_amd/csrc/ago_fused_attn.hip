@@ -387,8 +387,8 @@ hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int 
 
 // The chain with an additive bias / mask ahead of the softmax; q, k, v, o contiguous [B][Hh][S][D].
 hipError_t fused_attn_bias(const void* q, const void* k, const void* v, const void* bias, void* o, int B, int Hh,
-                           int S, long bias_sb, long bias_sh, float scale, int tile_cfg, hipStream_t s) {
-    const long stride_b = (long)Hh * S * kD, stride_h = (long)S * kD, stride_s = kD;
+                           int S, long bias_sb, long bias_sh, float scale, int tile_cfg, hipStream_t s, int D) {
+    const long stride_b = (long)Hh * S * D, stride_h = (long)S * D, stride_s = D;
     const AttnBias bs{bias, bias_sb, bias_sh};
     // Two LDS buffers throughout (the third costs the registers that the bias values need); the
     // element-by-element variant needs more registers still and runs configuration 3 as configuration 1.
@@ -398,6 +398,11 @@ hipError_t fused_attn_bias(const void* q, const void* k, const void* v, const vo
     }
     // 16-byte loads of 8 bias values need every row start 16-byte aligned
     const bool vec = S % 8 == 0 && bias_sb % 8 == 0 && bias_sh % 8 == 0 && reinterpret_cast<uintptr_t>(bias) % 16 == 0;
+    if (D == 128) {
+        if (vec) return launch_attn<3, 2, 1, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s, bs);
+        return launch_attn<3, 2, 2, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s, bs);
+    }
+    if (D != 64) return hipErrorInvalidValue;
 #define AGO_ATTN_BIAS_CASE(NQT, NQT_E)                                                                        \
     return vec ? launch_attn<NQT, 2, 1>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s, bs)     \
                : launch_attn<NQT_E, 2, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s, bs)

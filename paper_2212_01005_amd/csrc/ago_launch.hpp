@@ -47,7 +47,7 @@ hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int 
                       float scale, int tile_cfg, hipStream_t s,
                       long stride_b = 0, long stride_h = 0, long stride_s = 0, int D = 64);   // D: 64 or 128
 hipError_t fused_attn_bias(const void* q, const void* k, const void* v, const void* bias, void* o, int B, int Hh,
-                           int S, long bias_sb, long bias_sh, float scale, int tile_cfg, hipStream_t s);   // element strides; 0 = [B][Hh][S][D]
+                           int S, long bias_sb, long bias_sh, float scale, int tile_cfg, hipStream_t s, int D = 64);   // element strides; 0 = [B][Hh][S][D]
 
 // Instrumentation hook (see ago_profile_enable): record an event pair around the dominant kernel
 // of a fused entry point.  No-ops unless profiling is enabled.

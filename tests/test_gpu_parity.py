@@ -345,7 +345,9 @@ def test_attention_bias(gpu, oracle):
              wl.AttnCase(1, 3, 77, 64, 0.125, "bf16", 6203, name="attn_bias_full_s77", bias="full"),
              wl.AttnCase(1, 2, 600, 64, 0.125, "bf16", 6204, name="attn_bias_head_s600", bias="head"),
              wl.AttnCase(1, 1, 1, 64, 0.125, "bf16", 6205, name="attn_bias_s1", bias="full"),
-             wl.AttnCase(8, 12, 384, 64, 0.125, "bf16", 6206, name="attn_bias_head_8x12x384", bias="head")]
+             wl.AttnCase(8, 12, 384, 64, 0.125, "bf16", 6206, name="attn_bias_head_8x12x384", bias="head"),
+             wl.AttnCase(2, 2, 200, 128, 0.0884, "bf16", 6207, name="attn_bias_d128_s200", bias="full"),
+             wl.AttnCase(1, 3, 130, 128, 0.0884, "bf16", 6208, name="attn_bias_d128_mask_s130", bias="batch")]
     for case in cases:
         ref = oracle.run_case(case)
         t = runner.to_device(case)
