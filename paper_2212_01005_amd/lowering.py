@@ -1,0 +1,292 @@
+"""From an operator graph to fused-kernel launches (AGO Sec. IV -> Sec. III-B).
+
+The graph frontend of the library (``ago_graph_*``: Eq. 1 weights, acyclic Cluster) decides which
+operators form one subgraph; this module recognises, inside each subgraph, the operator chains the
+hand-written kernels implement (the structures of Sec. III-B and VI: pw -> dw -> pw, the pw / dw pairs,
+3x3 -> 3x3, matmul -> activation -> matmul, matmul -> scale -> softmax -> matmul) and turns them into one
+launch each; whatever is left runs operator by operator on the un-fused kernels.  Only host-side
+bookkeeping happens here: every tensor operation is a call into the library.
+
+Graph form: ``Graph.nodes`` is a list in topological order; node i is ``Node(op, inputs, attrs)`` with
+``inputs`` = ids of producer nodes.  Operators and their attributes:
+
+    input                      a tensor supplied at run time (attrs: name, shape)
+    conv1x1  (w)               x:[N,H,W,Cin]  w:[Cin,Cout]
+    dwconv   (w, stride)       w:[k,k,C], k = 3 or 5, zero padding (k-1)/2
+    conv3x3  (w)               w:[3,3,C,C]
+    gemm     (w)               x:[M,K]  w:[K,N]
+    bmm_nt / bmm_nn            two inputs, batched over the leading dimensions
+    bias (b) relu relu6 gelu_tanh add(two inputs) scale (alpha) softmax
+
+Weights / biases are named entries of ``Graph.params``.
+"""
+
+import re
+from dataclasses import dataclass, field
+
+COMPLEX = {"conv1x1", "dwconv", "conv3x3", "gemm", "bmm_nt", "bmm_nn"}
+_TOKEN = {"conv1x1": "P", "dwconv": "D", "conv3x3": "C", "gemm": "G", "bmm_nt": "T", "bmm_nn": "N",
+          "bias": "b", "relu": "r", "relu6": "6", "gelu_tanh": "g", "add": "+", "scale": "s", "softmax": "x",
+          "input": "i"}
+
+# fused structures, longest first; the token string of a chain is matched from its first operator
+_PATTERNS = [
+    ("invres", re.compile(r"Pb?6Db?6Pb?\+?")),
+    ("conv_chain", re.compile(r"Cb?rCb?\+?r")),
+    ("ffn", re.compile(r"Gb?[gr6]Gb?")),
+    ("attn", re.compile(r"TsxN")),
+    ("pw_dw", re.compile(r"Pb?6Db?6")),
+    ("dw_pw", re.compile(r"Db?6Pb?")),
+]
+
+
+@dataclass
+class Node:
+    op: str
+    inputs: list
+    attrs: dict = field(default_factory=dict)
+
+
+@dataclass
+class Graph:
+    nodes: list
+    params: dict
+    dtype: str = "bf16"
+
+    def add(self, op, inputs=(), **attrs):
+        self.nodes.append(Node(op, list(inputs), attrs))
+        return len(self.nodes) - 1
+
+    def edges(self):
+        return [(src, i) for i, n in enumerate(self.nodes) for src in n.inputs]
+
+    def consumers(self):
+        out = [[] for _ in self.nodes]
+        for i, n in enumerate(self.nodes):
+            for src in n.inputs:
+                out[src].append(i)
+        return out
+
+
+def infer_shapes(g):
+    """Output shape of every node (NHWC / row-major conventions of the library)."""
+    shapes = []
+    for n in g.nodes:
+        s_in = [shapes[i] for i in n.inputs]
+        if n.op == "input":
+            s = tuple(n.attrs["shape"])
+        elif n.op == "conv1x1":
+            s = s_in[0][:-1] + (g.params[n.attrs["w"]].shape[1],)
+        elif n.op == "dwconv":
+            st = n.attrs.get("stride", 1)
+            nb, h, w, c = s_in[0]
+            s = (nb, (h - 1) // st + 1, (w - 1) // st + 1, c)
+        elif n.op == "gemm":
+            s = s_in[0][:-1] + (g.params[n.attrs["w"]].shape[1],)
+        elif n.op == "bmm_nt":
+            s = s_in[0][:-1] + (s_in[1][-2],)
+        elif n.op == "bmm_nn":
+            s = s_in[0][:-1] + (s_in[1][-1],)
+        else:                       # conv3x3 (C -> C, stride 1) and the simple operators keep the shape
+            s = s_in[0]
+        shapes.append(tuple(int(v) for v in s))
+    return shapes
+
+
+def loop_extents(g, shapes, i):
+    """Extents of the loop nest of operator i (Sec. IV-A: the weight follows the loop nest)."""
+    n, out = g.nodes[i], shapes[i]
+    if n.op == "conv1x1" or n.op == "gemm":
+        return list(out) + [g.params[n.attrs["w"]].shape[0]]
+    if n.op == "dwconv":
+        k = g.params[n.attrs["w"]].shape[0]
+        return list(out) + [k, k]
+    if n.op == "conv3x3":
+        return list(out) + [out[-1], 3, 3]
+    if n.op == "bmm_nt" or n.op == "bmm_nn":
+        return list(out) + [shapes[n.inputs[0]][-1]]
+    return list(out)
+
+
+def partition(g, binding, c=0.01, b=1.0, td=float("inf")):
+    """Eq. 1 weights and Cluster through the library; returns (subgraph_of, weights)."""
+    shapes = infer_shapes(g)
+    weight = [binding.graph_op_weight(loop_extents(g, shapes, i), c, b) for i in range(len(g.nodes))]
+    return binding.graph_cluster(len(g.nodes), weight, g.edges(), td), weight
+
+
+def lower(g, subgraph_of):
+    """Launch plan: a list of (kind, node ids) in execution order.  kind is one of the fused structures
+    or "op" (one operator on its un-fused kernel); "input" nodes launch nothing."""
+    cons = g.consumers()
+    n_nodes = len(g.nodes)
+    done = [False] * n_nodes
+    plan = []
+    for i in range(n_nodes):
+        if done[i]:
+            continue
+        if g.nodes[i].op == "input":
+            done[i] = True
+            continue
+        # the chain that starts at i and stays inside i's subgraph: every link is the only consumer of its
+        # predecessor ("add" may take a second operand from anywhere that is already computed)
+        chain = [i]
+        while True:
+            last = chain[-1]
+            nxt = cons[last]
+            if len(nxt) != 1:
+                break
+            j = nxt[0]
+            if done[j] or subgraph_of[j] != subgraph_of[i] or g.nodes[j].op == "input":
+                break
+            others = [s for s in g.nodes[j].inputs if s != last]
+            if g.nodes[j].op == "add":
+                if len(others) != 1 or others[0] >= chain[0] and others[0] not in chain:
+                    break
+            elif g.nodes[j].op in ("bmm_nt", "bmm_nn"):
+                if any(o >= chain[0] and o not in chain for o in others):
+                    break
+            elif others:
+                break
+            chain.append(j)
+        tokens = "".join(_TOKEN[g.nodes[k].op] for k in chain)
+        matched = None
+        for kind, pat in _PATTERNS:
+            m = pat.match(tokens)
+            if m and not _admissible(g, kind, chain[:m.end()]) and "+" in m.group(0):
+                m = pat.match(tokens[:tokens.index("+")])          # the same structure without the residual
+            if m and _admissible(g, kind, chain[:m.end()]):
+                matched = (kind, chain[:m.end()])
+                break
+        if matched is None:
+            matched = ("op", [i])
+        plan.append(matched)
+        for k in matched[1]:
+            done[k] = True
+    return plan
+
+
+def _admissible(g, kind, ids):
+    """Checks the token pattern cannot express: what a residual adds, dtype and size limits of the kernels."""
+    nodes = [g.nodes[k] for k in ids]
+    first_in = nodes[0].inputs[0]
+    for k, n in zip(ids, nodes):
+        if n.op == "add":
+            other = [s for s in n.inputs if s not in ids]
+            if len(other) != 1 or other[0] != first_in:          # the fused residual is the block's own input
+                return False
+    if kind == "invres":
+        dws = [n for n in nodes if n.op == "dwconv"]
+        has_add = any(n.op == "add" for n in nodes)
+        return not has_add or dws[0].attrs.get("stride", 1) == 1
+    if kind == "conv_chain":
+        return g.dtype == "bf16" and g.params[nodes[0].attrs["w"]].shape[2] == 64
+    if kind in ("ffn", "attn"):
+        return g.dtype == "bf16"
+    return True
+
+
+# ---- execution (GPU) ---------------------------------------------------------------------------------
+
+_ACT_OF = {"relu": "ACT_RELU", "relu6": "ACT_RELU6", "gelu_tanh": "ACT_GELU_TANH"}
+
+
+class Executor:
+    """Runs a launch plan with the library's kernels.  ``params`` are device tensors (weights in the graph's
+    storage dtype, biases fp32); ``run(inputs)`` returns the tensor of every node that has no consumer."""
+
+    def __init__(self, g, plan, binding, torch, device="cuda:0"):
+        self.g, self.plan, self.ago, self.torch, self.device = g, plan, binding, torch, device
+        self.shapes = infer_shapes(g)
+        self.td = torch.bfloat16 if g.dtype == "bf16" else torch.float32
+        self.launches = 0
+
+    def _new(self, i):
+        return self.torch.empty(self.shapes[i], dtype=self.td, device=self.device)
+
+    def _bias_of(self, nodes, after):
+        """The bias that directly follows position `after` in a matched chain, or None."""
+        if after + 1 < len(nodes) and nodes[after + 1].op == "bias":
+            return self.g.params[nodes[after + 1].attrs["b"]]
+        return None
+
+    def run(self, inputs):
+        g, ago, P, val = self.g, self.ago, self.g.params, {}
+        for i, n in enumerate(g.nodes):
+            if n.op == "input":
+                val[i] = inputs[n.attrs["name"]]
+        for kind, ids in self.plan:
+            nodes = [g.nodes[k] for k in ids]
+            out = self._new(ids[-1])
+            x = val[nodes[0].inputs[0]]
+            self.launches += 1
+            if kind == "invres":
+                pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
+                w1, wd, w2 = (P[nodes[p].attrs["w"]] for p in pos)
+                residual = any(n.op == "add" for n in nodes)
+                stride = nodes[pos[1]].attrs.get("stride", 1)
+                fn = ago.ago_fused_invres if wd.shape[0] == 3 else ago.ago_fused_invres_k
+                fn(x, w1, self._bias_of(nodes, pos[0]), wd, self._bias_of(nodes, pos[1]), w2,
+                   self._bias_of(nodes, pos[2]), out, stride, residual)
+            elif kind == "pw_dw":
+                pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
+                ago.ago_fused_pw_dw(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]),
+                                    P[nodes[pos[1]].attrs["w"]], self._bias_of(nodes, pos[1]), out,
+                                    nodes[pos[1]].attrs.get("stride", 1))
+            elif kind == "dw_pw":
+                pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
+                ago.ago_fused_dw_pw(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]),
+                                    P[nodes[pos[1]].attrs["w"]], self._bias_of(nodes, pos[1]), out,
+                                    nodes[pos[0]].attrs.get("stride", 1))
+            elif kind == "conv_chain":
+                pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
+                ago.ago_fused_conv_chain(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]),
+                                         P[nodes[pos[1]].attrs["w"]], self._bias_of(nodes, pos[1]), out,
+                                         any(n.op == "add" for n in nodes))
+            elif kind == "ffn":
+                pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
+                act = next(n.op for n in nodes if n.op in _ACT_OF)
+                w1, w2 = P[nodes[pos[0]].attrs["w"]], P[nodes[pos[1]].attrs["w"]]
+                nbytes = ago.workspace_bytes(ago.OP_FUSED_FFN, [x.shape[0], x.shape[1], w1.shape[1], w2.shape[1]], ago.BF16)
+                ws = self.torch.empty(max(nbytes, 16), dtype=self.torch.uint8, device=self.device) if nbytes else None
+                ago.ago_fused_ffn(x, w1, self._bias_of(nodes, pos[0]), w2, self._bias_of(nodes, pos[1]), out,
+                                  getattr(ago, _ACT_OF[act]), ws)
+            elif kind == "attn":
+                k_t = val[nodes[0].inputs[1]]
+                v_t = val[[s for s in nodes[3].inputs if s not in ids][0]]
+                ago.ago_fused_attn(x, k_t, v_t, out, float(nodes[1].attrs["alpha"]))
+            else:
+                self._single(nodes[0], ids[0], val, out)
+            val[ids[-1]] = out
+        cons = g.consumers()
+        return {i: val[i] for i in range(len(g.nodes)) if not cons[i] and g.nodes[i].op != "input"}
+
+    def _single(self, n, i, val, out):
+        ago, P = self.ago, self.g.params
+        a = val[n.inputs[0]]
+        if n.op == "conv1x1":
+            ago.ago_conv1x1(a, P[n.attrs["w"]], None, None, out)
+        elif n.op == "gemm":
+            ago.ago_gemm(a, P[n.attrs["w"]], None, None, out)
+        elif n.op == "dwconv":
+            if P[n.attrs["w"]].shape[0] != 3:
+                raise NotImplementedError("un-fused depthwise kernels other than 3x3")
+            ago.ago_dwconv3x3(a, P[n.attrs["w"]], None, out, n.attrs.get("stride", 1))
+        elif n.op == "conv3x3":
+            ago.ago_conv3x3(a, P[n.attrs["w"]], None, None, out)
+        elif n.op == "bias":
+            ago.ago_bias_act(a, P[n.attrs["b"]], out)
+        elif n.op in _ACT_OF:
+            ago.ago_bias_act(a, None, out, getattr(ago, _ACT_OF[n.op]))
+        elif n.op == "add":
+            ago.ago_add_act(a, val[n.inputs[1]], out)
+        elif n.op == "scale":
+            ago.ago_scale(a, out, float(n.attrs["alpha"]))
+        elif n.op == "softmax":
+            ago.ago_softmax_rows(a, out)
+        elif n.op == "bmm_nt":
+            ago.ago_bmm_nt(a, val[n.inputs[1]], out)
+        elif n.op == "bmm_nn":
+            ago.ago_bmm_nn(a, val[n.inputs[1]], out)
+        else:
+            raise ValueError(n.op)

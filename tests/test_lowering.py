@@ -1,0 +1,191 @@
+"""Operator graph -> partition (library graph frontend) -> fused launches.  The plan is checked on the CPU;
+the execution (GPU) is compared with the oracle evaluating the same graph operator by operator."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from paper_2212_01005_amd import lowering as L
+
+
+def _mobile_graph(dtype, blocks):
+    """Inverted-residual blocks in a row.  blocks: list of (cexp, cout, stride, ksize)."""
+    g = L.Graph([], {}, dtype)
+    seed = 9000
+    cin = 16
+    x = g.add("input", name="x", shape=(2, 14, 14, cin))
+    cur = x
+
+    def param(name, shape, sigma):
+        nonlocal seed
+        seed += 1
+        v = wl.normal(seed, shape, sigma)
+        g.params[name] = wl.round_to_bf16(v) if (dtype == "bf16" and not name.startswith("b")) else \
+            np.asarray(v, dtype=np.float32).astype(np.float64)
+        return name
+
+    for bi, (cexp, cout, stride, ks) in enumerate(blocks):
+        src = cur
+        cur = g.add("conv1x1", [cur], w=param("w1_%d" % bi, (cin, cexp), cin ** -0.5))
+        cur = g.add("bias", [cur], b=param("b1_%d" % bi, (cexp,), 0.1))
+        cur = g.add("relu6", [cur])
+        cur = g.add("dwconv", [cur], w=param("wd_%d" % bi, (ks, ks, cexp), 1.0 / ks), stride=stride)
+        cur = g.add("bias", [cur], b=param("bd_%d" % bi, (cexp,), 0.1))
+        cur = g.add("relu6", [cur])
+        cur = g.add("conv1x1", [cur], w=param("w2_%d" % bi, (cexp, cout), cexp ** -0.5))
+        cur = g.add("bias", [cur], b=param("b2_%d" % bi, (cout,), 0.1))
+        if stride == 1 and cin == cout:
+            cur = g.add("add", [cur, src])
+        cin = cout
+    return g
+
+
+def _transformer_graph():
+    g = L.Graph([], {}, "bf16")
+    q = g.add("input", name="q", shape=(2, 2, 96, 64))
+    k = g.add("input", name="k", shape=(2, 2, 96, 64))
+    v = g.add("input", name="v", shape=(2, 2, 96, 64))
+    s = g.add("bmm_nt", [q, k])
+    s = g.add("scale", [s], alpha=0.125)
+    s = g.add("softmax", [s])
+    g.add("bmm_nn", [s, v])
+    x = g.add("input", name="x", shape=(100, 128))
+    g.params["w1"] = wl.round_to_bf16(wl.normal(9101, (128, 384), 128 ** -0.5))
+    g.params["w2"] = wl.round_to_bf16(wl.normal(9102, (384, 256), 384 ** -0.5))
+    g.params["b1"] = np.asarray(wl.normal(9103, (384,), 0.1), dtype=np.float32).astype(np.float64)
+    g.params["b2"] = np.asarray(wl.normal(9104, (256,), 0.1), dtype=np.float32).astype(np.float64)
+    h = g.add("gemm", [x], w="w1")
+    h = g.add("bias", [h], b="b1")
+    h = g.add("gelu_tanh", [h])
+    h = g.add("gemm", [h], w="w2")
+    g.add("bias", [h], b="b2")
+    return g
+
+
+def _oracle_eval(g, inputs, oracle):
+    """The graph operator by operator on the fp64 oracle."""
+    val = {}
+    for i, n in enumerate(g.nodes):
+        a = [val[s] for s in n.inputs]
+        P = g.params
+        if n.op == "input":
+            val[i] = inputs[n.attrs["name"]]
+        elif n.op == "conv1x1":
+            val[i] = oracle.conv1x1(a[0], P[n.attrs["w"]])
+        elif n.op == "dwconv":
+            val[i] = oracle.dwconv(a[0], P[n.attrs["w"]], n.attrs.get("stride", 1))
+        elif n.op == "conv3x3":
+            val[i] = oracle.conv3x3(a[0], P[n.attrs["w"]])
+        elif n.op == "gemm":
+            val[i] = oracle.gemm(a[0], P[n.attrs["w"]])
+        elif n.op == "bias":
+            val[i] = oracle.bias(a[0], P[n.attrs["b"]])
+        elif n.op in ("relu", "relu6", "gelu_tanh"):
+            val[i] = getattr(oracle, n.op)(a[0])
+        elif n.op == "add":
+            val[i] = oracle.add(a[0], a[1])
+        elif n.op == "scale":
+            val[i] = oracle.scale(a[0], n.attrs["alpha"])
+        elif n.op == "softmax":
+            val[i] = oracle.softmax_rows(a[0])
+        elif n.op == "bmm_nt":
+            val[i] = oracle.bmm_nt(a[0], a[1])
+        elif n.op == "bmm_nn":
+            val[i] = oracle.bmm_nn(a[0], a[1])
+        else:
+            raise ValueError(n.op)
+    cons = g.consumers()
+    return {i: val[i] for i in range(len(g.nodes)) if not cons[i] and g.nodes[i].op != "input"}
+
+
+BLOCKS = [(96, 16, 1, 3), (96, 24, 2, 3), (144, 24, 1, 5)]
+
+
+def test_plan_groups_whole_blocks_into_fused_launches():
+    from paper_2212_01005_amd import binding as ago
+    g = _mobile_graph("bf16", BLOCKS)
+    part, weight = L.partition(g, ago)                        # no threshold: one subgraph per component
+    assert len(set(part)) == 1
+    plan = L.lower(g, part)
+    assert [k for k, _ in plan] == ["invres", "invres", "invres"]
+    assert [len(ids) for _, ids in plan] == [9, 8, 9]         # blocks 0 and 2 take their residual add along
+    # a threshold just above one block's weight: subgraphs stay below it, the partition is what the library's
+    # Cluster returns, and whatever falls inside one subgraph still lowers to fused structures
+    block_w = sum(weight[1:10])
+    part2, _ = L.partition(g, ago, td=1.05 * block_w)
+    assert len(set(part2)) > 1
+    kinds2 = [k for k, _ in L.lower(g, part2)]
+    assert set(kinds2) <= {"invres", "pw_dw", "dw_pw", "op"} and ("invres" in kinds2 or "pw_dw" in kinds2 or "dw_pw" in kinds2)
+    # every operator alone: nothing to fuse
+    alone = L.lower(g, list(range(len(g.nodes))))
+    assert all(k == "op" for k, _ in alone) and len(alone) == len(g.nodes) - 1
+    # every non-input node is launched exactly once, in topological order
+    for pl in (plan, L.lower(g, part2), alone):
+        ids = [i for _, chain in pl for i in chain]
+        assert ids == sorted(ids) and len(ids) == len(set(ids)) == len(g.nodes) - 1
+
+
+def test_plan_for_transformer_pieces():
+    from paper_2212_01005_amd import binding as ago
+    g = _transformer_graph()
+    part, _ = L.partition(g, ago)
+    assert [k for k, _ in L.lower(g, part)] == ["attn", "ffn"]
+    # an intermediate with a second consumer must stay materialised: no fusion across it
+    g2 = _transformer_graph()
+    g2.add("relu", [9])                                       # a second reader of the first gemm's output
+    part2, _ = L.partition(g2, ago)
+    assert "ffn" not in [k for k, _ in L.lower(g2, part2)]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("fuse", [True, False])
+def test_mobile_graph_runs_fused_and_matches_the_oracle(dtype, fuse):
+    import torch
+    from oracle import ago_oracle
+    from paper_2212_01005_amd import binding as ago
+    blocks = BLOCKS if fuse else [(96, 16, 1, 3), (96, 24, 2, 3)]      # the un-fused depthwise kernels are 3x3 only
+    g = _mobile_graph(dtype, blocks)
+    part = L.partition(g, ago)[0] if fuse else list(range(len(g.nodes)))
+    plan = L.lower(g, part)
+    x = wl.uniform(9200, (2, 14, 14, 16), -1.0, 1.0)
+    x = wl.round_to_bf16(x) if dtype == "bf16" else np.asarray(x, dtype=np.float32).astype(np.float64)
+    ref = _oracle_eval(g, {"x": x}, ago_oracle)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    host = dict(g.params)
+    g.params = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to("cuda:0").to(
+        torch.float32 if k.startswith("b") else td).contiguous() for k, v in host.items()}
+    ex = L.Executor(g, plan, ago, torch)
+    out = ex.run({"x": torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to("cuda:0").to(td)})
+    torch.cuda.synchronize()
+    assert ex.launches == (len(blocks) if fuse else len(g.nodes) - 1)
+    (i, got), = out.items()
+    r = ref[i]
+    tol = (2e-2 if dtype == "bf16" else 1e-4) * len(blocks)              # one rounding of the block output per block
+    gotn = got.float().cpu().numpy().astype(np.float64)
+    rms = np.sqrt(np.mean(r ** 2))
+    assert np.max(np.abs(gotn - r) / np.maximum(np.abs(r), rms)) <= tol
+
+
+@pytest.mark.gpu
+def test_transformer_pieces_run_fused_and_match_the_oracle():
+    import torch
+    from oracle import ago_oracle
+    from paper_2212_01005_amd import binding as ago
+    g = _transformer_graph()
+    plan = L.lower(g, L.partition(g, ago)[0])
+    ins = {n: wl.round_to_bf16(wl.normal(9300 + j, shp, 1.0)) for j, (n, shp) in enumerate(
+        [("q", (2, 2, 96, 64)), ("k", (2, 2, 96, 64)), ("v", (2, 2, 96, 64)), ("x", (100, 128))])}
+    ref = _oracle_eval(g, ins, ago_oracle)
+    host = dict(g.params)
+    g.params = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to("cuda:0").to(
+        torch.float32 if k.startswith("b") else torch.bfloat16).contiguous() for k, v in host.items()}
+    ex = L.Executor(g, plan, ago, torch)
+    out = ex.run({k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to("cuda:0").to(torch.bfloat16)
+                  for k, v in ins.items()})
+    torch.cuda.synchronize()
+    assert ex.launches == 2
+    for i, got in out.items():
+        r = ref[i]
+        gotn = got.float().cpu().numpy().astype(np.float64)
+        rms = np.sqrt(np.mean(r ** 2))
+        assert np.max(np.abs(gotn - r) / np.maximum(np.abs(r), rms)) <= 2e-2
