@@ -40,7 +40,7 @@ namespace ago {
 namespace {
 
 constexpr int kProducerWaves = 4;
-constexpr int FS = 384, CB = 384, NST = 4;
+constexpr int FS = 384, CB = 384;
 constexpr int kRowB = 384 * 2;                 // bytes per k-row of a weight tile
 constexpr int kWWaves = kProducerWaves - 1;    // three waves load weights, one loads X
 constexpr int kXRing = 4096;
@@ -53,6 +53,8 @@ struct StreamCfg {
     static constexpr int WMG = CW / 4;                      // row groups of consumer waves
     static constexpr int BM = 32 * MW * WMG, BK = BK_;
     static constexpr int KSTEPS = BK / 16;                  // 16-deep k steps per tile
+    static constexpr int NST = 98304 / (BK * kRowB);        // ring stages: 96 KB of weight tiles (4 or 8)
+    static constexpr int DIST = NST - 1;                    // tiles a producer runs ahead of the consumers
     static constexpr int TPB = 64 / BK;                     // tiles per 64-deep X block
     static constexpr int kXBlockB = BM * 64 * 2;            // X travels in 64-deep blocks (whole 128-byte lines)
     static constexpr int kXLoads = kXBlockB / 1024;         // direct loads of 1 KB per X block: 8 or 16
@@ -67,7 +69,7 @@ struct StreamCfg {
     static constexpr int kB1 = 159744;
     static constexpr int kSmem = kB1 + FS * 4;              // 161280
     static constexpr int kWLoadsPerWave = kWTileB / 1024 / kWWaves;      // 8 or 4 direct loads per wave and tile
-    static_assert(kRing1 + NST * kWTileB <= kB1, "phase-1 rings must not reach the bias slice");
+    static_assert((NST & (NST - 1)) == 0 && kRing1 + NST * kWTileB <= kB1, "phase-1 rings must not reach the bias slice");
     static_assert(kRing2 + NST * kWTileB <= kB1, "phase-2 ring must not reach the bias slice");
     static_assert(kSmem <= 160 * 1024, "LDS");
     static_assert(kXSlots >= kXLead + 1 && kXLead * kXLoads < 64, "X ring");
@@ -123,7 +125,7 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
     constexpr int BM = C::BM, BK = C::BK, KSTEPS = C::KSTEPS, TPB = C::TPB;
     constexpr int kXBlockB = C::kXBlockB, kXSlots = C::kXSlots, kXLead = C::kXLead, kXLoads = C::kXLoads;
     constexpr int kWTileB = C::kWTileB, kRing1 = C::kRing1, kRing2 = C::kRing2, kB1 = C::kB1;
-    constexpr int kWLoadsPerWave = C::kWLoadsPerWave;
+    constexpr int kWLoadsPerWave = C::kWLoadsPerWave, NST = C::NST, DIST = C::DIST;
     const int split = blockIdx.x, nsplit = gridDim.x;
     const int f0 = split * FS;
     const int nrb = (M + BM - 1) / BM;       // row blocks; a workgroup walks blockIdx.y, blockIdx.y + gridDim.y, ...
@@ -218,15 +220,14 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
                     load_to_lds(w + woff[j], st + (kWLoadsPerWave * pw + j) * 1024);
             };
             constexpr int PER = kWLoadsPerWave;
-            issue(0);                        // NT1 is even and at least 2
-            issue(1);
-            issue(min(2, NT1 - 1));          // a surplus issue repeats the last tile into its own stage
-            wait_vm<PER>();                  // tiles 0 and 1 have landed
+#pragma unroll
+            for (int u = 0; u < DIST; ++u) issue(min(u, NT1 - 1));   // a surplus issue repeats the last tile into its own stage
+            wait_vm<(DIST - 2) * PER>();     // tiles 0 and 1 have landed
             __builtin_amdgcn_s_barrier();
             for (int t = 0; t < NT1; ++t) {
-                if (t + 3 < NT1) {
-                    issue(t + 3);
-                    wait_vm<PER>();          // everything up to tile t+2 has landed
+                if (t + DIST < NT1) {
+                    issue(t + DIST);
+                    wait_vm<(DIST - 2) * PER>();   // everything up to tile t+2 has landed
                 } else {
                     wait_vm<0>();
                 }
@@ -258,15 +259,14 @@ __global__ __launch_bounds__((CW + kProducerWaves) * 64) void fused_ffn_stream_k
                 }
             };
             constexpr int PER = kWLoadsPerWave;
-            issue(0);
-            issue(1);
-            issue(2);                        // NT2 >= 12
-            wait_vm<PER>();
+#pragma unroll
+            for (int u = 0; u < DIST; ++u) issue(u);      // NT2 >= 12
+            wait_vm<(DIST - 2) * PER>();
             __builtin_amdgcn_s_barrier();    // matches the consumers' barrier after the Hs epilogue
             for (int t = 0; t < NT2; ++t) {
-                if (t + 3 < NT2) {
-                    issue(t + 3);
-                    wait_vm<PER>();
+                if (t + DIST < NT2) {
+                    issue(t + DIST);
+                    wait_vm<(DIST - 2) * PER>();
                 } else {
                     wait_vm<0>();
                 }
@@ -527,7 +527,9 @@ hipError_t fused_ffn_stream(const void* x, const void* w1, const float* b1, cons
     const bool ragged = F % FS != 0 || K2 % CB != 0;
     // Row blocks per workgroup.  Two (half as many workgroups, each twice as long, the other compute units
     // left to other streams) was measured: 47 us instead of 30 us alone and a slower concurrent step, since
-    // what bounds a workgroup is its own compute unit's load path; one it stays.
+    // what bounds a workgroup is its own compute unit's load path; one it stays.  Likewise 16-deep tiles in
+    // an eight-stage ring (seven tiles, 84 KB, in flight instead of three, 72 KB): 31.4 us against 30.2 us,
+    // so the stream is not waiting on latency either.
     const int bpw = 1;
     if (variant == 1) {
         if (ragged) return launch_stream<2, 32, 4, true>(x, w1, b1, w2, b2, y, M, K, F, K2, act, workspace, s, 1);
