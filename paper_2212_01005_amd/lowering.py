@@ -17,6 +17,7 @@ Graph form: ``Graph.nodes`` is a list in topological order; node i is ``Node(op,
     gemm     (w)               x:[M,K]  w:[K,N]
     bmm_nt / bmm_nn            two inputs, batched over the leading dimensions
     bias (b) relu relu6 gelu_tanh add(two inputs) scale (alpha) softmax
+    to_heads (batch, heads, head_major)   [B*S, Hh*D] viewed as [B,S,Hh,D], transposed to [B,Hh,S,D] if head_major
 
 Weights / biases are named entries of ``Graph.params``.
 """
@@ -27,7 +28,7 @@ from dataclasses import dataclass, field
 COMPLEX = {"conv1x1", "dwconv", "conv3x3", "gemm", "bmm_nt", "bmm_nn"}
 _TOKEN = {"conv1x1": "P", "dwconv": "D", "conv3x3": "C", "gemm": "G", "bmm_nt": "T", "bmm_nn": "N",
           "bias": "b", "relu": "r", "relu6": "6", "gelu_tanh": "g", "add": "+", "scale": "s", "softmax": "x",
-          "input": "i"}
+          "input": "i", "to_heads": "h"}
 
 # fused structures, longest first; the token string of a chain is matched from its first operator
 _PATTERNS = [
@@ -83,6 +84,10 @@ def infer_shapes(g):
             s = (nb, (h - 1) // st + 1, (w - 1) // st + 1, c)
         elif n.op == "gemm":
             s = s_in[0][:-1] + (g.params[n.attrs["w"]].shape[1],)
+        elif n.op == "to_heads":            # [B*S, Hh*D] -> [B, Hh, S, D] (head_major) or [B, S, Hh, D]
+            rows, cols = s_in[0]
+            b_, hh = n.attrs["batch"], n.attrs["heads"]
+            s = (b_, hh, rows // b_, cols // hh) if n.attrs.get("head_major", True) else (b_, rows // b_, hh, cols // hh)
         elif n.op == "bmm_nt":
             s = s_in[0][:-1] + (s_in[1][-2],)
         elif n.op == "bmm_nn":
@@ -128,6 +133,12 @@ def lower(g, subgraph_of):
         if g.nodes[i].op == "input":
             done[i] = True
             continue
+        sib = _qkv_siblings(g, cons, subgraph_of, done, i)
+        if sib is not None:
+            plan.append(("qkv", sib))
+            for k in sib:
+                done[k] = True
+            continue
         # the chain that starts at i and stays inside i's subgraph: every link is the only consumer of its
         # predecessor ("add" may take a second operand from anywhere that is already computed)
         chain = [i]
@@ -164,6 +175,36 @@ def lower(g, subgraph_of):
         for k in matched[1]:
             done[k] = True
     return plan
+
+
+def _qkv_siblings(g, cons, subgraph_of, done, i):
+    """Sibling fusion: node i is a gemm whose input feeds exactly three gemms of one subgraph with equal weight
+    shapes, each followed (or not, all alike) by a bias and then a "to_heads" view.  Returns the node ids
+    [gemm, (bias), to_heads] x 3 in graph order, or None."""
+    n = g.nodes[i]
+    if n.op != "gemm" or g.dtype != "bf16":
+        return None
+    src = n.inputs[0]
+    sibs = [j for j in cons[src] if g.nodes[j].op == "gemm" and not done[j] and subgraph_of[j] == subgraph_of[i]]
+    if len(sibs) != 3 or sibs[0] != i or len(cons[src]) != 3:
+        return None
+    chains = []
+    for j in sibs:
+        chain = [j]
+        while len(cons[chain[-1]]) == 1 and g.nodes[cons[chain[-1]][0]].op in ("bias", "to_heads") \
+                and subgraph_of[cons[chain[-1]][0]] == subgraph_of[i]:
+            chain.append(cons[chain[-1]][0])
+            if g.nodes[chain[-1]].op == "to_heads":
+                break
+        chains.append(chain)
+    kinds = ["".join({"gemm": "G", "bias": "b", "to_heads": "h"}[g.nodes[k].op] for k in c) for c in chains]
+    if kinds[0] not in ("Gh", "Gbh") or kinds.count(kinds[0]) != 3:
+        return None
+    w = [g.params[g.nodes[c[0]].attrs["w"]].shape for c in chains]
+    heads = [(g.nodes[c[-1]].attrs["heads"], g.nodes[c[-1]].attrs.get("head_major", True)) for c in chains]
+    if w.count(w[0]) != 3 or heads.count(heads[0]) != 3:
+        return None
+    return sorted(k for c in chains for k in c)
 
 
 def _admissible(g, kind, ids):
@@ -217,9 +258,20 @@ class Executor:
                 val[i] = inputs[n.attrs["name"]]
         for kind, ids in self.plan:
             nodes = [g.nodes[k] for k in ids]
-            out = self._new(ids[-1])
             x = val[nodes[0].inputs[0]]
             self.launches += 1
+            if kind == "qkv":
+                ends = [k for k in ids if g.nodes[k].op == "to_heads"]
+                gemms = [k for k in ids if g.nodes[k].op == "gemm"]
+                biases = [next((P[g.nodes[b_].attrs["b"]] for b_ in ids if g.nodes[b_].op == "bias" and g.nodes[b_].inputs[0] == gm), None)
+                          for gm in gemms]
+                outs = [self._new(e) for e in ends]
+                ago.ago_fused_qkv(x, *(P[g.nodes[gm].attrs["w"]] for gm in gemms), *biases, *outs,
+                                  head_major=g.nodes[ends[0]].attrs.get("head_major", True))
+                for e, o in zip(ends, outs):
+                    val[e] = o
+                continue
+            out = self._new(ids[-1])
             if kind == "invres":
                 pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
                 w1, wd, w2 = (P[nodes[p].attrs["w"]] for p in pos)
@@ -284,6 +336,10 @@ class Executor:
             ago.ago_scale(a, out, float(n.attrs["alpha"]))
         elif n.op == "softmax":
             ago.ago_softmax_rows(a, out)
+        elif n.op == "to_heads":
+            b_, hh = n.attrs["batch"], n.attrs["heads"]
+            v4 = a.view(b_, a.shape[0] // b_, hh, a.shape[1] // hh)
+            out.copy_(v4.permute(0, 2, 1, 3) if n.attrs.get("head_major", True) else v4)   # a device copy, no arithmetic
         elif n.op == "bmm_nt":
             ago.ago_bmm_nt(a, val[n.inputs[1]], out)
         elif n.op == "bmm_nn":

@@ -87,6 +87,10 @@ def _oracle_eval(g, inputs, oracle):
             val[i] = oracle.scale(a[0], n.attrs["alpha"])
         elif n.op == "softmax":
             val[i] = oracle.softmax_rows(a[0])
+        elif n.op == "to_heads":
+            b_, hh = n.attrs["batch"], n.attrs["heads"]
+            v4 = a[0].reshape(b_, a[0].shape[0] // b_, hh, a[0].shape[1] // hh)
+            val[i] = np.ascontiguousarray(v4.transpose(0, 2, 1, 3)) if n.attrs.get("head_major", True) else v4
         elif n.op == "bmm_nt":
             val[i] = oracle.bmm_nt(a[0], a[1])
         elif n.op == "bmm_nn":
@@ -95,6 +99,26 @@ def _oracle_eval(g, inputs, oracle):
             raise ValueError(n.op)
     cons = g.consumers()
     return {i: val[i] for i in range(len(g.nodes)) if not cons[i] and g.nodes[i].op != "input"}
+
+
+def _attention_layer_graph():
+    """x -> three sibling projections -> heads -> attention chain (the sibling fusion of Sec. III feeding
+    the matmul -> softmax -> matmul chain of Sec. VI-C)."""
+    g = L.Graph([], {}, "bf16")
+    b_, s_, k_, hh, d = 2, 100, 128, 3, 64
+    x = g.add("input", name="x", shape=(b_ * s_, k_))
+    ends = []
+    for j, nm in enumerate("qkv"):
+        g.params["w" + nm] = wl.round_to_bf16(wl.normal(9400 + j, (k_, hh * d), k_ ** -0.5))
+        g.params["b" + nm] = np.asarray(wl.normal(9410 + j, (hh * d,), 0.1), dtype=np.float32).astype(np.float64)
+        y = g.add("gemm", [x], w="w" + nm)
+        y = g.add("bias", [y], b="b" + nm)
+        ends.append(g.add("to_heads", [y], batch=b_, heads=hh, head_major=True))
+    sc = g.add("bmm_nt", [ends[0], ends[1]])
+    sc = g.add("scale", [sc], alpha=0.125)
+    sc = g.add("softmax", [sc])
+    g.add("bmm_nn", [sc, ends[2]])
+    return g
 
 
 BLOCKS = [(96, 16, 1, 3), (96, 24, 2, 3), (144, 24, 1, 5)]
@@ -164,6 +188,40 @@ def test_mobile_graph_runs_fused_and_matches_the_oracle(dtype, fuse):
     gotn = got.float().cpu().numpy().astype(np.float64)
     rms = np.sqrt(np.mean(r ** 2))
     assert np.max(np.abs(gotn - r) / np.maximum(np.abs(r), rms)) <= tol
+
+
+def test_plan_fuses_sibling_projections():
+    from paper_2212_01005_amd import binding as ago
+    g = _attention_layer_graph()
+    plan = L.lower(g, L.partition(g, ago)[0])
+    assert [k for k, _ in plan] == ["qkv", "attn"]
+    assert len(plan[0][1]) == 9 and len(plan[1][1]) == 4
+    # siblings in different subgraphs are not fused
+    part = list(range(len(g.nodes)))
+    assert "qkv" not in [k for k, _ in L.lower(g, part)]
+
+
+@pytest.mark.gpu
+def test_attention_layer_runs_as_two_launches():
+    import torch
+    from oracle import ago_oracle
+    from paper_2212_01005_amd import binding as ago
+    g = _attention_layer_graph()
+    plan = L.lower(g, L.partition(g, ago)[0])
+    x = wl.round_to_bf16(wl.normal(9420, (200, 128), 1.0))
+    ref = _oracle_eval(g, {"x": x}, ago_oracle)
+    host = dict(g.params)
+    g.params = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to("cuda:0").to(
+        torch.float32 if k.startswith("b") else torch.bfloat16).contiguous() for k, v in host.items()}
+    ex = L.Executor(g, plan, ago, torch)
+    out = ex.run({"x": torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to("cuda:0").to(torch.bfloat16)})
+    torch.cuda.synchronize()
+    assert ex.launches == 2
+    (i, got), = out.items()
+    r = ref[i]
+    gotn = got.float().cpu().numpy().astype(np.float64)
+    rms = np.sqrt(np.mean(r ** 2))
+    assert np.max(np.abs(gotn - r) / np.maximum(np.abs(r), rms)) <= 3e-2      # q, k, v are rounded to bf16 in between
 
 
 @pytest.mark.gpu
