@@ -28,7 +28,9 @@
  *   errors     return codes only.  Argument validation happens on the host
  *              before any HIP call; AGO_ERR_LAUNCH reports a failed launch.
  *              A shape the kernels cannot run returns AGO_ERR_UNSUPPORTED,
- *              never a wrong answer.
+ *              never a wrong answer.  That includes any tensor (an on-chip
+ *              intermediate counted at full size) of 2^31 elements or more:
+ *              offsets inside a tensor are 32-bit.
  *   workspace  scratch for cross-workgroup partial results; size from
  *              ago_workspace_bytes().  May be NULL when that size is 0.
  */

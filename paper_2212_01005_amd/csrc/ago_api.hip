@@ -181,7 +181,7 @@ ago_status ago_fused_dw_dw(const void* x, const void* wa, const float* ba, const
     if (st != AGO_OK) return st;
     if (!valid_dtype(dt)) return AGO_ERR_DTYPE;
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || (stride != 1 && stride != 2)) return AGO_ERR_SHAPE;
-    if (C % 4) return AGO_ERR_UNSUPPORTED;
+    if (C % 4 || !fits31(N, H, W, C)) return AGO_ERR_UNSUPPORTED;
     return from_hip(fused_dw_dw(x, wa, ba, wb, bb, y, N, H, W, C, stride, dt == AGO_BF16, as_stream(hip_stream)));
 }
 
@@ -238,7 +238,7 @@ ago_status ago_gemm(const void* a, const void* b, const float* bias, const void*
     if (st != AGO_OK) return st;
     if (!valid_dtype(dt) || !valid_act(act)) return AGO_ERR_DTYPE;
     if (M <= 0 || K <= 0 || N <= 0) return AGO_ERR_SHAPE;
-    if (K % 8 || N % 8) return AGO_ERR_UNSUPPORTED;
+    if (K % 8 || N % 8 || !fits31(M, K > N ? K : N, 1, 1) || !fits31(K, N, 1, 1)) return AGO_ERR_UNSUPPORTED;
     return from_hip(dt == AGO_BF16 ? gemm_bf16(a, b, bias, res, c, M, K, N, act, as_stream(hip_stream))
                                    : gemm_f32(a, b, bias, res, c, M, K, N, act, as_stream(hip_stream)));
 }
@@ -258,7 +258,7 @@ ago_status ago_dwconv3x3(const void* x, const void* w, const float* bias, void* 
     if (st != AGO_OK) return st;
     if (!valid_dtype(dt) || !valid_act(act)) return AGO_ERR_DTYPE;
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || (stride != 1 && stride != 2)) return AGO_ERR_SHAPE;
-    if (C % 8) return AGO_ERR_UNSUPPORTED;
+    if (C % 8 || !fits31(N, H, W, C)) return AGO_ERR_UNSUPPORTED;
     return from_hip(dwconv3x3(x, w, bias, y, N, H, W, C, stride, act, dt == AGO_BF16, as_stream(hip_stream)));
 }
 
@@ -269,7 +269,7 @@ ago_status ago_conv3x3(const void* x, const void* w, const float* bias, const vo
     if (st != AGO_OK) return st;
     if (!valid_dtype(dt) || !valid_act(act)) return AGO_ERR_DTYPE;
     if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0) return AGO_ERR_SHAPE;
-    if (dt != AGO_BF16 || Cin != 64 || Cout != 64) return AGO_ERR_UNSUPPORTED;
+    if (dt != AGO_BF16 || Cin != 64 || Cout != 64 || !fits31(N, H, W, 64)) return AGO_ERR_UNSUPPORTED;
     return from_hip(conv3x3_bf16(x, w, bias, res, y, N, H, W, act, as_stream(hip_stream)));
 }
 
@@ -324,6 +324,7 @@ ago_status ago_bmm_nt(const void* a, const void* b, void* c, long batch, int M, 
     if (!valid_dtype(dt) || !valid_dtype(out_dt)) return AGO_ERR_DTYPE;
     if (batch <= 0 || M <= 0 || N <= 0 || K <= 0) return AGO_ERR_SHAPE;
     if (dt != AGO_BF16 || K % 8 || N % 8 || batch > 65535) return AGO_ERR_UNSUPPORTED;
+    if (!fits31(M, N, 1, 1) || !fits31(M, K, 1, 1) || !fits31(N, K, 1, 1)) return AGO_ERR_UNSUPPORTED;
     return from_hip(bmm_nt_bf16(a, b, c, batch, M, N, K, alpha, out_dt == AGO_F32, as_stream(hip_stream)));
 }
 
@@ -335,6 +336,7 @@ ago_status ago_bmm_nn(const void* a, const void* b, void* c, long batch, int M, 
     if (!valid_dtype(dt)) return AGO_ERR_DTYPE;
     if (batch <= 0 || M <= 0 || N <= 0 || K <= 0) return AGO_ERR_SHAPE;
     if (dt != AGO_BF16 || K % 8 || N % 8 || batch > 65535) return AGO_ERR_UNSUPPORTED;
+    if (!fits31(M, N, 1, 1) || !fits31(M, K, 1, 1) || !fits31(N, K, 1, 1)) return AGO_ERR_UNSUPPORTED;
     return from_hip(bmm_nn_bf16(a, b, c, batch, M, N, K, as_stream(hip_stream)));
 }
 
@@ -443,6 +445,7 @@ ago_status ago_fused_attn_bias(const void* q, const void* k, const void* v, cons
     if (bias_stride_h != 0 && bias_stride_h < plane) return AGO_ERR_SHAPE;
     if (bias_stride_b != 0 && bias_stride_b < (bias_stride_h ? bias_stride_h * Hh : plane)) return AGO_ERR_SHAPE;
     if (reinterpret_cast<uintptr_t>(bias) % 2) return AGO_ERR_ALIGN;
+    if (!fits31(S, S, 1, 1)) return AGO_ERR_UNSUPPORTED;
     return from_hip(fused_attn_bias(q, k, v, bias, o, B, Hh, S, (long)bias_stride_b, (long)bias_stride_h, scale,
                                     tile_config(AGO_OP_FUSED_ATTN), as_stream(hip_stream), D));
 }
@@ -460,6 +463,7 @@ ago_status ago_fused_qkv(const void* x, const void* wq, const void* wk, const vo
     for (const void* p : ps)
         if (p && reinterpret_cast<uintptr_t>(p) % 16) return AGO_ERR_ALIGN;
     if (dt != AGO_BF16 || K % 8 || (Hh * D) % 8) return AGO_ERR_UNSUPPORTED;
+    if (!fits31(B, S, K > Hh * D ? K : Hh * D, 1) || !fits31(K, Hh, D, 1)) return AGO_ERR_UNSUPPORTED;
     return from_hip(fused_qkv(x, wq, wk, wv, bq, bk, bv, q, k, v, B, S, K, Hh, D, head_major != 0,
                               as_stream(hip_stream)));
 }
@@ -468,7 +472,7 @@ ago_status ago_unfused_attn(const void* q, const void* k, const void* v, void* o
                             int D, float scale, ago_dtype dt, int epilogue_fused, void* workspace,
                             size_t workspace_bytes, void* s) {
     AGO_TRY(check_attn(q, k, v, o, B, Hh, S, D, scale, dt));
-    if (S % 8) return AGO_ERR_UNSUPPORTED;
+    if (S % 8 || !fits31(S, S, 1, 1)) return AGO_ERR_UNSUPPORTED;
     const int dims[4] = {B, Hh, S, D};
     AGO_TRY(check_workspace(workspace, workspace_bytes, ago::workspace_bytes(AGO_OP_UNFUSED_ATTN, dims, 4, dt)));
     // scores stay fp32 (the softmax is an fp32 operator); the probabilities are rounded to bf16

@@ -18,6 +18,17 @@ static int g_tile_cfg[4] = {-1, -1, -1, -1};
 bool valid_dtype(int dt) { return dt == AGO_F32 || dt == AGO_BF16; }
 bool valid_act(int act) { return act >= AGO_ACT_NONE && act <= AGO_ACT_GELU_TANH; }
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+// The kernels index a tensor with 32-bit element offsets inside one image / batch entry and derive grid
+// sizes from int products: a tensor of 2^31 elements or more is refused rather than risked.
+bool fits31(long long a, long long b, long long c, long long d) {
+    const long long lim = 1LL << 31;
+    long long n = a;
+    for (long long f : {b, c, d}) {
+        if (n >= lim || f >= lim) return false;
+        n *= f;
+    }
+    return n < lim;
+}
 
 ago_status check_ptrs(const void* const* ptrs, int n_required, int n_total) {
     for (int i = 0; i < n_required; ++i)
@@ -47,6 +58,8 @@ ago_status check_invres(const void* x, const void* w1, const void* wd, const voi
     for (const void* p : ps)
         if (p && !aligned16(p)) return AGO_ERR_ALIGN;
     if (Cin % 8 || Cexp % 16 || Cout % 8) return AGO_ERR_UNSUPPORTED;
+    const int cmax = Cin > Cexp ? (Cin > Cout ? Cin : Cout) : (Cexp > Cout ? Cexp : Cout);
+    if (!fits31(N, H, W, cmax)) return AGO_ERR_UNSUPPORTED;
     return AGO_OK;
 }
 
@@ -60,6 +73,7 @@ ago_status check_pw_dw(const void* x, const void* w1, const void* wd, const void
     for (const void* p : ps)
         if (p && !aligned16(p)) return AGO_ERR_ALIGN;
     if (Cin % 8 || Cexp % 16) return AGO_ERR_UNSUPPORTED;
+    if (!fits31(N, H, W, Cin > Cexp ? Cin : Cexp)) return AGO_ERR_UNSUPPORTED;
     return AGO_OK;
 }
 
@@ -73,6 +87,7 @@ ago_status check_dw_pw(const void* x, const void* wd, const void* w2, const void
     for (const void* p : ps)
         if (p && !aligned16(p)) return AGO_ERR_ALIGN;
     if (C % 16 || Cout % 8) return AGO_ERR_UNSUPPORTED;
+    if (!fits31(N, H, W, C > Cout ? C : Cout)) return AGO_ERR_UNSUPPORTED;
     return AGO_OK;
 }
 
@@ -85,6 +100,7 @@ ago_status check_conv_chain(const void* x, const void* wa, const void* wb, const
     for (const void* p : ps)
         if (p && !aligned16(p)) return AGO_ERR_ALIGN;
     if (dt != AGO_BF16 || C != 64) return AGO_ERR_UNSUPPORTED;
+    if (!fits31(N, H, W, C)) return AGO_ERR_UNSUPPORTED;
     return AGO_OK;
 }
 
@@ -97,6 +113,8 @@ ago_status check_ffn(const void* x, const void* w1, const void* w2, const void* 
     for (const void* p : ps)
         if (p && !aligned16(p)) return AGO_ERR_ALIGN;
     if (dt != AGO_BF16 || K % 64 || F % 8 || K2 % 8) return AGO_ERR_UNSUPPORTED;
+    if (!fits31(M, K > F ? (K > K2 ? K : K2) : (F > K2 ? F : K2), 1, 1) || !fits31(K > K2 ? K : K2, F, 1, 1))
+        return AGO_ERR_UNSUPPORTED;
     return AGO_OK;
 }
 
@@ -109,6 +127,7 @@ ago_status check_attn(const void* q, const void* k, const void* v, const void* o
     for (const void* p : ps)
         if (!aligned16(p)) return AGO_ERR_ALIGN;
     if (dt != AGO_BF16 || (D != 64 && D != 128) || !(scale > 0.0f)) return AGO_ERR_UNSUPPORTED;
+    if (!fits31(B, Hh, S, D)) return AGO_ERR_UNSUPPORTED;
     return AGO_OK;
 }
 

@@ -27,6 +27,7 @@ ago_status check_workspace(const void* workspace, size_t have, size_t need);
 ago_status check_ptrs(const void* const* ptrs, int n_required, int n_total);
 bool valid_dtype(int dt);
 bool valid_act(int act);
+bool fits31(long long a, long long b, long long c, long long d);   // a*b*c*d < 2^31 (each factor too)
 
 size_t workspace_bytes(int op, const int* dims, int ndims, int dt);
 int tile_config(int op);          // current selection for a fused op (-1 = built-in)

@@ -156,6 +156,25 @@ def test_validation_runs_before_any_gpu_call(lib):
     assert lib.ago_gemm(p, p, None, None, p, 8, 12, 8, 0, 1, None) == 5
 
 
+def test_tensors_of_two_to_the_31_elements_are_refused(lib):
+    """Sizes whose element counts do not fit 32-bit offsets return UNSUPPORTED on the host (no GPU call)."""
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    p = _fake()
+    lib.ago_fused_invres.argtypes = [vp] * 8 + [ci] * 9 + [vp, sz, vp]
+    inv = lambda N, H, W, Cin, Cexp, Cout: lib.ago_fused_invres(
+        p, p, None, p, None, p, None, p, N, H, W, Cin, Cexp, Cout, 1, 0, 1, None, 0, None)
+    assert inv(4096, 1024, 1024, 8, 16, 8) == 5
+    assert inv(64, 1024, 1024, 8, 48, 8) == 5                              # the expanded tensor counts too
+    lib.ago_fused_conv_chain.argtypes = [vp] * 6 + [ci] * 6 + [vp, sz, vp]
+    assert lib.ago_fused_conv_chain(p, p, None, p, None, p, 2048, 128, 128, 64, 0, 1, None, 0, None) == 5
+    lib.ago_fused_attn.argtypes = [vp] * 4 + [ci] * 4 + [ctypes.c_float, ci, vp, sz, vp]
+    assert lib.ago_fused_attn(p, p, p, p, 64, 64, 8192, 64, 0.125, 1, None, 0, None) == 5
+    lib.ago_fused_ffn.argtypes = [vp] * 6 + [ci] * 6 + [vp, sz, vp]
+    assert lib.ago_fused_ffn(p, p, None, p, None, p, 1 << 20, 4096, 64, 64, 3, 1, None, 0, None) == 5
+    lib.ago_gemm.argtypes = [vp] * 5 + [ci] * 5 + [vp]
+    assert lib.ago_gemm(p, p, None, None, p, 1 << 20, 4096, 8, 0, 1, None) == 5
+
+
 def test_status_strings(lib):
     lib.ago_status_string.restype = ctypes.c_char_p
     lib.ago_status_string.argtypes = [ctypes.c_int]
