@@ -297,6 +297,21 @@ def main():
                           "speedup": round(u_us / f_us, 2),
                           "tflops": round(c.flops() / (f_us * 1e-6) / 1e12, 3)})
 
+    # ---- inverted-residual blocks at the layer shapes of a whole network, batch 1 (not part of the step) ----
+    blocks = []
+    if not args.no_detail and not args.no_cold and args.only < 0:
+        for c in wl.network_block_cases(1):
+            t = runner.to_device(c)
+            y, ws = runner.alloc_output(c), runner.alloc_workspace(c, fused=True)
+            wsu = runner.alloc_workspace(c, fused=False)
+            f_us = time_us(runner.prepare_fused(c, t, y, ws), args.detail_iters)
+            u_us = time_us(runner.prepare_unfused(c, t, y, wsu, True), args.detail_iters)
+            plan = ago.fused_invres_plan(c.N, c.H, c.W, c.Cin, c.Cexp, c.Cout, c.stride, c.ksize, ago.BF16,
+                                         ws.numel() if ws is not None else 0)
+            blocks.append({"name": c.name, "fused_us": round(f_us, 2), "unfused_epilogue_us": round(u_us, 2),
+                           "speedup": round(u_us / f_us, 2), "tile": [plan["tile_h"], plan["tile_w"]],
+                           "channel_split": plan["split"]})
+
     # ---- CPU baseline: the oracle as it stands, on the host cores ---------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -329,7 +344,7 @@ def main():
                    "tile_config": tile_cfg or "built-in",
                    "note": "config 0 is fp32 storage, configs 1-4 bf16 storage with fp32 accumulation"},
         "roofline": roofline, "cpu_baseline": cpu, "one_stream": one_stream,
-        "per_config": per_config, "pairs": pairs,
+        "per_config": per_config, "pairs": pairs, "network_blocks": blocks,
         "fused_kernel_us": {str(k): round(v * 1e3, 2) for k, v in kernel_ms.items()},
     }
     print(json.dumps(out))

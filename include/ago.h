@@ -73,7 +73,13 @@ typedef enum {
  *   y = D * w2 + b2 (+ x if residual)   1x1 conv, Cexp -> Cout
  * x:[N,H,W,Cin] w1:[Cin,Cexp] wd:[3,3,Cexp] w2:[Cexp,Cout] y:[N,OH,OW,Cout],
  * OH = (H-1)/stride + 1.  stride is 1 or 2.  residual != 0 requires stride == 1 and
- * Cin == Cout.  Requires Cin % 8 == 0, Cexp % 16 == 0, Cout % 8 == 0 (else UNSUPPORTED). */
+ * Cin == Cout.  Requires Cin % 8 == 0, Cexp % 16 == 0, Cout % 8 == 0 (else UNSUPPORTED).
+ * workspace is optional.  With ago_workspace_bytes(AGO_OP_FUSED_INVRES, {N,H,W,Cin,Cexp,Cout,stride
+ * [,ksize]}) bytes of it, a wide block on few pixels (e.g. 7x7x960 at batch 1, a single tile) is cut
+ * along the expanded channels as well: each workgroup takes one slice of the projection's reduction
+ * (the "downstream pointwise" rule of Fig. 7b with the slices spread over the chip), writes an fp32
+ * partial, and a second small kernel adds the partials, b2 and the residual.  Without (or with too
+ * little) workspace one workgroup walks all slices of its tile: same result, slower on such shapes. */
 ago_status ago_fused_invres(const void* x, const void* w1, const float* b1,
                             const void* wd, const float* bd,
                             const void* w2, const float* b2, void* y,
@@ -95,11 +101,13 @@ ago_status ago_fused_invres_k(const void* x, const void* w1, const float* b1,
 /* Host-only: the tiling ago_fused_invres[_k] would launch for this shape (no GPU call).  The tile
  * is the candidate with the lowest predicted time of a cost model fitted to MI355X measurements
  * (the tile-size trade-off of Sec. III-B / Fig. 7a: re-computed halo against parallelism), or the
- * one set with ago_set_tile_config.  plan (host, 6 ints): candidate index, tile rows, tile columns
- * of output pixels, number of chunks of expanded channels, channels per chunk, LDS bytes.
- * predicted_us (host, may be NULL): the model's kernel time in microseconds. */
+ * one set with ago_set_tile_config (tile candidate + 16 x channel-split option).  workspace_bytes: what
+ * the launch would be given (plans whose partials need more are not considered).  plan (host, 7 ints):
+ * candidate index, tile rows, tile columns of output pixels, chunks of expanded channels one workgroup
+ * walks, channels per chunk, LDS bytes, workgroups per tile (1 = no channel split).
+ * predicted_us (host, may be NULL): the model's time in microseconds. */
 ago_status ago_fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize,
-                                 ago_dtype dt, int plan[6], float* predicted_us);
+                                 ago_dtype dt, size_t workspace_bytes, int plan[7], float* predicted_us);
 
 /* The two-operator pairs of the block as calls of their own (the micro-benchmark pairs of
  * Sec. VI, Fig. 13: pw->dw, dw->pw, dw->dw, pw->pw).  Same kernels, conventions and restrictions as the
@@ -109,6 +117,8 @@ ago_status ago_fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cou
  *                     tensor is 0 outside the image.  Cin % 8 == 0, Cexp % 16 == 0.
  *   ago_fused_dw_pw   y = relu6(dw3x3(x, wd, stride) + bd) * w2 + b2                (Fig. 7b)
  *                     x:[N,H,W,C] wd:[3,3,C] w2:[C,Cout] y:[N,OH,OW,Cout].  C % 16 == 0, Cout % 8 == 0.
+ *                     Optional workspace as for ago_fused_invres, size from
+ *                     ago_workspace_bytes(AGO_OP_FUSED_DW_PW, {N,H,W,C,Cout,stride}).
  *   ago_fused_dw_dw   y = relu6(dw3x3(relu6(dw3x3(x, wa, stride) + ba), wb, 1) + bb)  (Fig. 7a twice)
  *                     x:[N,H,W,C] wa,wb:[3,3,C] y:[N,OH,OW,C]; the intermediate is 0 outside its
  *                     image.  C % 4 == 0.  Vector ALUs only.

@@ -31,7 +31,7 @@ _vp, _i, _l, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_fl
 
 _SIGS = {
     "ago_fused_invres": [_vp] * 8 + [_i] * 9 + [_vp, _sz, _vp],
-    "ago_fused_invres_plan": [_i] * 9 + [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)],
+    "ago_fused_invres_plan": [_i] * 9 + [_sz, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)],
     "ago_fused_invres_k": [_vp] * 8 + [_i] * 10 + [_vp, _sz, _vp],
     "ago_fused_conv_chain": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_ffn": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
@@ -231,12 +231,13 @@ def ago_fused_invres(x, w1, b1, wd, bd, w2, b2, y, stride, residual, workspace=N
                               N, H, W, Cin, Cexp, Cout, stride, int(residual), _dt(x), wp, wb, _stream())
 
 
-def fused_invres_plan(N, H, W, Cin, Cexp, Cout, stride, ksize, dtype):
-    """Host-only: dict(config, tile_h, tile_w, chunks, chunk_channels, lds_bytes, predicted_us)."""
-    plan = (ctypes.c_int * 6)()
+def fused_invres_plan(N, H, W, Cin, Cexp, Cout, stride, ksize, dtype, workspace_bytes=0):
+    """Host-only: dict(config, tile_h, tile_w, chunks, chunk_channels, lds_bytes, split, predicted_us)."""
+    plan = (ctypes.c_int * 7)()
     us = ctypes.c_float(0.0)
-    _chk(lib.ago_fused_invres_plan(N, H, W, Cin, Cexp, Cout, stride, ksize, dtype, plan, ctypes.byref(us)))
-    keys = ("config", "tile_h", "tile_w", "chunks", "chunk_channels", "lds_bytes")
+    _chk(lib.ago_fused_invres_plan(N, H, W, Cin, Cexp, Cout, stride, ksize, dtype, workspace_bytes, plan,
+                                   ctypes.byref(us)))
+    keys = ("config", "tile_h", "tile_w", "chunks", "chunk_channels", "lds_bytes", "split")
     d = dict(zip(keys, list(plan)))
     d["predicted_us"] = us.value
     return d

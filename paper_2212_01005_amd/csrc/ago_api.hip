@@ -119,36 +119,36 @@ ago_status ago_fused_invres(const void* x, const void* w1, const float* b1, cons
                             const float* bd, const void* w2, const float* b2, void* y, int N, int H,
                             int W, int Cin, int Cexp, int Cout, int stride, int residual, ago_dtype dt,
                             void* workspace, size_t workspace_bytes, void* hip_stream) {
-    (void)workspace; (void)workspace_bytes;
     ago_status st = check_invres(x, w1, wd, w2, y, b1, bd, b2, N, H, W, Cin, Cexp, Cout, stride, residual, dt);
     if (st != AGO_OK) return st;
+    if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return AGO_ERR_ALIGN;
     return from_hip(fused_invres(x, w1, b1, wd, bd, w2, b2, y, N, H, W, Cin, Cexp, Cout, stride,
                                  residual, dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES),
-                                 as_stream(hip_stream)));
+                                 as_stream(hip_stream), 0, 3, workspace, workspace_bytes));
 }
 
 ago_status ago_fused_invres_k(const void* x, const void* w1, const float* b1, const void* wd,
                               const float* bd, const void* w2, const float* b2, void* y, int N, int H,
                               int W, int Cin, int Cexp, int Cout, int stride, int ksize, int residual,
                               ago_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    (void)workspace; (void)workspace_bytes;
     ago_status st = check_invres(x, w1, wd, w2, y, b1, bd, b2, N, H, W, Cin, Cexp, Cout, stride, residual, dt);
     if (st != AGO_OK) return st;
     if (ksize != 3 && ksize != 5) return AGO_ERR_UNSUPPORTED;
+    if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return AGO_ERR_ALIGN;
     return from_hip(fused_invres(x, w1, b1, wd, bd, w2, b2, y, N, H, W, Cin, Cexp, Cout, stride,
                                  residual, dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES),
-                                 as_stream(hip_stream), 0, ksize));
+                                 as_stream(hip_stream), 0, ksize, workspace, workspace_bytes));
 }
 
 ago_status ago_fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize,
-                                 ago_dtype dt, int plan[6], float* predicted_us) {
+                                 ago_dtype dt, size_t workspace_bytes, int plan[7], float* predicted_us) {
     if (!plan) return AGO_ERR_NULL;
     if (dt != AGO_F32 && dt != AGO_BF16) return AGO_ERR_DTYPE;
     if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cexp <= 0 || Cout <= 0) return AGO_ERR_SHAPE;
     if (stride != 1 && stride != 2) return AGO_ERR_SHAPE;
     if (Cin % 8 || Cexp % 16 || Cout % 8 || (ksize != 3 && ksize != 5)) return AGO_ERR_UNSUPPORTED;
     return fused_invres_plan(N, H, W, Cin, Cexp, Cout, stride, ksize, dt == AGO_BF16,
-                             tile_config(AGO_OP_FUSED_INVRES), 0, plan, predicted_us) == 0
+                             tile_config(AGO_OP_FUSED_INVRES), 0, workspace_bytes, plan, predicted_us) == 0
                ? AGO_OK : AGO_ERR_UNSUPPORTED;
 }
 
@@ -165,11 +165,12 @@ ago_status ago_fused_pw_dw(const void* x, const void* w1, const float* b1, const
 ago_status ago_fused_dw_pw(const void* x, const void* wd, const float* bd, const void* w2, const float* b2,
                            void* y, int N, int H, int W, int C, int Cout, int stride, ago_dtype dt,
                            void* workspace, size_t workspace_bytes, void* hip_stream) {
-    (void)workspace; (void)workspace_bytes;
     ago_status st = check_dw_pw(x, wd, w2, y, bd, b2, N, H, W, C, Cout, stride, dt);
     if (st != AGO_OK) return st;
+    if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return AGO_ERR_ALIGN;
     return from_hip(fused_invres(x, nullptr, nullptr, wd, bd, w2, b2, y, N, H, W, 8, C, Cout, stride, 0,
-                                 dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES), as_stream(hip_stream), 2));
+                                 dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES), as_stream(hip_stream), 2, 3,
+                                 workspace, workspace_bytes));
 }
 
 ago_status ago_fused_dw_dw(const void* x, const void* wa, const float* ba, const void* wb, const float* bb,

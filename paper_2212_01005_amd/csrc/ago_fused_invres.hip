@@ -18,6 +18,12 @@
 // in registers (the "downstream pointwise" rule applied inside the block: D is consumed in slices
 // of the reduction dimension).  One chunk = the whole of Cexp is the common case.
 //
+// Channel split (SPLIT): a wide block on few pixels (the 7 x 7 x 960 blocks at batch 1 are one tile)
+// leaves most of the chip idle if one workgroup walks all the chunks.  With a workspace the chunks go
+// to different workgroups instead (grid.y = chunk): each runs stages 0-3 for its chunk and writes its
+// slice of the projection's reduction as an fp32 partial; invres_reduce_kernel adds the partials, b2
+// and the residual.  Same rule as above, with the slices of the reduction spread over the chip.
+//
 // The same kernel runs the two-operator pairs of the block (the paper's Fig. 13 micro-benchmarks):
 //   mode 1  pw -> dw: stages 0-2, D is stored to global memory instead of LDS
 //   mode 2  dw -> pw: the input *is* E (stage 0 loads its halo tile into the E region, zero outside
@@ -41,6 +47,8 @@ struct InvresParams {
     int off_w1, off_e, off_d, off_w2, off_wd, off_b;  // LDS byte offsets (Xs at 0)
     int ksplit;                     // stage 3: waves per (pixel tile, channel tile) job, splitting k
     int mode;                       // 0: pw -> dw -> pw   1: pw -> dw   2: dw -> pw
+    int nsplit;                     // channel split: workgroups per tile (one chunk each), 1 = none
+    float* part;                    // channel split: [nsplit][N][OH][OW][Cout] fp32 partial projections
 };
 
 template <bool BF16> struct InT { typedef float type; };
@@ -52,8 +60,9 @@ constexpr int kInvresJobsPerWave = 4;  // stage-3 accumulators a wave can hold a
 
 // KS: odd depthwise kernel size (3 or 5), zero padding (KS - 1) / 2.  CHUNKED: several chunks of expanded
 // channels with the projection's accumulators carried in registers; the single-chunk instantiation
-// keeps none (64 registers or fewer: two workgroups per compute unit).
-template <bool BF16, int STRIDE, int KS, bool CHUNKED>
+// keeps none (64 registers or fewer: two workgroups per compute unit).  SPLIT (single-chunk only): the
+// workgroup's chunk is blockIdx.y and the projection's partial goes to the workspace.
+template <bool BF16, int STRIDE, int KS, bool CHUNKED, bool SPLIT = false>
 __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const InvresParams p) {
     typedef typename InT<BF16>::type T;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -106,7 +115,9 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
     f32x4 accj[CHUNKED ? kInvresJobsPerWave : 1];
 #pragma unroll
     for (int jj = 0; jj < (CHUNKED ? kInvresJobsPerWave : 1); ++jj) accj[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+    static_assert(!(SPLIT && CHUNKED), "a split workgroup runs one chunk");
     T* Y = reinterpret_cast<T*>(p.y) + (long)n * p.OH * p.OW * p.Cout;
+    float* P = SPLIT ? p.part + ((long)blockIdx.y * p.N + n) * p.OH * p.OW * p.Cout : nullptr;
     auto emit = [&](int pt, int ot, const f32x4& acc) {
         const int co = ot * 16 + i;        // this lane's output channel; registers = pixels 4g..4g+3
         if (co >= p.Cout) return;
@@ -117,16 +128,20 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
             const int oy = po / p.TOW, ox = po % p.TOW;
             const int oh = oh0 + oy, ow = ow0 + ox;
             if (po < p.TOH * p.TOW && oh < p.OH && ow < p.OW) {
-                float v = acc[r] + bv;
-                if (p.residual) v += (float)Xs[((oy + PAD) * p.EW + ox + PAD) * p.ldx + co];
-                Y[((long)oh * p.OW + ow) * p.Cout + co] = (T)v;
+                if constexpr (SPLIT) {
+                    P[((long)oh * p.OW + ow) * p.Cout + co] = acc[r];
+                } else {
+                    float v = acc[r] + bv;
+                    if (p.residual) v += (float)Xs[((oy + PAD) * p.EW + ox + PAD) * p.ldx + co];
+                    Y[((long)oh * p.OW + ow) * p.Cout + co] = (T)v;
+                }
             }
         }
     };
 
     const int nchunks = CHUNKED ? p.nchunks : 1;
     for (int chunk = 0; chunk < nchunks; ++chunk) {
-        const int c0 = chunk * p.CC;                       // first expanded channel of the chunk
+        const int c0 = (SPLIT ? (int)blockIdx.y : chunk) * p.CC;   // first expanded channel of the chunk
         const int cw = min(p.CC, p.Cexp - c0);             // its width (a multiple of 16)
         const int kpc = (cw + KG - 1) / KG * KG;           // padded to the k granularity (zeros beyond cw)
 
@@ -359,6 +374,37 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
     }
 }
 
+// y = T( sum_s part[s] + b2 (+ x) ), slices added in index order; 4 consecutive channels per thread.
+template <bool BF16>
+__global__ __launch_bounds__(256) void invres_reduce_kernel(const float* __restrict__ part,
+                                                            const float* __restrict__ b2, const void* __restrict__ xres,
+                                                            void* __restrict__ y, long total, int Cout, int nsplit) {
+    const long i4 = blockIdx.x * 256L + threadIdx.x;
+    if (i4 * 4 >= total) return;
+    float4 a = reinterpret_cast<const float4*>(part)[i4];
+    for (int sp = 1; sp < nsplit; ++sp) {
+        const float4 v = reinterpret_cast<const float4*>(part + (long)sp * total)[i4];
+        a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+    }
+    if (b2) {
+        const float4 bv = *reinterpret_cast<const float4*>(b2 + (int)((i4 * 4) % Cout));
+        a.x += bv.x; a.y += bv.y; a.z += bv.z; a.w += bv.w;
+    }
+    if constexpr (BF16) {
+        if (xres) {
+            const uint2 u = reinterpret_cast<const uint2*>(xres)[i4];
+            a.x += lo_bf16(u.x); a.y += hi_bf16(u.x); a.z += lo_bf16(u.y); a.w += hi_bf16(u.y);
+        }
+        reinterpret_cast<uint2*>(y)[i4] = make_uint2(pack_bf16(a.x, a.y), pack_bf16(a.z, a.w));
+    } else {
+        if (xres) {
+            const float4 u = reinterpret_cast<const float4*>(xres)[i4];
+            a.x += u.x; a.y += u.y; a.z += u.z; a.w += u.w;
+        }
+        reinterpret_cast<float4*>(y)[i4] = a;
+    }
+}
+
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 // Lay out LDS for a tile and a chunk width cc of expanded channels; returns the byte count.
@@ -421,6 +467,9 @@ static size_t plan_tile(InvresParams& p, bool bf16, int stride, int toh, int tow
     return 0;
 }
 
+// Cost of the channel split's reduction pass: a dependent launch, then its traffic at a few TB/s.
+constexpr double kSplitReduceUs = 3.0, kSplitReduceBytesPerUs = 3.0e6;
+
 // Predicted kernel time (microseconds) of a planned tile: a linear model of the work one workgroup
 // does between its barriers, times the number of rounds the launch needs on the chip's 256 compute
 // units.  In the paper's terms the tile size trades the re-computation of E's halo (and, here, the
@@ -430,11 +479,15 @@ static size_t plan_tile(InvresParams& p, bool bf16, int stride, int toh, int tow
 // 3% of the best candidate on every one of them, also when that shape is left out of the fit).
 //   units per workgroup: stage-1 jobs and matrix-instruction steps per wave, stage-2 iterations per
 //   thread (and their taps), stage-3 steps per wave, KB of weights and of the X tile staged, chunks
+//   channel split: every workgroup runs one chunk (its share of the weights), nsplit times as many
+//   workgroups, plus the reduction pass (a dependent launch and (nsplit + 1) passes over the output)
 static double predict_us(const InvresParams& p, bool bf16, int ksize, size_t smem) {
     constexpr int kCus = 256;
     const int kg = bf16 ? 32 : 4, es = bf16 ? 2 : 4;
-    const long wgs = (long)p.N * p.tiles_h * p.tiles_w;
-    const int nch = p.nchunks;
+    const bool split = p.nsplit > 1;
+    const long wgs = (long)p.N * p.tiles_h * p.tiles_w * (split ? p.nsplit : 1);
+    const int nch = split ? 1 : p.nchunks;
+    const double cexp_wg = split ? (double)p.CC : (double)p.Cexp;      // expanded channels a workgroup stages
     auto cdiv = [](long a, long b) { return (a + b - 1) / b; };
     const double s1_jobs = p.mode == 2 ? 0.0 : (double)cdiv((long)(p.PEpad / 16) * (p.CC / 16), kInvresWaves) * nch;
     const double s1_steps = s1_jobs * (p.KP1 / kg);
@@ -444,49 +497,78 @@ static double predict_us(const InvresParams& p, bool bf16, int ksize, size_t sme
     const double s3_steps = p.mode == 1 ? 0.0
                             : (njobs < kInvresWaves ? (double)cdiv(ksteps, p.ksplit) * nch
                                                     : (double)cdiv(njobs, kInvresWaves) * nch * ksteps);
-    const double w_kb = ((p.mode == 2 ? 0.0 : (double)p.Cin * p.Cexp) + (p.mode == 1 ? 0.0 : (double)p.Cexp * p.Cout) +
-                         (double)ksize * ksize * p.Cexp) * es / 1024.0;
-    const double x_kb = (double)p.PE * (p.mode == 2 ? p.Cexp : p.Cin) * es / 1024.0;
+    const double w_kb = ((p.mode == 2 ? 0.0 : (double)p.Cin * cexp_wg) + (p.mode == 1 ? 0.0 : cexp_wg * p.Cout) +
+                         (double)ksize * ksize * cexp_wg) * es / 1024.0;
+    const double x_kb = (double)p.PE * (p.mode == 2 ? cexp_wg : p.Cin) * es / 1024.0;
     const double t_wg = 2.156 + 2.198 * nch + 0.3036 * s1_jobs + 0.0417 * s1_steps + 0.3625 * s2_it +
                         0.0523 * s2_fma + 0.075 * s3_steps + 0.0089 * w_kb + 0.2013 * x_kb;
     // two workgroups share a compute unit when LDS and registers allow (single-chunk kernel, half the
     // LDS) and there are more workgroups than compute units; a shared unit runs each 1.5x slower
     const bool two = wgs > kCus && nch == 1 && smem <= kInvresLdsMax / 2;
     const double rounds = (double)cdiv(wgs, two ? 2 * kCus : kCus);
-    return 1.208 + rounds * (two ? 1.5 : 1.0) * t_wg;
+    double t = 1.208 + rounds * (two ? 1.5 : 1.0) * t_wg;
+    if (split) t += kSplitReduceUs + (double)(p.nsplit + 1) * p.N * p.OH * p.OW * p.Cout * 4.0 / kSplitReduceBytesPerUs;
+    return t;
 }
 
-// tile_cfg: -1 = built-in choice; otherwise index into the candidate list below.
+// tile_cfg: -1 = built-in choice; otherwise tile candidate + 16 * channel-split option.
 static const int kTileCand[][2] = {{2, 14}, {4, 4}, {1, 14}, {2, 2}, {4, 8}, {7, 7}, {2, 8}, {1, 8},
                                    {1, 2}, {2, 4}, {3, 3}, {1, 4}, {2, 3}, {1, 1}, {3, 4}, {2, 7}};
-int fused_invres_num_cfgs() { return (int)(sizeof(kTileCand) / sizeof(kTileCand[0])); }
+constexpr int kNumTiles = (int)(sizeof(kTileCand) / sizeof(kTileCand[0]));
+// channel-split options: 0 = one workgroup per tile, else the widest chunk (expanded channels) a
+// workgroup may take; the chunks are then balanced to multiples of 32
+static const int kSplitCC[] = {0, 32, 64, 96, 128, 192, 256, 384};
+constexpr int kNumSplits = (int)(sizeof(kSplitCC) / sizeof(kSplitCC[0]));
+int fused_invres_num_cfgs() { return kNumTiles * kNumSplits; }
 
-// Fill p's tile fields for tile_cfg (-1: the candidate with the lowest predicted time).  Returns the
-// LDS byte count, 0 when nothing fits; *chosen = the candidate's index, *us = its predicted time.
-static size_t choose_tile(InvresParams& p, bool bf16, int stride, int ksize, int tile_cfg, int* chosen, double* us) {
+// Plan tile candidate `tile` with split option `so`.  Returns the LDS byte count, 0 when it cannot run
+// (does not fit, or the option does not apply: no reduction to split, a single chunk anyway).
+static size_t plan_candidate(InvresParams& p, bool bf16, int stride, int ksize, int tile, int so) {
+    const int toh = kTileCand[tile][0], tow = kTileCand[tile][1];
+    p.nsplit = 1;
+    if (so == 0) return plan_tile(p, bf16, stride, toh, tow, ksize);
+    if (p.mode == 1 || kSplitCC[so] >= p.Cexp) return 0;
+    const int nch = (p.Cexp + kSplitCC[so] - 1) / kSplitCC[so];
+    const int bal = round_up((p.Cexp + nch - 1) / nch, 32);          // <= the option's width
+    const size_t smem = plan_layout(p, bf16, stride, toh, tow, ksize, bal);
+    if (smem > kInvresLdsMax || p.nchunks < 2 || p.nchunks > 65535) return 0;
+    p.nsplit = p.nchunks;
+    return smem;
+}
+
+size_t invres_split_bytes(const InvresParams& p) {
+    return p.nsplit > 1 ? (size_t)p.nsplit * p.N * p.OH * p.OW * p.Cout * sizeof(float) : 0;
+}
+
+// Fill p's tile fields for tile_cfg (-1: the candidate with the lowest predicted time among those whose
+// partials fit ws_bytes of workspace).  Returns the LDS byte count, 0 when nothing fits; *chosen = the
+// candidate's index, *us = its predicted time.
+static size_t choose_tile(InvresParams& p, bool bf16, int stride, int ksize, int tile_cfg, size_t ws_bytes,
+                          int* chosen, double* us) {
     int best = -1;
     double best_us = 0.0;
     if (tile_cfg >= 0 && tile_cfg < fused_invres_num_cfgs()) {
         best = tile_cfg;
     } else {
         for (int c = 0; c < fused_invres_num_cfgs(); ++c) {
-            const size_t sz = plan_tile(p, bf16, stride, kTileCand[c][0], kTileCand[c][1], ksize);
-            if (sz == 0) continue;
+            const size_t sz = plan_candidate(p, bf16, stride, ksize, c % kNumTiles, c / kNumTiles);
+            if (sz == 0 || invres_split_bytes(p) > ws_bytes) continue;
             const double t = predict_us(p, bf16, ksize, sz);
             if (best < 0 || t < best_us) { best = c; best_us = t; }
         }
         if (best < 0) return 0;
     }
-    const size_t smem = plan_tile(p, bf16, stride, kTileCand[best][0], kTileCand[best][1], ksize);
-    if (smem == 0) return 0;
+    const size_t smem = plan_candidate(p, bf16, stride, ksize, best % kNumTiles, best / kNumTiles);
+    if (smem == 0 || invres_split_bytes(p) > ws_bytes) return 0;
     if (chosen) *chosen = best;
     if (us) *us = predict_us(p, bf16, ksize, smem);
     return smem;
 }
 
-// Host-only query of the plan a launch would use (no GPU call).
+// Host-only query of the plan a launch would use with ws_bytes of workspace (no GPU call).
+// out: config, tile rows, tile columns, chunks per workgroup, chunk width, LDS bytes, workgroups per tile
 int fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize, bool bf16,
-                      int tile_cfg, int mode, int out[6], float* predicted_us) {
+                      int tile_cfg, int mode, size_t ws_bytes, int out[7], float* predicted_us) {
     if ((ksize != 3 && ksize != 5) || (stride != 1 && stride != 2)) return -1;
     InvresParams p = {};
     p.mode = mode;
@@ -494,30 +576,45 @@ int fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cout, int stri
     p.OH = (H - 1) / stride + 1; p.OW = (W - 1) / stride + 1;
     int chosen = -1;
     double us = 0.0;
-    const size_t smem = choose_tile(p, bf16, stride, ksize, tile_cfg, &chosen, &us);
+    const size_t smem = choose_tile(p, bf16, stride, ksize, tile_cfg, ws_bytes, &chosen, &us);
     if (smem == 0) return -1;
-    out[0] = chosen; out[1] = p.TOH; out[2] = p.TOW; out[3] = p.nchunks; out[4] = p.CC; out[5] = (int)smem;
+    out[0] = chosen; out[1] = p.TOH; out[2] = p.TOW; out[3] = p.nsplit > 1 ? 1 : p.nchunks; out[4] = p.CC;
+    out[5] = (int)smem; out[6] = p.nsplit;
     if (predicted_us) *predicted_us = (float)us;
     return 0;
+}
+
+// Workspace the preferred plan needs (0 when it does not split the expanded channels).
+size_t fused_invres_workspace(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize, bool bf16,
+                              int tile_cfg, int mode) {
+    if ((ksize != 3 && ksize != 5) || (stride != 1 && stride != 2)) return 0;
+    InvresParams p = {};
+    p.mode = mode;
+    p.N = N; p.H = H; p.W = W; p.Cin = Cin; p.Cexp = Cexp; p.Cout = Cout;
+    p.OH = (H - 1) / stride + 1; p.OW = (W - 1) / stride + 1;
+    if (choose_tile(p, bf16, stride, ksize, tile_cfg, ~(size_t)0, nullptr, nullptr) == 0) return 0;
+    return invres_split_bytes(p);
 }
 
 hipError_t fused_invres(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
                         const void* w2, const float* b2, void* y, int N, int H, int W, int Cin,
                         int Cexp, int Cout, int stride, int residual, bool bf16, int tile_cfg,
-                        hipStream_t s, int mode, int ksize) {
+                        hipStream_t s, int mode, int ksize, void* workspace, size_t ws_bytes) {
     if (ksize != 3 && ksize != 5) return hipErrorInvalidValue;
     InvresParams p;
     p.mode = mode;
     p.x = x; p.w1 = w1; p.b1 = b1; p.wd = wd; p.bd = bd; p.w2 = w2; p.b2 = b2; p.y = y;
     p.N = N; p.H = H; p.W = W; p.Cin = Cin; p.Cexp = Cexp; p.Cout = Cout;
     p.OH = (H - 1) / stride + 1; p.OW = (W - 1) / stride + 1; p.residual = residual;
+    p.nsplit = 1; p.part = static_cast<float*>(workspace);
     constexpr size_t kLdsMax = kInvresLdsMax;
-    const size_t smem = choose_tile(p, bf16, stride, ksize, tile_cfg, nullptr, nullptr);
+    const size_t smem = choose_tile(p, bf16, stride, ksize, tile_cfg, workspace ? ws_bytes : 0, nullptr, nullptr);
     if (smem == 0) return hipErrorInvalidValue;
-    const unsigned grid = (unsigned)(N * p.tiles_h * p.tiles_w);
-#define AGO_LAUNCH_INVRES_KC(BF, ST, KS, CH)                                                                      \
+    const bool split = p.nsplit > 1;
+    const dim3 grid((unsigned)(N * p.tiles_h * p.tiles_w), (unsigned)p.nsplit);
+#define AGO_LAUNCH_INVRES_KC(BF, ST, KS, CH, SP)                                                        \
     do {                                                                                                \
-        auto kern = fused_invres_kernel<BF, ST, KS, CH>;                                                       \
+        auto kern = fused_invres_kernel<BF, ST, KS, CH, SP>;                                            \
         static bool attr_set = false;                                                                   \
         if (!attr_set) {                                                                                \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                     \
@@ -526,13 +623,15 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
             attr_set = true;                                                                            \
         }                                                                                               \
         prof_start(0, s);                                                                               \
-        prof_shape(0, grid, kInvresThreads);                                                            \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kInvresThreads), smem, s, p);                                    \
+        prof_shape(0, grid.x * grid.y, kInvresThreads);                                                 \
+        hipLaunchKernelGGL(kern, grid, dim3(kInvresThreads), smem, s, p);                               \
         prof_stop(0, s);                                                                                \
     } while (0)
 #define AGO_LAUNCH_INVRES_K(BF, ST, KS)                                                                 \
     do {                                                                                                \
-        if (p.nchunks == 1) AGO_LAUNCH_INVRES_KC(BF, ST, KS, false); else AGO_LAUNCH_INVRES_KC(BF, ST, KS, true); \
+        if (split) AGO_LAUNCH_INVRES_KC(BF, ST, KS, false, true);                                       \
+        else if (p.nchunks == 1) AGO_LAUNCH_INVRES_KC(BF, ST, KS, false, false);                        \
+        else AGO_LAUNCH_INVRES_KC(BF, ST, KS, true, false);                                             \
     } while (0)
 #define AGO_LAUNCH_INVRES(BF, ST)                                                                       \
     do {                                                                                                \
@@ -543,6 +642,17 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
 #undef AGO_LAUNCH_INVRES
 #undef AGO_LAUNCH_INVRES_K
 #undef AGO_LAUNCH_INVRES_KC
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !split) return e;
+    // sum the partial projections; b2 and the residual were left to this pass
+    const long total = (long)N * p.OH * p.OW * Cout;
+    const unsigned rgrid = (unsigned)((total / 4 + 255) / 256);
+    if (bf16)
+        hipLaunchKernelGGL(invres_reduce_kernel<true>, dim3(rgrid), dim3(256), 0, s, p.part, b2, residual ? x : nullptr, y,
+                           total, Cout, p.nsplit);
+    else
+        hipLaunchKernelGGL(invres_reduce_kernel<false>, dim3(rgrid), dim3(256), 0, s, p.part, b2, residual ? x : nullptr, y,
+                           total, Cout, p.nsplit);
     return hipGetLastError();
 }
 

@@ -12,6 +12,8 @@ int fused_ffn_num_cfgs();
 int fused_attn_num_cfgs();
 int fused_ffn_pick_cfg(int M, int K, int F, int K2, int tile_cfg);
 int fused_ffn_nsplit(int cfg, int F);
+size_t fused_invres_workspace(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize, bool bf16,
+                              int tile_cfg, int mode);
 
 static int g_tile_cfg[4] = {-1, -1, -1, -1};
 
@@ -139,6 +141,16 @@ size_t workspace_bytes(int op, const int* d, int nd, int dt) {
         if (d[i] <= 0) return 0;
     const size_t es = dt == AGO_BF16 ? 2 : 4;
     switch (op) {
+        case AGO_OP_FUSED_INVRES: {       // dims N, H, W, Cin, Cexp, Cout, stride [, depthwise size]: channel-split partials
+            if (nd < 7 || d[3] % 8 || d[4] % 16 || d[5] % 8) return 0;
+            return fused_invres_workspace(d[0], d[1], d[2], d[3], d[4], d[5], d[6], nd > 7 ? d[7] : 3, dt == AGO_BF16,
+                                          g_tile_cfg[AGO_OP_FUSED_INVRES], 0);
+        }
+        case AGO_OP_FUSED_DW_PW: {        // dims N, H, W, C, Cout, stride
+            if (nd < 6 || d[3] % 16 || d[4] % 8) return 0;
+            return fused_invres_workspace(d[0], d[1], d[2], 8, d[3], d[4], d[5], 3, dt == AGO_BF16,
+                                          g_tile_cfg[AGO_OP_FUSED_INVRES], 2);
+        }
         case AGO_OP_FUSED_PW_PW: {        // dims N, H, W, Cin, Cmid, Cout: the FFN kernel on M = N H W rows
             if (nd < 6) return 0;
             const long long m = (long long)d[0] * d[1] * d[2];

@@ -31,12 +31,15 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
                         const void* w2, const float* b2, void* y, int N, int H, int W, int Cin,
                         int Cexp, int Cout, int stride, int residual, bool bf16, int tile_cfg,
                         hipStream_t s, int mode = 0,    // mode 1: pw -> dw (y = D), mode 2: dw -> pw (x = E)
-                        int ksize = 3);                 // depthwise kernel size, 3 or 5
+                        int ksize = 3,                  // depthwise kernel size, 3 or 5
+                        void* workspace = nullptr, size_t ws_bytes = 0);   // enables the channel split
 hipError_t fused_qkv(const void* x, const void* wq, const void* wk, const void* wv, const float* bq,
                      const float* bk, const float* bv, void* q, void* k, void* v, int B, int S, int K, int Hh,
                      int D, int head_major, hipStream_t s);
 int fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize, bool bf16,
-                      int tile_cfg, int mode, int out[6], float* predicted_us);
+                      int tile_cfg, int mode, size_t ws_bytes, int out[7], float* predicted_us);
+size_t fused_invres_workspace(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize, bool bf16,
+                              int tile_cfg, int mode);
 hipError_t fused_conv_chain(const void* x, const void* wa, const float* ba, const void* wb,
                             const float* bb, void* y, int N, int H, int W, int residual, int tile_cfg,
                             hipStream_t s);

@@ -245,6 +245,11 @@ class Executor:
     def _new(self, i):
         return self.torch.empty(self.shapes[i], dtype=self.td, device=self.device)
 
+    def _workspace(self, op, dims, dt):
+        """Scratch the library asks for (cross-workgroup partial results), or None."""
+        nbytes = self.ago.workspace_bytes(op, [int(d) for d in dims], dt)
+        return self.torch.empty(max(nbytes, 16), dtype=self.torch.uint8, device=self.device) if nbytes else None
+
     def _bias_of(self, nodes, after):
         """The bias that directly follows position `after` in a matched chain, or None."""
         if after + 1 < len(nodes) and nodes[after + 1].op == "bias":
@@ -278,8 +283,10 @@ class Executor:
                 residual = any(n.op == "add" for n in nodes)
                 stride = nodes[pos[1]].attrs.get("stride", 1)
                 fn = ago.ago_fused_invres if wd.shape[0] == 3 else ago.ago_fused_invres_k
+                dt = ago.BF16 if x.dtype == self.torch.bfloat16 else ago.F32
+                ws = self._workspace(ago.OP_FUSED_INVRES, list(x.shape) + [w1.shape[1], w2.shape[1], stride, wd.shape[0]], dt)
                 fn(x, w1, self._bias_of(nodes, pos[0]), wd, self._bias_of(nodes, pos[1]), w2,
-                   self._bias_of(nodes, pos[2]), out, stride, residual)
+                   self._bias_of(nodes, pos[2]), out, stride, residual, ws)
             elif kind == "pw_dw":
                 pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
                 ago.ago_fused_pw_dw(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]),
@@ -287,9 +294,12 @@ class Executor:
                                     nodes[pos[1]].attrs.get("stride", 1))
             elif kind == "dw_pw":
                 pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
+                dt = ago.BF16 if x.dtype == self.torch.bfloat16 else ago.F32
+                w2 = P[nodes[pos[1]].attrs["w"]]
+                ws = self._workspace(ago.OP_FUSED_DW_PW, list(x.shape) + [w2.shape[1], nodes[pos[0]].attrs.get("stride", 1)], dt)
                 ago.ago_fused_dw_pw(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]),
-                                    P[nodes[pos[1]].attrs["w"]], self._bias_of(nodes, pos[1]), out,
-                                    nodes[pos[0]].attrs.get("stride", 1))
+                                    w2, self._bias_of(nodes, pos[1]), out,
+                                    nodes[pos[0]].attrs.get("stride", 1), ws)
             elif kind == "conv_chain":
                 pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
                 ago.ago_fused_conv_chain(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]),
@@ -299,8 +309,7 @@ class Executor:
                 pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
                 act = next(n.op for n in nodes if n.op in _ACT_OF)
                 w1, w2 = P[nodes[pos[0]].attrs["w"]], P[nodes[pos[1]].attrs["w"]]
-                nbytes = ago.workspace_bytes(ago.OP_FUSED_FFN, [x.shape[0], x.shape[1], w1.shape[1], w2.shape[1]], ago.BF16)
-                ws = self.torch.empty(max(nbytes, 16), dtype=self.torch.uint8, device=self.device) if nbytes else None
+                ws = self._workspace(ago.OP_FUSED_FFN, [x.shape[0], x.shape[1], w1.shape[1], w2.shape[1]], ago.BF16)
                 ago.ago_fused_ffn(x, w1, self._bias_of(nodes, pos[0]), w2, self._bias_of(nodes, pos[1]), out,
                                   getattr(ago, _ACT_OF[act]), ws)
             elif kind == "attn":

@@ -31,7 +31,7 @@ def to_device(case, device="cuda:0"):
 def _dims(case):
     k = type(case).__name__
     if k == "InvresCase":
-        return [case.N, case.H, case.W, case.Cin, case.Cexp, case.Cout, case.stride]
+        return [case.N, case.H, case.W, case.Cin, case.Cexp, case.Cout, case.stride, case.ksize]
     if k == "ChainCase":
         return [case.N, case.H, case.W, case.C]
     if k == "FfnCase":
@@ -66,9 +66,13 @@ def alloc_workspace(case, fused=True, device="cuda:0"):
     if type(case).__name__ == "QkvCase":
         return None
     if type(case).__name__ == "PairCase":
-        if case.kind != "pw_pw" or not fused:
+        if not fused or case.kind not in ("pw_pw", "dw_pw"):
             return None
-        n = ago.workspace_bytes(ago.OP_FUSED_PW_PW, [case.N, case.H, case.W, case.C1, case.C2, case.C3], ago.BF16)
+        if case.kind == "dw_pw":
+            n = ago.workspace_bytes(ago.OP_FUSED_DW_PW, [case.N, case.H, case.W, case.C1, case.C2, case.stride],
+                                    ago.BF16 if case.dtype == "bf16" else ago.F32)
+        else:
+            n = ago.workspace_bytes(ago.OP_FUSED_PW_PW, [case.N, case.H, case.W, case.C1, case.C2, case.C3], ago.BF16)
         return torch.empty(max(n, 16), dtype=torch.uint8, device=device) if n > 0 else None
     op = _FUSED_OP[type(case).__name__] + (0 if fused else 4)
     n = ago.workspace_bytes(op, _dims(case), ago.BF16 if case.dtype == "bf16" else ago.F32)

@@ -280,6 +280,27 @@ def test_invres_plan_is_a_host_query(lib):
         assert (forced["config"], forced["tile_h"], forced["tile_w"]) == (5, 7, 7)
     finally:
         ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
+    # channel split: a wide block on one image asks for a workspace and, given it, spreads its chunks over
+    # workgroups (one chunk each); with less workspace than that it keeps the one-workgroup-per-tile plan
+    dims = [1, 7, 7, 160, 960, 160, 1, 3]
+    need = ago.workspace_bytes(ago.OP_FUSED_INVRES, dims, ago.BF16)
+    split = ago.fused_invres_plan(*dims, ago.BF16, need)
+    assert split["split"] > 1 and split["chunks"] == 1 and need == split["split"] * 49 * 160 * 4
+    assert split["split"] * split["chunk_channels"] >= 960 and split["chunk_channels"] % 32 == 0
+    whole = ago.fused_invres_plan(*dims, ago.BF16, need - 1)
+    assert whole["split"] < split["split"] and whole["predicted_us"] >= split["predicted_us"]
+    assert ago.fused_invres_plan(*dims, ago.BF16, 0)["split"] == 1
+    assert ago.workspace_bytes(ago.OP_FUSED_INVRES, [1, 14, 14, 32, 192, 32, 1], ago.F32) == 0      # narrow: no split
+    assert ago.workspace_bytes(ago.OP_FUSED_INVRES, [512, 7, 7, 160, 960, 160, 1], ago.BF16) == 0   # chip already full
+    assert ago.workspace_bytes(ago.OP_FUSED_DW_PW, [1, 7, 7, 960, 160, 1], ago.BF16) > 0
+    try:                                                                  # explicit: tile 13 (1x1) + 16 * option 2 (64 wide)
+        assert ago.set_tile_config(ago.OP_FUSED_INVRES, 16 * 2 + 13) == 0
+        forced = ago.fused_invres_plan(*dims, ago.BF16, 1 << 30)
+        assert (forced["tile_h"], forced["tile_w"], forced["chunk_channels"], forced["split"]) == (1, 1, 64, 15)
+        with pytest.raises(ago.AgoError):
+            ago.fused_invres_plan(*dims, ago.BF16, 0)                     # that configuration needs the workspace
+    finally:
+        ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
     with pytest.raises(ago.AgoError):
         ago.fused_invres_plan(1, 14, 14, 32, 192, 32, 1, 4, ago.F32)       # depthwise size
     with pytest.raises(ago.AgoError):

@@ -212,10 +212,57 @@ def test_invres_expanded_channels_in_chunks(gpu, oracle):
             ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
 
 
+def test_invres_channel_split(gpu, oracle):
+    """Wide blocks on few pixels with a workspace: the chunks of expanded channels go to different
+    workgroups, fp32 partials are summed by a second kernel (with b2 and the residual).  The built-in
+    plan (which must split these shapes), explicit split configurations, and the same call without
+    workspace (one workgroup walks the chunks) all agree with the oracle."""
+    torch, ago, runner = gpu
+    cases = [wl.InvresCase(1, 7, 7, 160, 960, 160, 1, True, True, "bf16", 6600, name="split_960_bf16_res"),
+             wl.InvresCase(1, 7, 7, 160, 960, 320, 1, False, True, "bf16", 6601, name="split_960_320"),
+             wl.InvresCase(2, 14, 14, 96, 576, 96, 1, True, True, "f32", 6602, name="split_576_f32_res"),
+             wl.InvresCase(1, 14, 14, 112, 672, 160, 2, False, True, "bf16", 6603, name="split5_672_s2", ksize=5),
+             wl.InvresCase(1, 9, 7, 160, 944, 320, 1, False, False, "bf16", 6604, name="split_944_ragged_chunk"),
+             wl.InvresCase(1, 5, 3, 64, 400, 64, 1, True, True, "f32", 6605, name="split_400_f32_ragged"),
+             wl.PairCase("dw_pw", 1, 7, 7, 960, 160, stride=1, dtype="bf16", seed=6606, name="split_dw_pw_960"),
+             wl.PairCase("dw_pw", 1, 9, 9, 576, 96, stride=2, dtype="f32", seed=6607, name="split_dw_pw_576_f32_s2")]
+    for case in cases:
+        ref = oracle.run_case(case)
+        t = runner.to_device(case)
+        ws = runner.alloc_workspace(case, fused=True)
+        assert ws is not None, "%s: the built-in plan should ask for a workspace" % case.name
+        big = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")      # enough for any explicit split
+        try:
+            ran = 0
+            for cfg, w in ((-1, ws), (-1, None), (16 * 1 + 13, big), (16 * 2 + 3, big), (16 * 4 + 5, big), (16 * 6 + 1, big)):
+                ago.set_tile_config(ago.OP_FUSED_INVRES, cfg)
+                y = runner.alloc_output(case)
+                y.fill_(7.0)
+                try:
+                    runner.run_fused(case, t, y, w)
+                except ago.AgoError as e:
+                    assert cfg >= 0 and e.status == 5, e      # an explicit configuration that cannot run
+                    continue
+                ran += 1
+                torch.cuda.synchronize()
+                assert_close(runner.to_numpy64(y), ref, case.dtype, "%s cfg %d ws %s" % (case.name, cfg, w is not None))
+            assert ran >= 3, case.name
+        finally:
+            ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
+    # the plan query reports the split, and falls back when the workspace is too small
+    if True:
+        full = ago.fused_invres_plan(1, 7, 7, 160, 960, 160, 1, 3, ago.BF16, 1 << 30)
+        none = ago.fused_invres_plan(1, 7, 7, 160, 960, 160, 1, 3, ago.BF16, 0)
+        assert full["split"] > 1 and full["chunks"] == 1 and none["split"] == 1 and none["chunks"] > 1
+        need = ago.workspace_bytes(ago.OP_FUSED_INVRES, [1, 7, 7, 160, 960, 160, 1, 3], ago.BF16)
+        assert need == full["split"] * 7 * 7 * 160 * 4
+        assert ago.fused_invres_plan(1, 7, 7, 160, 960, 160, 1, 3, ago.BF16, need - 4)["split"] != full["split"]
+
+
 def test_invres_planner_choice_is_near_the_best_candidate(gpu):
     """The built-in tile choice (cost model) is timed against every selectable tile on three shapes the
     model was not tuned for one by one: a latency-bound single image, a batch that fills the chip several
-    times over, and a chunked wide block."""
+    times over, a chunked wide block, and a wide block on one image (channel split, with workspace)."""
     torch, ago, runner = gpu
 
     def us(fn, n=40):
@@ -232,15 +279,17 @@ def test_invres_planner_choice_is_near_the_best_candidate(gpu):
 
     for case in (wl.InvresCase(1, 28, 28, 24, 144, 24, 1, True, True, "bf16", 6500, name="plan_single"),
                  wl.InvresCase(16, 28, 28, 32, 192, 48, 1, False, True, "bf16", 6501, name="plan_batch16"),
-                 wl.InvresCase(8, 14, 14, 80, 480, 112, 1, False, True, "bf16", 6502, name="plan_wide")):
+                 wl.InvresCase(8, 14, 14, 80, 480, 112, 1, False, True, "bf16", 6502, name="plan_wide"),
+                 wl.InvresCase(1, 7, 7, 160, 960, 160, 1, True, True, "bf16", 6503, name="plan_split")):
         t = runner.to_device(case)
         y = runner.alloc_output(case)
+        ws = torch.empty(32 << 20, dtype=torch.uint8, device="cuda:0")
         times = {}
         try:
             for cfg in [-1] + list(range(ago.num_tile_configs(ago.OP_FUSED_INVRES))):
                 ago.set_tile_config(ago.OP_FUSED_INVRES, cfg)
                 try:
-                    fn = runner.prepare_fused(case, t, y)
+                    fn = runner.prepare_fused(case, t, y, ws)
                     fn()
                 except ago.AgoError:
                     continue

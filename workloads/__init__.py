@@ -9,11 +9,11 @@ from it without sharing any part of the method.
 from .rng import uniform, normal, round_to_bf16, bf16_bits, bf16_from_bits
 from .configs import (
     InvresCase, ChainCase, FfnCase, AttnCase, PairCase, QkvCase,
-    baseline_case, BASELINE_NAMES, small_cases, pair_cases,
+    baseline_case, BASELINE_NAMES, small_cases, pair_cases, network_block_cases,
 )
 
 __all__ = [
     "uniform", "normal", "round_to_bf16", "bf16_bits", "bf16_from_bits",
     "InvresCase", "ChainCase", "FfnCase", "AttnCase", "PairCase", "QkvCase",
-    "baseline_case", "BASELINE_NAMES", "small_cases", "pair_cases",
+    "baseline_case", "BASELINE_NAMES", "small_cases", "pair_cases", "network_block_cases",
 ]

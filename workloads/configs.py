@@ -308,6 +308,19 @@ def pair_cases():
     ]
 
 
+def network_block_cases(batch=1, dtype="bf16"):
+    """Inverted-residual blocks with the layer shapes of a MobileNetV2-style network (expansion 6, 224 x 224
+    input; the paper's Sec. VI evaluates whole networks of this family): one block per distinct
+    (resolution, channels, stride), from the 112 x 112 x 16 stage down to the 7 x 7 x 960-wide blocks."""
+    s = _SEED0 + 3000
+    shapes = [(112, 16, 96, 24, 2), (56, 24, 144, 24, 1), (56, 24, 144, 32, 2), (28, 32, 192, 32, 1),
+              (28, 32, 192, 64, 2), (14, 64, 384, 64, 1), (14, 64, 384, 96, 1), (14, 96, 576, 96, 1),
+              (14, 96, 576, 160, 2), (7, 160, 960, 160, 1), (7, 160, 960, 320, 1)]
+    return [InvresCase(batch, hw, hw, ci, ce, co, st, st == 1 and ci == co, True, dtype, s + 16 * i,
+                       name="block_%dx%dx%d_%d_%d_s%d" % (hw, hw, ci, ce, co, st))
+            for i, (hw, ci, ce, co, st) in enumerate(shapes)]
+
+
 def small_cases():
     """Reduced-size variants: several tiles plus a ragged tail, seconds for the oracle."""
     s = _SEED0 + 1000
