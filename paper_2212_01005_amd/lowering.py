@@ -322,6 +322,22 @@ class Executor:
         cons = g.consumers()
         return {i: val[i] for i in range(len(g.nodes)) if not cons[i] and g.nodes[i].op != "input"}
 
+    def capture(self, example_inputs):
+        """Record one pass of the plan into a HIP graph: a plan of small kernels (a network at batch 1 is a
+        few microseconds per launch) is bound by launch overhead, and a replay issues all of them with one call.
+        Returns (replay, inputs, outputs): copy new data into ``inputs[name]`` (static buffers), call
+        ``replay()``, read ``outputs`` (the same dict ``run`` returns, static buffers as well).  One eager
+        pass runs first so that one-time set-up (function attributes) stays out of the capture."""
+        torch = self.torch
+        static_in = {k: v.clone() for k, v in example_inputs.items()}
+        self.run(static_in)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            static_out = self.run(static_in)
+        self._graph = graph                # keeps the graph (and its memory pool) alive with the executor
+        return graph.replay, static_in, static_out
+
     def _single(self, n, i, val, out):
         ago, P = self.ago, self.g.params
         a = val[n.inputs[0]]
