@@ -318,42 +318,45 @@ def main():
     # recorded into a HIP graph, so the figures are kernel time, not Python launch overhead
     network = None
     if not args.no_detail and not args.no_cold and args.only < 0:
-        import numpy as np
-        from paper_2212_01005_amd import lowering as L
-        g = L.Graph([], {}, "bf16")
-        cur, cin, seed = g.add("input", name="x", shape=(1, 112, 112, 16)), 16, 22120100 + 5000
+        try:                                   # an auxiliary figure must never cost the headline line
+            import numpy as np
+            from paper_2212_01005_amd import lowering as L
+            g = L.Graph([], {}, "bf16")
+            cur, cin, seed = g.add("input", name="x", shape=(1, 112, 112, 16)), 16, 22120100 + 5000
 
-        def dev_param(name, shape, sigma, bias=False):
-            nonlocal seed
-            seed += 1
-            v = torch.from_numpy(np.ascontiguousarray(wl.normal(seed, shape, sigma), dtype=np.float32)).to("cuda:0")
-            g.params[name] = v if bias else v.to(torch.bfloat16)
-            return name
+            def dev_param(name, shape, sigma, bias=False):
+                nonlocal seed
+                seed += 1
+                v = torch.from_numpy(np.ascontiguousarray(wl.normal(seed, shape, sigma), dtype=np.float32)).to("cuda:0")
+                g.params[name] = v if bias else v.to(torch.bfloat16)
+                return name
 
-        bi = 0
-        for cout, reps, stride in ((24, 2, 2), (32, 3, 2), (64, 4, 2), (96, 3, 1), (160, 3, 2), (320, 1, 1)):
-            for r in range(reps):
-                st, cexp, src = (stride if r == 0 else 1), 6 * cin, cur
-                cur = g.add("conv1x1", [cur], w=dev_param("w1_%d" % bi, (cin, cexp), cin ** -0.5))
-                cur = g.add("bias", [cur], b=dev_param("b1_%d" % bi, (cexp,), 0.1, True))
-                cur = g.add("relu6", [cur])
-                cur = g.add("dwconv", [cur], w=dev_param("wd_%d" % bi, (3, 3, cexp), 1.0 / 3), stride=st)
-                cur = g.add("bias", [cur], b=dev_param("bd_%d" % bi, (cexp,), 0.1, True))
-                cur = g.add("relu6", [cur])
-                cur = g.add("conv1x1", [cur], w=dev_param("w2_%d" % bi, (cexp, cout), cexp ** -0.5))
-                cur = g.add("bias", [cur], b=dev_param("b2_%d" % bi, (cout,), 0.1, True))
-                if st == 1 and cin == cout:
-                    cur = g.add("add", [cur, src])
-                cin, bi = cout, bi + 1
-        x = torch.from_numpy(np.ascontiguousarray(wl.uniform(seed + 1, (1, 112, 112, 16), -1.0, 1.0),
-                                                  dtype=np.float32)).to("cuda:0").to(torch.bfloat16)
-        network = {"blocks": bi, "operators": len(g.nodes) - 1}
-        for key, part in (("fused", L.partition(g, ago)[0]), ("per_op", list(range(len(g.nodes))))):
-            ex = L.Executor(g, L.lower(g, part), ago, torch)
-            replay, _, _ = ex.capture({"x": x})
-            network[key + "_launches"] = len(ex.plan)
-            network[key + "_graph_us"] = round(time_us(replay, args.detail_iters), 1)
-        network["speedup"] = round(network["per_op_graph_us"] / network["fused_graph_us"], 2)
+            bi = 0
+            for cout, reps, stride in ((24, 2, 2), (32, 3, 2), (64, 4, 2), (96, 3, 1), (160, 3, 2), (320, 1, 1)):
+                for r in range(reps):
+                    st, cexp, src = (stride if r == 0 else 1), 6 * cin, cur
+                    cur = g.add("conv1x1", [cur], w=dev_param("w1_%d" % bi, (cin, cexp), cin ** -0.5))
+                    cur = g.add("bias", [cur], b=dev_param("b1_%d" % bi, (cexp,), 0.1, True))
+                    cur = g.add("relu6", [cur])
+                    cur = g.add("dwconv", [cur], w=dev_param("wd_%d" % bi, (3, 3, cexp), 1.0 / 3), stride=st)
+                    cur = g.add("bias", [cur], b=dev_param("bd_%d" % bi, (cexp,), 0.1, True))
+                    cur = g.add("relu6", [cur])
+                    cur = g.add("conv1x1", [cur], w=dev_param("w2_%d" % bi, (cexp, cout), cexp ** -0.5))
+                    cur = g.add("bias", [cur], b=dev_param("b2_%d" % bi, (cout,), 0.1, True))
+                    if st == 1 and cin == cout:
+                        cur = g.add("add", [cur, src])
+                    cin, bi = cout, bi + 1
+            x = torch.from_numpy(np.ascontiguousarray(wl.uniform(seed + 1, (1, 112, 112, 16), -1.0, 1.0),
+                                                      dtype=np.float32)).to("cuda:0").to(torch.bfloat16)
+            network = {"blocks": bi, "operators": len(g.nodes) - 1}
+            for key, part in (("fused", L.partition(g, ago)[0]), ("per_op", list(range(len(g.nodes))))):
+                ex = L.Executor(g, L.lower(g, part), ago, torch)
+                replay, _, _ = ex.capture({"x": x})
+                network[key + "_launches"] = len(ex.plan)
+                network[key + "_graph_us"] = round(time_us(replay, args.detail_iters), 1)
+            network["speedup"] = round(network["per_op_graph_us"] / network["fused_graph_us"], 2)
+        except Exception as e:                 # noqa: BLE001
+            network = {"error": "%s: %s" % (type(e).__name__, e)}
 
     # ---- CPU baseline: the oracle as it stands, on the host cores ---------------------------
     cpu = None
