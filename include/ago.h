@@ -118,7 +118,9 @@ ago_status ago_fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cou
  *   ago_fused_dw_pw   y = relu6(dw3x3(x, wd, stride) + bd) * w2 + b2                (Fig. 7b)
  *                     x:[N,H,W,C] wd:[3,3,C] w2:[C,Cout] y:[N,OH,OW,Cout].  C % 16 == 0, Cout % 8 == 0.
  *                     Optional workspace as for ago_fused_invres, size from
- *                     ago_workspace_bytes(AGO_OP_FUSED_DW_PW, {N,H,W,C,Cout,stride}).
+ *                     ago_workspace_bytes(AGO_OP_FUSED_DW_PW, {N,H,W,C,Cout,stride[,ksize]}).
+ *   ago_fused_pw_dw_k, ago_fused_dw_pw_k   the same two pairs with a ksize x ksize depthwise (3 or 5,
+ *                     zero padding (ksize-1)/2, wd:[ksize,ksize,C]): the pairs of the 5x5 blocks.
  *   ago_fused_dw_dw   y = relu6(dw3x3(relu6(dw3x3(x, wa, stride) + ba), wb, 1) + bb)  (Fig. 7a twice)
  *                     x:[N,H,W,C] wa,wb:[3,3,C] y:[N,OH,OW,C]; the intermediate is 0 outside its
  *                     image.  C % 4 == 0.  Vector ALUs only.
@@ -131,6 +133,14 @@ ago_status ago_fused_pw_dw(const void* x, const void* w1, const float* b1,
                            const void* wd, const float* bd, void* y,
                            int N, int H, int W, int Cin, int Cexp, int stride, ago_dtype dt,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
+ago_status ago_fused_pw_dw_k(const void* x, const void* w1, const float* b1,
+                             const void* wd, const float* bd, void* y,
+                             int N, int H, int W, int Cin, int Cexp, int stride, int ksize, ago_dtype dt,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+ago_status ago_fused_dw_pw_k(const void* x, const void* wd, const float* bd,
+                             const void* w2, const float* b2, void* y,
+                             int N, int H, int W, int C, int Cout, int stride, int ksize, ago_dtype dt,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
 ago_status ago_fused_dw_pw(const void* x, const void* wd, const float* bd,
                            const void* w2, const float* b2, void* y,
                            int N, int H, int W, int C, int Cout, int stride, ago_dtype dt,

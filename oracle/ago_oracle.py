@@ -250,21 +250,26 @@ def qkv(x, wq, wk, wv, bq, bk, bv, batch, heads, head_major=True):
 
 # ---- two-operator pairs (Sec. VI, Fig. 13): the operators above called one after another --------
 
+def _dw(x, wd, stride):
+    """The depthwise of a pair: 3 x 3, or R x R read off the weight's shape (the MNasNet-style 5 x 5)."""
+    return dwconv3x3(x, wd, stride) if wd.shape[0] == 3 else dwconv(x, wd, stride)
+
+
 def pw_dw(x, w1, b1, wd, bd, stride=1):
-    """relu6(dw3x3(relu6(x * w1 + b1)) + bd); the padding of the depthwise pads the activated tensor."""
+    """relu6(dw(relu6(x * w1 + b1)) + bd); the padding of the depthwise pads the activated tensor."""
     e = conv1x1(x, w1)
     if b1 is not None:
         e = bias(e, b1)
     e = relu6(e)
-    d = dwconv3x3(e, wd, stride)
+    d = _dw(e, wd, stride)
     if bd is not None:
         d = bias(d, bd)
     return relu6(d)
 
 
 def dw_pw(x, wd, bd, w2, b2, stride=1):
-    """relu6(dw3x3(x) + bd) * w2 + b2."""
-    d = dwconv3x3(x, wd, stride)
+    """relu6(dw(x) + bd) * w2 + b2."""
+    d = _dw(x, wd, stride)
     if bd is not None:
         d = bias(d, bd)
     y = conv1x1(relu6(d), w2)

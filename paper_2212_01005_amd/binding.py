@@ -39,6 +39,8 @@ _SIGS = {
     "ago_fused_attn_strided": [_vp] * 4 + [_i] * 4 + [ctypes.c_longlong] * 3 + [_f, _i, _vp, _sz, _vp],
     "ago_fused_pw_dw": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
     "ago_fused_dw_pw": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
+    "ago_fused_pw_dw_k": [_vp] * 6 + [_i] * 8 + [_vp, _sz, _vp],
+    "ago_fused_dw_pw_k": [_vp] * 6 + [_i] * 8 + [_vp, _sz, _vp],
     "ago_fused_pw_pw": [_vp] * 6 + [_i] * 8 + [_vp, _sz, _vp],
     "ago_fused_dw_dw": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_gemm": [_vp] * 5 + [_i] * 5 + [_vp],
@@ -318,22 +320,51 @@ def ago_fused_attn_bshd(q, k, v, o, scale, workspace=None):
                                         float(scale), _dt(q), wp, wb, _stream())
 
 
+def _dw_size(wd, want=None):
+    """Depthwise size read off the weight's shape [k, k, C]; `want` fixes it for the 3 x 3 entry points."""
+    if wd.shape[0] != wd.shape[1] or (want is not None and wd.shape[0] != want):
+        raise ValueError("depthwise weight of shape %s" % (tuple(wd.shape),))
+    return int(wd.shape[0])
+
+
 @_entry
 def ago_fused_pw_dw(x, w1, b1, wd, bd, y, stride, workspace=None):
     N, H, W, Cin = x.shape
     Cexp = w1.shape[1]
+    _dw_size(wd, 3)
     wp, wb = _ws(workspace)
     return lib.ago_fused_pw_dw, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(y), N, H, W, Cin, Cexp, stride,
                                  _dt(x), wp, wb, _stream())
 
 
 @_entry
+def ago_fused_pw_dw_k(x, w1, b1, wd, bd, y, stride, workspace=None):
+    """wd: [ksize, ksize, Cexp]; the depthwise size is read off its shape."""
+    N, H, W, Cin = x.shape
+    Cexp = w1.shape[1]
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_pw_dw_k, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(y), N, H, W, Cin, Cexp, stride,
+                                   _dw_size(wd), _dt(x), wp, wb, _stream())
+
+
+@_entry
 def ago_fused_dw_pw(x, wd, bd, w2, b2, y, stride, workspace=None):
     N, H, W, C = x.shape
     Cout = w2.shape[1]
+    _dw_size(wd, 3)
     wp, wb = _ws(workspace)
     return lib.ago_fused_dw_pw, (_p(x), _p(wd), _p(bd), _p(w2), _p(b2), _p(y), N, H, W, C, Cout, stride,
                                  _dt(x), wp, wb, _stream())
+
+
+@_entry
+def ago_fused_dw_pw_k(x, wd, bd, w2, b2, y, stride, workspace=None):
+    """wd: [ksize, ksize, C]; the depthwise size is read off its shape."""
+    N, H, W, C = x.shape
+    Cout = w2.shape[1]
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_dw_pw_k, (_p(x), _p(wd), _p(bd), _p(w2), _p(b2), _p(y), N, H, W, C, Cout, stride,
+                                   _dw_size(wd), _dt(x), wp, wb, _stream())
 
 
 @_entry

@@ -152,25 +152,41 @@ ago_status ago_fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cou
                ? AGO_OK : AGO_ERR_UNSUPPORTED;
 }
 
-ago_status ago_fused_pw_dw(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
-                           void* y, int N, int H, int W, int Cin, int Cexp, int stride, ago_dtype dt,
-                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+ago_status ago_fused_pw_dw_k(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
+                             void* y, int N, int H, int W, int Cin, int Cexp, int stride, int ksize, ago_dtype dt,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
     (void)workspace; (void)workspace_bytes;
     ago_status st = check_pw_dw(x, w1, wd, y, b1, bd, N, H, W, Cin, Cexp, stride, dt);
     if (st != AGO_OK) return st;
+    if (ksize != 3 && ksize != 5) return AGO_ERR_UNSUPPORTED;
     return from_hip(fused_invres(x, w1, b1, wd, bd, nullptr, nullptr, y, N, H, W, Cin, Cexp, 16, stride, 0,
-                                 dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES), as_stream(hip_stream), 1));
+                                 dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES), as_stream(hip_stream), 1, ksize));
+}
+
+ago_status ago_fused_pw_dw(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
+                           void* y, int N, int H, int W, int Cin, int Cexp, int stride, ago_dtype dt,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return ago_fused_pw_dw_k(x, w1, b1, wd, bd, y, N, H, W, Cin, Cexp, stride, 3, dt, workspace, workspace_bytes,
+                             hip_stream);
+}
+
+ago_status ago_fused_dw_pw_k(const void* x, const void* wd, const float* bd, const void* w2, const float* b2,
+                             void* y, int N, int H, int W, int C, int Cout, int stride, int ksize, ago_dtype dt,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+    ago_status st = check_dw_pw(x, wd, w2, y, bd, b2, N, H, W, C, Cout, stride, dt);
+    if (st != AGO_OK) return st;
+    if (ksize != 3 && ksize != 5) return AGO_ERR_UNSUPPORTED;
+    if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return AGO_ERR_ALIGN;
+    return from_hip(fused_invres(x, nullptr, nullptr, wd, bd, w2, b2, y, N, H, W, 8, C, Cout, stride, 0,
+                                 dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES), as_stream(hip_stream), 2, ksize,
+                                 workspace, workspace_bytes));
 }
 
 ago_status ago_fused_dw_pw(const void* x, const void* wd, const float* bd, const void* w2, const float* b2,
                            void* y, int N, int H, int W, int C, int Cout, int stride, ago_dtype dt,
                            void* workspace, size_t workspace_bytes, void* hip_stream) {
-    ago_status st = check_dw_pw(x, wd, w2, y, bd, b2, N, H, W, C, Cout, stride, dt);
-    if (st != AGO_OK) return st;
-    if (workspace && reinterpret_cast<uintptr_t>(workspace) % 16) return AGO_ERR_ALIGN;
-    return from_hip(fused_invres(x, nullptr, nullptr, wd, bd, w2, b2, y, N, H, W, 8, C, Cout, stride, 0,
-                                 dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES), as_stream(hip_stream), 2, 3,
-                                 workspace, workspace_bytes));
+    return ago_fused_dw_pw_k(x, wd, bd, w2, b2, y, N, H, W, C, Cout, stride, 3, dt, workspace, workspace_bytes,
+                             hip_stream);
 }
 
 ago_status ago_fused_dw_dw(const void* x, const void* wa, const float* ba, const void* wb, const float* bb,

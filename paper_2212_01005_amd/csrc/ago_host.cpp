@@ -146,9 +146,9 @@ size_t workspace_bytes(int op, const int* d, int nd, int dt) {
             return fused_invres_workspace(d[0], d[1], d[2], d[3], d[4], d[5], d[6], nd > 7 ? d[7] : 3, dt == AGO_BF16,
                                           g_tile_cfg[AGO_OP_FUSED_INVRES], 0);
         }
-        case AGO_OP_FUSED_DW_PW: {        // dims N, H, W, C, Cout, stride
+        case AGO_OP_FUSED_DW_PW: {        // dims N, H, W, C, Cout, stride [, depthwise size]
             if (nd < 6 || d[3] % 16 || d[4] % 8) return 0;
-            return fused_invres_workspace(d[0], d[1], d[2], 8, d[3], d[4], d[5], 3, dt == AGO_BF16,
+            return fused_invres_workspace(d[0], d[1], d[2], 8, d[3], d[4], d[5], nd > 6 ? d[6] : 3, dt == AGO_BF16,
                                           g_tile_cfg[AGO_OP_FUSED_INVRES], 2);
         }
         case AGO_OP_FUSED_PW_PW: {        // dims N, H, W, Cin, Cmid, Cout: the FFN kernel on M = N H W rows

@@ -289,17 +289,20 @@ class Executor:
                    self._bias_of(nodes, pos[2]), out, stride, residual, ws)
             elif kind == "pw_dw":
                 pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
-                ago.ago_fused_pw_dw(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]),
-                                    P[nodes[pos[1]].attrs["w"]], self._bias_of(nodes, pos[1]), out,
-                                    nodes[pos[1]].attrs.get("stride", 1))
+                wd = P[nodes[pos[1]].attrs["w"]]
+                fn = ago.ago_fused_pw_dw if wd.shape[0] == 3 else ago.ago_fused_pw_dw_k
+                fn(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]), wd, self._bias_of(nodes, pos[1]), out,
+                   nodes[pos[1]].attrs.get("stride", 1))
             elif kind == "dw_pw":
                 pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
                 dt = ago.BF16 if x.dtype == self.torch.bfloat16 else ago.F32
                 w2 = P[nodes[pos[1]].attrs["w"]]
-                ws = self._workspace(ago.OP_FUSED_DW_PW, list(x.shape) + [w2.shape[1], nodes[pos[0]].attrs.get("stride", 1)], dt)
-                ago.ago_fused_dw_pw(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]),
-                                    w2, self._bias_of(nodes, pos[1]), out,
-                                    nodes[pos[0]].attrs.get("stride", 1), ws)
+                wd = P[nodes[pos[0]].attrs["w"]]
+                ws = self._workspace(ago.OP_FUSED_DW_PW,
+                                     list(x.shape) + [w2.shape[1], nodes[pos[0]].attrs.get("stride", 1), wd.shape[0]], dt)
+                fn = ago.ago_fused_dw_pw if wd.shape[0] == 3 else ago.ago_fused_dw_pw_k
+                fn(x, wd, self._bias_of(nodes, pos[0]), w2, self._bias_of(nodes, pos[1]), out,
+                   nodes[pos[0]].attrs.get("stride", 1), ws)
             elif kind == "conv_chain":
                 pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
                 ago.ago_fused_conv_chain(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]),

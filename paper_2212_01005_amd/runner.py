@@ -69,7 +69,7 @@ def alloc_workspace(case, fused=True, device="cuda:0"):
         if not fused or case.kind not in ("pw_pw", "dw_pw"):
             return None
         if case.kind == "dw_pw":
-            n = ago.workspace_bytes(ago.OP_FUSED_DW_PW, [case.N, case.H, case.W, case.C1, case.C2, case.stride],
+            n = ago.workspace_bytes(ago.OP_FUSED_DW_PW, [case.N, case.H, case.W, case.C1, case.C2, case.stride, case.ksize],
                                     ago.BF16 if case.dtype == "bf16" else ago.F32)
         else:
             n = ago.workspace_bytes(ago.OP_FUSED_PW_PW, [case.N, case.H, case.W, case.C1, case.C2, case.C3], ago.BF16)
@@ -86,9 +86,11 @@ def _fused_call(case, t, y, ws):
     k = type(case).__name__
     if k == "PairCase":
         if case.kind == "pw_dw":
-            return ago.ago_fused_pw_dw, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], y, case.stride, ws)
+            fn = ago.ago_fused_pw_dw if case.ksize == 3 else ago.ago_fused_pw_dw_k
+            return fn, (t["x"], t["w1"], t["b1"], t["wd"], t["bd"], y, case.stride, ws)
         if case.kind == "dw_pw":
-            return ago.ago_fused_dw_pw, (t["x"], t["wd"], t["bd"], t["w2"], t["b2"], y, case.stride, ws)
+            fn = ago.ago_fused_dw_pw if case.ksize == 3 else ago.ago_fused_dw_pw_k
+            return fn, (t["x"], t["wd"], t["bd"], t["w2"], t["b2"], y, case.stride, ws)
         if case.kind == "dw_dw":
             return ago.ago_fused_dw_dw, (t["x"], t["wd"], t["bd"], t["wd2"], t["bd2"], y, case.stride, ws)
         return ago.ago_fused_pw_pw, (t["x"], t["w1"], t["b1"], t["w2"], t["b2"], y, _ACT[case.act], ws)

@@ -506,6 +506,30 @@ def test_pair_fused_matches_oracle(gpu, oracle, case):
     assert worst <= 1.5 * RTOL[case.dtype]
 
 
+@pytest.mark.gpu
+def test_pairs_with_a_5x5_depthwise(gpu, oracle):
+    """pw->dw and dw->pw with a 5 x 5 depthwise (`ago_fused_pw_dw_k`, `ago_fused_dw_pw_k`): both dtypes and
+    strides, ragged images, an image smaller than the kernel, a wide dw->pw that takes the channel split."""
+    torch, ago, runner = gpu
+    cases = [wl.PairCase("pw_dw", 1, 14, 14, 40, 240, stride=1, dtype="f32", seed=6700, name="pw_dw5_f32", ksize=5),
+             wl.PairCase("pw_dw", 2, 9, 11, 24, 144, stride=2, dtype="bf16", seed=6701, name="pw_dw5_bf16_s2_ragged", ksize=5),
+             wl.PairCase("pw_dw", 1, 3, 2, 8, 16, stride=1, bias=False, dtype="bf16", seed=6702, name="pw_dw5_tiny", ksize=5),
+             wl.PairCase("dw_pw", 1, 14, 14, 240, 40, stride=1, dtype="bf16", seed=6703, name="dw_pw5_bf16", ksize=5),
+             wl.PairCase("dw_pw", 2, 13, 10, 96, 24, stride=2, dtype="f32", seed=6704, name="dw_pw5_f32_s2_ragged", ksize=5),
+             wl.PairCase("dw_pw", 1, 7, 7, 672, 160, stride=1, dtype="bf16", seed=6705, name="dw_pw5_672_split", ksize=5)]
+    for case in cases:
+        t = runner.to_device(case)
+        y = runner.alloc_output(case)
+        y.fill_(3.0)
+        runner.run_fused(case, t, y, runner.alloc_workspace(case, fused=True))
+        torch.cuda.synchronize()
+        assert_close(runner.to_numpy64(y), oracle.run_case(case), case.dtype, case.name)
+    # the 3 x 3 entry points refuse a weight of another size instead of mis-reading it
+    t = runner.to_device(cases[0])
+    with pytest.raises(ValueError):
+        ago.ago_fused_pw_dw(t["x"], t["w1"], t["b1"], t["wd"], t["bd"], runner.alloc_output(cases[0]), 1)
+
+
 # ---- single operators -----------------------------------------------------------------
 
 def _dev(torch, arr, dtype):

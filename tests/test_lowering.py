@@ -294,3 +294,28 @@ def test_captured_plan_replays_like_the_eager_run():
     t_eager, t_graph = per_pass(lambda: ex.run({"x": x})), per_pass(replay)
     print("four-block plan: eager %.1f us per pass, graph replay %.1f us" % (t_eager, t_graph))
     assert t_graph < t_eager
+
+
+@pytest.mark.gpu
+def test_a_cut_5x5_block_lowers_to_the_5x5_pair():
+    """A partition that cuts a 5 x 5 block after its depthwise: the first part is the pw->dw pair with a
+    5 x 5 depthwise and must run on the entry point for that size."""
+    import torch
+    from oracle import ago_oracle
+    from paper_2212_01005_amd import binding as ago
+    g = _mobile_graph("bf16", [(96, 24, 1, 5)])
+    part = [0] * 7 + [1] * (len(g.nodes) - 7)          # input + (conv1x1, bias, relu6, dwconv, bias, relu6) | the projection
+    plan = L.lower(g, part)
+    assert [k for k, _ in plan][0] == "pw_dw"
+    x = wl.round_to_bf16(wl.uniform(9400, (2, 14, 14, 16), -1.0, 1.0))
+    ref = _oracle_eval(g, {"x": x}, ago_oracle)
+    host = dict(g.params)
+    g.params = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to("cuda:0").to(
+        torch.float32 if k.startswith("b") else torch.bfloat16).contiguous() for k, v in host.items()}
+    out = L.Executor(g, plan, ago, torch).run(
+        {"x": torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to("cuda:0").to(torch.bfloat16)})
+    torch.cuda.synchronize()
+    (i, got), = out.items()
+    r = ref[i]
+    gotn = got.float().cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(gotn - r) / np.maximum(np.abs(r), np.sqrt(np.mean(r ** 2)))) <= 4e-2     # two roundings of an intermediate

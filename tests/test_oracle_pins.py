@@ -568,6 +568,25 @@ def test_pair_dw_dw_brute(oracle, stride):
     np.testing.assert_allclose(oracle.dw_dw(x, wa, ba, wb, bb, stride), lists_to_nhwc(y), rtol=1e-12, atol=1e-12)
 
 
+@pytest.mark.parametrize("stride", [1, 2])
+def test_pairs_with_a_5x5_depthwise_brute(oracle, stride):
+    """The two pairs with a 5 x 5 depthwise (zero padding 2) against the loop nest, and the closed form
+    of an all-ones kernel on an all-ones image: 25 taps inside, 15 on an edge, 9 in a corner."""
+    x = _tiny(941, (1, 6, 7, 3)); w1 = _tiny(942, (3, 4)); wd = _tiny(943, (5, 5, 4))
+    b1 = _tiny(944, (4,), -0.3, 0.3); bd = _tiny(945, (4,), -0.3, 0.3)
+    e = brute_bias_act(brute_conv_nchw(nhwc_to_lists(x), w1x1_to_oihw(w1), 0, 1), b1.tolist(), "relu6")
+    d = brute_bias_act(brute_conv_nchw(e, wdw_to_oihw(wd), 2, stride, groups_depthwise=True), bd.tolist(), "relu6")
+    np.testing.assert_allclose(oracle.pw_dw(x, w1, b1, wd, bd, stride), lists_to_nhwc(d), rtol=1e-12, atol=1e-12)
+    x2 = _tiny(946, (2, 5, 6, 4)); w2 = _tiny(947, (4, 3)); b2 = _tiny(948, (3,), -0.3, 0.3)
+    d2 = brute_bias_act(brute_conv_nchw(nhwc_to_lists(x2), wdw_to_oihw(wd), 2, stride, groups_depthwise=True), bd.tolist(), "relu6")
+    y2 = brute_bias_act(brute_conv_nchw(d2, w1x1_to_oihw(w2), 0, 1), b2.tolist(), "none")
+    np.testing.assert_allclose(oracle.dw_pw(x2, wd, bd, w2, b2, stride), lists_to_nhwc(y2), rtol=1e-12, atol=1e-12)
+    if stride == 1:
+        ones = oracle.pw_dw(np.ones((1, 7, 7, 2)), np.eye(2), None, np.full((5, 5, 2), 0.2), None, 1)[0, :, :, 0]
+        assert ones[3, 3] == pytest.approx(5.0) and ones[0, 3] == pytest.approx(3.0) and ones[0, 0] == pytest.approx(1.8)
+        assert ones[1, 1] == pytest.approx(16 * 0.2) and ones[6, 6] == pytest.approx(1.8)
+
+
 def test_pairs_compose_to_the_block_and_to_the_ffn(oracle):
     """pw_dw followed by the projection, and the expansion followed by dw_pw, both give the
     inverted residual; pw_pw on an NHWC tensor is the FFN chain on its rows."""

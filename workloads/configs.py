@@ -236,6 +236,7 @@ class PairCase:
     dtype: str = "bf16"
     seed: int = _SEED0 + 2000
     name: str = "pair"
+    ksize: int = 3            # depthwise size of pw_dw / dw_pw (3 or 5)
 
     @property
     def OH(self): return (self.H - 1) // self.stride + 1 if self.kind != "pw_pw" else self.H
@@ -249,9 +250,9 @@ class PairCase:
     def flops(self):
         pe, po = self.N * self.H * self.W, self.N * self.OH * self.OW
         if self.kind == "pw_dw":
-            return 2 * pe * self.C1 * self.C2 + 2 * 9 * po * self.C2
+            return 2 * pe * self.C1 * self.C2 + 2 * self.ksize ** 2 * po * self.C2
         if self.kind == "dw_pw":
-            return 2 * 9 * po * self.C1 + 2 * po * self.C1 * self.C2
+            return 2 * self.ksize ** 2 * po * self.C1 + 2 * po * self.C1 * self.C2
         if self.kind == "dw_dw":
             return 2 * 2 * 9 * po * self.C1
         return 2 * pe * self.C2 * (self.C1 + self.C3)
@@ -271,11 +272,11 @@ class PairCase:
         if self.kind == "pw_dw":
             return {"x": _store(rng.uniform(s, (self.N, self.H, self.W, self.C1), -1.0, 1.0), d),
                     "w1": _store(rng.normal(s + 1, (self.C1, self.C2), (1.0 / self.C1) ** 0.5), d),
-                    "wd": _store(rng.normal(s + 2, (3, 3, self.C2), (1.0 / 9.0) ** 0.5), d),
+                    "wd": _store(rng.normal(s + 2, (self.ksize, self.ksize, self.C2), (1.0 / self.ksize ** 2) ** 0.5), d),
                     "b1": b(4, self.C2), "bd": b(5, self.C2)}
         if self.kind == "dw_pw":
             return {"x": _store(rng.uniform(s, (self.N, self.H, self.W, self.C1), -1.0, 1.0), d),
-                    "wd": _store(rng.normal(s + 2, (3, 3, self.C1), (1.0 / 9.0) ** 0.5), d),
+                    "wd": _store(rng.normal(s + 2, (self.ksize, self.ksize, self.C1), (1.0 / self.ksize ** 2) ** 0.5), d),
                     "w2": _store(rng.normal(s + 3, (self.C1, self.C2), (1.0 / self.C1) ** 0.5), d),
                     "bd": b(5, self.C1), "b2": b(6, self.C2)}
         if self.kind == "dw_dw":
