@@ -197,6 +197,26 @@ def fused_upstream_iterations(N, O1, O2, H2, W2, R2, C2, to2, th2, tw2):
     return int(v), int(unf.value)
 
 
+def _want(name, t, shape, dtype=None, optional=False):
+    """The marshalling step's only check: a tensor the C call will index with these sizes must really have
+    them (a mismatch would be an out-of-bounds access on the GPU, not an error code): device, layout,
+    shape and element type."""
+    if t is None:
+        if optional:
+            return
+        raise ValueError("%s is required" % name)
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous device tensor" % name)
+    if tuple(t.shape) != tuple(int(d) for d in shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s has dtype %s, expected %s" % (name, t.dtype, dtype))
+
+
+def _want_bias(name, b, n):
+    _want(name, b, (n,), torch.float32, optional=True)
+
+
 def _entry(marshal):
     """Turn a marshalling function (tensors -> C function + argument tuple) into the entry point
     wrapper; the marshalling step stays reachable for prepare()."""
@@ -224,10 +244,20 @@ def prepare(entry, *a, **kw):
 
 # ---- fused subgraphs ---------------------------------------------------------------
 
+def _want_invres(x, w1, b1, wd, bd, w2, b2, y, stride, ks):
+    N, H, W, Cin = x.shape
+    Cexp, Cout = w2.shape
+    _want("x", x, x.shape)
+    _want("w1", w1, (Cin, Cexp), x.dtype); _want("wd", wd, (ks, ks, Cexp), x.dtype); _want("w2", w2, (Cexp, Cout), x.dtype)
+    _want_bias("b1", b1, Cexp); _want_bias("bd", bd, Cexp); _want_bias("b2", b2, Cout)
+    _want("y", y, (N, (H - 1) // stride + 1, (W - 1) // stride + 1, Cout), x.dtype)
+
+
 @_entry
 def ago_fused_invres(x, w1, b1, wd, bd, w2, b2, y, stride, residual, workspace=None):
     N, H, W, Cin = x.shape
     Cexp, Cout = w2.shape
+    _want_invres(x, w1, b1, wd, bd, w2, b2, y, stride, 3)
     wp, wb = _ws(workspace)
     return lib.ago_fused_invres, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
                               N, H, W, Cin, Cexp, Cout, stride, int(residual), _dt(x), wp, wb, _stream())
@@ -252,6 +282,7 @@ def ago_fused_invres_k(x, w1, b1, wd, bd, w2, b2, y, stride, residual, workspace
     Cexp, Cout = w2.shape
     if wd.shape[0] != wd.shape[1]:
         raise ValueError("square depthwise kernels only")
+    _want_invres(x, w1, b1, wd, bd, w2, b2, y, stride, int(wd.shape[0]))
     wp, wb = _ws(workspace)
     return lib.ago_fused_invres_k, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
                                     N, H, W, Cin, Cexp, Cout, stride, int(wd.shape[0]), int(residual), _dt(x),
@@ -261,6 +292,8 @@ def ago_fused_invres_k(x, w1, b1, wd, bd, w2, b2, y, stride, residual, workspace
 @_entry
 def ago_fused_conv_chain(x, wa, ba, wb_, bb, y, residual, workspace=None):
     N, H, W, C = x.shape
+    _want("x", x, x.shape); _want("wa", wa, (3, 3, C, C), x.dtype); _want("wb", wb_, (3, 3, C, C), x.dtype)
+    _want_bias("ba", ba, C); _want_bias("bb", bb, C); _want("y", y, x.shape, x.dtype)
     wp, wb = _ws(workspace)
     return lib.ago_fused_conv_chain, (_p(x), _p(wa), _p(ba), _p(wb_), _p(bb), _p(y),
                                   N, H, W, C, int(residual), _dt(x), wp, wb, _stream())
@@ -270,6 +303,8 @@ def ago_fused_conv_chain(x, wa, ba, wb_, bb, y, residual, workspace=None):
 def ago_fused_ffn(x, w1, b1, w2, b2, y, act=ACT_GELU_TANH, workspace=None):
     M, K = x.shape
     F, K2 = w2.shape
+    _want("x", x, x.shape); _want("w1", w1, (K, F), x.dtype); _want("w2", w2, (F, K2), x.dtype)
+    _want_bias("b1", b1, F); _want_bias("b2", b2, K2); _want("y", y, (M, K2), x.dtype)
     wp, wb = _ws(workspace)
     return lib.ago_fused_ffn, (_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
                            wp, wb, _stream())
@@ -278,6 +313,8 @@ def ago_fused_ffn(x, w1, b1, w2, b2, y, act=ACT_GELU_TANH, workspace=None):
 @_entry
 def ago_fused_attn(q, k, v, o, scale, workspace=None):
     B, Hh, S, D = q.shape
+    for name, t in (("q", q), ("k", k), ("v", v), ("o", o)):
+        _want(name, t, q.shape, q.dtype)
     wp, wb = _ws(workspace)
     return lib.ago_fused_attn, (_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q), wp, wb, _stream())
 
@@ -289,6 +326,9 @@ def ago_fused_attn_bias(q, k, v, bias, o, scale, workspace=None):
     Bb, Hb = bias.shape[:2]
     if Bb not in (1, B) or Hb not in (1, Hh) or tuple(bias.shape[2:]) != (S, S) or not bias.is_contiguous():
         raise ValueError("bias must be a contiguous [1|B, 1|Hh, S, S] tensor")
+    for name, t in (("q", q), ("k", k), ("v", v), ("o", o)):
+        _want(name, t, q.shape, q.dtype)
+    _want("bias", bias, bias.shape, q.dtype)
     sh = S * S if Hb > 1 else 0
     sb = Hb * S * S if Bb > 1 else 0
     wp, wb = _ws(workspace)
@@ -306,6 +346,13 @@ def ago_fused_qkv(x, wq, wk, wv, bq, bk, bv, q, k, v, head_major=True, workspace
         B, S, Hh, D = q.shape
     if B * S != rows or k.shape != q.shape or v.shape != q.shape:
         raise ValueError("q, k, v must share one shape with B * S == x.shape[0]")
+    _want("x", x, x.shape)
+    for name, t in (("wq", wq), ("wk", wk), ("wv", wv)):
+        _want(name, t, (K, Hh * D), x.dtype)
+    for name, t in (("bq", bq), ("bk", bk), ("bv", bv)):
+        _want_bias(name, t, Hh * D)
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        _want(name, t, q.shape, x.dtype)
     wp, wb = _ws(workspace)
     return lib.ago_fused_qkv, (_p(x), _p(wq), _p(wk), _p(wv), _p(bq), _p(bk), _p(bv), _p(q), _p(k), _p(v),
                                B, S, K, Hh, D, int(head_major), _dt(x), wp, wb, _stream())
@@ -315,9 +362,27 @@ def ago_fused_qkv(x, wq, wk, wv, bq, bk, bv, q, k, v, head_major=True, workspace
 def ago_fused_attn_bshd(q, k, v, o, scale, workspace=None):
     """q, k, v, o: [B, S, Hh, D] tensors (the layout a QKV projection leaves behind)."""
     B, S, Hh, D = q.shape
+    for name, t in (("q", q), ("k", k), ("v", v), ("o", o)):
+        _want(name, t, q.shape, q.dtype)
     wp, wb = _ws(workspace)
     return lib.ago_fused_attn_strided, (_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, S * Hh * D, D, Hh * D,
                                         float(scale), _dt(q), wp, wb, _stream())
+
+
+def _want_pw_dw(x, w1, b1, wd, bd, y, stride, ks):
+    N, H, W, Cin = x.shape
+    Cexp = w1.shape[1]
+    _want("x", x, x.shape); _want("w1", w1, (Cin, Cexp), x.dtype); _want("wd", wd, (ks, ks, Cexp), x.dtype)
+    _want_bias("b1", b1, Cexp); _want_bias("bd", bd, Cexp)
+    _want("y", y, (N, (H - 1) // stride + 1, (W - 1) // stride + 1, Cexp), x.dtype)
+
+
+def _want_dw_pw(x, wd, bd, w2, b2, y, stride, ks):
+    N, H, W, C = x.shape
+    Cout = w2.shape[1]
+    _want("x", x, x.shape); _want("wd", wd, (ks, ks, C), x.dtype); _want("w2", w2, (C, Cout), x.dtype)
+    _want_bias("bd", bd, C); _want_bias("b2", b2, Cout)
+    _want("y", y, (N, (H - 1) // stride + 1, (W - 1) // stride + 1, Cout), x.dtype)
 
 
 def _dw_size(wd, want=None):
@@ -331,7 +396,7 @@ def _dw_size(wd, want=None):
 def ago_fused_pw_dw(x, w1, b1, wd, bd, y, stride, workspace=None):
     N, H, W, Cin = x.shape
     Cexp = w1.shape[1]
-    _dw_size(wd, 3)
+    _want_pw_dw(x, w1, b1, wd, bd, y, stride, _dw_size(wd, 3))
     wp, wb = _ws(workspace)
     return lib.ago_fused_pw_dw, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(y), N, H, W, Cin, Cexp, stride,
                                  _dt(x), wp, wb, _stream())
@@ -342,6 +407,7 @@ def ago_fused_pw_dw_k(x, w1, b1, wd, bd, y, stride, workspace=None):
     """wd: [ksize, ksize, Cexp]; the depthwise size is read off its shape."""
     N, H, W, Cin = x.shape
     Cexp = w1.shape[1]
+    _want_pw_dw(x, w1, b1, wd, bd, y, stride, _dw_size(wd))
     wp, wb = _ws(workspace)
     return lib.ago_fused_pw_dw_k, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(y), N, H, W, Cin, Cexp, stride,
                                    _dw_size(wd), _dt(x), wp, wb, _stream())
@@ -351,7 +417,7 @@ def ago_fused_pw_dw_k(x, w1, b1, wd, bd, y, stride, workspace=None):
 def ago_fused_dw_pw(x, wd, bd, w2, b2, y, stride, workspace=None):
     N, H, W, C = x.shape
     Cout = w2.shape[1]
-    _dw_size(wd, 3)
+    _want_dw_pw(x, wd, bd, w2, b2, y, stride, _dw_size(wd, 3))
     wp, wb = _ws(workspace)
     return lib.ago_fused_dw_pw, (_p(x), _p(wd), _p(bd), _p(w2), _p(b2), _p(y), N, H, W, C, Cout, stride,
                                  _dt(x), wp, wb, _stream())
@@ -362,6 +428,7 @@ def ago_fused_dw_pw_k(x, wd, bd, w2, b2, y, stride, workspace=None):
     """wd: [ksize, ksize, C]; the depthwise size is read off its shape."""
     N, H, W, C = x.shape
     Cout = w2.shape[1]
+    _want_dw_pw(x, wd, bd, w2, b2, y, stride, _dw_size(wd))
     wp, wb = _ws(workspace)
     return lib.ago_fused_dw_pw_k, (_p(x), _p(wd), _p(bd), _p(w2), _p(b2), _p(y), N, H, W, C, Cout, stride,
                                    _dw_size(wd), _dt(x), wp, wb, _stream())
@@ -370,6 +437,9 @@ def ago_fused_dw_pw_k(x, wd, bd, w2, b2, y, stride, workspace=None):
 @_entry
 def ago_fused_dw_dw(x, wa, ba, wb_, bb, y, stride, workspace=None):
     N, H, W, C = x.shape
+    _want("x", x, x.shape); _want("wa", wa, (3, 3, C), x.dtype); _want("wb", wb_, (3, 3, C), x.dtype)
+    _want_bias("ba", ba, C); _want_bias("bb", bb, C)
+    _want("y", y, (N, (H - 1) // stride + 1, (W - 1) // stride + 1, C), x.dtype)
     wp, wb = _ws(workspace)
     return lib.ago_fused_dw_dw, (_p(x), _p(wa), _p(ba), _p(wb_), _p(bb), _p(y), N, H, W, C, stride,
                                  _dt(x), wp, wb, _stream())
@@ -379,6 +449,8 @@ def ago_fused_dw_dw(x, wa, ba, wb_, bb, y, stride, workspace=None):
 def ago_fused_pw_pw(x, w1, b1, w2, b2, y, act=ACT_RELU, workspace=None):
     N, H, W, Cin = x.shape
     Cmid, Cout = w2.shape
+    _want("x", x, x.shape); _want("w1", w1, (Cin, Cmid), x.dtype); _want("w2", w2, (Cmid, Cout), x.dtype)
+    _want_bias("b1", b1, Cmid); _want_bias("b2", b2, Cout); _want("y", y, (N, H, W, Cout), x.dtype)
     wp, wb = _ws(workspace)
     return lib.ago_fused_pw_pw, (_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), N, H, W, Cin, Cmid, Cout, act,
                                  _dt(x), wp, wb, _stream())
@@ -390,46 +462,58 @@ def ago_fused_pw_pw(x, w1, b1, w2, b2, y, act=ACT_RELU, workspace=None):
 def ago_gemm(a, b, bias, res, c, act=ACT_NONE):
     M, K = a.shape
     N = b.shape[1]
+    _want("a", a, a.shape); _want("b", b, (K, N), a.dtype); _want_bias("bias", bias, N)
+    _want("res", res, (M, N), a.dtype, optional=True); _want("c", c, (M, N), a.dtype)
     return lib.ago_gemm, (_p(a), _p(b), _p(bias), _p(res), _p(c), M, K, N, act, _dt(a), _stream())
 
 
 @_entry
 def ago_conv1x1(x, w, bias, res, y, act=ACT_NONE):
     N, H, W, Cin = x.shape
+    _want("x", x, x.shape); _want("w", w, (Cin, w.shape[1]), x.dtype); _want_bias("bias", bias, w.shape[1])
+    _want("res", res, (N, H, W, w.shape[1]), x.dtype, optional=True); _want("y", y, (N, H, W, w.shape[1]), x.dtype)
     return lib.ago_conv1x1, (_p(x), _p(w), _p(bias), _p(res), _p(y), N, H, W, Cin, w.shape[1], act, _dt(x), _stream())
 
 
 @_entry
 def ago_dwconv3x3(x, w, bias, y, stride, act=ACT_NONE):
     N, H, W, C = x.shape
+    _want("x", x, x.shape); _want("w", w, (3, 3, C), x.dtype); _want_bias("bias", bias, C)
+    _want("y", y, (N, (H - 1) // stride + 1, (W - 1) // stride + 1, C), x.dtype)
     return lib.ago_dwconv3x3, (_p(x), _p(w), _p(bias), _p(y), N, H, W, C, stride, act, _dt(x), _stream())
 
 
 @_entry
 def ago_conv3x3(x, w, bias, res, y, act=ACT_NONE):
     N, H, W, Cin = x.shape
+    _want("x", x, x.shape); _want("w", w, (3, 3, Cin, w.shape[3]), x.dtype); _want_bias("bias", bias, w.shape[3])
+    _want("res", res, (N, H, W, w.shape[3]), x.dtype, optional=True); _want("y", y, (N, H, W, w.shape[3]), x.dtype)
     return lib.ago_conv3x3, (_p(x), _p(w), _p(bias), _p(res), _p(y), N, H, W, Cin, w.shape[3], act, _dt(x), _stream())
 
 
 @_entry
 def ago_bias_act(x, bias, y, act=ACT_NONE):
     C = x.shape[-1]
+    _want("x", x, x.shape); _want_bias("bias", bias, C); _want("y", y, x.shape, x.dtype)
     return lib.ago_bias_act, (_p(x), _p(bias), _p(y), x.numel() // C, C, act, _dt(x), _stream())
 
 
 @_entry
 def ago_add_act(a, b, y, act=ACT_NONE):
+    _want("a", a, a.shape); _want("b", b, a.shape, a.dtype); _want("y", y, a.shape, a.dtype)
     return lib.ago_add_act, (_p(a), _p(b), _p(y), a.numel(), act, _dt(a), _stream())
 
 
 @_entry
 def ago_scale(x, y, alpha):
+    _want("x", x, x.shape); _want("y", y, x.shape, x.dtype)
     return lib.ago_scale, (_p(x), _p(y), x.numel(), float(alpha), _dt(x), _stream())
 
 
 @_entry
 def ago_softmax_rows(x, y):
     cols = x.shape[-1]
+    _want("x", x, x.shape); _want("y", y, x.shape)
     return lib.ago_softmax_rows, (_p(x), _p(y), x.numel() // cols, cols, _dt(x), _dt(y), _stream())
 
 
@@ -437,6 +521,7 @@ def ago_softmax_rows(x, y):
 def ago_bmm_nt(a, b, c, alpha=1.0):
     M, K = a.shape[-2:]
     N = b.shape[-2]
+    _want("a", a, a.shape); _want("b", b, tuple(a.shape[:-2]) + (N, K), a.dtype); _want("c", c, tuple(a.shape[:-2]) + (M, N))
     return lib.ago_bmm_nt, (_p(a), _p(b), _p(c), a.numel() // (M * K), M, N, K, float(alpha), _dt(a), _dt(c), _stream())
 
 
@@ -444,6 +529,7 @@ def ago_bmm_nt(a, b, c, alpha=1.0):
 def ago_bmm_nn(a, b, c):
     M, K = a.shape[-2:]
     N = b.shape[-1]
+    _want("a", a, a.shape); _want("b", b, tuple(a.shape[:-2]) + (K, N), a.dtype); _want("c", c, tuple(a.shape[:-2]) + (M, N), a.dtype)
     return lib.ago_bmm_nn, (_p(a), _p(b), _p(c), a.numel() // (M * K), M, N, K, _dt(a), _stream())
 
 
@@ -453,6 +539,7 @@ def ago_bmm_nn(a, b, c):
 def ago_unfused_invres(x, w1, b1, wd, bd, w2, b2, y, stride, residual, epilogue_fused, workspace):
     N, H, W, Cin = x.shape
     Cexp, Cout = w2.shape
+    _want_invres(x, w1, b1, wd, bd, w2, b2, y, stride, 3)
     wp, wb = _ws(workspace)
     return lib.ago_unfused_invres, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
                                 N, H, W, Cin, Cexp, Cout, stride, int(residual), _dt(x),
@@ -462,6 +549,8 @@ def ago_unfused_invres(x, w1, b1, wd, bd, w2, b2, y, stride, residual, epilogue_
 @_entry
 def ago_unfused_conv_chain(x, wa, ba, wb_, bb, y, residual, epilogue_fused, workspace):
     N, H, W, C = x.shape
+    _want("x", x, x.shape); _want("wa", wa, (3, 3, C, C), x.dtype); _want("wb", wb_, (3, 3, C, C), x.dtype)
+    _want_bias("ba", ba, C); _want_bias("bb", bb, C); _want("y", y, x.shape, x.dtype)
     wp, wb = _ws(workspace)
     return lib.ago_unfused_conv_chain, (_p(x), _p(wa), _p(ba), _p(wb_), _p(bb), _p(y), N, H, W, C,
                                     int(residual), _dt(x), int(epilogue_fused), wp, wb, _stream())
@@ -471,6 +560,8 @@ def ago_unfused_conv_chain(x, wa, ba, wb_, bb, y, residual, epilogue_fused, work
 def ago_unfused_ffn(x, w1, b1, w2, b2, y, act, epilogue_fused, workspace):
     M, K = x.shape
     F, K2 = w2.shape
+    _want("x", x, x.shape); _want("w1", w1, (K, F), x.dtype); _want("w2", w2, (F, K2), x.dtype)
+    _want_bias("b1", b1, F); _want_bias("b2", b2, K2); _want("y", y, (M, K2), x.dtype)
     wp, wb = _ws(workspace)
     return lib.ago_unfused_ffn, (_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
                              int(epilogue_fused), wp, wb, _stream())
@@ -479,6 +570,8 @@ def ago_unfused_ffn(x, w1, b1, w2, b2, y, act, epilogue_fused, workspace):
 @_entry
 def ago_unfused_attn(q, k, v, o, scale, epilogue_fused, workspace):
     B, Hh, S, D = q.shape
+    for name, t in (("q", q), ("k", k), ("v", v), ("o", o)):
+        _want(name, t, q.shape, q.dtype)
     wp, wb = _ws(workspace)
     return lib.ago_unfused_attn, (_p(q), _p(k), _p(v), _p(o), B, Hh, S, D, float(scale), _dt(q),
                               int(epilogue_fused), wp, wb, _stream())

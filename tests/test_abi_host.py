@@ -305,3 +305,32 @@ def test_invres_plan_is_a_host_query(lib):
         ago.fused_invres_plan(1, 14, 14, 32, 192, 32, 1, 4, ago.F32)       # depthwise size
     with pytest.raises(ago.AgoError):
         ago.fused_invres_plan(1, 14, 14, 30, 192, 32, 1, 3, ago.F32)       # Cin % 8
+
+
+def test_binding_refuses_tensors_that_do_not_match_the_sizes_it_passes(lib):
+    """The marshalling step checks device, layout, shape and element type of every tensor before the C
+    call: a mismatch would be an out-of-bounds access on the GPU.  Checked here with CPU tensors (refused
+    as such) and through the checker itself."""
+    import torch
+    from paper_2212_01005_amd import binding as ago
+    x = torch.zeros(4, 8)
+    with pytest.raises(ValueError, match="device"):
+        ago.ago_fused_ffn.marshal(x, x, None, x, None, x)
+    with pytest.raises(ValueError, match="required"):
+        ago._want("x", None, (1,))
+    ago._want("b", None, (1,), optional=True)
+
+    class Fake:                     # stands in for a device tensor: only the attributes the check reads
+        def __init__(self, shape, dtype=torch.bfloat16, contiguous=True):
+            self.shape, self.dtype, self.is_cuda, self._c = torch.Size(shape), dtype, True, contiguous
+        def is_contiguous(self):
+            return self._c
+    ago._want("w", Fake((8, 16)), (8, 16), torch.bfloat16)
+    with pytest.raises(ValueError, match="shape"):
+        ago._want("w", Fake((8, 16)), (16, 8), torch.bfloat16)
+    with pytest.raises(ValueError, match="dtype"):
+        ago._want("w", Fake((8, 16), torch.float32), (8, 16), torch.bfloat16)
+    with pytest.raises(ValueError, match="contiguous"):
+        ago._want("w", Fake((8, 16), contiguous=False), (8, 16))
+    with pytest.raises(ValueError, match="dtype"):
+        ago._want_bias("b1", Fake((16,), torch.bfloat16), 16)
