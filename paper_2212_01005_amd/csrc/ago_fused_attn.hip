@@ -258,15 +258,24 @@ __attribute__((amdgpu_waves_per_eu(NP == 2 || BIAS == 2 ? 2 : (BIAS == 1 ? 4 : 3
             for (int r = 0; r < 16; r += 2) mx = fmaxf(fmaxf(sc[kt][r], sc[kt][r + 1]), mx);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m, mx * ce);
-        // a half whose keys are all beyond S so far keeps m = -inf: subtract 0 instead (exp2(-inf) = 0)
-        const float mref = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m - mref);
-        m = m_new;
-        l *= alpha;
+        // The reference m that the exponentials subtract only has to bound the scores from above loosely:
+        // it moves (and the sum and O^T are rescaled, 16 (2 NP + ...) multiplies per lane) only when some
+        // row of the wave saw its maximum grow by more than kLazy in the exponent, i.e. when staying put
+        // would let a probability exceed 2^kLazy.  Any reference gives the same quotient at the end; after
+        // the first block a new maximum that far above the old one is rare, so the rescale mostly
+        // happens once.  (m = -inf, nothing seen yet: any finite maximum is "more".)
+        constexpr float kLazy = 8.0f;
+        if (__builtin_amdgcn_ballot_w64(m_new > m + kLazy) != 0) {        // wave-uniform
+            // a half whose keys are all beyond S so far keeps m = -inf: subtract 0 instead (exp2(-inf) = 0)
+            const float alpha = __builtin_amdgcn_exp2f(m - (m_new == -INFINITY ? 0.f : m_new));
+            m = m_new;
+            l *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < 2 * NP; ++dt)
+            for (int dt = 0; dt < 2 * NP; ++dt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+                for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        }
+        const float mref = m == -INFINITY ? 0.f : m;
 
         bf16x8 pf[2][2];
 #pragma unroll
@@ -279,13 +288,15 @@ __attribute__((amdgpu_waves_per_eu(NP == 2 || BIAS == 2 ? 2 : (BIAS == 1 ? 4 : 3
                     l += pv;
                     pf[kt][u][e] = (bf16_t)pv;
                 }
+        // the lane's two V^T base addresses of this block, once: the 8 NP fragment addresses are these plus constants
+        const lds_byte* vbase[2] = {vb + voff[0], vb + voff[1]};
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int dt = 0; dt < 2 * NP; ++dt)
-                    o[dt] = mfma32(lds_read_vt(vb + (dt >> 1) * kPlaneB + voff[dt & 1] + (kt * 32 + 16 * u) * 128), pf[kt][u], o[dt]);
+                    o[dt] = mfma32(lds_read_vt(vbase[dt & 1] + (dt >> 1) * kPlaneB + (kt * 32 + 16 * u) * 128), pf[kt][u], o[dt]);
 
         __builtin_amdgcn_s_barrier();
     }
