@@ -146,6 +146,31 @@ def test_attention_strided_layout(gpu, oracle):
         assert_close(runner.to_numpy64(o.permute(0, 2, 1, 3)), ref, "bf16", case.name)
 
 
+def test_attention_reference_moves_only_when_it_must(gpu, oracle):
+    """The kernel keeps its softmax reference until some row's maximum grows by more than 2^8.  Scores whose
+    scale rises along the keys (later blocks dominate: the reference has to move, and the accumulators are
+    rescaled, in every block) and scores whose scale falls (it never moves again) both match the oracle, in
+    every tile configuration, with ragged and long sequences."""
+    torch, ago, runner = gpu
+    for seed, S, ramp in ((6150, 384, 8.0), (6151, 384, 1.0 / 8.0), (6152, 600, 6.0), (6153, 100, 5.0), (6154, 1100, 3.0)):
+        case = wl.AttnCase(1, 2, S, 64, 0.125, "bf16", seed, name="attn_ramp")
+        t = case.tensors()
+        gain = ramp ** (np.arange(S) / float(S - 1))                      # 1 at the first key, `ramp` at the last
+        k = wl.round_to_bf16(t["k"] * gain[None, None, :, None])
+        ref = oracle.attn(t["q"], k, t["v"], case.scale)
+        dev = {n: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda:0").to(torch.bfloat16)
+               for n, a in (("q", t["q"]), ("k", k), ("v", t["v"]))}
+        try:
+            for cfg in [-1] + list(range(ago.num_tile_configs(ago.OP_FUSED_ATTN))):
+                ago.set_tile_config(ago.OP_FUSED_ATTN, cfg)
+                o = torch.zeros_like(dev["q"])
+                ago.ago_fused_attn(dev["q"], dev["k"], dev["v"], o, case.scale)
+                torch.cuda.synchronize()
+                assert_close(runner.to_numpy64(o), ref, "bf16", "attn ramp %g S %d cfg %d" % (ramp, S, cfg))
+        finally:
+            ago.set_tile_config(ago.OP_FUSED_ATTN, -1)
+
+
 def test_invres_5x5_depthwise(gpu, oracle):
     """The block with a 5x5 depthwise (2-pixel halo): both dtypes and strides, residual, ragged images,
     images smaller than the kernel, the built-in tile choice and explicit tile configurations."""
