@@ -171,6 +171,27 @@ def test_attention_reference_moves_only_when_it_must(gpu, oracle):
             ago.set_tile_config(ago.OP_FUSED_ATTN, -1)
 
 
+def test_attention_long_sequences(gpu, oracle):
+    """Two dozen key blocks and more through the LDS ring (buffers re-used many times, the softmax reference
+    carried across all of them): a ragged S = 3000 at head dimension 64 and S = 2048 at 128, both layouts."""
+    torch, ago, runner = gpu
+    for case in (wl.AttnCase(1, 2, 3000, 64, 0.125, "bf16", 6160, name="attn_s3000"),
+                 wl.AttnCase(1, 2, 2048, 128, 0.0884, "bf16", 6161, name="attn_s2048_d128")):
+        ref = oracle.run_case(case)
+        t = runner.to_device(case)
+        o = runner.alloc_output(case)
+        o.zero_()
+        runner.run_fused(case, t, o)
+        torch.cuda.synchronize()
+        assert_close(runner.to_numpy64(o), ref, "bf16", case.name)
+        if case.D == 64:
+            q, k, v = (t[n].permute(0, 2, 1, 3).contiguous() for n in ("q", "k", "v"))
+            ob = torch.zeros_like(q)
+            ago.ago_fused_attn_bshd(q, k, v, ob, case.scale)
+            torch.cuda.synchronize()
+            assert_close(runner.to_numpy64(ob.permute(0, 2, 1, 3)), ref, "bf16", case.name + " bshd")
+
+
 def test_invres_5x5_depthwise(gpu, oracle):
     """The block with a 5x5 depthwise (2-pixel halo): both dtypes and strides, residual, ragged images,
     images smaller than the kernel, the built-in tile choice and explicit tile configurations."""
