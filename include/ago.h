@@ -337,6 +337,17 @@ float ago_profile_event_overhead_ms(void* hip_stream, int pairs);
 int ago_profile_last_launch(ago_op op, int* grid, int* block);
 int ago_bench_empty_kernel(int grid, int block, void* hip_stream);
 
+/* Host-only: whether running matmul -> activation -> matmul as one fused kernel (ago_fused_ffn) is
+ * expected to beat the two products with fused epilogues (ago_unfused_ffn, epilogue_fused = 1) on
+ * MI355X: the decision the paper leaves to its tuner, and its own caveat for this pair (Sec. VI-C,
+ * Fig. 13d: fused, pw -> pw moves more data once the row count grows).  The fused kernel cuts the hidden
+ * dimension into slices of 384 and writes one fp32 partial result per slice and row, so its extra traffic
+ * grows with M * ceil(F / 384) while the un-fused pair only spills the hidden tensor once: measured, the
+ * fused kernel is 1.7 - 2.8 x faster up to 2048 rows (K x F = 768 x 3072, 1024 x 4096, 512 x 2048) and
+ * 0.6 - 0.85 x at 32768.  Returns 1 while the launch is at most 1024 workgroups of 64 rows x one slice
+ * (512 when F or K2 is not a multiple of 384), else 0; -1 on non-positive sizes. */
+int ago_fused_ffn_pays(int M, int K, int F, int K2);
+
 /* Redundancy model of Sec. III-B: number of times the upstream reduction body runs
  * when a conv R1xC1 (I -> O1) is fused under a downstream conv R2xC2 (O1 -> O2) whose
  * output is tiled (to2, th2, tw2) on (O2, H2, W2), no padding, stride 1 (the setting of

@@ -71,6 +71,8 @@ lib.ago_status_string.argtypes = [_i]
 lib.ago_status_string.restype = ctypes.c_char_p
 lib.ago_set_tile_config.argtypes = [_i, _i]
 lib.ago_set_tile_config.restype = _i
+lib.ago_fused_ffn_pays.argtypes = [_i] * 4
+lib.ago_fused_ffn_pays.restype = _i
 lib.ago_num_tile_configs.argtypes = [_i]
 lib.ago_num_tile_configs.restype = _i
 lib.ago_fused_upstream_iterations.argtypes = [_i] * 10 + [ctypes.POINTER(ctypes.c_longlong)]
@@ -103,7 +105,7 @@ lib.ago_graph_join.restype = _i
 
 EXPORTED = sorted(list(_SIGS) + ["ago_graph_op_weight", "ago_graph_topological_stage", "ago_graph_cluster",
                                  "ago_graph_split", "ago_graph_join"] + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
-                                 "ago_num_tile_configs", "ago_fused_upstream_iterations",
+                                 "ago_num_tile_configs", "ago_fused_upstream_iterations", "ago_fused_ffn_pays",
                                  "ago_profile_enable", "ago_profile_select", "ago_profile_read",
                                  "ago_profile_event_overhead_ms", "ago_profile_last_launch",
                                  "ago_bench_empty_kernel"])
@@ -143,6 +145,15 @@ def _ws(ws):
 def workspace_bytes(op, dims, dt):
     arr = (_i * len(dims))(*dims)
     return int(lib.ago_workspace_bytes(op, arr, len(dims), dt))
+
+
+def fused_ffn_pays(M, K, F, K2):
+    """Host-only: True when the fused matmul -> activation -> matmul kernel is expected to beat the two
+    products with fused epilogues at this size."""
+    r = int(lib.ago_fused_ffn_pays(int(M), int(K), int(F), int(K2)))
+    if r < 0:
+        raise ValueError("non-positive size")
+    return bool(r)
 
 
 def set_tile_config(op, config_id):

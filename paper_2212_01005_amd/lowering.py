@@ -120,10 +120,14 @@ def partition(g, binding, c=0.01, b=1.0, td=float("inf")):
     return binding.graph_cluster(len(g.nodes), weight, g.edges(), td), weight
 
 
-def lower(g, subgraph_of):
-    """Launch plan: a list of (kind, node ids) in execution order.  kind is one of the fused structures
-    or "op" (one operator on its un-fused kernel); "input" nodes launch nothing."""
+def lower(g, subgraph_of, binding=None):
+    """Launch plan: a list of (kind, node ids) in execution order.  kind is one of the fused structures,
+    "ffn_epilogue" (the matmul -> activation -> matmul chain as two products with fused epilogues: what
+    the chain becomes when ``binding.fused_ffn_pays`` says the fused kernel would lose at this row count;
+    without ``binding`` the chain is always fused) or "op" (one operator on its un-fused kernel);
+    "input" nodes launch nothing."""
     cons = g.consumers()
+    shapes = infer_shapes(g) if binding is not None else None
     n_nodes = len(g.nodes)
     done = [False] * n_nodes
     plan = []
@@ -168,6 +172,13 @@ def lower(g, subgraph_of):
                 m = pat.match(tokens[:tokens.index("+")])          # the same structure without the residual
             if m and _admissible(g, kind, chain[:m.end()]):
                 matched = (kind, chain[:m.end()])
+                if kind == "ffn" and binding is not None:
+                    ids = matched[1]
+                    gemms = [k for k in ids if g.nodes[k].op == "gemm"]
+                    m_rows, k_in = shapes[g.nodes[ids[0]].inputs[0]]
+                    f_hid, k_out = shapes[gemms[0]][1], shapes[gemms[1]][1]
+                    if not binding.fused_ffn_pays(m_rows, k_in, f_hid, k_out):
+                        matched = ("ffn_epilogue", ids)
                 break
         if matched is None:
             matched = ("op", [i])
@@ -308,13 +319,20 @@ class Executor:
                 ago.ago_fused_conv_chain(x, P[nodes[pos[0]].attrs["w"]], self._bias_of(nodes, pos[0]),
                                          P[nodes[pos[1]].attrs["w"]], self._bias_of(nodes, pos[1]), out,
                                          any(n.op == "add" for n in nodes))
-            elif kind == "ffn":
+            elif kind in ("ffn", "ffn_epilogue"):
                 pos = [k for k, n in enumerate(nodes) if n.op in COMPLEX]
                 act = next(n.op for n in nodes if n.op in _ACT_OF)
                 w1, w2 = P[nodes[pos[0]].attrs["w"]], P[nodes[pos[1]].attrs["w"]]
-                ws = self._workspace(ago.OP_FUSED_FFN, [x.shape[0], x.shape[1], w1.shape[1], w2.shape[1]], ago.BF16)
-                ago.ago_fused_ffn(x, w1, self._bias_of(nodes, pos[0]), w2, self._bias_of(nodes, pos[1]), out,
-                                  getattr(ago, _ACT_OF[act]), ws)
+                dims = [x.shape[0], x.shape[1], w1.shape[1], w2.shape[1]]
+                if kind == "ffn":
+                    ws = self._workspace(ago.OP_FUSED_FFN, dims, ago.BF16)
+                    ago.ago_fused_ffn(x, w1, self._bias_of(nodes, pos[0]), w2, self._bias_of(nodes, pos[1]), out,
+                                      getattr(ago, _ACT_OF[act]), ws)
+                else:                                  # two products with fused epilogues (two launches)
+                    self.launches += 1
+                    ws = self._workspace(ago.OP_UNFUSED_FFN, dims, ago.BF16)
+                    ago.ago_unfused_ffn(x, w1, self._bias_of(nodes, pos[0]), w2, self._bias_of(nodes, pos[1]), out,
+                                        getattr(ago, _ACT_OF[act]), True, ws)
             elif kind == "attn":
                 k_t = val[nodes[0].inputs[1]]
                 v_t = val[[s for s in nodes[3].inputs if s not in ids][0]]

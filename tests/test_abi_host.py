@@ -334,3 +334,17 @@ def test_binding_refuses_tensors_that_do_not_match_the_sizes_it_passes(lib):
         ago._want("w", Fake((8, 16), contiguous=False), (8, 16))
     with pytest.raises(ValueError, match="dtype"):
         ago._want_bias("b1", Fake((16,), torch.bfloat16), 16)
+
+
+def test_ffn_fuse_or_not_is_a_host_decision(lib):
+    """The fused matmul -> activation -> matmul kernel pays while its launch is small (its fp32 partials
+    grow with rows x hidden slices); beyond that the two products with fused epilogues are the schedule."""
+    from paper_2212_01005_amd import binding as ago
+    assert ago.fused_ffn_pays(2048, 768, 3072, 768)             # the benchmark shape: 256 workgroups
+    assert ago.fused_ffn_pays(8192, 768, 3072, 768)             # 1024 workgroups, exact slices
+    assert not ago.fused_ffn_pays(32768, 768, 3072, 768)
+    assert ago.fused_ffn_pays(2048, 1024, 4096, 1024) and not ago.fused_ffn_pays(8192, 1024, 4096, 1024)
+    assert ago.fused_ffn_pays(2048, 512, 2048, 512) and not ago.fused_ffn_pays(8192, 512, 2048, 512)
+    assert ago.fused_ffn_pays(1, 64, 8, 8)
+    with pytest.raises(ValueError):
+        ago.fused_ffn_pays(0, 768, 3072, 768)
