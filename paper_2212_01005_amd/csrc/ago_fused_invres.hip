@@ -601,15 +601,49 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
                         int Cexp, int Cout, int stride, int residual, bool bf16, int tile_cfg,
                         hipStream_t s, int mode, int ksize, void* workspace, size_t ws_bytes) {
     if (ksize != 3 && ksize != 5) return hipErrorInvalidValue;
+    // The plan (tile, chunking, split, LDS layout) depends on the shape only; walking all candidates costs
+    // as much host time as the kernel runs on the small blocks, so the last few plans are kept per thread.
+    struct PlanKey {
+        int v[11];
+        size_t ws;
+    };
+    struct PlanSlot {
+        PlanKey key;
+        InvresParams p;
+        size_t smem;
+        bool valid;
+    };
+    static thread_local PlanSlot plans[8] = {};
+    static thread_local int next_slot = 0;
+    const PlanKey key = {{N, H, W, Cin, Cexp, Cout, stride, ksize, bf16 ? 1 : 0, tile_cfg, mode}, workspace ? ws_bytes : 0};
+    const PlanSlot* hit = nullptr;
+    for (const PlanSlot& sl : plans) {
+        if (!sl.valid || sl.key.ws != key.ws) continue;
+        bool same = true;
+        for (int q = 0; q < 11; ++q) same = same && sl.key.v[q] == key.v[q];
+        if (same) { hit = &sl; break; }
+    }
     InvresParams p;
-    p.mode = mode;
+    size_t smem;
+    if (hit) {
+        p = hit->p;
+        smem = hit->smem;
+    } else {
+        p = InvresParams{};
+        p.mode = mode;
+        p.N = N; p.H = H; p.W = W; p.Cin = Cin; p.Cexp = Cexp; p.Cout = Cout;
+        p.OH = (H - 1) / stride + 1; p.OW = (W - 1) / stride + 1;
+        p.nsplit = 1;
+        smem = choose_tile(p, bf16, stride, ksize, tile_cfg, key.ws, nullptr, nullptr);
+        if (smem == 0) return hipErrorInvalidValue;
+        PlanSlot& sl = plans[next_slot];
+        next_slot = (next_slot + 1) % 8;
+        sl.key = key; sl.p = p; sl.smem = smem; sl.valid = true;
+    }
     p.x = x; p.w1 = w1; p.b1 = b1; p.wd = wd; p.bd = bd; p.w2 = w2; p.b2 = b2; p.y = y;
-    p.N = N; p.H = H; p.W = W; p.Cin = Cin; p.Cexp = Cexp; p.Cout = Cout;
-    p.OH = (H - 1) / stride + 1; p.OW = (W - 1) / stride + 1; p.residual = residual;
-    p.nsplit = 1; p.part = static_cast<float*>(workspace);
+    p.residual = residual;
+    p.part = static_cast<float*>(workspace);
     constexpr size_t kLdsMax = kInvresLdsMax;
-    const size_t smem = choose_tile(p, bf16, stride, ksize, tile_cfg, workspace ? ws_bytes : 0, nullptr, nullptr);
-    if (smem == 0) return hipErrorInvalidValue;
     const bool split = p.nsplit > 1;
     const dim3 grid((unsigned)(N * p.tiles_h * p.tiles_w), (unsigned)p.nsplit);
 #define AGO_LAUNCH_INVRES_KC(BF, ST, KS, CH, SP)                                                        \
