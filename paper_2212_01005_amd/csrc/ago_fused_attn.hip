@@ -301,39 +301,46 @@ __attribute__((amdgpu_waves_per_eu(NP == 2 || BIAS == 2 ? 2 : (BIAS == 1 ? 4 : 3
         __builtin_amdgcn_s_barrier();
     }
 
-    // merge the two key halves of each query tile: the kh = 1 wave parks (m, l, O^T) in LDS (the
-    // K / V buffers are free after the last barrier), the kh = 0 wave combines and writes O.
+    // merge the two key halves of each query tile, both waves at work: wave kh finishes the NP output
+    // tiles dt = kh NP .. kh NP + NP - 1 (32 head-dimension columns each).  It parks (m, l) and the tiles
+    // the other wave finishes in LDS (the K / V buffers are free after the last barrier), and after one
+    // barrier combines its own tiles with what the other parked and writes them.
     l += __shfl_xor(l, 32, 64);
-    constexpr int kParkRows = 2 + 32 * NP;
-    float* park = reinterpret_cast<float*>(smem_generic) + qt * kParkRows * 64;     // [2 + 32 NP][64] floats per query tile
-    if (kh == 1) {
-        park[lane] = m;
-        park[64 + lane] = l;
+    constexpr int kParkRows = 2 + 16 * NP;             // m, l, 16 NP accumulator registers
+    float* park = reinterpret_cast<float*>(smem_generic) + (qt * 2 + kh) * kParkRows * 64;      // [tile][kh][rows][64]
+    const float* theirs = reinterpret_cast<const float*>(smem_generic) + (qt * 2 + (kh ^ 1)) * kParkRows * 64;
+    park[lane] = m;
+    park[64 + lane] = l;
 #pragma unroll
-        for (int dt = 0; dt < 2 * NP; ++dt)
+    for (int t = 0; t < NP; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) park[(2 + dt * 16 + r) * 64 + lane] = o[dt][r];
-    }
+        for (int r = 0; r < 16; ++r) {
+            // kh is wave-uniform: select the register of the tile the other wave owns without dynamic indexing
+            const float mine_low = o[t][r], mine_high = o[NP + t][r];
+            park[(2 + t * 16 + r) * 64 + lane] = kh == 0 ? mine_high : mine_low;
+        }
     __syncthreads();
-    if (kh == 0) {
-        const float m1 = park[lane], l1 = park[64 + lane];
+    {
+        const float m1 = theirs[lane], l1 = theirs[64 + lane];
         const float mt = fmaxf(m, m1);                 // finite unless a bias of -inf covers the whole row
         const float a0 = __builtin_amdgcn_exp2f(m - mt), a1 = __builtin_amdgcn_exp2f(m1 - mt);
         const float inv = 1.0f / (l * a0 + l1 * a1);
         const float w0 = a0 * inv, w1 = a1 * inv;
 #pragma unroll
-        for (int dt = 0; dt < 2 * NP; ++dt)
+        for (int t = 0; t < NP; ++t) {
+            f32x16 acc;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] = o[dt][r] * w0 + park[(2 + dt * 16 + r) * 64 + lane] * w1;
-        if (q_row < S) {
-#pragma unroll
-            for (int dt = 0; dt < 2 * NP; ++dt)
+            for (int r = 0; r < 16; ++r)
+                acc[r] = (kh == 0 ? o[t][r] : o[NP + t][r]) * w0 + theirs[(2 + t * 16 + r) * 64 + lane] * w1;
+            if (q_row < S) {
+                const int dt = kh * NP + t;
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const int d = dt * 32 + 8 * gq + 4 * h;
                     *reinterpret_cast<uint2*>(O + (long)q_row * stride_s + d) =
-                        make_uint2(pack_bf16(o[dt][4 * gq], o[dt][4 * gq + 1]), pack_bf16(o[dt][4 * gq + 2], o[dt][4 * gq + 3]));
+                        make_uint2(pack_bf16(acc[4 * gq], acc[4 * gq + 1]), pack_bf16(acc[4 * gq + 2], acc[4 * gq + 3]));
                 }
+            }
         }
     }
 }
