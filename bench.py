@@ -32,7 +32,7 @@ PEAK_F32_TFLOPS = 157.3       # fp32 MFMA / vector
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the fused FFN kernel at the benchmark shape: FETCH_SIZE + WRITE_SIZE from
 # rocprofv3 --pmc, scaled by a 256 MiB copy (profiles/bench_all_fused_subgraphs.md).
-FFN_TRAFFIC_BYTES = 85111388
+FFN_TRAFFIC_BYTES = 85080717
 
 
 def parse():
