@@ -271,7 +271,9 @@ ago_status ago_bmm_nn(const void* a, const void* b, void* c, long batch, int M, 
  * intermediate tensor written to `workspace` (device) and read back by the next kernel.
  * epilogue_fused == 0: one kernel per operator, simple operators included (Fig. 3);
  * epilogue_fused != 0: each complex operator with its bias/activation/residual fused
- * (Fig. 4, the paper's "conventional fusion").  Arguments as in the fused calls. */
+ * (Fig. 4, the paper's "conventional fusion").  Arguments as in the fused calls.
+ * ago_unfused_attn takes any S <= 4096: the rows of the score and probability matrices in the
+ * workspace are padded to a multiple of 8 elements, the pad columns count as -inf in the softmax. */
 ago_status ago_unfused_invres(const void* x, const void* w1, const float* b1,
                               const void* wd, const float* bd,
                               const void* w2, const float* b2, void* y,

@@ -489,22 +489,27 @@ ago_status ago_unfused_attn(const void* q, const void* k, const void* v, void* o
                             int D, float scale, ago_dtype dt, int epilogue_fused, void* workspace,
                             size_t workspace_bytes, void* s) {
     AGO_TRY(check_attn(q, k, v, o, B, Hh, S, D, scale, dt));
-    if (S % 8 || !fits31(S, S, 1, 1)) return AGO_ERR_UNSUPPORTED;
+    // Rows of the score / probability matrices are padded to a multiple of 8 elements (16-byte accesses)
+    // in the workspace: the softmax treats the pad columns as -inf and writes them as 0, so the second
+    // product may read whole 16-byte chunks of a row.
+    const int Sp = (S + 7) & ~7;
+    if (Sp > 4096 || !fits31(S, Sp, 1, 1) || (long)B * Hh > 65535) return AGO_ERR_UNSUPPORTED;
     const int dims[4] = {B, Hh, S, D};
     AGO_TRY(check_workspace(workspace, workspace_bytes, ago::workspace_bytes(AGO_OP_UNFUSED_ATTN, dims, 4, dt)));
     // scores stay fp32 (the softmax is an fp32 operator); the probabilities are rounded to bf16
     // because they feed a bf16 matrix product
     const long batch = (long)B * Hh;
+    hipStream_t st = as_stream(s);
     void* sc = workspace;
-    void* pr = static_cast<char*>(workspace) + (size_t)batch * S * S * 4;
+    void* pr = static_cast<char*>(workspace) + (size_t)batch * S * Sp * 4;
     if (epilogue_fused) {
-        AGO_TRY(ago_bmm_nt(q, k, sc, batch, S, S, D, scale, dt, AGO_F32, s));
+        AGO_TRY(from_hip(bmm_nt_bf16(q, k, sc, batch, S, S, D, scale, true, st, Sp)));
     } else {
-        AGO_TRY(ago_bmm_nt(q, k, sc, batch, S, S, D, 1.0f, dt, AGO_F32, s));
-        AGO_TRY(ago_scale(sc, sc, batch * S * S, scale, AGO_F32, s));
+        AGO_TRY(from_hip(bmm_nt_bf16(q, k, sc, batch, S, S, D, 1.0f, true, st, Sp)));
+        AGO_TRY(from_hip(ago::scale(sc, sc, batch * S * Sp, scale, false, st)));
     }
-    AGO_TRY(ago_softmax_rows(sc, pr, batch * S, S, AGO_F32, dt, s));
-    AGO_TRY(ago_bmm_nn(pr, v, o, batch, S, D, S, dt, s));
+    AGO_TRY(from_hip(softmax_rows(sc, pr, batch * S, S, false, true, st, Sp)));
+    AGO_TRY(from_hip(bmm_nn_bf16(pr, v, o, batch, S, D, S, st, Sp)));
     return AGO_OK;
 }
 

@@ -80,12 +80,12 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // One wave per row; the row (cols <= 4096) lives in registers: 8 elements per lane per pass.
 template <bool BF16, bool OUT_BF16>
-__global__ __launch_bounds__(256) void softmax_rows_kernel(const void* x, void* y, long rows, int cols) {
+__global__ __launch_bounds__(256) void softmax_rows_kernel(const void* x, void* y, long rows, int cols, int ld) {
     constexpr int MAXP = 8;  // 8 passes x 64 lanes x 8 elements = 4096 columns
     const int lane = threadIdx.x & 63;
     const long row = blockIdx.x * 4L + (threadIdx.x >> 6);
     if (row >= rows) return;
-    const int c8 = cols / 8;
+    const int c8 = ld / 8;          // rows are ld elements apart; columns cols .. ld - 1 count as -inf and are written as 0
     const long base8 = row * c8;
     Vec8<BF16> v[MAXP];
     float m = -INFINITY;
@@ -95,7 +95,10 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(const void* x, void* 
         if (idx < c8) {
             v[p].load(x, base8 + idx);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) m = fmaxf(m, v[p].v[e]);
+            for (int e = 0; e < 8; ++e) {
+                if (8 * idx + e >= cols) v[p].v[e] = -INFINITY;
+                m = fmaxf(m, v[p].v[e]);
+            }
         }
     }
     m = wave_max(m);
@@ -153,11 +156,12 @@ hipError_t scale(const void* x, void* y, long n, float alpha, bool bf16, hipStre
 }
 
 hipError_t softmax_rows(const void* x, void* y, long rows, int cols, bool in_bf16, bool out_bf16,
-                        hipStream_t s) {
+                        hipStream_t s, int ld) {
+    if (ld == 0) ld = cols;
     const unsigned grid = (unsigned)((rows + 3) / 4);
-    if (in_bf16 && out_bf16) hipLaunchKernelGGL((softmax_rows_kernel<true, true>), dim3(grid), dim3(256), 0, s, x, y, rows, cols);
-    else if (!in_bf16 && out_bf16) hipLaunchKernelGGL((softmax_rows_kernel<false, true>), dim3(grid), dim3(256), 0, s, x, y, rows, cols);
-    else if (!in_bf16 && !out_bf16) hipLaunchKernelGGL((softmax_rows_kernel<false, false>), dim3(grid), dim3(256), 0, s, x, y, rows, cols);
+    if (in_bf16 && out_bf16) hipLaunchKernelGGL((softmax_rows_kernel<true, true>), dim3(grid), dim3(256), 0, s, x, y, rows, cols, ld);
+    else if (!in_bf16 && out_bf16) hipLaunchKernelGGL((softmax_rows_kernel<false, true>), dim3(grid), dim3(256), 0, s, x, y, rows, cols, ld);
+    else if (!in_bf16 && !out_bf16) hipLaunchKernelGGL((softmax_rows_kernel<false, false>), dim3(grid), dim3(256), 0, s, x, y, rows, cols, ld);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -357,13 +357,7 @@ static hipError_t launch_attn(const void* q, const void* k, const void* v, void*
     constexpr size_t smem = (size_t)NSTG * 2 * NP * kPlaneB;    // ring of (K block, V block) buffers; the merge reuses them
     static_assert((size_t)NQT * (2 + 32 * NP) * 64 * 4 <= smem, "merge scratch");
     auto kern = fused_attn_kernel<NQT, NSTG, BIAS, NP>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = allow_dynamic_lds<fused_attn_kernel<NQT, NSTG, BIAS, NP>>((int)((int)smem)); e != hipSuccess) return e;
     const int heads = B * Hh, qblocks = (S + 32 * NQT - 1) / (32 * NQT);
     dim3 grid((unsigned)(8 * qblocks * ((heads + 7) / 8)));
     prof_start(3, s);

@@ -311,13 +311,7 @@ static hipError_t launch_chain(const void* x, const void* wa, const float* ba, c
     constexpr size_t smem = ChainGeom<TH, TW>::kSmem;
     static_assert(smem <= 160 * 1024, "LDS");
     auto kern = fused_conv_chain_kernel<TH, TW>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = allow_dynamic_lds<fused_conv_chain_kernel<TH, TW>>((int)((int)smem)); e != hipSuccess) return e;
     const int tiles_h = (H + TH - 1) / TH, tiles_w = (W + TW - 1) / TW;
     prof_start(1, s);
     prof_shape(1, (unsigned)(N * tiles_h * tiles_w), 1024);

@@ -132,13 +132,7 @@ hipError_t launch_dw_dw(const void* x, const void* wa, const float* ba, const vo
     constexpr size_t smem = (size_t)(IH * IW + RH * RW + 18 + 2) * Q * 16;
     static_assert(smem <= 160 * 1024, "LDS");
     auto kern = fused_dw_dw_kernel<BF16, STRIDE>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = allow_dynamic_lds<fused_dw_dw_kernel<BF16, STRIDE>>((int)((int)smem)); e != hipSuccess) return e;
     const int OH = (H - 1) / STRIDE + 1, OW = (W - 1) / STRIDE + 1;
     const int tiles_h = (OH + kDwTH - 1) / kDwTH, tiles_w = (OW + kDwTW - 1) / kDwTW;
     const int cblocks = (C + kDwCB - 1) / kDwCB;

@@ -316,23 +316,17 @@ static hipError_t launch_ffn(const void* x, const void* w1, const float* b1, con
                              void* workspace, hipStream_t s) {
     typedef FfnCfg<BM, FS, BN2> Cfg;
     auto kern = fused_ffn_kernel<BM, FS, BN2>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kSmem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = allow_dynamic_lds<fused_ffn_kernel<BM, FS, BN2>>((int)((int)Cfg::kSmem)); e != hipSuccess) return e;
     const int nsplit = F / FS;
     dim3 grid(nsplit, (M + BM - 1) / BM);
     prof_start(2, s);
     prof_shape(2, grid.x * grid.y, kFfnThreads);
     hipLaunchKernelGGL(kern, grid, dim3(kFfnThreads), Cfg::kSmem, s, (const bf16_t*)x, (const bf16_t*)w1, b1,
                        (const bf16_t*)w2, b2, (bf16_t*)y, (float*)workspace, M, K, F, K2, act);
-    prof_stop(2, s);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || nsplit == 1) return e;
-    return ffn_reduce((const float*)workspace, b2, y, (long)M * K2, K2, nsplit, s);
+    if (e == hipSuccess && nsplit != 1) e = ffn_reduce((const float*)workspace, b2, y, (long)M * K2, K2, nsplit, s);
+    prof_stop(2, s);      // the event pair brackets the whole entry point, the reduction included
+    return e;
 }
 
 // Tile configurations (BM rows, FS hidden slice, phase-2 column block BN2):

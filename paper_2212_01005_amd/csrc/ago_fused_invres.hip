@@ -649,17 +649,10 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
 #define AGO_LAUNCH_INVRES_KC(BF, ST, KS, CH, SP)                                                        \
     do {                                                                                                \
         auto kern = fused_invres_kernel<BF, ST, KS, CH, SP>;                                            \
-        static bool attr_set = false;                                                                   \
-        if (!attr_set) {                                                                                \
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                     \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax); \
-            if (e != hipSuccess) return e;                                                              \
-            attr_set = true;                                                                            \
-        }                                                                                               \
+        if (hipError_t e = allow_dynamic_lds<fused_invres_kernel<BF, ST, KS, CH, SP>>((int)kLdsMax); e != hipSuccess) return e; \
         prof_start(0, s);                                                                               \
         prof_shape(0, grid.x * grid.y, kInvresThreads);                                                 \
         hipLaunchKernelGGL(kern, grid, dim3(kInvresThreads), smem, s, p);                               \
-        prof_stop(0, s);                                                                                \
     } while (0)
 #define AGO_LAUNCH_INVRES_K(BF, ST, KS)                                                                 \
     do {                                                                                                \
@@ -677,7 +670,10 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
 #undef AGO_LAUNCH_INVRES_K
 #undef AGO_LAUNCH_INVRES_KC
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || !split) return e;
+    if (e != hipSuccess || !split) {
+        prof_stop(0, s);
+        return e;
+    }
     // sum the partial projections; b2 and the residual were left to this pass
     const long total = (long)N * p.OH * p.OW * Cout;
     const unsigned rgrid = (unsigned)((total / 4 + 255) / 256);
@@ -687,6 +683,7 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
     else
         hipLaunchKernelGGL(invres_reduce_kernel<false>, dim3(rgrid), dim3(256), 0, s, p.part, b2, residual ? x : nullptr, y,
                            total, Cout, p.nsplit);
+    prof_stop(0, s);      // the event pair brackets the whole entry point, the reduction included
     return hipGetLastError();
 }
 

@@ -134,13 +134,7 @@ hipError_t fused_qkv(const void* x, const void* wq, const void* wk, const void* 
     p.nb = (p.N + 127) / 128;
     p.head_major = head_major;
     constexpr size_t smem = (size_t)2 * (128 + 128) * (64 + 8) * sizeof(bf16_t);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_qkv_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = allow_dynamic_lds<fused_qkv_kernel>((int)smem); e != hipSuccess) return e;
     dim3 grid((unsigned)(3 * p.nb), (unsigned)((p.M + 127) / 128));
     hipLaunchKernelGGL(fused_qkv_kernel, grid, dim3(256), smem, s, p);
     return hipGetLastError();

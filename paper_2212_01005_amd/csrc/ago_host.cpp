@@ -174,8 +174,8 @@ size_t workspace_bytes(int op, const int* d, int nd, int dt) {
             return nd < 4 ? 0 : (size_t)d[0] * d[1] * d[2] * d[3] * es;
         case AGO_OP_UNFUSED_FFN:          // hidden [M,F]
             return nd < 4 ? 0 : (size_t)d[0] * d[2] * es;
-        case AGO_OP_UNFUSED_ATTN:         // scores [B,Hh,S,S] fp32 + probabilities in the storage type
-            return nd < 4 ? 0 : (size_t)d[0] * d[1] * d[2] * d[2] * (4 + es);
+        case AGO_OP_UNFUSED_ATTN:         // scores [B,Hh,S,Sp] fp32 + probabilities in the storage type, Sp = S rounded up to 8
+            return nd < 4 ? 0 : (size_t)d[0] * d[1] * d[2] * ((d[2] + 7) & ~7) * (4 + es);
         default:
             return 0;
     }

@@ -3,8 +3,21 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
+#include <mutex>
 
 namespace ago {
+
+// Raises the dynamic-LDS limit of kernel Kern once per process; several host threads may make the first call
+// together.  (The first call of an entry point must therefore come outside a stream capture.)
+template <auto Kern>
+inline hipError_t allow_dynamic_lds(int bytes) {
+    static std::once_flag once;
+    static hipError_t err = hipSuccess;
+    std::call_once(once, [&] {
+        err = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    });
+    return err;
+}
 
 // un-fused operators
 hipError_t gemm_bf16(const void* a, const void* b, const float* bias, const void* res, void* c, int M,
@@ -12,9 +25,9 @@ hipError_t gemm_bf16(const void* a, const void* b, const float* bias, const void
 hipError_t gemm_f32(const void* a, const void* b, const float* bias, const void* res, void* c, int M,
                     int K, int N, int act, hipStream_t s);
 hipError_t bmm_nt_bf16(const void* a, const void* b, void* c, long batch, int M, int N, int K,
-                       float alpha, bool out_f32, hipStream_t s);
+                       float alpha, bool out_f32, hipStream_t s, int ldc = 0);   // ldc: elements per row of c (0 = N)
 hipError_t bmm_nn_bf16(const void* a, const void* b, void* c, long batch, int M, int N, int K,
-                       hipStream_t s);
+                       hipStream_t s, int lda = 0);   // lda: elements per row of a (0 = K), a multiple of 8; the row tail holds zeros
 hipError_t dwconv3x3(const void* x, const void* w, const float* bias, void* y, int N, int H, int W,
                      int C, int stride, int act, bool bf16, hipStream_t s);
 hipError_t conv3x3_bf16(const void* x, const void* w, const float* bias, const void* res, void* y,
@@ -24,7 +37,7 @@ hipError_t bias_act(const void* x, const float* bias, void* y, long P, int C, in
 hipError_t add_act(const void* a, const void* b, void* y, long n, int act, bool bf16, hipStream_t s);
 hipError_t scale(const void* x, void* y, long n, float alpha, bool bf16, hipStream_t s);
 hipError_t softmax_rows(const void* x, void* y, long rows, int cols, bool in_bf16, bool out_bf16,
-                        hipStream_t s);
+                        hipStream_t s, int ld = 0);   // ld: elements per row of x and y (0 = cols), a multiple of 8; y's row tail is written as 0
 
 // fused subgraphs
 hipError_t fused_invres(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,

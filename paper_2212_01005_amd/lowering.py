@@ -233,8 +233,15 @@ def _admissible(g, kind, ids):
         return not has_add or dws[0].attrs.get("stride", 1) == 1
     if kind == "conv_chain":
         return g.dtype == "bf16" and g.params[nodes[0].attrs["w"]].shape[2] == 64
-    if kind in ("ffn", "attn"):
+    if kind == "ffn":
         return g.dtype == "bf16"
+    if kind == "attn":
+        # the kernel computes softmax(alpha * in0 * in1^T) * v: the probabilities must be the first operand of
+        # the second product, alpha positive, head dimension one the kernel has; anything else runs operator by operator
+        t, sc, sm, nn = nodes
+        head_dim = infer_shapes(g)[t.inputs[0]][-1]
+        return (g.dtype == "bf16" and nn.inputs[0] == ids[2] and sm.inputs[0] == ids[1] and sc.inputs[0] == ids[0]
+                and float(sc.attrs.get("alpha", 0.0)) > 0.0 and head_dim in (64, 128))
     return True
 
 

@@ -6,6 +6,8 @@ fp32 accumulation.  "Relative" is taken per element against max(|oracle_i|, rms(
 exact zeros after a ReLU and sign changes do not make the ratio meaningless.
 """
 
+import warnings
+
 import numpy as np
 import pytest
 
@@ -58,8 +60,6 @@ def test_fused_matches_oracle(gpu, oracle, case):
 @pytest.mark.parametrize("case", _cases(), ids=lambda c: c.name)
 def test_unfused_matches_oracle(gpu, oracle, case, epilogue_fused):
     torch, ago, runner = gpu
-    if type(case).__name__ == "AttnCase" and case.S % 8:
-        pytest.skip("un-fused attention needs S % 8 == 0 (16-byte rows of the score matrix)")
     t = runner.to_device(case)
     y = runner.alloc_output(case)
     ws = runner.alloc_workspace(case, fused=False)
@@ -306,7 +306,7 @@ def test_invres_channel_split(gpu, oracle):
 
 
 def test_invres_planner_choice_is_near_the_best_candidate(gpu):
-    """The built-in tile choice (cost model) is timed against every selectable tile on three shapes the
+    """Report only (a warning, never a failure).  The built-in tile choice (cost model) is timed against every selectable tile on three shapes the
     model was not tuned for one by one: a latency-bound single image, a batch that fills the chip several
     times over, a chunked wide block, and a wide block on one image (channel split, with workspace)."""
     torch, ago, runner = gpu
@@ -344,7 +344,9 @@ def test_invres_planner_choice_is_near_the_best_candidate(gpu):
             ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
         best = min(v for k, v in times.items() if k >= 0)
         print("%s built-in %.2f us, best candidate %.2f us" % (case.name, times[-1], best))
-        assert times[-1] <= 1.25 * best + 1.0, (case.name, times)
+        # a timing is not a correctness result: a slow choice is reported, it does not fail the parity run
+        if times[-1] > 1.25 * best + 1.0:
+            warnings.warn("planner choice for %s: %.2f us against %.2f us for the best candidate" % (case.name, times[-1], best))
 
 
 def test_ffn_ragged_hidden_slices_and_column_blocks(gpu, oracle):
@@ -399,7 +401,7 @@ def test_sibling_qkv_projection(gpu, oracle):
     ago.ago_fused_attn(q, k, v, o, 0.125)
     torch.cuda.synchronize()
     rq, rk, rv = (wl.round_to_bf16(a) for a in oracle.run_case(case))
-    assert_close(runner.to_numpy64(o), oracle.attn(rq, rk, rv, 0.125), "bf16", case.name, scale=1.5)
+    assert_close(runner.to_numpy64(o), oracle.attn(rq, rk, rv, 0.125), "bf16", case.name)
 
 
 def test_attention_head_dim_128(gpu, oracle):
@@ -588,7 +590,10 @@ def _store(arr, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("shape", [(200, 72, 136), (64, 768, 64), (333, 256, 320)])
+@pytest.mark.parametrize("shape", [(200, 72, 136), (64, 768, 64), (333, 256, 320),
+                                   # shapes that tile exactly take the k-split kernels: 128 x 192 tiles with an even and an
+                                   # odd number of k tiles, 64 x 96 tiles with one and with three k tiles
+                                   (2048, 128, 3072), (2048, 192, 3072), (1024, 128, 768), (1024, 384, 768)])
 def test_gemm_op(gpu, oracle, dtype, shape):
     torch, ago, runner = gpu
     M, K, N = shape

@@ -163,6 +163,33 @@ def test_plan_for_transformer_pieces():
     assert "ffn" not in [k for k, _ in L.lower(g2, part2)]
 
 
+def _attn_chain_graph(swap_second_product=False, alpha=0.125, head_dim=64):
+    g = L.Graph([], {}, "bf16")
+    q = g.add("input", name="q", shape=(2, 2, 96, head_dim))
+    k = g.add("input", name="k", shape=(2, 2, 96, head_dim))
+    v = g.add("input", name="v", shape=(2, 2, 64, 96) if swap_second_product else (2, 2, 96, head_dim))
+    s = g.add("bmm_nt", [q, k])
+    s = g.add("scale", [s], alpha=alpha)
+    s = g.add("softmax", [s])
+    g.add("bmm_nn", [v, s] if swap_second_product else [s, v])      # v' * P: the probabilities are the second operand
+    return g
+
+
+def test_attention_chain_is_fused_only_in_the_form_the_kernel_computes():
+    """softmax(alpha q k^T) v with the probabilities as the first operand, alpha > 0 and a head dimension the
+    kernel has is one launch; the same operators wired differently stay operator by operator."""
+    from paper_2212_01005_amd import binding as ago
+    def kinds(g):
+        part, _ = L.partition(g, ago)
+        return [k for k, _ in L.lower(g, part)]
+    assert kinds(_attn_chain_graph()) == ["attn"]
+    assert kinds(_attn_chain_graph(head_dim=128)) == ["attn"]
+    for g in (_attn_chain_graph(swap_second_product=True), _attn_chain_graph(alpha=-0.125),
+              _attn_chain_graph(alpha=0.0), _attn_chain_graph(head_dim=32)):
+        assert "attn" not in kinds(g)
+        assert kinds(g).count("op") == 4
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("fuse", [True, False])

@@ -21,7 +21,8 @@ from workloads import rng
 
 
 # --------------------------------------------------------------------------
-# brute force in the paper's index form: Conv[n,o,h,w] += Inp[n,ri,h+rr,w+rc] * Weight[o,ri,rr,rc]
+# brute force in the paper's index form (Sec. III-A, Fig. 3): NCHW input, OIHW weight, the window walks
+# the input forwards from the output position (cross-correlation)
 # --------------------------------------------------------------------------
 
 def _pad_nchw(inp, pad):
