@@ -98,6 +98,24 @@ ago_status ago_fused_invres_k(const void* x, const void* w1, const float* b1,
                               int stride, int ksize, int residual, ago_dtype dt,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): ago_fused_invres_k with the channel-split partial sums kept in a
+ * buffer the library owns (a file-scope device array of AGO_NOALLOC_SCRATCH_BYTES; every GPU the library
+ * runs on holds its own copy until the process ends) instead of a caller workspace.  The call allocates
+ * and frees nothing.  Same arguments, result and restrictions as ago_fused_invres_k given the workspace
+ * ago_workspace_bytes(AGO_OP_FUSED_INVRES, ...) asks for; shapes for which that size exceeds
+ * AGO_NOALLOC_SCRATCH_BYTES return AGO_ERR_WORKSPACE before any GPU work.  All calls on one GPU share
+ * the buffer (every launch overwrites what it later reads, nothing has to be cleared): two such calls
+ * that overlap in time on one GPU (different streams or host threads) race; calls ordered on one stream
+ * do not.  The first call on a device looks up the buffer's address (hipGetSymbolAddress). */
+#define AGO_NOALLOC_SCRATCH_BYTES ((size_t)4 << 20)
+ago_status ago_fused_invres_noalloc(const void* x, const void* w1, const float* b1,
+                                    const void* wd, const float* bd,
+                                    const void* w2, const float* b2, void* y,
+                                    int N, int H, int W, int Cin, int Cexp, int Cout,
+                                    int stride, int ksize, int residual, ago_dtype dt,
+                                    void* hip_stream);
+
 /* Host-only: the tiling ago_fused_invres[_k] would launch for this shape (no GPU call).  The tile
  * is the candidate with the lowest predicted time of a cost model fitted to MI355X measurements
  * (the tile-size trade-off of Sec. III-B / Fig. 7a: re-computed halo against parallelism), or the

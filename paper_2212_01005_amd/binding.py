@@ -33,6 +33,7 @@ _SIGS = {
     "ago_fused_invres": [_vp] * 8 + [_i] * 9 + [_vp, _sz, _vp],
     "ago_fused_invres_plan": [_i] * 9 + [_sz, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)],
     "ago_fused_invres_k": [_vp] * 8 + [_i] * 10 + [_vp, _sz, _vp],
+    "ago_fused_invres_noalloc": [_vp] * 8 + [_i] * 10 + [_vp],
     "ago_fused_conv_chain": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_ffn": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_attn": [_vp] * 4 + [_i] * 4 + [_f, _i, _vp, _sz, _vp],
@@ -298,6 +299,22 @@ def ago_fused_invres_k(x, w1, b1, wd, bd, w2, b2, y, stride, residual, workspace
     return lib.ago_fused_invres_k, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
                                     N, H, W, Cin, Cexp, Cout, stride, int(wd.shape[0]), int(residual), _dt(x),
                                     wp, wb, _stream())
+
+
+NOALLOC_SCRATCH_BYTES = 4 << 20
+
+
+@_entry
+def ago_fused_invres_noalloc(x, w1, b1, wd, bd, w2, b2, y, stride, residual):
+    """ago_fused_invres_k without a workspace argument: the partial sums live in a buffer the library owns."""
+    N, H, W, Cin = x.shape
+    Cexp, Cout = w2.shape
+    if wd.shape[0] != wd.shape[1]:
+        raise ValueError("square depthwise kernels only")
+    _want_invres(x, w1, b1, wd, bd, w2, b2, y, stride, int(wd.shape[0]))
+    return lib.ago_fused_invres_noalloc, (_p(x), _p(w1), _p(b1), _p(wd), _p(bd), _p(w2), _p(b2), _p(y),
+                                          N, H, W, Cin, Cexp, Cout, stride, int(wd.shape[0]), int(residual), _dt(x),
+                                          _stream())
 
 
 @_entry

@@ -1,5 +1,6 @@
 // C ABI entry points: validate on the host (no HIP call before validation passes), then launch.
 #include <hip/hip_runtime.h>
+#include <mutex>
 #include <vector>
 #include "ago_host.hpp"
 #include "ago_launch.hpp"
@@ -38,6 +39,31 @@ void prof_stop(int op, hipStream_t s) {
 }
 void prof_shape(int op, unsigned grid, unsigned block) { g_last_grid[op] = grid; g_last_block[op] = block; }
 }  // namespace ago
+
+// ---------------------------------------------------------------- scratch owned by the library
+// ago_fused_invres_noalloc keeps its cross-workgroup partial sums here instead of in a caller workspace.
+// Every GPU the library runs on holds its own copy of the array until the process ends.  In host code the
+// array's name is only a stand-in: the device address comes from hipGetSymbolAddress, once per device.
+namespace {
+static __device__ __align__(256) unsigned char scratch[AGO_NOALLOC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+hipError_t scratch_address(void** out) {
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
 
 extern "C" {
 
@@ -138,6 +164,22 @@ ago_status ago_fused_invres_k(const void* x, const void* w1, const float* b1, co
     return from_hip(fused_invres(x, w1, b1, wd, bd, w2, b2, y, N, H, W, Cin, Cexp, Cout, stride,
                                  residual, dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES),
                                  as_stream(hip_stream), 0, ksize, workspace, workspace_bytes));
+}
+
+ago_status ago_fused_invres_noalloc(const void* x, const void* w1, const float* b1, const void* wd,
+                                    const float* bd, const void* w2, const float* b2, void* y, int N, int H,
+                                    int W, int Cin, int Cexp, int Cout, int stride, int ksize, int residual,
+                                    ago_dtype dt, void* hip_stream) {
+    ago_status st = check_invres(x, w1, wd, w2, y, b1, bd, b2, N, H, W, Cin, Cexp, Cout, stride, residual, dt);
+    if (st != AGO_OK) return st;
+    if (ksize != 3 && ksize != 5) return AGO_ERR_UNSUPPORTED;
+    const int dims[8] = {N, H, W, Cin, Cexp, Cout, stride, ksize};
+    if (ago::workspace_bytes(AGO_OP_FUSED_INVRES, dims, 8, dt) > AGO_NOALLOC_SCRATCH_BYTES) return AGO_ERR_WORKSPACE;
+    void* ptr = nullptr;
+    if (hipError_t e = scratch_address(&ptr); e != hipSuccess) return from_hip(e);
+    return from_hip(fused_invres(x, w1, b1, wd, bd, w2, b2, y, N, H, W, Cin, Cexp, Cout, stride,
+                                 residual, dt == AGO_BF16, tile_config(AGO_OP_FUSED_INVRES),
+                                 as_stream(hip_stream), 0, ksize, ptr, AGO_NOALLOC_SCRATCH_BYTES));
 }
 
 ago_status ago_fused_invres_plan(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize,

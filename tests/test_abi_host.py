@@ -114,6 +114,21 @@ def test_pair_entry_points_validate_before_any_gpu_call(lib):
         ago.workspace_bytes(ago.OP_FUSED_FFN, [64, 64, 768, 128], ago.BF16) > 0
 
 
+def test_noalloc_entry_point_refuses_what_its_buffer_cannot_hold(lib):
+    """ago_fused_invres_noalloc validates like ago_fused_invres_k and returns AGO_ERR_WORKSPACE (6), before any GPU
+    call, when the partial sums of the preferred plan exceed the library's own scratch buffer."""
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    p = _fake()
+    lib.ago_fused_invres_noalloc.argtypes = [vp] * 8 + [ci] * 10 + [vp]
+    call = lambda N, H, W, Cin, Cexp, Cout, st=1, ks=3, res=0, dt=1, x=p: lib.ago_fused_invres_noalloc(
+        x, p, None, p, None, p, None, p, N, H, W, Cin, Cexp, Cout, st, ks, res, dt, None)
+    assert call(1, 7, 7, 160, 960, 160, x=None) == 1
+    assert call(1, 7, 7, 160, 960, 160, st=3) == 2
+    assert call(1, 7, 7, 160, 960, 160, ks=4) == 5
+    assert call(1, 7, 7, 160, 960, 160, x=_fake(0x1004)) == 4
+    assert call(32, 7, 7, 160, 960, 160) == 6            # 8 slices x 32 x 7 x 7 x 160 x 4 bytes > 4 MiB
+
+
 def test_validation_runs_before_any_gpu_call(lib):
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.ago_fused_ffn.argtypes = [vp] * 6 + [ci] * 6 + [vp, sz, vp]
