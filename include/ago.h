@@ -345,6 +345,10 @@ int ago_num_tile_configs(ago_op op);
 int ago_profile_enable(int capacity);
 int ago_profile_select(unsigned op_mask);
 int ago_profile_read(ago_op op, float* total_ms, int* count);
+/* The same, and first_kernel_ms (host, may be NULL): the part of total_ms up to the end of the entry point's first
+ * kernel, for entry points that launch two (the FFN chain with several hidden slices: streaming kernel, then the
+ * partial-sum reduction); equal to total_ms otherwise. */
+int ago_profile_read_split(ago_op op, float* total_ms, float* first_kernel_ms, int* count);
 /* Average elapsed time in milliseconds of `pairs` (1..1024) event pairs recorded back to back on
  * `hip_stream` with nothing between them: the fixed cost an event pair adds to what it brackets.
  * Synchronises on the events.  Returns a negative value on misuse / a HIP error. */
@@ -356,17 +360,36 @@ float ago_profile_event_overhead_ms(void* hip_stream, int pairs);
  * Both return 0, or -1 on misuse / a HIP error. */
 int ago_profile_last_launch(ago_op op, int* grid, int* block);
 int ago_bench_empty_kernel(int grid, int block, void* hip_stream);
+/* Measured matrix-core peak: enqueues a kernel of matrix instructions only (one workgroup of eight waves per compute
+ * unit, six independent accumulators per wave, `iters` rounds; AGO_BF16: 32x32x16 bf16, AGO_F32: 32x32x2 fp32) and
+ * writes the FLOPs it executes to *flops (host).  out: device scratch of at least compute units x 2048 bytes.
+ * Time it with events: FLOPs / time is what bench.py reports as the measured peak beside the data-sheet one.
+ * (The measured memory peak uses ago_scale with alpha = 1 as a plain copy.) */
+int ago_bench_mfma_kernel(ago_dtype dt, int iters, void* out, size_t out_bytes, double* flops, void* hip_stream);
 
-/* Host-only: whether running matmul -> activation -> matmul as one fused kernel (ago_fused_ffn) is
- * expected to beat the two products with fused epilogues (ago_unfused_ffn, epilogue_fused = 1) on
- * MI355X: the decision the paper leaves to its tuner, and its own caveat for this pair (Sec. VI-C,
- * Fig. 13d: fused, pw -> pw moves more data once the row count grows).  The fused kernel cuts the hidden
- * dimension into slices of 384 and writes one fp32 partial result per slice and row, so its extra traffic
- * grows with M * ceil(F / 384) while the un-fused pair only spills the hidden tensor once: measured, the
- * fused kernel is 1.7 - 2.8 x faster up to 2048 rows (K x F = 768 x 3072, 1024 x 4096, 512 x 2048) and
- * 0.6 - 0.85 x at 32768.  Returns 1 while the launch is at most 1024 workgroups of 64 rows x one slice
- * (512 when F or K2 is not a multiple of 384), else 0; -1 on non-positive sizes. */
 int ago_fused_ffn_pays(int M, int K, int F, int K2);
+
+/* Host-only planners for the other three fused kernels (no GPU call): the tile candidate a launch would use, chosen
+ * by an explicit time model whose recompute term is the redundancy algebra of Sec. III-B,
+ *     upstream work = | GS2/TS2 x (GS1/TS1 - GS2/TS2) | * | TS1 |
+ * (downstream tile loops x upstream loops the downstream nest lacks x upstream tile), the rest being counts of what
+ * the kernels execute times rates measured on an MI355X.  ago_set_tile_config pins the candidate instead.
+ * plan (host, 8 ints):
+ *   conv chain  {candidate, tile rows, tile columns, workgroups, workgroups resident per compute unit, rounds, 0, 1}
+ *   attention   {candidate, query rows per workgroup, keys per block, workgroups, resident, rounds, LDS bytes, 1}
+ *   FFN         {candidate, rows per workgroup, hidden units per slice, workgroups, resident, rounds, slices,
+ *                fuse (1) or run the two products with fused epilogues (0)}
+ * recompute (host, may be NULL): executed / algorithmic multiply-adds of the upstream operator under that tiling:
+ * (TH+2)(TW+2) tiles / (N H W) for the 3x3 chain (the |TS2| < |TS1| case of Sec. III-B; 1.469 for 7 x 14 tiles of a
+ * 56 x 56 image), exactly 1 for the two "downstream pointwise" tilings of Fig. 7b.
+ * predicted_us (host, may be NULL): the model's time for the fused launch; predicted_unfused_us: for the two
+ * un-fused products.  ago_fused_ffn_pays returns the FFN plan's fuse decision (1 / 0; -1 on non-positive sizes):
+ * with few rows the fused kernel wins; once the rows fill the chip several times over, the fp32 partial sums of the
+ * hidden slices cost more than writing the hidden tensor once (the paper's own caveat for pw -> pw, Sec. VI-C). */
+ago_status ago_fused_conv_chain_plan(int N, int H, int W, int C, int plan[8], double* recompute, float* predicted_us);
+ago_status ago_fused_attn_plan(int B, int Hh, int S, int D, int plan[8], double* recompute, float* predicted_us);
+ago_status ago_fused_ffn_plan(int M, int K, int F, int K2, int plan[8], double* recompute, float* predicted_us,
+                              float* predicted_unfused_us);
 
 /* Redundancy model of Sec. III-B: number of times the upstream reduction body runs
  * when a conv R1xC1 (I -> O1) is fused under a downstream conv R2xC2 (O1 -> O2) whose

@@ -72,6 +72,12 @@ lib.ago_status_string.argtypes = [_i]
 lib.ago_status_string.restype = ctypes.c_char_p
 lib.ago_set_tile_config.argtypes = [_i, _i]
 lib.ago_set_tile_config.restype = _i
+_pd, _pf, _pi = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)
+lib.ago_fused_conv_chain_plan.argtypes = [_i] * 4 + [_pi, _pd, _pf]
+lib.ago_fused_attn_plan.argtypes = [_i] * 4 + [_pi, _pd, _pf]
+lib.ago_fused_ffn_plan.argtypes = [_i] * 4 + [_pi, _pd, _pf, _pf]
+for _n in ("ago_fused_conv_chain_plan", "ago_fused_attn_plan", "ago_fused_ffn_plan"):
+    getattr(lib, _n).restype = _i
 lib.ago_fused_ffn_pays.argtypes = [_i] * 4
 lib.ago_fused_ffn_pays.restype = _i
 lib.ago_num_tile_configs.argtypes = [_i]
@@ -87,6 +93,10 @@ lib.ago_profile_read.argtypes = [_i, ctypes.POINTER(_f), ctypes.POINTER(_i)]
 lib.ago_profile_read.restype = _i
 lib.ago_profile_last_launch.argtypes = [_i, ctypes.POINTER(_i), ctypes.POINTER(_i)]
 lib.ago_profile_last_launch.restype = _i
+lib.ago_profile_read_split.argtypes = [_i, ctypes.POINTER(_f), ctypes.POINTER(_f), ctypes.POINTER(_i)]
+lib.ago_profile_read_split.restype = _i
+lib.ago_bench_mfma_kernel.argtypes = [_i, _i, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]
+lib.ago_bench_mfma_kernel.restype = _i
 lib.ago_bench_empty_kernel.argtypes = [_i, _i, _vp]
 lib.ago_bench_empty_kernel.restype = _i
 lib.ago_profile_event_overhead_ms.argtypes = [_vp, _i]
@@ -107,7 +117,8 @@ lib.ago_graph_join.restype = _i
 EXPORTED = sorted(list(_SIGS) + ["ago_graph_op_weight", "ago_graph_topological_stage", "ago_graph_cluster",
                                  "ago_graph_split", "ago_graph_join"] + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
                                  "ago_num_tile_configs", "ago_fused_upstream_iterations", "ago_fused_ffn_pays",
-                                 "ago_profile_enable", "ago_profile_select", "ago_profile_read",
+                                 "ago_fused_conv_chain_plan", "ago_fused_attn_plan", "ago_fused_ffn_plan",
+                                 "ago_profile_enable", "ago_profile_select", "ago_profile_read", "ago_profile_read_split", "ago_bench_mfma_kernel",
                                  "ago_profile_event_overhead_ms", "ago_profile_last_launch",
                                  "ago_bench_empty_kernel"])
 
@@ -148,6 +159,37 @@ def workspace_bytes(op, dims, dt):
     return int(lib.ago_workspace_bytes(op, arr, len(dims), dt))
 
 
+def _plan(fn, dims, keys, unfused=False):
+    plan = (ctypes.c_int * 8)()
+    rec, us, us2 = ctypes.c_double(0.0), ctypes.c_float(0.0), ctypes.c_float(0.0)
+    args = [int(d) for d in dims] + [plan, ctypes.byref(rec), ctypes.byref(us)] + ([ctypes.byref(us2)] if unfused else [])
+    _chk(fn(*args))
+    d = dict(zip(keys, list(plan)))
+    d["recompute"], d["predicted_us"] = rec.value, us.value
+    if unfused:
+        d["predicted_unfused_us"] = us2.value
+    return d
+
+
+def fused_conv_chain_plan(N, H, W, C):
+    """Host-only: dict(config, tile_h, tile_w, workgroups, resident, rounds, recompute, predicted_us)."""
+    return _plan(lib.ago_fused_conv_chain_plan, (N, H, W, C),
+                 ("config", "tile_h", "tile_w", "workgroups", "resident", "rounds", "_", "fuse"))
+
+
+def fused_attn_plan(B, Hh, S, D):
+    """Host-only: dict(config, queries, key_block, workgroups, resident, rounds, lds_bytes, recompute, predicted_us)."""
+    return _plan(lib.ago_fused_attn_plan, (B, Hh, S, D),
+                 ("config", "queries", "key_block", "workgroups", "resident", "rounds", "lds_bytes", "fuse"))
+
+
+def fused_ffn_plan(M, K, F, K2):
+    """Host-only: dict(config, rows, slice, workgroups, resident, rounds, slices, fuse, recompute, predicted_us,
+    predicted_unfused_us)."""
+    return _plan(lib.ago_fused_ffn_plan, (M, K, F, K2),
+                 ("config", "rows", "slice", "workgroups", "resident", "rounds", "slices", "fuse"), unfused=True)
+
+
 def fused_ffn_pays(M, K, F, K2):
     """Host-only: True when the fused matmul -> activation -> matmul kernel is expected to beat the two
     products with fused epilogues at this size."""
@@ -181,6 +223,22 @@ def profile_read(op):
     if lib.ago_profile_read(op, ctypes.byref(ms), ctypes.byref(n)) != 0:
         raise RuntimeError("ago_profile_read failed")
     return float(ms.value), int(n.value)
+
+
+def profile_read_split(op):
+    """(total milliseconds, milliseconds up to the end of the entry point's first kernel, number of calls)."""
+    ms, ms1, n = _f(0.0), _f(0.0), _i(0)
+    if lib.ago_profile_read_split(op, ctypes.byref(ms), ctypes.byref(ms1), ctypes.byref(n)) != 0:
+        raise RuntimeError("ago_profile_read_split failed")
+    return float(ms.value), float(ms1.value), int(n.value)
+
+
+def bench_mfma_kernel(dtype, iters, out):
+    """Enqueue the matrix-instruction-only kernel on the current stream; returns the FLOPs it executes."""
+    fl = ctypes.c_double(0.0)
+    if lib.ago_bench_mfma_kernel(dtype, int(iters), _p(out), out.numel() * out.element_size(), ctypes.byref(fl), _stream()) != 0:
+        raise RuntimeError("ago_bench_mfma_kernel failed")
+    return float(fl.value)
 
 
 def profile_last_launch(op):

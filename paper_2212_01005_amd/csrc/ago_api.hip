@@ -4,6 +4,7 @@
 #include <vector>
 #include "ago_host.hpp"
 #include "ago_launch.hpp"
+#include "ago_dev.hpp"
 
 using namespace ago;
 
@@ -17,7 +18,8 @@ static inline size_t esize(ago_dtype dt) { return dt == AGO_BF16 ? 2 : 4; }
 // ---------------------------------------------------------------- instrumentation
 namespace {
 struct ProfRing {
-    std::vector<hipEvent_t> start, stop;
+    std::vector<hipEvent_t> start, mid, stop;      // mid: after the entry point's first kernel, when it launches two
+    std::vector<char> has_mid;
     long calls = 0;
 };
 ProfRing g_prof[4];
@@ -25,11 +27,50 @@ int g_prof_cap = 0;
 unsigned g_prof_mask = 0xFu;      // bit op: that fused entry point records events
 unsigned g_last_grid[4] = {0, 0, 0, 0}, g_last_block[4] = {0, 0, 0, 0};
 __global__ void empty_kernel() {}
+
+// Matrix-instruction-only loops: what the matrix cores sustain with every operand in registers.
+// bf16: six independent 32x32x16 accumulators per wave; fp32: six 32x32x2.
+template <bool BF16>
+__global__ __launch_bounds__(512) void mfma_only_kernel(float* out, int iters) {
+    ago::f32x16 acc[6];
+#pragma unroll
+    for (int j = 0; j < 6; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+    ago::bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (ago::bf16_t)(float)(threadIdx.x & 3); b[e] = (ago::bf16_t)(float)(e & 1); }
+    const float af = (float)(threadIdx.x & 3), bf = 0.5f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            if constexpr (BF16) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+            else acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af, bf, acc[j], 0, 0, 0);
+        }
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 6; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += acc[j][r];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
+}
 }  // namespace
 
 namespace ago {
 void prof_start(int op, hipStream_t s) {
-    if (g_prof_cap > 0 && ((g_prof_mask >> op) & 1u)) (void)hipEventRecord(g_prof[op].start[g_prof[op].calls % g_prof_cap], s);
+    if (g_prof_cap > 0 && ((g_prof_mask >> op) & 1u)) {
+        const long i = g_prof[op].calls % g_prof_cap;
+        g_prof[op].has_mid[i] = 0;
+        (void)hipEventRecord(g_prof[op].start[i], s);
+    }
+}
+void prof_mid(int op, hipStream_t s) {
+    if (g_prof_cap > 0 && ((g_prof_mask >> op) & 1u)) {
+        const long i = g_prof[op].calls % g_prof_cap;
+        (void)hipEventRecord(g_prof[op].mid[i], s);
+        g_prof[op].has_mid[i] = 1;
+    }
 }
 void prof_stop(int op, hipStream_t s) {
     if (g_prof_cap > 0 && ((g_prof_mask >> op) & 1u)) {
@@ -82,16 +123,18 @@ int ago_bench_empty_kernel(int grid, int block, void* hip_stream) {
 int ago_profile_enable(int capacity) {
     for (auto& r : g_prof) {
         for (hipEvent_t e : r.start) (void)hipEventDestroy(e);
+        for (hipEvent_t e : r.mid) (void)hipEventDestroy(e);
         for (hipEvent_t e : r.stop) (void)hipEventDestroy(e);
-        r.start.clear(); r.stop.clear(); r.calls = 0;
+        r.start.clear(); r.mid.clear(); r.stop.clear(); r.has_mid.clear(); r.calls = 0;
     }
     g_prof_cap = 0;
     if (capacity <= 0) return 0;
     if (capacity > 4096) return -1;
     for (auto& r : g_prof) {
-        r.start.resize(capacity); r.stop.resize(capacity);
+        r.start.resize(capacity); r.mid.resize(capacity); r.stop.resize(capacity); r.has_mid.assign(capacity, 0);
         for (int i = 0; i < capacity; ++i)
-            if (hipEventCreate(&r.start[i]) != hipSuccess || hipEventCreate(&r.stop[i]) != hipSuccess) return -1;
+            if (hipEventCreate(&r.start[i]) != hipSuccess || hipEventCreate(&r.mid[i]) != hipSuccess ||
+                hipEventCreate(&r.stop[i]) != hipSuccess) return -1;
     }
     g_prof_cap = capacity;
     return 0;
@@ -103,20 +146,45 @@ int ago_profile_select(unsigned op_mask) {
     return 0;
 }
 
-int ago_profile_read(ago_op op, float* total_ms, int* count) {
+int ago_profile_read_split(ago_op op, float* total_ms, float* first_kernel_ms, int* count) {
     if ((int)op < 0 || (int)op > 3 || !total_ms || !count || g_prof_cap <= 0) return -1;
     ProfRing& r = g_prof[(int)op];
     const int n = (int)(r.calls < g_prof_cap ? r.calls : g_prof_cap);
-    float tot = 0.f;
+    float tot = 0.f, first = 0.f;
     for (int i = 0; i < n; ++i) {
-        float ms = 0.f;
+        float ms = 0.f, ms1 = 0.f;
         if (hipEventSynchronize(r.stop[i]) != hipSuccess) return -1;
         if (hipEventElapsedTime(&ms, r.start[i], r.stop[i]) != hipSuccess) return -1;
+        if (r.has_mid[i]) {
+            if (hipEventElapsedTime(&ms1, r.start[i], r.mid[i]) != hipSuccess) return -1;
+        } else {
+            ms1 = ms;
+        }
         tot += ms;
+        first += ms1;
     }
     *total_ms = tot; *count = n;
+    if (first_kernel_ms) *first_kernel_ms = first;
     r.calls = 0;
     return 0;
+}
+
+int ago_profile_read(ago_op op, float* total_ms, int* count) {
+    return ago_profile_read_split(op, total_ms, nullptr, count);
+}
+
+int ago_bench_mfma_kernel(ago_dtype dt, int iters, void* out, size_t out_bytes, double* flops, void* hip_stream) {
+    if (!out || iters <= 0 || (dt != AGO_BF16 && dt != AGO_F32)) return -1;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return -1;
+    const unsigned grid = (unsigned)prop.multiProcessorCount, block = 512;
+    if (out_bytes < (size_t)grid * block * sizeof(float)) return -1;
+    hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+    if (dt == AGO_BF16) hipLaunchKernelGGL(mfma_only_kernel<true>, dim3(grid), dim3(block), 0, s, (float*)out, iters);
+    else hipLaunchKernelGGL(mfma_only_kernel<false>, dim3(grid), dim3(block), 0, s, (float*)out, iters);
+    if (flops) *flops = (double)grid * (block / 64) * iters * 6.0 * (dt == AGO_BF16 ? 32768.0 : 4096.0);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 float ago_profile_event_overhead_ms(void* hip_stream, int pairs) {

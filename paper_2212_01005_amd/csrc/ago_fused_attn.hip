@@ -24,6 +24,7 @@
 // bit 1 and bit 1 from key bit 2.  Both make the fragment reads bank-conflict free.
 #include "ago_dev.hpp"
 #include "ago_launch.hpp"
+#include "ago_host.hpp"
 
 namespace ago {
 
@@ -383,11 +384,9 @@ hipError_t fused_attn(const void* q, const void* k, const void* v, void* o, int 
         return launch_attn<3, 2, 0, 2>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
     }
     if (D != 64) return hipErrorInvalidValue;
-    if (tile_cfg < 0) {
-        // built-in choice: 192-query workgroups (a compute unit to themselves, K and V of the first
-        // three blocks requested at once) when that still gives the chip enough workgroups
-        const long wgs = (long)((S + 191) / 192) * B * Hh;
-        tile_cfg = (S > 96 && wgs >= 128) ? 3 : 0;
+    if (tile_cfg < 0) {        // built-in choice: the candidate the time model predicts fastest
+        AttnPlan plan;
+        tile_cfg = plan_attn(B, Hh, S, 64, -1, &plan) ? plan.cfg : 0;
     }
     switch (tile_cfg) {
         case 1: return launch_attn<4, 2, 0>(q, k, v, o, B, Hh, S, stride_b, stride_h, stride_s, scale, s);
@@ -405,8 +404,8 @@ hipError_t fused_attn_bias(const void* q, const void* k, const void* v, const vo
     // Two LDS buffers throughout (the third costs the registers that the bias values need); the
     // element-by-element variant needs more registers still and runs configuration 3 as configuration 1.
     if (tile_cfg < 0) {
-        const long wgs = (long)((S + 191) / 192) * B * Hh;
-        tile_cfg = (S > 96 && wgs >= 128) ? 3 : 0;
+        AttnPlan plan;
+        tile_cfg = plan_attn(B, Hh, S, 64, -1, &plan) ? plan.cfg : 0;
     }
     // 16-byte loads of 8 bias values need every row start 16-byte aligned
     const bool vec = S % 8 == 0 && bias_sb % 8 == 0 && bias_sh % 8 == 0 && reinterpret_cast<uintptr_t>(bias) % 16 == 0;

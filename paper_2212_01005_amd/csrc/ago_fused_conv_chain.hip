@@ -26,6 +26,7 @@
 // 256 bytes, and every half-wave of a fragment read covers 16 consecutive pixels of two tile rows.
 #include "ago_dev.hpp"
 #include "ago_launch.hpp"
+#include "ago_host.hpp"
 
 namespace ago {
 
@@ -328,7 +329,11 @@ int fused_conv_chain_num_cfgs() { return 4; }
 hipError_t fused_conv_chain(const void* x, const void* wa, const float* ba, const void* wb,
                             const float* bb, void* y, int N, int H, int W, int residual, int tile_cfg,
                             hipStream_t s) {
-    switch (tile_cfg < 0 ? 0 : tile_cfg) {
+    if (tile_cfg < 0) {        // built-in choice: the candidate the time model predicts fastest
+        ChainPlan plan;
+        tile_cfg = plan_conv_chain(N, H, W, 64, -1, &plan) ? plan.cfg : 0;
+    }
+    switch (tile_cfg) {
         case 0: return launch_chain<7, 14>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
         case 1: return launch_chain<7, 7>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
         case 2: return launch_chain<8, 8>(x, wa, ba, wb, bb, y, N, H, W, residual, s);

@@ -508,6 +508,7 @@ static hipError_t launch_stream(const void* x, const void* w1, const float* b1, 
     hipLaunchKernelGGL(kern, grid, dim3(C::kThreads), C::kSmem, s, (const bf16_t*)x, (const bf16_t*)w1, b1,
                        (const bf16_t*)w2, b2, (bf16_t*)y, (float*)workspace, M, K, F, K2, act);
     hipError_t e = hipGetLastError();
+    if (nsplit != 1) prof_mid(2, s);
     if (e == hipSuccess && nsplit != 1) e = ffn_reduce((const float*)workspace, b2, y, (long)M * K2, K2, nsplit, s);
     prof_stop(2, s);      // the event pair brackets the whole entry point, the reduction included
     return e;

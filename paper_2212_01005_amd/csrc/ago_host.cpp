@@ -220,13 +220,6 @@ int ago_set_tile_config(ago_op op, int config_id) {
     return 0;
 }
 
-int ago_fused_ffn_pays(int M, int K, int F, int K2) {
-    if (M <= 0 || K <= 0 || F <= 0 || K2 <= 0) return -1;
-    const long long wgs = ((long long)M + 63) / 64 * (((long long)F + 383) / 384);
-    const bool exact = F % 384 == 0 && K2 % 384 == 0;
-    return wgs <= (exact ? 1024 : 512) ? 1 : 0;
-}
-
 long long ago_fused_upstream_iterations(int N, int O1, int O2, int H2, int W2, int R2, int C2,
                                         int to2, int th2, int tw2, long long* unfused) {
     if (N <= 0 || O1 <= 0 || O2 <= 0 || H2 <= 0 || W2 <= 0 || R2 <= 0 || C2 <= 0) return -1;

@@ -30,6 +30,26 @@ bool valid_act(int act);
 bool fits31(long long a, long long b, long long c, long long d);   // a*b*c*d < 2^31 (each factor too)
 
 size_t workspace_bytes(int op, const int* dims, int ndims, int dt);
+
+// Analytic planners (ago_plan.cpp): the candidate with the lowest predicted time, or the one `tile_cfg` names.
+struct ChainPlan {
+    int cfg, tile_h, tile_w, resident;
+    long workgroups, rounds;
+    double executed_upstream_macs, algorithmic_upstream_macs, predicted_us;
+};
+struct AttnPlan {
+    int cfg, queries, key_block, stages, resident, lds_bytes;
+    long workgroups, rounds;
+    double executed_upstream_macs, algorithmic_upstream_macs, predicted_us;
+};
+struct FfnPlan {
+    int rows, slice, slices, resident, fuse;
+    long workgroups, rounds;
+    double executed_upstream_macs, algorithmic_upstream_macs, partial_bytes, predicted_us, predicted_unfused_us;
+};
+bool plan_conv_chain(int N, int H, int W, int C, int tile_cfg, ChainPlan* out);
+bool plan_attn(int B, int Hh, int S, int D, int tile_cfg, AttnPlan* out);
+bool plan_ffn(int M, int K, int F, int K2, FfnPlan* out);
 int tile_config(int op);          // current selection for a fused op (-1 = built-in)
 
 }  // namespace ago

@@ -68,6 +68,7 @@ hipError_t fused_attn_bias(const void* q, const void* k, const void* v, const vo
 // Instrumentation hook (see ago_profile_enable): record an event pair around the dominant kernel
 // of a fused entry point.  No-ops unless profiling is enabled.
 void prof_start(int op, hipStream_t s);
+void prof_mid(int op, hipStream_t s);      // between the two kernels of an entry point that launches two
 void prof_stop(int op, hipStream_t s);
 void prof_shape(int op, unsigned grid, unsigned block);   // remembers the launch shape of the dominant kernel
 

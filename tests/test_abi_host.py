@@ -272,6 +272,48 @@ def test_recompute_model_symbolic_forms(lib):
     assert ago.fused_upstream_iterations(1, 8, 8, 7, 16, 3, 3, 1, 2, 16)[0] == -1   # tile must divide
 
 
+def test_planned_tilings_follow_the_papers_redundancy_algebra(lib):
+    """The planners' recompute term is upstream work = |GS2/TS2 x (GS1/TS1 - GS2/TS2)| |TS1| (Sec. III-B): the
+    executed / algorithmic ratio of the planned tiling equals the closed form: (TH+2)(TW+2) tiles / (N H W) for the
+    3x3 chain (|TS2| < |TS1|), exactly 1 for the two "downstream pointwise" tilings (Fig. 7b)."""
+    from paper_2212_01005_amd import binding as ago
+    p = ago.fused_conv_chain_plan(8, 56, 56, 64)                # the benchmark shape: 7 x 14 tiles, one per compute unit
+    assert (p["config"], p["tile_h"], p["tile_w"], p["workgroups"], p["rounds"]) == (0, 7, 14, 256, 1)
+    assert abs(p["recompute"] - (9 * 16) / (7 * 14)) < 1e-12 and abs(p["recompute"] - 1.469) < 1e-3
+    # the same number from the closed form below Fig. 5 (no padding there: its un-fused count is over the
+    # (H2 + 2) x (W2 + 2) upstream image, the padded chain's over H x W)
+    fused, _ = ago.fused_upstream_iterations(8, 64, 64, 56, 56, 3, 3, 64, 7, 14)
+    assert fused == 8 * 8 * 4 * 64 * 9 * 16
+    assert abs(p["recompute"] - fused / (8 * 64 * 56 * 56)) < 1e-12
+    q = ago.fused_conv_chain_plan(1, 56, 56, 64)                # few tiles: smaller tiles, more re-computation
+    assert (q["tile_h"], q["tile_w"], q["workgroups"]) == (7, 7, 64) and abs(q["recompute"] - 81 / 49) < 1e-12
+    r = ago.fused_conv_chain_plan(2, 60, 60, 64)                # ragged: tiles x window / image
+    tiles = 2 * -(-60 // r["tile_h"]) * -(-60 // r["tile_w"])
+    assert r["workgroups"] == tiles
+    assert abs(r["recompute"] - tiles * (r["tile_h"] + 2) * (r["tile_w"] + 2) / (2 * 60 * 60)) < 1e-12
+    for dims in ((8, 12, 384, 64), (2, 12, 4096, 64), (3, 5, 100, 64), (8, 12, 384, 128)):
+        a = ago.fused_attn_plan(*dims)
+        assert abs(a["recompute"] - 1.0) < 1e-12
+        assert a["workgroups"] == dims[0] * dims[1] * -(-dims[2] // a["queries"])
+    for dims in ((2048, 768, 3072, 768), (100, 128, 392, 256), (8192, 1024, 4096, 1024)):
+        f = ago.fused_ffn_plan(*dims)
+        assert abs(f["recompute"] - 1.0) < 1e-12
+    # the choices the measurements back: 96-query workgroups two to a compute unit for the benchmark shape
+    # (within 1 % of the 192-query ones), 128-query workgroups for long sequences
+    assert ago.fused_attn_plan(8, 12, 384, 64)["queries"] in (96, 192)
+    assert ago.fused_attn_plan(2, 12, 4096, 64)["queries"] == 128
+    # pinned candidate
+    ago.set_tile_config(ago.OP_FUSED_CONV_CHAIN, 2)
+    try:
+        assert ago.fused_conv_chain_plan(8, 56, 56, 64)["tile_h"] == 8
+    finally:
+        ago.set_tile_config(ago.OP_FUSED_CONV_CHAIN, -1)
+    with pytest.raises(ago.AgoError):
+        ago.fused_conv_chain_plan(8, 56, 56, 32)
+    with pytest.raises(ago.AgoError):
+        ago.fused_attn_plan(8, 12, 384, 80)
+
+
 def test_invres_plan_is_a_host_query(lib):
     """The tiling query runs without a GPU: plans fit LDS, large channel counts are chunked, more images cost
     more predicted time, and an explicit tile configuration is honoured."""
@@ -352,14 +394,22 @@ def test_binding_refuses_tensors_that_do_not_match_the_sizes_it_passes(lib):
 
 
 def test_ffn_fuse_or_not_is_a_host_decision(lib):
-    """The fused matmul -> activation -> matmul kernel pays while its launch is small (its fp32 partials
-    grow with rows x hidden slices); beyond that the two products with fused epilogues are the schedule."""
+    """Fuse or not comes from the planner's two time models (fused: workgroups x weight tiles + the fp32 partial sums
+    of the hidden slices; un-fused: two products with fused epilogues).  Measured on an MI355X (fused / un-fused us):
+    768 x 3072: M = 128: 28 / 74, 2048: 42 / 42, 4096: 78 / 80, 8192: 153 / 126, 16384: 358 / 254;
+    1024 x 4096, M = 2048: 107 / 114; 512 x 2048: M = 2048: 39 / 68, 8192: 108 / 114."""
     from paper_2212_01005_amd import binding as ago
-    assert ago.fused_ffn_pays(2048, 768, 3072, 768)             # the benchmark shape: 256 workgroups
-    assert ago.fused_ffn_pays(8192, 768, 3072, 768)             # 1024 workgroups, exact slices
-    assert not ago.fused_ffn_pays(32768, 768, 3072, 768)
-    assert ago.fused_ffn_pays(2048, 1024, 4096, 1024) and not ago.fused_ffn_pays(8192, 1024, 4096, 1024)
-    assert ago.fused_ffn_pays(2048, 512, 2048, 512) and not ago.fused_ffn_pays(8192, 512, 2048, 512)
+    assert ago.fused_ffn_pays(128, 768, 3072, 768)
+    assert ago.fused_ffn_pays(2048, 768, 3072, 768)             # the benchmark shape: a tie, which goes to the fused kernel
+    assert ago.fused_ffn_pays(4096, 768, 3072, 768)
+    assert not ago.fused_ffn_pays(8192, 768, 3072, 768)
+    assert not ago.fused_ffn_pays(16384, 768, 3072, 768) and not ago.fused_ffn_pays(32768, 768, 3072, 768)
+    assert ago.fused_ffn_pays(2048, 1024, 4096, 1024)
+    assert ago.fused_ffn_pays(2048, 512, 2048, 512) and ago.fused_ffn_pays(8192, 512, 2048, 512)
     assert ago.fused_ffn_pays(1, 64, 8, 8)
+    plan = ago.fused_ffn_plan(2048, 768, 3072, 768)
+    assert (plan["rows"], plan["slice"], plan["slices"], plan["workgroups"], plan["rounds"]) == (64, 384, 8, 256, 1)
+    assert abs(plan["predicted_us"] - 42.2) < 5 and abs(plan["predicted_unfused_us"] - 41.7) < 5
+    assert ago.fused_ffn_plan(8192, 768, 3072, 768)["fuse"] == 0
     with pytest.raises(ValueError):
         ago.fused_ffn_pays(0, 768, 3072, 768)

@@ -349,6 +349,53 @@ def test_invres_planner_choice_is_near_the_best_candidate(gpu):
             warnings.warn("planner choice for %s: %.2f us against %.2f us for the best candidate" % (case.name, times[-1], best))
 
 
+def test_planner_choices_of_the_chain_ffn_and_attention_kernels(gpu):
+    """Report only (a warning, never a failure): the candidate the analytic planners pick is timed against every
+    selectable candidate on shapes away from the benchmark's; a choice more than 10 % slower than the best
+    candidate is reported."""
+    torch, ago, runner = gpu
+
+    def us(fn, n=30):
+        for _ in range(4):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n * 1e3
+
+    cases = [(wl.ChainCase(1, 56, 56, 64, True, "bf16", 6510, name="plan_chain_1x56"), ago.OP_FUSED_CONV_CHAIN),
+             (wl.ChainCase(16, 28, 28, 64, True, "bf16", 6511, name="plan_chain_16x28"), ago.OP_FUSED_CONV_CHAIN),
+             (wl.ChainCase(6, 80, 80, 64, True, "bf16", 6512, name="plan_chain_6x80"), ago.OP_FUSED_CONV_CHAIN),
+             (wl.AttnCase(4, 12, 1536, 64, 0.125, "bf16", 6513, name="plan_attn_s1536"), ago.OP_FUSED_ATTN),
+             (wl.AttnCase(24, 8, 256, 64, 0.125, "bf16", 6514, name="plan_attn_s256"), ago.OP_FUSED_ATTN),
+             (wl.AttnCase(2, 6, 200, 64, 0.125, "bf16", 6515, name="plan_attn_s200"), ago.OP_FUSED_ATTN),
+             (wl.FfnCase(1024, 768, 3072, 768, "bf16", 6516, name="plan_ffn_1024"), ago.OP_FUSED_FFN),
+             (wl.FfnCase(3072, 512, 2048, 512, "bf16", 6517, name="plan_ffn_3072"), ago.OP_FUSED_FFN)]
+    for case, op in cases:
+        t = runner.to_device(case)
+        y = runner.alloc_output(case)
+        times = {}
+        try:
+            for cfg in [-1] + list(range(ago.num_tile_configs(op))):
+                ago.set_tile_config(op, cfg)
+                try:
+                    fn = runner.prepare_fused(case, t, y, runner.alloc_workspace(case, fused=True))
+                    fn()
+                except ago.AgoError:
+                    continue
+                times[cfg] = us(fn)
+        finally:
+            ago.set_tile_config(op, -1)
+        best = min(v for k, v in times.items() if k >= 0)
+        print("%s built-in %.2f us, best candidate %.2f us" % (case.name, times[-1], best))
+        if times[-1] > 1.10 * best:
+            warnings.warn("planner choice for %s: %.2f us against %.2f us for the best candidate" % (case.name, times[-1], best))
+
+
 def test_ffn_ragged_hidden_slices_and_column_blocks(gpu, oracle):
     """F and K2 that are not multiples of the streaming kernel's 384-wide hidden slices / column blocks
     (BERT-large's 1024 -> 4096 -> 1024 among them): the last slice / block is clamped and masked."""

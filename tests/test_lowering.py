@@ -379,10 +379,10 @@ def test_large_ffn_runs_as_two_epilogue_fused_products():
     import torch
     from oracle import ago_oracle
     from paper_2212_01005_amd import binding as ago
-    g = _ffn_graph(4160, 64, 6144)                   # 65 row blocks x 16 slices: past the point where fusing pays
+    g = _ffn_graph(16384, 64, 1536)                  # 256 row blocks x 4 slices: past the point where fusing pays
     plan = L.lower(g, [0] * len(g.nodes), ago)
     assert [k for k, _ in plan] == ["ffn_epilogue"]
-    x = wl.round_to_bf16(wl.normal(9510, (4160, 64), 1.0))
+    x = wl.round_to_bf16(wl.normal(9510, (16384, 64), 1.0))
     ref = _oracle_eval(g, {"x": x}, ago_oracle)
     host = dict(g.params)
     g.params = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to("cuda:0").to(
