@@ -171,6 +171,9 @@ __global__ __launch_bounds__(256) void conv3x3_c64_kernel(
 
 hipError_t conv3x3_bf16(const void* x, const void* w, const float* bias, const void* res, void* y,
                         int N, int H, int W, int act, hipStream_t s) {
+    // The tiled kernel (input tile and all nine taps resident in LDS, the fused chain's matrix loop) is the
+    // operator; the one-tap-per-k-tile kernel below remains for images too small to give it tiles.
+    if ((long)N * ((H + 6) / 7) * ((W + 6) / 7) >= 8) return conv3x3_bf16_tiled(x, w, bias, res, y, N, H, W, act, s);
     const long P = (long)N * H * W;
     hipLaunchKernelGGL(conv3x3_c64_kernel, dim3((unsigned)((P + 127) / 128)), dim3(256), 0, s,
                        (const bf16_t*)x, (const bf16_t*)w, bias, (const bf16_t*)res, (bf16_t*)y, N, H, W, act);

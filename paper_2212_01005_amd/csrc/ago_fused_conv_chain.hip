@@ -145,6 +145,39 @@ struct ConvStage {
     }
 };
 
+// All nine taps of one weight tensor [3][3][64 in][64 out] -> LDS [tap][out][in]: 9 * 128 transposition
+// units of [8 in][4 out]; unit u -> tap u / 128, out-channel quad (u & 15), in-channel octet (u >> 4) & 7.
+__device__ __forceinline__ void load_weight_unit(const bf16_t* Wsrc, int u, uint2 (&r)[8]) {
+    constexpr int C = 64;
+    const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+        r[kk] = *reinterpret_cast<const uint2*>(Wsrc + ((long)tap * C + ko * 8 + kk) * C + nq * 4);
+}
+__device__ __forceinline__ void store_weight_unit(bf16_t* Ws, int u, const uint2 (&r)[8]) {
+    constexpr int LD = 72;
+    const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
+    // Transpose the [8 in][4 out] block one output channel at a time.  In store t lane nq writes
+    // output channel 4 nq + ((t + nq + nq / 4) & 3): with that rotation (and the row >> 5 swizzle)
+    // the 16-byte stores of a wave, whose rows are 4 apart, are bank-conflict free.
+    const int rot = nq + (nq >> 2);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int q = (t + rot) & 3;
+        const bool hi_word = q & 2;
+        const int sh = (q & 1) << 4;
+        uint32_t v[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const uint32_t e = hi_word ? r[2 * m].y : r[2 * m].x;
+            const uint32_t d = hi_word ? r[2 * m + 1].y : r[2 * m + 1].x;
+            v[m] = ((e >> sh) & 0xffffu) | ((d >> sh) << 16);
+        }
+        const int o = nq * 4 + q;
+        st_u4(Ws + (tap * 64 + o) * LD + ((ko ^ ((o >> 5) & 1)) << 3), make_uint4(v[0], v[1], v[2], v[3]));
+    }
+}
+
 template <int TH, int TW>
 __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wa, const float* __restrict__ ba,
@@ -169,46 +202,16 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
     X += (long)n * H * W * C;
     Y += (long)n * H * W * C;
 
-    // All nine taps of one weight tensor: 9 * 128 transposition units of [8 in][4 out];
-    // unit u -> tap u / 128, out-channel quad (u & 15), in-channel octet (u >> 4) & 7.
-    // Unit u < 1024 belongs to thread u and may stay in registers for a long time (the second weight
-    // tensor is prefetched during conv1); the remaining 128 units are loaded and stored in one go
-    // by the first 128 threads, so that only 16 registers are held across conv1.
+    // Wa / Wb: unit u < 1024 belongs to thread u and may stay in registers for a long time (the second weight
+    // tensor is prefetched during conv1); the remaining 128 units are loaded and stored in one go by the
+    // first 128 threads, so that only 16 registers are held across conv1.
     uint2 rw[8];
-    auto load_unit = [&](const bf16_t* Wsrc, int u, uint2 (&r)[8]) {
-        const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-            r[kk] = *reinterpret_cast<const uint2*>(Wsrc + ((long)tap * C + ko * 8 + kk) * C + nq * 4);
-    };
-    auto store_unit = [&](int u, const uint2 (&r)[8]) {
-        const int tap = u >> 7, nq = u & 15, ko = (u >> 4) & 7;
-        // Transpose the [8 in][4 out] block one output channel at a time.  In store t lane nq writes
-        // output channel 4 nq + ((t + nq + nq / 4) & 3): with that rotation (and the row >> 5 swizzle)
-        // the 16-byte stores of a wave, whose rows are 4 apart, are bank-conflict free.
-        const int rot = nq + (nq >> 2);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int q = (t + rot) & 3;
-            const bool hi_word = q & 2;
-            const int sh = (q & 1) << 4;
-            uint32_t v[4];
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const uint32_t e = hi_word ? r[2 * m].y : r[2 * m].x;
-                const uint32_t d = hi_word ? r[2 * m + 1].y : r[2 * m + 1].x;
-                v[m] = ((e >> sh) & 0xffffu) | ((d >> sh) << 16);
-            }
-            const int o = nq * 4 + q;
-            st_u4(Ws + (tap * 64 + o) * LD + ((ko ^ ((o >> 5) & 1)) << 3), make_uint4(v[0], v[1], v[2], v[3]));
-        }
-    };
-    auto load_w = [&](const bf16_t* Wsrc) { load_unit(Wsrc, tid, rw); };
+    auto load_w = [&](const bf16_t* Wsrc) { load_weight_unit(Wsrc, tid, rw); };
     auto store_w = [&](const bf16_t* Wsrc) {
         uint2 extra[8];
-        if (tid < 9 * 128 - 1024) load_unit(Wsrc, 1024 + tid, extra);
-        store_unit(tid, rw);
-        if (tid < 9 * 128 - 1024) store_unit(1024 + tid, extra);
+        if (tid < 9 * 128 - 1024) load_weight_unit(Wsrc, 1024 + tid, extra);
+        store_weight_unit(Ws, tid, rw);
+        if (tid < 9 * 128 - 1024) store_weight_unit(Ws, 1024 + tid, extra);
     };
 
     load_w(Wa);
@@ -321,6 +324,109 @@ static hipError_t launch_chain(const void* x, const void* wa, const float* ba, c
                        H, W, tiles_h, tiles_w, residual);
     prof_stop(1, s);
     return hipGetLastError();
+}
+
+
+// ---------------------------------------------------------------------------------------
+// One 3x3 convolution (64 -> 64 channels, zero padding 1) with its epilogue (bias, residual, activation),
+// built from the fused kernel's pieces: the same tile geometry, weight staging and matrix loop, reading its
+// input tile from global memory instead of computing it.  This is the un-fused operator of Fig. 3 / Fig. 4:
+// against the fused chain it differs by the intermediate's trip through memory and by the second launch,
+// not by the quality of its inner loop.
+// ---------------------------------------------------------------------------------------
+template <int TH, int TW>
+__global__ __launch_bounds__(1024) void conv3x3_tile_kernel(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wt, const float* __restrict__ bias,
+    const bf16_t* __restrict__ R, bf16_t* __restrict__ Y, int H, int W, int tiles_h, int tiles_w, int act) {
+    typedef ChainGeom<TH, TW> G;
+    constexpr int C = G::C, LD = G::LD, R1W = G::R1W, P2 = G::P2, TROW = G::TROW, P2W = G::P2W;
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* Ts = reinterpret_cast<bf16_t*>(smem);      // [TH + 2][TROW]: the input tile with its one-pixel halo
+    bf16_t* Ws = Ts + G::R1H * TROW;                   // [9][64][LD]
+    float* Bias = reinterpret_cast<float*>(Ws + 9 * 64 * LD);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 31, h = lane >> 5;
+    int b = blockIdx.x;
+    const int tw = b % tiles_w; b /= tiles_w;
+    const int th = b % tiles_h;
+    const int n = b / tiles_h;
+    const int oh0 = th * TH, ow0 = tw * TW;
+    X += (long)n * H * W * C;
+    Y += (long)n * H * W * C;
+    if (R) R += (long)n * H * W * C;
+
+    uint2 rw[8], extra[8];
+    load_weight_unit(Wt, tid, rw);
+    if (tid < 9 * 128 - 1024) load_weight_unit(Wt, 1024 + tid, extra);
+    if (tid < 64) Bias[tid] = bias ? bias[tid] : 0.0f;
+    for (int it = tid; it < G::R1H * R1W * 8; it += 1024) {
+        const int pix = it >> 3, kc = it & 7;
+        const int ih = oh0 - 1 + pix / R1W, iw = ow0 - 1 + pix % R1W;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (ih >= 0 && ih < H && iw >= 0 && iw < W) v = ld_u4(X + ((long)ih * W + iw) * C + kc * 8);
+        st_u4(Ts + (pix / R1W) * TROW + (pix % R1W) * LD + kc * 8, v);
+    }
+    store_weight_unit(Ws, tid, rw);
+    if (tid < 9 * 128 - 1024) store_weight_unit(Ws, 1024 + tid, extra);
+    __syncthreads();
+
+    typedef ConvStage<TROW, P2W, TW, P2, G::NMT2> Stage;
+    Stage st;
+    const bool live = Stage::live(wave);
+    const int me = Stage::tg(wave);
+    if (live) {
+        st.init(wave, j, h);
+        st.run(Ts, Ws, h);
+    }
+    __syncthreads();                           // the weights are dead: their LDS area becomes reduction scratch
+    if (live) st.park(reinterpret_cast<float*>(Ws), wave, lane);
+    __syncthreads();
+    if (live) {
+        st.gather(reinterpret_cast<const float*>(Ws), wave, lane);
+        const int m = Stage::tile(wave) * 32 + j;
+        const int py = m / P2W, px = m % P2W;
+        const int y = oh0 + py, x = ow0 + px;
+        if (m < P2 && px < TW && y < H && x < W) {
+#pragma unroll
+            for (int grp = 0; grp < 8; ++grp) {
+                if (Stage::owner_of(grp) != me) continue;
+                const int ot = grp >> 2, g = grp & 3;
+                const int o = ot * 32 + 8 * g + 4 * h;
+                float4 v = make_float4(st.acc[ot][4 * g], st.acc[ot][4 * g + 1], st.acc[ot][4 * g + 2], st.acc[ot][4 * g + 3]);
+                const float4 bv = *reinterpret_cast<const float4*>(Bias + o);
+                v.x += bv.x; v.y += bv.y; v.z += bv.z; v.w += bv.w;
+                if (R) {
+                    const uint2 xr = *reinterpret_cast<const uint2*>(R + ((long)y * W + x) * C + o);
+                    v.x += lo_bf16(xr.x); v.y += hi_bf16(xr.x); v.z += lo_bf16(xr.y); v.w += hi_bf16(xr.y);
+                }
+                *reinterpret_cast<uint2*>(Y + ((long)y * W + x) * C + o) =
+                    make_uint2(pack_bf16(apply_act_rt(v.x, act), apply_act_rt(v.y, act)),
+                               pack_bf16(apply_act_rt(v.z, act), apply_act_rt(v.w, act)));
+            }
+        }
+    }
+}
+
+template <int TH, int TW>
+static hipError_t launch_conv3x3_tile(const void* x, const void* w, const float* bias, const void* res, void* y,
+                                      int N, int H, int W, int act, hipStream_t s) {
+    typedef ChainGeom<TH, TW> G;
+    constexpr size_t smem = ((size_t)G::R1H * G::TROW + 9 * 64 * G::LD) * 2 + 64 * 4;
+    auto kern = conv3x3_tile_kernel<TH, TW>;
+    if (hipError_t e = allow_dynamic_lds<conv3x3_tile_kernel<TH, TW>>((int)smem); e != hipSuccess) return e;
+    const int tiles_h = (H + TH - 1) / TH, tiles_w = (W + TW - 1) / TW;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(N * tiles_h * tiles_w)), dim3(1024), smem, s, (const bf16_t*)x,
+                       (const bf16_t*)w, bias, (const bf16_t*)res, (bf16_t*)y, H, W, tiles_h, tiles_w, act);
+    return hipGetLastError();
+}
+
+// The un-fused 3x3 convolution: 7 x 14 tiles when they fill the chip, 7 x 7 tiles otherwise (the same
+// trade-off the chain's planner makes: more workgroups against more halo pixels loaded).
+hipError_t conv3x3_bf16_tiled(const void* x, const void* w, const float* bias, const void* res, void* y,
+                              int N, int H, int W, int act, hipStream_t s) {
+    const long t714 = (long)N * ((H + 6) / 7) * ((W + 13) / 14);
+    if (t714 >= 192) return launch_conv3x3_tile<7, 14>(x, w, bias, res, y, N, H, W, act, s);
+    return launch_conv3x3_tile<7, 7>(x, w, bias, res, y, N, H, W, act, s);
 }
 
 // Tile configurations (TH x TW output pixels per workgroup): 0: 7x14  1: 7x7  2: 8x8  3: 6x14

@@ -32,6 +32,8 @@ hipError_t dwconv3x3(const void* x, const void* w, const float* bias, void* y, i
                      int C, int stride, int act, bool bf16, hipStream_t s);
 hipError_t conv3x3_bf16(const void* x, const void* w, const float* bias, const void* res, void* y,
                         int N, int H, int W, int act, hipStream_t s);
+hipError_t conv3x3_bf16_tiled(const void* x, const void* w, const float* bias, const void* res, void* y,
+                              int N, int H, int W, int act, hipStream_t s);   // on the fused chain's tile loop
 hipError_t bias_act(const void* x, const float* bias, void* y, long P, int C, int act, bool bf16,
                     hipStream_t s);
 hipError_t add_act(const void* a, const void* b, void* y, long n, int act, bool bf16, hipStream_t s);
