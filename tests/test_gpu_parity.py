@@ -595,10 +595,12 @@ def test_pair_fused_matches_oracle(gpu, oracle, case):
     yu = runner.alloc_output(case)
     runner.run_pair_unfused(case, t, yu, runner.alloc_pair_scratch(case))
     torch.cuda.synchronize()
-    # operator by operator the intermediate tensor goes through memory in the storage type: one more
-    # bf16 rounding than the fused path, so this sanity check of the baseline gets 1.5x the bar
-    worst = assert_close(runner.to_numpy64(yu), ref, case.dtype, case.name + " un-fused", scale=1.5)
-    assert worst <= 1.5 * RTOL[case.dtype]
+    # Operator by operator the intermediate tensor goes through memory in the storage type.  For bf16 that is
+    # one rounding (2^-9 relative) the fused path does not make (it keeps the intermediate in fp32 ahead of a
+    # depthwise), and a depthwise adds up 9 such values of mixed sign: the worst element of the un-fused dw -> dw
+    # pair measures 2.2e-2 of max(|ref|, rms), just above the 2e-2 bar of the fused kernels.  This sanity check of
+    # the baseline therefore gets 1.25x the bar; every fused result is held to the bar itself.
+    assert_close(runner.to_numpy64(yu), ref, case.dtype, case.name + " un-fused", scale=1.25)
 
 
 @pytest.mark.gpu
