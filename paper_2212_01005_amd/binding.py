@@ -26,6 +26,7 @@ ACT_NONE, ACT_RELU, ACT_RELU6, ACT_GELU_TANH = 0, 1, 2, 3
 OP_FUSED_INVRES, OP_FUSED_CONV_CHAIN, OP_FUSED_FFN, OP_FUSED_ATTN = 0, 1, 2, 3
 OP_UNFUSED_INVRES, OP_UNFUSED_CONV_CHAIN, OP_UNFUSED_FFN, OP_UNFUSED_ATTN = 4, 5, 6, 7
 OP_FUSED_PW_DW, OP_FUSED_DW_PW, OP_FUSED_PW_PW, OP_FUSED_DW_DW = 8, 9, 10, 11
+OP_FUSED_FFN_PACKED = 12
 
 _vp, _i, _l, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float, ctypes.c_size_t
 
@@ -36,6 +37,10 @@ _SIGS = {
     "ago_fused_invres_noalloc": [_vp] * 8 + [_i] * 10 + [_vp],
     "ago_fused_conv_chain": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_ffn": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
+    "ago_fused_ffn_packed": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
+    "ago_pack_weight": [_vp, _vp, _i, _i, _i, _vp],
+    "ago_gemm_packed": [_vp] * 4 + [_i] * 5 + [_vp],
+    "ago_unfused_ffn_packed": [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp],
     "ago_fused_attn": [_vp] * 4 + [_i] * 4 + [_f, _i, _vp, _sz, _vp],
     "ago_fused_attn_strided": [_vp] * 4 + [_i] * 4 + [ctypes.c_longlong] * 3 + [_f, _i, _vp, _sz, _vp],
     "ago_fused_pw_dw": [_vp] * 6 + [_i] * 7 + [_vp, _sz, _vp],
@@ -97,6 +102,8 @@ lib.ago_profile_read_split.argtypes = [_i, ctypes.POINTER(_f), ctypes.POINTER(_f
 lib.ago_profile_read_split.restype = _i
 lib.ago_bench_mfma_kernel.argtypes = [_i, _i, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]
 lib.ago_bench_mfma_kernel.restype = _i
+lib.ago_packed_weight_bytes.argtypes = [_i, _i]
+lib.ago_packed_weight_bytes.restype = _sz
 lib.ago_bench_empty_kernel.argtypes = [_i, _i, _vp]
 lib.ago_bench_empty_kernel.restype = _i
 lib.ago_profile_event_overhead_ms.argtypes = [_vp, _i]
@@ -120,7 +127,7 @@ EXPORTED = sorted(list(_SIGS) + ["ago_graph_op_weight", "ago_graph_topological_s
                                  "ago_fused_conv_chain_plan", "ago_fused_attn_plan", "ago_fused_ffn_plan",
                                  "ago_profile_enable", "ago_profile_select", "ago_profile_read", "ago_profile_read_split", "ago_bench_mfma_kernel",
                                  "ago_profile_event_overhead_ms", "ago_profile_last_launch",
-                                 "ago_bench_empty_kernel"])
+                                 "ago_bench_empty_kernel", "ago_packed_weight_bytes"])
 
 
 class AgoError(RuntimeError):
@@ -394,6 +401,56 @@ def ago_fused_ffn(x, w1, b1, w2, b2, y, act=ACT_GELU_TANH, workspace=None):
     wp, wb = _ws(workspace)
     return lib.ago_fused_ffn, (_p(x), _p(w1), _p(b1), _p(w2), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
                            wp, wb, _stream())
+
+
+def packed_weight_shape(K, N):
+    """Shape of the packed copy of a [K, N] weight matrix: [k-steps of 32][column tiles of 16][64 lanes][8]."""
+    if int(lib.ago_packed_weight_bytes(int(K), int(N))) == 0:
+        raise ValueError("a %d x %d matrix cannot be packed (needs K %% 32 == 0 and N %% 16 == 0)" % (K, N))
+    return (K // 32, N // 16, 64, 8)
+
+
+@_entry
+def ago_pack_weight(w, wp):
+    """w: [K, N] row-major; wp: a tensor of packed_weight_shape(K, N) and w's dtype, written by the call."""
+    K, N = w.shape
+    _want("w", w, (K, N)); _want("wp", wp, packed_weight_shape(K, N), w.dtype)
+    return lib.ago_pack_weight, (_p(w), _p(wp), K, N, _dt(w), _stream())
+
+
+@_entry
+def ago_gemm_packed(a, wp, bias, c, act=ACT_NONE):
+    """c = act(a w + bias) with wp = the weight as written by ago_pack_weight."""
+    M, K = a.shape
+    N = int(wp.shape[1]) * 16
+    _want("a", a, (M, K)); _want("wp", wp, packed_weight_shape(K, N), a.dtype)
+    _want_bias("bias", bias, N); _want("c", c, (M, N), a.dtype)
+    return lib.ago_gemm_packed, (_p(a), _p(wp), _p(bias), _p(c), M, K, N, act, _dt(a), _stream())
+
+
+@_entry
+def ago_unfused_ffn_packed(x, w1p, b1, w2p, b2, y, act=ACT_GELU_TANH, workspace=None):
+    M, K = x.shape
+    F, K2 = int(w1p.shape[1]) * 16, int(w2p.shape[1]) * 16
+    _want("x", x, x.shape); _want("w1p", w1p, packed_weight_shape(K, F), x.dtype)
+    _want("w2p", w2p, packed_weight_shape(F, K2), x.dtype)
+    _want_bias("b1", b1, F); _want_bias("b2", b2, K2); _want("y", y, (M, K2), x.dtype)
+    wp, wb = _ws(workspace)
+    return lib.ago_unfused_ffn_packed, (_p(x), _p(w1p), _p(b1), _p(w2p), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
+                                        wp, wb, _stream())
+
+
+@_entry
+def ago_fused_ffn_packed(x, w1p, b1, w2p, b2, y, act=ACT_GELU_TANH, workspace=None):
+    """w1p, w2p: the weights as written by ago_pack_weight."""
+    M, K = x.shape
+    F, K2 = int(w1p.shape[1]) * 16, int(w2p.shape[1]) * 16
+    _want("x", x, x.shape); _want("w1p", w1p, packed_weight_shape(K, F), x.dtype)
+    _want("w2p", w2p, packed_weight_shape(F, K2), x.dtype)
+    _want_bias("b1", b1, F); _want_bias("b2", b2, K2); _want("y", y, (M, K2), x.dtype)
+    wp, wb = _ws(workspace)
+    return lib.ago_fused_ffn_packed, (_p(x), _p(w1p), _p(b1), _p(w2p), _p(b2), _p(y), M, K, F, K2, act, _dt(x),
+                                      wp, wb, _stream())
 
 
 @_entry

@@ -23,11 +23,13 @@ SOURCES = [
     "ago_api.hip",
     "ago_elementwise.hip",
     "ago_gemm.hip",
+    "ago_gemm_packed.hip",
     "ago_conv.hip",
     "ago_fused_invres.hip",
     "ago_fused_conv_chain.hip",
     "ago_fused_ffn.hip",
     "ago_fused_ffn_stream.hip",
+    "ago_fused_ffn_packed.hip",
     "ago_fused_dw_dw.hip",
     "ago_fused_attn.hip",
     "ago_fused_qkv.hip",

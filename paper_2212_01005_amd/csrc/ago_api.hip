@@ -347,6 +347,50 @@ ago_status ago_fused_ffn(const void* x, const void* w1, const float* b1, const v
     return from_hip(fused_ffn(x, w1, b1, w2, b2, y, M, K, F, K2, act, cfg, workspace, as_stream(hip_stream)));
 }
 
+size_t ago_packed_weight_bytes(int K, int N) {
+    return (K > 0 && N > 0 && K % 32 == 0 && N % 16 == 0) ? (size_t)K * (size_t)N * 2 : 0;
+}
+
+ago_status ago_pack_weight(const void* w, void* wp, int K, int N, ago_dtype dt, void* hip_stream) {
+    ago_status st = check_pack_weight(w, wp, K, N, dt);
+    if (st != AGO_OK) return st;
+    return from_hip(pack_weight(w, wp, K, N, as_stream(hip_stream)));
+}
+
+ago_status ago_gemm_packed(const void* a, const void* wp, const float* bias, void* c, int M, int K, int N,
+                           ago_act act, ago_dtype dt, void* hip_stream) {
+    ago_status st = check_gemm_packed(a, wp, c, bias, M, K, N, act, dt);
+    if (st != AGO_OK) return st;
+    return from_hip(gemm_packed(a, wp, bias, c, M, K, N, act, as_stream(hip_stream)));
+}
+
+ago_status ago_unfused_ffn_packed(const void* x, const void* w1p, const float* b1, const void* w2p,
+                                  const float* b2, void* y, int M, int K, int F, int K2, ago_act act,
+                                  ago_dtype dt, void* workspace, size_t workspace_bytes, void* s) {
+    if (!x || !w1p || !w2p || !y) return AGO_ERR_NULL;
+    if (M <= 0 || K <= 0 || F <= 0 || K2 <= 0) return AGO_ERR_SHAPE;
+    const int dims[4] = {M, K, F, K2};
+    ago_status st = check_workspace(workspace, workspace_bytes, ago::workspace_bytes(AGO_OP_UNFUSED_FFN, dims, 4, dt));
+    if (st != AGO_OK) return st;
+    if (workspace_bytes == 0 || !workspace) return AGO_ERR_WORKSPACE;
+    // both products are checked before the first is launched
+    if (gemm_packed_variant(M, K, F) == 0 || gemm_packed_variant(M, F, K2) == 0) return AGO_ERR_UNSUPPORTED;
+    st = ago_gemm_packed(x, w1p, b1, workspace, M, K, F, act, dt, s);
+    if (st != AGO_OK) return st;
+    return ago_gemm_packed(workspace, w2p, b2, y, M, F, K2, AGO_ACT_NONE, dt, s);
+}
+
+ago_status ago_fused_ffn_packed(const void* x, const void* w1p, const float* b1, const void* w2p,
+                                const float* b2, void* y, int M, int K, int F, int K2, ago_act act,
+                                ago_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    ago_status st = check_ffn_packed(x, w1p, w2p, y, b1, b2, M, K, F, K2, act, dt);
+    if (st != AGO_OK) return st;
+    const int dims[4] = {M, K, F, K2};
+    st = check_workspace(workspace, workspace_bytes, ago::workspace_bytes(AGO_OP_FUSED_FFN_PACKED, dims, 4, dt));
+    if (st != AGO_OK) return st;
+    return from_hip(fused_ffn_packed(x, w1p, b1, w2p, b2, y, M, K, F, K2, act, workspace, as_stream(hip_stream)));
+}
+
 ago_status ago_fused_attn(const void* q, const void* k, const void* v, void* o, int B, int Hh, int S,
                           int D, float scale, ago_dtype dt, void* workspace, size_t workspace_bytes,
                           void* hip_stream) {

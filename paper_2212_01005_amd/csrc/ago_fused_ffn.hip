@@ -287,12 +287,13 @@ __global__ __launch_bounds__(kFfnThreads) void fused_ffn_kernel(
 // y[m][n] = bf16( sum_s part[s][m][n] + b2[n] ), slices added in index order.
 __global__ __launch_bounds__(256) void ffn_reduce_kernel(const float* __restrict__ part,
                                                          const float* __restrict__ b2,
-                                                         bf16_t* __restrict__ Y, long MK2, int K2, int nsplit) {
+                                                         bf16_t* __restrict__ Y, long MK2, int K2, int nsplit,
+                                                         long slice_stride) {
     const long n4 = MK2 / 4;
     for (long i = blockIdx.x * 256L + threadIdx.x; i < n4; i += (long)gridDim.x * 256) {
         float4 a = reinterpret_cast<const float4*>(part)[i];
         for (int s = 1; s < nsplit; ++s) {
-            const float4 v = reinterpret_cast<const float4*>(part + (long)s * MK2)[i];
+            const float4 v = reinterpret_cast<const float4*>(part + (long)s * slice_stride)[i];
             a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
         }
         if (b2) {
@@ -303,10 +304,13 @@ __global__ __launch_bounds__(256) void ffn_reduce_kernel(const float* __restrict
     }
 }
 
-hipError_t ffn_reduce(const float* part, const float* b2, void* y, long MK2, int K2, int nsplit, hipStream_t s) {
+// slice_stride: elements between the partial results of consecutive slices (0: MK2, densely packed)
+hipError_t ffn_reduce(const float* part, const float* b2, void* y, long MK2, int K2, int nsplit, hipStream_t s,
+                      long slice_stride) {
+    if (slice_stride == 0) slice_stride = MK2;
     long g = (MK2 / 4 + 255) / 256;
     if (g > 2048) g = 2048;
-    hipLaunchKernelGGL(ffn_reduce_kernel, dim3((unsigned)g), dim3(256), 0, s, part, b2, (bf16_t*)y, MK2, K2, nsplit);
+    hipLaunchKernelGGL(ffn_reduce_kernel, dim3((unsigned)g), dim3(256), 0, s, part, b2, (bf16_t*)y, MK2, K2, nsplit, slice_stride);
     return hipGetLastError();
 }
 

@@ -12,6 +12,10 @@ int fused_ffn_num_cfgs();
 int fused_attn_num_cfgs();
 int fused_ffn_pick_cfg(int M, int K, int F, int K2, int tile_cfg);
 int fused_ffn_nsplit(int cfg, int F);
+bool fused_ffn_packed_ok(int M, int K, int F, int K2);
+long fused_ffn_packed_rows(int M);
+int fused_ffn_packed_nsplit(int F);
+int gemm_packed_variant(int M, int K, int N);
 size_t fused_invres_workspace(int N, int H, int W, int Cin, int Cexp, int Cout, int stride, int ksize, bool bf16,
                               int tile_cfg, int mode);
 
@@ -120,6 +124,42 @@ ago_status check_ffn(const void* x, const void* w1, const void* w2, const void* 
     return AGO_OK;
 }
 
+ago_status check_ffn_packed(const void* x, const void* w1p, const void* w2p, const void* y, const void* b1,
+                            const void* b2, int M, int K, int F, int K2, int act, int dt) {
+    if (!x || !w1p || !w2p || !y) return AGO_ERR_NULL;
+    if (!valid_dtype(dt) || !valid_act(act)) return AGO_ERR_DTYPE;
+    if (M <= 0 || K <= 0 || F <= 0 || K2 <= 0) return AGO_ERR_SHAPE;
+    const void* ps[6] = {x, w1p, w2p, y, b1, b2};
+    for (const void* p : ps)
+        if (p && !aligned16(p)) return AGO_ERR_ALIGN;
+    if (dt != AGO_BF16 || !fused_ffn_packed_ok(M, K, F, K2)) return AGO_ERR_UNSUPPORTED;
+    if (!fits31(M, K > F ? (K > K2 ? K : K2) : (F > K2 ? F : K2), 1, 1) || !fits31(K > K2 ? K : K2, F, 1, 1))
+        return AGO_ERR_UNSUPPORTED;
+    return AGO_OK;
+}
+
+ago_status check_gemm_packed(const void* a, const void* wp, const void* c, const void* bias, int M, int K, int N,
+                             int act, int dt) {
+    if (!a || !wp || !c) return AGO_ERR_NULL;
+    if (!valid_dtype(dt) || !valid_act(act)) return AGO_ERR_DTYPE;
+    if (M <= 0 || K <= 0 || N <= 0) return AGO_ERR_SHAPE;
+    const void* ps[4] = {a, wp, c, bias};
+    for (const void* p : ps)
+        if (p && !aligned16(p)) return AGO_ERR_ALIGN;
+    if (dt != AGO_BF16 || gemm_packed_variant(M, K, N) == 0) return AGO_ERR_UNSUPPORTED;
+    if (!fits31(M, K > N ? K : N, 1, 1) || !fits31(K, N, 1, 1)) return AGO_ERR_UNSUPPORTED;
+    return AGO_OK;
+}
+
+ago_status check_pack_weight(const void* w, const void* wp, int K, int N, int dt) {
+    if (!w || !wp) return AGO_ERR_NULL;
+    if (!valid_dtype(dt)) return AGO_ERR_DTYPE;
+    if (K <= 0 || N <= 0) return AGO_ERR_SHAPE;
+    if (!aligned16(w) || !aligned16(wp)) return AGO_ERR_ALIGN;
+    if (dt != AGO_BF16 || K % 32 || N % 16 || !fits31(K, N, 1, 1)) return AGO_ERR_UNSUPPORTED;
+    return AGO_OK;
+}
+
 ago_status check_attn(const void* q, const void* k, const void* v, const void* o, int B, int Hh, int S,
                       int D, float scale, int dt) {
     if (!q || !k || !v || !o) return AGO_ERR_NULL;
@@ -164,6 +204,10 @@ size_t workspace_bytes(int op, const int* d, int nd, int dt) {
             const int cfg = fused_ffn_pick_cfg(d[0], d[1], d[2], d[3], g_tile_cfg[AGO_OP_FUSED_FFN]);
             const int ns = fused_ffn_nsplit(cfg, d[2]);
             return ns > 1 ? (size_t)ns * d[0] * d[3] * 4 : 0;
+        }
+        case AGO_OP_FUSED_FFN_PACKED: {   // fp32 partial sums [slices][rows padded to 64][K2]
+            if (nd < 4 || !fused_ffn_packed_ok(d[0], d[1], d[2], d[3])) return 0;
+            return (size_t)fused_ffn_packed_nsplit(d[2]) * (size_t)fused_ffn_packed_rows(d[0]) * d[3] * 4;
         }
         case AGO_OP_UNFUSED_INVRES: {     // E [N,H,W,Cexp] and D [N,OH,OW,Cexp]
             if (nd < 7) return 0;

@@ -21,6 +21,11 @@ ago_status check_conv_chain(const void* x, const void* wa, const void* wb, const
                             const void* ba, const void* bb, int N, int H, int W, int C, int dt);
 ago_status check_ffn(const void* x, const void* w1, const void* w2, const void* y, const void* b1,
                      const void* b2, int M, int K, int F, int K2, int act, int dt);
+ago_status check_ffn_packed(const void* x, const void* w1p, const void* w2p, const void* y, const void* b1,
+                            const void* b2, int M, int K, int F, int K2, int act, int dt);
+ago_status check_pack_weight(const void* w, const void* wp, int K, int N, int dt);
+ago_status check_gemm_packed(const void* a, const void* wp, const void* c, const void* bias, int M, int K, int N,
+                             int act, int dt);
 ago_status check_attn(const void* q, const void* k, const void* v, const void* o, int B, int Hh, int S,
                       int D, float scale, int dt);
 ago_status check_workspace(const void* workspace, size_t have, size_t need);

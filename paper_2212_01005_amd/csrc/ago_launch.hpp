@@ -84,7 +84,18 @@ bool fused_ffn_stream_ok(int M, int K, int F, int K2);
 hipError_t fused_ffn_stream(const void* x, const void* w1, const float* b1, const void* w2, const float* b2,
                             void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s,
                             int variant = 0);
-hipError_t ffn_reduce(const float* part, const float* b2, void* y, long MK2, int K2, int nsplit, hipStream_t s);
+hipError_t ffn_reduce(const float* part, const float* b2, void* y, long MK2, int K2, int nsplit, hipStream_t s,
+                      long slice_stride = 0);
+// matmul -> activation -> matmul on weights packed into matrix-instruction fragments (pack_weight)
+bool fused_ffn_packed_ok(int M, int K, int F, int K2);
+long fused_ffn_packed_rows(int M);
+int fused_ffn_packed_nsplit(int F);
+hipError_t pack_weight(const void* w, void* wp, int K, int N, hipStream_t s);
+int gemm_packed_variant(int M, int K, int N);     // 0: the shape fits no tiling of the packed product
+hipError_t gemm_packed(const void* a, const void* wp, const float* bias, void* c, int M, int K, int N, int act,
+                       hipStream_t s);
+hipError_t fused_ffn_packed(const void* x, const void* w1p, const float* b1, const void* w2p, const float* b2,
+                            void* y, int M, int K, int F, int K2, int act, void* workspace, hipStream_t s);
 int fused_ffn_num_cfgs();
 int fused_attn_num_cfgs();
 int fused_ffn_pick_cfg(int M, int K, int F, int K2, int tile_cfg);   // -1 = no configuration fits

@@ -171,6 +171,54 @@ def test_validation_runs_before_any_gpu_call(lib):
     assert lib.ago_gemm(p, p, None, None, p, 8, 12, 8, 0, 1, None) == 5
 
 
+def test_packed_weight_entry_points_validate_on_the_host(lib):
+    """Weight pre-packing and the kernels that consume packed weights: sizes, divisibility rules and the
+    workspace check all run before any GPU call."""
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.ago_packed_weight_bytes.argtypes = [ci, ci]
+    lib.ago_packed_weight_bytes.restype = sz
+    assert lib.ago_packed_weight_bytes(768, 3072) == 768 * 3072 * 2
+    assert lib.ago_packed_weight_bytes(32, 16) == 1024                 # one fragment
+    assert lib.ago_packed_weight_bytes(48, 16) == 0                    # K % 32
+    assert lib.ago_packed_weight_bytes(32, 24) == 0                    # N % 16
+    assert lib.ago_packed_weight_bytes(0, 16) == 0
+    p = _fake()
+    lib.ago_pack_weight.argtypes = [vp, vp, ci, ci, ci, vp]
+    assert lib.ago_pack_weight(None, p, 32, 16, 1, None) == 1
+    assert lib.ago_pack_weight(p, p, 32, 16, 0, None) == 5             # fp32
+    assert lib.ago_pack_weight(p, p, 40, 16, 1, None) == 5
+    assert lib.ago_pack_weight(p, _fake(0x1008), 32, 16, 1, None) == 4
+    assert lib.ago_pack_weight(p, p, -32, 16, 1, None) == 2
+
+    lib.ago_workspace_bytes.restype = sz
+    lib.ago_workspace_bytes.argtypes = [ci, ctypes.POINTER(ci), ci, ci]
+    dims = (ci * 4)(2000, 768, 3072, 768)
+    need = lib.ago_workspace_bytes(12, dims, 4, 1)
+    assert need == 8 * 2048 * 768 * 4                                  # 8 slices, rows padded to 64, fp32
+    dims1 = (ci * 4)(64, 128, 384, 384)
+    assert lib.ago_workspace_bytes(12, dims1, 4, 1) == 64 * 384 * 4    # one slice still goes through the workspace
+    lib.ago_fused_ffn_packed.argtypes = [vp] * 6 + [ci] * 6 + [vp, sz, vp]
+    ffn = lambda x, w1, w2, y, M, K, F, K2, act=3, dt=1, ws=None, wsz=0: lib.ago_fused_ffn_packed(
+        x, w1, None, w2, None, y, M, K, F, K2, act, dt, ws, wsz, None)
+    assert ffn(None, p, p, p, 128, 64, 64, 64) == 1
+    assert ffn(p, p, p, p, 128, 64, 64, 64, dt=0) == 5
+    assert ffn(p, p, p, p, 128, 96, 64, 64) == 5                       # K % 64
+    assert ffn(p, p, p, p, 128, 64, 96, 64) == 5                       # F % 64
+    assert ffn(p, p, p, p, 128, 64, 64, 72) == 5                       # K2 % 16
+    assert ffn(p, p, p, p, 128, 1280, 64, 64) == 5                     # a row block of x no longer fits LDS
+    assert ffn(p, p, p, p, 2000, 768, 3072, 768) == 6                  # workspace missing
+    assert ffn(p, p, p, p, 2000, 768, 3072, 768, ws=p, wsz=need - 1) == 6
+
+    lib.ago_gemm_packed.argtypes = [vp] * 4 + [ci] * 5 + [vp]
+    assert lib.ago_gemm_packed(p, p, None, None, 128, 128, 192, 0, 1, None) == 1
+    assert lib.ago_gemm_packed(p, p, None, p, 128, 128, 200, 0, 1, None) == 5      # N fits neither tiling
+    assert lib.ago_gemm_packed(p, p, None, p, 128, 64, 192, 0, 1, None) == 5       # K % 128
+    assert lib.ago_gemm_packed(p, p, None, p, 128, 256, 96, 0, 1, None) == 5       # narrow tiling needs K % 512
+    lib.ago_unfused_ffn_packed.argtypes = [vp] * 6 + [ci] * 6 + [vp, sz, vp]
+    assert lib.ago_unfused_ffn_packed(p, p, None, p, None, p, 128, 128, 192, 100, 3, 1, p, 1 << 20, None) == 5
+    assert lib.ago_unfused_ffn_packed(p, p, None, p, None, p, 128, 128, 192, 192, 3, 1, None, 0, None) == 6
+
+
 def test_tensors_of_two_to_the_31_elements_are_refused(lib):
     """Sizes whose element counts do not fit 32-bit offsets return UNSUPPORTED on the host (no GPU call)."""
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t

@@ -420,6 +420,70 @@ def test_ffn_ragged_hidden_slices_and_column_blocks(gpu, oracle):
             ago.set_tile_config(ago.OP_FUSED_FFN, -1)
 
 
+def _packed_reference(w):
+    """The packed layout written out from its definition: fragment (ks, nt), lane l, element e holds
+    w[32 ks + 8 (l // 16) + e][16 nt + l % 16]."""
+    K, N = w.shape
+    ks, nt, l, e = np.meshgrid(np.arange(K // 32), np.arange(N // 16), np.arange(64), np.arange(8), indexing="ij")
+    return w[32 * ks + 8 * (l // 16) + e, 16 * nt + l % 16]
+
+
+def test_weight_packing_is_the_documented_permutation(gpu):
+    torch, ago, runner = gpu
+    for K, N in ((32, 16), (64, 48), (768, 3072), (3072, 768), (96, 400)):
+        w = torch.arange(K * N, device="cuda", dtype=torch.float32).remainder_(251.0).reshape(K, N).to(torch.bfloat16)
+        wp = torch.empty(ago.packed_weight_shape(K, N), device="cuda", dtype=torch.bfloat16)
+        ago.ago_pack_weight(w, wp)
+        torch.cuda.synchronize()
+        got = wp.float().cpu().numpy()
+        assert np.array_equal(got, _packed_reference(w.float().cpu().numpy())), (K, N)
+
+
+def test_ffn_on_packed_weights(gpu, oracle):
+    """matmul -> activation -> matmul with the weights pre-packed into matrix-instruction fragments: the
+    benchmark shape, ragged rows, a ragged last hidden slice and column block, k-steps in pairs and in
+    fours, one slice only, the three activations."""
+    torch, ago, runner = gpu
+    cases = [(wl.FfnCase(2048, 768, 3072, 768, "bf16", 6800, name="ffn_packed_bench"), ago.ACT_GELU_TANH),
+             (wl.FfnCase(130, 64, 64, 16, "bf16", 6801, name="ffn_packed_tiny"), ago.ACT_GELU_TANH),
+             (wl.FfnCase(300, 192, 448, 400, "bf16", 6802, name="ffn_packed_ragged"), ago.ACT_GELU_TANH),
+             (wl.FfnCase(512, 1024, 4096, 1024, "bf16", 6803, name="ffn_packed_bert_large"), ago.ACT_GELU_TANH),
+             (wl.FfnCase(64, 128, 384, 384, "bf16", 6804, name="ffn_packed_one_slice"), ago.ACT_GELU_TANH),
+             (wl.FfnCase(1, 128, 512, 768, "bf16", 6805, name="ffn_packed_one_row"), ago.ACT_GELU_TANH)]
+    for case, act in cases:
+        ref = oracle.run_case(case)
+        t = runner.to_device(case)
+        w1p = torch.empty(ago.packed_weight_shape(case.K, case.F), device="cuda", dtype=torch.bfloat16)
+        w2p = torch.empty(ago.packed_weight_shape(case.F, case.K2), device="cuda", dtype=torch.bfloat16)
+        ago.ago_pack_weight(t["w1"], w1p)
+        ago.ago_pack_weight(t["w2"], w2p)
+        n = ago.workspace_bytes(ago.OP_FUSED_FFN_PACKED, [case.M, case.K, case.F, case.K2], ago.BF16)
+        assert n > 0
+        ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+        y = runner.alloc_output(case)
+        y.zero_()
+        print("packed ffn", case.name, flush=True)
+        ago.ago_fused_ffn_packed(t["x"], w1p, t["b1"], w2p, t["b2"], y, act, ws)
+        torch.cuda.synchronize()
+        assert_close(runner.to_numpy64(y), ref, "bf16", case.name)
+    # other activations against the oracle's chain with that activation
+    case = wl.FfnCase(96, 128, 448, 64, "bf16", 6806, name="ffn_packed_relu")
+    tens = case.tensors()
+    t = runner.to_device(case)
+    w1p = torch.empty(ago.packed_weight_shape(case.K, case.F), device="cuda", dtype=torch.bfloat16)
+    w2p = torch.empty(ago.packed_weight_shape(case.F, case.K2), device="cuda", dtype=torch.bfloat16)
+    ago.ago_pack_weight(t["w1"], w1p)
+    ago.ago_pack_weight(t["w2"], w2p)
+    ws = torch.empty(ago.workspace_bytes(ago.OP_FUSED_FFN_PACKED, [case.M, case.K, case.F, case.K2], ago.BF16),
+                     dtype=torch.uint8, device="cuda")
+    for act, name in ((ago.ACT_RELU, "relu"), (ago.ACT_NONE, "none")):
+        y = runner.alloc_output(case)
+        ago.ago_fused_ffn_packed(t["x"], w1p, t["b1"], w2p, t["b2"], y, act, ws)
+        torch.cuda.synchronize()
+        ref = oracle.ffn(tens["x"], tens["w1"], tens["b1"], tens["w2"], tens["b2"], act=name)
+        assert_close(runner.to_numpy64(y), ref, "bf16", case.name + " " + name)
+
+
 def test_sibling_qkv_projection(gpu, oracle):
     """q, k, v = x W* + b* in one kernel, both output layouts, ragged row and column blocks; then the
     projections feed the attention chain without a transpose in between."""
@@ -656,6 +720,44 @@ def test_gemm_op(gpu, oracle, dtype, shape):
                  _dev(torch, res, dtype), c, ago.ACT_RELU)
     ref = oracle.relu(oracle.add(oracle.bias(oracle.gemm(a, b), bias), res))
     assert_close(runner.to_numpy64(c), ref, dtype, "gemm+bias+res+relu")
+
+
+@pytest.mark.parametrize("shape", [(2048, 768, 3072), (2048, 3072, 768), (200, 256, 384), (130, 512, 96),
+                                   (64, 1024, 192), (1, 128, 192)], ids=lambda s: "x".join(map(str, s)))
+def test_gemm_on_packed_weights(gpu, oracle, shape):
+    """The un-fused product on pre-packed weights: both tilings (128 x 192; 64 x 96 with the reduction split over
+    the waves), ragged rows, bias and activation in the epilogue."""
+    torch, ago, runner = gpu
+    M, K, N = shape
+    a, b = _store(rng.normal(21, (M, K)), "bf16"), _store(rng.normal(22, (K, N), 0.1), "bf16")
+    bias = _store(rng.uniform(23, (N,), -1, 1), "f32")
+    wp = torch.empty(ago.packed_weight_shape(K, N), device="cuda", dtype=torch.bfloat16)
+    ago.ago_pack_weight(_dev(torch, b, "bf16"), wp)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    ago.ago_gemm_packed(_dev(torch, a, "bf16"), wp, None, c, ago.ACT_NONE)
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(c), oracle.gemm(a, b), "bf16", "packed gemm")
+    ago.ago_gemm_packed(_dev(torch, a, "bf16"), wp, _dev(torch, bias, "f32"), c, ago.ACT_RELU)
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(c), oracle.relu(oracle.bias(oracle.gemm(a, b), bias)), "bf16", "packed gemm+bias+relu")
+
+
+def test_unfused_ffn_on_packed_weights(gpu, oracle):
+    torch, ago, runner = gpu
+    for case in (wl.FfnCase(2048, 768, 3072, 768, "bf16", 6810, name="ffn_u2_packed_bench"),
+                 wl.FfnCase(100, 512, 1536, 192, "bf16", 6811, name="ffn_u2_packed_small")):
+        ref = oracle.run_case(case)
+        t = runner.to_device(case)
+        w1p = torch.empty(ago.packed_weight_shape(case.K, case.F), device="cuda", dtype=torch.bfloat16)
+        w2p = torch.empty(ago.packed_weight_shape(case.F, case.K2), device="cuda", dtype=torch.bfloat16)
+        ago.ago_pack_weight(t["w1"], w1p)
+        ago.ago_pack_weight(t["w2"], w2p)
+        ws = runner.alloc_workspace(case, fused=False)
+        y = runner.alloc_output(case)
+        y.zero_()
+        ago.ago_unfused_ffn_packed(t["x"], w1p, t["b1"], w2p, t["b2"], y, ago.ACT_GELU_TANH, ws)
+        torch.cuda.synchronize()
+        assert_close(runner.to_numpy64(y), ref, "bf16", case.name)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
