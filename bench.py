@@ -332,6 +332,52 @@ def main():
                 "speedup_vs_epilogue": round(u2_us / fused_us, 2),
             })
 
+    # ---- the FFN chain on pre-packed weights (not part of the step: the step keeps the row-major weights the
+    # configurations name).  Packing is a separate call, once per weight tensor; its cost is reported.
+    packed = None
+    packed_y = None
+    if not args.no_detail and "fused" in args.variants.split(","):
+        for (c, t, y, ws) in state:
+            if type(c).__name__ != "FfnCase":
+                continue
+            w1p = torch.empty(ago.packed_weight_shape(c.K, c.F), device="cuda", dtype=torch.bfloat16)
+            w2p = torch.empty(ago.packed_weight_shape(c.F, c.K2), device="cuda", dtype=torch.bfloat16)
+            pack_us = time_us(lambda: (ago.ago_pack_weight(t["w1"], w1p), ago.ago_pack_weight(t["w2"], w2p)), 10)
+            wsp = torch.empty(ago.workspace_bytes(ago.OP_FUSED_FFN_PACKED, [c.M, c.K, c.F, c.K2], ago.BF16),
+                              dtype=torch.uint8, device="cuda")
+            packed_y = runner.alloc_output(c)
+            fp = ago.prepare(ago.ago_fused_ffn_packed, t["x"], w1p, t["b1"], w2p, t["b2"], packed_y, ago.ACT_GELU_TANH, wsp)
+            f_us = time_us(fp, args.detail_iters)
+            # the streaming kernel alone and the whole call, from the library's event pairs around single calls
+            ago.profile_enable(64)
+            ago.profile_select(1 << ago.OP_FUSED_FFN)
+            for _ in range(32):
+                fp()
+            torch.cuda.synchronize()
+            tot, first, n = ago.profile_read_split(ago.OP_FUSED_FFN)
+            ago.profile_enable(0)
+            ago.profile_select(0xF)
+            k_us = (first / max(n, 1) - ev_overhead_ms) * 1e3
+            yu = runner.alloc_output(c)
+            wsu = runner.alloc_workspace(c, fused=False)
+            u_us = time_us(ago.prepare(ago.ago_unfused_ffn_packed, t["x"], w1p, t["b1"], w2p, t["b2"], yu,
+                                       ago.ACT_GELU_TANH, wsu), args.detail_iters)
+            hid = torch.empty((c.M, c.F), device="cuda", dtype=torch.bfloat16)
+            g1_us = time_us(ago.prepare(ago.ago_gemm_packed, t["x"], w1p, t["b1"], hid, ago.ACT_GELU_TANH), args.detail_iters)
+            g2_us = time_us(ago.prepare(ago.ago_gemm_packed, hid, w2p, t["b2"], yu, ago.ACT_NONE), args.detail_iters)
+            fp()                                   # leave the fused result in packed_y for the oracle check
+            torch.cuda.synchronize()
+            packed = {"name": c.name, "what": "the same chain with w1, w2 pre-packed into matrix-instruction fragments "
+                                              "(ago_pack_weight, once per weight tensor)",
+                      "fused_us": round(f_us, 2), "fused_kernel_us": round(k_us, 2),
+                      "fused_kernel_tflops": round(c.flops() / (k_us * 1e-6) / 1e12, 1),
+                      "fused_kernel_frac": round(c.flops() / (k_us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                      "fused_call_frac": round(c.flops() / (f_us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                      "unfused_epilogue_us": round(u_us, 2),
+                      "gemm1_us": round(g1_us, 2), "gemm1_frac": round(2.0 * c.M * c.K * c.F / (g1_us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                      "gemm2_us": round(g2_us, 2), "gemm2_frac": round(2.0 * c.M * c.F * c.K2 / (g2_us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                      "pack_once_us": round(pack_us, 2), "speedup_vs_epilogue": round(u_us / f_us, 2)}
+
     # ---- the two-operator pairs (not part of the step): fused vs operator by operator --------------
     pairs = []
     if not args.no_detail and not args.no_cold and args.only < 0:
@@ -426,6 +472,11 @@ def main():
             err = float((np.abs(got - ref) / np.maximum(np.abs(ref), rms if rms > 0 else 1.0)).max())
             checks.append({"name": c.name, "max_rel_err": float("%.3e" % err),
                            "ok": bool(np.all(np.isfinite(got)) and err <= (1e-4 if c.dtype == "f32" else 2e-2))})
+            if packed_y is not None and type(c).__name__ == "FfnCase":
+                got = runner.to_numpy64(packed_y)
+                err = float((np.abs(got - ref) / np.maximum(np.abs(ref), rms if rms > 0 else 1.0)).max())
+                checks.append({"name": c.name + " (packed weights)", "max_rel_err": float("%.3e" % err),
+                               "ok": bool(np.all(np.isfinite(got)) and err <= 2e-2)})
         gen0 = time.perf_counter()
         for c in cases:
             c.tensors()
@@ -456,7 +507,7 @@ def main():
                    "note": "config 0 is fp32 storage, configs 1-4 bf16 storage with fp32 accumulation"},
         "roofline": roofline, "measured_peaks": measured, "cpu_baseline": cpu, "one_stream": one_stream,
         "checked_against_oracle": checks,
-        "per_config": per_config, "pairs": pairs, "network_blocks": blocks, "network_body": network,
+        "per_config": per_config, "ffn_packed_weights": packed, "pairs": pairs, "network_blocks": blocks, "network_body": network,
         "fused_kernel_us": {str(k): round(v * 1e3, 2) for k, v in kernel_ms.items()},
     }
     print(json.dumps(out))
