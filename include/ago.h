@@ -218,6 +218,8 @@ ago_status ago_fused_ffn(const void* x, const void* w1, const float* b1,
  *   ago_unfused_ffn_packed   the chain as two such products; workspace = the hidden tensor,
  *                            ago_workspace_bytes(AGO_OP_UNFUSED_FFN, {M,K,F,K2}). */
 size_t ago_packed_weight_bytes(int K, int N);
+/* Host-only: 1 when ago_gemm_packed has a tiling for an [M,K] x [K,N] product, else 0. */
+int ago_gemm_packed_supported(int M, int K, int N);
 ago_status ago_gemm_packed(const void* a, const void* wp, const float* bias, void* c,
                            int M, int K, int N, ago_act act, ago_dtype dt, void* hip_stream);
 ago_status ago_unfused_ffn_packed(const void* x, const void* w1p, const float* b1,

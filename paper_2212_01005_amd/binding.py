@@ -102,6 +102,8 @@ lib.ago_profile_read_split.argtypes = [_i, ctypes.POINTER(_f), ctypes.POINTER(_f
 lib.ago_profile_read_split.restype = _i
 lib.ago_bench_mfma_kernel.argtypes = [_i, _i, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]
 lib.ago_bench_mfma_kernel.restype = _i
+lib.ago_gemm_packed_supported.argtypes = [_i, _i, _i]
+lib.ago_gemm_packed_supported.restype = _i
 lib.ago_packed_weight_bytes.argtypes = [_i, _i]
 lib.ago_packed_weight_bytes.restype = _sz
 lib.ago_bench_empty_kernel.argtypes = [_i, _i, _vp]
@@ -127,7 +129,7 @@ EXPORTED = sorted(list(_SIGS) + ["ago_graph_op_weight", "ago_graph_topological_s
                                  "ago_fused_conv_chain_plan", "ago_fused_attn_plan", "ago_fused_ffn_plan",
                                  "ago_profile_enable", "ago_profile_select", "ago_profile_read", "ago_profile_read_split", "ago_bench_mfma_kernel",
                                  "ago_profile_event_overhead_ms", "ago_profile_last_launch",
-                                 "ago_bench_empty_kernel", "ago_packed_weight_bytes"])
+                                 "ago_bench_empty_kernel", "ago_packed_weight_bytes", "ago_gemm_packed_supported"])
 
 
 class AgoError(RuntimeError):
@@ -408,6 +410,16 @@ def packed_weight_shape(K, N):
     if int(lib.ago_packed_weight_bytes(int(K), int(N))) == 0:
         raise ValueError("a %d x %d matrix cannot be packed (needs K %% 32 == 0 and N %% 16 == 0)" % (K, N))
     return (K // 32, N // 16, 64, 8)
+
+
+def gemm_packed_supported(M, K, N):
+    """Host-only: whether ago_gemm_packed has a tiling for this product."""
+    return bool(lib.ago_gemm_packed_supported(int(M), int(K), int(N)))
+
+
+def fused_ffn_packed_supported(M, K, F, K2):
+    """Host-only: whether ago_fused_ffn_packed takes this shape (its workspace size is then non-zero)."""
+    return workspace_bytes(OP_FUSED_FFN_PACKED, [M, K, F, K2], BF16) > 0
 
 
 @_entry

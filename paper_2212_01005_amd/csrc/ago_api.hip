@@ -357,6 +357,10 @@ ago_status ago_pack_weight(const void* w, void* wp, int K, int N, ago_dtype dt, 
     return from_hip(pack_weight(w, wp, K, N, as_stream(hip_stream)));
 }
 
+int ago_gemm_packed_supported(int M, int K, int N) {
+    return (M > 0 && K > 0 && N > 0 && gemm_packed_variant(M, K, N) != 0) ? 1 : 0;
+}
+
 ago_status ago_gemm_packed(const void* a, const void* wp, const float* bias, void* c, int M, int K, int N,
                            ago_act act, ago_dtype dt, void* hip_stream) {
     ago_status st = check_gemm_packed(a, wp, c, bias, M, K, N, act, dt);

@@ -254,11 +254,26 @@ class Executor:
     """Runs a launch plan with the library's kernels.  ``params`` are device tensors (weights in the graph's
     storage dtype, biases fp32); ``run(inputs)`` returns the tensor of every node that has no consumer."""
 
-    def __init__(self, g, plan, binding, torch, device="cuda:0"):
+    def __init__(self, g, plan, binding, torch, device="cuda:0", pack_weights=False):
+        """pack_weights: the weights of a graph are constants, so the matrix products that have a kernel for it
+        get their weights re-laid out once (``ago_pack_weight``, on the first ``run``) into matrix-instruction
+        fragments and run on the packed kernels from then on: the data-layout choice the paper's tuner makes at
+        compile time (Sec. III), here with one fixed alternative layout."""
         self.g, self.plan, self.ago, self.torch, self.device = g, plan, binding, torch, device
         self.shapes = infer_shapes(g)
         self.td = torch.bfloat16 if g.dtype == "bf16" else torch.float32
         self.launches = 0
+        self.pack_weights = bool(pack_weights) and g.dtype == "bf16"
+        self.packed = {}                   # parameter name -> packed copy
+
+    def _packed(self, name):
+        """The packed copy of weight `name`, made on first use."""
+        if name not in self.packed:
+            w = self.g.params[name]
+            wp = self.torch.empty(self.ago.packed_weight_shape(w.shape[0], w.shape[1]), dtype=w.dtype, device=self.device)
+            self.ago.ago_pack_weight(w, wp)
+            self.packed[name] = wp
+        return self.packed[name]
 
     def _new(self, i):
         return self.torch.empty(self.shapes[i], dtype=self.td, device=self.device)
@@ -331,15 +346,26 @@ class Executor:
                 act = next(n.op for n in nodes if n.op in _ACT_OF)
                 w1, w2 = P[nodes[pos[0]].attrs["w"]], P[nodes[pos[1]].attrs["w"]]
                 dims = [x.shape[0], x.shape[1], w1.shape[1], w2.shape[1]]
+                n1, n2 = nodes[pos[0]].attrs["w"], nodes[pos[1]].attrs["w"]
                 if kind == "ffn":
-                    ws = self._workspace(ago.OP_FUSED_FFN, dims, ago.BF16)
-                    ago.ago_fused_ffn(x, w1, self._bias_of(nodes, pos[0]), w2, self._bias_of(nodes, pos[1]), out,
-                                      getattr(ago, _ACT_OF[act]), ws)
+                    if self.pack_weights and ago.fused_ffn_packed_supported(*dims):
+                        ws = self._workspace(ago.OP_FUSED_FFN_PACKED, dims, ago.BF16)
+                        ago.ago_fused_ffn_packed(x, self._packed(n1), self._bias_of(nodes, pos[0]), self._packed(n2),
+                                                 self._bias_of(nodes, pos[1]), out, getattr(ago, _ACT_OF[act]), ws)
+                    else:
+                        ws = self._workspace(ago.OP_FUSED_FFN, dims, ago.BF16)
+                        ago.ago_fused_ffn(x, w1, self._bias_of(nodes, pos[0]), w2, self._bias_of(nodes, pos[1]), out,
+                                          getattr(ago, _ACT_OF[act]), ws)
                 else:                                  # two products with fused epilogues (two launches)
                     self.launches += 1
                     ws = self._workspace(ago.OP_UNFUSED_FFN, dims, ago.BF16)
-                    ago.ago_unfused_ffn(x, w1, self._bias_of(nodes, pos[0]), w2, self._bias_of(nodes, pos[1]), out,
-                                        getattr(ago, _ACT_OF[act]), True, ws)
+                    if (self.pack_weights and ago.gemm_packed_supported(dims[0], dims[1], dims[2])
+                            and ago.gemm_packed_supported(dims[0], dims[2], dims[3])):
+                        ago.ago_unfused_ffn_packed(x, self._packed(n1), self._bias_of(nodes, pos[0]), self._packed(n2),
+                                                   self._bias_of(nodes, pos[1]), out, getattr(ago, _ACT_OF[act]), ws)
+                    else:
+                        ago.ago_unfused_ffn(x, w1, self._bias_of(nodes, pos[0]), w2, self._bias_of(nodes, pos[1]), out,
+                                            getattr(ago, _ACT_OF[act]), True, ws)
             elif kind == "attn":
                 k_t = val[nodes[0].inputs[1]]
                 v_t = val[[s for s in nodes[3].inputs if s not in ids][0]]
@@ -372,7 +398,11 @@ class Executor:
         if n.op == "conv1x1":
             ago.ago_conv1x1(a, P[n.attrs["w"]], None, None, out)
         elif n.op == "gemm":
-            ago.ago_gemm(a, P[n.attrs["w"]], None, None, out)
+            w = P[n.attrs["w"]]
+            if self.pack_weights and ago.gemm_packed_supported(a.shape[0], w.shape[0], w.shape[1]):
+                ago.ago_gemm_packed(a, self._packed(n.attrs["w"]), None, out)
+            else:
+                ago.ago_gemm(a, w, None, None, out)
         elif n.op == "dwconv":
             if P[n.attrs["w"]].shape[0] != 3:
                 raise NotImplementedError("un-fused depthwise kernels other than 3x3")

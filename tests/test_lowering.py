@@ -395,3 +395,54 @@ def test_large_ffn_runs_as_two_epilogue_fused_products():
     r = ref[i]
     gotn = got.float().cpu().numpy().astype(np.float64)
     assert np.max(np.abs(gotn - r) / np.maximum(np.abs(r), np.sqrt(np.mean(r ** 2)))) <= 3e-2    # hidden tensor rounded once more
+
+
+@pytest.mark.gpu
+def test_constant_weights_are_packed_once_and_the_packed_kernels_run():
+    """pack_weights: the executor packs each constant weight on first use and then runs the chain on the packed
+    kernels - fused where the library says fusing pays, as two packed products where it does not, and a lone
+    product on the packed un-fused kernel; every result against the oracle's operator-by-operator evaluation."""
+    import torch
+    from oracle import ago_oracle
+    from paper_2212_01005_amd import binding as ago
+
+    def to_dev(g):
+        g.params = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to("cuda:0").to(
+            torch.float32 if k.startswith("b") else torch.bfloat16).contiguous() for k, v in g.params.items()}
+
+    for rows, k, f, want in ((512, 128, 768, "ffn"), (16384, 384, 1536, "ffn_epilogue")):
+        g = _ffn_graph(rows, k, f)
+        plan = L.lower(g, [0] * len(g.nodes), ago)
+        assert [kind for kind, _ in plan] == [want]
+        x = wl.round_to_bf16(wl.normal(9520, (rows, k), 1.0))
+        ref = _oracle_eval(g, {"x": x}, ago_oracle)
+        to_dev(g)
+        ex = L.Executor(g, plan, ago, torch, pack_weights=True)
+        xd = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to("cuda:0").to(torch.bfloat16)
+        for _ in range(2):                                   # the second pass re-uses the packed copies
+            out = ex.run({"x": xd})
+        torch.cuda.synchronize()
+        assert sorted(ex.packed) == ["w1", "w2"]
+        (i, got), = out.items()
+        r = ref[i]
+        gotn = got.float().cpu().numpy().astype(np.float64)
+        bar = 2e-2 if want == "ffn" else 3e-2               # two products: the hidden tensor is rounded once more
+        assert np.max(np.abs(gotn - r) / np.maximum(np.abs(r), np.sqrt(np.mean(r ** 2)))) <= bar, want
+
+    # a lone product
+    g = L.Graph([], {}, "bf16")
+    x_id = g.add("input", name="x", shape=(256, 256))
+    g.params["w"] = wl.round_to_bf16(wl.normal(9530, (256, 384), 256 ** -0.5))
+    g.add("gemm", [x_id], w="w")
+    plan = L.lower(g, list(range(len(g.nodes))), ago)
+    x = wl.round_to_bf16(wl.normal(9531, (256, 256), 1.0))
+    ref = _oracle_eval(g, {"x": x}, ago_oracle)
+    to_dev(g)
+    ex = L.Executor(g, plan, ago, torch, pack_weights=True)
+    out = ex.run({"x": torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to("cuda:0").to(torch.bfloat16)})
+    torch.cuda.synchronize()
+    assert list(ex.packed) == ["w"]
+    (i, got), = out.items()
+    r = ref[i]
+    gotn = got.float().cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(gotn - r) / np.maximum(np.abs(r), np.sqrt(np.mean(r ** 2)))) <= 2e-2
