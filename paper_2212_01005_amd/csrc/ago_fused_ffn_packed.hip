@@ -48,20 +48,37 @@ __device__ __forceinline__ bf16x8 lds_frag(const unsigned char* p) {
     return *reinterpret_cast<const bf16x8*>(p);
 }
 
-// [K][N] row-major -> fragments; one thread per lane of a fragment
+// [K][N] row-major -> fragments.  A workgroup takes one k-step (32 rows) x 128 columns: the rows are read
+// 16 bytes per thread (coalesced), parked in LDS, and every thread then gathers the 8 k-values of its
+// lane for two fragments and writes them as 16 bytes.  Columns past N (N % 128 != 0) are skipped.
 __global__ __launch_bounds__(256) void pack_weight_kernel(const bf16_t* __restrict__ w, u32x4_t* __restrict__ wp,
                                                           int K, int N) {
-    const long total = (long)(K / 32) * (N / 16) * 64;
-    for (long u = blockIdx.x * 256L + threadIdx.x; u < total; u += (long)gridDim.x * 256) {
-        const int l = (int)(u & 63);
-        const long frag = u >> 6;
-        const int nt = (int)(frag % (N / 16)), ks = (int)(frag / (N / 16));
-        const bf16_t* src = w + (long)(32 * ks + 8 * (l >> 4)) * N + 16 * nt + (l & 15);
-        uint16_t e[8];
+    constexpr int TN = 128, LD = TN + 8;                  // LDS row: 136 elements (272 bytes)
+    __shared__ __attribute__((aligned(16))) uint16_t tile[32 * LD];
+    const int ks = blockIdx.y, n0 = blockIdx.x * TN, tid = threadIdx.x;
+    (void)K;
+    // 32 rows x 16 units of 16 bytes = 512 units, two per thread
 #pragma unroll
-        for (int q = 0; q < 8; ++q) e[q] = __builtin_bit_cast(uint16_t, src[(long)q * N]);
-        wp[u] = u32x4_t{(unsigned)e[0] | ((unsigned)e[1] << 16), (unsigned)e[2] | ((unsigned)e[3] << 16),
+    for (int q = 0; q < 2; ++q) {
+        const int u = tid + 256 * q, r = u >> 4, c = u & 15;
+        if (n0 + c * 8 < N)
+            *reinterpret_cast<u32x4_t*>(&tile[r * LD + c * 8]) =
+                *reinterpret_cast<const u32x4_t*>(w + (long)(32 * ks + r) * N + n0 + c * 8);
+    }
+    __syncthreads();
+    // 8 fragments (16 columns each) x 64 lanes = 512 outputs, two per thread
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int o = tid + 256 * q, f = o >> 6, l = o & 63;
+        const int col = f * 16 + (l & 15);
+        if (n0 + col < N) {
+            uint16_t e[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) e[t] = tile[(8 * (l >> 4) + t) * LD + col];
+            wp[((long)ks * (N / 16) + n0 / 16 + f) * 64 + l] =
+                u32x4_t{(unsigned)e[0] | ((unsigned)e[1] << 16), (unsigned)e[2] | ((unsigned)e[3] << 16),
                         (unsigned)e[4] | ((unsigned)e[5] << 16), (unsigned)e[6] | ((unsigned)e[7] << 16)};
+        }
     }
 }
 
@@ -192,32 +209,39 @@ __global__ __launch_bounds__(kThreads) void fused_ffn_packed_kernel(
 #pragma unroll
         for (int n = 0; n < kNT; ++n) acc[m][n] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // one k-step: activation fragments from LDS, 12 matrix instructions on the slot's weight fragments, refill
-    // the slot PD steps ahead.  The scheduling barriers keep the refill where it is written: left to itself the
-    // compiler sinks the loads down to their use and the stream stops running ahead.
-    auto step = [&](u32x4_t (&slot)[kNT], const unsigned char* bsrc, int row_stride) {
-        bf16x8 b[kMT];
+    // one k-step: 12 matrix instructions on the slot's weight fragments and the activation fragments `cur`
+    // (read from LDS during the previous step), the next step's activation fragments requested into `nxt` ahead
+    // of them, the slot refilled PD steps ahead after them.  The scheduling barriers keep the order as written:
+    // left to itself the compiler sinks the loads down to their use and nothing runs ahead any more.
+    auto step = [&](u32x4_t (&slot)[kNT], const bf16x8 (&cur)[kMT], bf16x8 (&nxt)[kMT], const unsigned char* next_src,
+                    int row_stride) {
 #pragma unroll
-        for (int m = 0; m < kMT; ++m) b[m] = lds_frag(bsrc + m * 16 * row_stride);
+        for (int m = 0; m < kMT; ++m) nxt[m] = lds_frag(next_src + m * 16 * row_stride);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int m = 0; m < kMT; ++m)
 #pragma unroll
             for (int n = 0; n < kNT; ++n)
-                acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, slot[n]), b[m], acc[m][n], 0, 0, 0);
+                acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, slot[n]), cur[m], acc[m][n], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         issue_step<RAGGED>(s, slot, voff1, voff2, voff2_last);
         __builtin_amdgcn_sched_barrier(0);
     };
+    // a loop of nk k-steps (a multiple of PD, PD even) over activation rows at `src`; the fragments of the step
+    // after the last are read from the last step's address again and dropped
+    bf16x8 frag[2][kMT];
+    auto k_loop = [&](const unsigned char* src, int row_stride, int nk) {
+#pragma unroll
+        for (int m = 0; m < kMT; ++m) frag[0][m] = lds_frag(src + m * 16 * row_stride);
+        for (int k = 0; k < nk; k += PD) {
+#pragma unroll
+            for (int j = 0; j < PD; ++j)
+                step(ring[j], frag[j & 1], frag[(j + 1) & 1], src + min(k + j + 1, nk - 1) * 64, row_stride);
+        }
+    };
 
     // ---- phase 1: D[hidden unit][row of x] += W1 fragment x x fragment
-    {
-        const unsigned char* xb = lds + i * XS + g * 16;
-        for (int k = 0; k < nk1; k += PD) {
-#pragma unroll
-            for (int j = 0; j < PD; ++j) step(ring[j], xb + (k + j) * 64, XS);
-        }
-    }
+    k_loop(lds + i * XS + g * 16, XS, nk1);
     lds_barrier();        // every wave is done reading x: the hidden tile takes its place
 
     // ---- activation, bf16, into LDS as [row of x][hidden unit of the slice]
@@ -246,10 +270,7 @@ __global__ __launch_bounds__(kThreads) void fused_ffn_packed_kernel(
     // ---- phase 2: per column block, D[output column][row of x] += W2 fragment x hidden fragment
     const unsigned char* hb = lds + i * kHS + g * 16;
     for (int cb = 0; cb < ncb; ++cb) {
-        for (int k = 0; k < nk2; k += PD) {
-#pragma unroll
-            for (int j = 0; j < PD; ++j) step(ring[j], hb + (k + j) * 64, kHS);
-        }
+        k_loop(hb, kHS, nk2);
         // partial sums of this block: lane = row of x, 4 consecutive output columns per tile
 #pragma unroll
         for (int n = 0; n < kNT; ++n) {
@@ -281,10 +302,8 @@ long fused_ffn_packed_rows(int M) { return ((long)M + kBM - 1) / kBM * kBM; }
 int fused_ffn_packed_nsplit(int F) { return (F + kFS - 1) / kFS; }
 
 hipError_t pack_weight(const void* w, void* wp, int K, int N, hipStream_t s) {
-    const long total = (long)(K / 32) * (N / 16) * 64;
-    long g = (total + 255) / 256;
-    if (g > 4096) g = 4096;
-    hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)g), dim3(256), 0, s, (const bf16_t*)w, (u32x4_t*)wp, K, N);
+    dim3 grid((N + 127) / 128, K / 32);
+    hipLaunchKernelGGL(pack_weight_kernel, grid, dim3(256), 0, s, (const bf16_t*)w, (u32x4_t*)wp, K, N);
     return hipGetLastError();
 }
 

@@ -21,34 +21,36 @@ namespace {
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 512;
-constexpr int kMT = 4, kNT = 3, kPD = 4;
+constexpr int kNT = 3, kPD = 4;
 
 __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-template <int BM, int BN, int KG>
+template <int BM, int BN, int RG, int KG>
 struct PackedCfg {
-    static constexpr int RG = BM / 64, CG = BN / 48;
+    static constexpr int CG = BN / 48;
     static_assert(RG * CG * KG == 8, "eight waves");
+    static constexpr int MT = BM / RG / 16;             // 16-row tiles per wave
     static constexpr int KT = 128 * KG;                 // k-values per LDS tile: four k-steps per k group
     static constexpr int AS = KT * 2 + 16;              // bytes per row of an A tile (16 mod 256: conflict-free 16-byte reads)
     static constexpr int kStage = BM * AS;
     static constexpr int UPT = BM * KT / 8 / kThreads;  // 16-byte units of an A tile per thread
-    static constexpr int kReduce = (KG - 1) * RG * CG * kMT * kNT * 1024;
+    static constexpr int kReduce = (KG - 1) * RG * CG * MT * kNT * 1024;
     static constexpr int kSmem = (2 * kStage > kReduce ? 2 * kStage : kReduce);
 };
 
-template <int BM, int BN, int KG>
+template <int BM, int BN, int RG, int KG>
 __global__ __launch_bounds__(kThreads) void gemm_packed_kernel(const bf16_t* __restrict__ A,
                                                                const unsigned char* __restrict__ Wp,
                                                                const float* __restrict__ bias, bf16_t* __restrict__ C,
                                                                int M, int K, int N, int act, int xcd_cols) {
-    typedef PackedCfg<BM, BN, KG> Cfg;
+    typedef PackedCfg<BM, BN, RG, KG> Cfg;
+    constexpr int kMT = Cfg::MT;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, g = lane >> 4;
-    const int cg = wave % Cfg::CG, rg = (wave / Cfg::CG) % Cfg::RG, kg = wave / (Cfg::CG * Cfg::RG);
+    const int cg = wave % Cfg::CG, rg = (wave / Cfg::CG) % RG, kg = wave / (Cfg::CG * RG);
     // Workgroups are dealt to the 8 XCDs (one L2 each) round-robin in launch order.  With xcd_cols = XC > 0 the
     // grid is cut into XC x (8 / XC) rectangles, one per XCD, so that an L2 fetches only its rectangle's rows of A
     // and columns of W instead of one operand in full.
@@ -112,7 +114,7 @@ __global__ __launch_bounds__(kThreads) void gemm_packed_kernel(const bf16_t* __r
 #pragma unroll
         for (int n = 0; n < kNT; ++n) acc[m][n] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const unsigned char* abase = lds + (rg * 64 + i) * Cfg::AS + (4 * kg) * 64 + g * 16;
+    const unsigned char* abase = lds + (rg * (BM / RG) + i) * Cfg::AS + (4 * kg) * 64 + g * 16;
     for (int t = 0; t < nt; ++t) {
         const int tn = min(t + 1, nt - 1);                    // past the end: the last tile again, never used
         load_a(tn);
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(kThreads) void gemm_packed_kernel(const bf16_t* __r
     // ---- k groups 1.. hand their partial sums to group 0 through LDS (the A tiles are no longer needed)
     if constexpr (KG > 1) {
         unsigned char* red = lds + ((rg * Cfg::CG + cg) * kMT * kNT) * 1024 + lane * 16;
-        constexpr int kGroupBytes = Cfg::RG * Cfg::CG * kMT * kNT * 1024;
+        constexpr int kGroupBytes = RG * Cfg::CG * kMT * kNT * 1024;
         if (kg > 0) {
 #pragma unroll
             for (int m = 0; m < kMT; ++m)
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(kThreads) void gemm_packed_kernel(const bf16_t* __r
         const f32x4 bv = bias ? *reinterpret_cast<const f32x4*>(bias + col) : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int m = 0; m < kMT; ++m) {
-            const int row = m_blk + rg * 64 + m * 16 + i;
+            const int row = m_blk + rg * (BM / RG) + m * 16 + i;
             if (row < M) {
                 float v[4];
 #pragma unroll
@@ -179,17 +181,17 @@ __global__ __launch_bounds__(kThreads) void gemm_packed_kernel(const bf16_t* __r
     }
 }
 
-template <int BM, int BN, int KG>
+template <int BM, int BN, int RG, int KG>
 hipError_t launch_packed_gemm(const void* a, const void* wp, const float* bias, void* c, int M, int K, int N, int act,
                               hipStream_t s) {
-    typedef PackedCfg<BM, BN, KG> Cfg;
-    if (hipError_t e = allow_dynamic_lds<gemm_packed_kernel<BM, BN, KG>>(Cfg::kSmem); e != hipSuccess) return e;
+    typedef PackedCfg<BM, BN, RG, KG> Cfg;
+    if (hipError_t e = allow_dynamic_lds<gemm_packed_kernel<BM, BN, RG, KG>>(Cfg::kSmem); e != hipSuccess) return e;
     dim3 grid(N / BN, (M + BM - 1) / BM);
     // 2 x 4 rectangles for the narrow tiling when the grid divides that way: in launch order every XCD would
     // fetch all of A (2048 x 3072 -> 768: 24.5 us in launch order, 20.6 us in rectangles).  The wide tiling
     // stays in launch order, an XCD owning column tiles (2048 x 768 -> 3072: 19.6 us against 23.2 us in rectangles).
     const int xcd_cols = (KG > 1 && grid.x % 2 == 0 && grid.y % 4 == 0 && grid.x * grid.y >= 64) ? 2 : 0;
-    hipLaunchKernelGGL((gemm_packed_kernel<BM, BN, KG>), grid, dim3(kThreads), Cfg::kSmem, s, (const bf16_t*)a,
+    hipLaunchKernelGGL((gemm_packed_kernel<BM, BN, RG, KG>), grid, dim3(kThreads), Cfg::kSmem, s, (const bf16_t*)a,
                        (const unsigned char*)wp, bias, (bf16_t*)c, M, K, N, act, xcd_cols);
     return hipGetLastError();
 }
@@ -206,11 +208,13 @@ int gemm_packed_variant(int M, int K, int N) {
     return 0;
 }
 
+int g_gemm_packed_force = 0;     // experiment hook
 hipError_t gemm_packed(const void* a, const void* wp, const float* bias, void* c, int M, int K, int N, int act,
                        hipStream_t s) {
-    switch (gemm_packed_variant(M, K, N)) {
-        case 1: return launch_packed_gemm<128, 192, 1>(a, wp, bias, c, M, K, N, act, s);
-        case 2: return launch_packed_gemm<64, 96, 4>(a, wp, bias, c, M, K, N, act, s);
+    switch (g_gemm_packed_force ? g_gemm_packed_force : gemm_packed_variant(M, K, N)) {
+        case 1: return launch_packed_gemm<128, 192, 2, 1>(a, wp, bias, c, M, K, N, act, s);
+        case 2: return launch_packed_gemm<64, 96, 1, 4>(a, wp, bias, c, M, K, N, act, s);
+        case 3: return launch_packed_gemm<128, 192, 1, 2>(a, wp, bias, c, M, K, N, act, s);
         default: return hipErrorInvalidValue;
     }
 }
