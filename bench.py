@@ -58,7 +58,7 @@ def parse():
                          "exactly that many bytes, which scales the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--no-cold", action="store_true",
                     help="skip the cold-cache timings and launch floors of the per-config table (profiling aid)")
-    ap.add_argument("--variants", default="fused,u1,u2",
+    ap.add_argument("--variants", default="fused,u1,u2,packed",
                     help="which variants the per-config table runs (profiling aid: counters of one variant alone)")
     ap.add_argument("--tile-config", default="",
                     help="tile-size sweep aid: comma-separated op=id pairs (op: invres, chain, ffn, attn) passed to "
@@ -336,7 +336,7 @@ def main():
     # configurations name).  Packing is a separate call, once per weight tensor; its cost is reported.
     packed = None
     packed_y = None
-    if not args.no_detail and "fused" in args.variants.split(","):
+    if not args.no_detail and "packed" in args.variants.split(","):
         for (c, t, y, ws) in state:
             if type(c).__name__ != "FfnCase":
                 continue
