@@ -742,6 +742,39 @@ def test_gemm_on_packed_weights(gpu, oracle, shape):
     assert_close(runner.to_numpy64(c), oracle.relu(oracle.bias(oracle.gemm(a, b), bias)), "bf16", "packed gemm+bias+relu")
 
 
+def _random_packed_ffn_cases():
+    r = np.random.RandomState(20221207)
+    out = []
+    for i in range(12):
+        k = 64 * int(r.randint(1, 20))                       # up to 1216: the x tile must fit LDS
+        f = 64 * int(r.randint(1, 20))
+        k2 = 16 * int(r.randint(1, 60))
+        out.append(wl.FfnCase(int(r.randint(1, 260)), k, f, k2, "bf16", 6900 + i,
+                              name="rand_packed_ffn_%dx%dx%dx" % (k, f, k2)))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_packed_ffn_cases(), ids=lambda c: c.name)
+def test_packed_ffn_random_shapes(gpu, oracle, case):
+    """Random rows, reductions, hidden widths (ragged last slice, one to five slices) and output widths
+    (ragged last column block) against the oracle."""
+    torch, ago, runner = gpu
+    ref = oracle.run_case(case)
+    t = runner.to_device(case)
+    w1p = torch.empty(ago.packed_weight_shape(case.K, case.F), device="cuda", dtype=torch.bfloat16)
+    w2p = torch.empty(ago.packed_weight_shape(case.F, case.K2), device="cuda", dtype=torch.bfloat16)
+    ago.ago_pack_weight(t["w1"], w1p)
+    ago.ago_pack_weight(t["w2"], w2p)
+    ws = torch.empty(ago.workspace_bytes(ago.OP_FUSED_FFN_PACKED, [case.M, case.K, case.F, case.K2], ago.BF16),
+                     dtype=torch.uint8, device="cuda")
+    y = runner.alloc_output(case)
+    y.zero_()
+    print("packed ffn", case, flush=True)
+    ago.ago_fused_ffn_packed(t["x"], w1p, t["b1"], w2p, t["b2"], y, ago.ACT_GELU_TANH, ws)
+    torch.cuda.synchronize()
+    assert_close(runner.to_numpy64(y), ref, "bf16", "%s %r" % (case.name, case))
+
+
 def test_unfused_ffn_on_packed_weights(gpu, oracle):
     torch, ago, runner = gpu
     for case in (wl.FfnCase(2048, 768, 3072, 768, "bf16", 6810, name="ffn_u2_packed_bench"),
