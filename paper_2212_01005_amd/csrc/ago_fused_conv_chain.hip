@@ -12,10 +12,12 @@
 //   swap   barrier, Wb registers -> the weight area of LDS, barrier
 //   conv2  Y = relu(conv3x3(T) + bb (+ X)) on TH x TW -> global memory
 // Both convolutions are implicit GEMMs [pixels] x [9 taps x 64] x [64] on 32x32x16 bf16 matrix
-// instructions, on up to 15 of 16 waves (four per SIMD: a single wave cannot issue LDS fragment
-// reads fast enough to keep its SIMD's matrix pipe busy).  The work of each convolution is dealt
-// out as (32-pixel row tile, kernel row) units, one per wave; the three partial sums of a row tile
-// are added through LDS.
+// instructions.  The work of each convolution is dealt out as (32-pixel row tile, half of the output
+// channels) units, one per wave, each running all nine taps over all 64 input channels into one accumulator:
+// 10 units for conv1 and 8 for conv2 at 7 x 14, two to three waves per SIMD, and nothing to exchange afterwards.
+// (The earlier cut, (row tile, kernel row) units whose three partial sums met in LDS, needed one activation
+// fragment per two matrix instructions instead of one per one, but paid 2.8 us for the two exchanges; it is
+// kept as tile configurations 4 and 5: 12.5 us against 10.9 us on 8 x 56 x 56 x 64.)
 //
 // LDS layouts.  A 16-byte-per-lane fragment read is served one half-wave (32 lanes) at a time and is
 // bank-conflict free when the 32 rows it touches are 144 bytes apart (72-element rows) or fall into
@@ -145,6 +147,55 @@ struct ConvStage {
     }
 };
 
+// The other way to cut a convolution into units: (32-pixel row tile, half of the output channels), 2 NMT of
+// them, each running all nine taps.  One accumulator per unit and nothing to exchange afterwards, at the
+// price of one activation fragment per matrix instruction instead of one per two.
+template <int SRC_ROW, int DST_P, int DST_W, int NP, int NMT>
+struct ConvStageFull {
+    static constexpr int LD = 72;
+    static constexpr int NU = 2 * NMT;
+    static_assert(NU <= 16, "one unit per wave");
+    f32x16 acc;                                         // output channels 32 half .. 32 half + 31
+    int off;                                            // LDS offset of this lane's pixel, kernel row 0, column 0
+    int wbase;                                          // LDS offset of this lane's weight row, tap 0
+    int swz;
+
+    __device__ __forceinline__ static bool live(int wave) { return wave < NU; }
+    __device__ __forceinline__ static int tile(int wave) { return wave >> 1; }
+    __device__ __forceinline__ static int half(int wave) { return wave & 1; }
+
+    __device__ __forceinline__ void init(int wave, int j, int h) {
+        int m = tile(wave) * 32 + j;
+        if (m >= NP) m = 0;
+        const int px = (m % DST_P) < DST_W ? m % DST_P : 0;
+        off = (m / DST_P) * SRC_ROW + px * LD + 8 * h;
+        wbase = (half(wave) * 32 + j) * LD;
+        swz = half(wave);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    }
+    struct Frag { bf16x8 x, w; };
+    __device__ __forceinline__ Frag fetch(const bf16_t* src, const bf16_t* ws, int step, int h) const {
+        const int tap = step >> 2, ks = step & 3, kr = tap / 3, col = tap % 3;
+        Frag f;
+        f.x = ld_bf16x8(src + off + kr * SRC_ROW + col * LD + ks * 16);
+        f.w = ld_bf16x8(ws + wbase + tap * 64 * LD + (((ks * 2 + h) ^ swz) << 3));
+        return f;
+    }
+    __device__ __forceinline__ void run(const bf16_t* src, const bf16_t* ws, int h) {
+        constexpr int DEPTH = 4, STEPS = 36;
+        Frag q[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) q[d] = fetch(src, ws, d, h);
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const Frag cur = q[s % DEPTH];
+            if (s + DEPTH < STEPS) q[s % DEPTH] = fetch(src, ws, s + DEPTH, h);
+            acc = mfma32(cur.w, cur.x, acc);
+        }
+    }
+};
+
 // All nine taps of one weight tensor [3][3][64 in][64 out] -> LDS [tap][out][in]: 9 * 128 transposition
 // units of [8 in][4 out]; unit u -> tap u / 128, out-channel quad (u & 15), in-channel octet (u >> 4) & 7.
 __device__ __forceinline__ void load_weight_unit(const bf16_t* Wsrc, int u, uint2 (&r)[8]) {
@@ -178,7 +229,7 @@ __device__ __forceinline__ void store_weight_unit(bf16_t* Ws, int u, const uint2
     }
 }
 
-template <int TH, int TW>
+template <int TH, int TW, bool FULL = true>
 __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wa, const float* __restrict__ ba,
     const bf16_t* __restrict__ Wb, const float* __restrict__ bb, bf16_t* __restrict__ Y,
@@ -228,7 +279,30 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
     load_w(Wb);            // in flight during conv1
 
     // ---- conv1: rows = output channels (weights are operand A), cols = region pixels --------
-    {
+    if constexpr (FULL) {
+        typedef ConvStageFull<XROW, R1W, R1W, P1, G::NMT1> Stage;
+        Stage st;
+        if (Stage::live(wave)) {
+            st.init(wave, j, h);
+            st.run(Xs, Ws, h);
+            const int m = Stage::tile(wave) * 32 + j;
+            if (m < P1) {
+                const int y = oh0 - 1 + m / R1W, x = ow0 - 1 + m % R1W;
+                const bool inside = y >= 0 && y < H && x >= 0 && x < W;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int o = Stage::half(wave) * 32 + 8 * g + 4 * h;
+                    uint2 v = make_uint2(0, 0);
+                    if (inside) {
+                        const float4 bv = *reinterpret_cast<const float4*>(Bias + o);
+                        v = make_uint2(pack_bf16(fmaxf(st.acc[4 * g] + bv.x, 0.f), fmaxf(st.acc[4 * g + 1] + bv.y, 0.f)),
+                                       pack_bf16(fmaxf(st.acc[4 * g + 2] + bv.z, 0.f), fmaxf(st.acc[4 * g + 3] + bv.w, 0.f)));
+                    }
+                    *reinterpret_cast<uint2*>(Ts + (m / R1W) * TROW + (m % R1W) * LD + o) = v;
+                }
+            }
+        }
+    } else {
         typedef ConvStage<XROW, R1W, R1W, P1, G::NMT1> Stage;
         Stage st;
         const bool live = Stage::live(wave);
@@ -268,7 +342,32 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
     __syncthreads();
 
     // ---- conv2: rows = output channels, cols = output pixels --------------------------------
-    {
+    if constexpr (FULL) {
+        typedef ConvStageFull<TROW, P2W, TW, P2, G::NMT2> Stage;
+        Stage st;
+        if (Stage::live(wave)) {
+            st.init(wave, j, h);
+            st.run(Ts, Ws, h);
+            const int m = Stage::tile(wave) * 32 + j;
+            const int py = m / P2W, px = m % P2W;
+            const int y = oh0 + py, x = ow0 + px;
+            if (m < P2 && px < TW && y < H && x < W) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int o = Stage::half(wave) * 32 + 8 * g + 4 * h;
+                    float4 v = make_float4(st.acc[4 * g], st.acc[4 * g + 1], st.acc[4 * g + 2], st.acc[4 * g + 3]);
+                    const float4 bv = *reinterpret_cast<const float4*>(Bias + 64 + o);
+                    v.x += bv.x; v.y += bv.y; v.z += bv.z; v.w += bv.w;
+                    if (residual) {
+                        const uint2 xr = *reinterpret_cast<const uint2*>(Xs + (py + 2) * XROW + (px + 2) * LD + o);
+                        v.x += lo_bf16(xr.x); v.y += hi_bf16(xr.x); v.z += lo_bf16(xr.y); v.w += hi_bf16(xr.y);
+                    }
+                    *reinterpret_cast<uint2*>(Y + ((long)y * W + x) * C + o) =
+                        make_uint2(pack_bf16(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f)), pack_bf16(fmaxf(v.z, 0.f), fmaxf(v.w, 0.f)));
+                }
+            }
+        }
+    } else {
         typedef ConvStage<TROW, P2W, TW, P2, G::NMT2> Stage;
         Stage st;
         const bool live = Stage::live(wave);
@@ -308,14 +407,14 @@ __global__ __launch_bounds__(1024) void fused_conv_chain_kernel(
     }
 }
 
-template <int TH, int TW>
+template <int TH, int TW, bool FULL = true>
 static hipError_t launch_chain(const void* x, const void* wa, const float* ba, const void* wb,
                                const float* bb, void* y, int N, int H, int W, int residual,
                                hipStream_t s) {
     constexpr size_t smem = ChainGeom<TH, TW>::kSmem;
     static_assert(smem <= 160 * 1024, "LDS");
-    auto kern = fused_conv_chain_kernel<TH, TW>;
-    if (hipError_t e = allow_dynamic_lds<fused_conv_chain_kernel<TH, TW>>((int)((int)smem)); e != hipSuccess) return e;
+    auto kern = fused_conv_chain_kernel<TH, TW, FULL>;
+    if (hipError_t e = allow_dynamic_lds<fused_conv_chain_kernel<TH, TW, FULL>>((int)((int)smem)); e != hipSuccess) return e;
     const int tiles_h = (H + TH - 1) / TH, tiles_w = (W + TW - 1) / TW;
     prof_start(1, s);
     prof_shape(1, (unsigned)(N * tiles_h * tiles_w), 1024);
@@ -370,29 +469,19 @@ __global__ __launch_bounds__(1024) void conv3x3_tile_kernel(
     if (tid < 9 * 128 - 1024) store_weight_unit(Ws, 1024 + tid, extra);
     __syncthreads();
 
-    typedef ConvStage<TROW, P2W, TW, P2, G::NMT2> Stage;
+    typedef ConvStageFull<TROW, P2W, TW, P2, G::NMT2> Stage;
     Stage st;
-    const bool live = Stage::live(wave);
-    const int me = Stage::tg(wave);
-    if (live) {
+    if (Stage::live(wave)) {
         st.init(wave, j, h);
         st.run(Ts, Ws, h);
-    }
-    __syncthreads();                           // the weights are dead: their LDS area becomes reduction scratch
-    if (live) st.park(reinterpret_cast<float*>(Ws), wave, lane);
-    __syncthreads();
-    if (live) {
-        st.gather(reinterpret_cast<const float*>(Ws), wave, lane);
         const int m = Stage::tile(wave) * 32 + j;
         const int py = m / P2W, px = m % P2W;
         const int y = oh0 + py, x = ow0 + px;
         if (m < P2 && px < TW && y < H && x < W) {
 #pragma unroll
-            for (int grp = 0; grp < 8; ++grp) {
-                if (Stage::owner_of(grp) != me) continue;
-                const int ot = grp >> 2, g = grp & 3;
-                const int o = ot * 32 + 8 * g + 4 * h;
-                float4 v = make_float4(st.acc[ot][4 * g], st.acc[ot][4 * g + 1], st.acc[ot][4 * g + 2], st.acc[ot][4 * g + 3]);
+            for (int g = 0; g < 4; ++g) {
+                const int o = Stage::half(wave) * 32 + 8 * g + 4 * h;
+                float4 v = make_float4(st.acc[4 * g], st.acc[4 * g + 1], st.acc[4 * g + 2], st.acc[4 * g + 3]);
                 const float4 bv = *reinterpret_cast<const float4*>(Bias + o);
                 v.x += bv.x; v.y += bv.y; v.z += bv.z; v.w += bv.w;
                 if (R) {
@@ -429,8 +518,10 @@ hipError_t conv3x3_bf16_tiled(const void* x, const void* w, const float* bias, c
     return launch_conv3x3_tile<7, 7>(x, w, bias, res, y, N, H, W, act, s);
 }
 
-// Tile configurations (TH x TW output pixels per workgroup): 0: 7x14  1: 7x7  2: 8x8  3: 6x14
-int fused_conv_chain_num_cfgs() { return 4; }
+// Tile configurations (TH x TW output pixels per workgroup): 0: 7x14  1: 7x7  2: 8x8  3: 6x14, each convolution
+// cut into (row tile, output-channel half) units; 4: 7x14 and 5: 7x7 with (row tile, kernel row) units, whose
+// partial sums meet in LDS (the earlier form, kept for comparison: 12.5 us against 10.9 us on 8 x 56 x 56)
+int fused_conv_chain_num_cfgs() { return 6; }
 
 hipError_t fused_conv_chain(const void* x, const void* wa, const float* ba, const void* wb,
                             const float* bb, void* y, int N, int H, int W, int residual, int tile_cfg,
@@ -444,6 +535,8 @@ hipError_t fused_conv_chain(const void* x, const void* wa, const float* ba, cons
         case 1: return launch_chain<7, 7>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
         case 2: return launch_chain<8, 8>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
         case 3: return launch_chain<6, 14>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
+        case 4: return launch_chain<7, 14, false>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
+        case 5: return launch_chain<7, 7, false>(x, wa, ba, wb, bb, y, N, H, W, residual, s);
         default: return hipErrorInvalidValue;
     }
 }

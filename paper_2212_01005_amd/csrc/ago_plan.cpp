@@ -33,22 +33,24 @@ inline double upstream_work(double outer2, double extra1, double ts1) { return o
 // conv3x3 -> conv3x3 (general-conv downstream: the re-use dimensions H2, W2 are tiled, so |TS2| < |TS1|
 // and the halo of the intermediate is re-computed).
 // One workgroup per TH x TW output tile, one per compute unit (1024 threads).  Time of a workgroup =
-// a fixed part (both 3 x 3 weight tensors and the input tile staged through LDS, the two reductions and
-// epilogues) + its matrix instructions: both convolutions run on 32-pixel x 32-channel tiles, 36 k steps
-// of 16 each (K = 9 x 64), two channel tiles.
-// Calibrated on 10 shapes x 4 candidates (batch 1 - 128 of 14 x 14 ... 112 x 112 x 64): mean error 4 %.
+// a fixed part (both 3 x 3 weight tensors and the input tile staged through LDS, the two epilogues)
+// + its matrix instructions: both convolutions run on 32-pixel x 32-channel tiles, 36 k steps
+// of 16 each (K = 9 x 64), two channel tiles; a last round that fills the chip only partly is cheaper.
+// Calibrated on 10 shapes x 4 candidates (batch 1 - 128 of 14 x 14 ... 112 x 112 x 64): mean error 2 %.
 // ---------------------------------------------------------------------------------------------------
-const int kChainTiles[4][2] = {{7, 14}, {7, 7}, {8, 8}, {6, 14}};
-constexpr double kChainFixedUs = 7.0, kChainUsPerMfma = 0.005;
+// candidates 0..3: units of (row tile, output-channel half); 4, 5: the earlier units of (row tile, kernel row)
+const int kChainTiles[6][2] = {{7, 14}, {7, 7}, {8, 8}, {6, 14}, {7, 14}, {7, 7}};
+constexpr double kChainFixedUs = 6.5, kChainUsPerMfma = 0.0045, kChainPartialRoundUs = 2.0;
+constexpr double kChainFixedUsKernelRows = 7.0, kChainUsPerMfmaKernelRows = 0.005;
 
 }  // namespace
 
 bool plan_conv_chain(int N, int H, int W, int C, int tile_cfg, ChainPlan* out) {
-    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || tile_cfg >= 4) return false;
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || tile_cfg >= 6) return false;
     ChainPlan best{};
     bool have = false;
-    for (int cfg = 0; cfg < 4; ++cfg) {
-        if (tile_cfg >= 0 && cfg != tile_cfg) continue;
+    for (int cfg = 0; cfg < 6; ++cfg) {
+        if (tile_cfg >= 0 ? cfg != tile_cfg : cfg >= 4) continue;      // the built-in choice is among 0..3
         const int th = kChainTiles[cfg][0], tw = kChainTiles[cfg][1];
         ChainPlan p{};
         p.cfg = cfg; p.tile_h = th; p.tile_w = tw;
@@ -62,7 +64,10 @@ bool plan_conv_chain(int N, int H, int W, int C, int tile_cfg, ChainPlan* out) {
         p.algorithmic_upstream_macs = (double)N * H * W * C * 9.0 * C;
         // what the matrix cores execute on top of that: pixel counts padded to 32-pixel tiles
         const long mfma = (ceil_div((th + 2) * (tw + 2), 32) + ceil_div(th * tw, 32)) * ceil_div(C, 32) * (9 * ceil_div(C, 16));
-        p.predicted_us = kLaunchUs + p.rounds * (kChainFixedUs + kChainUsPerMfma * mfma);
+        // a last round that fills only part of the chip finishes sooner (fewer workgroups share the L2s and HBM)
+        const double last = (double)(tiles - (p.rounds - 1) * kCUs) / kCUs;
+        p.predicted_us = cfg < 4 ? kLaunchUs + p.rounds * (kChainFixedUs + kChainUsPerMfma * mfma) - kChainPartialRoundUs * (1.0 - last)
+                                 : kLaunchUs + p.rounds * (kChainFixedUsKernelRows + kChainUsPerMfmaKernelRows * mfma);
         if (!have || p.predicted_us < best.predicted_us) { best = p; have = true; }
     }
     if (have && out) *out = best;
