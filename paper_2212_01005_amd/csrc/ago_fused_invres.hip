@@ -58,13 +58,93 @@ constexpr int kInvresThreads = 1024;   // 16 waves: LDS / global latency is hidd
 constexpr int kInvresWaves = kInvresThreads / 64;
 constexpr int kInvresJobsPerWave = 4;  // stage-3 accumulators a wave can hold across the chunks
 
+static constexpr int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// Lay out LDS for a tile and a chunk width cc of expanded channels; returns the byte count.
+static constexpr size_t plan_layout(InvresParams& p, bool bf16, int stride, int toh, int tow, int ksize, int cc) {
+    p.TOH = toh; p.TOW = tow;
+    p.tiles_h = (p.OH + toh - 1) / toh; p.tiles_w = (p.OW + tow - 1) / tow;
+    p.EH = (toh - 1) * stride + ksize; p.EW = (tow - 1) * stride + ksize;
+    p.PE = p.EH * p.EW; p.PEpad = round_up(p.PE, 16); p.POpad = round_up(toh * tow, 16);
+    const int kg = bf16 ? 32 : 4, es = bf16 ? 2 : 4;
+    p.CC = cc; p.nchunks = (p.Cexp + cc - 1) / cc;
+    p.KP1 = round_up(p.Cin, kg); p.KPC = round_up(cc, kg); p.CoutP = round_up(p.Cout, 16);
+    auto pad16 = [](int c) { int q = c; while (q % 32 != 16) q += 4; return q; };  // fp32 [k][n] rows
+    p.ldx = bf16 ? p.KP1 + 8 : p.KP1 + 4;
+    p.ldw1 = bf16 ? p.KP1 + 8 : pad16(cc);
+    p.lde = cc + 4;
+    p.ldd = bf16 ? p.KPC + 8 : p.KPC + 4;
+    p.ldw2 = bf16 ? p.KPC + 8 : pad16(p.CoutP);
+    size_t off = (size_t)p.PEpad * p.ldx * es;
+    auto al = [](size_t v) { return (v + 15) / 16 * 16; };
+    p.off_w1 = (int)(off = al(off));
+    off += (size_t)(bf16 ? cc : p.KP1) * p.ldw1 * es;
+    p.off_e = (int)(off = al(off));
+    off += (size_t)p.PE * p.lde * 4;
+    p.off_d = (int)(off = al(off));
+    off += (size_t)p.POpad * p.ldd * es;
+    p.off_w2 = (int)(off = al(off));
+    off += (size_t)(bf16 ? p.CoutP : p.KPC) * p.ldw2 * es;
+    p.off_wd = (int)(off = al(off));
+    off += (size_t)ksize * ksize * cc * 4;
+    p.off_b = (int)(off = al(off));
+    off += (size_t)(2 * p.Cexp + p.CoutP) * 4;
+    // stage-3 k split: as many waves per job as there are, limited by the k steps of a chunk and by
+    // the scratch (1 KB per wave) that fits in the E region
+    const int njobs = (p.POpad / 16) * (p.CoutP / 16);
+    const int ksteps = p.KPC / kg;
+    int ks = njobs < kInvresWaves ? kInvresWaves / njobs : 1;
+    if (ks > ksteps) ks = ksteps;
+    const size_t e_bytes = (size_t)p.PE * p.lde * 4;
+    while (ks > 1 && (size_t)njobs * ks * 1024 > e_bytes) --ks;
+    p.ksplit = ks < 1 ? 1 : ks;
+    return al(off);
+}
+
+// Shape-specialised instantiations: the paper's tuner emits code for one subgraph shape at a time, so tile sizes,
+// strides and trip counts are constants of the generated loop nest.  SPEC > 0 selects a geometry known at
+// compile time (all integer fields of the parameter block, laid out by the same plan_layout as at run time):
+// index arithmetic by constants, fully unrolled job loops, dead modes removed.  The launcher picks such an
+// instantiation only when the run-time plan is field for field the same.
+//   1: 1 x 14 x 14 x 32 -> 192 -> 32, stride 1, fp32, residual, 2 x 2 tiles
+//   2: 1 x 56 x 56 x 24 -> 144 -> 32, stride 2, bf16, no residual, 2 x 2 tiles
+struct InvresSpecShape { int N, H, W, Cin, Cexp, Cout, stride, bf16, residual, toh, tow; };
+constexpr InvresSpecShape kInvresSpecs[3] = {{}, {1, 14, 14, 32, 192, 32, 1, 0, 1, 2, 2}, {1, 56, 56, 24, 144, 32, 2, 1, 0, 2, 2}};
+constexpr InvresParams invres_spec_geometry(int spec) {
+    const InvresSpecShape q = kInvresSpecs[spec];
+    InvresParams p = {};
+    p.N = q.N; p.H = q.H; p.W = q.W; p.Cin = q.Cin; p.Cexp = q.Cexp; p.Cout = q.Cout;
+    p.OH = (q.H - 1) / q.stride + 1; p.OW = (q.W - 1) / q.stride + 1;
+    p.residual = q.residual; p.mode = 0; p.nsplit = 1;
+    plan_layout(p, q.bf16 != 0, q.stride, q.toh, q.tow, 3, q.Cexp);
+    return p;
+}
+// true when the run-time parameter block has exactly the geometry of specialisation `spec`
+inline bool invres_matches_spec(const InvresParams& a, int spec) {
+    const InvresParams b = invres_spec_geometry(spec);
+    return a.N == b.N && a.H == b.H && a.W == b.W && a.Cin == b.Cin && a.Cexp == b.Cexp && a.Cout == b.Cout && a.OH == b.OH &&
+           a.OW == b.OW && a.residual == b.residual && a.TOH == b.TOH && a.TOW == b.TOW && a.tiles_h == b.tiles_h &&
+           a.tiles_w == b.tiles_w && a.EH == b.EH && a.EW == b.EW && a.PE == b.PE && a.PEpad == b.PEpad && a.POpad == b.POpad &&
+           a.KP1 == b.KP1 && a.CC == b.CC && a.nchunks == b.nchunks && a.KPC == b.KPC && a.CoutP == b.CoutP && a.ldx == b.ldx &&
+           a.ldw1 == b.ldw1 && a.lde == b.lde && a.ldd == b.ldd && a.ldw2 == b.ldw2 && a.off_w1 == b.off_w1 && a.off_e == b.off_e &&
+           a.off_d == b.off_d && a.off_w2 == b.off_w2 && a.off_wd == b.off_wd && a.off_b == b.off_b && a.ksplit == b.ksplit &&
+           a.mode == b.mode && a.nsplit == b.nsplit;
+}
+
 // KS: odd depthwise kernel size (3 or 5), zero padding (KS - 1) / 2.  CHUNKED: several chunks of expanded
 // channels with the projection's accumulators carried in registers; the single-chunk instantiation
 // keeps none (64 registers or fewer: two workgroups per compute unit).  SPLIT (single-chunk only): the
 // workgroup's chunk is blockIdx.y and the projection's partial goes to the workspace.
-template <bool BF16, int STRIDE, int KS, bool CHUNKED, bool SPLIT = false>
-__global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const InvresParams p) {
+template <bool BF16, int STRIDE, int KS, bool CHUNKED, bool SPLIT = false, int SPEC = 0>
+__global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const InvresParams p_in) {
     typedef typename InT<BF16>::type T;
+    InvresParams p = p_in;
+    if constexpr (SPEC != 0) {
+        constexpr InvresParams G = invres_spec_geometry(SPEC);
+        p = G;
+        p.x = p_in.x; p.w1 = p_in.w1; p.b1 = p_in.b1; p.wd = p_in.wd; p.bd = p_in.bd; p.w2 = p_in.w2; p.b2 = p_in.b2;
+        p.y = p_in.y; p.part = p_in.part;
+    }
     extern __shared__ __align__(16) unsigned char smem[];
     T* Xs = reinterpret_cast<T*>(smem);
     T* W1s = reinterpret_cast<T*>(smem + p.off_w1);
@@ -405,48 +485,6 @@ __global__ __launch_bounds__(256) void invres_reduce_kernel(const float* __restr
     }
 }
 
-static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
-
-// Lay out LDS for a tile and a chunk width cc of expanded channels; returns the byte count.
-static size_t plan_layout(InvresParams& p, bool bf16, int stride, int toh, int tow, int ksize, int cc) {
-    p.TOH = toh; p.TOW = tow;
-    p.tiles_h = (p.OH + toh - 1) / toh; p.tiles_w = (p.OW + tow - 1) / tow;
-    p.EH = (toh - 1) * stride + ksize; p.EW = (tow - 1) * stride + ksize;
-    p.PE = p.EH * p.EW; p.PEpad = round_up(p.PE, 16); p.POpad = round_up(toh * tow, 16);
-    const int kg = bf16 ? 32 : 4, es = bf16 ? 2 : 4;
-    p.CC = cc; p.nchunks = (p.Cexp + cc - 1) / cc;
-    p.KP1 = round_up(p.Cin, kg); p.KPC = round_up(cc, kg); p.CoutP = round_up(p.Cout, 16);
-    auto pad16 = [](int c) { int q = c; while (q % 32 != 16) q += 4; return q; };  // fp32 [k][n] rows
-    p.ldx = bf16 ? p.KP1 + 8 : p.KP1 + 4;
-    p.ldw1 = bf16 ? p.KP1 + 8 : pad16(cc);
-    p.lde = cc + 4;
-    p.ldd = bf16 ? p.KPC + 8 : p.KPC + 4;
-    p.ldw2 = bf16 ? p.KPC + 8 : pad16(p.CoutP);
-    size_t off = (size_t)p.PEpad * p.ldx * es;
-    auto al = [](size_t v) { return (v + 15) / 16 * 16; };
-    p.off_w1 = (int)(off = al(off));
-    off += (size_t)(bf16 ? cc : p.KP1) * p.ldw1 * es;
-    p.off_e = (int)(off = al(off));
-    off += (size_t)p.PE * p.lde * 4;
-    p.off_d = (int)(off = al(off));
-    off += (size_t)p.POpad * p.ldd * es;
-    p.off_w2 = (int)(off = al(off));
-    off += (size_t)(bf16 ? p.CoutP : p.KPC) * p.ldw2 * es;
-    p.off_wd = (int)(off = al(off));
-    off += (size_t)ksize * ksize * cc * 4;
-    p.off_b = (int)(off = al(off));
-    off += (size_t)(2 * p.Cexp + p.CoutP) * 4;
-    // stage-3 k split: as many waves per job as there are, limited by the k steps of a chunk and by
-    // the scratch (1 KB per wave) that fits in the E region
-    const int njobs = (p.POpad / 16) * (p.CoutP / 16);
-    const int ksteps = p.KPC / kg;
-    int ks = njobs < kInvresWaves ? kInvresWaves / njobs : 1;
-    if (ks > ksteps) ks = ksteps;
-    const size_t e_bytes = (size_t)p.PE * p.lde * 4;
-    while (ks > 1 && (size_t)njobs * ks * 1024 > e_bytes) --ks;
-    p.ksplit = ks < 1 ? 1 : ks;
-    return al(off);
-}
 
 constexpr size_t kInvresLdsMax = 160 * 1024;
 
@@ -664,8 +702,20 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
     do {                                                                                                \
         if (ksize == 3) AGO_LAUNCH_INVRES_K(BF, ST, 3); else AGO_LAUNCH_INVRES_K(BF, ST, 5);            \
     } while (0)
-    if (bf16) { if (stride == 1) AGO_LAUNCH_INVRES(true, 1); else AGO_LAUNCH_INVRES(true, 2); }
+#define AGO_LAUNCH_INVRES_SPEC(BF, ST, ID)                                                               \
+    do {                                                                                                \
+        auto kern = fused_invres_kernel<BF, ST, 3, false, false, ID>;                                   \
+        if (hipError_t e = allow_dynamic_lds<fused_invres_kernel<BF, ST, 3, false, false, ID>>((int)kLdsMax); e != hipSuccess) return e; \
+        prof_start(0, s);                                                                               \
+        prof_shape(0, grid.x * grid.y, kInvresThreads);                                                 \
+        hipLaunchKernelGGL(kern, grid, dim3(kInvresThreads), smem, s, p);                               \
+    } while (0)
+    const bool may_spec = ksize == 3 && !split && mode == 0 && tile_cfg < 0;
+    if (may_spec && !bf16 && stride == 1 && invres_matches_spec(p, 1)) AGO_LAUNCH_INVRES_SPEC(false, 1, 1);
+    else if (may_spec && bf16 && stride == 2 && invres_matches_spec(p, 2)) AGO_LAUNCH_INVRES_SPEC(true, 2, 2);
+    else if (bf16) { if (stride == 1) AGO_LAUNCH_INVRES(true, 1); else AGO_LAUNCH_INVRES(true, 2); }
     else { if (stride == 1) AGO_LAUNCH_INVRES(false, 1); else AGO_LAUNCH_INVRES(false, 2); }
+#undef AGO_LAUNCH_INVRES_SPEC
 #undef AGO_LAUNCH_INVRES
 #undef AGO_LAUNCH_INVRES_K
 #undef AGO_LAUNCH_INVRES_KC
