@@ -30,6 +30,7 @@
 //           the image), stages 2-3 follow
 #include "ago_dev.hpp"
 #include "ago_launch.hpp"
+#include <utility>
 
 namespace ago {
 
@@ -106,17 +107,33 @@ static constexpr size_t plan_layout(InvresParams& p, bool bf16, int stride, int 
 // compile time (all integer fields of the parameter block, laid out by the same plan_layout as at run time):
 // index arithmetic by constants, fully unrolled job loops, dead modes removed.  The launcher picks such an
 // instantiation only when the run-time plan is field for field the same.
-//   1: 1 x 14 x 14 x 32 -> 192 -> 32, stride 1, fp32, residual, 2 x 2 tiles
-//   2: 1 x 56 x 56 x 24 -> 144 -> 32, stride 2, bf16, no residual, 2 x 2 tiles
-struct InvresSpecShape { int N, H, W, Cin, Cexp, Cout, stride, bf16, residual, toh, tow; };
-constexpr InvresSpecShape kInvresSpecs[3] = {{}, {1, 14, 14, 32, 192, 32, 1, 0, 1, 2, 2}, {1, 56, 56, 24, 144, 32, 2, 1, 0, 2, 2}};
+// The table: the two benchmark blocks and the eleven block shapes of a MobileNetV2-style network at batch 1,
+// each with the tile (and, for the wide blocks, the channel split) the planner picks for it.
+struct InvresSpecShape { int N, H, W, Cin, Cexp, Cout, stride, bf16, residual, toh, tow, cc, split; };
+constexpr InvresSpecShape kInvresSpecs[] = {
+    {},
+    {1, 14, 14, 32, 192, 32, 1, 0, 1, 2, 2, 192, 0},       // benchmark block, fp32
+    {1, 56, 56, 24, 144, 32, 2, 1, 0, 2, 2, 144, 0},       // benchmark block, bf16 (= the network's 56 x 56 stride-2 block)
+    {1, 112, 112, 16, 96, 24, 2, 1, 0, 2, 7, 96, 0},
+    {1, 56, 56, 24, 144, 24, 1, 1, 1, 4, 4, 144, 0},
+    {1, 28, 28, 32, 192, 32, 1, 1, 1, 2, 2, 192, 0},
+    {1, 28, 28, 32, 192, 64, 2, 1, 0, 1, 2, 192, 0},
+    {1, 14, 14, 64, 384, 64, 1, 1, 1, 1, 1, 384, 0},
+    {1, 14, 14, 64, 384, 96, 1, 1, 0, 2, 3, 64, 1},
+    {1, 14, 14, 96, 576, 96, 1, 1, 1, 2, 3, 96, 1},
+    {1, 14, 14, 96, 576, 160, 2, 1, 0, 1, 2, 64, 1},
+    {1, 7, 7, 160, 960, 160, 1, 1, 1, 2, 2, 64, 1},
+    {1, 7, 7, 160, 960, 320, 1, 1, 0, 2, 2, 64, 1},
+};
+constexpr int kNumInvresSpecs = (int)(sizeof(kInvresSpecs) / sizeof(kInvresSpecs[0]));
 constexpr InvresParams invres_spec_geometry(int spec) {
     const InvresSpecShape q = kInvresSpecs[spec];
     InvresParams p = {};
     p.N = q.N; p.H = q.H; p.W = q.W; p.Cin = q.Cin; p.Cexp = q.Cexp; p.Cout = q.Cout;
     p.OH = (q.H - 1) / q.stride + 1; p.OW = (q.W - 1) / q.stride + 1;
-    p.residual = q.residual; p.mode = 0; p.nsplit = 1;
-    plan_layout(p, q.bf16 != 0, q.stride, q.toh, q.tow, 3, q.Cexp);
+    p.residual = q.residual; p.mode = 0;
+    plan_layout(p, q.bf16 != 0, q.stride, q.toh, q.tow, 3, q.cc);
+    p.nsplit = q.split ? p.nchunks : 1;
     return p;
 }
 // true when the run-time parameter block has exactly the geometry of specialisation `spec`
@@ -634,6 +651,27 @@ size_t fused_invres_workspace(int N, int H, int W, int Cin, int Cexp, int Cout, 
     return invres_split_bytes(p);
 }
 
+// Launch the shape-specialised instantiation whose geometry equals the run-time plan, if there is one.
+template <int ID>
+static bool try_invres_spec(const InvresParams& p, bool bf16, int stride, int residual, dim3 grid, size_t smem, hipStream_t s,
+                            hipError_t* err) {
+    constexpr InvresSpecShape q = kInvresSpecs[ID];
+    if (bf16 != (q.bf16 != 0) || stride != q.stride || residual != q.residual || !invres_matches_spec(p, ID)) return false;
+    constexpr size_t kLdsMax = 160 * 1024;
+    auto kern = fused_invres_kernel<(q.bf16 != 0), q.stride, 3, false, (q.split != 0), ID>;
+    *err = allow_dynamic_lds<fused_invres_kernel<(q.bf16 != 0), q.stride, 3, false, (q.split != 0), ID>>((int)kLdsMax);
+    if (*err != hipSuccess) return true;
+    prof_start(0, s);
+    prof_shape(0, grid.x * grid.y, kInvresThreads);
+    hipLaunchKernelGGL(kern, grid, dim3(kInvresThreads), smem, s, p);
+    return true;
+}
+template <int... IDS>
+static bool launch_invres_spec(const InvresParams& p, bool bf16, int stride, int residual, dim3 grid, size_t smem, hipStream_t s,
+                               std::integer_sequence<int, IDS...>, hipError_t* err) {
+    return (try_invres_spec<IDS + 1>(p, bf16, stride, residual, grid, smem, s, err) || ...);
+}
+
 hipError_t fused_invres(const void* x, const void* w1, const float* b1, const void* wd, const float* bd,
                         const void* w2, const float* b2, void* y, int N, int H, int W, int Cin,
                         int Cexp, int Cout, int stride, int residual, bool bf16, int tile_cfg,
@@ -702,20 +740,15 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
     do {                                                                                                \
         if (ksize == 3) AGO_LAUNCH_INVRES_K(BF, ST, 3); else AGO_LAUNCH_INVRES_K(BF, ST, 5);            \
     } while (0)
-#define AGO_LAUNCH_INVRES_SPEC(BF, ST, ID)                                                               \
-    do {                                                                                                \
-        auto kern = fused_invres_kernel<BF, ST, 3, false, false, ID>;                                   \
-        if (hipError_t e = allow_dynamic_lds<fused_invres_kernel<BF, ST, 3, false, false, ID>>((int)kLdsMax); e != hipSuccess) return e; \
-        prof_start(0, s);                                                                               \
-        prof_shape(0, grid.x * grid.y, kInvresThreads);                                                 \
-        hipLaunchKernelGGL(kern, grid, dim3(kInvresThreads), smem, s, p);                               \
-    } while (0)
-    const bool may_spec = ksize == 3 && !split && mode == 0 && tile_cfg < 0;
-    if (may_spec && !bf16 && stride == 1 && invres_matches_spec(p, 1)) AGO_LAUNCH_INVRES_SPEC(false, 1, 1);
-    else if (may_spec && bf16 && stride == 2 && invres_matches_spec(p, 2)) AGO_LAUNCH_INVRES_SPEC(true, 2, 2);
+    bool launched = false;
+    if (ksize == 3 && mode == 0 && tile_cfg < 0) {
+        hipError_t spec_err = hipSuccess;
+        launched = launch_invres_spec(p, bf16, stride, residual, grid, smem, s, std::make_integer_sequence<int, kNumInvresSpecs - 1>{}, &spec_err);
+        if (spec_err != hipSuccess) return spec_err;
+    }
+    if (launched) {}
     else if (bf16) { if (stride == 1) AGO_LAUNCH_INVRES(true, 1); else AGO_LAUNCH_INVRES(true, 2); }
     else { if (stride == 1) AGO_LAUNCH_INVRES(false, 1); else AGO_LAUNCH_INVRES(false, 2); }
-#undef AGO_LAUNCH_INVRES_SPEC
 #undef AGO_LAUNCH_INVRES
 #undef AGO_LAUNCH_INVRES_K
 #undef AGO_LAUNCH_INVRES_KC
