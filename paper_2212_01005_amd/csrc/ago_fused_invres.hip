@@ -107,9 +107,10 @@ static constexpr size_t plan_layout(InvresParams& p, bool bf16, int stride, int 
 // compile time (all integer fields of the parameter block, laid out by the same plan_layout as at run time):
 // index arithmetic by constants, fully unrolled job loops, dead modes removed.  The launcher picks such an
 // instantiation only when the run-time plan is field for field the same.
-// The table: the two benchmark blocks and the eleven block shapes of a MobileNetV2-style network at batch 1,
-// each with the tile (and, for the wide blocks, the channel split) the planner picks for it.
-struct InvresSpecShape { int N, H, W, Cin, Cexp, Cout, stride, bf16, residual, toh, tow, cc, split; };
+// The table: the two benchmark blocks, the eleven block shapes of a MobileNetV2-style network at batch 1 and the
+// two-operator pairs of the benchmark blocks, each with the tile (and, for the wide blocks, the channel split)
+// the planner picks for it.
+struct InvresSpecShape { int N, H, W, Cin, Cexp, Cout, stride, bf16, residual, toh, tow, cc, split, mode; };
 constexpr InvresSpecShape kInvresSpecs[] = {
     {},
     {1, 14, 14, 32, 192, 32, 1, 0, 1, 2, 2, 192, 0},       // benchmark block, fp32
@@ -124,6 +125,11 @@ constexpr InvresSpecShape kInvresSpecs[] = {
     {1, 14, 14, 96, 576, 160, 2, 1, 0, 1, 2, 64, 1},
     {1, 7, 7, 160, 960, 160, 1, 1, 1, 2, 2, 64, 1},
     {1, 7, 7, 160, 960, 320, 1, 1, 0, 2, 2, 64, 1},
+    // the pw -> dw and dw -> pw pairs cut from the two benchmark blocks (mode 1: Cout unused, 16; mode 2: Cin unused, 8)
+    {1, 14, 14, 32, 192, 16, 1, 0, 0, 1, 1, 192, 0, 1},
+    {1, 56, 56, 24, 144, 16, 2, 1, 0, 2, 2, 144, 0, 1},
+    {1, 14, 14, 8, 192, 32, 1, 0, 0, 1, 1, 192, 0, 2},
+    {1, 56, 56, 8, 144, 32, 2, 1, 0, 2, 2, 144, 0, 2},
 };
 constexpr int kNumInvresSpecs = (int)(sizeof(kInvresSpecs) / sizeof(kInvresSpecs[0]));
 constexpr InvresParams invres_spec_geometry(int spec) {
@@ -131,7 +137,7 @@ constexpr InvresParams invres_spec_geometry(int spec) {
     InvresParams p = {};
     p.N = q.N; p.H = q.H; p.W = q.W; p.Cin = q.Cin; p.Cexp = q.Cexp; p.Cout = q.Cout;
     p.OH = (q.H - 1) / q.stride + 1; p.OW = (q.W - 1) / q.stride + 1;
-    p.residual = q.residual; p.mode = 0;
+    p.residual = q.residual; p.mode = q.mode;
     plan_layout(p, q.bf16 != 0, q.stride, q.toh, q.tow, 3, q.cc);
     p.nsplit = q.split ? p.nchunks : 1;
     return p;
@@ -741,7 +747,7 @@ hipError_t fused_invres(const void* x, const void* w1, const float* b1, const vo
         if (ksize == 3) AGO_LAUNCH_INVRES_K(BF, ST, 3); else AGO_LAUNCH_INVRES_K(BF, ST, 5);            \
     } while (0)
     bool launched = false;
-    if (ksize == 3 && mode == 0 && tile_cfg < 0) {
+    if (ksize == 3 && tile_cfg < 0) {
         hipError_t spec_err = hipSuccess;
         launched = launch_invres_spec(p, bf16, stride, residual, grid, smem, s, std::make_integer_sequence<int, kNumInvresSpecs - 1>{}, &spec_err);
         if (spec_err != hipSuccess) return spec_err;
