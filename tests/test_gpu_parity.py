@@ -420,6 +420,36 @@ def test_ffn_ragged_hidden_slices_and_column_blocks(gpu, oracle):
             ago.set_tile_config(ago.OP_FUSED_FFN, -1)
 
 
+def test_specialised_instantiations_match_the_general_kernel(gpu, oracle):
+    """The shape-specialised instantiations of the inverted-residual kernel (compile-time geometry) against the
+    general instantiation forced through the tile-configuration switch: the same arithmetic in the same order,
+    so the outputs are bit-identical; and both match the oracle."""
+    torch, ago, runner = gpu
+    cases = [wl.baseline_case(0), wl.baseline_case(1)] + [c for c in wl.network_block_cases(1)
+                                                           if c.name in ("block_112x112x16_96_24_s2", "block_28x28x32_192_64_s2",
+                                                                         "block_14x14x64_384_96_s1", "block_7x7x160_960_160_s1")]
+    for case in cases:
+        dt = ago.BF16 if case.dtype == "bf16" else ago.F32
+        t = runner.to_device(case)
+        ws = runner.alloc_workspace(case, fused=True)
+        plan = ago.fused_invres_plan(case.N, case.H, case.W, case.Cin, case.Cexp, case.Cout, case.stride, case.ksize, dt,
+                                     ws.numel() if ws is not None else 0)
+        y_spec = runner.alloc_output(case)
+        y_spec.zero_()
+        runner.run_fused(case, t, y_spec, ws)
+        torch.cuda.synchronize()
+        y_gen = runner.alloc_output(case)
+        y_gen.zero_()
+        try:
+            ago.set_tile_config(ago.OP_FUSED_INVRES, plan["config"])      # the same tile, general instantiation
+            runner.run_fused(case, t, y_gen, ws)
+            torch.cuda.synchronize()
+        finally:
+            ago.set_tile_config(ago.OP_FUSED_INVRES, -1)
+        assert torch.equal(y_spec, y_gen), case.name
+        assert_close(runner.to_numpy64(y_spec), oracle.run_case(case), case.dtype, case.name)
+
+
 def _packed_reference(w):
     """The packed layout written out from its definition: fragment (ks, nt), lane l, element e holds
     w[32 ks + 8 (l // 16) + e][16 nt + l % 16]."""
