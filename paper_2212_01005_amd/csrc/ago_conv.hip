@@ -21,16 +21,17 @@ __device__ __forceinline__ void load8(const void* base, long elem, float (&v)[8]
     }
 }
 
-template <bool BF16>
+// IDX: type of the flat output index (32-bit when the tensor allows it: the index is divided four times per item)
+template <bool BF16, typename IDX>
 __global__ __launch_bounds__(256) void dwconv3x3_kernel(const void* x, const void* w,
                                                         const float* __restrict__ bias, void* y,
                                                         int N, int H, int W, int C, int OH, int OW,
                                                         int stride, int act) {
     const int C8 = C / 8;
-    const long total = (long)N * OH * OW * C8;
-    for (long it = blockIdx.x * 256L + threadIdx.x; it < total; it += (long)gridDim.x * 256) {
+    const IDX total = (IDX)N * OH * OW * C8;
+    for (IDX it = (IDX)blockIdx.x * 256 + threadIdx.x; it < total; it += (IDX)gridDim.x * 256) {
         const int c = (int)(it % C8) * 8;
-        long p = it / C8;
+        IDX p = it / C8;
         const int ow = (int)(p % OW); p /= OW;
         const int oh = (int)(p % OH);
         const int n = (int)(p / OH);
@@ -72,8 +73,10 @@ hipError_t dwconv3x3(const void* x, const void* w, const float* bias, void* y, i
     long g = (total + 255) / 256;
     if (g > 4096) g = 4096;
     if (g < 1) g = 1;
-    if (bf16) hipLaunchKernelGGL(dwconv3x3_kernel<true>, dim3((unsigned)g), dim3(256), 0, s, x, w, bias, y, N, H, W, C, OH, OW, stride, act);
-    else hipLaunchKernelGGL(dwconv3x3_kernel<false>, dim3((unsigned)g), dim3(256), 0, s, x, w, bias, y, N, H, W, C, OH, OW, stride, act);
+    const bool narrow = total + 4096L * 256 < (1L << 31);
+    auto kern = bf16 ? (narrow ? dwconv3x3_kernel<true, unsigned> : dwconv3x3_kernel<true, long>)
+                     : (narrow ? dwconv3x3_kernel<false, unsigned> : dwconv3x3_kernel<false, long>);
+    hipLaunchKernelGGL(kern, dim3((unsigned)g), dim3(256), 0, s, x, w, bias, y, N, H, W, C, OH, OW, stride, act);
     return hipGetLastError();
 }
 

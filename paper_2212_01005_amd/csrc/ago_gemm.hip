@@ -342,6 +342,92 @@ __global__ __launch_bounds__(512) void gemm_bf16_ksplit_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Small products (a 1 x 1 convolution of one image, a projection with few rows): too little work for
+// the LDS-tiled kernels above, whose few workgroups would each walk the whole reduction serially.
+// Here an output tile is 32 x 32 and KS of the workgroup's eight waves split its reduction, so that even
+// a 196 x 32 output keeps 56 waves busy; operands go global -> registers directly (they are read once
+// per tile row / column and the whole problem sits in the caches), products run on the fp32 matrix
+// instruction (bf16 inputs are widened first, exactly), partial sums meet in LDS in wave order.
+// Lane (i, h) of v_mfma_f32_32x32x2_f32 supplies row / column i at reduction index h: the wave gives
+// h = 0 the first half of its k range and h = 1 the second, so every lane walks consecutive k.
+// ---------------------------------------------------------------------------------------
+template <typename T> __device__ __forceinline__ float widen(T v) { return (float)v; }
+
+template <typename T, int KS>
+__global__ __launch_bounds__(512) void gemm_small_kernel(
+    const T* __restrict__ A, const T* __restrict__ B, const float* __restrict__ bias,
+    const T* __restrict__ R, T* __restrict__ C, int M, int K, int N, int act) {
+    constexpr int TPW = 8 / KS, LD = 33;
+    __shared__ float red[8][32 * LD];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kh = wave % KS, grp = wave / KS;
+    const int tiles_n = (N + 31) / 32, tiles_m = (M + 31) / 32;
+    const int tile = blockIdx.x * TPW + grp;
+    const bool live = tile < tiles_m * tiles_n;                 // uniform per wave
+    const int m0 = (tile / tiles_n) * 32, n0 = (tile % tiles_n) * 32;
+    const int i = lane & 31, h = lane >> 5;
+
+    f32x16 acc = {0};
+    if (live) {
+        const int per = (K + 2 * KS - 1) / (2 * KS);            // reduction indices per lane
+        const int k_lo = (2 * kh + h) * per;
+        const int row = m0 + i, col = n0 + i;
+        const bool row_ok = row < M, col_ok = col < N;
+        const T* pa = A + (long)(row_ok ? row : 0) * K;
+        const T* pb = B + (col_ok ? col : 0);
+        for (int s0 = 0; s0 < per; s0 += 8) {
+            float av[8], bv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int k = k_lo + s0 + u;
+                const bool ok = s0 + u < per && k < K;
+                const int kc = ok ? k : 0;
+                const float a = widen(pa[kc]), b = widen(pb[(long)kc * N]);
+                av[u] = ok && row_ok ? a : 0.0f;
+                bv[u] = ok && col_ok ? b : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv[u], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[wave][acc_row(r, h) * LD + i] = acc[r];
+    }
+    __syncthreads();
+    if (!live) return;
+    // the KS waves of a tile each finish 32 / KS of its rows
+    constexpr int RS = 32 / KS;
+    for (int u = lane; u < RS * 32; u += 64) {
+        const int rr = kh * RS + u / 32, cc = u % 32;
+        const int row = m0 + rr, col = n0 + cc;
+        if (row >= M || col >= N) continue;
+        float v = red[grp * KS][rr * LD + cc];
+#pragma unroll
+        for (int q = 1; q < KS; ++q) v += red[grp * KS + q][rr * LD + cc];
+        if (bias) v += bias[col];
+        if (R) v += widen(R[(long)row * N + col]);
+        C[(long)row * N + col] = (T)apply_act_rt(v, act);
+    }
+}
+
+template <typename T>
+static hipError_t launch_gemm_small(const void* a, const void* b, const float* bias, const void* res, void* c,
+                                    int M, int K, int N, int act, hipStream_t s) {
+    const int tiles = ((M + 31) / 32) * ((N + 31) / 32);
+#define AGO_SMALL(KS)                                                                                         \
+    hipLaunchKernelGGL((gemm_small_kernel<T, KS>), dim3((tiles * KS + 7) / 8), dim3(512), 0, s, (const T*)a,   \
+                       (const T*)b, bias, (const T*)res, (T*)c, M, K, N, act)
+    if (K >= 64) AGO_SMALL(8);
+    else if (K >= 32) AGO_SMALL(4);
+    else if (K >= 16) AGO_SMALL(2);
+    else AGO_SMALL(1);
+#undef AGO_SMALL
+    return hipGetLastError();
+}
+
+// A product this small is bound by latency, not by the matrix cores: it takes the direct kernel.
+static bool is_small_product(int M, int K, int N) { return (long)M * K * N <= (1L << 25); }
+
 template <int BM, int BN, int KS, int KPW>
 static hipError_t launch_gemm_ksplit(const void* a, const void* b, const float* bias, const void* res, void* c,
                                      int M, int K, int N, int act, hipStream_t s) {
@@ -370,6 +456,7 @@ static hipError_t launch_gemm_bf16(const void* a, const void* b, const float* bi
 
 hipError_t gemm_bf16(const void* a, const void* b, const float* bias, const void* res, void* c, int M,
                      int K, int N, int act, hipStream_t s) {
+    if (is_small_product(M, K, N)) return launch_gemm_small<bf16_t>(a, b, bias, res, c, M, K, N, act, s);
     // Shapes that tile exactly take the k-split kernels: 128 x 192 tiles when they fill the chip, else
     // 64 x 96 tiles whose eight waves split k (a product with few outputs and a long reduction).
     if (M % 128 == 0 && N % 192 == 0 && K % 64 == 0 && (long)(M / 128) * (N / 192) >= 192)
@@ -385,6 +472,7 @@ hipError_t gemm_bf16(const void* a, const void* b, const float* bias, const void
 
 hipError_t gemm_f32(const void* a, const void* b, const float* bias, const void* res, void* c, int M,
                     int K, int N, int act, hipStream_t s) {
+    if (is_small_product(M, K, N)) return launch_gemm_small<float>(a, b, bias, res, c, M, K, N, act, s);
     dim3 grid((N + 63) / 64, (M + 63) / 64);
     hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, s, (const float*)a, (const float*)b, bias,
                        (const float*)res, (float*)c, M, K, N, act);
