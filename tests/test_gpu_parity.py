@@ -734,6 +734,11 @@ def _store(arr, dtype):
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("shape", [(200, 72, 136), (64, 768, 64), (333, 256, 320),
+                                   # small products (direct kernel): reductions split over 1, 2, 4 and 8 waves, ragged
+                                   # 32 x 32 tiles, a k range that does not divide, a single output
+                                   (196, 8, 40), (3136, 24, 144), (50, 40, 24), (196, 192, 32), (784, 144, 32), (1, 8, 8),
+                                   # above the small-product limit, no exact tiling: the LDS-tiled kernels
+                                   (700, 264, 200),
                                    # shapes that tile exactly take the k-split kernels: 128 x 192 tiles with an even and an
                                    # odd number of k tiles, 64 x 96 tiles with one and with three k tiles
                                    (2048, 128, 3072), (2048, 192, 3072), (1024, 128, 768), (1024, 384, 768)])
