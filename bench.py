@@ -60,10 +60,62 @@ def parse():
                     help="skip the cold-cache timings and launch floors of the per-config table (profiling aid)")
     ap.add_argument("--variants", default="fused,u1,u2,packed",
                     help="which variants the per-config table runs (profiling aid: counters of one variant alone)")
+    ap.add_argument("--vendor-context", action="store_true",
+                    help="also time the complex operators of the configurations as PyTorch reaches them in the vendor "
+                         "libraries (matmul, conv2d, scaled_dot_product_attention), each captured ten times into a HIP "
+                         "graph so that no framework dispatch time is included; context for how good the un-fused "
+                         "baselines are, reported under 'vendor_context', never part of 'value'")
     ap.add_argument("--tile-config", default="",
                     help="tile-size sweep aid: comma-separated op=id pairs (op: invres, chain, ffn, attn) passed to "
                          "ago_set_tile_config before anything runs; the default is the library's built-in choice")
     return ap.parse_args()
+
+
+def vendor_context(torch):
+    """The benchmark's complex operators through PyTorch's vendor-library calls, us per call (HIP-graph replays)."""
+    F = torch.nn.functional
+    bf = torch.bfloat16
+    torch.backends.cudnn.benchmark = True        # let the convolution library time its own candidates first
+
+    def us(fn):
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            for _ in range(5):
+                fn()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                for _ in range(10):
+                    fn()
+        torch.cuda.synchronize()
+        for _ in range(3):
+            g.replay()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(20):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        return round(a.elapsed_time(b) / 200 * 1e3, 2)
+
+    res = {"how": "torch %s; each operator captured 10x into a HIP graph, 20 replays timed" % torch.__version__}
+    for m, k, n in [(2048, 768, 3072), (2048, 3072, 768), (196, 192, 32), (3136, 24, 144), (784, 144, 32)]:
+        a, b = torch.randn(m, k, device="cuda", dtype=bf), torch.randn(k, n, device="cuda", dtype=bf)
+        c = torch.empty(m, n, device="cuda", dtype=bf)
+        res["matmul_%dx%dx%d_us" % (m, k, n)] = us(lambda: torch.matmul(a, b, out=c))
+    x = torch.randn(2048, 768, device="cuda", dtype=bf)
+    w1, b1 = torch.randn(3072, 768, device="cuda", dtype=bf), torch.randn(3072, device="cuda", dtype=bf)
+    w2, b2 = torch.randn(768, 3072, device="cuda", dtype=bf), torch.randn(768, device="cuda", dtype=bf)
+    res["linear_gelu_linear_2048x768x3072_us"] = us(lambda: F.linear(F.gelu(F.linear(x, w1, b1), approximate="tanh"), w2, b2))
+    q = torch.randn(8, 12, 384, 64, device="cuda", dtype=bf)
+    kk, v = torch.randn_like(q), torch.randn_like(q)
+    res["sdpa_8x12x384x64_us"] = us(lambda: F.scaled_dot_product_attention(q, kk, v))
+    xc = torch.randn(8, 64, 56, 56, device="cuda", dtype=bf).contiguous(memory_format=torch.channels_last)
+    wc = torch.randn(64, 64, 3, 3, device="cuda", dtype=bf).contiguous(memory_format=torch.channels_last)
+    res["conv3x3_8x56x56x64_nhwc_us"] = us(lambda: F.conv2d(xc, wc, padding=1))
+    xd = torch.randn(1, 144, 56, 56, device="cuda", dtype=bf).contiguous(memory_format=torch.channels_last)
+    wd = torch.randn(144, 1, 3, 3, device="cuda", dtype=bf)
+    res["dwconv3x3_s2_56x56x144_us"] = us(lambda: F.conv2d(xd, wd, padding=1, stride=2, groups=144))
+    return res
 
 
 def main():
@@ -495,6 +547,8 @@ def main():
                "sample": "%d full steps (all %d configurations once each, fp64; %.2f s per step, %.1f s in all)"
                          % (passes, len(cases), secs, spent)}
 
+    vendor = vendor_context(torch) if args.vendor_context else None
+
     out = {
         "metric": "fused-block TFLOP/s (algorithmic, one pass over the 5 fused subgraphs)",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -509,6 +563,7 @@ def main():
         "roofline": roofline, "measured_peaks": measured, "cpu_baseline": cpu, "one_stream": one_stream,
         "checked_against_oracle": checks,
         "per_config": per_config, "ffn_packed_weights": packed, "pairs": pairs, "network_blocks": blocks, "network_body": network,
+        "vendor_context": vendor,
         "fused_kernel_us": {str(k): round(v * 1e3, 2) for k, v in kernel_ms.items()},
     }
     print(json.dumps(out))
