@@ -273,11 +273,12 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
             // W1 [Cin][Cexp] -> W1s[e][k], W2 [Cexp][Cout] -> W2s[co][k]; k beyond the real extent = 0
             const bf16_t* W1 = reinterpret_cast<const bf16_t*>(p.w1) + c0;
             const int nq1 = p.mode == 2 ? 0 : cw / 4;
-            // unit = (8 input channels ko, 4 output channels nq), dealt to threads with ko's low two bits fastest:
-            // the rows of W1s / W2s are an odd number of 16-byte chunks long, so the 16 lanes that a 16-byte LDS
-            // store serves together ((ko & 3, nq & 3): chunk 4 nq c + ko, c odd) then hit 16 different chunks
+            // unit = (8 input channels ko, 4 output channels nq).  Sixteen consecutive threads take (nq & 3, ko & 3),
+            // nq fastest: a quad of lanes loads 32 contiguous bytes of a weight row, and because the rows of W1s /
+            // W2s are an odd number c of 16-byte chunks long, the 16 lanes that a 16-byte LDS store serves
+            // together hit 16 different chunks (4 c (nq & 3) + (ko & 3) mod 16)
             for (int it = tid; it < (p.KP1 / 8) * nq1; it += kInvresThreads) {
-                const int nq = (it >> 2) % nq1, ko = ((it >> 2) / nq1) * 4 + (it & 3);
+                const int hi = it >> 4, nq = (hi % (nq1 / 4)) * 4 + (it & 3), ko = (hi / (nq1 / 4)) * 4 + ((it >> 2) & 3);
                 uint2 r[8];
 #pragma unroll
                 for (int kk = 0; kk < 8; ++kk) {
@@ -292,7 +293,7 @@ __global__ __launch_bounds__(kInvresThreads) void fused_invres_kernel(const Invr
             const bf16_t* W2 = reinterpret_cast<const bf16_t*>(p.w2) + (long)c0 * p.Cout;
             const int nq2 = p.mode == 1 ? 0 : p.CoutP / 4;
             for (int it = tid; it < (kpc / 8) * nq2; it += kInvresThreads) {
-                const int nq = (it >> 2) % nq2, ko = ((it >> 2) / nq2) * 4 + (it & 3);
+                const int hi = it >> 4, nq = (hi % (nq2 / 4)) * 4 + (it & 3), ko = (hi / (nq2 / 4)) * 4 + ((it >> 2) & 3);
                 uint2 r[8];
 #pragma unroll
                 for (int kk = 0; kk < 8; ++kk) {
