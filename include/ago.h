@@ -481,6 +481,49 @@ ago_status ago_graph_split(int n_nodes, const double* weight, const unsigned cha
 ago_status ago_graph_join(int n_nodes, const int* mini_of, int n_minis, const int* parent_of_mini,
                           int* subgraph_of);
 
+/* Lowering (Sec. III-B, VI: the structures intensive fusion covers; Sec. III: sibling operators sharing an input):
+ * inside every subgraph of a partition, recognise the operator chains the fused kernels implement and turn the
+ * graph into a list of launches.  Host only.
+ *
+ * Graph: nodes 0..n_nodes-1 in topological order; op[v] is an ago_graph_op; the producers of node v are
+ * input_ids[input_begin[v] .. input_begin[v+1]) (each < v, first operand first).  attr:[n_nodes][4] and
+ * attr_f:[n_nodes] carry what the choice depends on (unused entries are ignored):
+ *   DWCONV   attr[0] = stride                      CONV3X3  attr[0] = input channels
+ *   GEMM     attr[0], attr[1] = rows, columns of its weight; attr[2] = rows of its input
+ *   BMM_NT   attr[0] = last dimension of its first operand (the head dimension)
+ *   TO_HEADS attr[0] = heads, attr[1] = 1 if the view is head-major ([B,Hh,S,D])
+ *   SCALE    attr_f = the factor
+ * subgraph_of:[n_nodes] is the partition (ago_graph_cluster).  dt is the storage type of the graph's tensors.
+ * decide_ffn != 0: a matmul -> activation -> matmul chain becomes AGO_LAUNCH_FFN only where ago_fused_ffn_pays
+ * says the fused kernel wins, else AGO_LAUNCH_FFN_EPILOGUE (two products with fused epilogues); 0: always fused.
+ *
+ * A chain starts at the first operator not yet placed and follows single-consumer links inside its subgraph (an
+ * ADD may take its other operand from outside the chain, a batched product from anything computed before the
+ * chain's start).  It is matched from its first operator against, in this order,
+ *   INVRES      conv1x1 [bias] relu6 dwconv [bias] relu6 conv1x1 [bias] [add]   (add: the block's own input, stride 1)
+ *   CONV_CHAIN  conv3x3 [bias] relu conv3x3 [bias] [add] relu                   (bf16, 64 channels)
+ *   FFN         gemm [bias] (gelu_tanh | relu | relu6) gemm [bias]              (bf16)
+ *   ATTN        bmm_nt scale softmax bmm_nn    (bf16, factor > 0, head dimension 64 or 128, the probabilities
+ *                                               are the first operand of the second product)
+ *   PW_DW       conv1x1 [bias] relu6 dwconv [bias] relu6
+ *   DW_PW       dwconv [bias] relu6 conv1x1 [bias]
+ * a structure whose residual is not admissible is retried without it.  QKV: three products that are the only
+ * consumers of one tensor, in one subgraph, with equal weight shapes, each followed by [bias] and a TO_HEADS view
+ * of equal form (bf16).  Everything else: AGO_LAUNCH_OP, one operator.  INPUT nodes launch nothing.
+ *
+ * Out: launch l has kind launch_kind[l] and the nodes launch_nodes[launch_begin[l] .. launch_begin[l+1]), chains in
+ * chain order, QKV in increasing id; launches are in execution order.  launch_kind:[n_nodes],
+ * launch_begin:[n_nodes+1], launch_nodes:[n_nodes], n_launches out.  Errors: NULL, SHAPE (ids out of range or not
+ * topological, unknown operator), DTYPE. */
+typedef enum { AGO_GOP_INPUT = 0, AGO_GOP_CONV1X1, AGO_GOP_DWCONV, AGO_GOP_CONV3X3, AGO_GOP_GEMM, AGO_GOP_BMM_NT,
+               AGO_GOP_BMM_NN, AGO_GOP_BIAS, AGO_GOP_RELU, AGO_GOP_RELU6, AGO_GOP_GELU_TANH, AGO_GOP_ADD,
+               AGO_GOP_SCALE, AGO_GOP_SOFTMAX, AGO_GOP_TO_HEADS, AGO_GOP_COUNT } ago_graph_op;
+typedef enum { AGO_LAUNCH_OP = 0, AGO_LAUNCH_INVRES, AGO_LAUNCH_CONV_CHAIN, AGO_LAUNCH_FFN, AGO_LAUNCH_FFN_EPILOGUE,
+               AGO_LAUNCH_ATTN, AGO_LAUNCH_PW_DW, AGO_LAUNCH_DW_PW, AGO_LAUNCH_QKV } ago_launch_kind;
+ago_status ago_graph_lower(int n_nodes, const int* op, const int* input_begin, const int* input_ids,
+                           const int* attr, const float* attr_f, const int* subgraph_of, ago_dtype dt,
+                           int decide_ffn, int* launch_kind, int* launch_begin, int* launch_nodes, int* n_launches);
+
 #ifdef __cplusplus
 }
 #endif

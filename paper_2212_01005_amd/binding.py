@@ -122,9 +122,11 @@ lib.ago_graph_split.argtypes = [_i, _dp, _bp, _i, _ip, _ip, _ip, ctypes.c_double
 lib.ago_graph_split.restype = _i
 lib.ago_graph_join.argtypes = [_i, _ip, _i, _ip, _ip]
 lib.ago_graph_join.restype = _i
+lib.ago_graph_lower.argtypes = [_i, _ip, _ip, _ip, _ip, ctypes.POINTER(ctypes.c_float), _ip, _i, _i, _ip, _ip, _ip, _ip]
+lib.ago_graph_lower.restype = _i
 
 EXPORTED = sorted(list(_SIGS) + ["ago_graph_op_weight", "ago_graph_topological_stage", "ago_graph_cluster",
-                                 "ago_graph_split", "ago_graph_join"] + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
+                                 "ago_graph_split", "ago_graph_join", "ago_graph_lower"] + ["ago_workspace_bytes", "ago_status_string", "ago_set_tile_config",
                                  "ago_num_tile_configs", "ago_fused_upstream_iterations", "ago_fused_ffn_pays",
                                  "ago_fused_conv_chain_plan", "ago_fused_attn_plan", "ago_fused_ffn_plan",
                                  "ago_profile_enable", "ago_profile_select", "ago_profile_read", "ago_profile_read_split", "ago_bench_mfma_kernel",
@@ -775,6 +777,28 @@ def graph_split(n_nodes, weight, edges, subgraph_of, is_complex, td_mini):
     _chk(lib.ago_graph_split(n_nodes, w, cx, ne, es, ed, _ints(subgraph_of), float(td_mini), mini, parent,
                              ctypes.byref(count)))
     return list(mini), list(parent)[:count.value]
+
+
+GRAPH_OPS = ["input", "conv1x1", "dwconv", "conv3x3", "gemm", "bmm_nt", "bmm_nn", "bias", "relu", "relu6", "gelu_tanh",
+             "add", "scale", "softmax", "to_heads"]                       # index = ago_graph_op
+LAUNCH_KINDS = ["op", "invres", "conv_chain", "ffn", "ffn_epilogue", "attn", "pw_dw", "dw_pw", "qkv"]   # index = ago_launch_kind
+
+
+def graph_lower(ops, inputs, attr, attr_f, subgraph_of, dtype, decide_ffn):
+    """ago_graph_lower on a graph given as lists: operator names, producer lists, [4]-int and float attributes per
+    node.  Returns [(launch kind name, [node ids])] in execution order."""
+    n = len(ops)
+    begin, ids = [0], []
+    for inp in inputs:
+        ids += [int(i) for i in inp]
+        begin.append(len(ids))
+    flat_attr = [int(v) for a in attr for v in (list(a) + [0, 0, 0, 0])[:4]]
+    af = (ctypes.c_float * n)(*[float(v) for v in attr_f])
+    kind, lb, ln = (ctypes.c_int * n)(), (ctypes.c_int * (n + 1))(), (ctypes.c_int * n)()
+    count = ctypes.c_int(0)
+    _chk(lib.ago_graph_lower(n, _ints(GRAPH_OPS.index(o) for o in ops), _ints(begin), _ints(ids), _ints(flat_attr), af,
+                             _ints(subgraph_of), int(dtype), 1 if decide_ffn else 0, kind, lb, ln, ctypes.byref(count)))
+    return [(LAUNCH_KINDS[kind[l]], [ln[k] for k in range(lb[l], lb[l + 1])]) for l in range(count.value)]
 
 
 def graph_join(mini_of, parent_of_mini):

@@ -19,6 +19,7 @@ LIB = os.path.join(HERE, "libago.so")
 SOURCES = [
     "ago_host.cpp",
     "ago_graph.cpp",
+    "ago_lower.cpp",
     "ago_plan.cpp",
     "ago_api.hip",
     "ago_elementwise.hip",

@@ -1,11 +1,12 @@
 """From an operator graph to fused-kernel launches (AGO Sec. IV -> Sec. III-B).
 
-The graph frontend of the library (``ago_graph_*``: Eq. 1 weights, acyclic Cluster) decides which
-operators form one subgraph; this module recognises, inside each subgraph, the operator chains the
-hand-written kernels implement (the structures of Sec. III-B and VI: pw -> dw -> pw, the pw / dw pairs,
-3x3 -> 3x3, matmul -> activation -> matmul, matmul -> scale -> softmax -> matmul) and turns them into one
-launch each; whatever is left runs operator by operator on the un-fused kernels.  Only host-side
-bookkeeping happens here: every tensor operation is a call into the library.
+The graph frontend of the library decides which operators form one subgraph (``ago_graph_cluster``: Eq. 1
+weights, acyclic Cluster) and which operator chains inside each subgraph become one fused launch
+(``ago_graph_lower``: the structures of Sec. III-B and VI: pw -> dw -> pw, the pw / dw pairs, 3x3 -> 3x3,
+matmul -> activation -> matmul, matmul -> scale -> softmax -> matmul, sibling projections); whatever is left runs
+operator by operator on the un-fused kernels.  This module holds the graph form, marshals it for those two calls
+and executes the resulting plan: only host-side bookkeeping, every decision and every tensor operation is a call
+into the library.
 
 Graph form: ``Graph.nodes`` is a list in topological order; node i is ``Node(op, inputs, attrs)`` with
 ``inputs`` = ids of producer nodes.  Operators and their attributes:
@@ -22,23 +23,9 @@ Graph form: ``Graph.nodes`` is a list in topological order; node i is ``Node(op,
 Weights / biases are named entries of ``Graph.params``.
 """
 
-import re
 from dataclasses import dataclass, field
 
 COMPLEX = {"conv1x1", "dwconv", "conv3x3", "gemm", "bmm_nt", "bmm_nn"}
-_TOKEN = {"conv1x1": "P", "dwconv": "D", "conv3x3": "C", "gemm": "G", "bmm_nt": "T", "bmm_nn": "N",
-          "bias": "b", "relu": "r", "relu6": "6", "gelu_tanh": "g", "add": "+", "scale": "s", "softmax": "x",
-          "input": "i", "to_heads": "h"}
-
-# fused structures, longest first; the token string of a chain is matched from its first operator
-_PATTERNS = [
-    ("invres", re.compile(r"Pb?6Db?6Pb?\+?")),
-    ("conv_chain", re.compile(r"Cb?rCb?\+?r")),
-    ("ffn", re.compile(r"Gb?[gr6]Gb?")),
-    ("attn", re.compile(r"TsxN")),
-    ("pw_dw", re.compile(r"Pb?6Db?6")),
-    ("dw_pw", re.compile(r"Db?6Pb?")),
-]
 
 
 @dataclass
@@ -120,129 +107,44 @@ def partition(g, binding, c=0.01, b=1.0, td=float("inf")):
     return binding.graph_cluster(len(g.nodes), weight, g.edges(), td), weight
 
 
+def node_attributes(g, shapes):
+    """What the library's lowering needs to know about every node beyond its kind (``ago_graph_lower``)."""
+    attr, attr_f = [], []
+    for n in g.nodes:
+        a, f = [0, 0, 0, 0], 0.0
+        if n.op == "dwconv":
+            a[0] = int(n.attrs.get("stride", 1))
+        elif n.op == "conv3x3":
+            a[0] = int(g.params[n.attrs["w"]].shape[2])
+        elif n.op == "gemm":
+            rows = 1
+            for d in shapes[n.inputs[0]][:-1]:
+                rows *= int(d)
+            a[0], a[1], a[2] = int(g.params[n.attrs["w"]].shape[0]), int(g.params[n.attrs["w"]].shape[1]), rows
+        elif n.op == "bmm_nt":
+            a[0] = int(shapes[n.inputs[0]][-1])
+        elif n.op == "to_heads":
+            a[0], a[1] = int(n.attrs["heads"]), 1 if n.attrs.get("head_major", True) else 0
+        elif n.op == "scale":
+            f = float(n.attrs.get("alpha", 0.0))
+        attr.append(a)
+        attr_f.append(f)
+    return attr, attr_f
+
+
 def lower(g, subgraph_of, binding=None):
-    """Launch plan: a list of (kind, node ids) in execution order.  kind is one of the fused structures,
-    "ffn_epilogue" (the matmul -> activation -> matmul chain as two products with fused epilogues: what
-    the chain becomes when ``binding.fused_ffn_pays`` says the fused kernel would lose at this row count;
-    without ``binding`` the chain is always fused) or "op" (one operator on its un-fused kernel);
-    "input" nodes launch nothing."""
-    cons = g.consumers()
-    shapes = infer_shapes(g) if binding is not None else None
-    n_nodes = len(g.nodes)
-    done = [False] * n_nodes
-    plan = []
-    for i in range(n_nodes):
-        if done[i]:
-            continue
-        if g.nodes[i].op == "input":
-            done[i] = True
-            continue
-        sib = _qkv_siblings(g, cons, subgraph_of, done, i)
-        if sib is not None:
-            plan.append(("qkv", sib))
-            for k in sib:
-                done[k] = True
-            continue
-        # the chain that starts at i and stays inside i's subgraph: every link is the only consumer of its
-        # predecessor ("add" may take a second operand from anywhere that is already computed)
-        chain = [i]
-        while True:
-            last = chain[-1]
-            nxt = cons[last]
-            if len(nxt) != 1:
-                break
-            j = nxt[0]
-            if done[j] or subgraph_of[j] != subgraph_of[i] or g.nodes[j].op == "input":
-                break
-            others = [s for s in g.nodes[j].inputs if s != last]
-            if g.nodes[j].op == "add":
-                if len(others) != 1 or others[0] >= chain[0] and others[0] not in chain:
-                    break
-            elif g.nodes[j].op in ("bmm_nt", "bmm_nn"):
-                if any(o >= chain[0] and o not in chain for o in others):
-                    break
-            elif others:
-                break
-            chain.append(j)
-        tokens = "".join(_TOKEN[g.nodes[k].op] for k in chain)
-        matched = None
-        for kind, pat in _PATTERNS:
-            m = pat.match(tokens)
-            if m and not _admissible(g, kind, chain[:m.end()]) and "+" in m.group(0):
-                m = pat.match(tokens[:tokens.index("+")])          # the same structure without the residual
-            if m and _admissible(g, kind, chain[:m.end()]):
-                matched = (kind, chain[:m.end()])
-                if kind == "ffn" and binding is not None:
-                    ids = matched[1]
-                    gemms = [k for k in ids if g.nodes[k].op == "gemm"]
-                    m_rows, k_in = shapes[g.nodes[ids[0]].inputs[0]]
-                    f_hid, k_out = shapes[gemms[0]][1], shapes[gemms[1]][1]
-                    if not binding.fused_ffn_pays(m_rows, k_in, f_hid, k_out):
-                        matched = ("ffn_epilogue", ids)
-                break
-        if matched is None:
-            matched = ("op", [i])
-        plan.append(matched)
-        for k in matched[1]:
-            done[k] = True
-    return plan
-
-
-def _qkv_siblings(g, cons, subgraph_of, done, i):
-    """Sibling fusion: node i is a gemm whose input feeds exactly three gemms of one subgraph with equal weight
-    shapes, each followed (or not, all alike) by a bias and then a "to_heads" view.  Returns the node ids
-    [gemm, (bias), to_heads] x 3 in graph order, or None."""
-    n = g.nodes[i]
-    if n.op != "gemm" or g.dtype != "bf16":
-        return None
-    src = n.inputs[0]
-    sibs = [j for j in cons[src] if g.nodes[j].op == "gemm" and not done[j] and subgraph_of[j] == subgraph_of[i]]
-    if len(sibs) != 3 or sibs[0] != i or len(cons[src]) != 3:
-        return None
-    chains = []
-    for j in sibs:
-        chain = [j]
-        while len(cons[chain[-1]]) == 1 and g.nodes[cons[chain[-1]][0]].op in ("bias", "to_heads") \
-                and subgraph_of[cons[chain[-1]][0]] == subgraph_of[i]:
-            chain.append(cons[chain[-1]][0])
-            if g.nodes[chain[-1]].op == "to_heads":
-                break
-        chains.append(chain)
-    kinds = ["".join({"gemm": "G", "bias": "b", "to_heads": "h"}[g.nodes[k].op] for k in c) for c in chains]
-    if kinds[0] not in ("Gh", "Gbh") or kinds.count(kinds[0]) != 3:
-        return None
-    w = [g.params[g.nodes[c[0]].attrs["w"]].shape for c in chains]
-    heads = [(g.nodes[c[-1]].attrs["heads"], g.nodes[c[-1]].attrs.get("head_major", True)) for c in chains]
-    if w.count(w[0]) != 3 or heads.count(heads[0]) != 3:
-        return None
-    return sorted(k for c in chains for k in c)
-
-
-def _admissible(g, kind, ids):
-    """Checks the token pattern cannot express: what a residual adds, dtype and size limits of the kernels."""
-    nodes = [g.nodes[k] for k in ids]
-    first_in = nodes[0].inputs[0]
-    for k, n in zip(ids, nodes):
-        if n.op == "add":
-            other = [s for s in n.inputs if s not in ids]
-            if len(other) != 1 or other[0] != first_in:          # the fused residual is the block's own input
-                return False
-    if kind == "invres":
-        dws = [n for n in nodes if n.op == "dwconv"]
-        has_add = any(n.op == "add" for n in nodes)
-        return not has_add or dws[0].attrs.get("stride", 1) == 1
-    if kind == "conv_chain":
-        return g.dtype == "bf16" and g.params[nodes[0].attrs["w"]].shape[2] == 64
-    if kind == "ffn":
-        return g.dtype == "bf16"
-    if kind == "attn":
-        # the kernel computes softmax(alpha * in0 * in1^T) * v: the probabilities must be the first operand of
-        # the second product, alpha positive, head dimension one the kernel has; anything else runs operator by operator
-        t, sc, sm, nn = nodes
-        head_dim = infer_shapes(g)[t.inputs[0]][-1]
-        return (g.dtype == "bf16" and nn.inputs[0] == ids[2] and sm.inputs[0] == ids[1] and sc.inputs[0] == ids[0]
-                and float(sc.attrs.get("alpha", 0.0)) > 0.0 and head_dim in (64, 128))
-    return True
+    """Launch plan: a list of (kind, node ids) in execution order, made by the library (``ago_graph_lower``:
+    the structures, the chain rule and the admissibility checks are documented with its declaration).  kind is
+    one of the fused structures ("invres", "conv_chain", "ffn", "attn", "pw_dw", "dw_pw", "qkv"), "ffn_epilogue"
+    (the matmul -> activation -> matmul chain as two products with fused epilogues: what the chain becomes when
+    the library's fuse-or-not decision says the fused kernel would lose at this row count; asked for only when
+    ``binding`` is given, otherwise the chain is always fused) or "op" (one operator on its un-fused kernel);
+    "input" nodes launch nothing.  This function only marshals the graph."""
+    from . import binding as _ago
+    shapes = infer_shapes(g)
+    attr, attr_f = node_attributes(g, shapes)
+    return _ago.graph_lower([n.op for n in g.nodes], [n.inputs for n in g.nodes], attr, attr_f, subgraph_of,
+                            _ago.BF16 if g.dtype == "bf16" else _ago.F32, binding is not None)
 
 
 # ---- execution (GPU) ---------------------------------------------------------------------------------

@@ -1,0 +1,249 @@
+"""Host-only: the library's lowering (ago_graph_lower) against the independent Python oracle, and the oracle against
+hand-worked plans."""
+import random
+
+import pytest
+
+from oracle import ago_lower_oracle as O
+
+
+def _lib():
+    from paper_2212_01005_amd import binding as ago
+    return ago
+
+
+def _attr4(op, a):
+    if op == "dwconv":
+        return [a.get("stride", 1), 0, 0, 0]
+    if op == "conv3x3":
+        return [a["channels"], 0, 0, 0]
+    if op == "gemm":
+        return [a["w_shape"][0], a["w_shape"][1], a["rows"], 0]
+    if op == "bmm_nt":
+        return [a["head_dim"], 0, 0, 0]
+    if op == "to_heads":
+        return [a["heads"], 1 if a.get("head_major", True) else 0, 0, 0]
+    return [0, 0, 0, 0]
+
+
+def _library_plan(ops, inputs, attrs, dtype, part, decide):
+    ago = _lib()
+    return ago.graph_lower(ops, inputs, [_attr4(o, a) for o, a in zip(ops, attrs)],
+                           [float(a.get("alpha", 0.0)) for a in attrs], part, ago.BF16 if dtype == "bf16" else ago.F32, decide)
+
+
+def _pays(m, k, f, k2):
+    try:
+        return _lib().fused_ffn_pays(m, k, f, k2)
+    except ValueError:
+        return None
+
+
+class _B:
+    """Tiny graph builder for the cases below."""
+
+    def __init__(self):
+        self.ops, self.inputs, self.attrs = [], [], []
+
+    def add(self, op, inputs=(), **attrs):
+        self.ops.append(op)
+        self.inputs.append(list(inputs))
+        self.attrs.append(attrs)
+        return len(self.ops) - 1
+
+    def chain(self, src, spec):
+        """spec: list of (op, attrs) applied one after the other to src; returns the ids."""
+        ids = []
+        for op, a in spec:
+            src = self.add(op, [src], **a)
+            ids.append(src)
+        return ids
+
+
+# ---- the oracle against plans worked out by hand ----------------------------------------------------------------
+
+def test_oracle_inverted_residual_with_and_without_an_admissible_residual():
+    for stride, expect_add in ((1, True), (2, False)):
+        b = _B()
+        x = b.add("input")
+        ids = b.chain(x, [("conv1x1", {}), ("bias", {}), ("relu6", {}), ("dwconv", {"stride": stride}), ("relu6", {}),
+                          ("conv1x1", {}), ("bias", {})])
+        add = b.add("add", [ids[-1], x])
+        plan = O.lower(b.ops, b.inputs, b.attrs, "f32", [0] * len(b.ops))
+        if expect_add:
+            assert plan == [("invres", ids + [add])]
+        else:                                   # stride 2: the block without its residual, the add on its own
+            assert plan == [("invres", ids), ("op", [add])]
+
+
+def test_oracle_residual_from_elsewhere_is_not_fused():
+    b = _B()
+    x, z = b.add("input"), b.add("input")
+    ids = b.chain(x, [("conv1x1", {}), ("relu6", {}), ("dwconv", {"stride": 1}), ("relu6", {}), ("conv1x1", {})])
+    add = b.add("add", [ids[-1], z])
+    assert O.lower(b.ops, b.inputs, b.attrs, "bf16", [0] * len(b.ops)) == [("invres", ids), ("op", [add])]
+
+
+def test_oracle_partition_cuts_a_block_into_its_pairs():
+    b = _B()
+    x = b.add("input")
+    ids = b.chain(x, [("conv1x1", {}), ("relu6", {}), ("dwconv", {"stride": 1}), ("relu6", {}), ("conv1x1", {}), ("bias", {})])
+    part = [0, 1, 1, 1, 1, 2, 2]            # pw + dw in one subgraph, the projection in another
+    assert O.lower(b.ops, b.inputs, b.attrs, "bf16", part) == [("pw_dw", ids[:4]), ("op", [ids[4]]), ("op", [ids[5]])]
+    part = [0, 1, 1, 2, 2, 2, 2]
+    assert O.lower(b.ops, b.inputs, b.attrs, "bf16", part) == [("op", [ids[0]]), ("op", [ids[1]]), ("dw_pw", ids[2:])]
+
+
+def test_oracle_conv_chain_needs_bf16_and_64_channels():
+    for dtype, ch, fused in (("bf16", 64, True), ("f32", 64, False), ("bf16", 32, False)):
+        b = _B()
+        x = b.add("input")
+        ids = b.chain(x, [("conv3x3", {"channels": ch}), ("bias", {}), ("relu", {}), ("conv3x3", {"channels": ch}), ("bias", {})])
+        add = b.add("add", [ids[-1], x])
+        r = b.add("relu", [add])
+        plan = O.lower(b.ops, b.inputs, b.attrs, dtype, [0] * len(b.ops))
+        assert plan == ([("conv_chain", ids + [add, r])] if fused else [("op", [k]) for k in ids + [add, r]])
+
+
+def test_oracle_attention_only_in_the_form_the_kernel_computes():
+    def build(swap, alpha, hd):
+        b = _B()
+        q, k, v = b.add("input"), b.add("input"), b.add("input")
+        t = b.add("bmm_nt", [q, k], head_dim=hd)
+        s = b.add("scale", [t], alpha=alpha)
+        sm = b.add("softmax", [s])
+        nn = b.add("bmm_nn", [v, sm] if swap else [sm, v])
+        return b, [t, s, sm, nn]
+    b, ids = build(False, 0.125, 64)
+    assert O.lower(b.ops, b.inputs, b.attrs, "bf16", [0] * 7) == [("attn", ids)]
+    for swap, alpha, hd in ((True, 0.125, 64), (False, -1.0, 64), (False, 0.125, 32)):
+        b, ids = build(swap, alpha, hd)
+        assert O.lower(b.ops, b.inputs, b.attrs, "bf16", [0] * 7) == [("op", [k]) for k in ids]
+
+
+def test_oracle_ffn_decision_and_sibling_projections():
+    b = _B()
+    x = b.add("input")
+    ids = b.chain(x, [("gemm", {"w_shape": (64, 256), "rows": 128}), ("bias", {}), ("gelu_tanh", {}),
+                      ("gemm", {"w_shape": (256, 64), "rows": 128}), ("bias", {})])
+    part = [0] * len(b.ops)
+    assert O.lower(b.ops, b.inputs, b.attrs, "bf16", part) == [("ffn", ids)]
+    assert O.lower(b.ops, b.inputs, b.attrs, "bf16", part, lambda *a: True) == [("ffn", ids)]
+    assert O.lower(b.ops, b.inputs, b.attrs, "bf16", part, lambda *a: False) == [("ffn_epilogue", ids)]
+    assert O.lower(b.ops, b.inputs, b.attrs, "f32", part) == [("op", [k]) for k in ids]
+    b = _B()
+    x = b.add("input")
+    heads = []
+    for _ in range(3):
+        heads += b.chain(x, [("gemm", {"w_shape": (64, 64), "rows": 256}), ("bias", {}), ("to_heads", {"heads": 4})])
+    assert O.lower(b.ops, b.inputs, b.attrs, "bf16", [0] * len(b.ops)) == [("qkv", sorted(heads))]
+    b.attrs[heads[3]]["w_shape"] = (64, 128)          # one projection of another width: three plain products
+    plan = O.lower(b.ops, b.inputs, b.attrs, "bf16", [0] * len(b.ops))
+    assert all(kind == "op" for kind, _ in plan) and sorted(k for _, ids_ in plan for k in ids_) == sorted(heads)
+
+
+# ---- the library against the oracle on random graphs -----------------------------------------------------------
+
+_TEMPLATES = [
+    ["conv1x1", "bias", "relu6", "dwconv", "bias", "relu6", "conv1x1", "bias", "add"],
+    ["conv3x3", "bias", "relu", "conv3x3", "bias", "add", "relu"],
+    ["gemm", "bias", "gelu_tanh", "gemm", "bias"],
+    ["bmm_nt", "scale", "softmax", "bmm_nn"],
+    ["dwconv", "bias", "relu6", "conv1x1", "bias"],
+    ["conv1x1", "relu6", "dwconv", "relu6"],
+]
+_OPTIONAL = {"bias", "add"}
+_SIMPLE = ["bias", "relu", "relu6", "gelu_tanh", "scale", "softmax"]
+
+
+def _random_attrs(rnd, op):
+    if op == "dwconv":
+        return {"stride": rnd.choice([1, 1, 2])}
+    if op == "conv3x3":
+        return {"channels": rnd.choice([64, 64, 32])}
+    if op == "gemm":
+        return {"w_shape": rnd.choice([(768, 3072), (3072, 768), (64, 64), (100, 64)]), "rows": rnd.choice([128, 512, 8192, 65536])}
+    if op == "bmm_nt":
+        return {"head_dim": rnd.choice([64, 128, 32])}
+    if op == "scale":
+        return {"alpha": rnd.choice([0.125, 0.125, 0.0, -0.5])}
+    if op == "to_heads":
+        return {"heads": rnd.choice([4, 8]), "head_major": rnd.choice([True, False])}
+    return {}
+
+
+def _random_graph(rnd):
+    b = _B()
+    pool = [b.add("input") for _ in range(rnd.randint(1, 3))]
+    cur = pool[0]
+    for _ in range(rnd.randint(1, 5)):
+        if rnd.random() < 0.2:                                  # sibling projections off the current tensor
+            same = rnd.random() < 0.7
+            shape, view = rnd.choice([(64, 64), (64, 128)]), _random_attrs(rnd, "to_heads")
+            with_bias = rnd.random() < 0.5
+            outs = []
+            for s in range(rnd.choice([3, 3, 2, 4])):
+                g = b.add("gemm", [cur], w_shape=shape if same or s else (64, 192), rows=256)
+                if with_bias or (not same and rnd.random() < 0.3):
+                    g = b.add("bias", [g])
+                outs.append(b.add("to_heads", [g], **(view if same or rnd.random() < 0.5 else _random_attrs(rnd, "to_heads"))))
+            pool += outs
+            cur = rnd.choice(outs)
+            continue
+        block_in = cur
+        for op in rnd.choice(_TEMPLATES):
+            if op in _OPTIONAL and rnd.random() < 0.35:
+                continue
+            if rnd.random() < 0.08:
+                op = rnd.choice(_SIMPLE + ["conv1x1", "dwconv", "gemm"])
+            if op == "add":
+                other = rnd.choice([block_in, block_in, block_in, rnd.choice(pool), cur])
+                cur = b.add("add", [cur, other] if rnd.random() < 0.8 else [other, cur])
+            elif op in ("bmm_nt", "bmm_nn"):
+                other = rnd.choice(pool)
+                cur = b.add(op, [cur, other] if rnd.random() < 0.8 else [other, cur], **_random_attrs(rnd, op))
+            else:
+                cur = b.add(op, [cur], **_random_attrs(rnd, op))
+            if rnd.random() < 0.1:
+                pool.append(cur)                                 # a later block may read this tensor as well
+        pool.append(cur)
+        if rnd.random() < 0.3:
+            cur = rnd.choice(pool)
+    n = len(b.ops)
+    mode = rnd.random()
+    if mode < 0.4:
+        part = [0] * n
+    elif mode < 0.5:
+        part = list(range(n))
+    else:
+        part, sid = [], 0
+        for _ in range(n):
+            part.append(sid)
+            if rnd.random() < 0.15:
+                sid += 1
+    return b, part
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_library_lowering_equals_the_oracle_on_random_graphs(seed):
+    rnd = random.Random(9100 + seed)
+    kinds = set()
+    for _ in range(150):
+        b, part = _random_graph(rnd)
+        dtype = rnd.choice(["bf16", "bf16", "f32"])
+        decide = rnd.random() < 0.5
+        want = O.lower(b.ops, b.inputs, b.attrs, dtype, part, _pays if decide else None)
+        got = _library_plan(b.ops, b.inputs, b.attrs, dtype, part, decide)
+        assert got == want, (b.ops, b.inputs, b.attrs, dtype, part, decide)
+        placed = sorted(k for _, ids in got for k in ids)
+        assert placed == [k for k in range(len(b.ops)) if b.ops[k] != "input"]      # every operator exactly once
+        kinds |= {k for k, _ in got}
+    assert {"op", "invres", "ffn", "attn"} <= kinds                 # the generator reaches the fused structures
+
+
+def test_library_lowering_rejects_malformed_graphs():
+    ago = _lib()
+    with pytest.raises(ago.AgoError):
+        ago.graph_lower(["input", "relu"], [[], [1]], [[0] * 4] * 2, [0.0] * 2, [0, 0], ago.BF16, False)     # not topological
+    with pytest.raises(ago.AgoError):
+        ago.graph_lower(["input", "relu"], [[], [5]], [[0] * 4] * 2, [0.0] * 2, [0, 0], ago.BF16, False)     # id out of range
