@@ -247,3 +247,23 @@ def test_library_lowering_rejects_malformed_graphs():
         ago.graph_lower(["input", "relu"], [[], [1]], [[0] * 4] * 2, [0.0] * 2, [0, 0], ago.BF16, False)     # not topological
     with pytest.raises(ago.AgoError):
         ago.graph_lower(["input", "relu"], [[], [5]], [[0] * 4] * 2, [0.0] * 2, [0, 0], ago.BF16, False)     # id out of range
+
+
+def test_library_lowering_checks_its_arguments_through_the_c_abi():
+    import ctypes
+    ago = _lib()
+    lib = ago.lib
+    n = 2
+    ints = lambda *v: (ctypes.c_int * len(v))(*v)
+    op, begin, ids = ints(0, 8), ints(0, 0, 1), ints(0)                 # input -> relu
+    attr, attr_f, part = ints(*([0] * 8)), (ctypes.c_float * n)(), ints(0, 0)
+    kind, lb, ln, count = ints(0, 0), ints(0, 0, 0), ints(0, 0), ctypes.c_int(0)
+    ok = lib.ago_graph_lower(n, op, begin, ids, attr, attr_f, part, ago.BF16, 0, kind, lb, ln, ctypes.byref(count))
+    assert ok == 0 and count.value == 1 and kind[0] == 0 and list(lb)[:2] == [0, 1] and ln[0] == 1
+    null = ago.lib.ago_status_string(lib.ago_graph_lower(n, None, begin, ids, attr, attr_f, part, ago.BF16, 0, kind, lb, ln,
+                                                         ctypes.byref(count)))
+    assert b"NULL" in null.upper() or b"null" in null
+    bad_op = ints(0, 99)
+    assert lib.ago_graph_lower(n, bad_op, begin, ids, attr, attr_f, part, ago.BF16, 0, kind, lb, ln, ctypes.byref(count)) != 0
+    assert lib.ago_graph_lower(n, op, begin, ids, attr, attr_f, part, 7, 0, kind, lb, ln, ctypes.byref(count)) != 0   # dtype
+    assert lib.ago_graph_lower(0, op, begin, ids, attr, attr_f, part, ago.BF16, 0, kind, lb, ln, ctypes.byref(count)) != 0
