@@ -183,7 +183,7 @@ struct ConvStageFull {
         return f;
     }
     __device__ __forceinline__ void run(const bf16_t* src, const bf16_t* ws, int h) {
-        constexpr int DEPTH = 6, STEPS = 36;
+        constexpr int DEPTH = 4, STEPS = 36;
         Frag q[DEPTH];
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) q[d] = fetch(src, ws, d, h);
